@@ -1,0 +1,165 @@
+/*
+ * gbdt_hist.h -- C ABI of libgbdt_hist: feature-histogram construction for the
+ * leaves of a histogram-based gradient-boosted decision tree, the sibling
+ * histogram by subtraction, and the best-split gain scan, on one AMD gfx950
+ * (MI355X) GPU.  Method: "GPU-acceleration for Large-scale Tree Boosting"
+ * (arXiv 1706.08359), Sec. 3.3 / Alg. 1 (what a feature histogram is), Sec. 4
+ * (building many of them at once on a GPU), App. C.4 (4-bit bins).
+ *
+ * Conventions shared by every call
+ *  - Pointers marked DEVICE are device (HBM) addresses owned by the caller;
+ *    the library neither frees nor keeps them after the call's work on
+ *    `stream` has finished.  No call takes a host data pointer.
+ *  - `stream` is a hipStream_t passed as void*; NULL is the default stream.
+ *    Calls enqueue kernels and return; they do not synchronise and never read
+ *    device data on the host.
+ *  - Return value: GBDT_OK (0) or a negative gbdt_status code.  Argument
+ *    errors are detected before anything is enqueued.  Contents of device
+ *    buffers (bin values < n_bins, row ids < n_rows) are NOT checked;
+ *    violating them is undefined behaviour.
+ *  - Bins are 0-based: a binned value b satisfies 0 <= b < n_bins (the paper
+ *    writes 1..k).  2 <= n_bins <= 256.
+ *  - The library keeps one scratch workspace per process (partial histograms,
+ *    split candidates).  Calls that use it (gbdt_hist_build, gbdt_best_split)
+ *    must not run concurrently on different streams.
+ */
+#ifndef GBDT_HIST_H_
+#define GBDT_HIST_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  GBDT_OK = 0,
+  GBDT_EINVAL = -1,       /* NULL required pointer, size out of range, lambda < 0 */
+  GBDT_EUNSUPPORTED = -2, /* valid request the library cannot serve (e.g. n_rows >= 2^31) */
+  GBDT_EHIP = -3,         /* a HIP runtime call or kernel launch failed */
+  GBDT_ENOMEM = -4        /* workspace allocation failed or caller workspace too small */
+} gbdt_status;
+
+/* One histogram bin: o[b][1..3] of Alg. 1 -- summed gradient, summed hessian,
+ * sample count.  12 bytes, no padding. */
+typedef struct {
+  float grad;
+  float hess;
+  uint32_t count;
+} gbdt_bin_t;
+
+/* Result of the split search.  A split is [feature id, threshold] (Sec. 3.1);
+ * the threshold is a bin index t: rows with bin <= t go left, the others right.
+ * feature = bin = -1 and gain = 0 when no threshold is admissible. */
+typedef struct {
+  int32_t feature;
+  int32_t bin;
+  float gain; /* G_L^2/(H_L+lambda) + G_R^2/(H_R+lambda) - G^2/(H+lambda), no 1/2 factor */
+  float left_grad;
+  float left_hess;
+  uint32_t left_count;
+  float right_grad;
+  float right_hess;
+  uint32_t right_count;
+} gbdt_split_t;
+
+/*
+ * Size in bytes of the device layout of an n_rows x n_features binned matrix
+ * (App. C.4: n_bins <= 16 stores two 4-bit values per byte, otherwise one byte
+ * per value; Sec. 4 "Data Structure": features are bundled so that one thread
+ * loads a 4-byte group of one sample).  Rows are kept contiguous inside
+ * feature tiles of 16, 32 or 64 bytes.  Returns 0 on invalid arguments.
+ */
+size_t gbdt_bins_packed_bytes(int64_t n_rows, int32_t n_features, int32_t n_bins);
+
+/*
+ * Re-lay a row-major matrix of binned values into the device layout.  Done
+ * once before training (App. A.5: feature data is copied once and then stays
+ * unchanged).
+ *   bins_rowmajor  DEVICE, uint8 [n_rows][n_features], every value < n_bins
+ *   packed_out     DEVICE, gbdt_bins_packed_bytes(...) bytes, 16-byte aligned,
+ *                  fully overwritten (padding bytes are written as 0)
+ */
+int gbdt_bins_pack(const uint8_t* bins_rowmajor, int64_t n_rows, int32_t n_features,
+                   int32_t n_bins, void* packed_out, void* stream);
+
+/*
+ * Feature histograms of one leaf (Alg. 1 for every feature; Sec. 4 and
+ * App. A.1 for the GPU organisation: work split by features and by samples,
+ * per-workgroup histograms in local memory, a final reduction pass).
+ * For every leaf sample i with row id d = leaf_row_idx[i] and every feature j:
+ *   hist_out[j][bin(d, j)] += (grad[d], hess[d], 1).
+ *   bin_matrix     DEVICE, layout written by gbdt_bins_pack with the same
+ *                  n_rows, n_features, n_bins
+ *   leaf_row_idx   DEVICE int32 [n_leaf_rows], row ids in [0, n_rows); NULL
+ *                  means rows 0..n_leaf_rows-1 (the root when n_leaf_rows ==
+ *                  n_rows).  Any order and repeats are legal (each occurrence
+ *                  counts); ascending order reads memory best.
+ *   n_leaf_rows    0 <= n_leaf_rows; with NULL index also <= n_rows
+ *   grad, hess     DEVICE float [n_rows], indexed by ROW ID (g_{d_ri}, h_{d_ri}
+ *                  in Alg. 1), not by position in the leaf
+ *   hist_out       DEVICE gbdt_bin_t [n_features][n_bins], fully overwritten;
+ *                  all zero when n_leaf_rows == 0
+ * Sums are accumulated in fp32 in local memory per workgroup and combined in
+ * fp64 before rounding to fp32; counts are exact.  The order of fp32 additions
+ * inside a workgroup is not fixed, so gradient / hessian sums may differ in
+ * the last bits between runs.
+ */
+int gbdt_hist_build(const void* bin_matrix, int64_t n_rows, int32_t n_features, int32_t n_bins,
+                    const int32_t* leaf_row_idx, int64_t n_leaf_rows, const float* grad,
+                    const float* hess, gbdt_bin_t* hist_out, void* stream);
+
+/*
+ * Sibling histogram: sibling_out[j][b] = parent[j][b] - child[j][b] for the
+ * gradient sum, hessian sum and count.  Not described in the paper; it is the
+ * complement of Alg. 1 over the parent's samples that are not in the child.
+ * All three are DEVICE gbdt_bin_t [n_features][n_bins]; sibling_out may alias
+ * parent or child.  child counts must not exceed parent counts.
+ * (n_features, n_bins: sizes the short form of the call leaves implicit.)
+ */
+int gbdt_hist_subtract(const gbdt_bin_t* parent, const gbdt_bin_t* child, gbdt_bin_t* sibling_out,
+                       int32_t n_features, int32_t n_bins, void* stream);
+
+/*
+ * Best split of a leaf from its histograms (Sec. 3.3: the split objective of
+ * Eq. (4), in its gradient/hessian form from Eq. (9), is evaluated only at the
+ * bin boundaries).  For every feature j and threshold t in 0..n_bins-2, left =
+ * bins <= t (running prefix), right = feature total - left.  A threshold is
+ * admissible when both sides have count >= 1 and hessian sum >= min_child_hess.
+ * The admissible threshold with the largest gain wins; equal gains go to the
+ * smaller feature, then the smaller bin.  Prefix sums and gains are computed in
+ * fp64 from the fp32 histogram, bins in ascending order.
+ *   hist        DEVICE gbdt_bin_t [n_features][n_bins]
+ *   lambda      L2 regularisation added to each hessian sum, >= 0
+ *   split_out   DEVICE, one gbdt_split_t, overwritten
+ */
+int gbdt_best_split(const gbdt_bin_t* hist, float lambda, float min_child_hess,
+                    gbdt_split_t* split_out, int32_t n_features, int32_t n_bins, void* stream);
+
+/*
+ * Scratch workspace.  By default the library allocates device scratch itself
+ * on first use and grows it when a larger problem arrives (hipMalloc inside
+ * gbdt_hist_build / gbdt_best_split).  A caller that wants no allocation in
+ * those calls registers its own buffer:
+ *   gbdt_workspace_bytes  upper bound on scratch needed by gbdt_hist_build and
+ *                         gbdt_best_split for this problem shape on the
+ *                         current device (0 on invalid arguments)
+ *   gbdt_set_workspace    DEVICE buffer, 256-byte aligned, kept until replaced;
+ *                         (NULL, 0) returns to library-owned scratch.  With a
+ *                         caller buffer, a call that needs more returns
+ *                         GBDT_ENOMEM.
+ */
+size_t gbdt_workspace_bytes(int64_t n_rows, int32_t n_features, int32_t n_bins);
+int gbdt_set_workspace(void* dev_ptr, size_t bytes);
+
+/* Static, human-readable text for a gbdt_status code. */
+const char* gbdt_strerror(int code);
+
+/* Text of the last HIP error seen by this thread's failing call ("" if none). */
+const char* gbdt_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GBDT_HIST_H_ */
