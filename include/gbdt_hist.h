@@ -159,6 +159,31 @@ const char* gbdt_strerror(int code);
 /* Text of the last HIP error seen by this thread's failing call ("" if none). */
 const char* gbdt_last_hip_error(void);
 
+/*
+ * Timing of the histogram build kernel by itself (gbdt_hist_build also launches
+ * the reduction pass in the same call).  While enabled, every gbdt_hist_build
+ * records a HIP event on its stream before and after the build kernel.
+ * gbdt_profile_collect waits for the recorded events, returns the summed kernel
+ * time in milliseconds and the number of launches, and forgets them.
+ */
+int gbdt_profile_enable(int enable);
+int gbdt_profile_collect(double* build_kernel_ms_total, int64_t* n_launches);
+
+/*
+ * Introspection of the host-side launch planning (no GPU needed; used by tests).
+ * gbdt_debug_geometry fills out[0..15] with: bin capacity, 4-bit flag, main tile
+ * width, number of main tiles, remainder tile width, packed bytes per row, feature
+ * bytes per row, threads per workgroup, LDS bytes per workgroup, row chunks per
+ * main tile, row chunks of the remainder tile, rows per main chunk, rows per
+ * remainder chunk, total 4-byte words of partial histograms, 0, 0 -- as planned for
+ * a device with n_cus compute units (<= 0: 256).  n_out must be >= 16.
+ * gbdt_debug_locate reports the tile and the local-memory slot of a feature.
+ */
+int gbdt_debug_geometry(int32_t n_features, int32_t n_bins, int64_t n_leaf_rows, int32_t n_cus,
+                        int64_t* out, int32_t n_out);
+int gbdt_debug_locate(int32_t n_features, int32_t n_bins, int32_t feature, int32_t* tile_out,
+                      int32_t* slot_out);
+
 #ifdef __cplusplus
 }
 #endif

@@ -1,0 +1,232 @@
+"""Thin ctypes binding of libgbdt_hist (include/gbdt_hist.h): argument marshalling only.
+
+Every function has the name and argument order of its C counterpart, takes torch
+CUDA tensors (used purely as device memory) and launches on torch's current
+stream unless `stream` is given.  There is no CPU fallback: if the library has not
+been built, or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libgbdt_hist.so")
+
+EXPORTS = [
+    "gbdt_bins_packed_bytes", "gbdt_bins_pack", "gbdt_hist_build", "gbdt_hist_subtract",
+    "gbdt_best_split", "gbdt_workspace_bytes", "gbdt_set_workspace", "gbdt_strerror",
+    "gbdt_last_hip_error", "gbdt_debug_geometry", "gbdt_debug_locate",
+    "gbdt_profile_enable", "gbdt_profile_collect",
+]
+
+# numpy views of the two C structs
+BIN_DTYPE = np.dtype([("grad", "<f4"), ("hess", "<f4"), ("count", "<u4")])
+SPLIT_DTYPE = np.dtype([("feature", "<i4"), ("bin", "<i4"), ("gain", "<f4"),
+                        ("left_grad", "<f4"), ("left_hess", "<f4"), ("left_count", "<u4"),
+                        ("right_grad", "<f4"), ("right_hess", "<f4"), ("right_count", "<u4")])
+
+_lib = None
+
+
+class GbdtError(RuntimeError):
+    pass
+
+
+def load():
+    """Load the built library; raises if it is missing (build it with
+    `python -m paper_1706_08359_amd.build`)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise GbdtError("libgbdt_hist.so is not built: run `python -m paper_1706_08359_amd.build`")
+    lib = ctypes.CDLL(LIB_PATH)
+    c = ctypes
+    lib.gbdt_bins_packed_bytes.restype = c.c_size_t
+    lib.gbdt_bins_packed_bytes.argtypes = [c.c_int64, c.c_int32, c.c_int32]
+    lib.gbdt_bins_pack.restype = c.c_int
+    lib.gbdt_bins_pack.argtypes = [c.c_void_p, c.c_int64, c.c_int32, c.c_int32, c.c_void_p, c.c_void_p]
+    lib.gbdt_hist_build.restype = c.c_int
+    lib.gbdt_hist_build.argtypes = [c.c_void_p, c.c_int64, c.c_int32, c.c_int32, c.c_void_p,
+                                    c.c_int64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p]
+    lib.gbdt_hist_subtract.restype = c.c_int
+    lib.gbdt_hist_subtract.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32, c.c_int32,
+                                       c.c_void_p]
+    lib.gbdt_best_split.restype = c.c_int
+    lib.gbdt_best_split.argtypes = [c.c_void_p, c.c_float, c.c_float, c.c_void_p, c.c_int32,
+                                    c.c_int32, c.c_void_p]
+    lib.gbdt_workspace_bytes.restype = c.c_size_t
+    lib.gbdt_workspace_bytes.argtypes = [c.c_int64, c.c_int32, c.c_int32]
+    lib.gbdt_set_workspace.restype = c.c_int
+    lib.gbdt_set_workspace.argtypes = [c.c_void_p, c.c_size_t]
+    lib.gbdt_strerror.restype = c.c_char_p
+    lib.gbdt_strerror.argtypes = [c.c_int]
+    lib.gbdt_last_hip_error.restype = c.c_char_p
+    lib.gbdt_last_hip_error.argtypes = []
+    lib.gbdt_debug_geometry.restype = c.c_int
+    lib.gbdt_debug_geometry.argtypes = [c.c_int32, c.c_int32, c.c_int64, c.c_int32,
+                                        c.POINTER(c.c_int64), c.c_int32]
+    lib.gbdt_debug_locate.restype = c.c_int
+    lib.gbdt_debug_locate.argtypes = [c.c_int32, c.c_int32, c.c_int32, c.POINTER(c.c_int32),
+                                      c.POINTER(c.c_int32)]
+    lib.gbdt_profile_enable.restype = c.c_int
+    lib.gbdt_profile_enable.argtypes = [c.c_int]
+    lib.gbdt_profile_collect.restype = c.c_int
+    lib.gbdt_profile_collect.argtypes = [c.POINTER(c.c_double), c.POINTER(c.c_int64)]
+    _lib = lib
+    return lib
+
+
+def _check(rc: int, what: str) -> None:
+    if rc != 0:
+        lib = load()
+        msg = lib.gbdt_strerror(rc).decode()
+        hip = lib.gbdt_last_hip_error().decode()
+        raise GbdtError(f"{what}: {msg} ({rc})" + (f" [{hip}]" if hip and rc == -3 else ""))
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        return int(torch.cuda.current_stream().cuda_stream)
+    if isinstance(stream, torch.cuda.Stream):
+        return int(stream.cuda_stream)
+    return int(stream)
+
+
+def _dev(t: torch.Tensor, dtype, name: str) -> int:
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == dtype and t.is_contiguous()):
+        raise TypeError(f"{name}: expected a contiguous CUDA tensor of dtype {dtype}")
+    return t.data_ptr()
+
+
+def gbdt_strerror(code: int) -> str:
+    return load().gbdt_strerror(int(code)).decode()
+
+
+def gbdt_bins_packed_bytes(n_rows: int, n_features: int, n_bins: int) -> int:
+    return int(load().gbdt_bins_packed_bytes(n_rows, n_features, n_bins))
+
+
+def gbdt_workspace_bytes(n_rows: int, n_features: int, n_bins: int) -> int:
+    return int(load().gbdt_workspace_bytes(n_rows, n_features, n_bins))
+
+
+def gbdt_set_workspace(buf) -> None:
+    """buf: uint8 CUDA tensor (kept alive by the caller) or None."""
+    if buf is None:
+        _check(load().gbdt_set_workspace(None, 0), "gbdt_set_workspace")
+    else:
+        _check(load().gbdt_set_workspace(_dev(buf, torch.uint8, "buf"), buf.numel()),
+               "gbdt_set_workspace")
+
+
+def gbdt_bins_pack(bins_rowmajor: torch.Tensor, n_bins: int, packed_out=None, stream=None):
+    """bins_rowmajor: uint8 [n_rows, n_features] on the GPU.  Returns the packed uint8 buffer."""
+    src = _dev(bins_rowmajor, torch.uint8, "bins_rowmajor")
+    n_rows, n_features = bins_rowmajor.shape
+    nbytes = gbdt_bins_packed_bytes(n_rows, n_features, n_bins)
+    if nbytes == 0 and n_rows != 0:
+        raise GbdtError("gbdt_bins_packed_bytes: invalid argument")
+    if packed_out is None:
+        packed_out = torch.empty(max(nbytes, 1), dtype=torch.uint8, device=bins_rowmajor.device)
+    elif packed_out.numel() < nbytes:
+        raise GbdtError("packed_out too small")
+    _check(load().gbdt_bins_pack(src, n_rows, n_features, n_bins,
+                                 _dev(packed_out, torch.uint8, "packed_out"), _stream(stream)),
+           "gbdt_bins_pack")
+    return packed_out
+
+
+def gbdt_hist_build(bin_matrix, n_rows, n_features, n_bins, leaf_row_idx, n_leaf_rows, grad, hess,
+                    hist_out=None, stream=None):
+    """Returns hist_out: float32 CUDA tensor [n_features, n_bins, 3] holding gbdt_bin_t records
+    (the third word of each record is the uint32 count; see hist_to_numpy)."""
+    if hist_out is None:
+        hist_out = torch.empty((n_features, n_bins, 3), dtype=torch.float32, device=grad.device)
+    idx_p = None if leaf_row_idx is None else _dev(leaf_row_idx, torch.int32, "leaf_row_idx")
+    if leaf_row_idx is not None and leaf_row_idx.numel() < n_leaf_rows:
+        raise GbdtError("leaf_row_idx shorter than n_leaf_rows")
+    if grad.numel() < n_rows or hess.numel() < n_rows:
+        raise GbdtError("grad/hess shorter than n_rows")
+    if bin_matrix.numel() < gbdt_bins_packed_bytes(n_rows, n_features, n_bins):
+        raise GbdtError("bin_matrix smaller than the packed layout of this shape")
+    if hist_out.numel() < n_features * n_bins * 3:
+        raise GbdtError("hist_out too small")
+    _check(load().gbdt_hist_build(_dev(bin_matrix, torch.uint8, "bin_matrix"), n_rows, n_features,
+                                  n_bins, idx_p, n_leaf_rows, _dev(grad, torch.float32, "grad"),
+                                  _dev(hess, torch.float32, "hess"),
+                                  _dev(hist_out, torch.float32, "hist_out"), _stream(stream)),
+           "gbdt_hist_build")
+    return hist_out
+
+
+def gbdt_hist_subtract(parent, child, sibling_out=None, stream=None):
+    n_features, n_bins = parent.shape[0], parent.shape[1]
+    if child.shape != parent.shape:
+        raise GbdtError("parent/child shape mismatch")
+    if sibling_out is None:
+        sibling_out = torch.empty_like(parent)
+    _check(load().gbdt_hist_subtract(_dev(parent, torch.float32, "parent"),
+                                     _dev(child, torch.float32, "child"),
+                                     _dev(sibling_out, torch.float32, "sibling_out"), n_features,
+                                     n_bins, _stream(stream)), "gbdt_hist_subtract")
+    return sibling_out
+
+
+def gbdt_best_split(hist, lam, min_child_hess, split_out=None, stream=None):
+    """Returns split_out: int32 CUDA tensor [9] holding one gbdt_split_t (see split_to_dict)."""
+    n_features, n_bins = hist.shape[0], hist.shape[1]
+    if split_out is None:
+        split_out = torch.empty(9, dtype=torch.int32, device=hist.device)
+    _check(load().gbdt_best_split(_dev(hist, torch.float32, "hist"), float(lam),
+                                  float(min_child_hess), _dev(split_out, torch.int32, "split_out"),
+                                  n_features, n_bins, _stream(stream)), "gbdt_best_split")
+    return split_out
+
+
+GEOMETRY_FIELDS = ["cap", "nib", "wm", "n_main", "wr", "row_bytes", "feat_bytes", "threads",
+                   "lds_bytes", "chunks_main", "chunks_rem", "rows_per_chunk_main",
+                   "rows_per_chunk_rem", "partial_words"]
+
+
+def gbdt_debug_geometry(n_features: int, n_bins: int, n_leaf_rows: int, n_cus: int = 256) -> dict:
+    out = (ctypes.c_int64 * 16)()
+    _check(load().gbdt_debug_geometry(n_features, n_bins, n_leaf_rows, n_cus, out, 16),
+           "gbdt_debug_geometry")
+    return {k: int(out[i]) for i, k in enumerate(GEOMETRY_FIELDS)}
+
+
+def gbdt_debug_locate(n_features: int, n_bins: int, feature: int):
+    t, s = ctypes.c_int32(), ctypes.c_int32()
+    _check(load().gbdt_debug_locate(n_features, n_bins, feature, ctypes.byref(t), ctypes.byref(s)),
+           "gbdt_debug_locate")
+    return t.value, s.value
+
+
+def gbdt_profile_enable(enable: bool) -> None:
+    _check(load().gbdt_profile_enable(1 if enable else 0), "gbdt_profile_enable")
+
+
+def gbdt_profile_collect():
+    """(total build-kernel milliseconds, number of launches) since the last collect."""
+    ms, n = ctypes.c_double(), ctypes.c_int64()
+    _check(load().gbdt_profile_collect(ctypes.byref(ms), ctypes.byref(n)), "gbdt_profile_collect")
+    return ms.value, n.value
+
+
+# ---- host-side views of results (copies to the host; synchronises) -----------------
+
+
+def hist_to_numpy(hist: torch.Tensor) -> np.ndarray:
+    """[n_features, n_bins] structured array (grad f4, hess f4, count u4)."""
+    a = hist.detach().cpu().contiguous().numpy()
+    return a.view(BIN_DTYPE).reshape(a.shape[0], a.shape[1])
+
+
+def split_to_dict(split: torch.Tensor) -> dict:
+    a = split.detach().cpu().contiguous().numpy().view(SPLIT_DTYPE)[0]
+    return {k: a[k].item() for k in SPLIT_DTYPE.names}

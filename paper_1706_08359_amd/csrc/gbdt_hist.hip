@@ -1,0 +1,798 @@
+// libgbdt_hist: feature-histogram construction, sibling subtraction and best-split
+// scan for histogram-based GBDT training on AMD gfx950 (MI355X).
+// Method: arXiv 1706.08359 -- Alg. 1 (Sec. 3.3) defines the histogram, Sec. 4 /
+// Alg. 2 / App. A.1 describe a GPU organisation for older hardware.  What is
+// kept from that design: one lane handles a 4-byte bundle of features of one
+// sample; lanes that work in the same step are steered to different histograms
+// by rotating the feature order per lane; work is split by features and by
+// samples with a final reduction pass; small bin counts get cheaper variants.
+// What is new here is stated at each kernel.
+//
+// Written for gfx950 only: 64-wide wavefronts, 160 KB LDS per CU, native LDS
+// float atomics (ds_add_f32), 256 CUs.
+#include <hip/hip_runtime.h>
+
+#include <stdint.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <mutex>
+#include <utility>
+#include <vector>
+
+#include "../../include/gbdt_hist.h"
+#include "tile_plan.h"
+
+namespace {
+
+// ------------------------------------------------------------------ pack kernel
+
+// One thread writes one 4-byte word of the packed layout (see tile_plan.h).
+// grid.y = tile, grid.x covers n_rows * (W / 4) words of that tile.
+__global__ void __launch_bounds__(256)
+pack_kernel(const uint8_t* __restrict__ src, int64_t n_rows, int32_t n_features, TilePlan plan,
+            uint8_t* __restrict__ dst) {
+  const int32_t t = blockIdx.y;
+  const int32_t w = plan_tile_width(plan, t);
+  const int32_t lpr = w >> 2;
+  const int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (q >= n_rows * lpr) return;
+  const int64_t r = q / lpr;
+  const int32_t j = (int32_t)(q - r * lpr);
+  const int64_t tile_off = n_rows * ((int64_t)t * plan.wm);  // t <= n_main, all earlier tiles are main
+  const uint8_t* row = src + r * (int64_t)n_features;
+  uint32_t word = 0;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int32_t fb = t * plan.wm + 4 * j + i;  // byte of the (virtual, unpadded) packed row
+    uint32_t v;
+    if (plan.nib) {
+      const int32_t f0 = 2 * fb, f1 = 2 * fb + 1;
+      const uint32_t lo = f0 < n_features ? (row[f0] & 15u) : 0u;
+      const uint32_t hi = f1 < n_features ? (row[f1] & 15u) : 0u;
+      v = lo | (hi << 4);
+    } else {
+      v = fb < n_features ? row[fb] : 0u;
+    }
+    word |= v << (8 * i);
+  }
+  *reinterpret_cast<uint32_t*>(dst + tile_off + r * w + 4 * j) = word;
+}
+
+// ----------------------------------------------------------- histogram build kernel
+
+struct BuildArgs {
+  const uint8_t* packed;
+  const int32_t* idx;  // NULL: rows 0..n_leaf-1
+  const float* grad;
+  const float* hess;
+  uint32_t* partials;  // one [3][CAP][SLOTS] block of words per workgroup
+  int64_t n_rows;
+  int64_t n_leaf;
+  int32_t n_main;       // main tiles
+  int32_t wr;           // remainder tile width, 0 if none
+  int32_t chunks_main;  // row chunks per main tile
+  int32_t chunks_rem;   // row chunks of the remainder tile
+  int64_t rows_per_chunk_main;
+  int64_t rows_per_chunk_rem;
+};
+
+// Histogram of rows [begin, end) of the leaf for one feature tile, accumulated in
+// this workgroup's local memory and then copied out as one partial block.
+//
+// Lane mapping.  A row of the tile is LPR = W/4 words; a wavefront load covers
+// RPW = 64/LPR rows: lane = rho * LPR + j loads word j of row rho.  The word's NP
+// features are then handled in NP steps; in step k the lane takes position
+// p = (rho + k) mod NP of its word.  This is the rotation of Alg. 2 (p = (l + s)
+// mod 4 there) used for a stronger purpose: with slot = j + LPR * p, in every
+// step the 32 lanes of a half-wavefront address 32 different slots (W = 64: rho in
+// {0,1} gives two consecutive p, i.e. both parities of p, times 16 values of j;
+// W = 32: rho in 0..3 gives all four p times 8 values of j), and the histogram
+// arrays are [bin][slot] with SLOTS a multiple of 32 words, so the bank is
+// slot mod 32 whatever the bin values are: LDS atomics of a step are free of bank
+// conflicts and of same-address collisions by construction, not by chance as with
+// the paper's 8-way interleave or its banked counters (App. A.1).  (W = 16 tiles,
+// used only for a narrow last tile, have 16 or 32 slots and can still collide.)
+//
+// All updates are LDS atomics (ds_add_f32 / ds_add_u32), so the wavefronts of a
+// workgroup share ONE histogram and no replica has to be reduced afterwards.
+template <int CAP, int W, bool NIB, int NT, bool INDEXED>
+__device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
+                                           const int32_t* __restrict__ idx,
+                                           const float* __restrict__ grad,
+                                           const float* __restrict__ hess, int64_t begin,
+                                           int64_t end, float* lds, uint32_t* __restrict__ out) {
+  constexpr int LPR = W / 4;
+  constexpr int RPW = 64 / LPR;
+  constexpr int NP = NIB ? 8 : 4;
+  constexpr int SLOTS = LPR * NP;
+  constexpr int HW = CAP * SLOTS;  // words per statistic
+  constexpr int NW = NT / 64;
+  constexpr int U = 4;  // row groups in flight per wavefront
+
+  const int tid = threadIdx.x;
+  for (int i = tid; i < 3 * HW; i += NT) lds[i] = 0.0f;
+  __syncthreads();
+
+  float* lg = lds;
+  float* lh = lds + HW;
+  uint32_t* lc = reinterpret_cast<uint32_t*>(lds + 2 * HW);
+
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int j = lane % LPR;
+  const int rho = lane / LPR;
+
+  const int64_t stride = (int64_t)NW * RPW * U;
+  for (int64_t base = begin + (int64_t)wave * (RPW * U); base < end; base += stride) {
+    uint32_t word[U];
+    float g[U], h[U];
+    bool ok[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      int64_t i = base + u * RPW + rho;
+      ok[u] = i < end;
+      i = ok[u] ? i : end - 1;  // clamp: loads stay in range and unpredicated
+      const int64_t r = INDEXED ? (int64_t)idx[i] : i;
+      word[u] = *reinterpret_cast<const uint32_t*>(tile + r * W + 4 * j);
+      g[u] = grad[r];
+      h[u] = hess[r];
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      if (ok[u]) {
+#pragma unroll
+        for (int k = 0; k < NP; ++k) {
+          const int p = (rho + k) & (NP - 1);
+          const uint32_t b = NIB ? ((word[u] >> (4 * p)) & 15u) : ((word[u] >> (8 * p)) & (uint32_t)(CAP - 1));
+          const uint32_t a = b * SLOTS + (uint32_t)(j + LPR * p);
+          __hip_atomic_fetch_add(&lg[a], g[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+          __hip_atomic_fetch_add(&lh[a], h[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+          __hip_atomic_fetch_add(&lc[a], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        }
+      }
+    }
+  }
+  __syncthreads();
+  const uint32_t* lw = reinterpret_cast<const uint32_t*>(lds);
+  for (int i = tid; i < 3 * HW; i += NT) out[i] = lw[i];
+}
+
+// Work is split by feature tiles and by row chunks (Sec. 4, "Parallel By Features
+// and Data"): block -> (tile, chunk).  Consecutive blocks take different tiles of
+// the same chunk, so the chunk's row ids / gradients / hessians are fetched from
+// HBM once and served to the other tiles from cache.
+template <int CAP, int WM, bool NIB, int NT, bool INDEXED>
+__global__ void __launch_bounds__(NT) hist_build_kernel(BuildArgs a) {
+  extern __shared__ __align__(16) float lds[];
+  constexpr int NPF = NIB ? 2 : 1;
+  const int32_t main_blocks = a.n_main * a.chunks_main;
+  const int32_t b = blockIdx.x;
+  if (b < main_blocks) {
+    const int32_t t = b % a.n_main;
+    const int32_t c = b / a.n_main;
+    const int64_t begin = (int64_t)c * a.rows_per_chunk_main;
+    int64_t end = begin + a.rows_per_chunk_main;
+    if (end > a.n_leaf) end = a.n_leaf;
+    const uint8_t* tile = a.packed + a.n_rows * ((int64_t)t * WM);
+    uint32_t* out = a.partials + ((size_t)t * a.chunks_main + c) * (size_t)(3 * CAP * WM * NPF);
+    build_tile<CAP, WM, NIB, NT, INDEXED>(tile, a.idx, a.grad, a.hess, begin, end, lds, out);
+  } else {
+    const int32_t c = b - main_blocks;
+    const int64_t begin = (int64_t)c * a.rows_per_chunk_rem;
+    int64_t end = begin + a.rows_per_chunk_rem;
+    if (end > a.n_leaf) end = a.n_leaf;
+    const uint8_t* tile = a.packed + a.n_rows * ((int64_t)a.n_main * WM);
+    uint32_t* rem_base = a.partials + (size_t)main_blocks * (size_t)(3 * CAP * WM * NPF);
+    if (a.wr == 16) {
+      build_tile<CAP, 16, NIB, NT, INDEXED>(tile, a.idx, a.grad, a.hess, begin, end, lds,
+                                            rem_base + (size_t)c * (size_t)(3 * CAP * 16 * NPF));
+    } else {
+      build_tile<CAP, 32, NIB, NT, INDEXED>(tile, a.idx, a.grad, a.hess, begin, end, lds,
+                                            rem_base + (size_t)c * (size_t)(3 * CAP * 32 * NPF));
+    }
+  }
+}
+
+// ------------------------------------------------------------------ merge kernel
+
+struct MergeArgs {
+  const uint32_t* partials;
+  gbdt_bin_t* out;
+  TilePlan plan;
+  int32_t n_features;
+  int32_t n_bins;
+  int32_t chunks_main;
+  int32_t chunks_rem;
+};
+
+// The "final reduction program" of Sec. 4: sums the partial histograms of the
+// workgroups that shared a feature tile.  One thread per (tile, bin, slot), slot
+// fastest, so the reads of every chunk's block are coalesced; gradient / hessian
+// partials are summed in fp64 in chunk order (deterministic), counts as integers.
+// grid.y = tile.
+__global__ void __launch_bounds__(256) hist_merge_kernel(MergeArgs a) {
+  const int32_t t = blockIdx.y;
+  const int32_t w = plan_tile_width(a.plan, t);
+  const int32_t slots = plan_slots(a.plan, w);
+  const int32_t cap = a.plan.cap;
+  const int32_t e = blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= a.n_bins * slots) return;
+  const int32_t bin = e / slots;
+  const int32_t slot = e - bin * slots;
+  // slot -> feature (inverse of plan_locate)
+  const int32_t lpr = w >> 2;
+  const int32_t pos = slot / lpr;
+  const int32_t j = slot - pos * lpr;
+  int32_t f;
+  if (a.plan.nib) {
+    f = 2 * (t * a.plan.wm + 4 * j + (pos >> 1)) + (pos & 1);
+  } else {
+    f = t * a.plan.wm + 4 * j + pos;
+  }
+  if (f >= a.n_features) return;  // padding slot
+  const size_t hw = (size_t)cap * slots;
+  const size_t main_block = (size_t)3 * cap * plan_slots(a.plan, a.plan.wm);
+  const uint32_t* p;
+  int32_t chunks;
+  if (t < a.plan.n_main) {
+    p = a.partials + (size_t)t * a.chunks_main * main_block;
+    chunks = a.chunks_main;
+  } else {
+    p = a.partials + (size_t)a.plan.n_main * a.chunks_main * main_block;
+    chunks = a.chunks_rem;
+  }
+  p += (size_t)bin * slots + slot;
+  double g = 0.0, h = 0.0;
+  uint32_t n = 0;
+  for (int32_t c = 0; c < chunks; ++c) {
+    g += (double)__uint_as_float(p[0]);
+    h += (double)__uint_as_float(p[hw]);
+    n += p[2 * hw];
+    p += 3 * hw;
+  }
+  gbdt_bin_t r;
+  r.grad = (float)g;
+  r.hess = (float)h;
+  r.count = n;
+  a.out[(size_t)f * a.n_bins + bin] = r;
+}
+
+// --------------------------------------------------------------- subtract kernel
+
+// sibling = parent - child, element by element over [n_features][n_bins].
+__global__ void __launch_bounds__(256)
+hist_subtract_kernel(const gbdt_bin_t* parent, const gbdt_bin_t* child, gbdt_bin_t* sibling,
+                     int32_t n) {
+  const int32_t e = blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= n) return;
+  const gbdt_bin_t p = parent[e];
+  const gbdt_bin_t c = child[e];
+  gbdt_bin_t s;
+  s.grad = p.grad - c.grad;
+  s.hess = p.hess - c.hess;
+  s.count = p.count - c.count;
+  sibling[e] = s;
+}
+
+// Histogram of an empty leaf: all zero.  (A fill kernel, not a memset node, so the
+// call can be captured into a graph.)
+__global__ void __launch_bounds__(256) hist_zero_kernel(gbdt_bin_t* hist, int32_t n) {
+  const int32_t e = blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= n) return;
+  gbdt_bin_t z;
+  z.grad = 0.0f;
+  z.hess = 0.0f;
+  z.count = 0;
+  hist[e] = z;
+}
+
+// ------------------------------------------------------------------ split kernels
+
+struct SplitCand {
+  double gain;
+  double gl, hl, gr, hr;
+  uint32_t nl, nr;
+  int32_t bin;  // -1: feature has no admissible threshold
+  int32_t pad;
+};
+
+// Gain scan of Sec. 3.3 for one feature per thread: totals over the feature's own
+// bins, then a running left prefix over thresholds t = 0..n_bins-2, all in fp64,
+// bins ascending.  The feature's best threshold (first one on equal gain) goes to
+// cand[f].
+__global__ void __launch_bounds__(64)
+split_scan_kernel(const gbdt_bin_t* __restrict__ hist, int32_t n_features, int32_t n_bins,
+                  double lambda, double min_child_hess, SplitCand* __restrict__ cand) {
+  const int32_t f = blockIdx.x * blockDim.x + threadIdx.x;
+  if (f >= n_features) return;
+  const gbdt_bin_t* o = hist + (size_t)f * n_bins;
+  double G = 0.0, H = 0.0;
+  uint32_t N = 0;
+  for (int32_t b = 0; b < n_bins; ++b) {
+    G = G + (double)o[b].grad;
+    H = H + (double)o[b].hess;
+    N = N + o[b].count;
+  }
+  const double parent_term = __ddiv_rn(__dmul_rn(G, G), H + lambda);
+  SplitCand best;
+  best.gain = 0.0;
+  best.bin = -1;
+  best.gl = best.hl = best.gr = best.hr = 0.0;
+  best.nl = best.nr = 0;
+  best.pad = 0;
+  double GL = 0.0, HL = 0.0;
+  uint32_t NL = 0;
+  for (int32_t t = 0; t + 1 < n_bins; ++t) {
+    GL = GL + (double)o[t].grad;
+    HL = HL + (double)o[t].hess;
+    NL = NL + o[t].count;
+    const double GR = G - GL, HR = H - HL;
+    const uint32_t NR = N - NL;
+    const bool ok = NL >= 1u && NR >= 1u && HL >= min_child_hess && HR >= min_child_hess;
+    if (ok) {
+      const double lt = __ddiv_rn(__dmul_rn(GL, GL), HL + lambda);
+      const double rt = __ddiv_rn(__dmul_rn(GR, GR), HR + lambda);
+      const double gain = __dsub_rn(__dadd_rn(lt, rt), parent_term);
+      if (best.bin < 0 || gain > best.gain) {
+        best.gain = gain;
+        best.bin = t;
+        best.gl = GL;
+        best.hl = HL;
+        best.gr = GR;
+        best.hr = HR;
+        best.nl = NL;
+        best.nr = NR;
+      }
+    }
+  }
+  cand[f] = best;
+}
+
+// Arg-max over the per-feature candidates with the tie-break "larger gain, then
+// smaller feature" (the per-feature scan already kept the smaller bin).  One
+// workgroup; each thread folds a strided subset in ascending feature order, then
+// a tree reduction in local memory compares (gain, feature).
+__global__ void __launch_bounds__(256)
+split_argmax_kernel(const SplitCand* __restrict__ cand, int32_t n_features,
+                    gbdt_split_t* __restrict__ out) {
+  __shared__ double s_gain[256];
+  __shared__ int32_t s_feat[256];
+  const int tid = threadIdx.x;
+  double bg = 0.0;
+  int32_t bf = -1;
+  for (int32_t f = tid; f < n_features; f += 256) {
+    if (cand[f].bin >= 0) {
+      const double g = cand[f].gain;
+      if (bf < 0 || g > bg) {  // f ascends, so ties keep the smaller feature
+        bg = g;
+        bf = f;
+      }
+    }
+  }
+  s_gain[tid] = bg;
+  s_feat[tid] = bf;
+  __syncthreads();
+  for (int s = 128; s > 0; s >>= 1) {
+    if (tid < s) {
+      const double g2 = s_gain[tid + s];
+      const int32_t f2 = s_feat[tid + s];
+      const double g1 = s_gain[tid];
+      const int32_t f1 = s_feat[tid];
+      const bool take = f2 >= 0 && (f1 < 0 || g2 > g1 || (g2 == g1 && f2 < f1));
+      if (take) {
+        s_gain[tid] = g2;
+        s_feat[tid] = f2;
+      }
+    }
+    __syncthreads();
+  }
+  if (tid == 0) {
+    gbdt_split_t r;
+    const int32_t f = s_feat[0];
+    if (f < 0) {
+      r.feature = -1;
+      r.bin = -1;
+      r.gain = 0.0f;
+      r.left_grad = r.left_hess = r.right_grad = r.right_hess = 0.0f;
+      r.left_count = r.right_count = 0;
+    } else {
+      const SplitCand c = cand[f];
+      r.feature = f;
+      r.bin = c.bin;
+      r.gain = (float)c.gain;
+      r.left_grad = (float)c.gl;
+      r.left_hess = (float)c.hl;
+      r.left_count = c.nl;
+      r.right_grad = (float)c.gr;
+      r.right_hess = (float)c.hr;
+      r.right_count = c.nr;
+    }
+    *out = r;
+  }
+}
+
+// ------------------------------------------------------------------- host state
+
+thread_local char g_hip_err[256] = "";
+
+int hip_fail(hipError_t e, const char* what) {
+  snprintf(g_hip_err, sizeof g_hip_err, "%s: %s", what, hipGetErrorString(e));
+  return GBDT_EHIP;
+}
+
+#define HIP_TRY(expr)                                  \
+  do {                                                 \
+    hipError_t e_ = (expr);                            \
+    if (e_ != hipSuccess) return hip_fail(e_, #expr);  \
+  } while (0)
+
+struct Workspace {
+  std::mutex mu;
+  void* own = nullptr;  // library-owned scratch
+  size_t own_bytes = 0;
+  int own_device = -1;
+  void* user = nullptr;  // caller-registered scratch
+  size_t user_bytes = 0;
+};
+Workspace g_ws;
+
+// Returns a scratch pointer of at least `bytes`, growing the library-owned buffer
+// when no caller buffer is registered.
+int get_workspace(size_t bytes, void** out) {
+  std::lock_guard<std::mutex> lk(g_ws.mu);
+  if (g_ws.user) {
+    if (bytes > g_ws.user_bytes) return GBDT_ENOMEM;
+    *out = g_ws.user;
+    return GBDT_OK;
+  }
+  int dev = 0;
+  HIP_TRY(hipGetDevice(&dev));
+  if (g_ws.own && (g_ws.own_device != dev || g_ws.own_bytes < bytes)) {
+    HIP_TRY(hipDeviceSynchronize());  // earlier work may still use the old buffer
+    HIP_TRY(hipFree(g_ws.own));
+    g_ws.own = nullptr;
+    g_ws.own_bytes = 0;
+  }
+  if (!g_ws.own) {
+    size_t want = bytes < (size_t)(1 << 20) ? (size_t)(1 << 20) : bytes;
+    hipError_t e = hipMalloc(&g_ws.own, want);
+    if (e != hipSuccess) {
+      g_ws.own = nullptr;
+      hip_fail(e, "hipMalloc(workspace)");
+      return GBDT_ENOMEM;
+    }
+    g_ws.own_bytes = want;
+    g_ws.own_device = dev;
+  }
+  *out = g_ws.own;
+  return GBDT_OK;
+}
+
+// Optional timing of the build kernel alone (it shares its C-ABI call with the merge
+// kernel): when enabled, every gbdt_hist_build records a HIP event on the call's
+// stream right before and right after the build kernel.
+struct Profile {
+  std::mutex mu;
+  bool on = false;
+  std::vector<std::pair<hipEvent_t, hipEvent_t>> pairs;
+};
+Profile g_prof;
+
+int device_cu_count() {
+  static int cached_dev = -1, cached_cus = 0;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return 256;
+  if (dev != cached_dev) {
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+      cus = 256;
+    cached_cus = cus;
+    cached_dev = dev;
+  }
+  return cached_cus;
+}
+
+constexpr size_t kLdsPerCu = 160 * 1024;
+constexpr int kMinRowsPerChunk = 512;
+
+struct BuildGeom {
+  TilePlan plan;
+  int nt;               // threads per workgroup
+  size_t lds_bytes;     // dynamic LDS per workgroup
+  int chunks_main, chunks_rem;
+  int64_t rpc_main, rpc_rem;
+  size_t partial_words;  // total words of all partial blocks
+};
+
+int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+
+// Chooses how many row chunks each tile is cut into so that the grid about fills
+// the machine at the occupancy the LDS footprint allows.
+BuildGeom make_geom(int32_t n_features, int32_t n_bins, int64_t n_leaf, int cus) {
+  BuildGeom g;
+  g.plan = make_tile_plan(n_features, n_bins);
+  const TilePlan& p = g.plan;
+  g.nt = p.cap == 256 ? 1024 : 512;
+  const size_t main_block = (size_t)3 * p.cap * plan_slots(p, p.wm);
+  g.lds_bytes = main_block * 4;
+  int wg_per_cu = (int)(kLdsPerCu / g.lds_bytes);
+  const int by_threads = 2048 / g.nt;
+  if (wg_per_cu > by_threads) wg_per_cu = by_threads;
+  if (wg_per_cu < 1) wg_per_cu = 1;
+  const int64_t resident = (int64_t)cus * wg_per_cu;
+  // remainder tile counted by its share of a main tile's work
+  const double tiles_equiv = p.n_main + (p.wr ? (double)p.wr / p.wm : 0.0);
+  int64_t chunks = (int64_t)((double)resident / (tiles_equiv > 0 ? tiles_equiv : 1.0));
+  const int64_t max_chunks = (n_leaf + kMinRowsPerChunk - 1) / kMinRowsPerChunk;
+  if (chunks > max_chunks) chunks = max_chunks;
+  if (chunks < 1) chunks = 1;
+  g.chunks_main = p.n_main ? (int)chunks : 0;
+  g.rpc_main = p.n_main ? round_up((n_leaf + chunks - 1) / chunks, 64) : 0;
+  if (g.rpc_main < 64) g.rpc_main = 64;
+  if (p.n_main) g.chunks_main = (int)((n_leaf + g.rpc_main - 1) / g.rpc_main);
+  if (p.n_main && g.chunks_main < 1) g.chunks_main = 1;
+  g.chunks_rem = 0;
+  g.rpc_rem = 0;
+  if (p.wr) {
+    int64_t cr = p.n_main ? (chunks * p.wr + p.wm - 1) / p.wm : chunks;
+    if (cr < 1) cr = 1;
+    g.rpc_rem = round_up((n_leaf + cr - 1) / cr, 64);
+    if (g.rpc_rem < 64) g.rpc_rem = 64;
+    g.chunks_rem = (int)((n_leaf + g.rpc_rem - 1) / g.rpc_rem);
+    if (g.chunks_rem < 1) g.chunks_rem = 1;
+  }
+  g.partial_words = (size_t)p.n_main * g.chunks_main * main_block +
+                    (size_t)g.chunks_rem * 3 * p.cap * (p.wr ? plan_slots(p, p.wr) : 0);
+  return g;
+}
+
+bool valid_shape(int64_t n_rows, int32_t n_features, int32_t n_bins) {
+  return n_rows >= 0 && n_features > 0 && n_bins >= 2 && n_bins <= 256;
+}
+
+template <int CAP, int WM, bool NIB, int NT>
+int launch_build(const BuildArgs& a, int blocks, size_t lds_bytes, hipStream_t s) {
+  hipEvent_t ev0 = nullptr, ev1 = nullptr;
+  bool prof = false;
+  {
+    std::lock_guard<std::mutex> lk(g_prof.mu);
+    prof = g_prof.on;
+  }
+  if (prof) {
+    HIP_TRY(hipEventCreate(&ev0));
+    HIP_TRY(hipEventCreate(&ev1));
+    HIP_TRY(hipEventRecord(ev0, s));
+  }
+  if (a.idx) {
+    auto k = hist_build_kernel<CAP, WM, NIB, NT, true>;
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
+    hipLaunchKernelGGL(k, dim3(blocks), dim3(NT), lds_bytes, s, a);
+  } else {
+    auto k = hist_build_kernel<CAP, WM, NIB, NT, false>;
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
+    hipLaunchKernelGGL(k, dim3(blocks), dim3(NT), lds_bytes, s, a);
+  }
+  HIP_TRY(hipGetLastError());
+  if (prof) {
+    HIP_TRY(hipEventRecord(ev1, s));
+    std::lock_guard<std::mutex> lk(g_prof.mu);
+    g_prof.pairs.emplace_back(ev0, ev1);
+  }
+  return GBDT_OK;
+}
+
+}  // namespace
+
+// ----------------------------------------------------------------------- C ABI
+
+extern "C" {
+
+size_t gbdt_bins_packed_bytes(int64_t n_rows, int32_t n_features, int32_t n_bins) {
+  if (!valid_shape(n_rows, n_features, n_bins)) return 0;
+  const TilePlan p = make_tile_plan(n_features, n_bins);
+  return (size_t)n_rows * (size_t)p.row_bytes;
+}
+
+int gbdt_bins_pack(const uint8_t* bins_rowmajor, int64_t n_rows, int32_t n_features,
+                   int32_t n_bins, void* packed_out, void* stream) {
+  if (!valid_shape(n_rows, n_features, n_bins)) return GBDT_EINVAL;
+  if (n_rows == 0) return GBDT_OK;
+  if (!bins_rowmajor || !packed_out) return GBDT_EINVAL;
+  if (((uintptr_t)packed_out & 15u) != 0) return GBDT_EINVAL;
+  if (n_rows >= ((int64_t)1 << 31)) return GBDT_EUNSUPPORTED;
+  const TilePlan p = make_tile_plan(n_features, n_bins);
+  const int tiles = plan_n_tiles(p);
+  if (tiles > 65535) return GBDT_EUNSUPPORTED;
+  const int64_t max_words = n_rows * (p.wm / 4);
+  const int64_t bx = (max_words + 255) / 256;
+  if (bx >= ((int64_t)1 << 31)) return GBDT_EUNSUPPORTED;
+  hipLaunchKernelGGL(pack_kernel, dim3((unsigned)bx, (unsigned)tiles), dim3(256), 0,
+                     (hipStream_t)stream, bins_rowmajor, n_rows, n_features, p,
+                     (uint8_t*)packed_out);
+  HIP_TRY(hipGetLastError());
+  return GBDT_OK;
+}
+
+size_t gbdt_workspace_bytes(int64_t n_rows, int32_t n_features, int32_t n_bins) {
+  if (!valid_shape(n_rows, n_features, n_bins)) return 0;
+  const BuildGeom g = make_geom(n_features, n_bins, n_rows, device_cu_count());
+  size_t b = g.partial_words * 4;
+  const size_t cand = (size_t)n_features * sizeof(SplitCand);
+  if (cand > b) b = cand;
+  return (b + 255) / 256 * 256;
+}
+
+int gbdt_set_workspace(void* dev_ptr, size_t bytes) {
+  if ((dev_ptr == nullptr) != (bytes == 0)) return GBDT_EINVAL;
+  if (((uintptr_t)dev_ptr & 255u) != 0) return GBDT_EINVAL;
+  std::lock_guard<std::mutex> lk(g_ws.mu);
+  g_ws.user = dev_ptr;
+  g_ws.user_bytes = bytes;
+  return GBDT_OK;
+}
+
+int gbdt_hist_build(const void* bin_matrix, int64_t n_rows, int32_t n_features, int32_t n_bins,
+                    const int32_t* leaf_row_idx, int64_t n_leaf_rows, const float* grad,
+                    const float* hess, gbdt_bin_t* hist_out, void* stream) {
+  if (!valid_shape(n_rows, n_features, n_bins)) return GBDT_EINVAL;
+  if (!hist_out) return GBDT_EINVAL;
+  if (n_leaf_rows < 0) return GBDT_EINVAL;
+  if (!leaf_row_idx && n_leaf_rows > n_rows) return GBDT_EINVAL;
+  if (n_rows >= ((int64_t)1 << 31) || n_leaf_rows >= ((int64_t)1 << 31)) return GBDT_EUNSUPPORTED;
+  hipStream_t s = (hipStream_t)stream;
+  if (n_leaf_rows == 0) {
+    const int32_t n = n_features * n_bins;
+    hipLaunchKernelGGL(hist_zero_kernel, dim3((n + 255) / 256), dim3(256), 0, s, hist_out, n);
+    HIP_TRY(hipGetLastError());
+    return GBDT_OK;
+  }
+  if (!bin_matrix || !grad || !hess) return GBDT_EINVAL;
+
+  const BuildGeom g = make_geom(n_features, n_bins, n_leaf_rows, device_cu_count());
+  const TilePlan& p = g.plan;
+  if (plan_n_tiles(p) > 65535) return GBDT_EUNSUPPORTED;
+  void* ws = nullptr;
+  int rc = get_workspace(g.partial_words * 4, &ws);
+  if (rc != GBDT_OK) return rc;
+
+  BuildArgs a;
+  a.packed = (const uint8_t*)bin_matrix;
+  a.idx = leaf_row_idx;
+  a.grad = grad;
+  a.hess = hess;
+  a.partials = (uint32_t*)ws;
+  a.n_rows = n_rows;
+  a.n_leaf = n_leaf_rows;
+  a.n_main = p.n_main;
+  a.wr = p.wr;
+  a.chunks_main = g.chunks_main;
+  a.chunks_rem = g.chunks_rem;
+  a.rows_per_chunk_main = g.rpc_main;
+  a.rows_per_chunk_rem = g.rpc_rem;
+  const int blocks = p.n_main * g.chunks_main + g.chunks_rem;
+
+  if (p.cap == 16) {
+    rc = launch_build<16, 64, true, 512>(a, blocks, g.lds_bytes, s);
+  } else if (p.cap == 64) {
+    rc = launch_build<64, 64, false, 512>(a, blocks, g.lds_bytes, s);
+  } else {
+    rc = launch_build<256, 32, false, 1024>(a, blocks, g.lds_bytes, s);
+  }
+  if (rc != GBDT_OK) return rc;
+
+  MergeArgs m;
+  m.partials = (const uint32_t*)ws;
+  m.out = hist_out;
+  m.plan = p;
+  m.n_features = n_features;
+  m.n_bins = n_bins;
+  m.chunks_main = g.chunks_main;
+  m.chunks_rem = g.chunks_rem;
+  const int max_slots = plan_slots(p, p.wm);
+  const int mx = (n_bins * max_slots + 255) / 256;
+  hipLaunchKernelGGL(hist_merge_kernel, dim3(mx, plan_n_tiles(p)), dim3(256), 0, s, m);
+  HIP_TRY(hipGetLastError());
+  return GBDT_OK;
+}
+
+int gbdt_hist_subtract(const gbdt_bin_t* parent, const gbdt_bin_t* child, gbdt_bin_t* sibling_out,
+                       int32_t n_features, int32_t n_bins, void* stream) {
+  if (!parent || !child || !sibling_out) return GBDT_EINVAL;
+  if (n_features <= 0 || n_bins < 2 || n_bins > 256) return GBDT_EINVAL;
+  const int32_t n = n_features * n_bins;
+  hipLaunchKernelGGL(hist_subtract_kernel, dim3((n + 255) / 256), dim3(256), 0,
+                     (hipStream_t)stream, parent, child, sibling_out, n);
+  HIP_TRY(hipGetLastError());
+  return GBDT_OK;
+}
+
+int gbdt_best_split(const gbdt_bin_t* hist, float lambda, float min_child_hess,
+                    gbdt_split_t* split_out, int32_t n_features, int32_t n_bins, void* stream) {
+  if (!hist || !split_out) return GBDT_EINVAL;
+  if (n_features <= 0 || n_bins < 2 || n_bins > 256) return GBDT_EINVAL;
+  if (!(lambda >= 0.0f)) return GBDT_EINVAL;
+  void* ws = nullptr;
+  int rc = get_workspace((size_t)n_features * sizeof(SplitCand), &ws);
+  if (rc != GBDT_OK) return rc;
+  hipStream_t s = (hipStream_t)stream;
+  hipLaunchKernelGGL(split_scan_kernel, dim3((n_features + 63) / 64), dim3(64), 0, s, hist,
+                     n_features, n_bins, (double)lambda, (double)min_child_hess, (SplitCand*)ws);
+  HIP_TRY(hipGetLastError());
+  hipLaunchKernelGGL(split_argmax_kernel, dim3(1), dim3(256), 0, s, (const SplitCand*)ws,
+                     n_features, split_out);
+  HIP_TRY(hipGetLastError());
+  return GBDT_OK;
+}
+
+int gbdt_debug_geometry(int32_t n_features, int32_t n_bins, int64_t n_leaf_rows, int32_t n_cus,
+                        int64_t* out, int32_t n_out) {
+  if (!out || n_out < 16 || n_features <= 0 || n_bins < 2 || n_bins > 256 || n_leaf_rows < 0)
+    return GBDT_EINVAL;
+  const BuildGeom g = make_geom(n_features, n_bins, n_leaf_rows, n_cus > 0 ? n_cus : 256);
+  const TilePlan& p = g.plan;
+  const int64_t v[16] = {p.cap,         p.nib,          p.wm,          p.n_main,
+                         p.wr,          p.row_bytes,    p.feat_bytes,  g.nt,
+                         (int64_t)g.lds_bytes, g.chunks_main, g.chunks_rem, g.rpc_main,
+                         g.rpc_rem,     (int64_t)g.partial_words, 0, 0};
+  for (int i = 0; i < 16; ++i) out[i] = v[i];
+  return GBDT_OK;
+}
+
+int gbdt_debug_locate(int32_t n_features, int32_t n_bins, int32_t feature, int32_t* tile_out,
+                      int32_t* slot_out) {
+  if (!tile_out || !slot_out || n_features <= 0 || n_bins < 2 || n_bins > 256 || feature < 0 ||
+      feature >= n_features)
+    return GBDT_EINVAL;
+  const TilePlan p = make_tile_plan(n_features, n_bins);
+  const FeatureSlot fs = plan_locate(p, feature);
+  *tile_out = fs.tile;
+  *slot_out = fs.slot;
+  return GBDT_OK;
+}
+
+int gbdt_profile_enable(int enable) {
+  std::lock_guard<std::mutex> lk(g_prof.mu);
+  g_prof.on = enable != 0;
+  return GBDT_OK;
+}
+
+int gbdt_profile_collect(double* build_kernel_ms_total, int64_t* n_launches) {
+  if (!build_kernel_ms_total || !n_launches) return GBDT_EINVAL;
+  std::vector<std::pair<hipEvent_t, hipEvent_t>> pairs;
+  {
+    std::lock_guard<std::mutex> lk(g_prof.mu);
+    pairs.swap(g_prof.pairs);
+  }
+  double total = 0.0;
+  int rc = GBDT_OK;
+  for (auto& pr : pairs) {
+    float ms = 0.0f;
+    hipError_t e = hipEventSynchronize(pr.second);
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, pr.first, pr.second);
+    if (e != hipSuccess && rc == GBDT_OK) rc = hip_fail(e, "hipEventElapsedTime");
+    total += ms;
+    (void)hipEventDestroy(pr.first);
+    (void)hipEventDestroy(pr.second);
+  }
+  *build_kernel_ms_total = total;
+  *n_launches = (int64_t)pairs.size();
+  return rc;
+}
+
+const char* gbdt_strerror(int code) {
+  switch (code) {
+    case GBDT_OK: return "ok";
+    case GBDT_EINVAL: return "invalid argument";
+    case GBDT_EUNSUPPORTED: return "unsupported problem size";
+    case GBDT_EHIP: return "HIP runtime error";
+    case GBDT_ENOMEM: return "workspace allocation failed or too small";
+    default: return "unknown error code";
+  }
+}
+
+const char* gbdt_last_hip_error(void) { return g_hip_err; }
+
+}  // extern "C"

@@ -1,0 +1,115 @@
+"""CPU-only checks of the built C-ABI library: it loads, exports every symbol the
+header declares, rejects bad arguments before touching a GPU, and its host-side
+launch planning (tiles, slots, chunks, workspace) is self-consistent."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_1706_08359_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = B.load()
+    header = open(os.path.join(ROOT, "include", "gbdt_hist.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(gbdt_[a-z_]+)\s*\(", header))
+    assert declared, "no declarations found"
+    assert declared == set(B.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_strerror():
+    assert B.gbdt_strerror(0) == "ok"
+    assert "invalid" in B.gbdt_strerror(-1)
+    assert "unknown" in B.gbdt_strerror(-99)
+
+
+def test_argument_errors_are_rejected_before_any_gpu_work():
+    lib = B.load()
+    EINVAL, EUNSUP = -1, -2
+    assert lib.gbdt_bins_packed_bytes(10, 0, 64) == 0
+    assert lib.gbdt_bins_packed_bytes(10, 5, 1) == 0
+    assert lib.gbdt_bins_packed_bytes(10, 5, 257) == 0
+    assert lib.gbdt_bins_packed_bytes(-1, 5, 64) == 0
+    assert lib.gbdt_workspace_bytes(10, 5, 300) == 0
+    one = ctypes.c_void_p(256)    # never dereferenced: all calls below fail validation first
+    assert lib.gbdt_bins_pack(None, 10, 5, 64, one, None) == EINVAL
+    assert lib.gbdt_bins_pack(one, 10, 5, 64, None, None) == EINVAL
+    assert lib.gbdt_bins_pack(one, 10, 5, 64, ctypes.c_void_p(260), None) == EINVAL   # misaligned
+    assert lib.gbdt_bins_pack(one, 10, 5, 1, one, None) == EINVAL
+    assert lib.gbdt_bins_pack(one, 1 << 31, 5, 64, one, None) == EUNSUP
+    assert lib.gbdt_hist_build(one, 10, 5, 64, None, 5, one, one, None, None) == EINVAL
+    assert lib.gbdt_hist_build(None, 10, 5, 64, None, 5, one, one, one, None) == EINVAL
+    assert lib.gbdt_hist_build(one, 10, 5, 64, None, 5, None, one, one, None) == EINVAL
+    assert lib.gbdt_hist_build(one, 10, 5, 64, None, 5, one, None, one, None) == EINVAL
+    assert lib.gbdt_hist_build(one, 10, 5, 64, None, 11, one, one, one, None) == EINVAL   # root leaf > n_rows
+    assert lib.gbdt_hist_build(one, 10, 5, 64, None, -1, one, one, one, None) == EINVAL
+    assert lib.gbdt_hist_build(one, 10, 5, 0, None, 5, one, one, one, None) == EINVAL
+    assert lib.gbdt_hist_build(one, 10, 5, 257, None, 5, one, one, one, None) == EINVAL
+    assert lib.gbdt_hist_build(one, 10, 0, 64, None, 5, one, one, one, None) == EINVAL
+    assert lib.gbdt_hist_build(one, 1 << 31, 5, 64, None, 5, one, one, one, None) == EUNSUP
+    assert lib.gbdt_hist_subtract(None, one, one, 5, 64, None) == EINVAL
+    assert lib.gbdt_hist_subtract(one, None, one, 5, 64, None) == EINVAL
+    assert lib.gbdt_hist_subtract(one, one, None, 5, 64, None) == EINVAL
+    assert lib.gbdt_hist_subtract(one, one, one, 5, 1, None) == EINVAL
+    assert lib.gbdt_best_split(None, 1.0, 0.0, one, 5, 64, None) == EINVAL
+    assert lib.gbdt_best_split(one, 1.0, 0.0, None, 5, 64, None) == EINVAL
+    assert lib.gbdt_best_split(one, -1.0, 0.0, one, 5, 64, None) == EINVAL
+    assert lib.gbdt_best_split(one, float("nan"), 0.0, one, 5, 64, None) == EINVAL
+    assert lib.gbdt_best_split(one, 1.0, 0.0, one, 0, 64, None) == EINVAL
+    assert lib.gbdt_set_workspace(one, 0) == EINVAL
+    assert lib.gbdt_set_workspace(None, 16) == EINVAL
+    assert lib.gbdt_set_workspace(ctypes.c_void_p(100), 1024) == EINVAL               # misaligned
+    assert lib.gbdt_set_workspace(None, 0) == 0
+
+
+SHAPES = [(1, 2), (3, 16), (4, 17), (27, 63), (28, 64), (28, 255), (33, 64), (64, 64), (65, 65),
+          (100, 256), (137, 255), (129, 16), (130, 16), (255, 16), (257, 16), (700, 16),
+          (2000, 63), (2001, 63), (2047, 64), (968, 255)]
+
+
+@pytest.mark.parametrize("n_features,n_bins", SHAPES)
+def test_tile_plan_is_a_bijection_onto_slots(n_features, n_bins):
+    g = B.gbdt_debug_geometry(n_features, n_bins, 1000)
+    assert g["cap"] >= n_bins and g["cap"] in (16, 64, 256)
+    assert g["nib"] == (1 if n_bins <= 16 else 0)
+    assert g["wm"] == (32 if g["cap"] == 256 else 64) and g["wr"] in (0, 16, 32)
+    assert g["row_bytes"] == g["n_main"] * g["wm"] + g["wr"]
+    per_byte = 2 if g["nib"] else 1
+    assert g["feat_bytes"] == (n_features + per_byte - 1) // per_byte
+    assert g["feat_bytes"] <= g["row_bytes"] < g["feat_bytes"] + g["wm"] // 2 + 16
+    assert B.gbdt_bins_packed_bytes(12345, n_features, n_bins) == 12345 * g["row_bytes"]
+    seen = set()
+    for f in range(n_features):
+        t, s = B.gbdt_debug_locate(n_features, n_bins, f)
+        w = g["wm"] if t < g["n_main"] else g["wr"]
+        assert 0 <= t < g["n_main"] + (1 if g["wr"] else 0) and w > 0
+        assert 0 <= s < w * per_byte
+        assert (t, s) not in seen
+        seen.add((t, s))
+    # largest histogram must fit the LDS the launch requests, and the CU
+    assert g["lds_bytes"] == 3 * g["cap"] * g["wm"] * per_byte * 4 <= 160 * 1024
+
+
+@pytest.mark.parametrize("n_features,n_bins", [(28, 64), (2000, 63), (28, 255), (137, 255), (700, 16), (5, 2)])
+@pytest.mark.parametrize("n_leaf", [1, 63, 64, 65, 511, 512, 513, 4000, 100_003, 10_500_000])
+def test_row_chunks_cover_the_leaf_exactly(n_features, n_bins, n_leaf):
+    g = B.gbdt_debug_geometry(n_features, n_bins, n_leaf)
+    per_byte = 2 if g["nib"] else 1
+    words = 0
+    for chunks, rpc, w, tiles in ((g["chunks_main"], g["rows_per_chunk_main"], g["wm"], g["n_main"]),
+                                  (g["chunks_rem"], g["rows_per_chunk_rem"], g["wr"], 1 if g["wr"] else 0)):
+        if tiles == 0:
+            continue
+        assert chunks >= 1 and rpc >= 1
+        assert chunks * rpc >= n_leaf            # every row belongs to a chunk
+        assert (chunks - 1) * rpc < n_leaf       # no chunk starts past the end
+        words += tiles * chunks * 3 * g["cap"] * w * per_byte
+    assert words == g["partial_words"]
+    assert B.gbdt_workspace_bytes(n_leaf, n_features, n_bins) >= 4 * g["partial_words"]
+    assert (g["n_main"] * g["chunks_main"] + g["chunks_rem"]) < 2 ** 31
