@@ -77,85 +77,186 @@ struct BuildArgs {
   int64_t rows_per_chunk_rem;
 };
 
+// Power-of-two scale 2^k for quantising the values of one epoch to integers: the
+// largest k with 2^k * (sum of |v| over the epoch) + (rounding slack) < 2^31, so
+// that no bin's integer sum can leave 32 bits whatever the bin values are.
+__device__ __forceinline__ int epoch_scale_exp(float sum_abs) {
+  if (!(sum_abs > 0.0f)) return 0;
+  const float m = sum_abs * 1.001953125f;  // covers the rounding of the fp32 sum itself
+  int k = 30 - ilogbf(m);                  // 2^k * m in [2^30, 2^31)
+  if (k > 126) k = 126;
+  if (k < -126) k = -126;
+  if (ldexpf(m, k) > 2147479552.0f) k -= 1;  // keep 2^k * m <= 2^31 - 4096
+  return k;
+}
+
+constexpr int kEpochRows = 4096;  // rows a workgroup accumulates between two drains
+
 // Histogram of rows [begin, end) of the leaf for one feature tile, accumulated in
-// this workgroup's local memory and then copied out as one partial block.
+// this workgroup's local memory and then written out as one partial block.
 //
 // Lane mapping.  A row of the tile is LPR = W/4 words; a wavefront load covers
 // RPW = 64/LPR rows: lane = rho * LPR + j loads word j of row rho.  The word's NP
 // features are then handled in NP steps; in step k the lane takes position
 // p = (rho + k) mod NP of its word.  This is the rotation of Alg. 2 (p = (l + s)
 // mod 4 there) used for a stronger purpose: with slot = j + LPR * p, in every
-// step the 32 lanes of a half-wavefront address 32 different slots (W = 64: rho in
-// {0,1} gives two consecutive p, i.e. both parities of p, times 16 values of j;
-// W = 32: rho in 0..3 gives all four p times 8 values of j), and the histogram
-// arrays are [bin][slot] with SLOTS a multiple of 32 words, so the bank is
-// slot mod 32 whatever the bin values are: LDS atomics of a step are free of bank
-// conflicts and of same-address collisions by construction, not by chance as with
-// the paper's 8-way interleave or its banked counters (App. A.1).  (W = 16 tiles,
-// used only for a narrow last tile, have 16 or 32 slots and can still collide.)
+// step the lanes that the LDS serves together address different slots, and the
+// histogram arrays are [bin][slot], so their banks differ whatever the bin values
+// are: the atomics of a step are free of bank conflicts and of same-address
+// collisions by construction, not by chance as with the paper's 8-way interleave
+// or its banked counters (App. A.1).
 //
-// All updates are LDS atomics (ds_add_f32 / ds_add_u32), so the wavefronts of a
-// workgroup share ONE histogram and no replica has to be reduced afterwards.
+// Arithmetic.  The paper adds floats with a compare-and-swap loop in local memory
+// (App. B.3).  gfx950 has a native LDS float add, but it retires about 0.33
+// lanes/clock/CU against about 16 for a 32-bit and 10 for a 64-bit integer add, so
+// floats are accumulated as integers instead: rows are taken in epochs of at most
+// 4096; per epoch the workgroup sums |grad| and |hess| of the epoch's rows, picks
+// the largest power-of-two scales that cannot overflow 32 bits, and every (row,
+// feature) then costs ONE 64-bit integer atomic that carries the quantised
+// gradient (low half) and hessian (high half), plus one 32-bit atomic for the
+// count.  After each epoch the integer sums are drained into fp64 accumulators
+// held in registers (each thread owns PAIRS/NT bins) and the LDS is cleared.
+// Error: each value is rounded once, by at most half a quantum; the quantum is at
+// most sum|g|_epoch / 2^30, so a bin is off by at most 4096 / 2^31 = 1.9e-6 of the
+// leaf's sum |g| (likewise for h) -- and integer addition is order-independent, so
+// the result is bit-reproducible.
+//
+// All wavefronts of a workgroup share ONE histogram; no replica has to be reduced.
 template <int CAP, int W, bool NIB, int NT, bool INDEXED>
 __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
                                            const int32_t* __restrict__ idx,
                                            const float* __restrict__ grad,
                                            const float* __restrict__ hess, int64_t begin,
-                                           int64_t end, float* lds, uint32_t* __restrict__ out) {
+                                           int64_t end, unsigned long long* lds,
+                                           uint32_t* __restrict__ out) {
   constexpr int LPR = W / 4;
   constexpr int RPW = 64 / LPR;
   constexpr int NP = NIB ? 8 : 4;
   constexpr int SLOTS = LPR * NP;
-  constexpr int HW = CAP * SLOTS;  // words per statistic
+  constexpr int PAIRS = CAP * SLOTS;  // (bin, slot) pairs
+  constexpr int PP = PAIRS / NT;      // pairs drained by one thread
   constexpr int NW = NT / 64;
   constexpr int U = 4;  // row groups in flight per wavefront
+  static_assert(PAIRS % NT == 0, "every thread drains the same number of bins");
+
+  unsigned long long* lgh = lds;                              // [bin][slot] hess:grad
+  uint32_t* lc = reinterpret_cast<uint32_t*>(lds + PAIRS);    // [bin][slot] count
+  float* red = reinterpret_cast<float*>(lc + PAIRS);          // 2 * NW floats
 
   const int tid = threadIdx.x;
-  for (int i = tid; i < 3 * HW; i += NT) lds[i] = 0.0f;
-  __syncthreads();
-
-  float* lg = lds;
-  float* lh = lds + HW;
-  uint32_t* lc = reinterpret_cast<uint32_t*>(lds + 2 * HW);
-
   const int lane = tid & 63;
   const int wave = tid >> 6;
   const int j = lane % LPR;
   const int rho = lane / LPR;
 
-  const int64_t stride = (int64_t)NW * RPW * U;
-  for (int64_t base = begin + (int64_t)wave * (RPW * U); base < end; base += stride) {
-    uint32_t word[U];
-    float g[U], h[U];
-    bool ok[U];
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      int64_t i = base + u * RPW + rho;
-      ok[u] = i < end;
-      i = ok[u] ? i : end - 1;  // clamp: loads stay in range and unpredicated
+  for (int m = 0; m < PP; ++m) {
+    lgh[tid + m * NT] = 0ull;
+    lc[tid + m * NT] = 0u;
+  }
+  double acc_g[PP], acc_h[PP];
+  uint32_t acc_c[PP];
+#pragma unroll
+  for (int m = 0; m < PP; ++m) {
+    acc_g[m] = 0.0;
+    acc_h[m] = 0.0;
+    acc_c[m] = 0u;
+  }
+
+  for (int64_t e0 = begin; e0 < end; e0 += kEpochRows) {
+    const int64_t e1 = e0 + kEpochRows < end ? e0 + kEpochRows : end;
+
+    // ---- scales of this epoch from sum |g|, sum |h| over its rows
+    float sg = 0.0f, sh = 0.0f;
+    for (int64_t i = e0 + tid; i < e1; i += NT) {
       const int64_t r = INDEXED ? (int64_t)idx[i] : i;
-      word[u] = *reinterpret_cast<const uint32_t*>(tile + r * W + 4 * j);
-      g[u] = grad[r];
-      h[u] = hess[r];
+      sg += fabsf(grad[r]);
+      sh += fabsf(hess[r]);
     }
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      if (ok[u]) {
+    for (int o = 32; o > 0; o >>= 1) {
+      sg += __shfl_xor(sg, o);
+      sh += __shfl_xor(sh, o);
+    }
+    if (lane == 0) {
+      red[wave] = sg;
+      red[NW + wave] = sh;
+    }
+    __syncthreads();  // also orders the LDS clearing before the first atomics
+    float tg = 0.0f, th = 0.0f;
 #pragma unroll
-        for (int k = 0; k < NP; ++k) {
-          const int p = (rho + k) & (NP - 1);
-          const uint32_t b = NIB ? ((word[u] >> (4 * p)) & 15u) : ((word[u] >> (8 * p)) & (uint32_t)(CAP - 1));
-          const uint32_t a = b * SLOTS + (uint32_t)(j + LPR * p);
-          __hip_atomic_fetch_add(&lg[a], g[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-          __hip_atomic_fetch_add(&lh[a], h[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-          __hip_atomic_fetch_add(&lc[a], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    for (int q = 0; q < NW; ++q) {
+      tg += red[q];
+      th += red[NW + q];
+    }
+    const int kg = epoch_scale_exp(tg);
+    const int kh = epoch_scale_exp(th);
+    const float scale_g = ldexpf(1.0f, kg);
+    const float scale_h = ldexpf(1.0f, kh);
+
+    // ---- accumulate the epoch's rows
+    const int64_t stride = (int64_t)NW * RPW * U;
+    for (int64_t base = e0 + (int64_t)wave * (RPW * U); base < e1; base += stride) {
+      uint32_t word[U];
+      float g[U], h[U];
+      bool ok[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        int64_t i = base + u * RPW + rho;
+        ok[u] = i < e1;
+        i = ok[u] ? i : e1 - 1;  // clamp: loads stay in range and unpredicated
+        const int64_t r = INDEXED ? (int64_t)idx[i] : i;
+        word[u] = *reinterpret_cast<const uint32_t*>(tile + r * W + 4 * j);
+        g[u] = grad[r];
+        h[u] = hess[r];
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        if (ok[u]) {
+          const int32_t gq = __float2int_rn(g[u] * scale_g);
+          const int32_t hq = __float2int_rn(h[u] * scale_h);
+          // sign-extended gq + (hq << 32) as one 64-bit addend
+          const uint32_t hi = (uint32_t)hq + (uint32_t)(gq >> 31);
+          const unsigned long long add = ((unsigned long long)hi << 32) | (uint32_t)gq;
+#pragma unroll
+          for (int k = 0; k < NP; ++k) {
+            const int p = (rho + k) & (NP - 1);
+            const uint32_t b = NIB ? ((word[u] >> (4 * p)) & 15u)
+                                   : ((word[u] >> (8 * p)) & (uint32_t)(CAP - 1));
+            const uint32_t a = b * SLOTS + (uint32_t)(j + LPR * p);
+            __hip_atomic_fetch_add(&lgh[a], add, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            __hip_atomic_fetch_add(&lc[a], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+          }
         }
       }
     }
+    __syncthreads();
+
+    // ---- drain: integer sums -> fp64 registers, clear the LDS for the next epoch
+    const double inv_g = ldexp(1.0, -kg);
+    const double inv_h = ldexp(1.0, -kh);
+#pragma unroll
+    for (int m = 0; m < PP; ++m) {
+      const int64_t t = (int64_t)lgh[tid + m * NT];
+      const int32_t lo = (int32_t)t;
+      const int32_t hi = (int32_t)((t - (int64_t)lo) >> 32);
+      acc_g[m] += (double)lo * inv_g;
+      acc_h[m] += (double)hi * inv_h;
+      acc_c[m] += lc[tid + m * NT];
+      lgh[tid + m * NT] = 0ull;
+      lc[tid + m * NT] = 0u;
+    }
+    // the next epoch's first barrier separates this clearing from its atomics, and
+    // this epoch's reads of `red` (before the accumulate loop) from its rewriting
   }
-  __syncthreads();
-  const uint32_t* lw = reinterpret_cast<const uint32_t*>(lds);
-  for (int i = tid; i < 3 * HW; i += NT) out[i] = lw[i];
+
+  // partial block layout: [stat][bin][slot] words, pair index = bin * SLOTS + slot
+#pragma unroll
+  for (int m = 0; m < PP; ++m) {
+    out[tid + m * NT] = __float_as_uint((float)acc_g[m]);
+    out[PAIRS + tid + m * NT] = __float_as_uint((float)acc_h[m]);
+    out[2 * PAIRS + tid + m * NT] = acc_c[m];
+  }
 }
 
 // Work is split by feature tiles and by row chunks (Sec. 4, "Parallel By Features
@@ -164,7 +265,7 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
 // HBM once and served to the other tiles from cache.
 template <int CAP, int WM, bool NIB, int NT, bool INDEXED>
 __global__ void __launch_bounds__(NT) hist_build_kernel(BuildArgs a) {
-  extern __shared__ __align__(16) float lds[];
+  extern __shared__ __align__(16) unsigned long long lds[];
   constexpr int NPF = NIB ? 2 : 1;
   const int32_t main_blocks = a.n_main * a.chunks_main;
   const int32_t b = blockIdx.x;
@@ -515,7 +616,7 @@ BuildGeom make_geom(int32_t n_features, int32_t n_bins, int64_t n_leaf, int cus)
   const TilePlan& p = g.plan;
   g.nt = p.cap == 256 ? 1024 : 512;
   const size_t main_block = (size_t)3 * p.cap * plan_slots(p, p.wm);
-  g.lds_bytes = main_block * 4;
+  g.lds_bytes = main_block * 4 + 2 * (g.nt / 64) * sizeof(float);
   int wg_per_cu = (int)(kLdsPerCu / g.lds_bytes);
   const int by_threads = 2048 / g.nt;
   if (wg_per_cu > by_threads) wg_per_cu = by_threads;

@@ -93,7 +93,7 @@ def test_tile_plan_is_a_bijection_onto_slots(n_features, n_bins):
         assert (t, s) not in seen
         seen.add((t, s))
     # largest histogram must fit the LDS the launch requests, and the CU
-    assert g["lds_bytes"] == 3 * g["cap"] * g["wm"] * per_byte * 4 <= 160 * 1024
+    assert 3 * g["cap"] * g["wm"] * per_byte * 4 <= g["lds_bytes"] <= 160 * 1024
 
 
 @pytest.mark.parametrize("n_features,n_bins", [(28, 64), (2000, 63), (28, 255), (137, 255), (700, 16), (5, 2)])
