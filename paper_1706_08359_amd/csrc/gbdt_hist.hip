@@ -95,16 +95,21 @@ constexpr int kEpochRows = 4096;  // rows a workgroup accumulates between two dr
 // Histogram of rows [begin, end) of the leaf for one feature tile, accumulated in
 // this workgroup's local memory and then written out as one partial block.
 //
-// Lane mapping.  A row of the tile is LPR = W/4 words; a wavefront load covers
-// RPW = 64/LPR rows: lane = rho * LPR + j loads word j of row rho.  The word's NP
-// features are then handled in NP steps; in step k the lane takes position
-// p = (rho + k) mod NP of its word.  This is the rotation of Alg. 2 (p = (l + s)
-// mod 4 there) used for a stronger purpose: with slot = j + LPR * p, in every
-// step the lanes that the LDS serves together address different slots, and the
-// histogram arrays are [bin][slot], so their banks differ whatever the bin values
-// are: the atomics of a step are free of bank conflicts and of same-address
-// collisions by construction, not by chance as with the paper's 8-way interleave
-// or its banked counters (App. A.1).
+// Lane mapping.  A lane loads VEC bytes (8 from a 64-byte tile row, else 4), so a
+// row is LPR = W/VEC lane-chunks and a wavefront load covers RPW = 64/LPR rows:
+// lane = rho * LPR + j loads chunk j of row rho.  The chunk's NP features are then
+// handled in NP steps, and the order of the steps is rotated by the lane's row:
+// in step k the lane takes position p = (rho + k) mod (positions per word), in a
+// word that is also swapped by row when a lane holds two words.  This is the
+// rotation of Alg. 2 (p = (l + s) mod 4 there) used for a stronger purpose: with
+// slot = j + LPR * p, in every step the lanes that the LDS serves together (16
+// for a 64-bit atomic, 32 for a 32-bit one) address different, consecutive slots,
+// and the histogram arrays are [bin][slot] with a row length that is a multiple of
+// all 32 banks, so the bank is fixed by the slot whatever the bin values are: the
+// atomics of a step are free of bank conflicts and of same-address collisions by
+// construction, not by chance as with the paper's 8-way interleave or its banked
+// counters (App. A.1).  (16-byte tiles, used only for a narrow last tile, keep
+// this for the 64-bit atomics only.)
 //
 // Arithmetic.  The paper adds floats with a compare-and-swap loop in local memory
 // (App. B.3).  gfx950 has a native LDS float add, but it retires about 0.33
@@ -114,8 +119,8 @@ constexpr int kEpochRows = 4096;  // rows a workgroup accumulates between two dr
 // the largest power-of-two scales that cannot overflow 32 bits, and every (row,
 // feature) then costs ONE 64-bit integer atomic that carries the quantised
 // gradient (low half) and hessian (high half), plus one 32-bit atomic for the
-// count.  After each epoch the integer sums are drained into fp64 accumulators
-// held in registers (each thread owns PAIRS/NT bins) and the LDS is cleared.
+// count.  After each epoch the integer sums are drained into accumulators held in
+// registers (each thread owns PAIRS/NT bins) and the LDS is cleared.
 // Error: each value is rounded once, by at most half a quantum; the quantum is at
 // most sum|g|_epoch / 2^30, so a bin is off by at most 4096 / 2^31 = 1.9e-6 of the
 // leaf's sum |g| (likewise for h) -- and integer addition is order-independent, so
@@ -126,61 +131,103 @@ template <int CAP, int W, bool NIB, int NT, bool INDEXED>
 __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
                                            const int32_t* __restrict__ idx,
                                            const float* __restrict__ grad,
-                                           const float* __restrict__ hess, int64_t begin,
-                                           int64_t end, unsigned long long* lds,
+                                           const float* __restrict__ hess, uint32_t begin,
+                                           uint32_t end, unsigned long long* lds,
                                            uint32_t* __restrict__ out) {
-  constexpr int LPR = W / 4;
+  constexpr int VEC = W == 64 ? 8 : 4;   // bytes a lane loads
+  constexpr int NWORD = VEC / 4;
+  constexpr int LPR = W / VEC;
   constexpr int RPW = 64 / LPR;
-  constexpr int NP = NIB ? 8 : 4;
+  constexpr int NPW = NIB ? 8 : 4;       // positions per 32-bit word
+  constexpr int NP = NPW * NWORD;
   constexpr int SLOTS = LPR * NP;
-  constexpr int PAIRS = CAP * SLOTS;  // (bin, slot) pairs
-  constexpr int PP = PAIRS / NT;      // pairs drained by one thread
+  constexpr int STRIDE = (!NIB && CAP == 64) ? 64 : SLOTS;  // slots per bin row
+  constexpr int PAIRS = CAP * STRIDE;    // (bin, slot) cells
+  constexpr int PP = PAIRS / NT;         // cells drained by one thread
   constexpr int NW = NT / 64;
-  constexpr int U = 4;  // row groups in flight per wavefront
-  static_assert(PAIRS % NT == 0, "every thread drains the same number of bins");
+  constexpr int U = 2;                   // row groups per register set (two sets in flight)
+  constexpr bool PERM = !NIB && STRIDE == 64;  // count address = (bin << 8) | 4 * slot
+  constexpr int ROW_SHIFT = NIB ? (STRIDE == 128 ? 9 : (STRIDE == 64 ? 8 : 7))
+                                : (STRIDE == 64 ? 8 : (STRIDE == 32 ? 7 : 6));
+  static_assert((4 * STRIDE) == (1 << ROW_SHIFT), "count row bytes must be a power of two");
+  static_assert(PAIRS % NT == 0, "every thread drains the same number of cells");
 
-  unsigned long long* lgh = lds;                              // [bin][slot] hess:grad
-  uint32_t* lc = reinterpret_cast<uint32_t*>(lds + PAIRS);    // [bin][slot] count
-  float* red = reinterpret_cast<float*>(lc + PAIRS);          // 2 * NW floats
+  char* lgh = reinterpret_cast<char*>(lds);                    // u64 [bin][STRIDE] hess:grad
+  char* lc = reinterpret_cast<char*>(lds + PAIRS);             // u32 [bin][STRIDE] count
+  float* red = reinterpret_cast<float*>(lc + 4 * PAIRS);       // 2 * NW floats
+  unsigned long long* lgh64 = lds;
+  uint32_t* lc32 = reinterpret_cast<uint32_t*>(lc);
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = tid >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, kept scalar
   const int j = lane % LPR;
   const int rho = lane / LPR;
 
+  // Per-lane constants of the rotated step order.  pw[k]: position inside a word
+  // taken in step k (k and k + NPW share it).  swap: lanes of rows 4..7 take their
+  // two words in the opposite order (u8, two words), so that 8 rows x 8 positions
+  // stay pairwise different.
+  const bool swap = (!NIB && NWORD == 2) ? ((rho >> 2) & 1) : false;
+  uint32_t sel[4];      // PERM: byte-permute selectors
+  uint32_t tbl[2];      // PERM: 4 * slot of the 4 positions of the first / second word taken
+  uint32_t sh[NPW];     // generic: bit offset of the position inside its word
+  uint32_t s4[NPW];     // generic: 4 * slot of the position in word 0
+  if (PERM) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const uint32_t q = (uint32_t)(rho + k) & 3u;
+      sel[k] = 0x0c0c0000u | ((4u + q) << 8) | q;  // byte1 = word byte q, byte0 = table byte q
+    }
+#pragma unroll
+    for (int wi = 0; wi < 2; ++wi) {
+      const int word_taken = swap ? (1 - wi) : wi;
+      uint32_t t = 0;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) t |= (uint32_t)(4 * (j + LPR * (4 * word_taken + q))) << (8 * q);
+      tbl[wi] = t;
+    }
+  } else {
+#pragma unroll
+    for (int k = 0; k < NPW; ++k) {
+      const uint32_t q = (uint32_t)(rho + k) & (uint32_t)(NPW - 1);
+      sh[k] = q * (NIB ? 4u : 8u);
+      s4[k] = 4u * (uint32_t)(j + LPR * (int)q);
+    }
+  }
+
 #pragma unroll
   for (int m = 0; m < PP; ++m) {
-    lgh[tid + m * NT] = 0ull;
-    lc[tid + m * NT] = 0u;
+    lgh64[tid + m * NT] = 0ull;
+    lc32[tid + m * NT] = 0u;
   }
-  double acc_g[PP], acc_h[PP];
+  float acc_g[PP], acc_h[PP];
   uint32_t acc_c[PP];
 #pragma unroll
   for (int m = 0; m < PP; ++m) {
-    acc_g[m] = 0.0;
-    acc_h[m] = 0.0;
+    acc_g[m] = 0.0f;
+    acc_h[m] = 0.0f;
     acc_c[m] = 0u;
   }
 
-  for (int64_t e0 = begin; e0 < end; e0 += kEpochRows) {
-    const int64_t e1 = e0 + kEpochRows < end ? e0 + kEpochRows : end;
+  for (uint32_t e0 = begin; e0 < end; e0 += kEpochRows) {
+    const uint32_t e1 = (end - e0 > (uint32_t)kEpochRows) ? e0 + kEpochRows : end;
 
     // ---- scales of this epoch from sum |g|, sum |h| over its rows
-    float sg = 0.0f, sh = 0.0f;
-    for (int64_t i = e0 + tid; i < e1; i += NT) {
-      const int64_t r = INDEXED ? (int64_t)idx[i] : i;
-      sg += fabsf(grad[r]);
-      sh += fabsf(hess[r]);
+    float sg = 0.0f, sh_abs = 0.0f;
+    for (uint32_t i = e0 + tid; i < e1; i += NT) {
+      const uint32_t r = INDEXED ? (uint32_t)idx[i] : i;
+      sg += fabsf(*reinterpret_cast<const float*>(reinterpret_cast<const char*>(grad) + (r << 2)));
+      sh_abs += fabsf(*reinterpret_cast<const float*>(reinterpret_cast<const char*>(hess) + (r << 2)));
     }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) {
       sg += __shfl_xor(sg, o);
-      sh += __shfl_xor(sh, o);
+      sh_abs += __shfl_xor(sh_abs, o);
     }
     if (lane == 0) {
       red[wave] = sg;
-      red[NW + wave] = sh;
+      red[NW + wave] = sh_abs;
     }
     __syncthreads();  // also orders the LDS clearing before the first atomics
     float tg = 0.0f, th = 0.0f;
@@ -194,69 +241,124 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
     const float scale_g = ldexpf(1.0f, kg);
     const float scale_h = ldexpf(1.0f, kh);
 
-    // ---- accumulate the epoch's rows
-    const int64_t stride = (int64_t)NW * RPW * U;
-    for (int64_t base = e0 + (int64_t)wave * (RPW * U); base < e1; base += stride) {
-      uint32_t word[U];
-      float g[U], h[U];
-      bool ok[U];
+    // ---- accumulate the epoch's rows.  Each wavefront walks its row groups with
+    // the loads of the next U groups in flight while the current U are added
+    // (two register sets, A and B, alternate).  Rows past the epoch end are
+    // clamped to its last row for the loads and add zero.
+    constexpr uint32_t kStep = (uint32_t)NW * RPW * U;
+    auto load_set = [&](uint32_t base, uint2 (&w)[U], float (&g)[U], float (&h)[U],
+                        uint32_t (&one)[U]) {
 #pragma unroll
       for (int u = 0; u < U; ++u) {
-        int64_t i = base + u * RPW + rho;
-        ok[u] = i < e1;
-        i = ok[u] ? i : e1 - 1;  // clamp: loads stay in range and unpredicated
-        const int64_t r = INDEXED ? (int64_t)idx[i] : i;
-        word[u] = *reinterpret_cast<const uint32_t*>(tile + r * W + 4 * j);
-        g[u] = grad[r];
-        h[u] = hess[r];
-      }
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        if (ok[u]) {
-          const int32_t gq = __float2int_rn(g[u] * scale_g);
-          const int32_t hq = __float2int_rn(h[u] * scale_h);
-          // sign-extended gq + (hq << 32) as one 64-bit addend
-          const uint32_t hi = (uint32_t)hq + (uint32_t)(gq >> 31);
-          const unsigned long long add = ((unsigned long long)hi << 32) | (uint32_t)gq;
-#pragma unroll
-          for (int k = 0; k < NP; ++k) {
-            const int p = (rho + k) & (NP - 1);
-            const uint32_t b = NIB ? ((word[u] >> (4 * p)) & 15u)
-                                   : ((word[u] >> (8 * p)) & (uint32_t)(CAP - 1));
-            const uint32_t a = b * SLOTS + (uint32_t)(j + LPR * p);
-            __hip_atomic_fetch_add(&lgh[a], add, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-            __hip_atomic_fetch_add(&lc[a], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-          }
+        uint32_t i = base + u * RPW + rho;
+        const bool ok = i < e1;
+        one[u] = ok ? 1u : 0u;
+        i = ok ? i : e1 - 1;  // clamp: loads stay in range and unpredicated
+        const uint32_t r = INDEXED ? (uint32_t)*reinterpret_cast<const int32_t*>(
+                                         reinterpret_cast<const char*>(idx) + (i << 2))
+                                   : i;
+        const uint32_t off = r * (uint32_t)W + (uint32_t)(VEC * j);
+        if (NWORD == 2) {
+          w[u] = *reinterpret_cast<const uint2*>(tile + off);
+        } else {
+          w[u].x = *reinterpret_cast<const uint32_t*>(tile + off);
+          w[u].y = 0;
         }
+        // 32-bit byte offsets (n_rows < 2^30) keep the address arithmetic out of 64 bits
+        g[u] = *reinterpret_cast<const float*>(reinterpret_cast<const char*>(grad) + (r << 2));
+        h[u] = *reinterpret_cast<const float*>(reinterpret_cast<const char*>(hess) + (r << 2));
+      }
+    };
+    auto add_set = [&](const uint2 (&w)[U], const float (&g)[U], const float (&h)[U],
+                       const uint32_t (&one)[U]) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        int32_t gq = __float2int_rn(g[u] * scale_g);
+        int32_t hq = __float2int_rn(h[u] * scale_h);
+        gq = one[u] ? gq : 0;
+        hq = one[u] ? hq : 0;
+        // sign-extended gq + (hq << 32) as one 64-bit addend
+        const uint32_t hi = (uint32_t)hq + (uint32_t)(gq >> 31);
+        const unsigned long long add = ((unsigned long long)hi << 32) | (uint32_t)gq;
+        uint32_t wa = w[u].x, wb = w[u].y;
+        if (!NIB && CAP == 64) {  // keep a stray bin value inside the histogram
+          wa &= 0x3f3f3f3fu;
+          wb &= 0x3f3f3f3fu;
+        }
+        if (PERM && NWORD == 2 && swap) {
+          const uint32_t t = wa;
+          wa = wb;
+          wb = t;
+        }
+#pragma unroll
+        for (int k = 0; k < NP; ++k) {
+          const int wi = k / NPW;  // first or second word taken (compile time)
+          const int kk = k % NPW;
+          const uint32_t word = wi == 0 ? wa : wb;
+          uint32_t a4;  // byte offset of the cell in the count array
+          if (PERM) {
+            a4 = __builtin_amdgcn_perm(word, tbl[wi], sel[kk]);
+          } else {
+            const uint32_t b = __builtin_amdgcn_ubfe(word, sh[kk], NIB ? 4u : 8u);
+            a4 = (b << ROW_SHIFT) + s4[kk] + (uint32_t)(wi * 4 * LPR * NPW);
+          }
+          __hip_atomic_fetch_add(reinterpret_cast<unsigned long long*>(lgh + 2 * a4), add,
+                                 __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+          __hip_atomic_fetch_add(reinterpret_cast<uint32_t*>(lc + a4), one[u], __ATOMIC_RELAXED,
+                                 __HIP_MEMORY_SCOPE_WORKGROUP);
+        }
+      }
+    };
+    {
+      uint2 aw[U], bw[U];
+      uint32_t aone[U], bone[U];
+      float ag[U], ah[U], bg[U], bh[U];
+      // Loads are issued unconditionally (clamped rows), so that the wait counts
+      // between a set's loads and its use are the same on every path.
+      uint32_t base = e0 + (uint32_t)wave * (RPW * U);
+      load_set(base, aw, ag, ah, aone);
+      while (base < e1) {
+        load_set(base + kStep, bw, bg, bh, bone);
+        add_set(aw, ag, ah, aone);
+        load_set(base + 2 * kStep, aw, ag, ah, aone);
+        add_set(bw, bg, bh, bone);  // all-zero addends when this set lies past the end
+        base += 2 * kStep;
       }
     }
     __syncthreads();
 
-    // ---- drain: integer sums -> fp64 registers, clear the LDS for the next epoch
-    const double inv_g = ldexp(1.0, -kg);
-    const double inv_h = ldexp(1.0, -kh);
+    // ---- drain: integer sums -> registers, clear the LDS for the next epoch
+    const float inv_g = ldexpf(1.0f, -kg);
+    const float inv_h = ldexpf(1.0f, -kh);
 #pragma unroll
     for (int m = 0; m < PP; ++m) {
-      const int64_t t = (int64_t)lgh[tid + m * NT];
+      const int64_t t = (int64_t)lgh64[tid + m * NT];
       const int32_t lo = (int32_t)t;
       const int32_t hi = (int32_t)((t - (int64_t)lo) >> 32);
-      acc_g[m] += (double)lo * inv_g;
-      acc_h[m] += (double)hi * inv_h;
-      acc_c[m] += lc[tid + m * NT];
-      lgh[tid + m * NT] = 0ull;
-      lc[tid + m * NT] = 0u;
+      // exact product of an integer and a power of two, rounded once to fp32
+      acc_g[m] += (float)((double)lo * (double)inv_g);
+      acc_h[m] += (float)((double)hi * (double)inv_h);
+      acc_c[m] += lc32[tid + m * NT];
+      lgh64[tid + m * NT] = 0ull;
+      lc32[tid + m * NT] = 0u;
     }
     // the next epoch's first barrier separates this clearing from its atomics, and
     // this epoch's reads of `red` (before the accumulate loop) from its rewriting
   }
 
-  // partial block layout: [stat][bin][slot] words, pair index = bin * SLOTS + slot
+  // partial block layout: [stat][bin][STRIDE] words, cell index = bin * STRIDE + slot
 #pragma unroll
   for (int m = 0; m < PP; ++m) {
-    out[tid + m * NT] = __float_as_uint((float)acc_g[m]);
-    out[PAIRS + tid + m * NT] = __float_as_uint((float)acc_h[m]);
+    out[tid + m * NT] = __float_as_uint(acc_g[m]);
+    out[PAIRS + tid + m * NT] = __float_as_uint(acc_h[m]);
     out[2 * PAIRS + tid + m * NT] = acc_c[m];
   }
+}
+
+// Words of one partial block of a tile of width w.
+template <int CAP, bool NIB>
+__device__ __host__ constexpr int block_words(int w) {
+  return 3 * CAP * ((!NIB && CAP == 64) ? 64 : (NIB ? 2 * w : w));
 }
 
 // Work is split by feature tiles and by row chunks (Sec. 4, "Parallel By Features
@@ -265,32 +367,34 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
 // HBM once and served to the other tiles from cache.
 template <int CAP, int WM, bool NIB, int NT, bool INDEXED>
 __global__ void __launch_bounds__(NT) hist_build_kernel(BuildArgs a) {
-  extern __shared__ __align__(16) unsigned long long lds[];
-  constexpr int NPF = NIB ? 2 : 1;
+  // one histogram of the main tile width (12 bytes per cell) + the reduction scratch
+  constexpr int kLdsBytes = 4 * block_words<CAP, NIB>(WM) + 2 * (NT / 64) * 4;
+  __shared__ __align__(16) unsigned long long lds[(kLdsBytes + 7) / 8];
   const int32_t main_blocks = a.n_main * a.chunks_main;
   const int32_t b = blockIdx.x;
+  const uint32_t n_leaf = (uint32_t)a.n_leaf;
   if (b < main_blocks) {
     const int32_t t = b % a.n_main;
     const int32_t c = b / a.n_main;
-    const int64_t begin = (int64_t)c * a.rows_per_chunk_main;
-    int64_t end = begin + a.rows_per_chunk_main;
-    if (end > a.n_leaf) end = a.n_leaf;
+    const uint32_t begin = (uint32_t)c * (uint32_t)a.rows_per_chunk_main;
+    uint32_t end = begin + (uint32_t)a.rows_per_chunk_main;
+    if (end > n_leaf) end = n_leaf;
     const uint8_t* tile = a.packed + a.n_rows * ((int64_t)t * WM);
-    uint32_t* out = a.partials + ((size_t)t * a.chunks_main + c) * (size_t)(3 * CAP * WM * NPF);
+    uint32_t* out = a.partials + ((size_t)t * a.chunks_main + c) * (size_t)block_words<CAP, NIB>(WM);
     build_tile<CAP, WM, NIB, NT, INDEXED>(tile, a.idx, a.grad, a.hess, begin, end, lds, out);
   } else {
     const int32_t c = b - main_blocks;
-    const int64_t begin = (int64_t)c * a.rows_per_chunk_rem;
-    int64_t end = begin + a.rows_per_chunk_rem;
-    if (end > a.n_leaf) end = a.n_leaf;
+    const uint32_t begin = (uint32_t)c * (uint32_t)a.rows_per_chunk_rem;
+    uint32_t end = begin + (uint32_t)a.rows_per_chunk_rem;
+    if (end > n_leaf) end = n_leaf;
     const uint8_t* tile = a.packed + a.n_rows * ((int64_t)a.n_main * WM);
-    uint32_t* rem_base = a.partials + (size_t)main_blocks * (size_t)(3 * CAP * WM * NPF);
+    uint32_t* rem_base = a.partials + (size_t)main_blocks * (size_t)block_words<CAP, NIB>(WM);
     if (a.wr == 16) {
       build_tile<CAP, 16, NIB, NT, INDEXED>(tile, a.idx, a.grad, a.hess, begin, end, lds,
-                                            rem_base + (size_t)c * (size_t)(3 * CAP * 16 * NPF));
+                                            rem_base + (size_t)c * (size_t)block_words<CAP, NIB>(16));
     } else {
       build_tile<CAP, 32, NIB, NT, INDEXED>(tile, a.idx, a.grad, a.hess, begin, end, lds,
-                                            rem_base + (size_t)c * (size_t)(3 * CAP * 32 * NPF));
+                                            rem_base + (size_t)c * (size_t)block_words<CAP, NIB>(32));
     }
   }
 }
@@ -316,24 +420,16 @@ __global__ void __launch_bounds__(256) hist_merge_kernel(MergeArgs a) {
   const int32_t t = blockIdx.y;
   const int32_t w = plan_tile_width(a.plan, t);
   const int32_t slots = plan_slots(a.plan, w);
+  const int32_t stride = plan_stride(a.plan, w);
   const int32_t cap = a.plan.cap;
   const int32_t e = blockIdx.x * blockDim.x + threadIdx.x;
   if (e >= a.n_bins * slots) return;
   const int32_t bin = e / slots;
   const int32_t slot = e - bin * slots;
-  // slot -> feature (inverse of plan_locate)
-  const int32_t lpr = w >> 2;
-  const int32_t pos = slot / lpr;
-  const int32_t j = slot - pos * lpr;
-  int32_t f;
-  if (a.plan.nib) {
-    f = 2 * (t * a.plan.wm + 4 * j + (pos >> 1)) + (pos & 1);
-  } else {
-    f = t * a.plan.wm + 4 * j + pos;
-  }
+  const int32_t f = plan_feature_of(a.plan, t, slot);
   if (f >= a.n_features) return;  // padding slot
-  const size_t hw = (size_t)cap * slots;
-  const size_t main_block = (size_t)3 * cap * plan_slots(a.plan, a.plan.wm);
+  const size_t hw = (size_t)cap * stride;
+  const size_t main_block = (size_t)3 * cap * plan_stride(a.plan, a.plan.wm);
   const uint32_t* p;
   int32_t chunks;
   if (t < a.plan.n_main) {
@@ -343,7 +439,7 @@ __global__ void __launch_bounds__(256) hist_merge_kernel(MergeArgs a) {
     p = a.partials + (size_t)a.plan.n_main * a.chunks_main * main_block;
     chunks = a.chunks_rem;
   }
-  p += (size_t)bin * slots + slot;
+  p += (size_t)bin * stride + slot;
   double g = 0.0, h = 0.0;
   uint32_t n = 0;
   for (int32_t c = 0; c < chunks; ++c) {
@@ -615,7 +711,7 @@ BuildGeom make_geom(int32_t n_features, int32_t n_bins, int64_t n_leaf, int cus)
   g.plan = make_tile_plan(n_features, n_bins);
   const TilePlan& p = g.plan;
   g.nt = p.cap == 256 ? 1024 : 512;
-  const size_t main_block = (size_t)3 * p.cap * plan_slots(p, p.wm);
+  const size_t main_block = (size_t)3 * p.cap * plan_stride(p, p.wm);
   g.lds_bytes = main_block * 4 + 2 * (g.nt / 64) * sizeof(float);
   int wg_per_cu = (int)(kLdsPerCu / g.lds_bytes);
   const int by_threads = 2048 / g.nt;
@@ -644,7 +740,7 @@ BuildGeom make_geom(int32_t n_features, int32_t n_bins, int64_t n_leaf, int cus)
     if (g.chunks_rem < 1) g.chunks_rem = 1;
   }
   g.partial_words = (size_t)p.n_main * g.chunks_main * main_block +
-                    (size_t)g.chunks_rem * 3 * p.cap * (p.wr ? plan_slots(p, p.wr) : 0);
+                    (size_t)g.chunks_rem * 3 * p.cap * (p.wr ? plan_stride(p, p.wr) : 0);
   return g;
 }
 
@@ -653,7 +749,7 @@ bool valid_shape(int64_t n_rows, int32_t n_features, int32_t n_bins) {
 }
 
 template <int CAP, int WM, bool NIB, int NT>
-int launch_build(const BuildArgs& a, int blocks, size_t lds_bytes, hipStream_t s) {
+int launch_build(const BuildArgs& a, int blocks, hipStream_t s) {
   hipEvent_t ev0 = nullptr, ev1 = nullptr;
   bool prof = false;
   {
@@ -666,15 +762,9 @@ int launch_build(const BuildArgs& a, int blocks, size_t lds_bytes, hipStream_t s
     HIP_TRY(hipEventRecord(ev0, s));
   }
   if (a.idx) {
-    auto k = hist_build_kernel<CAP, WM, NIB, NT, true>;
-    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
-    hipLaunchKernelGGL(k, dim3(blocks), dim3(NT), lds_bytes, s, a);
+    hipLaunchKernelGGL((hist_build_kernel<CAP, WM, NIB, NT, true>), dim3(blocks), dim3(NT), 0, s, a);
   } else {
-    auto k = hist_build_kernel<CAP, WM, NIB, NT, false>;
-    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
-    hipLaunchKernelGGL(k, dim3(blocks), dim3(NT), lds_bytes, s, a);
+    hipLaunchKernelGGL((hist_build_kernel<CAP, WM, NIB, NT, false>), dim3(blocks), dim3(NT), 0, s, a);
   }
   HIP_TRY(hipGetLastError());
   if (prof) {
@@ -742,7 +832,7 @@ int gbdt_hist_build(const void* bin_matrix, int64_t n_rows, int32_t n_features, 
   if (!hist_out) return GBDT_EINVAL;
   if (n_leaf_rows < 0) return GBDT_EINVAL;
   if (!leaf_row_idx && n_leaf_rows > n_rows) return GBDT_EINVAL;
-  if (n_rows >= ((int64_t)1 << 31) || n_leaf_rows >= ((int64_t)1 << 31)) return GBDT_EUNSUPPORTED;
+  if (n_rows >= ((int64_t)1 << 30) || n_leaf_rows >= ((int64_t)1 << 31)) return GBDT_EUNSUPPORTED;
   hipStream_t s = (hipStream_t)stream;
   if (n_leaf_rows == 0) {
     const int32_t n = n_features * n_bins;
@@ -755,6 +845,8 @@ int gbdt_hist_build(const void* bin_matrix, int64_t n_rows, int32_t n_features, 
   const BuildGeom g = make_geom(n_features, n_bins, n_leaf_rows, device_cu_count());
   const TilePlan& p = g.plan;
   if (plan_n_tiles(p) > 65535) return GBDT_EUNSUPPORTED;
+  // byte offsets inside a tile are formed in 32 bits
+  if (n_rows * (int64_t)p.wm >= ((int64_t)1 << 32)) return GBDT_EUNSUPPORTED;
   void* ws = nullptr;
   int rc = get_workspace(g.partial_words * 4, &ws);
   if (rc != GBDT_OK) return rc;
@@ -776,11 +868,11 @@ int gbdt_hist_build(const void* bin_matrix, int64_t n_rows, int32_t n_features, 
   const int blocks = p.n_main * g.chunks_main + g.chunks_rem;
 
   if (p.cap == 16) {
-    rc = launch_build<16, 64, true, 512>(a, blocks, g.lds_bytes, s);
+    rc = launch_build<16, 64, true, 512>(a, blocks, s);
   } else if (p.cap == 64) {
-    rc = launch_build<64, 64, false, 512>(a, blocks, g.lds_bytes, s);
+    rc = launch_build<64, 64, false, 512>(a, blocks, s);
   } else {
-    rc = launch_build<256, 32, false, 1024>(a, blocks, g.lds_bytes, s);
+    rc = launch_build<256, 32, false, 1024>(a, blocks, s);
   }
   if (rc != GBDT_OK) return rc;
 

@@ -13,14 +13,19 @@
 // All tiles have the "main" width WM except possibly the last one, which is 16
 // or 32 bytes wide when few feature bytes remain (so that padding stays small).
 //
-// Inside a tile, byte i of a row sits in word j = i / 4 at position i % 4; with
-// 4-bit bins the low nibble of byte i is feature 2i, the high nibble 2i + 1, so
-// a word holds NP = 4 (or 8) features at positions p = 0..NP-1.
+// Inside a tile, a lane loads VEC consecutive bytes of a row: 8 bytes from a
+// 64-byte tile, 4 bytes from a 16- or 32-byte tile.  Byte i of the tile row is
+// byte i % VEC of lane-chunk j = i / VEC; with 4-bit bins the low nibble of a
+// byte is feature 2i, the high nibble 2i + 1.  A lane-chunk so holds NP = VEC
+// (or 2 * VEC) features at positions p = 0..NP-1.
 //
-// Local-memory histogram of one tile: three arrays (grad, hess, count), each
-// [bin][slot] with slot = j + LPR * p, LPR = W / 4 words per row.  With this
-// slot order the lanes of a wavefront, which at any step work on pairwise
-// different (j, p), fall into different banks (see hist_build_kernel).
+// Local-memory histogram of one tile: an array of 64-bit (hess:grad) sums and an
+// array of 32-bit counts, each [bin][stride] with the feature at slot
+// = j + LPR * p, LPR = W / VEC lane-chunks per row.  The stride is the number of
+// slots of the tile, except that all tiles of the 64-bin variant use stride 64 so
+// that (bin << 8) | (4 * slot) is a byte address a single byte-permute can form.
+// With this slot order the lanes the LDS serves together, which at any step work
+// on pairwise different (j, p), fall into different banks (see build_tile).
 #ifndef GBDT_TILE_PLAN_H_
 #define GBDT_TILE_PLAN_H_
 
@@ -64,6 +69,10 @@ GBDT_HD int32_t plan_n_tiles(const TilePlan& p) { return p.n_main + (p.wr ? 1 : 
 GBDT_HD int32_t plan_tile_width(const TilePlan& p, int32_t t) { return t < p.n_main ? p.wm : p.wr; }
 // features (= slots) held by a tile of width w
 GBDT_HD int32_t plan_slots(const TilePlan& p, int32_t w) { return p.nib ? 2 * w : w; }
+// bytes a lane loads from a row of a tile of width w
+GBDT_HD int32_t plan_vec(int32_t w) { return w == 64 ? 8 : 4; }
+// slots per bin row of the LDS / partial-block histogram of a tile of width w
+GBDT_HD int32_t plan_stride(const TilePlan& p, int32_t w) { return p.cap == 64 ? 64 : plan_slots(p, w); }
 
 struct FeatureSlot {
   int32_t tile;
@@ -77,12 +86,26 @@ GBDT_HD FeatureSlot plan_locate(const TilePlan& p, int32_t f) {
   if (t >= p.n_main) t = p.n_main;  // remainder tile
   int32_t w = plan_tile_width(p, t);
   int32_t i = fb - t * p.wm;  // byte inside the tile row
-  int32_t j = i >> 2;
-  int32_t pos = p.nib ? ((i & 3) * 2 + (f & 1)) : (i & 3);
+  int32_t vec = plan_vec(w);
+  int32_t j = i / vec;
+  int32_t bl = i - j * vec;  // byte inside the lane-chunk
+  int32_t pos = p.nib ? (bl * 2 + (f & 1)) : bl;
   FeatureSlot r;
   r.tile = t;
-  r.slot = j + (w / 4) * pos;
+  r.slot = j + (w / vec) * pos;
   return r;
+}
+
+// Inverse of plan_locate: the feature held by `slot` of tile t (may be >= n_features
+// for padding slots).
+GBDT_HD int32_t plan_feature_of(const TilePlan& p, int32_t t, int32_t slot) {
+  int32_t w = plan_tile_width(p, t);
+  int32_t vec = plan_vec(w);
+  int32_t lpr = w / vec;
+  int32_t pos = slot / lpr;
+  int32_t j = slot - pos * lpr;
+  if (p.nib) return 2 * (t * p.wm + j * vec + (pos >> 1)) + (pos & 1);
+  return t * p.wm + j * vec + pos;
 }
 
 #endif  // GBDT_TILE_PLAN_H_

@@ -109,7 +109,8 @@ def test_row_chunks_cover_the_leaf_exactly(n_features, n_bins, n_leaf):
         assert chunks >= 1 and rpc >= 1
         assert chunks * rpc >= n_leaf            # every row belongs to a chunk
         assert (chunks - 1) * rpc < n_leaf       # no chunk starts past the end
-        words += tiles * chunks * 3 * g["cap"] * w * per_byte
+        stride = 64 if g["cap"] == 64 else w * per_byte
+        words += tiles * chunks * 3 * g["cap"] * stride
     assert words == g["partial_words"]
     assert B.gbdt_workspace_bytes(n_leaf, n_features, n_bins) >= 4 * g["partial_words"]
     assert (g["n_main"] * g["chunks_main"] + g["chunks_rem"]) < 2 ** 31
