@@ -181,6 +181,10 @@ int gbdt_profile_collect(double* build_kernel_ms_total, int64_t* n_launches);
  */
 int gbdt_debug_geometry(int32_t n_features, int32_t n_bins, int64_t n_leaf_rows, int32_t n_cus,
                         int64_t* out, int32_t n_out);
+/* Resident workgroups per compute unit of the build kernel variant that serves
+ * n_bins (indexed != 0: the variant that gathers through leaf_row_idx), as the HIP
+ * runtime reports it on the current device; 0 if the query is not possible. */
+int gbdt_debug_occupancy(int32_t n_bins, int32_t indexed);
 int gbdt_debug_locate(int32_t n_features, int32_t n_bins, int32_t feature, int32_t* tile_out,
                       int32_t* slot_out);
 

@@ -20,7 +20,7 @@ EXPORTS = [
     "gbdt_bins_packed_bytes", "gbdt_bins_pack", "gbdt_hist_build", "gbdt_hist_subtract",
     "gbdt_best_split", "gbdt_workspace_bytes", "gbdt_set_workspace", "gbdt_strerror",
     "gbdt_last_hip_error", "gbdt_debug_geometry", "gbdt_debug_locate",
-    "gbdt_profile_enable", "gbdt_profile_collect",
+    "gbdt_profile_enable", "gbdt_profile_collect", "gbdt_debug_occupancy",
 ]
 
 # numpy views of the two C structs
@@ -198,6 +198,13 @@ def gbdt_debug_geometry(n_features: int, n_bins: int, n_leaf_rows: int, n_cus: i
     _check(load().gbdt_debug_geometry(n_features, n_bins, n_leaf_rows, n_cus, out, 16),
            "gbdt_debug_geometry")
     return {k: int(out[i]) for i, k in enumerate(GEOMETRY_FIELDS)}
+
+
+def gbdt_debug_occupancy(n_bins: int, indexed: bool) -> int:
+    lib = load()
+    lib.gbdt_debug_occupancy.restype = ctypes.c_int
+    lib.gbdt_debug_occupancy.argtypes = [ctypes.c_int32, ctypes.c_int32]
+    return int(lib.gbdt_debug_occupancy(n_bins, 1 if indexed else 0))
 
 
 def gbdt_debug_locate(n_features: int, n_bins: int, feature: int):

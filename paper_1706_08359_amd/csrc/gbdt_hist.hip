@@ -14,6 +14,7 @@
 
 #include <stdint.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <mutex>
@@ -86,11 +87,11 @@ __device__ __forceinline__ int epoch_scale_exp(float sum_abs) {
   int k = 30 - ilogbf(m);                  // 2^k * m in [2^30, 2^31)
   if (k > 126) k = 126;
   if (k < -126) k = -126;
-  if (ldexpf(m, k) > 2147479552.0f) k -= 1;  // keep 2^k * m <= 2^31 - 4096
+  if (ldexpf(m, k) > 2147475456.0f) k -= 1;  // keep 2^k * m <= 2^31 - 8192
   return k;
 }
 
-constexpr int kEpochRows = 4096;  // rows a workgroup accumulates between two drains
+constexpr int kEpochRows = 8192;  // rows a workgroup accumulates between two drains
 
 // Histogram of rows [begin, end) of the leaf for one feature tile, accumulated in
 // this workgroup's local memory and then written out as one partial block.
@@ -115,14 +116,14 @@ constexpr int kEpochRows = 4096;  // rows a workgroup accumulates between two dr
 // (App. B.3).  gfx950 has a native LDS float add, but it retires about 0.33
 // lanes/clock/CU against about 16 for a 32-bit and 10 for a 64-bit integer add, so
 // floats are accumulated as integers instead: rows are taken in epochs of at most
-// 4096; per epoch the workgroup sums |grad| and |hess| of the epoch's rows, picks
+// 8192; per epoch the workgroup sums |grad| and |hess| of the epoch's rows, picks
 // the largest power-of-two scales that cannot overflow 32 bits, and every (row,
 // feature) then costs ONE 64-bit integer atomic that carries the quantised
 // gradient (low half) and hessian (high half), plus one 32-bit atomic for the
 // count.  After each epoch the integer sums are drained into accumulators held in
 // registers (each thread owns PAIRS/NT bins) and the LDS is cleared.
 // Error: each value is rounded once, by at most half a quantum; the quantum is at
-// most sum|g|_epoch / 2^30, so a bin is off by at most 4096 / 2^31 = 1.9e-6 of the
+// most sum|g|_epoch / 2^30, so a bin is off by at most 8192 / 2^31 = 3.8e-6 of the
 // leaf's sum |g| (likewise for h) -- and integer addition is order-independent, so
 // the result is bit-reproducible.
 //
@@ -366,7 +367,8 @@ __device__ __host__ constexpr int block_words(int w) {
 // the same chunk, so the chunk's row ids / gradients / hessians are fetched from
 // HBM once and served to the other tiles from cache.
 template <int CAP, int WM, bool NIB, int NT, bool INDEXED>
-__global__ void __launch_bounds__(NT) hist_build_kernel(BuildArgs a) {
+__global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT == 512 ? 6 : 4, NT == 512 ? 6 : 4)))
+hist_build_kernel(BuildArgs a) {
   // one histogram of the main tile width (12 bytes per cell) + the reduction scratch
   constexpr int kLdsBytes = 4 * block_words<CAP, NIB>(WM) + 2 * (NT / 64) * 4;
   __shared__ __align__(16) unsigned long long lds[(kLdsBytes + 7) / 8];
@@ -411,23 +413,30 @@ struct MergeArgs {
   int32_t chunks_rem;
 };
 
+constexpr int kMergeCells = 64;   // histogram cells per workgroup
+constexpr int kMergeLanes = 4;    // threads that share the chunks of one cell
+
 // The "final reduction program" of Sec. 4: sums the partial histograms of the
-// workgroups that shared a feature tile.  One thread per (tile, bin, slot), slot
-// fastest, so the reads of every chunk's block are coalesced; gradient / hessian
-// partials are summed in fp64 in chunk order (deterministic), counts as integers.
-// grid.y = tile.
-__global__ void __launch_bounds__(256) hist_merge_kernel(MergeArgs a) {
+// workgroups that shared a feature tile.  A workgroup takes 64 consecutive (bin,
+// slot) cells of one tile (slot fastest, so every read of a partial block is
+// coalesced); 4 threads per cell each sum every 4th chunk in fp64, in chunk order,
+// and the 4 sub-sums are added in a fixed order: the result does not depend on
+// scheduling.  Counts are summed as integers.  grid.y = tile.
+__global__ void __launch_bounds__(kMergeCells * kMergeLanes) hist_merge_kernel(MergeArgs a) {
+  __shared__ double s_g[kMergeLanes][kMergeCells];
+  __shared__ double s_h[kMergeLanes][kMergeCells];
+  __shared__ uint32_t s_n[kMergeLanes][kMergeCells];
   const int32_t t = blockIdx.y;
   const int32_t w = plan_tile_width(a.plan, t);
   const int32_t slots = plan_slots(a.plan, w);
   const int32_t stride = plan_stride(a.plan, w);
   const int32_t cap = a.plan.cap;
-  const int32_t e = blockIdx.x * blockDim.x + threadIdx.x;
-  if (e >= a.n_bins * slots) return;
-  const int32_t bin = e / slots;
-  const int32_t slot = e - bin * slots;
-  const int32_t f = plan_feature_of(a.plan, t, slot);
-  if (f >= a.n_features) return;  // padding slot
+  const int cell = threadIdx.x % kMergeCells;
+  const int part = threadIdx.x / kMergeCells;
+  const int32_t e = blockIdx.x * kMergeCells + cell;
+  const bool live = e < a.n_bins * slots;
+  const int32_t bin = live ? e / slots : 0;
+  const int32_t slot = live ? e - bin * slots : 0;
   const size_t hw = (size_t)cap * stride;
   const size_t main_block = (size_t)3 * cap * plan_stride(a.plan, a.plan.wm);
   const uint32_t* p;
@@ -439,20 +448,37 @@ __global__ void __launch_bounds__(256) hist_merge_kernel(MergeArgs a) {
     p = a.partials + (size_t)a.plan.n_main * a.chunks_main * main_block;
     chunks = a.chunks_rem;
   }
-  p += (size_t)bin * stride + slot;
+  p += (size_t)bin * stride + slot + (size_t)part * 3 * hw;
   double g = 0.0, h = 0.0;
   uint32_t n = 0;
-  for (int32_t c = 0; c < chunks; ++c) {
-    g += (double)__uint_as_float(p[0]);
-    h += (double)__uint_as_float(p[hw]);
-    n += p[2 * hw];
-    p += 3 * hw;
+  if (live) {
+    for (int32_t c = part; c < chunks; c += kMergeLanes) {
+      g += (double)__uint_as_float(p[0]);
+      h += (double)__uint_as_float(p[hw]);
+      n += p[2 * hw];
+      p += (size_t)kMergeLanes * 3 * hw;
+    }
   }
-  gbdt_bin_t r;
-  r.grad = (float)g;
-  r.hess = (float)h;
-  r.count = n;
-  a.out[(size_t)f * a.n_bins + bin] = r;
+  s_g[part][cell] = g;
+  s_h[part][cell] = h;
+  s_n[part][cell] = n;
+  __syncthreads();
+  if (part == 0 && live) {
+    const int32_t f = plan_feature_of(a.plan, t, slot);
+    if (f < a.n_features) {  // else: padding slot
+#pragma unroll
+      for (int q = 1; q < kMergeLanes; ++q) {
+        g += s_g[q][cell];
+        h += s_h[q][cell];
+        n += s_n[q][cell];
+      }
+      gbdt_bin_t r;
+      r.grad = (float)g;
+      r.hess = (float)h;
+      r.count = n;
+      a.out[(size_t)f * a.n_bins + bin] = r;
+    }
+  }
 }
 
 // --------------------------------------------------------------- subtract kernel
@@ -490,112 +516,178 @@ struct SplitCand {
   double gain;
   double gl, hl, gr, hr;
   uint32_t nl, nr;
-  int32_t bin;  // -1: feature has no admissible threshold
-  int32_t pad;
+  int32_t feature;  // -1: no admissible threshold among this workgroup's features
+  int32_t bin;
 };
 
-// Gain scan of Sec. 3.3 for one feature per thread: totals over the feature's own
-// bins, then a running left prefix over thresholds t = 0..n_bins-2, all in fp64,
-// bins ascending.  The feature's best threshold (first one on equal gain) goes to
-// cand[f].
-__global__ void __launch_bounds__(64)
-split_scan_kernel(const gbdt_bin_t* __restrict__ hist, int32_t n_features, int32_t n_bins,
-                  double lambda, double min_child_hess, SplitCand* __restrict__ cand) {
-  const int32_t f = blockIdx.x * blockDim.x + threadIdx.x;
-  if (f >= n_features) return;
-  const gbdt_bin_t* o = hist + (size_t)f * n_bins;
-  double G = 0.0, H = 0.0;
-  uint32_t N = 0;
-  for (int32_t b = 0; b < n_bins; ++b) {
-    G = G + (double)o[b].grad;
-    H = H + (double)o[b].hess;
-    N = N + o[b].count;
+constexpr int kSplitThreads = 256;
+constexpr int kSplitLdsBudget = 48 * 1024;
+
+// LDS bytes one feature needs in split_gain_kernel: raw bins (12 B) + fp64 prefix of
+// grad and hess (16 B) + prefix of count (4 B) per bin, + the feature's parent term.
+__host__ __device__ inline int split_feature_bytes(int n_bins) { return 32 * n_bins + 8; }
+
+// Gain scan of Sec. 3.3.  A workgroup takes a group of consecutive features.
+//  1. Their histogram rows are copied into local memory with coalesced reads.
+//  2. One lane per feature runs the left-to-right prefix sums of grad, hess and count
+//     in fp64, bins ascending (this fixes the rounding order; it is the cheap part).
+//  3. All lanes then evaluate the gain of every (feature, threshold) pair from those
+//     prefixes -- the divisions, the expensive part -- and keep the best pair under
+//     the order "larger gain, then smaller feature, then smaller bin".
+// Feature totals are the prefix at the last bin, right = total - left, a threshold is
+// admissible when both sides hold >= 1 sample and >= min_child_hess of hessian.
+__global__ void __launch_bounds__(kSplitThreads)
+split_gain_kernel(const gbdt_bin_t* __restrict__ hist, int32_t n_features, int32_t n_bins,
+                  int32_t group, double lambda, double min_child_hess,
+                  SplitCand* __restrict__ cand) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  __shared__ double s_gain[kSplitThreads];
+  __shared__ int32_t s_pair[kSplitThreads];
+  const int tid = threadIdx.x;
+  const int32_t f0 = blockIdx.x * group;
+  const int32_t nf = (n_features - f0 < group) ? (n_features - f0) : group;
+  const int B = n_bins;
+  // layout: pg[group][B] | ph[group][B] | parent[group] (doubles) | pn[group][B] | raw[group][3B] (words)
+  double* pg = reinterpret_cast<double*>(smem);
+  double* ph = pg + (size_t)group * B;
+  double* parent = ph + (size_t)group * B;
+  uint32_t* pn = reinterpret_cast<uint32_t*>(parent + group);
+  uint32_t* raw = pn + (size_t)group * B;
+
+  const uint32_t* src = reinterpret_cast<const uint32_t*>(hist + (size_t)f0 * B);
+  const int n_words = nf * B * 3;
+  for (int e = tid; e < n_words; e += kSplitThreads) raw[e] = src[e];
+  __syncthreads();
+
+  if (tid < nf) {
+    const uint32_t* r = raw + (size_t)tid * B * 3;
+    double G = 0.0, H = 0.0;
+    uint32_t N = 0;
+    for (int b = 0; b < B; ++b) {
+      G = G + (double)__uint_as_float(r[3 * b]);
+      H = H + (double)__uint_as_float(r[3 * b + 1]);
+      N = N + r[3 * b + 2];
+      pg[tid * B + b] = G;
+      ph[tid * B + b] = H;
+      pn[tid * B + b] = N;
+    }
+    parent[tid] = __ddiv_rn(__dmul_rn(G, G), H + lambda);
   }
-  const double parent_term = __ddiv_rn(__dmul_rn(G, G), H + lambda);
-  SplitCand best;
-  best.gain = 0.0;
-  best.bin = -1;
-  best.gl = best.hl = best.gr = best.hr = 0.0;
-  best.nl = best.nr = 0;
-  best.pad = 0;
-  double GL = 0.0, HL = 0.0;
-  uint32_t NL = 0;
-  for (int32_t t = 0; t + 1 < n_bins; ++t) {
-    GL = GL + (double)o[t].grad;
-    HL = HL + (double)o[t].hess;
-    NL = NL + o[t].count;
-    const double GR = G - GL, HR = H - HL;
-    const uint32_t NR = N - NL;
+  __syncthreads();
+
+  double best_gain = 0.0;
+  int32_t best_pair = -1;  // fl * (B - 1) + t, ascending in (feature, bin)
+  const int n_pairs = nf * (B - 1);
+  for (int e = tid; e < n_pairs; e += kSplitThreads) {
+    const int fl = e / (B - 1);
+    const int t = e - fl * (B - 1);
+    const double GL = pg[fl * B + t], HL = ph[fl * B + t];
+    const uint32_t NL = pn[fl * B + t];
+    const double GR = pg[fl * B + B - 1] - GL, HR = ph[fl * B + B - 1] - HL;
+    const uint32_t NR = pn[fl * B + B - 1] - NL;
     const bool ok = NL >= 1u && NR >= 1u && HL >= min_child_hess && HR >= min_child_hess;
     if (ok) {
       const double lt = __ddiv_rn(__dmul_rn(GL, GL), HL + lambda);
       const double rt = __ddiv_rn(__dmul_rn(GR, GR), HR + lambda);
-      const double gain = __dsub_rn(__dadd_rn(lt, rt), parent_term);
-      if (best.bin < 0 || gain > best.gain) {
-        best.gain = gain;
-        best.bin = t;
-        best.gl = GL;
-        best.hl = HL;
-        best.gr = GR;
-        best.hr = HR;
-        best.nl = NL;
-        best.nr = NR;
+      const double gain = __dsub_rn(__dadd_rn(lt, rt), parent[fl]);
+      if (best_pair < 0 || gain > best_gain) {  // e ascends: ties keep the earlier pair
+        best_gain = gain;
+        best_pair = e;
       }
     }
   }
-  cand[f] = best;
+  s_gain[tid] = best_gain;
+  s_pair[tid] = best_pair;
+  __syncthreads();
+  for (int s = kSplitThreads / 2; s > 0; s >>= 1) {
+    if (tid < s) {
+      const double g2 = s_gain[tid + s];
+      const int32_t p2 = s_pair[tid + s];
+      const double g1 = s_gain[tid];
+      const int32_t p1 = s_pair[tid];
+      const bool take = p2 >= 0 && (p1 < 0 || g2 > g1 || (g2 == g1 && p2 < p1));
+      if (take) {
+        s_gain[tid] = g2;
+        s_pair[tid] = p2;
+      }
+    }
+    __syncthreads();
+  }
+  if (tid == 0) {
+    SplitCand c;
+    const int32_t e = s_pair[0];
+    if (e < 0) {
+      c.gain = 0.0;
+      c.gl = c.hl = c.gr = c.hr = 0.0;
+      c.nl = c.nr = 0;
+      c.feature = -1;
+      c.bin = -1;
+    } else {
+      const int fl = e / (B - 1);
+      const int t = e - fl * (B - 1);
+      c.gain = s_gain[0];
+      c.gl = pg[fl * B + t];
+      c.hl = ph[fl * B + t];
+      c.nl = pn[fl * B + t];
+      c.gr = pg[fl * B + B - 1] - c.gl;
+      c.hr = ph[fl * B + B - 1] - c.hl;
+      c.nr = pn[fl * B + B - 1] - c.nl;
+      c.feature = f0 + fl;
+      c.bin = t;
+    }
+    cand[blockIdx.x] = c;
+  }
 }
 
-// Arg-max over the per-feature candidates with the tie-break "larger gain, then
-// smaller feature" (the per-feature scan already kept the smaller bin).  One
-// workgroup; each thread folds a strided subset in ascending feature order, then
-// a tree reduction in local memory compares (gain, feature).
+// Arg-max over the per-workgroup candidates (workgroups hold ascending feature
+// groups, so "smaller candidate index" is "smaller feature").  One workgroup; each
+// thread folds a strided subset in ascending order, then a tree reduction.
 __global__ void __launch_bounds__(256)
-split_argmax_kernel(const SplitCand* __restrict__ cand, int32_t n_features,
+split_argmax_kernel(const SplitCand* __restrict__ cand, int32_t n_cand,
                     gbdt_split_t* __restrict__ out) {
   __shared__ double s_gain[256];
-  __shared__ int32_t s_feat[256];
+  __shared__ int32_t s_idx[256];
   const int tid = threadIdx.x;
   double bg = 0.0;
-  int32_t bf = -1;
-  for (int32_t f = tid; f < n_features; f += 256) {
-    if (cand[f].bin >= 0) {
-      const double g = cand[f].gain;
-      if (bf < 0 || g > bg) {  // f ascends, so ties keep the smaller feature
+  int32_t bi = -1;
+  for (int32_t i = tid; i < n_cand; i += 256) {
+    if (cand[i].feature >= 0) {
+      const double g = cand[i].gain;
+      if (bi < 0 || g > bg) {  // i ascends, so ties keep the smaller feature
         bg = g;
-        bf = f;
+        bi = i;
       }
     }
   }
   s_gain[tid] = bg;
-  s_feat[tid] = bf;
+  s_idx[tid] = bi;
   __syncthreads();
   for (int s = 128; s > 0; s >>= 1) {
     if (tid < s) {
       const double g2 = s_gain[tid + s];
-      const int32_t f2 = s_feat[tid + s];
+      const int32_t i2 = s_idx[tid + s];
       const double g1 = s_gain[tid];
-      const int32_t f1 = s_feat[tid];
-      const bool take = f2 >= 0 && (f1 < 0 || g2 > g1 || (g2 == g1 && f2 < f1));
+      const int32_t i1 = s_idx[tid];
+      const bool take = i2 >= 0 && (i1 < 0 || g2 > g1 || (g2 == g1 && i2 < i1));
       if (take) {
         s_gain[tid] = g2;
-        s_feat[tid] = f2;
+        s_idx[tid] = i2;
       }
     }
     __syncthreads();
   }
   if (tid == 0) {
     gbdt_split_t r;
-    const int32_t f = s_feat[0];
-    if (f < 0) {
+    const int32_t i = s_idx[0];
+    if (i < 0) {
       r.feature = -1;
       r.bin = -1;
       r.gain = 0.0f;
       r.left_grad = r.left_hess = r.right_grad = r.right_hess = 0.0f;
       r.left_count = r.right_count = 0;
     } else {
-      const SplitCand c = cand[f];
-      r.feature = f;
+      const SplitCand c = cand[i];
+      r.feature = c.feature;
       r.bin = c.bin;
       r.gain = (float)c.gain;
       r.left_grad = (float)c.gl;
@@ -692,6 +784,7 @@ int device_cu_count() {
 
 constexpr size_t kLdsPerCu = 160 * 1024;
 constexpr int kMinRowsPerChunk = 512;
+constexpr int kOversubscribe = 3;  // rounds of workgroups per resident slot
 
 struct BuildGeom {
   TilePlan plan;
@@ -705,19 +798,33 @@ struct BuildGeom {
 int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 
 // Chooses how many row chunks each tile is cut into so that the grid about fills
-// the machine at the occupancy the LDS footprint allows.
-BuildGeom make_geom(int32_t n_features, int32_t n_bins, int64_t n_leaf, int cus) {
+// the machine exactly once: one workgroup per resident slot, so that no second,
+// partly empty round of workgroups is needed.  wg_per_cu: resident workgroups per CU
+// of the kernel variant as reported by the runtime (<= 0: estimate from the LDS
+// footprint alone).
+BuildGeom make_geom(int32_t n_features, int32_t n_bins, int64_t n_leaf, int cus,
+                    int wg_per_cu_hint) {
   BuildGeom g;
   g.plan = make_tile_plan(n_features, n_bins);
   const TilePlan& p = g.plan;
   g.nt = p.cap == 256 ? 1024 : 512;
   const size_t main_block = (size_t)3 * p.cap * plan_stride(p, p.wm);
   g.lds_bytes = main_block * 4 + 2 * (g.nt / 64) * sizeof(float);
-  int wg_per_cu = (int)(kLdsPerCu / g.lds_bytes);
-  const int by_threads = 2048 / g.nt;
-  if (wg_per_cu > by_threads) wg_per_cu = by_threads;
+  int wg_per_cu = wg_per_cu_hint;
+  if (wg_per_cu <= 0) {
+    wg_per_cu = (int)(kLdsPerCu / g.lds_bytes);
+    const int by_threads = 2048 / g.nt;
+    if (wg_per_cu > by_threads) wg_per_cu = by_threads;
+  }
   if (wg_per_cu < 1) wg_per_cu = 1;
-  const int64_t resident = (int64_t)cus * wg_per_cu;
+  // Workgroups of a CU that reach their barriers / epoch boundaries together leave
+  // its LDS idle; several rounds of smaller workgroups keep them out of phase.
+  int oversub = kOversubscribe;
+  if (const char* e = getenv("GBDT_HIST_OVERSUB")) {  // tuning experiments only
+    const int v = atoi(e);
+    if (v > 0) oversub = v;
+  }
+  const int64_t resident = (int64_t)cus * wg_per_cu * oversub;
   // remainder tile counted by its share of a main tile's work
   const double tiles_equiv = p.n_main + (p.wr ? (double)p.wr / p.wm : 0.0);
   int64_t chunks = (int64_t)((double)resident / (tiles_equiv > 0 ? tiles_equiv : 1.0));
@@ -742,6 +849,49 @@ BuildGeom make_geom(int32_t n_features, int32_t n_bins, int64_t n_leaf, int cus)
   g.partial_words = (size_t)p.n_main * g.chunks_main * main_block +
                     (size_t)g.chunks_rem * 3 * p.cap * (p.wr ? plan_stride(p, p.wr) : 0);
   return g;
+}
+
+template <int CAP, int WM, bool NIB, int NT, bool INDEXED>
+int query_occupancy() {
+  int n = 0;
+  hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(
+      &n, reinterpret_cast<const void*>(hist_build_kernel<CAP, WM, NIB, NT, INDEXED>), NT, 0);
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    return 0;
+  }
+  return n;
+}
+
+// Resident workgroups per CU of the build kernel variant for this bin capacity
+// (registers, LDS and wave slots taken into account by the runtime); cached.
+int build_wg_per_cu(int cap, bool indexed) {
+  // GBDT_HIST_WG_PER_CU overrides the runtime's answer (tuning experiments only)
+  if (const char* e = getenv("GBDT_HIST_WG_PER_CU")) {
+    const int v = atoi(e);
+    if (v > 0) return v;
+  }
+  static int cache[3][2] = {{-1, -1}, {-1, -1}, {-1, -1}};
+  const int ci = cap == 16 ? 0 : (cap == 64 ? 1 : 2);
+  int& c = cache[ci][indexed ? 1 : 0];
+  if (c < 0) {
+    if (cap == 16) c = indexed ? query_occupancy<16, 64, true, 512, true>() : query_occupancy<16, 64, true, 512, false>();
+    else if (cap == 64) c = indexed ? query_occupancy<64, 64, false, 512, true>() : query_occupancy<64, 64, false, 512, false>();
+    else c = indexed ? query_occupancy<256, 32, false, 1024, true>() : query_occupancy<256, 32, false, 1024, false>();
+  }
+  return c;
+}
+
+// Features per workgroup of split_gain_kernel: as many as fit its LDS budget, at most
+// 32, but fewer when that leaves the machine short of workgroups.
+void split_grouping(int32_t n_features, int32_t n_bins, int* group_out, int* n_groups_out) {
+  int group = kSplitLdsBudget / split_feature_bytes(n_bins);
+  if (group > 32) group = 32;
+  const int spread = (n_features + 255) / 256;  // features per group that gives ~256 groups
+  if (spread < group) group = spread;
+  if (group < 1) group = 1;
+  *group_out = group;
+  *n_groups_out = (n_features + group - 1) / group;
 }
 
 bool valid_shape(int64_t n_rows, int32_t n_features, int32_t n_bins) {
@@ -809,9 +959,13 @@ int gbdt_bins_pack(const uint8_t* bins_rowmajor, int64_t n_rows, int32_t n_featu
 
 size_t gbdt_workspace_bytes(int64_t n_rows, int32_t n_features, int32_t n_bins) {
   if (!valid_shape(n_rows, n_features, n_bins)) return 0;
-  const BuildGeom g = make_geom(n_features, n_bins, n_rows, device_cu_count());
-  size_t b = g.partial_words * 4;
-  const size_t cand = (size_t)n_features * sizeof(SplitCand);
+  const int cap = make_tile_plan(n_features, n_bins).cap;
+  const BuildGeom g0 = make_geom(n_features, n_bins, n_rows, device_cu_count(), build_wg_per_cu(cap, false));
+  const BuildGeom g1 = make_geom(n_features, n_bins, n_rows, device_cu_count(), build_wg_per_cu(cap, true));
+  size_t b = (g0.partial_words > g1.partial_words ? g0.partial_words : g1.partial_words) * 4;
+  int sg = 0, sn = 0;
+  split_grouping(n_features, n_bins, &sg, &sn);
+  const size_t cand = (size_t)sn * sizeof(SplitCand);
   if (cand > b) b = cand;
   return (b + 255) / 256 * 256;
 }
@@ -842,7 +996,9 @@ int gbdt_hist_build(const void* bin_matrix, int64_t n_rows, int32_t n_features, 
   }
   if (!bin_matrix || !grad || !hess) return GBDT_EINVAL;
 
-  const BuildGeom g = make_geom(n_features, n_bins, n_leaf_rows, device_cu_count());
+  const BuildGeom g =
+      make_geom(n_features, n_bins, n_leaf_rows, device_cu_count(),
+                build_wg_per_cu(make_tile_plan(n_features, n_bins).cap, leaf_row_idx != nullptr));
   const TilePlan& p = g.plan;
   if (plan_n_tiles(p) > 65535) return GBDT_EUNSUPPORTED;
   // byte offsets inside a tile are formed in 32 bits
@@ -885,8 +1041,9 @@ int gbdt_hist_build(const void* bin_matrix, int64_t n_rows, int32_t n_features, 
   m.chunks_main = g.chunks_main;
   m.chunks_rem = g.chunks_rem;
   const int max_slots = plan_slots(p, p.wm);
-  const int mx = (n_bins * max_slots + 255) / 256;
-  hipLaunchKernelGGL(hist_merge_kernel, dim3(mx, plan_n_tiles(p)), dim3(256), 0, s, m);
+  const int mx = (n_bins * max_slots + kMergeCells - 1) / kMergeCells;
+  hipLaunchKernelGGL(hist_merge_kernel, dim3(mx, plan_n_tiles(p)), dim3(kMergeCells * kMergeLanes),
+                     0, s, m);
   HIP_TRY(hipGetLastError());
   return GBDT_OK;
 }
@@ -907,15 +1064,19 @@ int gbdt_best_split(const gbdt_bin_t* hist, float lambda, float min_child_hess,
   if (!hist || !split_out) return GBDT_EINVAL;
   if (n_features <= 0 || n_bins < 2 || n_bins > 256) return GBDT_EINVAL;
   if (!(lambda >= 0.0f)) return GBDT_EINVAL;
+  int group = 0, n_groups = 0;
+  split_grouping(n_features, n_bins, &group, &n_groups);
   void* ws = nullptr;
-  int rc = get_workspace((size_t)n_features * sizeof(SplitCand), &ws);
+  int rc = get_workspace((size_t)n_groups * sizeof(SplitCand), &ws);
   if (rc != GBDT_OK) return rc;
   hipStream_t s = (hipStream_t)stream;
-  hipLaunchKernelGGL(split_scan_kernel, dim3((n_features + 63) / 64), dim3(64), 0, s, hist,
-                     n_features, n_bins, (double)lambda, (double)min_child_hess, (SplitCand*)ws);
+  const size_t lds = (size_t)group * split_feature_bytes(n_bins);
+  hipLaunchKernelGGL(split_gain_kernel, dim3(n_groups), dim3(kSplitThreads), lds, s, hist,
+                     n_features, n_bins, group, (double)lambda, (double)min_child_hess,
+                     (SplitCand*)ws);
   HIP_TRY(hipGetLastError());
   hipLaunchKernelGGL(split_argmax_kernel, dim3(1), dim3(256), 0, s, (const SplitCand*)ws,
-                     n_features, split_out);
+                     n_groups, split_out);
   HIP_TRY(hipGetLastError());
   return GBDT_OK;
 }
@@ -924,7 +1085,7 @@ int gbdt_debug_geometry(int32_t n_features, int32_t n_bins, int64_t n_leaf_rows,
                         int64_t* out, int32_t n_out) {
   if (!out || n_out < 16 || n_features <= 0 || n_bins < 2 || n_bins > 256 || n_leaf_rows < 0)
     return GBDT_EINVAL;
-  const BuildGeom g = make_geom(n_features, n_bins, n_leaf_rows, n_cus > 0 ? n_cus : 256);
+  const BuildGeom g = make_geom(n_features, n_bins, n_leaf_rows, n_cus > 0 ? n_cus : 256, 0);
   const TilePlan& p = g.plan;
   const int64_t v[16] = {p.cap,         p.nib,          p.wm,          p.n_main,
                          p.wr,          p.row_bytes,    p.feat_bytes,  g.nt,
@@ -932,6 +1093,11 @@ int gbdt_debug_geometry(int32_t n_features, int32_t n_bins, int64_t n_leaf_rows,
                          g.rpc_rem,     (int64_t)g.partial_words, 0, 0};
   for (int i = 0; i < 16; ++i) out[i] = v[i];
   return GBDT_OK;
+}
+
+int gbdt_debug_occupancy(int32_t n_bins, int32_t indexed) {
+  if (n_bins < 2 || n_bins > 256) return GBDT_EINVAL;
+  return build_wg_per_cu(n_bins <= 16 ? 16 : (n_bins <= 64 ? 64 : 256), indexed != 0);
 }
 
 int gbdt_debug_locate(int32_t n_features, int32_t n_bins, int32_t feature, int32_t* tile_out,
