@@ -36,7 +36,7 @@ extern "C" {
 typedef enum {
   GBDT_OK = 0,
   GBDT_EINVAL = -1,       /* NULL required pointer, size out of range, lambda < 0 */
-  GBDT_EUNSUPPORTED = -2, /* valid request the library cannot serve (e.g. n_rows >= 2^31) */
+  GBDT_EUNSUPPORTED = -2, /* valid request the library cannot serve (e.g. n_rows >= 2^30) */
   GBDT_EHIP = -3,         /* a HIP runtime call or kernel launch failed */
   GBDT_ENOMEM = -4        /* workspace allocation failed or caller workspace too small */
 } gbdt_status;
@@ -101,10 +101,21 @@ int gbdt_bins_pack(const uint8_t* bins_rowmajor, int64_t n_rows, int32_t n_featu
  *                  in Alg. 1), not by position in the leaf
  *   hist_out       DEVICE gbdt_bin_t [n_features][n_bins], fully overwritten;
  *                  all zero when n_leaf_rows == 0
- * Sums are accumulated in fp32 in local memory per workgroup and combined in
- * fp64 before rounding to fp32; counts are exact.  The order of fp32 additions
- * inside a workgroup is not fixed, so gradient / hessian sums may differ in
- * the last bits between runs.
+ * Arithmetic: a workgroup takes its rows in epochs of at most 8192.  Per epoch it
+ * sums |grad| and |hess| over the epoch's rows, derives the largest power-of-two
+ * scales for which no 32-bit integer bin sum can overflow, rounds every gradient
+ * and hessian once to that grid and accumulates integers (App. A.6 discusses the
+ * precision of this accumulation; gfx950's local-memory float add is ~35x slower
+ * than its integer add).  Epoch sums are rescaled to fp32, partial histograms are
+ * combined in fp64 in a fixed order and rounded to fp32.  Consequences:
+ *   - counts are exact;
+ *   - every gradient (hessian) bin sum is within 8192 / 2^31 = 3.8e-6 of the sum
+ *     of |grad| (|hess|) over the leaf, plus fp32 rounding of the result, for any
+ *     input values and any bin distribution;
+ *   - values that are multiples of a power of two well above the quantum (e.g.
+ *     +-0.5, 0.25) are accumulated exactly;
+ *   - the result is bit-reproducible: it does not depend on scheduling.
+ * grad / hess must be finite.
  */
 int gbdt_hist_build(const void* bin_matrix, int64_t n_rows, int32_t n_features, int32_t n_bins,
                     const int32_t* leaf_row_idx, int64_t n_leaf_rows, const float* grad,
