@@ -79,86 +79,135 @@ struct BuildArgs {
   int64_t rows_per_chunk_rem;
 };
 
+// A histogram cell is ONE 64-bit integer that carries, from the low bits up, the
+// count (10 bits), the quantised gradient sum (27 bits, signed) and the quantised
+// hessian sum (27 bits, signed).  A workgroup drains its cells after every epoch
+// of kEpochRows rows, so a cell receives at most 512 additions between drains.
+constexpr int kEpochRows = 512;
+constexpr int kCountBits = 10;
+constexpr int kSumBits = 27;
+static_assert(kEpochRows < (1 << kCountBits), "an epoch's count must fit its field");
+static_assert(kCountBits + 2 * kSumBits == 64, "the three fields fill the cell");
+
 // Power-of-two scale 2^k for quantising the values of one epoch to integers: the
-// largest k with 2^k * (sum of |v| over the epoch) + (rounding slack) < 2^31, so
-// that no bin's integer sum can leave 32 bits whatever the bin values are.
-__device__ __forceinline__ int epoch_scale_exp(float sum_abs) {
-  if (!(sum_abs > 0.0f)) return 0;
-  const float m = sum_abs * 1.001953125f;  // covers the rounding of the fp32 sum itself
-  int k = 30 - ilogbf(m);                  // 2^k * m in [2^30, 2^31)
+// largest k with 2^k * m + kEpochRows / 2 (rounding slack) < 2^26, so that no cell's
+// signed 27-bit field can overflow whatever the bins are.  m_bits: the bit pattern of
+// m = 1.002 * (fp32 sum of |v| over the epoch) (the factor covers the rounding of the
+// sum itself).  Integer arithmetic only: on a wave-uniform value it runs on the
+// scalar unit.  A zero (or denormal) sum gives k = 0; k is kept in [-126, 126] so
+// that 2^k and 2^-k are normal floats.
+__device__ __forceinline__ int epoch_scale_exp(uint32_t m_bits) {
+  const int e = (int)((m_bits >> 23) & 0xffu);
+  const uint32_t mant = m_bits & 0x7fffffu;
+  if (e == 0) return 0;
+  int k = (kSumBits - 2) + 127 - e;  // 2^k * m in [2^25, 2^26)
+  // 2^k * m = (1 + mant / 2^23) * 2^25 > 2^26 - kEpochRows  <=>  mant > 2^23 - kEpochRows / 4
+  if (mant > (1u << 23) - (uint32_t)(kEpochRows >> (kSumBits - 25))) k -= 1;
   if (k > 126) k = 126;
   if (k < -126) k = -126;
-  if (ldexpf(m, k) > 2147475456.0f) k -= 1;  // keep 2^k * m <= 2^31 - 8192
   return k;
 }
+__device__ __forceinline__ float pow2f(int k) { return __uint_as_float((uint32_t)(k + 127) << 23); }
 
-constexpr int kEpochRows = 8192;  // rows a workgroup accumulates between two drains
+// Sum over the lanes of a wavefront with DPP moves (no LDS traffic); the total
+// arrives in lane 63.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_add(float v) {
+  const int t = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, ROW_MASK, 0xf, false);
+  return v + __int_as_float(t);
+}
+__device__ __forceinline__ float sum_in_8(float v) {  // every lane: sum of its aligned group of 8
+  v = dpp_add<0xb1, 0xf>(v);   // quad_perm [1,0,3,2]
+  v = dpp_add<0x4e, 0xf>(v);   // quad_perm [2,3,0,1]
+  v = dpp_add<0x141, 0xf>(v);  // row_half_mirror
+  return v;
+}
+__device__ __forceinline__ float wave_sum_to_lane63(float v) {
+  v = sum_in_8(v);
+  v = dpp_add<0x140, 0xf>(v);  // row_mirror: every lane holds the sum of its row of 16
+  v = dpp_add<0x142, 0xa>(v);  // row_bcast15: rows 1 and 3 add the row before
+  v = dpp_add<0x143, 0xc>(v);  // row_bcast31: rows 2 and 3 add lane 31 (rows 0 + 1)
+  return v;
+}
+
+// Compile-time shape of the work of one wavefront on a tile of width W.
+template <int CAP, int W, bool NIB, int NT>
+struct TileShape {
+  static constexpr int VEC = W == 16 ? 4 : 8;       // bytes a lane loads
+  static constexpr int NWORD = VEC / 4;             // 32-bit words a lane loads
+  static constexpr int LPR = W / VEC;               // lanes per row
+  static constexpr int RPW = 64 / LPR;              // rows per wavefront load
+  static constexpr int NBW = NWORD * (NIB ? 2 : 1); // byte-words (4 bin values each) per lane
+  static constexpr int SLOTS = 4 * LPR * NBW;       // features of the tile
+  static constexpr int PAGES = (SLOTS + 31) / 32;
+  static constexpr int CELLS = PAGES * CAP * 32;
+  static constexpr int NW = NT / 64;
+  static constexpr int PP = CELLS / NT;             // cells drained by one thread
+  static constexpr int GPE = 64 / RPW;              // row groups per wavefront per epoch
+  static constexpr int U = GPE / 2;                 // row groups per register set (two sets)
+  static_assert(NT == kEpochRows, "an epoch gives every lane one row of its own");
+  static_assert(CELLS % NT == 0, "every thread drains the same number of cells");
+  static_assert(4 * LPR <= 32 && (LPR == 8 || LPR == 4), "slot tables are bytes");
+};
 
 // Histogram of rows [begin, end) of the leaf for one feature tile, accumulated in
 // this workgroup's local memory and then written out as one partial block.
 //
-// Lane mapping.  A lane loads VEC bytes (8 from a 64-byte tile row, else 4), so a
-// row is LPR = W/VEC lane-chunks and a wavefront load covers RPW = 64/LPR rows:
-// lane = rho * LPR + j loads chunk j of row rho.  The chunk's NP features are then
-// handled in NP steps, and the order of the steps is rotated by the lane's row:
-// in step k the lane takes position p = (rho + k) mod (positions per word), in a
-// word that is also swapped by row when a lane holds two words.  This is the
-// rotation of Alg. 2 (p = (l + s) mod 4 there) used for a stronger purpose: with
-// slot = j + LPR * p, in every step the lanes that the LDS serves together (16
-// for a 64-bit atomic, 32 for a 32-bit one) address different, consecutive slots,
-// and the histogram arrays are [bin][slot] with a row length that is a multiple of
-// all 32 banks, so the bank is fixed by the slot whatever the bin values are: the
-// atomics of a step are free of bank conflicts and of same-address collisions by
-// construction, not by chance as with the paper's 8-way interleave or its banked
-// counters (App. A.1).  (16-byte tiles, used only for a narrow last tile, keep
-// this for the 64-bit atomics only.)
+// Lane mapping.  A lane loads VEC bytes of a tile row, so a row is LPR = W / VEC
+// lane-chunks and a wavefront load covers RPW = 64 / LPR rows: lane = rho * LPR + j
+// loads chunk j of row rho.  The chunk's bin values are then handled in steps, 4 per
+// byte-word, and the order of the 4 steps is rotated by the lane's row: in step k
+// the lane takes byte q = (rho + k) mod 4.  This is the rotation of Alg. 2 (p = (l +
+// s) mod 4 there) used for a stronger purpose: with slot = j + LPR * q (+ a
+// compile-time term per byte-word) and cells laid out [page][bin][32 slots], the 16
+// lanes whose 64-bit atomics the LDS serves together address 16 different,
+// 16-aligned consecutive slots, and a row of 32 cells covers all 32 banks once, so
+// the bank pair is fixed by the slot whatever the bin values are: the atomics of a
+// step are free of bank conflicts and of same-address collisions by construction,
+// not by chance as with the paper's 8-way interleave or its banked counters
+// (App. A.1).  Skewed bin distributions (App. A.3) cost nothing extra.
+//
+// Addressing.  The byte address of a cell inside its page is (bin << 8) | (8 *
+// slot): one byte-permute builds it from the loaded bins and a per-lane table of
+// the four values 8 * slot; the page is an immediate offset of the instruction.
 //
 // Arithmetic.  The paper adds floats with a compare-and-swap loop in local memory
 // (App. B.3).  gfx950 has a native LDS float add, but it retires about 0.33
-// lanes/clock/CU against about 16 for a 32-bit and 10 for a 64-bit integer add, so
-// floats are accumulated as integers instead: rows are taken in epochs of at most
-// 8192; per epoch the workgroup sums |grad| and |hess| of the epoch's rows, picks
-// the largest power-of-two scales that cannot overflow 32 bits, and every (row,
-// feature) then costs ONE 64-bit integer atomic that carries the quantised
-// gradient (low half) and hessian (high half), plus one 32-bit atomic for the
-// count.  After each epoch the integer sums are drained into accumulators held in
-// registers (each thread owns PAIRS/NT bins) and the LDS is cleared.
+// lanes/clock/CU against about 10 for a 64-bit integer add, so values are
+// accumulated as integers instead: rows are taken in epochs of kEpochRows = one row
+// per thread.  A lane fetches the gradient and hessian of ITS row of the next epoch
+// while the current epoch is accumulated; the workgroup sums their magnitudes, picks
+// the largest power-of-two scales that cannot overflow a 27-bit field, and each lane
+// quantises its own row once into a 64-bit addend that carries count, gradient and
+// hessian.  The lanes that then work on a row fetch its addend with a wavefront
+// permute, and every (row, feature) costs ONE 64-bit integer atomic.  After each
+// epoch the cells are drained into accumulators held in registers (each thread owns
+// PP cells) and cleared.
 // Error: each value is rounded once, by at most half a quantum; the quantum is at
-// most sum|g|_epoch / 2^30, so a bin is off by at most 8192 / 2^31 = 3.8e-6 of the
-// leaf's sum |g| (likewise for h) -- and integer addition is order-independent, so
-// the result is bit-reproducible.
+// most sum|g|_epoch / (2^25 - 256), so a bin is off by at most 512 / (2^26 - 512) =
+// 7.7e-6 of the leaf's sum |g| (likewise for h) -- and integer addition is
+// order-independent, so the result is bit-reproducible.
+//
+// Memory.  The bins of a wavefront's 64 rows of an epoch are loaded as two register
+// sets of U row groups; the set after next is requested before the current one is
+// added, the gradients / hessians one epoch and the row ids two epochs ahead, so
+// that requests stay in flight across the epoch barriers.
 //
 // All wavefronts of a workgroup share ONE histogram; no replica has to be reduced.
-template <int CAP, int W, bool NIB, int NT, bool INDEXED>
+template <int CAP, int W, bool NIB, int NT, typename ACC, bool INDEXED>
 __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
                                            const int32_t* __restrict__ idx,
                                            const float* __restrict__ grad,
                                            const float* __restrict__ hess, uint32_t begin,
                                            uint32_t end, unsigned long long* lds,
                                            uint32_t* __restrict__ out) {
-  constexpr int VEC = W == 64 ? 8 : 4;   // bytes a lane loads
-  constexpr int NWORD = VEC / 4;
-  constexpr int LPR = W / VEC;
-  constexpr int RPW = 64 / LPR;
-  constexpr int NPW = NIB ? 8 : 4;       // positions per 32-bit word
-  constexpr int NP = NPW * NWORD;
-  constexpr int SLOTS = LPR * NP;
-  constexpr int STRIDE = (!NIB && CAP == 64) ? 64 : SLOTS;  // slots per bin row
-  constexpr int PAIRS = CAP * STRIDE;    // (bin, slot) cells
-  constexpr int PP = PAIRS / NT;         // cells drained by one thread
-  constexpr int NW = NT / 64;
-  constexpr int U = 2;                   // row groups per register set (two sets in flight)
-  constexpr bool PERM = !NIB && STRIDE == 64;  // count address = (bin << 8) | 4 * slot
-  constexpr int ROW_SHIFT = NIB ? (STRIDE == 128 ? 9 : (STRIDE == 64 ? 8 : 7))
-                                : (STRIDE == 64 ? 8 : (STRIDE == 32 ? 7 : 6));
-  static_assert((4 * STRIDE) == (1 << ROW_SHIFT), "count row bytes must be a power of two");
-  static_assert(PAIRS % NT == 0, "every thread drains the same number of cells");
+  using S = TileShape<CAP, W, NIB, NT>;
+  constexpr int VEC = S::VEC, NWORD = S::NWORD, LPR = S::LPR, RPW = S::RPW, NBW = S::NBW;
+  constexpr int CELLS = S::CELLS, PP = S::PP, NW = S::NW, U = S::U;
+  constexpr int NTBL = LPR == 8 ? 1 : 2;  // LPR 4: two byte-words share a page
 
-  char* lgh = reinterpret_cast<char*>(lds);                    // u64 [bin][STRIDE] hess:grad
-  char* lc = reinterpret_cast<char*>(lds + PAIRS);             // u32 [bin][STRIDE] count
-  float* red = reinterpret_cast<float*>(lc + 4 * PAIRS);       // 2 * NW floats
-  unsigned long long* lgh64 = lds;
-  uint32_t* lc32 = reinterpret_cast<uint32_t*>(lc);
+  char* cells = reinterpret_cast<char*>(lds);
+  float* red = reinterpret_cast<float*>(lds + CELLS);  // [2 parities][2 stats][NW]
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -166,213 +215,235 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
   const int j = lane % LPR;
   const int rho = lane / LPR;
 
-  // Per-lane constants of the rotated step order.  pw[k]: position inside a word
-  // taken in step k (k and k + NPW share it).  swap: lanes of rows 4..7 take their
-  // two words in the opposite order (u8, two words), so that 8 rows x 8 positions
-  // stay pairwise different.
-  const bool swap = (!NIB && NWORD == 2) ? ((rho >> 2) & 1) : false;
-  uint32_t sel[4];      // PERM: byte-permute selectors
-  uint32_t tbl[2];      // PERM: 4 * slot of the 4 positions of the first / second word taken
-  uint32_t sh[NPW];     // generic: bit offset of the position inside its word
-  uint32_t s4[NPW];     // generic: 4 * slot of the position in word 0
-  if (PERM) {
+  // Per-lane constants of the rotated step order.
+  uint32_t sel[4];     // byte-permute selectors: byte 1 = bins byte q, byte 0 = table byte q
+  uint32_t tbl[NTBL];  // 8 * slot-in-page of bytes q = 0..3
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      const uint32_t q = (uint32_t)(rho + k) & 3u;
-      sel[k] = 0x0c0c0000u | ((4u + q) << 8) | q;  // byte1 = word byte q, byte0 = table byte q
-    }
+  for (int k = 0; k < 4; ++k) {
+    const uint32_t q = (uint32_t)(rho + k) & 3u;
+    sel[k] = 0x0c0c0000u | ((4u + q) << 8) | q;
+  }
 #pragma unroll
-    for (int wi = 0; wi < 2; ++wi) {
-      const int word_taken = swap ? (1 - wi) : wi;
-      uint32_t t = 0;
+  for (int v = 0; v < NTBL; ++v) {
+    uint32_t t = 0;
 #pragma unroll
-      for (int q = 0; q < 4; ++q) t |= (uint32_t)(4 * (j + LPR * (4 * word_taken + q))) << (8 * q);
-      tbl[wi] = t;
-    }
-  } else {
-#pragma unroll
-    for (int k = 0; k < NPW; ++k) {
-      const uint32_t q = (uint32_t)(rho + k) & (uint32_t)(NPW - 1);
-      sh[k] = q * (NIB ? 4u : 8u);
-      s4[k] = 4u * (uint32_t)(j + LPR * (int)q);
-    }
+    for (int q = 0; q < 4; ++q) t |= (uint32_t)(8 * (16 * v + j + LPR * q)) << (8 * q);
+    tbl[v] = t;
   }
 
 #pragma unroll
-  for (int m = 0; m < PP; ++m) {
-    lgh64[tid + m * NT] = 0ull;
-    lc32[tid + m * NT] = 0u;
-  }
-  float acc_g[PP], acc_h[PP];
+  for (int m = 0; m < PP; ++m) lds[tid + m * NT] = 0ull;
+  ACC acc_g[PP], acc_h[PP];
   uint32_t acc_c[PP];
 #pragma unroll
   for (int m = 0; m < PP; ++m) {
-    acc_g[m] = 0.0f;
-    acc_h[m] = 0.0f;
+    acc_g[m] = (ACC)0;
+    acc_h[m] = (ACC)0;
     acc_c[m] = 0u;
   }
 
-  for (uint32_t e0 = begin; e0 < end; e0 += kEpochRows) {
-    const uint32_t e1 = (end - e0 > (uint32_t)kEpochRows) ? e0 + kEpochRows : end;
+  static_assert(NW == 8, "the wave sums of one statistic fill one group of 8 lanes");
+  auto reduce_abs = [&](float ag, float ah, int parity) {
+    ag = wave_sum_to_lane63(ag);
+    ah = wave_sum_to_lane63(ah);
+    if (lane == 63) {
+      red[parity * 2 * NW + wave] = ag;
+      red[parity * 2 * NW + NW + wave] = ah;
+    }
+  };
+  // lanes 0..7 fetch the wave sums of |g|, lanes 8..15 those of |h|; the two totals are
+  // moved to scalar registers and turned into exponents there
+  auto read_scales = [&](int parity, int& kg, int& kh) {
+    float v = red[parity * 2 * NW + (lane & (2 * NW - 1))];
+    v = sum_in_8(v) * 1.001953125f;
+    kg = epoch_scale_exp(__builtin_amdgcn_readlane(__float_as_uint(v), 0));
+    kh = epoch_scale_exp(__builtin_amdgcn_readlane(__float_as_uint(v), 8));
+  };
 
-    // ---- scales of this epoch from sum |g|, sum |h| over its rows
-    float sg = 0.0f, sh_abs = 0.0f;
-    for (uint32_t i = e0 + tid; i < e1; i += NT) {
-      const uint32_t r = INDEXED ? (uint32_t)idx[i] : i;
-      sg += fabsf(*reinterpret_cast<const float*>(reinterpret_cast<const char*>(grad) + (r << 2)));
-      sh_abs += fabsf(*reinterpret_cast<const float*>(reinterpret_cast<const char*>(hess) + (r << 2)));
-    }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-      sg += __shfl_xor(sg, o);
-      sh_abs += __shfl_xor(sh_abs, o);
-    }
-    if (lane == 0) {
-      red[wave] = sg;
-      red[NW + wave] = sh_abs;
-    }
-    __syncthreads();  // also orders the LDS clearing before the first atomics
-    float tg = 0.0f, th = 0.0f;
-#pragma unroll
-    for (int q = 0; q < NW; ++q) {
-      tg += red[q];
-      th += red[NW + q];
-    }
-    const int kg = epoch_scale_exp(tg);
-    const int kh = epoch_scale_exp(th);
-    const float scale_g = ldexpf(1.0f, kg);
-    const float scale_h = ldexpf(1.0f, kh);
+  // This lane's own row of the epoch that starts at e0: leaf position (clamped to the
+  // chunk's last row, so that every load stays in range), validity, row id.
+  const uint32_t own = (uint32_t)wave * 64u + (uint32_t)lane;
+  auto own_pos = [&](uint32_t e0) {
+    const uint32_t i = e0 + own;
+    return i < end ? i : end - 1;
+  };
+  auto own_valid = [&](uint32_t e0) { return e0 + own < end; };
+  auto load_row_id = [&](uint32_t e0) -> uint32_t {
+    const uint32_t i = own_pos(e0);
+    return INDEXED ? (uint32_t)*reinterpret_cast<const int32_t*>(
+                         reinterpret_cast<const char*>(idx) + (i << 2))
+                   : i;
+  };
+  auto load_stat = [&](const float* a, uint32_t r) {
+    return *reinterpret_cast<const float*>(reinterpret_cast<const char*>(a) + (r << 2));
+  };
+  // value of `v` held by the lane that owns row `rho` of row group gi
+  const int perm_base = 4 * rho;
+  auto from_owner = [&](uint32_t v, int gi) {
+    return (uint32_t)__builtin_amdgcn_ds_bpermute(perm_base + 4 * RPW * gi, (int)v);
+  };
 
-    // ---- accumulate the epoch's rows.  Each wavefront walks its row groups with
-    // the loads of the next U groups in flight while the current U are added
-    // (two register sets, A and B, alternate).  Rows past the epoch end are
-    // clamped to its last row for the loads and add zero.
-    constexpr uint32_t kStep = (uint32_t)NW * RPW * U;
-    auto load_set = [&](uint32_t base, uint2 (&w)[U], float (&g)[U], float (&h)[U],
-                        uint32_t (&one)[U]) {
+  // Register set: the bins of U row groups of one epoch.  rows: the row ids the lanes
+  // own in that epoch; e0: its first leaf position; half: which half of the groups.
+  auto load_set = [&](uint2 (&w)[U], uint32_t rows, uint32_t e0, int half) {
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
-        uint32_t i = base + u * RPW + rho;
-        const bool ok = i < e1;
-        one[u] = ok ? 1u : 0u;
-        i = ok ? i : e1 - 1;  // clamp: loads stay in range and unpredicated
-        const uint32_t r = INDEXED ? (uint32_t)*reinterpret_cast<const int32_t*>(
-                                         reinterpret_cast<const char*>(idx) + (i << 2))
-                                   : i;
-        const uint32_t off = r * (uint32_t)W + (uint32_t)(VEC * j);
-        if (NWORD == 2) {
-          w[u] = *reinterpret_cast<const uint2*>(tile + off);
+    for (int u = 0; u < U; ++u) {
+      const int gi = half * U + u;
+      uint32_t r;
+      if (INDEXED) {
+        r = from_owner(rows, gi);
+      } else {
+        const uint32_t i = e0 + (uint32_t)wave * 64u + (uint32_t)(gi * RPW + rho);
+        r = i < end ? i : end - 1;
+      }
+      // 32-bit byte offsets (n_rows * W < 2^32) keep the address arithmetic out of 64 bits
+      const uint32_t off = r * (uint32_t)W + (uint32_t)(VEC * j);
+      if (NWORD == 2) {
+        w[u] = *reinterpret_cast<const uint2*>(tile + off);
+      } else {
+        w[u].x = *reinterpret_cast<const uint32_t*>(tile + off);
+        w[u].y = 0;
+      }
+    }
+  };
+  // lo, hi: the addend of the row this lane owns (zero for a row past the chunk end)
+  auto add_set = [&](const uint2 (&w)[U], uint32_t lo, uint32_t hi, int half) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int gi = half * U + u;
+      const unsigned long long add =
+          ((unsigned long long)from_owner(hi, gi) << 32) | from_owner(lo, gi);
+      uint32_t bword[NBW];
+#pragma unroll
+      for (int x = 0; x < NWORD; ++x) {
+        const uint32_t word = x == 0 ? w[u].x : w[u].y;
+        if (NIB) {
+          bword[2 * x] = word & 0x0f0f0f0fu;
+          bword[2 * x + 1] = (word >> 4) & 0x0f0f0f0fu;
         } else {
-          w[u].x = *reinterpret_cast<const uint32_t*>(tile + off);
-          w[u].y = 0;
-        }
-        // 32-bit byte offsets (n_rows < 2^30) keep the address arithmetic out of 64 bits
-        g[u] = *reinterpret_cast<const float*>(reinterpret_cast<const char*>(grad) + (r << 2));
-        h[u] = *reinterpret_cast<const float*>(reinterpret_cast<const char*>(hess) + (r << 2));
-      }
-    };
-    auto add_set = [&](const uint2 (&w)[U], const float (&g)[U], const float (&h)[U],
-                       const uint32_t (&one)[U]) {
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        int32_t gq = __float2int_rn(g[u] * scale_g);
-        int32_t hq = __float2int_rn(h[u] * scale_h);
-        gq = one[u] ? gq : 0;
-        hq = one[u] ? hq : 0;
-        // sign-extended gq + (hq << 32) as one 64-bit addend
-        const uint32_t hi = (uint32_t)hq + (uint32_t)(gq >> 31);
-        const unsigned long long add = ((unsigned long long)hi << 32) | (uint32_t)gq;
-        uint32_t wa = w[u].x, wb = w[u].y;
-        if (!NIB && CAP == 64) {  // keep a stray bin value inside the histogram
-          wa &= 0x3f3f3f3fu;
-          wb &= 0x3f3f3f3fu;
-        }
-        if (PERM && NWORD == 2 && swap) {
-          const uint32_t t = wa;
-          wa = wb;
-          wb = t;
-        }
-#pragma unroll
-        for (int k = 0; k < NP; ++k) {
-          const int wi = k / NPW;  // first or second word taken (compile time)
-          const int kk = k % NPW;
-          const uint32_t word = wi == 0 ? wa : wb;
-          uint32_t a4;  // byte offset of the cell in the count array
-          if (PERM) {
-            a4 = __builtin_amdgcn_perm(word, tbl[wi], sel[kk]);
-          } else {
-            const uint32_t b = __builtin_amdgcn_ubfe(word, sh[kk], NIB ? 4u : 8u);
-            a4 = (b << ROW_SHIFT) + s4[kk] + (uint32_t)(wi * 4 * LPR * NPW);
-          }
-          __hip_atomic_fetch_add(reinterpret_cast<unsigned long long*>(lgh + 2 * a4), add,
-                                 __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-          __hip_atomic_fetch_add(reinterpret_cast<uint32_t*>(lc + a4), one[u], __ATOMIC_RELAXED,
-                                 __HIP_MEMORY_SCOPE_WORKGROUP);
+          // CAP 64: keep a stray bin value inside the histogram
+          bword[x] = CAP == 64 ? (word & 0x3f3f3f3fu) : word;
         }
       }
-    };
-    {
-      uint2 aw[U], bw[U];
-      uint32_t aone[U], bone[U];
-      float ag[U], ah[U], bg[U], bh[U];
-      // Loads are issued unconditionally (clamped rows), so that the wait counts
-      // between a set's loads and its use are the same on every path.
-      uint32_t base = e0 + (uint32_t)wave * (RPW * U);
-      load_set(base, aw, ag, ah, aone);
-      while (base < e1) {
-        load_set(base + kStep, bw, bg, bh, bone);
-        add_set(aw, ag, ah, aone);
-        load_set(base + 2 * kStep, aw, ag, ah, aone);
-        add_set(bw, bg, bh, bone);  // all-zero addends when this set lies past the end
-        base += 2 * kStep;
+#pragma unroll
+      for (int bw = 0; bw < NBW; ++bw) {
+        constexpr int kPageShift = LPR == 8 ? 0 : 1;
+        const int page = bw >> kPageShift;
+        const int tv = LPR == 8 ? 0 : (bw & 1);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          const uint32_t a = __builtin_amdgcn_perm(bword[bw], tbl[tv], sel[k]);
+          __hip_atomic_fetch_add(
+              reinterpret_cast<unsigned long long*>(cells + a + page * (CAP * 256)), add,
+              __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        }
       }
     }
-    __syncthreads();
+  };
 
-    // ---- drain: integer sums -> registers, clear the LDS for the next epoch
-    const float inv_g = ldexpf(1.0f, -kg);
-    const float inv_h = ldexpf(1.0f, -kh);
+  const uint32_t n_epochs = (end - begin + kEpochRows - 1) / kEpochRows;
+  int kg, kh;
+  // rows the lane owns in the current epoch and the next one; the current row's stats
+  uint32_t row_cur = load_row_id(begin);
+  uint32_t row_nxt = load_row_id(begin + kEpochRows);
+  float g_cur = load_stat(grad, row_cur);
+  float h_cur = load_stat(hess, row_cur);
+  {
+    const bool ok = own_valid(begin);
+    reduce_abs(ok ? fabsf(g_cur) : 0.0f, ok ? fabsf(h_cur) : 0.0f, 0);
+  }
+  __syncthreads();  // also orders the LDS clearing before the first atomics
+  read_scales(0, kg, kh);
+
+  uint2 set_a[U], set_b[U];
+  load_set(set_a, row_cur, begin, 0);
+  for (uint32_t e = 0; e < n_epochs; ++e) {
+    const uint32_t e0 = begin + e * (uint32_t)kEpochRows;
+    // ---- this lane's row -> 64-bit addend 1 + gq * 2^10 + hq * 2^37 (two's complement)
+    uint32_t lo, hi;
+    {
+      const int32_t gq = __float2int_rn(g_cur * pow2f(kg));
+      const int32_t hq = __float2int_rn(h_cur * pow2f(kh));
+      lo = ((uint32_t)gq << kCountBits) + 1u;
+      hi = (uint32_t)(gq >> (32 - kCountBits)) + ((uint32_t)hq << (kCountBits + kSumBits - 32));
+      const bool ok = own_valid(e0);
+      lo = ok ? lo : 0u;
+      hi = ok ? hi : 0u;
+    }
+    // ---- requests for later epochs
+    const uint32_t row_nn = load_row_id(e0 + 2 * kEpochRows);
+    const float g_nxt = load_stat(grad, row_nxt);
+    const float h_nxt = load_stat(hess, row_nxt);
+    // ---- accumulate: the loads of one register set fly while the other is added
+    load_set(set_b, row_cur, e0, 1);
+    add_set(set_a, lo, hi, 0);
+    load_set(set_a, row_nxt, e0 + kEpochRows, 0);
+    add_set(set_b, lo, hi, 1);
+
+    const int parity = (int)((e + 1) & 1u);
+    {
+      const bool ok = own_valid(e0 + kEpochRows);
+      reduce_abs(ok ? fabsf(g_nxt) : 0.0f, ok ? fabsf(h_nxt) : 0.0f, parity);
+    }
+    __syncthreads();  // all atomics of the epoch have landed
+
+    // ---- drain: integer sums -> registers, clear the cells for the next epoch
+    const float inv_g = pow2f(-kg);
+    const float inv_h = pow2f(-kh);
 #pragma unroll
     for (int m = 0; m < PP; ++m) {
-      const int64_t t = (int64_t)lgh64[tid + m * NT];
-      const int32_t lo = (int32_t)t;
-      const int32_t hi = (int32_t)((t - (int64_t)lo) >> 32);
-      // exact product of an integer and a power of two, rounded once to fp32
-      acc_g[m] += (float)((double)lo * (double)inv_g);
-      acc_h[m] += (float)((double)hi * (double)inv_h);
-      acc_c[m] += lc32[tid + m * NT];
-      lgh64[tid + m * NT] = 0ull;
-      lc32[tid + m * NT] = 0u;
+      const unsigned long long t = lds[tid + m * NT];
+      lds[tid + m * NT] = 0ull;
+      const uint32_t tlo = (uint32_t)t, thi = (uint32_t)(t >> 32);
+      const uint32_t c = tlo & ((1u << kCountBits) - 1u);
+      // bits 10..36: the gradient sum, sign-extended; the hessian sum sits above a
+      // borrow of one when the gradient sum is negative
+      const uint32_t mid = (thi << (32 - kCountBits)) | (tlo >> kCountBits);
+      const int32_t gs = (int32_t)(mid << (32 - kSumBits)) >> (32 - kSumBits);
+      const int32_t hs = ((int32_t)thi >> (kCountBits + kSumBits - 32)) + (int32_t)((mid >> (kSumBits - 1)) & 1u);
+      // integer * power of two + accumulator, rounded once
+      if (sizeof(ACC) == 8) {
+        acc_g[m] = (ACC)fma((double)gs, (double)inv_g, (double)acc_g[m]);
+        acc_h[m] = (ACC)fma((double)hs, (double)inv_h, (double)acc_h[m]);
+      } else {
+        acc_g[m] = (ACC)__fmaf_rn((float)gs, inv_g, (float)acc_g[m]);
+        acc_h[m] = (ACC)__fmaf_rn((float)hs, inv_h, (float)acc_h[m]);
+      }
+      acc_c[m] += c;
     }
-    // the next epoch's first barrier separates this clearing from its atomics, and
-    // this epoch's reads of `red` (before the accumulate loop) from its rewriting
+    read_scales(parity, kg, kh);
+    row_cur = row_nxt;
+    row_nxt = row_nn;
+    g_cur = g_nxt;
+    h_cur = h_nxt;
+    __syncthreads();  // cells are clear, and `red` of this parity is read, before reuse
   }
 
-  // partial block layout: [stat][bin][STRIDE] words, cell index = bin * STRIDE + slot
+  // partial block layout: [stat][cell] words
 #pragma unroll
   for (int m = 0; m < PP; ++m) {
-    out[tid + m * NT] = __float_as_uint(acc_g[m]);
-    out[PAIRS + tid + m * NT] = __float_as_uint(acc_h[m]);
-    out[2 * PAIRS + tid + m * NT] = acc_c[m];
+    out[tid + m * NT] = __float_as_uint((float)acc_g[m]);
+    out[CELLS + tid + m * NT] = __float_as_uint((float)acc_h[m]);
+    out[2 * CELLS + tid + m * NT] = acc_c[m];
   }
 }
 
-// Words of one partial block of a tile of width w.
-template <int CAP, bool NIB>
-__device__ __host__ constexpr int block_words(int w) {
-  return 3 * CAP * ((!NIB && CAP == 64) ? 64 : (NIB ? 2 * w : w));
+// Words of one partial block of a tile of width W.
+template <int CAP, int W, bool NIB, int NT>
+__device__ __host__ constexpr int block_words() {
+  return 3 * TileShape<CAP, W, NIB, NT>::CELLS;
 }
 
 // Work is split by feature tiles and by row chunks (Sec. 4, "Parallel By Features
 // and Data"): block -> (tile, chunk).  Consecutive blocks take different tiles of
 // the same chunk, so the chunk's row ids / gradients / hessians are fetched from
 // HBM once and served to the other tiles from cache.
-template <int CAP, int WM, bool NIB, int NT, bool INDEXED>
-__global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT == 512 ? 6 : 4, NT == 512 ? 6 : 4)))
+template <int CAP, int WM, bool NIB, int NT, int WPE, typename ACC, bool INDEXED>
+__global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(WPE, WPE)))
 hist_build_kernel(BuildArgs a) {
-  // one histogram of the main tile width (12 bytes per cell) + the reduction scratch
-  constexpr int kLdsBytes = 4 * block_words<CAP, NIB>(WM) + 2 * (NT / 64) * 4;
-  __shared__ __align__(16) unsigned long long lds[(kLdsBytes + 7) / 8];
+  // one histogram of the main tile width (8 bytes per cell) + the reduction scratch
+  constexpr int kCells = TileShape<CAP, WM, NIB, NT>::CELLS;
+  __shared__ __align__(16) unsigned long long lds[kCells + (4 * (NT / 64) * 4 + 7) / 8];
   const int32_t main_blocks = a.n_main * a.chunks_main;
   const int32_t b = blockIdx.x;
   const uint32_t n_leaf = (uint32_t)a.n_leaf;
@@ -383,21 +454,21 @@ hist_build_kernel(BuildArgs a) {
     uint32_t end = begin + (uint32_t)a.rows_per_chunk_main;
     if (end > n_leaf) end = n_leaf;
     const uint8_t* tile = a.packed + a.n_rows * ((int64_t)t * WM);
-    uint32_t* out = a.partials + ((size_t)t * a.chunks_main + c) * (size_t)block_words<CAP, NIB>(WM);
-    build_tile<CAP, WM, NIB, NT, INDEXED>(tile, a.idx, a.grad, a.hess, begin, end, lds, out);
+    uint32_t* out = a.partials + ((size_t)t * a.chunks_main + c) * (size_t)block_words<CAP, WM, NIB, NT>();
+    build_tile<CAP, WM, NIB, NT, ACC, INDEXED>(tile, a.idx, a.grad, a.hess, begin, end, lds, out);
   } else {
     const int32_t c = b - main_blocks;
     const uint32_t begin = (uint32_t)c * (uint32_t)a.rows_per_chunk_rem;
     uint32_t end = begin + (uint32_t)a.rows_per_chunk_rem;
     if (end > n_leaf) end = n_leaf;
     const uint8_t* tile = a.packed + a.n_rows * ((int64_t)a.n_main * WM);
-    uint32_t* rem_base = a.partials + (size_t)main_blocks * (size_t)block_words<CAP, NIB>(WM);
+    uint32_t* rem_base = a.partials + (size_t)main_blocks * (size_t)block_words<CAP, WM, NIB, NT>();
     if (a.wr == 16) {
-      build_tile<CAP, 16, NIB, NT, INDEXED>(tile, a.idx, a.grad, a.hess, begin, end, lds,
-                                            rem_base + (size_t)c * (size_t)block_words<CAP, NIB>(16));
+      build_tile<CAP, 16, NIB, NT, ACC, INDEXED>(tile, a.idx, a.grad, a.hess, begin, end, lds,
+                                            rem_base + (size_t)c * (size_t)block_words<CAP, 16, NIB, NT>());
     } else {
-      build_tile<CAP, 32, NIB, NT, INDEXED>(tile, a.idx, a.grad, a.hess, begin, end, lds,
-                                            rem_base + (size_t)c * (size_t)block_words<CAP, NIB>(32));
+      build_tile<CAP, 32, NIB, NT, ACC, INDEXED>(tile, a.idx, a.grad, a.hess, begin, end, lds,
+                                            rem_base + (size_t)c * (size_t)block_words<CAP, 32, NIB, NT>());
     }
   }
 }
@@ -419,10 +490,10 @@ constexpr int kMergeLanes = 4;    // threads that share the chunks of one cell
 
 // The "final reduction program" of Sec. 4: sums the partial histograms of the
 // workgroups that shared a feature tile.  A workgroup takes 64 consecutive (bin,
-// slot) cells of one tile (slot fastest, so every read of a partial block is
-// coalesced); 4 threads per cell each sum every 4th chunk in fp64, in chunk order,
-// and the 4 sub-sums are added in a fixed order: the result does not depend on
-// scheduling.  Counts are summed as integers.  grid.y = tile.
+// slot) pairs of one tile (slot fastest, so reads of a partial block are coalesced
+// in runs of 32); 4 threads per pair each sum every 4th chunk in fp64, in chunk
+// order, and the 4 sub-sums are added in a fixed order: the result does not depend
+// on scheduling.  Counts are summed as integers.  grid.y = tile.
 __global__ void __launch_bounds__(kMergeCells * kMergeLanes) hist_merge_kernel(MergeArgs a) {
   __shared__ double s_g[kMergeLanes][kMergeCells];
   __shared__ double s_h[kMergeLanes][kMergeCells];
@@ -430,16 +501,14 @@ __global__ void __launch_bounds__(kMergeCells * kMergeLanes) hist_merge_kernel(M
   const int32_t t = blockIdx.y;
   const int32_t w = plan_tile_width(a.plan, t);
   const int32_t slots = plan_slots(a.plan, w);
-  const int32_t stride = plan_stride(a.plan, w);
-  const int32_t cap = a.plan.cap;
   const int cell = threadIdx.x % kMergeCells;
   const int part = threadIdx.x / kMergeCells;
   const int32_t e = blockIdx.x * kMergeCells + cell;
   const bool live = e < a.n_bins * slots;
   const int32_t bin = live ? e / slots : 0;
   const int32_t slot = live ? e - bin * slots : 0;
-  const size_t hw = (size_t)cap * stride;
-  const size_t main_block = (size_t)3 * cap * plan_stride(a.plan, a.plan.wm);
+  const size_t hw = (size_t)plan_cells(a.plan, w);
+  const size_t main_block = (size_t)3 * plan_cells(a.plan, a.plan.wm);
   const uint32_t* p;
   int32_t chunks;
   if (t < a.plan.n_main) {
@@ -449,7 +518,7 @@ __global__ void __launch_bounds__(kMergeCells * kMergeLanes) hist_merge_kernel(M
     p = a.partials + (size_t)a.plan.n_main * a.chunks_main * main_block;
     chunks = a.chunks_rem;
   }
-  p += (size_t)bin * stride + slot + (size_t)part * 3 * hw;
+  p += (size_t)plan_cell(a.plan, bin, slot) + (size_t)part * 3 * hw;
   double g = 0.0, h = 0.0;
   uint32_t n = 0;
   if (live) {
@@ -784,7 +853,8 @@ int device_cu_count() {
 }
 
 constexpr size_t kLdsPerCu = 160 * 1024;
-constexpr int kMinRowsPerChunk = 512;
+constexpr int kMinRowsPerChunk = kEpochRows;
+constexpr int kBuildThreads = 512;  // threads per workgroup of every build kernel variant
 constexpr int kOversubscribe = 3;  // rounds of workgroups per resident slot
 
 struct BuildGeom {
@@ -808,9 +878,9 @@ BuildGeom make_geom(int32_t n_features, int32_t n_bins, int64_t n_leaf, int cus,
   BuildGeom g;
   g.plan = make_tile_plan(n_features, n_bins);
   const TilePlan& p = g.plan;
-  g.nt = p.cap == 256 ? 1024 : 512;
-  const size_t main_block = (size_t)3 * p.cap * plan_stride(p, p.wm);
-  g.lds_bytes = main_block * 4 + 2 * (g.nt / 64) * sizeof(float);
+  g.nt = kBuildThreads;
+  const size_t main_block = (size_t)3 * plan_cells(p, p.wm);
+  g.lds_bytes = (size_t)plan_cells(p, p.wm) * 8 + 4 * (g.nt / 64) * sizeof(float);
   int wg_per_cu = wg_per_cu_hint;
   if (wg_per_cu <= 0) {
     wg_per_cu = (int)(kLdsPerCu / g.lds_bytes);
@@ -833,8 +903,8 @@ BuildGeom make_geom(int32_t n_features, int32_t n_bins, int64_t n_leaf, int cus,
   if (chunks > max_chunks) chunks = max_chunks;
   if (chunks < 1) chunks = 1;
   g.chunks_main = p.n_main ? (int)chunks : 0;
-  g.rpc_main = p.n_main ? round_up((n_leaf + chunks - 1) / chunks, 64) : 0;
-  if (g.rpc_main < 64) g.rpc_main = 64;
+  g.rpc_main = p.n_main ? round_up((n_leaf + chunks - 1) / chunks, kEpochRows) : 0;
+  if (g.rpc_main < kEpochRows) g.rpc_main = kEpochRows;
   if (p.n_main) g.chunks_main = (int)((n_leaf + g.rpc_main - 1) / g.rpc_main);
   if (p.n_main && g.chunks_main < 1) g.chunks_main = 1;
   g.chunks_rem = 0;
@@ -842,21 +912,27 @@ BuildGeom make_geom(int32_t n_features, int32_t n_bins, int64_t n_leaf, int cus,
   if (p.wr) {
     int64_t cr = p.n_main ? (chunks * p.wr + p.wm - 1) / p.wm : chunks;
     if (cr < 1) cr = 1;
-    g.rpc_rem = round_up((n_leaf + cr - 1) / cr, 64);
-    if (g.rpc_rem < 64) g.rpc_rem = 64;
+    g.rpc_rem = round_up((n_leaf + cr - 1) / cr, kEpochRows);
+    if (g.rpc_rem < kEpochRows) g.rpc_rem = kEpochRows;
     g.chunks_rem = (int)((n_leaf + g.rpc_rem - 1) / g.rpc_rem);
     if (g.chunks_rem < 1) g.chunks_rem = 1;
   }
   g.partial_words = (size_t)p.n_main * g.chunks_main * main_block +
-                    (size_t)g.chunks_rem * 3 * p.cap * (p.wr ? plan_stride(p, p.wr) : 0);
+                    (size_t)g.chunks_rem * 3 * (p.wr ? plan_cells(p, p.wr) : 0);
   return g;
 }
 
-template <int CAP, int WM, bool NIB, int NT, bool INDEXED>
+// Kernel variants: bin capacity -> (main tile width, 4-bit, waves per SIMD the
+// register budget is set for).
+#define GBDT_VARIANT_16 16, 64, true, kBuildThreads, 8, double
+#define GBDT_VARIANT_64 64, 64, false, kBuildThreads, 6, float
+#define GBDT_VARIANT_256 256, 32, false, kBuildThreads, 4, float
+
+template <int CAP, int WM, bool NIB, int NT, int WPE, typename ACC, bool INDEXED>
 int query_occupancy() {
   int n = 0;
   hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(
-      &n, reinterpret_cast<const void*>(hist_build_kernel<CAP, WM, NIB, NT, INDEXED>), NT, 0);
+      &n, reinterpret_cast<const void*>(hist_build_kernel<CAP, WM, NIB, NT, WPE, ACC, INDEXED>), NT, 0);
   if (e != hipSuccess) {
     (void)hipGetLastError();
     return 0;
@@ -876,9 +952,9 @@ int build_wg_per_cu(int cap, bool indexed) {
   const int ci = cap == 16 ? 0 : (cap == 64 ? 1 : 2);
   int& c = cache[ci][indexed ? 1 : 0];
   if (c < 0) {
-    if (cap == 16) c = indexed ? query_occupancy<16, 64, true, 512, true>() : query_occupancy<16, 64, true, 512, false>();
-    else if (cap == 64) c = indexed ? query_occupancy<64, 64, false, 512, true>() : query_occupancy<64, 64, false, 512, false>();
-    else c = indexed ? query_occupancy<256, 32, false, 1024, true>() : query_occupancy<256, 32, false, 1024, false>();
+    if (cap == 16) c = indexed ? query_occupancy<GBDT_VARIANT_16, true>() : query_occupancy<GBDT_VARIANT_16, false>();
+    else if (cap == 64) c = indexed ? query_occupancy<GBDT_VARIANT_64, true>() : query_occupancy<GBDT_VARIANT_64, false>();
+    else c = indexed ? query_occupancy<GBDT_VARIANT_256, true>() : query_occupancy<GBDT_VARIANT_256, false>();
   }
   return c;
 }
@@ -899,7 +975,7 @@ bool valid_shape(int64_t n_rows, int32_t n_features, int32_t n_bins) {
   return n_rows >= 0 && n_features > 0 && n_bins >= 2 && n_bins <= 256;
 }
 
-template <int CAP, int WM, bool NIB, int NT>
+template <int CAP, int WM, bool NIB, int NT, int WPE, typename ACC>
 int launch_build(const BuildArgs& a, int blocks, hipStream_t s) {
   hipEvent_t ev0 = nullptr, ev1 = nullptr;
   bool prof = false;
@@ -913,9 +989,9 @@ int launch_build(const BuildArgs& a, int blocks, hipStream_t s) {
     HIP_TRY(hipEventRecord(ev0, s));
   }
   if (a.idx) {
-    hipLaunchKernelGGL((hist_build_kernel<CAP, WM, NIB, NT, true>), dim3(blocks), dim3(NT), 0, s, a);
+    hipLaunchKernelGGL((hist_build_kernel<CAP, WM, NIB, NT, WPE, ACC, true>), dim3(blocks), dim3(NT), 0, s, a);
   } else {
-    hipLaunchKernelGGL((hist_build_kernel<CAP, WM, NIB, NT, false>), dim3(blocks), dim3(NT), 0, s, a);
+    hipLaunchKernelGGL((hist_build_kernel<CAP, WM, NIB, NT, WPE, ACC, false>), dim3(blocks), dim3(NT), 0, s, a);
   }
   HIP_TRY(hipGetLastError());
   if (prof) {
@@ -1025,11 +1101,11 @@ int gbdt_hist_build(const void* bin_matrix, int64_t n_rows, int32_t n_features, 
   const int blocks = p.n_main * g.chunks_main + g.chunks_rem;
 
   if (p.cap == 16) {
-    rc = launch_build<16, 64, true, 512>(a, blocks, s);
+    rc = launch_build<GBDT_VARIANT_16>(a, blocks, s);
   } else if (p.cap == 64) {
-    rc = launch_build<64, 64, false, 512>(a, blocks, s);
+    rc = launch_build<GBDT_VARIANT_64>(a, blocks, s);
   } else {
-    rc = launch_build<256, 32, false, 1024>(a, blocks, s);
+    rc = launch_build<GBDT_VARIANT_256>(a, blocks, s);
   }
   if (rc != GBDT_OK) return rc;
 

@@ -2,8 +2,8 @@
 //
 // The paper (Sec. 4, "Data Structure") bundles 4 one-byte features of a sample
 // into one 4-byte word so that a thread never fetches a single byte, and stores
-// those words tuple-major.  Here the bundle is kept (a lane still loads one
-// 4-byte word = 4 features, or 8 with 4-bit bins, App. C.4) but words are laid
+// those words tuple-major.  Here the bundle is kept (a lane loads 4 or 8 bytes
+// = 4 or 8 features, twice that with 4-bit bins, App. C.4) but words are laid
 // out row-major inside FEATURE TILES of W bytes: tile t holds, for every row, W
 // consecutive bytes.  A gathered leaf row then costs one contiguous W-byte
 // segment per tile instead of one 4-byte word per cache line.
@@ -13,19 +13,20 @@
 // All tiles have the "main" width WM except possibly the last one, which is 16
 // or 32 bytes wide when few feature bytes remain (so that padding stays small).
 //
-// Inside a tile, a lane loads VEC consecutive bytes of a row: 8 bytes from a
-// 64-byte tile, 4 bytes from a 16- or 32-byte tile.  Byte i of the tile row is
-// byte i % VEC of lane-chunk j = i / VEC; with 4-bit bins the low nibble of a
-// byte is feature 2i, the high nibble 2i + 1.  A lane-chunk so holds NP = VEC
-// (or 2 * VEC) features at positions p = 0..NP-1.
+// Inside a tile, a lane loads VEC consecutive bytes of a row (4 from a 16-byte
+// tile, else 8), so a row is LPR = W / VEC lane-chunks.  Byte i of the tile row
+// is byte bl = i % VEC of lane-chunk j = i / VEC.  The lane splits its bytes
+// into "byte-words" of 4 bin values each: with 8-bit bins byte-word bw is the
+// loaded word bl / 4; with 4-bit bins each loaded word gives two byte-words, its
+// low nibbles (features 2i) and its high nibbles (features 2i + 1): bw = 2 *
+// (bl / 4) + half.  q = bl % 4 is the value's byte inside its byte-word.
 //
-// Local-memory histogram of one tile: an array of 64-bit (hess:grad) sums and an
-// array of 32-bit counts, each [bin][stride] with the feature at slot
-// = j + LPR * p, LPR = W / VEC lane-chunks per row.  The stride is the number of
-// slots of the tile, except that all tiles of the 64-bin variant use stride 64 so
-// that (bin << 8) | (4 * slot) is a byte address a single byte-permute can form.
-// With this slot order the lanes the LDS serves together, which at any step work
-// on pairwise different (j, p), fall into different banks (see build_tile).
+// Histogram slot of a feature of the tile:  s = j + LPR * q + 4 * LPR * bw.
+// The local-memory histogram and each partial block in the workspace are cells
+// [page = s / 32][bin][s % 32]; one page row (32 cells of 8 bytes) spans all 32
+// banks exactly once.  With this slot order the lanes the LDS serves together,
+// which at any step work on pairwise different (j, q), fall into different
+// banks whatever the bin values are (see build_tile).
 #ifndef GBDT_TILE_PLAN_H_
 #define GBDT_TILE_PLAN_H_
 
@@ -70,9 +71,15 @@ GBDT_HD int32_t plan_tile_width(const TilePlan& p, int32_t t) { return t < p.n_m
 // features (= slots) held by a tile of width w
 GBDT_HD int32_t plan_slots(const TilePlan& p, int32_t w) { return p.nib ? 2 * w : w; }
 // bytes a lane loads from a row of a tile of width w
-GBDT_HD int32_t plan_vec(int32_t w) { return w == 64 ? 8 : 4; }
-// slots per bin row of the LDS / partial-block histogram of a tile of width w
-GBDT_HD int32_t plan_stride(const TilePlan& p, int32_t w) { return p.cap == 64 ? 64 : plan_slots(p, w); }
+GBDT_HD int32_t plan_vec(int32_t w) { return w == 16 ? 4 : 8; }
+// pages of 32 slots in the histogram of a tile of width w
+GBDT_HD int32_t plan_pages(const TilePlan& p, int32_t w) { return (plan_slots(p, w) + 31) / 32; }
+// cells ((bin, slot) pairs, padding included) of the histogram of a tile of width w
+GBDT_HD int32_t plan_cells(const TilePlan& p, int32_t w) { return plan_pages(p, w) * p.cap * 32; }
+// index of cell (bin, slot) inside a histogram / partial block
+GBDT_HD int32_t plan_cell(const TilePlan& p, int32_t bin, int32_t slot) {
+  return (slot >> 5) * p.cap * 32 + bin * 32 + (slot & 31);
+}
 
 struct FeatureSlot {
   int32_t tile;
@@ -87,12 +94,14 @@ GBDT_HD FeatureSlot plan_locate(const TilePlan& p, int32_t f) {
   int32_t w = plan_tile_width(p, t);
   int32_t i = fb - t * p.wm;  // byte inside the tile row
   int32_t vec = plan_vec(w);
+  int32_t lpr = w / vec;
   int32_t j = i / vec;
   int32_t bl = i - j * vec;  // byte inside the lane-chunk
-  int32_t pos = p.nib ? (bl * 2 + (f & 1)) : bl;
+  int32_t bw = p.nib ? (2 * (bl >> 2) + (f & 1)) : (bl >> 2);
+  int32_t q = bl & 3;
   FeatureSlot r;
   r.tile = t;
-  r.slot = j + (w / vec) * pos;
+  r.slot = j + lpr * q + 4 * lpr * bw;
   return r;
 }
 
@@ -102,10 +111,15 @@ GBDT_HD int32_t plan_feature_of(const TilePlan& p, int32_t t, int32_t slot) {
   int32_t w = plan_tile_width(p, t);
   int32_t vec = plan_vec(w);
   int32_t lpr = w / vec;
-  int32_t pos = slot / lpr;
-  int32_t j = slot - pos * lpr;
-  if (p.nib) return 2 * (t * p.wm + j * vec + (pos >> 1)) + (pos & 1);
-  return t * p.wm + j * vec + pos;
+  int32_t bw = slot / (4 * lpr);
+  int32_t rest = slot - bw * 4 * lpr;
+  int32_t q = rest / lpr;
+  int32_t j = rest - q * lpr;
+  if (p.nib) {
+    int32_t bl = 4 * (bw >> 1) + q;
+    return 2 * (t * p.wm + j * vec + bl) + (bw & 1);
+  }
+  return t * p.wm + j * vec + 4 * bw + q;
 }
 
 #endif  // GBDT_TILE_PLAN_H_

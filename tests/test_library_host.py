@@ -92,8 +92,10 @@ def test_tile_plan_is_a_bijection_onto_slots(n_features, n_bins):
         assert 0 <= s < w * per_byte
         assert (t, s) not in seen
         seen.add((t, s))
-    # largest histogram must fit the LDS the launch requests, and the CU
-    assert 3 * g["cap"] * g["wm"] * per_byte * 4 <= g["lds_bytes"] <= 160 * 1024
+    # the main tile's histogram (8-byte cells, 32 slots per page row) must fit the LDS
+    # the kernel declares, and the CU
+    pages = (g["wm"] * per_byte + 31) // 32
+    assert pages * g["cap"] * 32 * 8 <= g["lds_bytes"] <= 160 * 1024
 
 
 @pytest.mark.parametrize("n_features,n_bins", [(28, 64), (2000, 63), (28, 255), (137, 255), (700, 16), (5, 2)])
@@ -109,8 +111,8 @@ def test_row_chunks_cover_the_leaf_exactly(n_features, n_bins, n_leaf):
         assert chunks >= 1 and rpc >= 1
         assert chunks * rpc >= n_leaf            # every row belongs to a chunk
         assert (chunks - 1) * rpc < n_leaf       # no chunk starts past the end
-        stride = 64 if g["cap"] == 64 else w * per_byte
-        words += tiles * chunks * 3 * g["cap"] * stride
+        pages = (w * per_byte + 31) // 32
+        words += tiles * chunks * 3 * g["cap"] * 32 * pages
     assert words == g["partial_words"]
     assert B.gbdt_workspace_bytes(n_leaf, n_features, n_bins) >= 4 * g["partial_words"]
     assert (g["n_main"] * g["chunks_main"] + g["chunks_rem"]) < 2 ** 31
