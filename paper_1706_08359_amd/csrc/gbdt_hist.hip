@@ -19,6 +19,7 @@
 #include <string.h>
 
 #include <mutex>
+#include <type_traits>
 #include <utility>
 #include <vector>
 
@@ -260,9 +261,15 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
     kh = epoch_scale_exp(__builtin_amdgcn_readlane(__float_as_uint(v), 8));
   };
 
-  // This lane's own row of the epoch that starts at e0: leaf position (clamped to the
-  // chunk's last row, so that every load stays in range), validity, row id.
-  const uint32_t own = (uint32_t)wave * 64u + (uint32_t)lane;
+  // Row ownership.  In every epoch the wavefront takes 64 consecutive leaf positions,
+  // as GPE row groups of RPW rows; lane (rho, j) works on row rho of every group and
+  // OWNS (fetches the row id, gradient and hessian of, and quantises) row rho of
+  // group j.  The owner of a row therefore sits among the LPR lanes that work on it,
+  // and its values reach them with DPP broadcasts, without LDS traffic.
+  static_assert(S::GPE == LPR, "one owner lane per (row, group)");
+  const uint32_t own = (uint32_t)wave * 64u + (uint32_t)(j * RPW + rho);
+  // leaf position (clamped to the chunk's last row, so that every load stays in
+  // range), validity and row id of the row this lane owns in the epoch starting at e0
   auto own_pos = [&](uint32_t e0) {
     const uint32_t i = e0 + own;
     return i < end ? i : end - 1;
@@ -277,69 +284,89 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
   auto load_stat = [&](const float* a, uint32_t r) {
     return *reinterpret_cast<const float*>(reinterpret_cast<const char*>(a) + (r << 2));
   };
-  // value of `v` held by the lane that owns row `rho` of row group gi
-  const int perm_base = 4 * rho;
-  auto from_owner = [&](uint32_t v, int gi) {
-    return (uint32_t)__builtin_amdgcn_ds_bpermute(perm_base + 4 * RPW * gi, (int)v);
+  // value of `v` held by the owner of this lane's row of group gi: lane j = gi of the
+  // lane's group of LPR lanes
+  auto from_owner = [&](uint32_t v, auto gi_tag) -> uint32_t {
+    constexpr int gi = decltype(gi_tag)::value;
+    if (LPR == 4) {  // quad broadcast
+      return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, gi * 0x55, 0xf, 0xf, false);
+    }
+    // LPR 8: lanes 0..7 of each row of 16 take lane gi, lanes 8..15 take lane 8 + gi
+    const int lo8 = __builtin_amdgcn_update_dpp(0, (int)v, 0x150 + gi, 0xf, 0x3, false);
+    return (uint32_t)__builtin_amdgcn_update_dpp(lo8, (int)v, 0x158 + gi, 0xf, 0xc, false);
   };
 
   // Register set: the bins of U row groups of one epoch.  rows: the row ids the lanes
-  // own in that epoch; e0: its first leaf position; half: which half of the groups.
-  auto load_set = [&](uint2 (&w)[U], uint32_t rows, uint32_t e0, int half) {
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int gi = half * U + u;
-      uint32_t r;
-      if (INDEXED) {
-        r = from_owner(rows, gi);
-      } else {
-        const uint32_t i = e0 + (uint32_t)wave * 64u + (uint32_t)(gi * RPW + rho);
-        r = i < end ? i : end - 1;
-      }
-      // 32-bit byte offsets (n_rows * W < 2^32) keep the address arithmetic out of 64 bits
-      const uint32_t off = r * (uint32_t)W + (uint32_t)(VEC * j);
-      if (NWORD == 2) {
-        w[u] = *reinterpret_cast<const uint2*>(tile + off);
-      } else {
-        w[u].x = *reinterpret_cast<const uint32_t*>(tile + off);
-        w[u].y = 0;
-      }
+  // own in that epoch; e0: its first leaf position; HALF: which half of the groups.
+  auto load_group = [&](uint2& w, uint32_t rows, uint32_t e0, auto gi_tag) {
+    constexpr int gi = decltype(gi_tag)::value;
+    uint32_t r;
+    if (INDEXED) {
+      r = from_owner(rows, gi_tag);
+    } else {
+      const uint32_t i = e0 + (uint32_t)wave * 64u + (uint32_t)(gi * RPW + rho);
+      r = i < end ? i : end - 1;
+    }
+    // 32-bit byte offsets (n_rows * W < 2^32) keep the address arithmetic out of 64 bits
+    const uint32_t off = r * (uint32_t)W + (uint32_t)(VEC * j);
+    if (NWORD == 2) {
+      w = *reinterpret_cast<const uint2*>(tile + off);
+    } else {
+      w.x = *reinterpret_cast<const uint32_t*>(tile + off);
+      w.y = 0;
     }
   };
   // lo, hi: the addend of the row this lane owns (zero for a row past the chunk end)
-  auto add_set = [&](const uint2 (&w)[U], uint32_t lo, uint32_t hi, int half) {
+  auto add_group = [&](const uint2& w, uint32_t lo, uint32_t hi, auto gi_tag) {
+    const unsigned long long add =
+        ((unsigned long long)from_owner(hi, gi_tag) << 32) | from_owner(lo, gi_tag);
+    uint32_t bword[NBW];
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int gi = half * U + u;
-      const unsigned long long add =
-          ((unsigned long long)from_owner(hi, gi) << 32) | from_owner(lo, gi);
-      uint32_t bword[NBW];
-#pragma unroll
-      for (int x = 0; x < NWORD; ++x) {
-        const uint32_t word = x == 0 ? w[u].x : w[u].y;
-        if (NIB) {
-          bword[2 * x] = word & 0x0f0f0f0fu;
-          bword[2 * x + 1] = (word >> 4) & 0x0f0f0f0fu;
-        } else {
-          // CAP 64: keep a stray bin value inside the histogram
-          bword[x] = CAP == 64 ? (word & 0x3f3f3f3fu) : word;
-        }
+    for (int x = 0; x < NWORD; ++x) {
+      const uint32_t word = x == 0 ? w.x : w.y;
+      if (NIB) {
+        bword[2 * x] = word & 0x0f0f0f0fu;
+        bword[2 * x + 1] = (word >> 4) & 0x0f0f0f0fu;
+      } else {
+        // CAP 64: keep a stray bin value inside the histogram
+        bword[x] = CAP == 64 ? (word & 0x3f3f3f3fu) : word;
       }
+    }
 #pragma unroll
-      for (int bw = 0; bw < NBW; ++bw) {
-        constexpr int kPageShift = LPR == 8 ? 0 : 1;
-        const int page = bw >> kPageShift;
-        const int tv = LPR == 8 ? 0 : (bw & 1);
+    for (int bw = 0; bw < NBW; ++bw) {
+      constexpr int kPageShift = LPR == 8 ? 0 : 1;
+      const int page = bw >> kPageShift;
+      const int tv = LPR == 8 ? 0 : (bw & 1);
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-          const uint32_t a = __builtin_amdgcn_perm(bword[bw], tbl[tv], sel[k]);
-          __hip_atomic_fetch_add(
-              reinterpret_cast<unsigned long long*>(cells + a + page * (CAP * 256)), add,
-              __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-        }
+      for (int k = 0; k < 4; ++k) {
+        const uint32_t a = __builtin_amdgcn_perm(bword[bw], tbl[tv], sel[k]);
+        __hip_atomic_fetch_add(
+            reinterpret_cast<unsigned long long*>(cells + a + page * (CAP * 256)), add,
+            __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
       }
     }
   };
+  auto load_set = [&](uint2 (&w)[U], uint32_t rows, uint32_t e0, auto half_tag) {
+    constexpr int half = decltype(half_tag)::value;
+    static_assert(U == 2 || U == 4, "row groups per register set");
+    load_group(w[0], rows, e0, std::integral_constant<int, half * U + 0>{});
+    load_group(w[1], rows, e0, std::integral_constant<int, half * U + 1>{});
+    if constexpr (U == 4) {
+      load_group(w[2], rows, e0, std::integral_constant<int, half * U + 2>{});
+      load_group(w[3], rows, e0, std::integral_constant<int, half * U + 3>{});
+    }
+  };
+  auto add_set = [&](const uint2 (&w)[U], uint32_t lo, uint32_t hi, auto half_tag) {
+    constexpr int half = decltype(half_tag)::value;
+    add_group(w[0], lo, hi, std::integral_constant<int, half * U + 0>{});
+    add_group(w[1], lo, hi, std::integral_constant<int, half * U + 1>{});
+    if constexpr (U == 4) {
+      add_group(w[2], lo, hi, std::integral_constant<int, half * U + 2>{});
+      add_group(w[3], lo, hi, std::integral_constant<int, half * U + 3>{});
+    }
+  };
+  constexpr std::integral_constant<int, 0> kFirstHalf{};
+  constexpr std::integral_constant<int, 1> kSecondHalf{};
 
   const uint32_t n_epochs = (end - begin + kEpochRows - 1) / kEpochRows;
   int kg, kh;
@@ -356,7 +383,7 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
   read_scales(0, kg, kh);
 
   uint2 set_a[U], set_b[U];
-  load_set(set_a, row_cur, begin, 0);
+  load_set(set_a, row_cur, begin, kFirstHalf);
   for (uint32_t e = 0; e < n_epochs; ++e) {
     const uint32_t e0 = begin + e * (uint32_t)kEpochRows;
     // ---- this lane's row -> 64-bit addend 1 + gq * 2^10 + hq * 2^37 (two's complement)
@@ -375,10 +402,10 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
     const float g_nxt = load_stat(grad, row_nxt);
     const float h_nxt = load_stat(hess, row_nxt);
     // ---- accumulate: the loads of one register set fly while the other is added
-    load_set(set_b, row_cur, e0, 1);
-    add_set(set_a, lo, hi, 0);
-    load_set(set_a, row_nxt, e0 + kEpochRows, 0);
-    add_set(set_b, lo, hi, 1);
+    load_set(set_b, row_cur, e0, kSecondHalf);
+    add_set(set_a, lo, hi, kFirstHalf);
+    load_set(set_a, row_nxt, e0 + kEpochRows, kFirstHalf);
+    add_set(set_b, lo, hi, kSecondHalf);
 
     const int parity = (int)((e + 1) & 1u);
     {
@@ -392,8 +419,9 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
     const float inv_h = pow2f(-kh);
 #pragma unroll
     for (int m = 0; m < PP; ++m) {
-      const unsigned long long t = lds[tid + m * NT];
-      lds[tid + m * NT] = 0ull;
+      // read and clear in one LDS operation
+      const unsigned long long t = __hip_atomic_exchange(&lds[tid + m * NT], 0ull, __ATOMIC_RELAXED,
+                                                         __HIP_MEMORY_SCOPE_WORKGROUP);
       const uint32_t tlo = (uint32_t)t, thi = (uint32_t)(t >> 32);
       const uint32_t c = tlo & ((1u << kCountBits) - 1u);
       // bits 10..36: the gradient sum, sign-extended; the hessian sum sits above a
