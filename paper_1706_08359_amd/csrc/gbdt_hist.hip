@@ -55,7 +55,7 @@ pack_kernel(const uint8_t* __restrict__ src, int64_t n_rows, int32_t n_features,
       const uint32_t hi = f1 < n_features ? (row[f1] & 15u) : 0u;
       v = lo | (hi << 4);
     } else {
-      v = fb < n_features ? row[fb] : 0u;
+      v = fb < n_features ? (row[fb] & (uint32_t)(plan.cap - 1)) : 0u;
     }
     word |= v << (8 * i);
   }
@@ -145,7 +145,6 @@ struct TileShape {
   static constexpr int NW = NT / 64;
   static constexpr int PP = CELLS / NT;             // cells drained by one thread
   static constexpr int GPE = 64 / RPW;              // row groups per wavefront per epoch
-  static constexpr int U = GPE / 2;                 // row groups per register set (two sets)
   static_assert(NT == kEpochRows, "an epoch gives every lane one row of its own");
   static_assert(CELLS % NT == 0, "every thread drains the same number of cells");
   static_assert(4 * LPR <= 32 && (LPR == 8 || LPR == 4), "slot tables are bytes");
@@ -204,7 +203,7 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
                                            uint32_t* __restrict__ out) {
   using S = TileShape<CAP, W, NIB, NT>;
   constexpr int VEC = S::VEC, NWORD = S::NWORD, LPR = S::LPR, RPW = S::RPW, NBW = S::NBW;
-  constexpr int CELLS = S::CELLS, PP = S::PP, NW = S::NW, U = S::U;
+  constexpr int CELLS = S::CELLS, PP = S::PP, NW = S::NW;
   constexpr int NTBL = LPR == 8 ? 1 : 2;  // LPR 4: two byte-words share a page
 
   char* cells = reinterpret_cast<char*>(lds);
@@ -296,19 +295,20 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
     return (uint32_t)__builtin_amdgcn_update_dpp(lo8, (int)v, 0x158 + gi, 0xf, 0xc, false);
   };
 
-  // Register set: the bins of U row groups of one epoch.  rows: the row ids the lanes
-  // own in that epoch; e0: its first leaf position; HALF: which half of the groups.
-  auto load_group = [&](uint2& w, uint32_t rows, uint32_t e0, auto gi_tag) {
+  // Bins of one row group.  Without an index list the rows of an epoch are
+  // consecutive, so group gi sits gi * RPW * W bytes behind group 0 (an immediate
+  // offset of the load) and rows past the chunk end are simply read: they lie inside
+  // the matrix or its slack and their addend is zero.  With an index list the row id
+  // comes from the row's owner.
+  constexpr int GPE = S::GPE;
+  auto load_group = [&](uint2& w, uint32_t rows, uint32_t off0, auto gi_tag) {
     constexpr int gi = decltype(gi_tag)::value;
-    uint32_t r;
+    uint32_t off;  // 32-bit byte offsets ((n_rows + slack) * W < 2^32)
     if (INDEXED) {
-      r = from_owner(rows, gi_tag);
+      off = from_owner(rows, gi_tag) * (uint32_t)W + (uint32_t)(VEC * j);
     } else {
-      const uint32_t i = e0 + (uint32_t)wave * 64u + (uint32_t)(gi * RPW + rho);
-      r = i < end ? i : end - 1;
+      off = off0 + (uint32_t)(gi * RPW * W);
     }
-    // 32-bit byte offsets (n_rows * W < 2^32) keep the address arithmetic out of 64 bits
-    const uint32_t off = r * (uint32_t)W + (uint32_t)(VEC * j);
     if (NWORD == 2) {
       w = *reinterpret_cast<const uint2*>(tile + off);
     } else {
@@ -328,8 +328,7 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
         bword[2 * x] = word & 0x0f0f0f0fu;
         bword[2 * x + 1] = (word >> 4) & 0x0f0f0f0fu;
       } else {
-        // CAP 64: keep a stray bin value inside the histogram
-        bword[x] = CAP == 64 ? (word & 0x3f3f3f3fu) : word;
+        bword[x] = word;  // the pack kernel keeps every bin value below CAP
       }
     }
 #pragma unroll
@@ -346,27 +345,33 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
       }
     }
   };
-  auto load_set = [&](uint2 (&w)[U], uint32_t rows, uint32_t e0, auto half_tag) {
-    constexpr int half = decltype(half_tag)::value;
-    static_assert(U == 2 || U == 4, "row groups per register set");
-    load_group(w[0], rows, e0, std::integral_constant<int, half * U + 0>{});
-    load_group(w[1], rows, e0, std::integral_constant<int, half * U + 1>{});
-    if constexpr (U == 4) {
-      load_group(w[2], rows, e0, std::integral_constant<int, half * U + 2>{});
-      load_group(w[3], rows, e0, std::integral_constant<int, half * U + 3>{});
+  static_assert(GPE == 4 || GPE == 8, "row groups per epoch");
+  // the bins of all row groups of one epoch
+  auto load_epoch = [&](uint2 (&w)[GPE], uint32_t rows, uint32_t e0) {
+    const uint32_t off0 = (e0 + (uint32_t)wave * 64u + (uint32_t)rho) * (uint32_t)W + (uint32_t)(VEC * j);
+    load_group(w[0], rows, off0, std::integral_constant<int, 0>{});
+    load_group(w[1], rows, off0, std::integral_constant<int, 1>{});
+    load_group(w[2], rows, off0, std::integral_constant<int, 2>{});
+    load_group(w[3], rows, off0, std::integral_constant<int, 3>{});
+    if constexpr (GPE == 8) {
+      load_group(w[4], rows, off0, std::integral_constant<int, 4>{});
+      load_group(w[5], rows, off0, std::integral_constant<int, 5>{});
+      load_group(w[6], rows, off0, std::integral_constant<int, 6>{});
+      load_group(w[7], rows, off0, std::integral_constant<int, 7>{});
     }
   };
-  auto add_set = [&](const uint2 (&w)[U], uint32_t lo, uint32_t hi, auto half_tag) {
-    constexpr int half = decltype(half_tag)::value;
-    add_group(w[0], lo, hi, std::integral_constant<int, half * U + 0>{});
-    add_group(w[1], lo, hi, std::integral_constant<int, half * U + 1>{});
-    if constexpr (U == 4) {
-      add_group(w[2], lo, hi, std::integral_constant<int, half * U + 2>{});
-      add_group(w[3], lo, hi, std::integral_constant<int, half * U + 3>{});
+  auto add_epoch = [&](const uint2 (&w)[GPE], uint32_t lo, uint32_t hi) {
+    add_group(w[0], lo, hi, std::integral_constant<int, 0>{});
+    add_group(w[1], lo, hi, std::integral_constant<int, 1>{});
+    add_group(w[2], lo, hi, std::integral_constant<int, 2>{});
+    add_group(w[3], lo, hi, std::integral_constant<int, 3>{});
+    if constexpr (GPE == 8) {
+      add_group(w[4], lo, hi, std::integral_constant<int, 4>{});
+      add_group(w[5], lo, hi, std::integral_constant<int, 5>{});
+      add_group(w[6], lo, hi, std::integral_constant<int, 6>{});
+      add_group(w[7], lo, hi, std::integral_constant<int, 7>{});
     }
   };
-  constexpr std::integral_constant<int, 0> kFirstHalf{};
-  constexpr std::integral_constant<int, 1> kSecondHalf{};
 
   const uint32_t n_epochs = (end - begin + kEpochRows - 1) / kEpochRows;
   int kg, kh;
@@ -382,10 +387,16 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
   __syncthreads();  // also orders the LDS clearing before the first atomics
   read_scales(0, kg, kh);
 
-  uint2 set_a[U], set_b[U];
-  load_set(set_a, row_cur, begin, kFirstHalf);
-  for (uint32_t e = 0; e < n_epochs; ++e) {
+  // One epoch: `cur` holds its bins (requested one epoch earlier), `nxt` receives the
+  // next epoch's, requested before anything is added, so that a full epoch of loads is
+  // in flight across the barriers.
+  auto epoch = [&](uint32_t e, const uint2 (&cur)[GPE], uint2 (&nxt)[GPE]) {
     const uint32_t e0 = begin + e * (uint32_t)kEpochRows;
+    // ---- requests for later epochs
+    const uint32_t row_nn = load_row_id(e0 + 2 * kEpochRows);
+    const float g_nxt = load_stat(grad, row_nxt);
+    const float h_nxt = load_stat(hess, row_nxt);
+    load_epoch(nxt, row_nxt, e0 + kEpochRows);
     // ---- this lane's row -> 64-bit addend 1 + gq * 2^10 + hq * 2^37 (two's complement)
     uint32_t lo, hi;
     {
@@ -397,15 +408,7 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
       lo = ok ? lo : 0u;
       hi = ok ? hi : 0u;
     }
-    // ---- requests for later epochs
-    const uint32_t row_nn = load_row_id(e0 + 2 * kEpochRows);
-    const float g_nxt = load_stat(grad, row_nxt);
-    const float h_nxt = load_stat(hess, row_nxt);
-    // ---- accumulate: the loads of one register set fly while the other is added
-    load_set(set_b, row_cur, e0, kSecondHalf);
-    add_set(set_a, lo, hi, kFirstHalf);
-    load_set(set_a, row_nxt, e0 + kEpochRows, kFirstHalf);
-    add_set(set_b, lo, hi, kSecondHalf);
+    add_epoch(cur, lo, hi);
 
     const int parity = (int)((e + 1) & 1u);
     {
@@ -445,6 +448,13 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
     g_cur = g_nxt;
     h_cur = h_nxt;
     __syncthreads();  // cells are clear, and `red` of this parity is read, before reuse
+  };
+
+  uint2 set_a[GPE], set_b[GPE];
+  load_epoch(set_a, row_cur, begin);
+  for (uint32_t e = 0; e < n_epochs; e += 2) {  // n_epochs is uniform over the workgroup
+    epoch(e, set_a, set_b);
+    if (e + 1 < n_epochs) epoch(e + 1, set_b, set_a);
   }
 
   // partial block layout: [stat][cell] words
@@ -882,6 +892,10 @@ int device_cu_count() {
 
 constexpr size_t kLdsPerCu = 160 * 1024;
 constexpr int kMinRowsPerChunk = kEpochRows;
+// Bytes behind the last tile that the build kernel may read (and ignore): its last
+// epoch of a root leaf fetches whole row groups, up to one epoch of rows of the widest
+// tile past the end.
+constexpr size_t kPackSlackBytes = (size_t)kEpochRows * 64;
 constexpr int kBuildThreads = 512;  // threads per workgroup of every build kernel variant
 constexpr int kOversubscribe = 3;  // rounds of workgroups per resident slot
 
@@ -924,8 +938,7 @@ BuildGeom make_geom(int32_t n_features, int32_t n_bins, int64_t n_leaf, int cus,
     if (v > 0) oversub = v;
   }
   const int64_t resident = (int64_t)cus * wg_per_cu * oversub;
-  // remainder tile counted by its share of a main tile's work
-  const double tiles_equiv = p.n_main + (p.wr ? (double)p.wr / p.wm : 0.0);
+  const double tiles_equiv = p.n_main + (p.wr ? 1.0 : 0.0);
   int64_t chunks = (int64_t)((double)resident / (tiles_equiv > 0 ? tiles_equiv : 1.0));
   const int64_t max_chunks = (n_leaf + kMinRowsPerChunk - 1) / kMinRowsPerChunk;
   if (chunks > max_chunks) chunks = max_chunks;
@@ -938,7 +951,10 @@ BuildGeom make_geom(int32_t n_features, int32_t n_bins, int64_t n_leaf, int cus,
   g.chunks_rem = 0;
   g.rpc_rem = 0;
   if (p.wr) {
-    int64_t cr = p.n_main ? (chunks * p.wr + p.wm - 1) / p.wm : chunks;
+    // The narrow tile is cut into the same row chunks as the main tiles: a workgroup's
+    // time is dominated by per-epoch work that does not shrink with the tile width, so
+    // chunks sized by bytes would make these workgroups, which start last, the slowest.
+    int64_t cr = chunks;
     if (cr < 1) cr = 1;
     g.rpc_rem = round_up((n_leaf + cr - 1) / cr, kEpochRows);
     if (g.rpc_rem < kEpochRows) g.rpc_rem = kEpochRows;
@@ -952,7 +968,7 @@ BuildGeom make_geom(int32_t n_features, int32_t n_bins, int64_t n_leaf, int cus,
 
 // Kernel variants: bin capacity -> (main tile width, 4-bit, waves per SIMD the
 // register budget is set for).
-#define GBDT_VARIANT_16 16, 64, true, kBuildThreads, 8, double
+#define GBDT_VARIANT_16 16, 64, true, kBuildThreads, 6, double
 #define GBDT_VARIANT_64 64, 64, false, kBuildThreads, 6, float
 #define GBDT_VARIANT_256 256, 32, false, kBuildThreads, 4, float
 
@@ -1039,7 +1055,7 @@ extern "C" {
 size_t gbdt_bins_packed_bytes(int64_t n_rows, int32_t n_features, int32_t n_bins) {
   if (!valid_shape(n_rows, n_features, n_bins)) return 0;
   const TilePlan p = make_tile_plan(n_features, n_bins);
-  return (size_t)n_rows * (size_t)p.row_bytes;
+  return (size_t)n_rows * (size_t)p.row_bytes + kPackSlackBytes;
 }
 
 int gbdt_bins_pack(const uint8_t* bins_rowmajor, int64_t n_rows, int32_t n_features,
@@ -1106,8 +1122,8 @@ int gbdt_hist_build(const void* bin_matrix, int64_t n_rows, int32_t n_features, 
                 build_wg_per_cu(make_tile_plan(n_features, n_bins).cap, leaf_row_idx != nullptr));
   const TilePlan& p = g.plan;
   if (plan_n_tiles(p) > 65535) return GBDT_EUNSUPPORTED;
-  // byte offsets inside a tile are formed in 32 bits
-  if (n_rows * (int64_t)p.wm >= ((int64_t)1 << 32)) return GBDT_EUNSUPPORTED;
+  // byte offsets inside a tile (slack included) are formed in 32 bits
+  if ((n_rows + kEpochRows) * (int64_t)p.wm >= ((int64_t)1 << 32)) return GBDT_EUNSUPPORTED;
   void* ws = nullptr;
   int rc = get_workspace(g.partial_words * 4, &ws);
   if (rc != GBDT_OK) return rc;

@@ -83,7 +83,7 @@ def test_tile_plan_is_a_bijection_onto_slots(n_features, n_bins):
     per_byte = 2 if g["nib"] else 1
     assert g["feat_bytes"] == (n_features + per_byte - 1) // per_byte
     assert g["feat_bytes"] <= g["row_bytes"] < g["feat_bytes"] + g["wm"] // 2 + 16
-    assert B.gbdt_bins_packed_bytes(12345, n_features, n_bins) == 12345 * g["row_bytes"]
+    assert B.gbdt_bins_packed_bytes(12345, n_features, n_bins) == 12345 * g["row_bytes"] + 512 * 64
     seen = set()
     for f in range(n_features):
         t, s = B.gbdt_debug_locate(n_features, n_bins, f)
