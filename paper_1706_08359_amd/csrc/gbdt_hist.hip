@@ -346,30 +346,52 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
     }
   };
   static_assert(GPE == 4 || GPE == 8, "row groups per epoch");
-  // the bins of all row groups of one epoch
+  auto group_offset0 = [&](uint32_t e0) {
+    return (e0 + (uint32_t)wave * 64u + (uint32_t)rho) * (uint32_t)W + (uint32_t)(VEC * j);
+  };
+  // The bins of all row groups of one epoch, requested in group order.  (The scheduling
+  // barriers keep that order: the epoch loop waits for group gi with "at most 9 younger
+  // requests outstanding", which is only right when the first epoch's requests were
+  // issued in the order the loop re-issues them.)
   auto load_epoch = [&](uint2 (&w)[GPE], uint32_t rows, uint32_t e0) {
-    const uint32_t off0 = (e0 + (uint32_t)wave * 64u + (uint32_t)rho) * (uint32_t)W + (uint32_t)(VEC * j);
-    load_group(w[0], rows, off0, std::integral_constant<int, 0>{});
-    load_group(w[1], rows, off0, std::integral_constant<int, 1>{});
-    load_group(w[2], rows, off0, std::integral_constant<int, 2>{});
-    load_group(w[3], rows, off0, std::integral_constant<int, 3>{});
+    const uint32_t off0 = group_offset0(e0);
+    auto step = [&](auto gi_tag) {
+      constexpr int gi = decltype(gi_tag)::value;
+      load_group(w[gi], rows, off0, gi_tag);
+      __builtin_amdgcn_sched_barrier(0);
+    };
+    step(std::integral_constant<int, 0>{});
+    step(std::integral_constant<int, 1>{});
+    step(std::integral_constant<int, 2>{});
+    step(std::integral_constant<int, 3>{});
     if constexpr (GPE == 8) {
-      load_group(w[4], rows, off0, std::integral_constant<int, 4>{});
-      load_group(w[5], rows, off0, std::integral_constant<int, 5>{});
-      load_group(w[6], rows, off0, std::integral_constant<int, 6>{});
-      load_group(w[7], rows, off0, std::integral_constant<int, 7>{});
+      step(std::integral_constant<int, 4>{});
+      step(std::integral_constant<int, 5>{});
+      step(std::integral_constant<int, 6>{});
+      step(std::integral_constant<int, 7>{});
     }
   };
-  auto add_epoch = [&](const uint2 (&w)[GPE], uint32_t lo, uint32_t hi) {
-    add_group(w[0], lo, hi, std::integral_constant<int, 0>{});
-    add_group(w[1], lo, hi, std::integral_constant<int, 1>{});
-    add_group(w[2], lo, hi, std::integral_constant<int, 2>{});
-    add_group(w[3], lo, hi, std::integral_constant<int, 3>{});
+  // Adds the row groups of one epoch and, as soon as a group's registers are free,
+  // requests the same group of the next epoch into them: every request has a whole
+  // epoch to complete, requests are spread evenly over the epoch, and one register set
+  // serves both epochs.
+  auto add_and_reload = [&](uint2 (&w)[GPE], uint32_t lo, uint32_t hi, uint32_t rows_nxt,
+                            uint32_t e0_nxt) {
+    const uint32_t off0 = group_offset0(e0_nxt);
+    auto step = [&](auto gi_tag) {
+      constexpr int gi = decltype(gi_tag)::value;
+      add_group(w[gi], lo, hi, gi_tag);
+      load_group(w[gi], rows_nxt, off0, gi_tag);
+    };
+    step(std::integral_constant<int, 0>{});
+    step(std::integral_constant<int, 1>{});
+    step(std::integral_constant<int, 2>{});
+    step(std::integral_constant<int, 3>{});
     if constexpr (GPE == 8) {
-      add_group(w[4], lo, hi, std::integral_constant<int, 4>{});
-      add_group(w[5], lo, hi, std::integral_constant<int, 5>{});
-      add_group(w[6], lo, hi, std::integral_constant<int, 6>{});
-      add_group(w[7], lo, hi, std::integral_constant<int, 7>{});
+      step(std::integral_constant<int, 4>{});
+      step(std::integral_constant<int, 5>{});
+      step(std::integral_constant<int, 6>{});
+      step(std::integral_constant<int, 7>{});
     }
   };
 
@@ -387,16 +409,13 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
   __syncthreads();  // also orders the LDS clearing before the first atomics
   read_scales(0, kg, kh);
 
-  // One epoch: `cur` holds its bins (requested one epoch earlier), `nxt` receives the
-  // next epoch's, requested before anything is added, so that a full epoch of loads is
-  // in flight across the barriers.
-  auto epoch = [&](uint32_t e, const uint2 (&cur)[GPE], uint2 (&nxt)[GPE]) {
+  // One epoch.  `w` holds its bins, requested during the previous epoch.
+  auto epoch = [&](uint32_t e, uint2 (&w)[GPE]) {
     const uint32_t e0 = begin + e * (uint32_t)kEpochRows;
     // ---- requests for later epochs
     const uint32_t row_nn = load_row_id(e0 + 2 * kEpochRows);
     const float g_nxt = load_stat(grad, row_nxt);
     const float h_nxt = load_stat(hess, row_nxt);
-    load_epoch(nxt, row_nxt, e0 + kEpochRows);
     // ---- this lane's row -> 64-bit addend 1 + gq * 2^10 + hq * 2^37 (two's complement)
     uint32_t lo, hi;
     {
@@ -408,7 +427,7 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
       lo = ok ? lo : 0u;
       hi = ok ? hi : 0u;
     }
-    add_epoch(cur, lo, hi);
+    add_and_reload(w, lo, hi, row_nxt, e0 + kEpochRows);
 
     const int parity = (int)((e + 1) & 1u);
     {
@@ -450,12 +469,9 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
     __syncthreads();  // cells are clear, and `red` of this parity is read, before reuse
   };
 
-  uint2 set_a[GPE], set_b[GPE];
-  load_epoch(set_a, row_cur, begin);
-  for (uint32_t e = 0; e < n_epochs; e += 2) {  // n_epochs is uniform over the workgroup
-    epoch(e, set_a, set_b);
-    if (e + 1 < n_epochs) epoch(e + 1, set_b, set_a);
-  }
+  uint2 w[GPE];
+  load_epoch(w, row_cur, begin);
+  for (uint32_t e = 0; e < n_epochs; ++e) epoch(e, w);  // n_epochs is uniform over the workgroup
 
   // partial block layout: [stat][cell] words
 #pragma unroll
