@@ -184,9 +184,9 @@ int gbdt_profile_collect(double* build_kernel_ms_total, int64_t* n_launches);
  * Introspection of the host-side launch planning (no GPU needed; used by tests).
  * gbdt_debug_geometry fills out[0..15] with: bin capacity, 4-bit flag, main tile
  * width, number of main tiles, remainder tile width, packed bytes per row, feature
- * bytes per row, threads per workgroup, LDS bytes per workgroup, row chunks per
- * main tile, row chunks of the remainder tile, rows per main chunk, rows per
- * remainder chunk, total 4-byte words of partial histograms, 0, 0 -- as planned for
+ * bytes per row, threads per workgroup, LDS bytes per workgroup, workgroups per
+ * main tile, workgroups of the remainder tile, epochs (of 512 rows) per unit of work,
+ * units per tile, total 4-byte words of partial histograms, 0, 0 -- as planned for
  * a device with n_cus compute units (<= 0: 256).  n_out must be >= 16.
  * gbdt_debug_locate reports the tile and the local-memory slot of a feature.
  */

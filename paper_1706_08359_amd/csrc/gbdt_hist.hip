@@ -69,15 +69,16 @@ struct BuildArgs {
   const int32_t* idx;  // NULL: rows 0..n_leaf-1
   const float* grad;
   const float* hess;
-  uint32_t* partials;  // one [3][CAP][SLOTS] block of words per workgroup
+  uint32_t* partials;  // one [3][cells] block of words per workgroup
+  uint32_t* counters;  // per tile: the next unit of work to hand out
   int64_t n_rows;
   int64_t n_leaf;
   int32_t n_main;       // main tiles
   int32_t wr;           // remainder tile width, 0 if none
-  int32_t chunks_main;  // row chunks per main tile
-  int32_t chunks_rem;   // row chunks of the remainder tile
-  int64_t rows_per_chunk_main;
-  int64_t rows_per_chunk_rem;
+  int32_t wgs_main;     // workgroups per main tile
+  int32_t wgs_rem;      // workgroups of the remainder tile
+  int32_t unit_epochs;  // epochs per unit of work
+  int32_t n_units;      // units per tile
 };
 
 // A histogram cell is ONE 64-bit integer that carries, from the low bits up, the
@@ -198,8 +199,10 @@ template <int CAP, int W, bool NIB, int NT, typename ACC, bool INDEXED>
 __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
                                            const int32_t* __restrict__ idx,
                                            const float* __restrict__ grad,
-                                           const float* __restrict__ hess, uint32_t begin,
-                                           uint32_t end, unsigned long long* lds,
+                                           const float* __restrict__ hess, uint32_t end,
+                                           uint32_t first_unit, uint32_t n_units,
+                                           uint32_t unit_epochs, uint32_t* counter,
+                                           unsigned long long* lds,
                                            uint32_t* __restrict__ out) {
   using S = TileShape<CAP, W, NIB, NT>;
   constexpr int VEC = S::VEC, NWORD = S::NWORD, LPR = S::LPR, RPW = S::RPW, NBW = S::NBW;
@@ -208,6 +211,7 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
 
   char* cells = reinterpret_cast<char*>(lds);
   float* red = reinterpret_cast<float*>(lds + CELLS);  // [2 parities][2 stats][NW]
+  uint32_t* unit_box = reinterpret_cast<uint32_t*>(red + 4 * NW);     // the unit just handed out
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -346,8 +350,12 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
     }
   };
   static_assert(GPE == 4 || GPE == 8, "row groups per epoch");
+  // (an epoch past the leaf is read at the leaf's last epoch: in range, and ignored)
+  const uint32_t n_epochs_leaf = (end + kEpochRows - 1) / kEpochRows;
+  const uint32_t past = n_epochs_leaf * (uint32_t)kEpochRows;  // position of "no epoch"
   auto group_offset0 = [&](uint32_t e0) {
-    return (e0 + (uint32_t)wave * 64u + (uint32_t)rho) * (uint32_t)W + (uint32_t)(VEC * j);
+    const uint32_t e = e0 < past ? e0 : past - (uint32_t)kEpochRows;
+    return (e + (uint32_t)wave * 64u + (uint32_t)rho) * (uint32_t)W + (uint32_t)(VEC * j);
   };
   // The bins of all row groups of one epoch, requested in group order.  (The scheduling
   // barriers keep that order: the epoch loop waits for group gi with "at most 9 younger
@@ -370,6 +378,28 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
       step(std::integral_constant<int, 6>{});
       step(std::integral_constant<int, 7>{});
     }
+  };
+  // Moves the sums of cell m into this thread's accumulators and clears it.
+  auto drain_cell = [&](int m, float inv_g, float inv_h) {
+    // read and clear in one LDS operation
+    const unsigned long long t = __hip_atomic_exchange(&lds[tid + m * NT], 0ull, __ATOMIC_RELAXED,
+                                                       __HIP_MEMORY_SCOPE_WORKGROUP);
+    const uint32_t tlo = (uint32_t)t, thi = (uint32_t)(t >> 32);
+    const uint32_t c = tlo & ((1u << kCountBits) - 1u);
+    // bits 10..36: the gradient sum, sign-extended; the hessian sum sits above a
+    // borrow of one when the gradient sum is negative
+    const uint32_t mid = (thi << (32 - kCountBits)) | (tlo >> kCountBits);
+    const int32_t gs = (int32_t)(mid << (32 - kSumBits)) >> (32 - kSumBits);
+    const int32_t hs = ((int32_t)thi >> (kCountBits + kSumBits - 32)) + (int32_t)((mid >> (kSumBits - 1)) & 1u);
+    // integer * power of two + accumulator, rounded once
+    if (sizeof(ACC) == 8) {
+      acc_g[m] = (ACC)fma((double)gs, (double)inv_g, (double)acc_g[m]);
+      acc_h[m] = (ACC)fma((double)hs, (double)inv_h, (double)acc_h[m]);
+    } else {
+      acc_g[m] = (ACC)__fmaf_rn((float)gs, inv_g, (float)acc_g[m]);
+      acc_h[m] = (ACC)__fmaf_rn((float)hs, inv_h, (float)acc_h[m]);
+    }
+    acc_c[m] += c;
   };
   // Adds the row groups of one epoch and, as soon as a group's registers are free,
   // requests the same group of the next epoch into them: every request has a whole
@@ -395,83 +425,74 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
     }
   };
 
-  const uint32_t n_epochs = (end - begin + kEpochRows - 1) / kEpochRows;
-  int kg, kh;
-  // rows the lane owns in the current epoch and the next one; the current row's stats
-  uint32_t row_cur = load_row_id(begin);
-  uint32_t row_nxt = load_row_id(begin + kEpochRows);
-  float g_cur = load_stat(grad, row_cur);
-  float h_cur = load_stat(hess, row_cur);
-  {
-    const bool ok = own_valid(begin);
-    reduce_abs(ok ? fabsf(g_cur) : 0.0f, ok ? fabsf(h_cur) : 0.0f, 0);
-  }
-  __syncthreads();  // also orders the LDS clearing before the first atomics
-  read_scales(0, kg, kh);
+  // Work distribution.  The leaf's epochs are handed out in units of unit_epochs
+  // consecutive epochs.  A workgroup starts with unit first_unit; while it works on a
+  // unit, one lane takes the next one from the tile's counter (a global atomic).  Slow
+  // and fast workgroups (the CU issues the instructions of its oldest workgroup first)
+  // so end together, and one partial block per workgroup suffices.  Inside a unit the
+  // loads run an epoch ahead; a new unit starts its pipeline afresh.
+  for (uint32_t unit = first_unit; unit < n_units;) {  // uniform over the workgroup
+    const uint32_t begin = unit * unit_epochs * (uint32_t)kEpochRows;
+    const uint32_t stop = begin + unit_epochs * (uint32_t)kEpochRows;  // may pass the leaf end
+    uint32_t taken = 0;
+    if (tid == 0)
+      taken = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 
-  // One epoch.  `w` holds its bins, requested during the previous epoch.
-  auto epoch = [&](uint32_t e, uint2 (&w)[GPE]) {
-    const uint32_t e0 = begin + e * (uint32_t)kEpochRows;
-    // ---- requests for later epochs
-    const uint32_t row_nn = load_row_id(e0 + 2 * kEpochRows);
-    const float g_nxt = load_stat(grad, row_nxt);
-    const float h_nxt = load_stat(hess, row_nxt);
-    // ---- this lane's row -> 64-bit addend 1 + gq * 2^10 + hq * 2^37 (two's complement)
-    uint32_t lo, hi;
+    int kg, kh;
+    // rows the lane owns in the current epoch and the next one; the current row's stats
+    uint32_t row_cur = load_row_id(begin);
+    uint32_t row_nxt = load_row_id(begin + kEpochRows);
+    float g_cur = load_stat(grad, row_cur);
+    float h_cur = load_stat(hess, row_cur);
+    uint2 w[GPE];
+    load_epoch(w, row_cur, begin);
     {
-      const int32_t gq = __float2int_rn(g_cur * pow2f(kg));
-      const int32_t hq = __float2int_rn(h_cur * pow2f(kh));
-      lo = ((uint32_t)gq << kCountBits) + 1u;
-      hi = (uint32_t)(gq >> (32 - kCountBits)) + ((uint32_t)hq << (kCountBits + kSumBits - 32));
-      const bool ok = own_valid(e0);
-      lo = ok ? lo : 0u;
-      hi = ok ? hi : 0u;
+      const bool ok = own_valid(begin);
+      reduce_abs(ok ? fabsf(g_cur) : 0.0f, ok ? fabsf(h_cur) : 0.0f, 0);
     }
-    add_and_reload(w, lo, hi, row_nxt, e0 + kEpochRows);
+    __syncthreads();  // (the first one also orders the LDS clearing before the atomics)
+    read_scales(0, kg, kh);
 
-    const int parity = (int)((e + 1) & 1u);
-    {
-      const bool ok = own_valid(e0 + kEpochRows);
-      reduce_abs(ok ? fabsf(g_nxt) : 0.0f, ok ? fabsf(h_nxt) : 0.0f, parity);
-    }
-    __syncthreads();  // all atomics of the epoch have landed
-
-    // ---- drain: integer sums -> registers, clear the cells for the next epoch
-    const float inv_g = pow2f(-kg);
-    const float inv_h = pow2f(-kh);
-#pragma unroll
-    for (int m = 0; m < PP; ++m) {
-      // read and clear in one LDS operation
-      const unsigned long long t = __hip_atomic_exchange(&lds[tid + m * NT], 0ull, __ATOMIC_RELAXED,
-                                                         __HIP_MEMORY_SCOPE_WORKGROUP);
-      const uint32_t tlo = (uint32_t)t, thi = (uint32_t)(t >> 32);
-      const uint32_t c = tlo & ((1u << kCountBits) - 1u);
-      // bits 10..36: the gradient sum, sign-extended; the hessian sum sits above a
-      // borrow of one when the gradient sum is negative
-      const uint32_t mid = (thi << (32 - kCountBits)) | (tlo >> kCountBits);
-      const int32_t gs = (int32_t)(mid << (32 - kSumBits)) >> (32 - kSumBits);
-      const int32_t hs = ((int32_t)thi >> (kCountBits + kSumBits - 32)) + (int32_t)((mid >> (kSumBits - 1)) & 1u);
-      // integer * power of two + accumulator, rounded once
-      if (sizeof(ACC) == 8) {
-        acc_g[m] = (ACC)fma((double)gs, (double)inv_g, (double)acc_g[m]);
-        acc_h[m] = (ACC)fma((double)hs, (double)inv_h, (double)acc_h[m]);
-      } else {
-        acc_g[m] = (ACC)__fmaf_rn((float)gs, inv_g, (float)acc_g[m]);
-        acc_h[m] = (ACC)__fmaf_rn((float)hs, inv_h, (float)acc_h[m]);
+    uint32_t parity = 0;
+    for (uint32_t e0 = begin; e0 < stop && e0 < end; e0 += kEpochRows) {
+      // ---- requests for later epochs
+      const uint32_t row_nn = load_row_id(e0 + 2 * kEpochRows);
+      const float g_nxt = load_stat(grad, row_nxt);
+      const float h_nxt = load_stat(hess, row_nxt);
+      // ---- this lane's row -> 64-bit addend 1 + gq * 2^10 + hq * 2^37 (two's complement)
+      uint32_t lo, hi;
+      {
+        const int32_t gq = __float2int_rn(g_cur * pow2f(kg));
+        const int32_t hq = __float2int_rn(h_cur * pow2f(kh));
+        lo = ((uint32_t)gq << kCountBits) + 1u;
+        hi = (uint32_t)(gq >> (32 - kCountBits)) + ((uint32_t)hq << (kCountBits + kSumBits - 32));
+        const bool ok = own_valid(e0);
+        lo = ok ? lo : 0u;
+        hi = ok ? hi : 0u;
       }
-      acc_c[m] += c;
-    }
-    read_scales(parity, kg, kh);
-    row_cur = row_nxt;
-    row_nxt = row_nn;
-    g_cur = g_nxt;
-    h_cur = h_nxt;
-    __syncthreads();  // cells are clear, and `red` of this parity is read, before reuse
-  };
+      add_and_reload(w, lo, hi, row_nxt, e0 + kEpochRows);
 
-  uint2 w[GPE];
-  load_epoch(w, row_cur, begin);
-  for (uint32_t e = 0; e < n_epochs; ++e) epoch(e, w);  // n_epochs is uniform over the workgroup
+      parity ^= 1u;
+      {
+        const bool ok = own_valid(e0 + kEpochRows);
+        reduce_abs(ok ? fabsf(g_nxt) : 0.0f, ok ? fabsf(h_nxt) : 0.0f, (int)parity);
+      }
+      if (tid == 0) unit_box[0] = taken;  // (needed after the unit's last epoch only)
+      __syncthreads();  // all atomics of the epoch have landed
+
+      // ---- drain: integer sums -> registers, clear the cells for the next epoch
+      const float inv_g = pow2f(-kg), inv_h = pow2f(-kh);
+#pragma unroll
+      for (int m = 0; m < PP; ++m) drain_cell(m, inv_g, inv_h);
+      read_scales((int)parity, kg, kh);
+      unit = __builtin_amdgcn_readfirstlane(unit_box[0]);
+      row_cur = row_nxt;
+      row_nxt = row_nn;
+      g_cur = g_nxt;
+      h_cur = h_nxt;
+      __syncthreads();  // cells are clear, `red` and the unit box are read, before reuse
+    }
+  }
 
   // partial block layout: [stat][cell] words
 #pragma unroll
@@ -488,43 +509,54 @@ __device__ __host__ constexpr int block_words() {
   return 3 * TileShape<CAP, W, NIB, NT>::CELLS;
 }
 
-// Work is split by feature tiles and by row chunks (Sec. 4, "Parallel By Features
-// and Data"): block -> (tile, chunk).  Consecutive blocks take different tiles of
-// the same chunk, so the chunk's row ids / gradients / hessians are fetched from
-// HBM once and served to the other tiles from cache.
+// Work is split by feature tiles and by samples (Sec. 4, "Parallel By Features and
+// Data"): every tile has a fixed set of workgroups that share out its epochs.  Block
+// -> (tile, workgroup of the tile); consecutive blocks take different tiles, so the
+// row ids / gradients / hessians of an epoch are fetched from HBM once and served to
+// the other tiles from cache.
 template <int CAP, int WM, bool NIB, int NT, int WPE, typename ACC, bool INDEXED>
 __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(WPE, WPE)))
 hist_build_kernel(BuildArgs a) {
-  // one histogram of the main tile width (8 bytes per cell) + the reduction scratch
+  // one histogram of the main tile width (8 bytes per cell), the reduction scratch and
+  // the unit box
   constexpr int kCells = TileShape<CAP, WM, NIB, NT>::CELLS;
-  __shared__ __align__(16) unsigned long long lds[kCells + (4 * (NT / 64) * 4 + 7) / 8];
-  const int32_t main_blocks = a.n_main * a.chunks_main;
+  __shared__ __align__(16) unsigned long long lds[kCells + (4 * (NT / 64) * 4 + 7) / 8 + 1];
+  const int32_t main_blocks = a.n_main * a.wgs_main;
   const int32_t b = blockIdx.x;
   const uint32_t n_leaf = (uint32_t)a.n_leaf;
   if (b < main_blocks) {
     const int32_t t = b % a.n_main;
     const int32_t c = b / a.n_main;
-    const uint32_t begin = (uint32_t)c * (uint32_t)a.rows_per_chunk_main;
-    uint32_t end = begin + (uint32_t)a.rows_per_chunk_main;
-    if (end > n_leaf) end = n_leaf;
     const uint8_t* tile = a.packed + a.n_rows * ((int64_t)t * WM);
-    uint32_t* out = a.partials + ((size_t)t * a.chunks_main + c) * (size_t)block_words<CAP, WM, NIB, NT>();
-    build_tile<CAP, WM, NIB, NT, ACC, INDEXED>(tile, a.idx, a.grad, a.hess, begin, end, lds, out);
+    uint32_t* out = a.partials + ((size_t)t * a.wgs_main + c) * (size_t)block_words<CAP, WM, NIB, NT>();
+    build_tile<CAP, WM, NIB, NT, ACC, INDEXED>(tile, a.idx, a.grad, a.hess, n_leaf, (uint32_t)c,
+                                                   (uint32_t)a.n_units, (uint32_t)a.unit_epochs,
+                                                   a.counters + t, lds, out);
   } else {
     const int32_t c = b - main_blocks;
-    const uint32_t begin = (uint32_t)c * (uint32_t)a.rows_per_chunk_rem;
-    uint32_t end = begin + (uint32_t)a.rows_per_chunk_rem;
-    if (end > n_leaf) end = n_leaf;
     const uint8_t* tile = a.packed + a.n_rows * ((int64_t)a.n_main * WM);
     uint32_t* rem_base = a.partials + (size_t)main_blocks * (size_t)block_words<CAP, WM, NIB, NT>();
     if (a.wr == 16) {
-      build_tile<CAP, 16, NIB, NT, ACC, INDEXED>(tile, a.idx, a.grad, a.hess, begin, end, lds,
-                                            rem_base + (size_t)c * (size_t)block_words<CAP, 16, NIB, NT>());
+      build_tile<CAP, 16, NIB, NT, ACC, INDEXED>(
+          tile, a.idx, a.grad, a.hess, n_leaf, (uint32_t)c, (uint32_t)a.n_units,
+          (uint32_t)a.unit_epochs, a.counters + a.n_main, lds,
+          rem_base + (size_t)c * (size_t)block_words<CAP, 16, NIB, NT>());
     } else {
-      build_tile<CAP, 32, NIB, NT, ACC, INDEXED>(tile, a.idx, a.grad, a.hess, begin, end, lds,
-                                            rem_base + (size_t)c * (size_t)block_words<CAP, 32, NIB, NT>());
+      build_tile<CAP, 32, NIB, NT, ACC, INDEXED>(
+          tile, a.idx, a.grad, a.hess, n_leaf, (uint32_t)c, (uint32_t)a.n_units,
+          (uint32_t)a.unit_epochs, a.counters + a.n_main, lds,
+          rem_base + (size_t)c * (size_t)block_words<CAP, 32, NIB, NT>());
     }
   }
+}
+
+// Sets every tile's unit counter to the number of units its workgroups start with.
+// (A fill kernel, not a memset node, so the call can be captured into a graph.)
+__global__ void __launch_bounds__(256)
+counters_init_kernel(uint32_t* counters, int32_t n_main, int32_t wgs_main, int32_t wgs_rem,
+                     int32_t n_tiles) {
+  const int32_t t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t < n_tiles) counters[t] = (uint32_t)(t < n_main ? wgs_main : wgs_rem);
 }
 
 // ------------------------------------------------------------------ merge kernel
@@ -913,24 +945,24 @@ constexpr int kMinRowsPerChunk = kEpochRows;
 // tile past the end.
 constexpr size_t kPackSlackBytes = (size_t)kEpochRows * 64;
 constexpr int kBuildThreads = 512;  // threads per workgroup of every build kernel variant
-constexpr int kOversubscribe = 3;  // rounds of workgroups per resident slot
 
 struct BuildGeom {
   TilePlan plan;
   int nt;               // threads per workgroup
-  size_t lds_bytes;     // dynamic LDS per workgroup
-  int chunks_main, chunks_rem;
-  int64_t rpc_main, rpc_rem;
+  size_t lds_bytes;     // LDS per workgroup
+  int wgs_main, wgs_rem;  // workgroups per main tile / of the remainder tile
+  int unit_epochs;      // epochs per unit of work
+  int n_units;          // units per tile
   size_t partial_words;  // total words of all partial blocks
+  size_t counter_words;  // one unit counter per tile
 };
 
-int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+constexpr int kUnitEpochs = 8;  // epochs per unit when units are handed out dynamically
 
-// Chooses how many row chunks each tile is cut into so that the grid about fills
-// the machine exactly once: one workgroup per resident slot, so that no second,
-// partly empty round of workgroups is needed.  wg_per_cu: resident workgroups per CU
-// of the kernel variant as reported by the runtime (<= 0: estimate from the LDS
-// footprint alone).
+// Chooses the grid: as many workgroups per tile as fit the machine at once (they stay
+// until their tile's units are used up), and the unit size.  wg_per_cu: resident
+// workgroups per CU of the kernel variant as reported by the runtime (<= 0: estimate
+// from the LDS footprint alone).
 BuildGeom make_geom(int32_t n_features, int32_t n_bins, int64_t n_leaf, int cus,
                     int wg_per_cu_hint) {
   BuildGeom g;
@@ -938,7 +970,8 @@ BuildGeom make_geom(int32_t n_features, int32_t n_bins, int64_t n_leaf, int cus,
   const TilePlan& p = g.plan;
   g.nt = kBuildThreads;
   const size_t main_block = (size_t)3 * plan_cells(p, p.wm);
-  g.lds_bytes = (size_t)plan_cells(p, p.wm) * 8 + 4 * (g.nt / 64) * sizeof(float);
+  g.lds_bytes = (size_t)plan_cells(p, p.wm) * 8 +
+                4 * (g.nt / 64) * sizeof(float) + 8;
   int wg_per_cu = wg_per_cu_hint;
   if (wg_per_cu <= 0) {
     wg_per_cu = (int)(kLdsPerCu / g.lds_bytes);
@@ -946,46 +979,42 @@ BuildGeom make_geom(int32_t n_features, int32_t n_bins, int64_t n_leaf, int cus,
     if (wg_per_cu > by_threads) wg_per_cu = by_threads;
   }
   if (wg_per_cu < 1) wg_per_cu = 1;
-  // Workgroups of a CU that reach their barriers / epoch boundaries together leave
-  // its LDS idle; several rounds of smaller workgroups keep them out of phase.
-  int oversub = kOversubscribe;
-  if (const char* e = getenv("GBDT_HIST_OVERSUB")) {  // tuning experiments only
-    const int v = atoi(e);
-    if (v > 0) oversub = v;
+  const int64_t resident = (int64_t)cus * wg_per_cu;
+  const int n_tiles = plan_n_tiles(p);
+  const int64_t n_epochs = (n_leaf + kEpochRows - 1) / kEpochRows;
+  int64_t wgs = resident / n_tiles;  // per tile
+  if (wgs < 1) wgs = 1;
+  if (wgs * kUnitEpochs <= n_epochs) {
+    // enough work: units of kUnitEpochs handed out by the tile's counter
+    g.unit_epochs = kUnitEpochs;
+  } else {
+    // little work: one unit per workgroup, as short as it takes to use `wgs` of them
+    g.unit_epochs = (int)((n_epochs + wgs - 1) / wgs);
+    if (g.unit_epochs < 1) g.unit_epochs = 1;
   }
-  const int64_t resident = (int64_t)cus * wg_per_cu * oversub;
-  const double tiles_equiv = p.n_main + (p.wr ? 1.0 : 0.0);
-  int64_t chunks = (int64_t)((double)resident / (tiles_equiv > 0 ? tiles_equiv : 1.0));
-  const int64_t max_chunks = (n_leaf + kMinRowsPerChunk - 1) / kMinRowsPerChunk;
-  if (chunks > max_chunks) chunks = max_chunks;
-  if (chunks < 1) chunks = 1;
-  g.chunks_main = p.n_main ? (int)chunks : 0;
-  g.rpc_main = p.n_main ? round_up((n_leaf + chunks - 1) / chunks, kEpochRows) : 0;
-  if (g.rpc_main < kEpochRows) g.rpc_main = kEpochRows;
-  if (p.n_main) g.chunks_main = (int)((n_leaf + g.rpc_main - 1) / g.rpc_main);
-  if (p.n_main && g.chunks_main < 1) g.chunks_main = 1;
-  g.chunks_rem = 0;
-  g.rpc_rem = 0;
+  g.n_units = (int)((n_epochs + g.unit_epochs - 1) / g.unit_epochs);
+  if (g.n_units < 1) g.n_units = 1;
+  if (wgs > g.n_units) wgs = g.n_units;
+  g.wgs_main = p.n_main ? (int)wgs : 0;
+  // (A narrow tile's epochs are cheaper, but not by much: the per-epoch overhead does
+  // not shrink with the tile.  It gets as many workgroups as a main tile.)
+  g.wgs_rem = 0;
   if (p.wr) {
-    // The narrow tile is cut into the same row chunks as the main tiles: a workgroup's
-    // time is dominated by per-epoch work that does not shrink with the tile width, so
-    // chunks sized by bytes would make these workgroups, which start last, the slowest.
-    int64_t cr = chunks;
-    if (cr < 1) cr = 1;
-    g.rpc_rem = round_up((n_leaf + cr - 1) / cr, kEpochRows);
-    if (g.rpc_rem < kEpochRows) g.rpc_rem = kEpochRows;
-    g.chunks_rem = (int)((n_leaf + g.rpc_rem - 1) / g.rpc_rem);
-    if (g.chunks_rem < 1) g.chunks_rem = 1;
+    int64_t wr_wgs = wgs;
+    if (wr_wgs < 1) wr_wgs = 1;
+    if (wr_wgs > g.n_units) wr_wgs = g.n_units;
+    g.wgs_rem = (int)wr_wgs;
   }
-  g.partial_words = (size_t)p.n_main * g.chunks_main * main_block +
-                    (size_t)g.chunks_rem * 3 * (p.wr ? plan_cells(p, p.wr) : 0);
+  g.partial_words = (size_t)p.n_main * g.wgs_main * main_block +
+                    (size_t)g.wgs_rem * 3 * (p.wr ? plan_cells(p, p.wr) : 0);
+  g.counter_words = (size_t)n_tiles;
   return g;
 }
 
 // Kernel variants: bin capacity -> (main tile width, 4-bit, waves per SIMD the
 // register budget is set for).
-#define GBDT_VARIANT_16 16, 64, true, kBuildThreads, 6, double
-#define GBDT_VARIANT_64 64, 64, false, kBuildThreads, 6, float
+#define GBDT_VARIANT_16 16, 64, true, kBuildThreads, 8, double
+#define GBDT_VARIANT_64 64, 64, false, kBuildThreads, 8, float
 #define GBDT_VARIANT_256 256, 32, false, kBuildThreads, 4, float
 
 template <int CAP, int WM, bool NIB, int NT, int WPE, typename ACC, bool INDEXED>
@@ -1099,7 +1128,8 @@ size_t gbdt_workspace_bytes(int64_t n_rows, int32_t n_features, int32_t n_bins) 
   const int cap = make_tile_plan(n_features, n_bins).cap;
   const BuildGeom g0 = make_geom(n_features, n_bins, n_rows, device_cu_count(), build_wg_per_cu(cap, false));
   const BuildGeom g1 = make_geom(n_features, n_bins, n_rows, device_cu_count(), build_wg_per_cu(cap, true));
-  size_t b = (g0.partial_words > g1.partial_words ? g0.partial_words : g1.partial_words) * 4;
+  size_t b = (g0.partial_words > g1.partial_words ? g0.partial_words : g1.partial_words) * 4 +
+             g0.counter_words * 4;
   int sg = 0, sn = 0;
   split_grouping(n_features, n_bins, &sg, &sn);
   const size_t cand = (size_t)sn * sizeof(SplitCand);
@@ -1141,7 +1171,7 @@ int gbdt_hist_build(const void* bin_matrix, int64_t n_rows, int32_t n_features, 
   // byte offsets inside a tile (slack included) are formed in 32 bits
   if ((n_rows + kEpochRows) * (int64_t)p.wm >= ((int64_t)1 << 32)) return GBDT_EUNSUPPORTED;
   void* ws = nullptr;
-  int rc = get_workspace(g.partial_words * 4, &ws);
+  int rc = get_workspace((g.partial_words + g.counter_words) * 4, &ws);
   if (rc != GBDT_OK) return rc;
 
   BuildArgs a;
@@ -1150,15 +1180,20 @@ int gbdt_hist_build(const void* bin_matrix, int64_t n_rows, int32_t n_features, 
   a.grad = grad;
   a.hess = hess;
   a.partials = (uint32_t*)ws;
+  a.counters = (uint32_t*)ws + g.partial_words;
   a.n_rows = n_rows;
   a.n_leaf = n_leaf_rows;
   a.n_main = p.n_main;
   a.wr = p.wr;
-  a.chunks_main = g.chunks_main;
-  a.chunks_rem = g.chunks_rem;
-  a.rows_per_chunk_main = g.rpc_main;
-  a.rows_per_chunk_rem = g.rpc_rem;
-  const int blocks = p.n_main * g.chunks_main + g.chunks_rem;
+  a.wgs_main = g.wgs_main;
+  a.wgs_rem = g.wgs_rem;
+  a.unit_epochs = g.unit_epochs;
+  a.n_units = g.n_units;
+  const int blocks = p.n_main * g.wgs_main + g.wgs_rem;
+  const int n_tiles = plan_n_tiles(p);
+  hipLaunchKernelGGL(counters_init_kernel, dim3((n_tiles + 255) / 256), dim3(256), 0, s, a.counters,
+                     p.n_main, g.wgs_main, g.wgs_rem, n_tiles);
+  HIP_TRY(hipGetLastError());
 
   if (p.cap == 16) {
     rc = launch_build<GBDT_VARIANT_16>(a, blocks, s);
@@ -1175,8 +1210,8 @@ int gbdt_hist_build(const void* bin_matrix, int64_t n_rows, int32_t n_features, 
   m.plan = p;
   m.n_features = n_features;
   m.n_bins = n_bins;
-  m.chunks_main = g.chunks_main;
-  m.chunks_rem = g.chunks_rem;
+  m.chunks_main = g.wgs_main;
+  m.chunks_rem = g.wgs_rem;
   const int max_slots = plan_slots(p, p.wm);
   const int mx = (n_bins * max_slots + kMergeCells - 1) / kMergeCells;
   hipLaunchKernelGGL(hist_merge_kernel, dim3(mx, plan_n_tiles(p)), dim3(kMergeCells * kMergeLanes),
@@ -1226,8 +1261,8 @@ int gbdt_debug_geometry(int32_t n_features, int32_t n_bins, int64_t n_leaf_rows,
   const TilePlan& p = g.plan;
   const int64_t v[16] = {p.cap,         p.nib,          p.wm,          p.n_main,
                          p.wr,          p.row_bytes,    p.feat_bytes,  g.nt,
-                         (int64_t)g.lds_bytes, g.chunks_main, g.chunks_rem, g.rpc_main,
-                         g.rpc_rem,     (int64_t)g.partial_words, 0, 0};
+                         (int64_t)g.lds_bytes, g.wgs_main, g.wgs_rem, g.unit_epochs,
+                         g.n_units,     (int64_t)g.partial_words, 0, 0};
   for (int i = 0; i < 16; ++i) out[i] = v[i];
   return GBDT_OK;
 }

@@ -100,19 +100,21 @@ def test_tile_plan_is_a_bijection_onto_slots(n_features, n_bins):
 
 @pytest.mark.parametrize("n_features,n_bins", [(28, 64), (2000, 63), (28, 255), (137, 255), (700, 16), (5, 2)])
 @pytest.mark.parametrize("n_leaf", [1, 63, 64, 65, 511, 512, 513, 4000, 100_003, 10_500_000])
-def test_row_chunks_cover_the_leaf_exactly(n_features, n_bins, n_leaf):
+def test_units_cover_the_leaf_exactly(n_features, n_bins, n_leaf):
     g = B.gbdt_debug_geometry(n_features, n_bins, n_leaf)
     per_byte = 2 if g["nib"] else 1
+    n_epochs = (n_leaf + 511) // 512
+    assert g["unit_epochs"] >= 1 and g["n_units"] >= 1
+    assert g["n_units"] * g["unit_epochs"] >= n_epochs            # every epoch belongs to a unit
+    assert (g["n_units"] - 1) * g["unit_epochs"] < n_epochs       # no unit starts past the end
     words = 0
-    for chunks, rpc, w, tiles in ((g["chunks_main"], g["rows_per_chunk_main"], g["wm"], g["n_main"]),
-                                  (g["chunks_rem"], g["rows_per_chunk_rem"], g["wr"], 1 if g["wr"] else 0)):
+    for wgs, w, tiles in ((g["wgs_main"], g["wm"], g["n_main"]), (g["wgs_rem"], g["wr"], 1 if g["wr"] else 0)):
         if tiles == 0:
             continue
-        assert chunks >= 1 and rpc >= 1
-        assert chunks * rpc >= n_leaf            # every row belongs to a chunk
-        assert (chunks - 1) * rpc < n_leaf       # no chunk starts past the end
+        assert 1 <= wgs <= g["n_units"]                           # no workgroup without a first unit
         pages = (w * per_byte + 31) // 32
-        words += tiles * chunks * 3 * g["cap"] * 32 * pages
+        words += tiles * wgs * 3 * g["cap"] * 32 * pages
     assert words == g["partial_words"]
-    assert B.gbdt_workspace_bytes(n_leaf, n_features, n_bins) >= 4 * g["partial_words"]
-    assert (g["n_main"] * g["chunks_main"] + g["chunks_rem"]) < 2 ** 31
+    n_tiles = g["n_main"] + (1 if g["wr"] else 0)
+    assert B.gbdt_workspace_bytes(n_leaf, n_features, n_bins) >= 4 * (g["partial_words"] + n_tiles)
+    assert (g["n_main"] * g["wgs_main"] + g["wgs_rem"]) < 2 ** 31
