@@ -52,6 +52,19 @@ def algorithmic_bytes(n_leaf, n_features, n_bins, indexed):
     return n_leaf * n_features * bpv + n_leaf * (12 if indexed else 8) + n_features * n_bins * 12
 
 
+def measured_traffic(workload: str):
+    """HBM bytes per build-kernel launch from the committed counter summary of this
+    workload (FETCH_SIZE + WRITE_SIZE of rocprofv3 --pmc runs, scaled by a copy kernel of
+    known size), or None when no summary is committed."""
+    import re
+    path = os.path.join(ROOT, "profiles", f"hist_build_{workload}_hbm_traffic.md")
+    try:
+        m = re.search(r"TRAFFIC_BYTES_PER_LAUNCH\s*=\s*([0-9.eE+]+)", open(path).read())
+    except OSError:
+        return None
+    return float(m.group(1)) if m else None
+
+
 def cpu_baseline(w, budget_values=1.2e9):
     """Time the CPU oracle (as it stands) on the same leaf: build + subtract + best split."""
     import numpy as np
@@ -152,7 +165,7 @@ def main():
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
-            "traffic": None,
+            "traffic": measured_traffic(w.name),
             "kernel_ms": kernel_ms,
             "algorithmic_bytes": alg,
         },

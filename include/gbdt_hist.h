@@ -181,6 +181,13 @@ int gbdt_profile_enable(int enable);
 int gbdt_profile_collect(double* build_kernel_ms_total, int64_t* n_launches);
 
 /*
+ * A plain copy kernel of known HBM traffic (bytes read + bytes written), used to scale
+ * the memory counters of a profiler run.  src, dst: DEVICE, 16-byte aligned, bytes a
+ * multiple of 16, not overlapping.
+ */
+int gbdt_calibration_copy(const void* src, void* dst, size_t bytes, void* stream);
+
+/*
  * Introspection of the host-side launch planning (no GPU needed; used by tests).
  * gbdt_debug_geometry fills out[0..15] with: bin capacity, 4-bit flag, main tile
  * width, number of main tiles, remainder tile width, packed bytes per row, feature

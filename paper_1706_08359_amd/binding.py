@@ -21,6 +21,7 @@ EXPORTS = [
     "gbdt_best_split", "gbdt_workspace_bytes", "gbdt_set_workspace", "gbdt_strerror",
     "gbdt_last_hip_error", "gbdt_debug_geometry", "gbdt_debug_locate",
     "gbdt_profile_enable", "gbdt_profile_collect", "gbdt_debug_occupancy",
+    "gbdt_calibration_copy",
 ]
 
 # numpy views of the two C structs
@@ -77,6 +78,8 @@ def load():
     lib.gbdt_profile_enable.argtypes = [c.c_int]
     lib.gbdt_profile_collect.restype = c.c_int
     lib.gbdt_profile_collect.argtypes = [c.POINTER(c.c_double), c.POINTER(c.c_int64)]
+    lib.gbdt_calibration_copy.restype = c.c_int
+    lib.gbdt_calibration_copy.argtypes = [c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p]
     _lib = lib
     return lib
 
@@ -211,6 +214,14 @@ def gbdt_debug_locate(n_features: int, n_bins: int, feature: int):
     _check(load().gbdt_debug_locate(n_features, n_bins, feature, ctypes.byref(t), ctypes.byref(s)),
            "gbdt_debug_locate")
     return t.value, s.value
+
+
+def gbdt_calibration_copy(src: torch.Tensor, dst: torch.Tensor, stream=None) -> None:
+    """Plain copy kernel over two uint8 CUDA tensors of equal size (a multiple of 16 bytes)."""
+    if src.numel() != dst.numel():
+        raise GbdtError("src/dst size mismatch")
+    _check(load().gbdt_calibration_copy(_dev(src, torch.uint8, "src"), _dev(dst, torch.uint8, "dst"),
+                                        src.numel(), _stream(stream)), "gbdt_calibration_copy")
 
 
 def gbdt_profile_enable(enable: bool) -> None:

@@ -470,7 +470,10 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
         lo = ok ? lo : 0u;
         hi = ok ? hi : 0u;
       }
-      add_and_reload(w, lo, hi, row_nxt, e0 + kEpochRows);
+      // (after the unit's last epoch nothing new is needed: re-request the same rows,
+      // which come from cache, instead of an epoch of another workgroup's unit)
+      const bool more = e0 + kEpochRows < stop;
+      add_and_reload(w, lo, hi, more ? row_nxt : row_cur, more ? e0 + kEpochRows : e0);
 
       parity ^= 1u;
       {
@@ -855,6 +858,16 @@ split_argmax_kernel(const SplitCand* __restrict__ cand, int32_t n_cand,
     }
     *out = r;
   }
+}
+
+// ------------------------------------------------------- calibration copy kernel
+
+// Plain copy of n 16-byte words: a kernel of known HBM traffic (n * 16 bytes read, n *
+// 16 bytes written) against which the memory counters of a profiler run are scaled.
+__global__ void __launch_bounds__(256)
+calibration_copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = src[i];
 }
 
 // ------------------------------------------------------------------- host state
@@ -1281,6 +1294,15 @@ int gbdt_debug_locate(int32_t n_features, int32_t n_bins, int32_t feature, int32
   const FeatureSlot fs = plan_locate(p, feature);
   *tile_out = fs.tile;
   *slot_out = fs.slot;
+  return GBDT_OK;
+}
+
+int gbdt_calibration_copy(const void* src, void* dst, size_t bytes, void* stream) {
+  if (!src || !dst || bytes == 0 || (bytes & 15u) != 0) return GBDT_EINVAL;
+  if ((((uintptr_t)src) | ((uintptr_t)dst)) & 15u) return GBDT_EINVAL;
+  hipLaunchKernelGGL(calibration_copy_kernel, dim3(device_cu_count() * 8), dim3(256), 0,
+                     (hipStream_t)stream, (const uint4*)src, (uint4*)dst, bytes / 16);
+  HIP_TRY(hipGetLastError());
   return GBDT_OK;
 }
 

@@ -1,0 +1,47 @@
+"""Driver for profiler runs (rocprofv3 --kernel-trace / --pmc): packs one of the
+benchmark workloads, launches its root-leaf histogram build a few times through the C
+ABI and, with --copy-bytes, one plain copy kernel of that many bytes whose memory
+counters calibrate the build kernel's.
+
+    python -m paper_1706_08359_amd.prof_driver dense_wide --launches 3 --copy-bytes 800000000
+"""
+from __future__ import annotations
+
+import argparse
+import os
+import sys
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("workload", nargs="?", default="dense_wide")
+    ap.add_argument("--launches", type=int, default=3)
+    ap.add_argument("--copy-bytes", type=int, default=0)
+    args = ap.parse_args()
+
+    import torch
+    import bench
+    from paper_1706_08359_amd import binding as B
+
+    dev = torch.device("cuda:0")
+    w = bench.make_workload(args.workload, dev)
+    packed = B.gbdt_bins_pack(w.bins, w.n_bins)
+    hist = None
+    for _ in range(args.launches):
+        hist = B.gbdt_hist_build(packed, w.n_rows, w.n_features, w.n_bins, None, w.n_rows,
+                                 w.grad, w.hess, hist_out=hist)
+    if args.copy_bytes:
+        n = args.copy_bytes // 16 * 16
+        src = torch.zeros(n, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        B.gbdt_calibration_copy(src, dst)
+    torch.cuda.synchronize()
+    print("prof_driver done:", args.workload, args.launches, "launches", flush=True)
+
+
+if __name__ == "__main__":
+    main()
