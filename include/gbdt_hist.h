@@ -69,7 +69,9 @@ typedef struct {
  * (App. C.4: n_bins <= 16 stores two 4-bit values per byte, otherwise one byte
  * per value; Sec. 4 "Data Structure": features are bundled so that one thread
  * loads a 4-byte group of one sample).  Rows are kept contiguous inside
- * feature tiles of 16, 32 or 64 bytes.  Returns 0 on invalid arguments.
+ * feature tiles of 16, 32 or 64 bytes; 32 KiB of slack follow the last tile (the
+ * build kernel may read, and ignore, whole row groups past the last row).
+ * Returns 0 on invalid arguments.
  */
 size_t gbdt_bins_packed_bytes(int64_t n_rows, int32_t n_features, int32_t n_bins);
 
@@ -78,8 +80,10 @@ size_t gbdt_bins_packed_bytes(int64_t n_rows, int32_t n_features, int32_t n_bins
  * once before training (App. A.5: feature data is copied once and then stays
  * unchanged).
  *   bins_rowmajor  DEVICE, uint8 [n_rows][n_features], every value < n_bins
- *   packed_out     DEVICE, gbdt_bins_packed_bytes(...) bytes, 16-byte aligned,
- *                  fully overwritten (padding bytes are written as 0)
+ *   packed_out     DEVICE, gbdt_bins_packed_bytes(...) bytes, 16-byte aligned;
+ *                  the tiles are fully overwritten (padding bytes are written as 0,
+ *                  bin values are reduced modulo the kernel's bin capacity 16 / 64 /
+ *                  256), the slack is left as it is
  */
 int gbdt_bins_pack(const uint8_t* bins_rowmajor, int64_t n_rows, int32_t n_features,
                    int32_t n_bins, void* packed_out, void* stream);
@@ -101,20 +105,23 @@ int gbdt_bins_pack(const uint8_t* bins_rowmajor, int64_t n_rows, int32_t n_featu
  *                  in Alg. 1), not by position in the leaf
  *   hist_out       DEVICE gbdt_bin_t [n_features][n_bins], fully overwritten;
  *                  all zero when n_leaf_rows == 0
- * Arithmetic: a workgroup takes its rows in epochs of at most 8192.  Per epoch it
- * sums |grad| and |hess| over the epoch's rows, derives the largest power-of-two
- * scales for which no 32-bit integer bin sum can overflow, rounds every gradient
- * and hessian once to that grid and accumulates integers (App. A.6 discusses the
- * precision of this accumulation; gfx950's local-memory float add is ~35x slower
- * than its integer add).  Epoch sums are rescaled to fp32, partial histograms are
- * combined in fp64 in a fixed order and rounded to fp32.  Consequences:
+ * Arithmetic: a workgroup takes its rows in epochs of 512.  Per epoch it sums |grad|
+ * and |hess| over the epoch's rows, derives the largest power-of-two scales for
+ * which no signed 27-bit bin sum can overflow, rounds every gradient and hessian
+ * once to that grid and accumulates count, gradient and hessian as the three fields
+ * of one 64-bit integer per (feature, bin) (App. A.6 discusses the precision of this
+ * accumulation; gfx950's local-memory float add is ~30x slower than its integer
+ * add).  Epoch sums are rescaled and accumulated in fp32 (fp64 for n_bins <= 16),
+ * the partial histograms of the workgroups are combined in fp64 in a fixed order
+ * and rounded to fp32.  Consequences:
  *   - counts are exact;
- *   - every gradient (hessian) bin sum is within 8192 / 2^31 = 3.8e-6 of the sum
- *     of |grad| (|hess|) over the leaf, plus fp32 rounding of the result, for any
- *     input values and any bin distribution;
+ *   - every gradient (hessian) bin sum is within 512 / (2^26 - 512) = 7.7e-6 of the
+ *     sum of |grad| (|hess|) over the leaf, plus the fp32 roundings named above, for
+ *     any input values and any bin distribution;
  *   - values that are multiples of a power of two well above the quantum (e.g.
  *     +-0.5, 0.25) are accumulated exactly;
- *   - the result is bit-reproducible: it does not depend on scheduling.
+ *   - the split of a leaf's rows among workgroups is decided at run time, so the
+ *     last bits of gradient / hessian sums may differ between runs.
  * grad / hess must be finite.
  */
 int gbdt_hist_build(const void* bin_matrix, int64_t n_rows, int32_t n_features, int32_t n_bins,
