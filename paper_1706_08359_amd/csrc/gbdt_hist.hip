@@ -135,7 +135,7 @@ __device__ __forceinline__ float wave_sum_to_lane63(float v) {
 // Compile-time shape of the work of one wavefront on a tile of width W.
 template <int CAP, int W, bool NIB, int NT>
 struct TileShape {
-  static constexpr int VEC = W == 16 ? 4 : 8;       // bytes a lane loads
+  static constexpr int VEC = NIB ? (W == 16 ? 4 : 8) : W / 4;  // bytes a lane loads: 4, 8 or 16
   static constexpr int NWORD = VEC / 4;             // 32-bit words a lane loads
   static constexpr int LPR = W / VEC;               // lanes per row
   static constexpr int RPW = 64 / LPR;              // rows per wavefront load
@@ -148,7 +148,7 @@ struct TileShape {
   static constexpr int GPE = 64 / RPW;              // row groups per wavefront per epoch
   static_assert(NT == kEpochRows, "an epoch gives every lane one row of its own");
   static_assert(CELLS % NT == 0, "every thread drains the same number of cells");
-  static_assert(4 * LPR <= 32 && (LPR == 8 || LPR == 4), "slot tables are bytes");
+  static_assert(LPR == 4 || LPR == 8, "a row is shared by a quad or by two quads");
 };
 
 // Histogram of rows [begin, end) of the leaf for one feature tile, accumulated in
@@ -207,7 +207,7 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
   using S = TileShape<CAP, W, NIB, NT>;
   constexpr int VEC = S::VEC, NWORD = S::NWORD, LPR = S::LPR, RPW = S::RPW, NBW = S::NBW;
   constexpr int CELLS = S::CELLS, PP = S::PP, NW = S::NW;
-  constexpr int NTBL = LPR == 8 ? 1 : 2;  // LPR 4: two byte-words share a page
+  constexpr int NTBL = LPR == 8 ? 1 : 2;  // LPR 4: two byte-words share a page of 32 slots
 
   char* cells = reinterpret_cast<char*>(lds);
   float* red = reinterpret_cast<float*>(lds + CELLS);  // [2 parities][2 stats][NW]
@@ -288,10 +288,10 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
     return *reinterpret_cast<const float*>(reinterpret_cast<const char*>(a) + (r << 2));
   };
   // value of `v` held by the owner of this lane's row of group gi: lane j = gi of the
-  // lane's group of LPR lanes
+  // LPR lanes that share the row
   auto from_owner = [&](uint32_t v, auto gi_tag) -> uint32_t {
     constexpr int gi = decltype(gi_tag)::value;
-    if (LPR == 4) {  // quad broadcast
+    if (LPR == 4) {  // quad broadcast: every lane of a quad takes lane gi of the quad
       return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, gi * 0x55, 0xf, 0xf, false);
     }
     // LPR 8: lanes 0..7 of each row of 16 take lane gi, lanes 8..15 take lane 8 + gi
@@ -305,7 +305,7 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
   // the matrix or its slack and their addend is zero.  With an index list the row id
   // comes from the row's owner.
   constexpr int GPE = S::GPE;
-  auto load_group = [&](uint2& w, uint32_t rows, uint32_t off0, auto gi_tag) {
+  auto load_group = [&](uint4& w, uint32_t rows, uint32_t off0, auto gi_tag) {
     constexpr int gi = decltype(gi_tag)::value;
     uint32_t off;  // 32-bit byte offsets ((n_rows + slack) * W < 2^32)
     if (INDEXED) {
@@ -313,21 +313,24 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
     } else {
       off = off0 + (uint32_t)(gi * RPW * W);
     }
-    if (NWORD == 2) {
-      w = *reinterpret_cast<const uint2*>(tile + off);
+    if (NWORD == 4) {
+      w = *reinterpret_cast<const uint4*>(tile + off);
+    } else if (NWORD == 2) {
+      const uint2 v = *reinterpret_cast<const uint2*>(tile + off);
+      w.x = v.x;
+      w.y = v.y;
     } else {
       w.x = *reinterpret_cast<const uint32_t*>(tile + off);
-      w.y = 0;
     }
   };
   // lo, hi: the addend of the row this lane owns (zero for a row past the chunk end)
-  auto add_group = [&](const uint2& w, uint32_t lo, uint32_t hi, auto gi_tag) {
+  auto add_group = [&](const uint4& w, uint32_t lo, uint32_t hi, auto gi_tag) {
     const unsigned long long add =
         ((unsigned long long)from_owner(hi, gi_tag) << 32) | from_owner(lo, gi_tag);
     uint32_t bword[NBW];
 #pragma unroll
     for (int x = 0; x < NWORD; ++x) {
-      const uint32_t word = x == 0 ? w.x : w.y;
+      const uint32_t word = x == 0 ? w.x : (x == 1 ? w.y : (x == 2 ? w.z : w.w));
       if (NIB) {
         bword[2 * x] = word & 0x0f0f0f0fu;
         bword[2 * x + 1] = (word >> 4) & 0x0f0f0f0fu;
@@ -337,8 +340,7 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
     }
 #pragma unroll
     for (int bw = 0; bw < NBW; ++bw) {
-      constexpr int kPageShift = LPR == 8 ? 0 : 1;
-      const int page = bw >> kPageShift;
+      const int page = LPR == 8 ? bw : (bw >> 1);
       const int tv = LPR == 8 ? 0 : (bw & 1);
 #pragma unroll
       for (int k = 0; k < 4; ++k) {
@@ -358,10 +360,10 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
     return (e + (uint32_t)wave * 64u + (uint32_t)rho) * (uint32_t)W + (uint32_t)(VEC * j);
   };
   // The bins of all row groups of one epoch, requested in group order.  (The scheduling
-  // barriers keep that order: the epoch loop waits for group gi with "at most 9 younger
-  // requests outstanding", which is only right when the first epoch's requests were
+  // barriers keep that order: the epoch loop waits for group gi with "at most GPE + 1
+  // younger requests outstanding", which is only right when the first epoch's requests were
   // issued in the order the loop re-issues them.)
-  auto load_epoch = [&](uint2 (&w)[GPE], uint32_t rows, uint32_t e0) {
+  auto load_epoch = [&](uint4 (&w)[GPE], uint32_t rows, uint32_t e0) {
     const uint32_t off0 = group_offset0(e0);
     auto step = [&](auto gi_tag) {
       constexpr int gi = decltype(gi_tag)::value;
@@ -405,7 +407,7 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
   // requests the same group of the next epoch into them: every request has a whole
   // epoch to complete, requests are spread evenly over the epoch, and one register set
   // serves both epochs.
-  auto add_and_reload = [&](uint2 (&w)[GPE], uint32_t lo, uint32_t hi, uint32_t rows_nxt,
+  auto add_and_reload = [&](uint4 (&w)[GPE], uint32_t lo, uint32_t hi, uint32_t rows_nxt,
                             uint32_t e0_nxt) {
     const uint32_t off0 = group_offset0(e0_nxt);
     auto step = [&](auto gi_tag) {
@@ -444,7 +446,7 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
     uint32_t row_nxt = load_row_id(begin + kEpochRows);
     float g_cur = load_stat(grad, row_cur);
     float h_cur = load_stat(hess, row_cur);
-    uint2 w[GPE];
+    uint4 w[GPE];
     load_epoch(w, row_cur, begin);
     {
       const bool ok = own_valid(begin);
@@ -544,7 +546,7 @@ hist_build_kernel(BuildArgs a) {
           tile, a.idx, a.grad, a.hess, n_leaf, (uint32_t)c, (uint32_t)a.n_units,
           (uint32_t)a.unit_epochs, a.counters + a.n_main, lds,
           rem_base + (size_t)c * (size_t)block_words<CAP, 16, NIB, NT>());
-    } else {
+    } else if constexpr (WM > 32) {
       build_tile<CAP, 32, NIB, NT, ACC, INDEXED>(
           tile, a.idx, a.grad, a.hess, n_leaf, (uint32_t)c, (uint32_t)a.n_units,
           (uint32_t)a.unit_epochs, a.counters + a.n_main, lds,

@@ -2,8 +2,8 @@
 //
 // The paper (Sec. 4, "Data Structure") bundles 4 one-byte features of a sample
 // into one 4-byte word so that a thread never fetches a single byte, and stores
-// those words tuple-major.  Here the bundle is kept (a lane loads 4 or 8 bytes
-// = 4 or 8 features, twice that with 4-bit bins, App. C.4) but words are laid
+// those words tuple-major.  Here the bundle is kept (a lane loads 4, 8 or 16 bytes
+// = that many features, twice as many with 4-bit bins, App. C.4) but words are laid
 // out row-major inside FEATURE TILES of W bytes: tile t holds, for every row, W
 // consecutive bytes.  A gathered leaf row then costs one contiguous W-byte
 // segment per tile instead of one 4-byte word per cache line.
@@ -13,8 +13,8 @@
 // All tiles have the "main" width WM except possibly the last one, which is 16
 // or 32 bytes wide when few feature bytes remain (so that padding stays small).
 //
-// Inside a tile, a lane loads VEC consecutive bytes of a row (4 from a 16-byte
-// tile, else 8), so a row is LPR = W / VEC lane-chunks.  Byte i of the tile row
+// Inside a tile, a lane loads VEC consecutive bytes of a row (W / 4 with 8-bit bins;
+// 4 or 8 with 4-bit bins), so a row is LPR = W / VEC = 4 or 8 lane-chunks.  Byte i of the tile row
 // is byte bl = i % VEC of lane-chunk j = i / VEC.  The lane splits its bytes
 // into "byte-words" of 4 bin values each: with 8-bit bins byte-word bw is the
 // loaded word bl / 4; with 4-bit bins each loaded word gives two byte-words, its
@@ -70,8 +70,9 @@ GBDT_HD int32_t plan_n_tiles(const TilePlan& p) { return p.n_main + (p.wr ? 1 : 
 GBDT_HD int32_t plan_tile_width(const TilePlan& p, int32_t t) { return t < p.n_main ? p.wm : p.wr; }
 // features (= slots) held by a tile of width w
 GBDT_HD int32_t plan_slots(const TilePlan& p, int32_t w) { return p.nib ? 2 * w : w; }
-// bytes a lane loads from a row of a tile of width w
-GBDT_HD int32_t plan_vec(int32_t w) { return w == 16 ? 4 : 8; }
+// bytes a lane loads from a row of a tile of width w: a quarter of the row with 8-bit
+// bins; with 4-bit bins at most 8 (16 bin values)
+GBDT_HD int32_t plan_vec(const TilePlan& p, int32_t w) { return p.nib ? (w == 16 ? 4 : 8) : w / 4; }
 // pages of 32 slots in the histogram of a tile of width w
 GBDT_HD int32_t plan_pages(const TilePlan& p, int32_t w) { return (plan_slots(p, w) + 31) / 32; }
 // cells ((bin, slot) pairs, padding included) of the histogram of a tile of width w
@@ -93,7 +94,7 @@ GBDT_HD FeatureSlot plan_locate(const TilePlan& p, int32_t f) {
   if (t >= p.n_main) t = p.n_main;  // remainder tile
   int32_t w = plan_tile_width(p, t);
   int32_t i = fb - t * p.wm;  // byte inside the tile row
-  int32_t vec = plan_vec(w);
+  int32_t vec = plan_vec(p, w);
   int32_t lpr = w / vec;
   int32_t j = i / vec;
   int32_t bl = i - j * vec;  // byte inside the lane-chunk
@@ -109,7 +110,7 @@ GBDT_HD FeatureSlot plan_locate(const TilePlan& p, int32_t f) {
 // for padding slots).
 GBDT_HD int32_t plan_feature_of(const TilePlan& p, int32_t t, int32_t slot) {
   int32_t w = plan_tile_width(p, t);
-  int32_t vec = plan_vec(w);
+  int32_t vec = plan_vec(p, w);
   int32_t lpr = w / vec;
   int32_t bw = slot / (4 * lpr);
   int32_t rest = slot - bw * 4 * lpr;

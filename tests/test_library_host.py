@@ -78,7 +78,7 @@ def test_tile_plan_is_a_bijection_onto_slots(n_features, n_bins):
     g = B.gbdt_debug_geometry(n_features, n_bins, 1000)
     assert g["cap"] >= n_bins and g["cap"] in (16, 64, 256)
     assert g["nib"] == (1 if n_bins <= 16 else 0)
-    assert g["wm"] == (32 if g["cap"] == 256 else 64) and g["wr"] in (0, 16, 32)
+    assert g["wm"] == (32 if g["cap"] == 256 else 64) and g["wr"] in (0, 16, 32) and g["wr"] < g["wm"]
     assert g["row_bytes"] == g["n_main"] * g["wm"] + g["wr"]
     per_byte = 2 if g["nib"] else 1
     assert g["feat_bytes"] == (n_features + per_byte - 1) // per_byte
