@@ -95,8 +95,8 @@ def cpu_baseline(w, budget_values=1.2e9):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="dense_wide")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()

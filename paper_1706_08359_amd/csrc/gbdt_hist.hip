@@ -77,8 +77,6 @@ struct BuildArgs {
   int32_t wr;           // remainder tile width, 0 if none
   int32_t wgs_main;     // workgroups per main tile
   int32_t wgs_rem;      // workgroups of the remainder tile
-  int32_t unit_epochs;  // epochs per unit of work
-  int32_t n_units;      // units per tile
 };
 
 // A histogram cell is ONE 64-bit integer that carries, from the low bits up, the
@@ -200,8 +198,8 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
                                            const int32_t* __restrict__ idx,
                                            const float* __restrict__ grad,
                                            const float* __restrict__ hess, uint32_t end,
-                                           uint32_t first_unit, uint32_t n_units,
-                                           uint32_t unit_epochs, uint32_t* counter,
+                                           uint32_t first_epoch, uint32_t n_wgs,
+                                           uint32_t* counter,
                                            unsigned long long* lds,
                                            uint32_t* __restrict__ out) {
   using S = TileShape<CAP, W, NIB, NT>;
@@ -211,7 +209,7 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
 
   char* cells = reinterpret_cast<char*>(lds);
   float* red = reinterpret_cast<float*>(lds + CELLS);  // [2 parities][2 stats][NW]
-  uint32_t* unit_box = reinterpret_cast<uint32_t*>(red + 4 * NW);     // the unit just handed out
+  uint32_t* unit_box = reinterpret_cast<uint32_t*>(red + 4 * NW);     // the epoch just taken from the counter
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -427,76 +425,78 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
     }
   };
 
-  // Work distribution.  The leaf's epochs are handed out in units of unit_epochs
-  // consecutive epochs.  A workgroup starts with unit first_unit; while it works on a
-  // unit, one lane takes the next one from the tile's counter (a global atomic).  Slow
-  // and fast workgroups (the CU issues the instructions of its oldest workgroup first)
-  // so end together, and one partial block per workgroup suffices.  Inside a unit the
-  // loads run an epoch ahead; a new unit starts its pipeline afresh.
-  for (uint32_t unit = first_unit; unit < n_units;) {  // uniform over the workgroup
-    const uint32_t begin = unit * unit_epochs * (uint32_t)kEpochRows;
-    const uint32_t stop = begin + unit_epochs * (uint32_t)kEpochRows;  // may pass the leaf end
+  // Work distribution.  The tile's workgroups share out the leaf's epochs one at a time.
+  // The requests of an epoch are issued up to two epochs ahead (row ids two, gradients /
+  // hessians and bins one), so a workgroup always knows its next three epochs: the first
+  // three are fixed (workgroup c takes epochs c, c + n_wgs, c + 2 n_wgs), every further
+  // one is taken from the tile's counter (a global atomic by one lane, three epochs
+  // before it is worked on).  Fast and slow workgroups (the CU issues the instructions
+  // of its oldest workgroup first) so end within one epoch of each other, and one
+  // partial block per workgroup suffices.
+  auto epoch_pos = [&](uint32_t e) {  // first leaf position of epoch e; `past`: none
+    return e < n_epochs_leaf ? e * (uint32_t)kEpochRows : past;
+  };
+  uint32_t p0 = epoch_pos(first_epoch), p1 = epoch_pos(first_epoch + n_wgs),
+           p2 = epoch_pos(first_epoch + 2 * n_wgs);
+
+  int kg, kh;
+  // rows the lane owns in the current epoch and the next one; the current row's stats
+  uint32_t row_cur = load_row_id(p0);
+  uint32_t row_nxt = load_row_id(p1);
+  float g_cur = load_stat(grad, row_cur);
+  float h_cur = load_stat(hess, row_cur);
+  uint4 w[GPE];
+  load_epoch(w, row_cur, p0);
+  {
+    const bool ok = own_valid(p0);
+    reduce_abs(ok ? fabsf(g_cur) : 0.0f, ok ? fabsf(h_cur) : 0.0f, 0);
+  }
+  __syncthreads();  // also orders the LDS clearing before the first atomics
+  read_scales(0, kg, kh);
+
+  uint32_t parity = 0;
+  while (p0 < end) {  // uniform over the workgroup
     uint32_t taken = 0;
     if (tid == 0)
       taken = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-
-    int kg, kh;
-    // rows the lane owns in the current epoch and the next one; the current row's stats
-    uint32_t row_cur = load_row_id(begin);
-    uint32_t row_nxt = load_row_id(begin + kEpochRows);
-    float g_cur = load_stat(grad, row_cur);
-    float h_cur = load_stat(hess, row_cur);
-    uint4 w[GPE];
-    load_epoch(w, row_cur, begin);
+    // ---- requests for later epochs
+    const uint32_t row_nn = load_row_id(p2);
+    const float g_nxt = load_stat(grad, row_nxt);
+    const float h_nxt = load_stat(hess, row_nxt);
+    // ---- this lane's row -> 64-bit addend 1 + gq * 2^10 + hq * 2^37 (two's complement)
+    uint32_t lo, hi;
     {
-      const bool ok = own_valid(begin);
-      reduce_abs(ok ? fabsf(g_cur) : 0.0f, ok ? fabsf(h_cur) : 0.0f, 0);
+      const int32_t gq = __float2int_rn(g_cur * pow2f(kg));
+      const int32_t hq = __float2int_rn(h_cur * pow2f(kh));
+      lo = ((uint32_t)gq << kCountBits) + 1u;
+      hi = (uint32_t)(gq >> (32 - kCountBits)) + ((uint32_t)hq << (kCountBits + kSumBits - 32));
+      const bool ok = own_valid(p0);
+      lo = ok ? lo : 0u;
+      hi = ok ? hi : 0u;
     }
-    __syncthreads();  // (the first one also orders the LDS clearing before the atomics)
-    read_scales(0, kg, kh);
+    add_and_reload(w, lo, hi, row_nxt, p1);
 
-    uint32_t parity = 0;
-    for (uint32_t e0 = begin; e0 < stop && e0 < end; e0 += kEpochRows) {
-      // ---- requests for later epochs
-      const uint32_t row_nn = load_row_id(e0 + 2 * kEpochRows);
-      const float g_nxt = load_stat(grad, row_nxt);
-      const float h_nxt = load_stat(hess, row_nxt);
-      // ---- this lane's row -> 64-bit addend 1 + gq * 2^10 + hq * 2^37 (two's complement)
-      uint32_t lo, hi;
-      {
-        const int32_t gq = __float2int_rn(g_cur * pow2f(kg));
-        const int32_t hq = __float2int_rn(h_cur * pow2f(kh));
-        lo = ((uint32_t)gq << kCountBits) + 1u;
-        hi = (uint32_t)(gq >> (32 - kCountBits)) + ((uint32_t)hq << (kCountBits + kSumBits - 32));
-        const bool ok = own_valid(e0);
-        lo = ok ? lo : 0u;
-        hi = ok ? hi : 0u;
-      }
-      // (after the unit's last epoch nothing new is needed: re-request the same rows,
-      // which come from cache, instead of an epoch of another workgroup's unit)
-      const bool more = e0 + kEpochRows < stop;
-      add_and_reload(w, lo, hi, more ? row_nxt : row_cur, more ? e0 + kEpochRows : e0);
+    parity ^= 1u;
+    {
+      const bool ok = own_valid(p1);
+      reduce_abs(ok ? fabsf(g_nxt) : 0.0f, ok ? fabsf(h_nxt) : 0.0f, (int)parity);
+    }
+    if (tid == 0) unit_box[0] = taken;
+    __syncthreads();  // all atomics of the epoch have landed
 
-      parity ^= 1u;
-      {
-        const bool ok = own_valid(e0 + kEpochRows);
-        reduce_abs(ok ? fabsf(g_nxt) : 0.0f, ok ? fabsf(h_nxt) : 0.0f, (int)parity);
-      }
-      if (tid == 0) unit_box[0] = taken;  // (needed after the unit's last epoch only)
-      __syncthreads();  // all atomics of the epoch have landed
-
-      // ---- drain: integer sums -> registers, clear the cells for the next epoch
-      const float inv_g = pow2f(-kg), inv_h = pow2f(-kh);
+    // ---- drain: integer sums -> registers, clear the cells for the next epoch
+    const float inv_g = pow2f(-kg), inv_h = pow2f(-kh);
 #pragma unroll
-      for (int m = 0; m < PP; ++m) drain_cell(m, inv_g, inv_h);
-      read_scales((int)parity, kg, kh);
-      unit = __builtin_amdgcn_readfirstlane(unit_box[0]);
-      row_cur = row_nxt;
-      row_nxt = row_nn;
-      g_cur = g_nxt;
-      h_cur = h_nxt;
-      __syncthreads();  // cells are clear, `red` and the unit box are read, before reuse
-    }
+    for (int m = 0; m < PP; ++m) drain_cell(m, inv_g, inv_h);
+    read_scales((int)parity, kg, kh);
+    p0 = p1;
+    p1 = p2;
+    p2 = epoch_pos(__builtin_amdgcn_readfirstlane(unit_box[0]));
+    row_cur = row_nxt;
+    row_nxt = row_nn;
+    g_cur = g_nxt;
+    h_cur = h_nxt;
+    __syncthreads();  // cells are clear, `red` and the epoch box are read, before reuse
   }
 
   // partial block layout: [stat][cell] words
@@ -535,33 +535,31 @@ hist_build_kernel(BuildArgs a) {
     const uint8_t* tile = a.packed + a.n_rows * ((int64_t)t * WM);
     uint32_t* out = a.partials + ((size_t)t * a.wgs_main + c) * (size_t)block_words<CAP, WM, NIB, NT>();
     build_tile<CAP, WM, NIB, NT, ACC, INDEXED>(tile, a.idx, a.grad, a.hess, n_leaf, (uint32_t)c,
-                                                   (uint32_t)a.n_units, (uint32_t)a.unit_epochs,
-                                                   a.counters + t, lds, out);
+                                               (uint32_t)a.wgs_main, a.counters + t, lds, out);
   } else {
     const int32_t c = b - main_blocks;
     const uint8_t* tile = a.packed + a.n_rows * ((int64_t)a.n_main * WM);
     uint32_t* rem_base = a.partials + (size_t)main_blocks * (size_t)block_words<CAP, WM, NIB, NT>();
     if (a.wr == 16) {
       build_tile<CAP, 16, NIB, NT, ACC, INDEXED>(
-          tile, a.idx, a.grad, a.hess, n_leaf, (uint32_t)c, (uint32_t)a.n_units,
-          (uint32_t)a.unit_epochs, a.counters + a.n_main, lds,
-          rem_base + (size_t)c * (size_t)block_words<CAP, 16, NIB, NT>());
+          tile, a.idx, a.grad, a.hess, n_leaf, (uint32_t)c, (uint32_t)a.wgs_rem,
+          a.counters + a.n_main, lds, rem_base + (size_t)c * (size_t)block_words<CAP, 16, NIB, NT>());
     } else if constexpr (WM > 32) {
       build_tile<CAP, 32, NIB, NT, ACC, INDEXED>(
-          tile, a.idx, a.grad, a.hess, n_leaf, (uint32_t)c, (uint32_t)a.n_units,
-          (uint32_t)a.unit_epochs, a.counters + a.n_main, lds,
-          rem_base + (size_t)c * (size_t)block_words<CAP, 32, NIB, NT>());
+          tile, a.idx, a.grad, a.hess, n_leaf, (uint32_t)c, (uint32_t)a.wgs_rem,
+          a.counters + a.n_main, lds, rem_base + (size_t)c * (size_t)block_words<CAP, 32, NIB, NT>());
     }
   }
 }
 
-// Sets every tile's unit counter to the number of units its workgroups start with.
+// Sets every tile's epoch counter to the number of epochs its workgroups start with
+// (three each).
 // (A fill kernel, not a memset node, so the call can be captured into a graph.)
 __global__ void __launch_bounds__(256)
 counters_init_kernel(uint32_t* counters, int32_t n_main, int32_t wgs_main, int32_t wgs_rem,
                      int32_t n_tiles) {
   const int32_t t = blockIdx.x * blockDim.x + threadIdx.x;
-  if (t < n_tiles) counters[t] = (uint32_t)(t < n_main ? wgs_main : wgs_rem);
+  if (t < n_tiles) counters[t] = 3u * (uint32_t)(t < n_main ? wgs_main : wgs_rem);
 }
 
 // ------------------------------------------------------------------ merge kernel
@@ -966,18 +964,14 @@ struct BuildGeom {
   int nt;               // threads per workgroup
   size_t lds_bytes;     // LDS per workgroup
   int wgs_main, wgs_rem;  // workgroups per main tile / of the remainder tile
-  int unit_epochs;      // epochs per unit of work
-  int n_units;          // units per tile
   size_t partial_words;  // total words of all partial blocks
-  size_t counter_words;  // one unit counter per tile
+  size_t counter_words;  // one epoch counter per tile
 };
 
-constexpr int kUnitEpochs = 8;  // epochs per unit when units are handed out dynamically
-
 // Chooses the grid: as many workgroups per tile as fit the machine at once (they stay
-// until their tile's units are used up), and the unit size.  wg_per_cu: resident
-// workgroups per CU of the kernel variant as reported by the runtime (<= 0: estimate
-// from the LDS footprint alone).
+// until their tile's epochs are used up), but no more than the leaf has epochs.
+// wg_per_cu: resident workgroups per CU of the kernel variant as reported by the
+// runtime (<= 0: estimate from the LDS footprint alone).
 BuildGeom make_geom(int32_t n_features, int32_t n_bins, int64_t n_leaf, int cus,
                     int wg_per_cu_hint) {
   BuildGeom g;
@@ -985,8 +979,7 @@ BuildGeom make_geom(int32_t n_features, int32_t n_bins, int64_t n_leaf, int cus,
   const TilePlan& p = g.plan;
   g.nt = kBuildThreads;
   const size_t main_block = (size_t)3 * plan_cells(p, p.wm);
-  g.lds_bytes = (size_t)plan_cells(p, p.wm) * 8 +
-                4 * (g.nt / 64) * sizeof(float) + 8;
+  g.lds_bytes = (size_t)plan_cells(p, p.wm) * 8 + 4 * (g.nt / 64) * sizeof(float) + 8;
   int wg_per_cu = wg_per_cu_hint;
   if (wg_per_cu <= 0) {
     wg_per_cu = (int)(kLdsPerCu / g.lds_bytes);
@@ -998,28 +991,12 @@ BuildGeom make_geom(int32_t n_features, int32_t n_bins, int64_t n_leaf, int cus,
   const int n_tiles = plan_n_tiles(p);
   const int64_t n_epochs = (n_leaf + kEpochRows - 1) / kEpochRows;
   int64_t wgs = resident / n_tiles;  // per tile
+  if (wgs > n_epochs) wgs = n_epochs;
   if (wgs < 1) wgs = 1;
-  if (wgs * kUnitEpochs <= n_epochs) {
-    // enough work: units of kUnitEpochs handed out by the tile's counter
-    g.unit_epochs = kUnitEpochs;
-  } else {
-    // little work: one unit per workgroup, as short as it takes to use `wgs` of them
-    g.unit_epochs = (int)((n_epochs + wgs - 1) / wgs);
-    if (g.unit_epochs < 1) g.unit_epochs = 1;
-  }
-  g.n_units = (int)((n_epochs + g.unit_epochs - 1) / g.unit_epochs);
-  if (g.n_units < 1) g.n_units = 1;
-  if (wgs > g.n_units) wgs = g.n_units;
-  g.wgs_main = p.n_main ? (int)wgs : 0;
   // (A narrow tile's epochs are cheaper, but not by much: the per-epoch overhead does
   // not shrink with the tile.  It gets as many workgroups as a main tile.)
-  g.wgs_rem = 0;
-  if (p.wr) {
-    int64_t wr_wgs = wgs;
-    if (wr_wgs < 1) wr_wgs = 1;
-    if (wr_wgs > g.n_units) wr_wgs = g.n_units;
-    g.wgs_rem = (int)wr_wgs;
-  }
+  g.wgs_main = p.n_main ? (int)wgs : 0;
+  g.wgs_rem = p.wr ? (int)wgs : 0;
   g.partial_words = (size_t)p.n_main * g.wgs_main * main_block +
                     (size_t)g.wgs_rem * 3 * (p.wr ? plan_cells(p, p.wr) : 0);
   g.counter_words = (size_t)n_tiles;
@@ -1029,7 +1006,7 @@ BuildGeom make_geom(int32_t n_features, int32_t n_bins, int64_t n_leaf, int cus,
 // Kernel variants: bin capacity -> (main tile width, 4-bit, waves per SIMD the
 // register budget is set for).
 #define GBDT_VARIANT_16 16, 64, true, kBuildThreads, 8, double
-#define GBDT_VARIANT_64 64, 64, false, kBuildThreads, 8, float
+#define GBDT_VARIANT_64 64, 64, false, kBuildThreads, 6, float
 #define GBDT_VARIANT_256 256, 32, false, kBuildThreads, 4, float
 
 template <int CAP, int WM, bool NIB, int NT, int WPE, typename ACC, bool INDEXED>
@@ -1202,8 +1179,6 @@ int gbdt_hist_build(const void* bin_matrix, int64_t n_rows, int32_t n_features, 
   a.wr = p.wr;
   a.wgs_main = g.wgs_main;
   a.wgs_rem = g.wgs_rem;
-  a.unit_epochs = g.unit_epochs;
-  a.n_units = g.n_units;
   const int blocks = p.n_main * g.wgs_main + g.wgs_rem;
   const int n_tiles = plan_n_tiles(p);
   hipLaunchKernelGGL(counters_init_kernel, dim3((n_tiles + 255) / 256), dim3(256), 0, s, a.counters,
@@ -1276,8 +1251,8 @@ int gbdt_debug_geometry(int32_t n_features, int32_t n_bins, int64_t n_leaf_rows,
   const TilePlan& p = g.plan;
   const int64_t v[16] = {p.cap,         p.nib,          p.wm,          p.n_main,
                          p.wr,          p.row_bytes,    p.feat_bytes,  g.nt,
-                         (int64_t)g.lds_bytes, g.wgs_main, g.wgs_rem, g.unit_epochs,
-                         g.n_units,     (int64_t)g.partial_words, 0, 0};
+                         (int64_t)g.lds_bytes, g.wgs_main, g.wgs_rem, (int64_t)g.partial_words,
+                         0,             0, 0, 0};
   for (int i = 0; i < 16; ++i) out[i] = v[i];
   return GBDT_OK;
 }

@@ -100,21 +100,20 @@ def test_tile_plan_is_a_bijection_onto_slots(n_features, n_bins):
 
 @pytest.mark.parametrize("n_features,n_bins", [(28, 64), (2000, 63), (28, 255), (137, 255), (700, 16), (5, 2)])
 @pytest.mark.parametrize("n_leaf", [1, 63, 64, 65, 511, 512, 513, 4000, 100_003, 10_500_000])
-def test_units_cover_the_leaf_exactly(n_features, n_bins, n_leaf):
+def test_workgroups_per_tile(n_features, n_bins, n_leaf):
     g = B.gbdt_debug_geometry(n_features, n_bins, n_leaf)
     per_byte = 2 if g["nib"] else 1
     n_epochs = (n_leaf + 511) // 512
-    assert g["unit_epochs"] >= 1 and g["n_units"] >= 1
-    assert g["n_units"] * g["unit_epochs"] >= n_epochs            # every epoch belongs to a unit
-    assert (g["n_units"] - 1) * g["unit_epochs"] < n_epochs       # no unit starts past the end
+    n_tiles = g["n_main"] + (1 if g["wr"] else 0)
     words = 0
     for wgs, w, tiles in ((g["wgs_main"], g["wm"], g["n_main"]), (g["wgs_rem"], g["wr"], 1 if g["wr"] else 0)):
         if tiles == 0:
             continue
-        assert 1 <= wgs <= g["n_units"]                           # no workgroup without a first unit
+        # every workgroup's first epoch exists; the grid fits the machine once
+        assert 1 <= wgs <= n_epochs
+        assert wgs * n_tiles <= max(256 * 4, n_tiles)
         pages = (w * per_byte + 31) // 32
         words += tiles * wgs * 3 * g["cap"] * 32 * pages
     assert words == g["partial_words"]
-    n_tiles = g["n_main"] + (1 if g["wr"] else 0)
     assert B.gbdt_workspace_bytes(n_leaf, n_features, n_bins) >= 4 * (g["partial_words"] + n_tiles)
     assert (g["n_main"] * g["wgs_main"] + g["wgs_rem"]) < 2 ** 31
