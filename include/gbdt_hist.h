@@ -199,7 +199,7 @@ int gbdt_calibration_copy(const void* src, void* dst, size_t bytes, void* stream
  * gbdt_debug_geometry fills out[0..15] with: bin capacity, 4-bit flag, main tile
  * width, number of main tiles, remainder tile width, packed bytes per row, feature
  * bytes per row, threads per workgroup, LDS bytes per workgroup, workgroups per
- * main tile, workgroups of the remainder tile, total 4-byte words of partial
+ * tile, epochs (of 512 rows) per unit of work, total 4-byte words of partial
  * histograms, 0, 0, 0, 0 -- as planned for a device with n_cus compute units (<= 0:
  * 256).  n_out must be >= 16.
  * gbdt_debug_locate reports the tile and the local-memory slot of a feature.

@@ -192,7 +192,7 @@ def gbdt_best_split(hist, lam, min_child_hess, split_out=None, stream=None):
 
 
 GEOMETRY_FIELDS = ["cap", "nib", "wm", "n_main", "wr", "row_bytes", "feat_bytes", "threads",
-                   "lds_bytes", "wgs_main", "wgs_rem", "partial_words"]
+                   "lds_bytes", "wgs", "unit_epochs", "partial_words"]
 
 
 def gbdt_debug_geometry(n_features: int, n_bins: int, n_leaf_rows: int, n_cus: int = 256) -> dict:

@@ -75,8 +75,8 @@ struct BuildArgs {
   int64_t n_leaf;
   int32_t n_main;       // main tiles
   int32_t wr;           // remainder tile width, 0 if none
-  int32_t wgs_main;     // workgroups per main tile
-  int32_t wgs_rem;      // workgroups of the remainder tile
+  int32_t wgs;          // workgroups per tile
+  int32_t unit_epochs;  // consecutive epochs a workgroup takes at a time
 };
 
 // A histogram cell is ONE 64-bit integer that carries, from the low bits up, the
@@ -84,6 +84,7 @@ struct BuildArgs {
 // hessian sum (27 bits, signed).  A workgroup drains its cells after every epoch
 // of kEpochRows rows, so a cell receives at most 512 additions between drains.
 constexpr int kEpochRows = 512;
+constexpr int kUnitEpochs = 4;  // consecutive epochs a workgroup takes from its group's counter (>= 3)
 constexpr int kCountBits = 10;
 constexpr int kSumBits = 27;
 static_assert(kEpochRows < (1 << kCountBits), "an epoch's count must fit its field");
@@ -198,7 +199,7 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
                                            const int32_t* __restrict__ idx,
                                            const float* __restrict__ grad,
                                            const float* __restrict__ hess, uint32_t end,
-                                           uint32_t first_epoch, uint32_t n_wgs,
+                                           uint32_t first_unit, uint32_t unit_epochs,
                                            uint32_t* counter,
                                            unsigned long long* lds,
                                            uint32_t* __restrict__ out) {
@@ -425,42 +426,69 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
     }
   };
 
-  // Work distribution.  The tile's workgroups share out the leaf's epochs one at a time.
-  // The requests of an epoch are issued up to two epochs ahead (row ids two, gradients /
-  // hessians and bins one), so a workgroup always knows its next three epochs: the first
-  // three are fixed (workgroup c takes epochs c, c + n_wgs, c + 2 n_wgs), every further
-  // one is taken from the tile's counter (a global atomic by one lane, three epochs
-  // before it is worked on).  Fast and slow workgroups (the CU issues the instructions
-  // of its oldest workgroup first) so end within one epoch of each other, and one
-  // partial block per workgroup suffices.
-  auto epoch_pos = [&](uint32_t e) {  // first leaf position of epoch e; `past`: none
-    return e < n_epochs_leaf ? e * (uint32_t)kEpochRows : past;
+  // Work distribution.  The workgroups of a tile share out the n_epochs epochs of the
+  // leaf in units of unit_epochs consecutive epochs.  Workgroup c of the tile starts
+  // with unit c; when it enters a unit, one lane takes the next one from the tile's
+  // counter (a global atomic), and the pipeline of
+  // requests (row ids two epochs ahead, gradients / hessians and bins one epoch ahead)
+  // runs on from the last epoch of a unit into the first epoch of the next.  Fast and
+  // slow workgroups (the CU issues the instructions of its oldest workgroup first) so
+  // end within a unit of each other, and one partial block per workgroup suffices.
+  // Looking two epochs ahead needs the next unit from a unit's second-last epoch on:
+  // the counter is only used with units of at least 3 epochs; shorter units (short
+  // leaves) are handed out one per workgroup, and every take from the counter fails.
+  // (Units also keep a workgroup's rows together.)
+  struct Pos {
+    uint32_t row;  // first leaf position of the epoch; `past`: no epoch
+    uint32_t idx;  // its number inside its unit
   };
-  uint32_t p0 = epoch_pos(first_epoch), p1 = epoch_pos(first_epoch + n_wgs),
-           p2 = epoch_pos(first_epoch + 2 * n_wgs);
+  const uint32_t n_units = (n_epochs_leaf + unit_epochs - 1) / unit_epochs;
+  uint32_t next_unit = n_units;  // the unit taken from the counter (n_units or more: none)
+  auto unit_first = [&](uint32_t u) {
+    Pos r;
+    r.row = u < n_units ? u * unit_epochs * (uint32_t)kEpochRows : past;
+    r.idx = 0;
+    return r;
+  };
+  auto after = [&](Pos x) {  // the epoch after x in this workgroup's sequence
+    if (x.row >= past) return x;
+    Pos r;
+    r.row = x.row + kEpochRows;
+    r.idx = x.idx + 1;
+    // the leaf may end inside its last unit
+    if (r.idx == unit_epochs || r.row >= past) {
+      // The taken unit is used up: until the next take arrives there is no further unit
+      // (only the leaf's short last unit can end before that, and nothing follows it).
+      r = unit_first(next_unit);
+      next_unit = n_units;
+    }
+    return r;
+  };
+  Pos p0 = unit_first(first_unit), p1 = after(p0), p2 = after(p1);
 
   int kg, kh;
   // rows the lane owns in the current epoch and the next one; the current row's stats
-  uint32_t row_cur = load_row_id(p0);
-  uint32_t row_nxt = load_row_id(p1);
+  uint32_t row_cur = load_row_id(p0.row);
+  uint32_t row_nxt = load_row_id(p1.row);
   float g_cur = load_stat(grad, row_cur);
   float h_cur = load_stat(hess, row_cur);
   uint4 w[GPE];
-  load_epoch(w, row_cur, p0);
+  load_epoch(w, row_cur, p0.row);
   {
-    const bool ok = own_valid(p0);
+    const bool ok = own_valid(p0.row);
     reduce_abs(ok ? fabsf(g_cur) : 0.0f, ok ? fabsf(h_cur) : 0.0f, 0);
   }
   __syncthreads();  // also orders the LDS clearing before the first atomics
   read_scales(0, kg, kh);
 
   uint32_t parity = 0;
-  while (p0 < end) {  // uniform over the workgroup
+  while (p0.row < end) {  // uniform over the workgroup
+    const bool enters_unit = p0.idx == 0;
     uint32_t taken = 0;
-    if (tid == 0)
+    if (enters_unit && tid == 0)
       taken = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     // ---- requests for later epochs
-    const uint32_t row_nn = load_row_id(p2);
+    const uint32_t row_nn = load_row_id(p2.row);
     const float g_nxt = load_stat(grad, row_nxt);
     const float h_nxt = load_stat(hess, row_nxt);
     // ---- this lane's row -> 64-bit addend 1 + gq * 2^10 + hq * 2^37 (two's complement)
@@ -470,18 +498,18 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
       const int32_t hq = __float2int_rn(h_cur * pow2f(kh));
       lo = ((uint32_t)gq << kCountBits) + 1u;
       hi = (uint32_t)(gq >> (32 - kCountBits)) + ((uint32_t)hq << (kCountBits + kSumBits - 32));
-      const bool ok = own_valid(p0);
+      const bool ok = own_valid(p0.row);
       lo = ok ? lo : 0u;
       hi = ok ? hi : 0u;
     }
-    add_and_reload(w, lo, hi, row_nxt, p1);
+    add_and_reload(w, lo, hi, row_nxt, p1.row);
 
     parity ^= 1u;
     {
-      const bool ok = own_valid(p1);
+      const bool ok = own_valid(p1.row);
       reduce_abs(ok ? fabsf(g_nxt) : 0.0f, ok ? fabsf(h_nxt) : 0.0f, (int)parity);
     }
-    if (tid == 0) unit_box[0] = taken;
+    if (enters_unit && tid == 0) unit_box[0] = taken;
     __syncthreads();  // all atomics of the epoch have landed
 
     // ---- drain: integer sums -> registers, clear the cells for the next epoch
@@ -489,14 +517,15 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
 #pragma unroll
     for (int m = 0; m < PP; ++m) drain_cell(m, inv_g, inv_h);
     read_scales((int)parity, kg, kh);
+    if (enters_unit) next_unit = __builtin_amdgcn_readfirstlane(unit_box[0]);
     p0 = p1;
     p1 = p2;
-    p2 = epoch_pos(__builtin_amdgcn_readfirstlane(unit_box[0]));
+    p2 = after(p2);
     row_cur = row_nxt;
     row_nxt = row_nn;
     g_cur = g_nxt;
     h_cur = h_nxt;
-    __syncthreads();  // cells are clear, `red` and the epoch box are read, before reuse
+    __syncthreads();  // cells are clear, `red` and the unit box are read, before reuse
   }
 
   // partial block layout: [stat][cell] words
@@ -526,40 +555,38 @@ hist_build_kernel(BuildArgs a) {
   // the unit box
   constexpr int kCells = TileShape<CAP, WM, NIB, NT>::CELLS;
   __shared__ __align__(16) unsigned long long lds[kCells + (4 * (NT / 64) * 4 + 7) / 8 + 1];
-  const int32_t main_blocks = a.n_main * a.wgs_main;
+  const int32_t main_blocks = a.n_main * a.wgs;
   const int32_t b = blockIdx.x;
   const uint32_t n_leaf = (uint32_t)a.n_leaf;
+  const int32_t t = b < main_blocks ? b % a.n_main : a.n_main;         // tile
+  const int32_t c = b < main_blocks ? b / a.n_main : b - main_blocks;  // workgroup of the tile
+  uint32_t* counter = a.counters + t;
+  const uint8_t* tile = a.packed + a.n_rows * ((int64_t)t * WM);
   if (b < main_blocks) {
-    const int32_t t = b % a.n_main;
-    const int32_t c = b / a.n_main;
-    const uint8_t* tile = a.packed + a.n_rows * ((int64_t)t * WM);
-    uint32_t* out = a.partials + ((size_t)t * a.wgs_main + c) * (size_t)block_words<CAP, WM, NIB, NT>();
+    uint32_t* out = a.partials + ((size_t)t * a.wgs + c) * (size_t)block_words<CAP, WM, NIB, NT>();
     build_tile<CAP, WM, NIB, NT, ACC, INDEXED>(tile, a.idx, a.grad, a.hess, n_leaf, (uint32_t)c,
-                                               (uint32_t)a.wgs_main, a.counters + t, lds, out);
+                                               (uint32_t)a.unit_epochs, counter, lds, out);
   } else {
-    const int32_t c = b - main_blocks;
-    const uint8_t* tile = a.packed + a.n_rows * ((int64_t)a.n_main * WM);
     uint32_t* rem_base = a.partials + (size_t)main_blocks * (size_t)block_words<CAP, WM, NIB, NT>();
     if (a.wr == 16) {
       build_tile<CAP, 16, NIB, NT, ACC, INDEXED>(
-          tile, a.idx, a.grad, a.hess, n_leaf, (uint32_t)c, (uint32_t)a.wgs_rem,
-          a.counters + a.n_main, lds, rem_base + (size_t)c * (size_t)block_words<CAP, 16, NIB, NT>());
+          tile, a.idx, a.grad, a.hess, n_leaf, (uint32_t)c, (uint32_t)a.unit_epochs, counter, lds,
+          rem_base + (size_t)c * (size_t)block_words<CAP, 16, NIB, NT>());
     } else if constexpr (WM > 32) {
       build_tile<CAP, 32, NIB, NT, ACC, INDEXED>(
-          tile, a.idx, a.grad, a.hess, n_leaf, (uint32_t)c, (uint32_t)a.wgs_rem,
-          a.counters + a.n_main, lds, rem_base + (size_t)c * (size_t)block_words<CAP, 32, NIB, NT>());
+          tile, a.idx, a.grad, a.hess, n_leaf, (uint32_t)c, (uint32_t)a.unit_epochs, counter, lds,
+          rem_base + (size_t)c * (size_t)block_words<CAP, 32, NIB, NT>());
     }
   }
 }
 
-// Sets every tile's epoch counter to the number of epochs its workgroups start with
-// (three each).
-// (A fill kernel, not a memset node, so the call can be captured into a graph.)
+// Sets every tile's unit counter to the number of units its workgroups start with
+// (one each).  (A fill kernel, not a memset node, so the call can be captured into a
+// graph.)
 __global__ void __launch_bounds__(256)
-counters_init_kernel(uint32_t* counters, int32_t n_main, int32_t wgs_main, int32_t wgs_rem,
-                     int32_t n_tiles) {
-  const int32_t t = blockIdx.x * blockDim.x + threadIdx.x;
-  if (t < n_tiles) counters[t] = 3u * (uint32_t)(t < n_main ? wgs_main : wgs_rem);
+counters_init_kernel(uint32_t* counters, int32_t wgs, int32_t n_counters) {
+  const int32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n_counters) counters[i] = (uint32_t)wgs;
 }
 
 // ------------------------------------------------------------------ merge kernel
@@ -963,15 +990,16 @@ struct BuildGeom {
   TilePlan plan;
   int nt;               // threads per workgroup
   size_t lds_bytes;     // LDS per workgroup
-  int wgs_main, wgs_rem;  // workgroups per main tile / of the remainder tile
+  int wgs;              // workgroups per tile
+  int unit_epochs;      // epochs per unit
   size_t partial_words;  // total words of all partial blocks
-  size_t counter_words;  // one epoch counter per tile
+  size_t counter_words;  // one unit counter per tile
 };
 
 // Chooses the grid: as many workgroups per tile as fit the machine at once (they stay
-// until their tile's epochs are used up), but no more than the leaf has epochs.
-// wg_per_cu: resident workgroups per CU of the kernel variant as reported by the
-// runtime (<= 0: estimate from the LDS footprint alone).
+// until their tile's units are used up), and the unit size.  wg_per_cu: resident
+// workgroups per CU of the kernel variant as reported by the runtime (<= 0: estimate
+// from the LDS footprint alone).
 BuildGeom make_geom(int32_t n_features, int32_t n_bins, int64_t n_leaf, int cus,
                     int wg_per_cu_hint) {
   BuildGeom g;
@@ -990,15 +1018,23 @@ BuildGeom make_geom(int32_t n_features, int32_t n_bins, int64_t n_leaf, int cus,
   const int64_t resident = (int64_t)cus * wg_per_cu;
   const int n_tiles = plan_n_tiles(p);
   const int64_t n_epochs = (n_leaf + kEpochRows - 1) / kEpochRows;
+  // (A narrow tile's epochs are cheaper, but not by much: the per-epoch overhead does
+  // not shrink with the tile.  It gets as many workgroups as a main tile.)
   int64_t wgs = resident / n_tiles;  // per tile
   if (wgs > n_epochs) wgs = n_epochs;
   if (wgs < 1) wgs = 1;
-  // (A narrow tile's epochs are cheaper, but not by much: the per-epoch overhead does
-  // not shrink with the tile.  It gets as many workgroups as a main tile.)
-  g.wgs_main = p.n_main ? (int)wgs : 0;
-  g.wgs_rem = p.wr ? (int)wgs : 0;
-  g.partial_words = (size_t)p.n_main * g.wgs_main * main_block +
-                    (size_t)g.wgs_rem * 3 * (p.wr ? plan_cells(p, p.wr) : 0);
+  // Units: kUnitEpochs when every workgroup gets at least one of them; otherwise (short
+  // leaf) one shorter unit per workgroup, none from the counter.
+  g.unit_epochs = kUnitEpochs;
+  if (wgs * kUnitEpochs > n_epochs) {
+    g.unit_epochs = (int)((n_epochs + wgs - 1) / wgs);
+    if (g.unit_epochs < 1) g.unit_epochs = 1;
+    const int64_t n_units = (n_epochs + g.unit_epochs - 1) / g.unit_epochs;
+    if (n_units >= 1 && wgs > n_units) wgs = n_units;  // no workgroup without a unit
+  }
+  g.wgs = (int)wgs;
+  g.partial_words = (size_t)p.n_main * g.wgs * main_block +
+                    (size_t)(p.wr ? g.wgs : 0) * 3 * (p.wr ? plan_cells(p, p.wr) : 0);
   g.counter_words = (size_t)n_tiles;
   return g;
 }
@@ -1177,12 +1213,13 @@ int gbdt_hist_build(const void* bin_matrix, int64_t n_rows, int32_t n_features, 
   a.n_leaf = n_leaf_rows;
   a.n_main = p.n_main;
   a.wr = p.wr;
-  a.wgs_main = g.wgs_main;
-  a.wgs_rem = g.wgs_rem;
-  const int blocks = p.n_main * g.wgs_main + g.wgs_rem;
+  a.wgs = g.wgs;
+  a.unit_epochs = g.unit_epochs;
   const int n_tiles = plan_n_tiles(p);
-  hipLaunchKernelGGL(counters_init_kernel, dim3((n_tiles + 255) / 256), dim3(256), 0, s, a.counters,
-                     p.n_main, g.wgs_main, g.wgs_rem, n_tiles);
+  const int blocks = n_tiles * g.wgs;
+  const int n_counters = (int)g.counter_words;
+  hipLaunchKernelGGL(counters_init_kernel, dim3((n_counters + 255) / 256), dim3(256), 0, s,
+                     a.counters, g.wgs, n_counters);
   HIP_TRY(hipGetLastError());
 
   if (p.cap == 16) {
@@ -1200,8 +1237,8 @@ int gbdt_hist_build(const void* bin_matrix, int64_t n_rows, int32_t n_features, 
   m.plan = p;
   m.n_features = n_features;
   m.n_bins = n_bins;
-  m.chunks_main = g.wgs_main;
-  m.chunks_rem = g.wgs_rem;
+  m.chunks_main = g.wgs;
+  m.chunks_rem = p.wr ? g.wgs : 0;
   const int max_slots = plan_slots(p, p.wm);
   const int mx = (n_bins * max_slots + kMergeCells - 1) / kMergeCells;
   hipLaunchKernelGGL(hist_merge_kernel, dim3(mx, plan_n_tiles(p)), dim3(kMergeCells * kMergeLanes),
@@ -1251,7 +1288,7 @@ int gbdt_debug_geometry(int32_t n_features, int32_t n_bins, int64_t n_leaf_rows,
   const TilePlan& p = g.plan;
   const int64_t v[16] = {p.cap,         p.nib,          p.wm,          p.n_main,
                          p.wr,          p.row_bytes,    p.feat_bytes,  g.nt,
-                         (int64_t)g.lds_bytes, g.wgs_main, g.wgs_rem, (int64_t)g.partial_words,
+                         (int64_t)g.lds_bytes, g.wgs, g.unit_epochs, (int64_t)g.partial_words,
                          0,             0, 0, 0};
   for (int i = 0; i < 16; ++i) out[i] = v[i];
   return GBDT_OK;

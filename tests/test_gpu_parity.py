@@ -62,6 +62,25 @@ def test_small_shapes_root_indexed_unsorted(n_rows, n_features, n_bins):
         check_split(h, ref, 1.0, 1e-3, name)
 
 
+@pytest.mark.parametrize("n_epochs,n_features,n_bins", [(2053, 28, 255), (3121, 40, 64), (2741, 70, 16)])
+def test_single_tile_long_leaf_with_a_short_last_unit(n_epochs, n_features, n_bins):
+    """One feature tile and a long leaf: every resident workgroup serves that tile, grouped
+    around shared work counters; the group slices do not divide into whole units, so short
+    last units occur (a unit worked on twice or skipped shows up in the counts)."""
+    n_rows = n_epochs * 512 - 77
+    _say(f"single tile {n_rows}x{n_features} bins={n_bins}")
+    rng = np.random.default_rng(n_epochs)
+    bins = rng.integers(0, n_bins, size=(n_rows, n_features), dtype=np.uint8)
+    grad = rng.normal(size=n_rows).astype(np.float32)
+    hess = rng.uniform(0.01, 1.0, size=n_rows).astype(np.float32)
+    p = GpuProblem(bins, n_bins, grad, hess)
+    idx = np.sort(rng.choice(n_rows, size=n_rows - 40_001, replace=False)).astype(np.int32)
+    for name, leaf in (("root", None), ("indexed", idx)):
+        h, ref = p.build(leaf), p.oracle(leaf)
+        assert_hist_close(B.hist_to_numpy(h), ref, *p.leaf_abs_sums(leaf), name)
+        check_split(h, ref, 1.0, 1e-3, name)
+
+
 def test_empty_leaf_gives_zero_histogram_and_no_split():
     rng = np.random.default_rng(0)
     bins = rng.integers(0, 64, size=(100, 9), dtype=np.uint8)

@@ -99,21 +99,24 @@ def test_tile_plan_is_a_bijection_onto_slots(n_features, n_bins):
 
 
 @pytest.mark.parametrize("n_features,n_bins", [(28, 64), (2000, 63), (28, 255), (137, 255), (700, 16), (5, 2)])
-@pytest.mark.parametrize("n_leaf", [1, 63, 64, 65, 511, 512, 513, 4000, 100_003, 10_500_000])
+@pytest.mark.parametrize("n_leaf", [1, 63, 64, 65, 511, 512, 513, 4000, 100_003, 266_000, 10_500_000])
 def test_workgroups_per_tile(n_features, n_bins, n_leaf):
     g = B.gbdt_debug_geometry(n_features, n_bins, n_leaf)
     per_byte = 2 if g["nib"] else 1
     n_epochs = (n_leaf + 511) // 512
     n_tiles = g["n_main"] + (1 if g["wr"] else 0)
+    wgs, k = g["wgs"], g["unit_epochs"]
+    # the grid fits the machine once; every workgroup's first unit exists
+    assert wgs >= 1 and k >= 1 and wgs * n_tiles <= max(256 * 4, n_tiles)
+    n_units = (n_epochs + k - 1) // k
+    assert wgs <= max(n_units, 1)
+    # units beyond a workgroup's first come from the tile's counter; the two epochs of
+    # look-ahead across a unit's end need units of at least 3 epochs then
+    assert n_units <= wgs or k >= 3
     words = 0
-    for wgs, w, tiles in ((g["wgs_main"], g["wm"], g["n_main"]), (g["wgs_rem"], g["wr"], 1 if g["wr"] else 0)):
-        if tiles == 0:
-            continue
-        # every workgroup's first epoch exists; the grid fits the machine once
-        assert 1 <= wgs <= n_epochs
-        assert wgs * n_tiles <= max(256 * 4, n_tiles)
+    for w, tiles in ((g["wm"], g["n_main"]), (g["wr"], 1 if g["wr"] else 0)):
         pages = (w * per_byte + 31) // 32
         words += tiles * wgs * 3 * g["cap"] * 32 * pages
     assert words == g["partial_words"]
     assert B.gbdt_workspace_bytes(n_leaf, n_features, n_bins) >= 4 * (g["partial_words"] + n_tiles)
-    assert (g["n_main"] * g["wgs_main"] + g["wgs_rem"]) < 2 ** 31
+    assert n_tiles * wgs < 2 ** 31
