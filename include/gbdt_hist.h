@@ -129,6 +129,17 @@ int gbdt_hist_build(const void* bin_matrix, int64_t n_rows, int32_t n_features, 
                     const float* hess, gbdt_bin_t* hist_out, void* stream);
 
 /*
+ * Bit-reproducible histograms (App. A.6 weighs precision against speed; this switch
+ * weighs run-to-run reproducibility against speed).  By default the workgroups of
+ * gbdt_hist_build share out a leaf's rows at run time, which balances them best but
+ * lets the last bits of gradient / hessian sums vary between runs.  With enable != 0
+ * (process-wide, affects later gbdt_hist_build calls) the split is fixed by the
+ * problem shape and the device: the same call then gives the same bits every time.
+ * Counts are identical in both modes.
+ */
+int gbdt_set_deterministic(int enable);
+
+/*
  * Sibling histogram: sibling_out[j][b] = parent[j][b] - child[j][b] for the
  * gradient sum, hessian sum and count.  Not described in the paper; it is the
  * complement of Alg. 1 over the parent's samples that are not in the child.

@@ -21,7 +21,7 @@ EXPORTS = [
     "gbdt_best_split", "gbdt_workspace_bytes", "gbdt_set_workspace", "gbdt_strerror",
     "gbdt_last_hip_error", "gbdt_debug_geometry", "gbdt_debug_locate",
     "gbdt_profile_enable", "gbdt_profile_collect", "gbdt_debug_occupancy",
-    "gbdt_calibration_copy",
+    "gbdt_calibration_copy", "gbdt_set_deterministic",
 ]
 
 # numpy views of the two C structs
@@ -78,6 +78,8 @@ def load():
     lib.gbdt_profile_enable.argtypes = [c.c_int]
     lib.gbdt_profile_collect.restype = c.c_int
     lib.gbdt_profile_collect.argtypes = [c.POINTER(c.c_double), c.POINTER(c.c_int64)]
+    lib.gbdt_set_deterministic.restype = c.c_int
+    lib.gbdt_set_deterministic.argtypes = [c.c_int]
     lib.gbdt_calibration_copy.restype = c.c_int
     lib.gbdt_calibration_copy.argtypes = [c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p]
     _lib = lib
@@ -214,6 +216,10 @@ def gbdt_debug_locate(n_features: int, n_bins: int, feature: int):
     _check(load().gbdt_debug_locate(n_features, n_bins, feature, ctypes.byref(t), ctypes.byref(s)),
            "gbdt_debug_locate")
     return t.value, s.value
+
+
+def gbdt_set_deterministic(enable: bool) -> None:
+    _check(load().gbdt_set_deterministic(1 if enable else 0), "gbdt_set_deterministic")
 
 
 def gbdt_calibration_copy(src: torch.Tensor, dst: torch.Tensor, stream=None) -> None:

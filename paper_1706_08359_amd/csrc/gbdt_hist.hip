@@ -2,10 +2,11 @@
 // scan for histogram-based GBDT training on AMD gfx950 (MI355X).
 // Method: arXiv 1706.08359 -- Alg. 1 (Sec. 3.3) defines the histogram, Sec. 4 /
 // Alg. 2 / App. A.1 describe a GPU organisation for older hardware.  What is
-// kept from that design: one lane handles a 4-byte bundle of features of one
-// sample; lanes that work in the same step are steered to different histograms
-// by rotating the feature order per lane; work is split by features and by
-// samples with a final reduction pass; small bin counts get cheaper variants.
+// kept from that design: one lane handles a bundle of adjacent features of one
+// sample (there 4 bytes, here up to 16); lanes that work in the same step are
+// steered to different histogram columns by rotating the feature order per lane;
+// work is split by features and by samples with a final reduction pass; small
+// bin counts get cheaper variants.
 // What is new here is stated at each kernel.
 //
 // Written for gfx950 only: 64-wide wavefronts, 160 KB LDS per CU, fast integer LDS
@@ -18,6 +19,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <atomic>
 #include <mutex>
 #include <type_traits>
 #include <utility>
@@ -77,6 +79,7 @@ struct BuildArgs {
   int32_t wr;           // remainder tile width, 0 if none
   int32_t wgs;          // workgroups per tile
   int32_t unit_epochs;  // consecutive epochs a workgroup takes at a time
+  int32_t fixed_stride; // 0: units from the tile's counter; else unit u is followed by u + this
 };
 
 // A histogram cell is ONE 64-bit integer that carries, from the low bits up, the
@@ -150,8 +153,8 @@ struct TileShape {
   static_assert(LPR == 4 || LPR == 8, "a row is shared by a quad or by two quads");
 };
 
-// Histogram of rows [begin, end) of the leaf for one feature tile, accumulated in
-// this workgroup's local memory and then written out as one partial block.
+// This workgroup's share of the histogram of leaf positions [0, end) for one feature
+// tile, accumulated in its local memory and then written out as one partial block.
 //
 // Lane mapping.  A lane loads VEC bytes of a tile row, so a row is LPR = W / VEC
 // lane-chunks and a wavefront load covers RPW = 64 / LPR rows: lane = rho * LPR + j
@@ -179,19 +182,20 @@ struct TileShape {
 // while the current epoch is accumulated; the workgroup sums their magnitudes, picks
 // the largest power-of-two scales that cannot overflow a 27-bit field, and each lane
 // quantises its own row once into a 64-bit addend that carries count, gradient and
-// hessian.  The lanes that then work on a row fetch its addend with a wavefront
-// permute, and every (row, feature) costs ONE 64-bit integer atomic.  After each
-// epoch the cells are drained into accumulators held in registers (each thread owns
-// PP cells) and cleared.
+// hessian.  The lanes that then work on a row fetch its addend with DPP moves, and
+// every (row, feature) costs ONE 64-bit integer atomic.  After each epoch the cells
+// are drained into accumulators held in registers (each thread owns PP cells) and
+// cleared.
 // Error: each value is rounded once, by at most half a quantum; the quantum is at
 // most sum|g|_epoch / (2^25 - 256), so a bin is off by at most 512 / (2^26 - 512) =
-// 7.7e-6 of the leaf's sum |g| (likewise for h) -- and integer addition is
-// order-independent, so the result is bit-reproducible.
+// 7.7e-6 of the leaf's sum |g| (likewise for h), and integer addition is
+// order-independent.  (The accumulators add one fp32 rounding per epoch on top.)
 //
-// Memory.  The bins of a wavefront's 64 rows of an epoch are loaded as two register
-// sets of U row groups; the set after next is requested before the current one is
-// added, the gradients / hessians one epoch and the row ids two epochs ahead, so
-// that requests stay in flight across the epoch barriers.
+// Memory.  The bins of a wavefront's 64 rows of an epoch sit in one register set of
+// GPE row groups; as soon as a group has been added, the same group of the next
+// epoch is requested into its registers; gradients / hessians are requested one
+// epoch and row ids two epochs ahead, so that requests stay in flight across the
+// epoch barriers and across the hand-out of work.
 //
 // All wavefronts of a workgroup share ONE histogram; no replica has to be reduced.
 template <int CAP, int W, bool NIB, int NT, typename ACC, bool INDEXED>
@@ -200,7 +204,7 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
                                            const float* __restrict__ grad,
                                            const float* __restrict__ hess, uint32_t end,
                                            uint32_t first_unit, uint32_t unit_epochs,
-                                           uint32_t* counter,
+                                           uint32_t fixed_stride, uint32_t* counter,
                                            unsigned long long* lds,
                                            uint32_t* __restrict__ out) {
   using S = TileShape<CAP, W, NIB, NT>;
@@ -210,7 +214,7 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
 
   char* cells = reinterpret_cast<char*>(lds);
   float* red = reinterpret_cast<float*>(lds + CELLS);  // [2 parities][2 stats][NW]
-  uint32_t* unit_box = reinterpret_cast<uint32_t*>(red + 4 * NW);     // the epoch just taken from the counter
+  uint32_t* unit_box = reinterpret_cast<uint32_t*>(red + 4 * NW);  // the unit just taken from the counter
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -438,6 +442,9 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
   // the counter is only used with units of at least 3 epochs; shorter units (short
   // leaves) are handed out one per workgroup, and every take from the counter fails.
   // (Units also keep a workgroup's rows together.)
+  // With fixed_stride != 0 the counter is not used: after unit u a workgroup takes unit
+  // u + fixed_stride.  The grouping of epochs into partial sums is then the same in
+  // every run, and so is every bit of the result.
   struct Pos {
     uint32_t row;  // first leaf position of the epoch; `past`: no epoch
     uint32_t idx;  // its number inside its unit
@@ -485,8 +492,13 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
   while (p0.row < end) {  // uniform over the workgroup
     const bool enters_unit = p0.idx == 0;
     uint32_t taken = 0;
-    if (enters_unit && tid == 0)
-      taken = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (enters_unit) {
+      if (fixed_stride) {
+        taken = p0.row / (unit_epochs * (uint32_t)kEpochRows) + fixed_stride;
+      } else if (tid == 0) {
+        taken = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+    }
     // ---- requests for later epochs
     const uint32_t row_nn = load_row_id(p2.row);
     const float g_nxt = load_stat(grad, row_nxt);
@@ -509,7 +521,7 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
       const bool ok = own_valid(p1.row);
       reduce_abs(ok ? fabsf(g_nxt) : 0.0f, ok ? fabsf(h_nxt) : 0.0f, (int)parity);
     }
-    if (enters_unit && tid == 0) unit_box[0] = taken;
+    if (enters_unit && !fixed_stride && tid == 0) unit_box[0] = taken;
     __syncthreads();  // all atomics of the epoch have landed
 
     // ---- drain: integer sums -> registers, clear the cells for the next epoch
@@ -517,7 +529,7 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
 #pragma unroll
     for (int m = 0; m < PP; ++m) drain_cell(m, inv_g, inv_h);
     read_scales((int)parity, kg, kh);
-    if (enters_unit) next_unit = __builtin_amdgcn_readfirstlane(unit_box[0]);
+    if (enters_unit) next_unit = __builtin_amdgcn_readfirstlane(fixed_stride ? taken : unit_box[0]);
     p0 = p1;
     p1 = p2;
     p2 = after(p2);
@@ -565,16 +577,19 @@ hist_build_kernel(BuildArgs a) {
   if (b < main_blocks) {
     uint32_t* out = a.partials + ((size_t)t * a.wgs + c) * (size_t)block_words<CAP, WM, NIB, NT>();
     build_tile<CAP, WM, NIB, NT, ACC, INDEXED>(tile, a.idx, a.grad, a.hess, n_leaf, (uint32_t)c,
-                                               (uint32_t)a.unit_epochs, counter, lds, out);
+                                               (uint32_t)a.unit_epochs, (uint32_t)a.fixed_stride, counter,
+                                               lds, out);
   } else {
     uint32_t* rem_base = a.partials + (size_t)main_blocks * (size_t)block_words<CAP, WM, NIB, NT>();
     if (a.wr == 16) {
       build_tile<CAP, 16, NIB, NT, ACC, INDEXED>(
-          tile, a.idx, a.grad, a.hess, n_leaf, (uint32_t)c, (uint32_t)a.unit_epochs, counter, lds,
+          tile, a.idx, a.grad, a.hess, n_leaf, (uint32_t)c, (uint32_t)a.unit_epochs,
+          (uint32_t)a.fixed_stride, counter, lds,
           rem_base + (size_t)c * (size_t)block_words<CAP, 16, NIB, NT>());
     } else if constexpr (WM > 32) {
       build_tile<CAP, 32, NIB, NT, ACC, INDEXED>(
-          tile, a.idx, a.grad, a.hess, n_leaf, (uint32_t)c, (uint32_t)a.unit_epochs, counter, lds,
+          tile, a.idx, a.grad, a.hess, n_leaf, (uint32_t)c, (uint32_t)a.unit_epochs,
+          (uint32_t)a.fixed_stride, counter, lds,
           rem_base + (size_t)c * (size_t)block_words<CAP, 32, NIB, NT>());
     }
   }
@@ -912,6 +927,8 @@ int hip_fail(hipError_t e, const char* what) {
     if (e_ != hipSuccess) return hip_fail(e_, #expr);  \
   } while (0)
 
+std::atomic<int> g_deterministic{0};
+
 struct Workspace {
   std::mutex mu;
   void* own = nullptr;  // library-owned scratch
@@ -1215,6 +1232,7 @@ int gbdt_hist_build(const void* bin_matrix, int64_t n_rows, int32_t n_features, 
   a.wr = p.wr;
   a.wgs = g.wgs;
   a.unit_epochs = g.unit_epochs;
+  a.fixed_stride = g_deterministic.load() ? g.wgs : 0;
   const int n_tiles = plan_n_tiles(p);
   const int blocks = n_tiles * g.wgs;
   const int n_counters = (int)g.counter_words;
@@ -1308,6 +1326,11 @@ int gbdt_debug_locate(int32_t n_features, int32_t n_bins, int32_t feature, int32
   const FeatureSlot fs = plan_locate(p, feature);
   *tile_out = fs.tile;
   *slot_out = fs.slot;
+  return GBDT_OK;
+}
+
+int gbdt_set_deterministic(int enable) {
+  g_deterministic.store(enable != 0);
   return GBDT_OK;
 }
 

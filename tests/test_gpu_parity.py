@@ -123,6 +123,32 @@ def test_counts_are_reproducible_and_sums_stable():
         assert np.abs(a["grad"].astype(np.float64) - b["grad"]).max() <= 1e-5 * sg
 
 
+def test_deterministic_mode_is_bit_reproducible():
+    w = synth.config4_ranking_sparse(n_rows=700_000, fractions=(1.0, 0.5))
+    p = GpuProblem(w.bins, w.n_bins, w.grad, w.hess)
+    try:
+        B.gbdt_set_deterministic(True)
+        for leaf in w.leaves:
+            a = B.hist_to_numpy(p.build(leaf))
+            ref = p.oracle(leaf)
+            assert_hist_close(a, ref, *p.leaf_abs_sums(leaf), "deterministic")
+            for _ in range(3):
+                b = B.hist_to_numpy(p.build(leaf))
+                assert a.tobytes() == b.tobytes()
+    finally:
+        B.gbdt_set_deterministic(False)
+    # the default mode agrees with it to the tolerance (and exactly in the counts)
+    c = B.hist_to_numpy(p.build(w.leaves[0]))
+    B.gbdt_set_deterministic(True)
+    try:
+        d = B.hist_to_numpy(p.build(w.leaves[0]))
+    finally:
+        B.gbdt_set_deterministic(False)
+    assert (c["count"] == d["count"]).all()
+    sg, sh = p.leaf_abs_sums(w.leaves[0])
+    assert np.abs(c["grad"].astype(np.float64) - d["grad"]).max() <= 1e-5 * sg
+
+
 def test_subtract_matches_oracle_and_may_alias():
     rng = np.random.default_rng(11)
     n, F, nb = 40_000, 90, 64
@@ -166,6 +192,51 @@ def test_user_workspace_and_too_small_workspace():
     finally:
         B.gbdt_set_workspace(None)
     assert (B.hist_to_numpy(p.build())["count"] == ref["count"]).all()
+
+
+def test_graph_capture_replays_match_eager():
+    """build + subtract + best split captured into one graph and replayed with changing
+    inputs; every replay is checked against the eager result (the calls clear memory with
+    fill kernels, not memset nodes)."""
+    w = synth.config2_dense_wide(n_rows=80_000, n_features=300, with_leaves=False)
+    p = GpuProblem(w.bins, w.n_bins, w.grad, w.hess)
+    n, F, nb = p.n_rows, p.n_features, p.n_bins
+    idx = torch.arange(0, n, 3, dtype=torch.int32, device="cuda:0")
+    parent = p.build()
+    hist, sib = torch.empty_like(parent), torch.empty_like(parent)
+    split = torch.empty(9, dtype=torch.int32, device="cuda:0")
+
+    def step(h, s_, sp):
+        B.gbdt_hist_build(p.packed, n, F, nb, idx, idx.numel(), p.grad, p.hess, hist_out=h)
+        B.gbdt_hist_subtract(parent, h, sibling_out=s_)
+        B.gbdt_best_split(h, w.lam, w.min_child_hess, split_out=sp)
+
+    B.gbdt_set_deterministic(True)          # so that replays can be compared bit for bit
+    try:
+        step(hist, sib, split)              # warm-up: workspace and occupancy query outside the capture
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step(hist, sib, split)
+        e_hist, e_sib = torch.empty_like(parent), torch.empty_like(parent)
+        e_split = torch.empty_like(split)
+        for trial in range(4):
+            p.grad.mul_(-1.25).add_(0.01 * trial)      # the program's own eager work between replays
+            p.hess.mul_(0.9).add_(0.05)
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            step(e_hist, e_sib, e_split)
+            torch.cuda.synchronize()
+            assert torch.equal(hist.view(torch.int32), e_hist.view(torch.int32)), trial
+            assert torch.equal(sib.view(torch.int32), e_sib.view(torch.int32)), trial
+            assert torch.equal(split, e_split), trial
+        # and the last replay against the oracle
+        ref = orc.hist_build(p.bins_cpu.numpy(), nb, p.grad.cpu().numpy(), p.hess.cpu().numpy(), idx.cpu().numpy())
+        g64, h64 = p.grad[idx.long()].double(), p.hess[idx.long()].double()
+        assert_hist_close(B.hist_to_numpy(hist), ref, g64.abs().sum().item(), h64.abs().sum().item(), "graph")
+    finally:
+        B.gbdt_set_deterministic(False)
 
 
 def test_runs_on_a_side_stream():
