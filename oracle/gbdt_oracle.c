@@ -11,8 +11,10 @@
  * Pins (all in tests/, CPU only): numpy.bincount per feature, the per-feature
  * sum invariant, a closed form for constant hessians, parent = left + right,
  * brute-force enumeration of every (feature, threshold) from raw rows, the
- * square-loss special case of Eq. (4), and a planted split.  Nothing here is
- * "parity unpinned".
+ * square-loss special case of Eq. (4), and a planted split; for the row
+ * partition a per-row loop over raw values, the disjoint-ordered-cover
+ * invariant and agreement of its child sizes with the counts the split search
+ * derived from the histogram.  Nothing here is "parity unpinned".
  *
  * Build: gcc -O2 -ffp-contract=off -fopenmp -shared -fPIC gbdt_oracle.c
  */
@@ -202,5 +204,45 @@ int oracle_best_split(const oracle_bin_t *hist, int32_t n_features,
           (0.0 / 0.0);
   }
   *split_out = best;
+  return 0;
+}
+
+/*
+ * Split() of App. C.1: hand the samples of a node to its two children, given
+ * the feature and the threshold bin the split search chose.  A sample goes left
+ * when its bin of that feature is <= the threshold (the convention of
+ * oracle_best_split) and right otherwise; each child keeps the samples in the
+ * order the parent listed them, so sorted index lists stay sorted.  This is the
+ * per-leaf index list the CPU maintains and ships after every split in
+ * App. A.5.  leaf_row_idx == NULL means the node is rows 0..n_leaf_rows-1.
+ * left_out and right_out each have room for n_leaf_rows entries.
+ * Returns 0, or -1 on a bad argument or an out-of-range row id.
+ */
+int oracle_partition_rows(const uint8_t *bins, int64_t n_rows,
+                          int32_t n_features, const int32_t *leaf_row_idx,
+                          int64_t n_leaf_rows, int32_t feature,
+                          int32_t threshold_bin, int32_t *left_out,
+                          int64_t *n_left_out, int32_t *right_out,
+                          int64_t *n_right_out) {
+  if (!bins || !left_out || !right_out || !n_left_out || !n_right_out)
+    return -1;
+  if (n_rows < 0 || n_features <= 0 || n_leaf_rows < 0) return -1;
+  if (feature < 0 || feature >= n_features) return -1;
+  if (!leaf_row_idx && n_leaf_rows > n_rows) return -1;
+  int64_t nl = 0, nr = 0;
+  for (int64_t i = 0; i < n_leaf_rows; ++i) {
+    int64_t d = leaf_row_idx ? (int64_t)leaf_row_idx[i] : i;
+    if (d < 0 || d >= n_rows) return -1;
+    int32_t b = bins[(size_t)d * (size_t)n_features + (size_t)feature];
+    if (b <= threshold_bin) {
+      left_out[nl] = (int32_t)d;
+      nl = nl + 1;
+    } else {
+      right_out[nr] = (int32_t)d;
+      nr = nr + 1;
+    }
+  }
+  *n_left_out = nl;
+  *n_right_out = nr;
   return 0;
 }

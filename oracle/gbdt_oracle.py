@@ -63,6 +63,11 @@ def _load():
         lib.oracle_best_split.restype = c.c_int
         lib.oracle_best_split.argtypes = [c.c_void_p, c.c_int32, c.c_int32, c.c_double,
                                           c.c_double, c.POINTER(_Split), c.c_void_p]
+        lib.oracle_partition_rows.restype = c.c_int
+        lib.oracle_partition_rows.argtypes = [c.c_void_p, c.c_int64, c.c_int32, c.c_void_p,
+                                              c.c_int64, c.c_int32, c.c_int32, c.c_void_p,
+                                              c.POINTER(c.c_int64), c.c_void_p,
+                                              c.POINTER(c.c_int64)]
         lib.oracle_num_threads.restype = c.c_int
         lib.oracle_set_num_threads.argtypes = [c.c_int]
         _lib = lib
@@ -129,6 +134,32 @@ def best_split(hist, lam, min_child_hess, return_gains=False):
         raise ValueError("oracle_best_split: bad argument")
     d = {name: getattr(s, name) for name, _ in _Split._fields_}
     return (d, gains) if return_gains else d
+
+
+def partition_rows(bins, feature, threshold_bin, leaf_row_idx=None, n_leaf_rows=None):
+    """Split() of App. C.1: (left, right) int32 row-id arrays, parent order kept.
+
+    left = rows whose bin of `feature` is <= threshold_bin.
+    """
+    bins = np.ascontiguousarray(bins, dtype=np.uint8)
+    assert bins.ndim == 2
+    n_rows, n_features = bins.shape
+    if leaf_row_idx is None:
+        idx_p = None
+        n_leaf = n_rows if n_leaf_rows is None else int(n_leaf_rows)
+    else:
+        leaf_row_idx = np.ascontiguousarray(leaf_row_idx, dtype=np.int32)
+        idx_p = leaf_row_idx.ctypes.data
+        n_leaf = leaf_row_idx.shape[0] if n_leaf_rows is None else int(n_leaf_rows)
+    left = np.empty(max(n_leaf, 1), dtype=np.int32)
+    right = np.empty(max(n_leaf, 1), dtype=np.int32)
+    nl, nr = ctypes.c_int64(0), ctypes.c_int64(0)
+    rc = _load().oracle_partition_rows(bins.ctypes.data, n_rows, n_features, idx_p, n_leaf,
+                                       int(feature), int(threshold_bin), left.ctypes.data,
+                                       ctypes.byref(nl), right.ctypes.data, ctypes.byref(nr))
+    if rc != 0:
+        raise ValueError("oracle_partition_rows: bad argument or row id")
+    return left[:nl.value].copy(), right[:nr.value].copy()
 
 
 def from_f32_hist(grad, hess, count):

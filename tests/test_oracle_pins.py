@@ -275,3 +275,80 @@ def test_from_f32_hist_is_exact():
     c = np.array([[3, 4]], dtype=np.uint32)
     h = orc.from_f32_hist(g, g, c)
     assert h["grad"][0, 1] == -2.25 and h["count"][0, 1] == 4 and h.dtype == orc.BIN_DTYPE
+
+
+# ------------------------------------------------------------ row partition (App. C.1, Split())
+
+@pytest.mark.parametrize("seed", [0, 1, 2, 3])
+def test_partition_equals_per_row_loop(seed):
+    """Pin: a pure-Python walk over the raw matrix, no numpy masking, no C."""
+    rng = np.random.default_rng(900 + seed)
+    n, F, B = 157, 6, 11
+    bins = rng.integers(0, B, size=(n, F), dtype=np.uint8)
+    rows = np.sort(rng.choice(n, size=int(rng.integers(1, n)), replace=False)).astype(np.int32)
+    if seed == 3:
+        rows = rng.permutation(rows).astype(np.int32)     # order must be kept, sorted or not
+    f, t = int(rng.integers(0, F)), int(rng.integers(0, B - 1))
+    left, right = orc.partition_rows(bins, f, t, rows)
+    want_l = [int(r) for r in rows if int(bins[int(r)][f]) <= t]
+    want_r = [int(r) for r in rows if int(bins[int(r)][f]) > t]
+    assert left.tolist() == want_l and right.tolist() == want_r
+
+
+def test_partition_is_an_ordered_disjoint_cover():
+    rng = np.random.default_rng(77)
+    n, F, B = 5000, 9, 64
+    bins = rng.integers(0, B, size=(n, F), dtype=np.uint8)
+    rows = np.sort(rng.choice(n, size=3211, replace=False)).astype(np.int32)
+    left, right = orc.partition_rows(bins, 4, 20, rows)
+    assert left.size + right.size == rows.size
+    assert np.array_equal(np.sort(np.concatenate([left, right])), rows)
+    assert np.all(np.diff(left) > 0) and np.all(np.diff(right) > 0)
+    assert np.all(bins[left, 4] <= 20) and np.all(bins[right, 4] > 20)
+    # the feature is the one asked for, not a neighbour, and the comparison is <=, not <
+    assert not np.array_equal(left, rows[bins[rows, 3] <= 20])
+    assert not np.array_equal(left, rows[bins[rows, 4] < 20])
+
+
+def test_partition_root_and_degenerate_thresholds():
+    rng = np.random.default_rng(5)
+    bins = rng.integers(0, 16, size=(300, 3), dtype=np.uint8)
+    left, right = orc.partition_rows(bins, 1, 7)                       # NULL index list = all rows
+    assert np.array_equal(left, np.nonzero(bins[:, 1] <= 7)[0])
+    assert np.array_equal(right, np.nonzero(bins[:, 1] > 7)[0])
+    left, right = orc.partition_rows(bins, 1, 7, None, n_leaf_rows=100)  # ... or a prefix of them
+    assert np.array_equal(left, np.nonzero(bins[:100, 1] <= 7)[0])
+    left, right = orc.partition_rows(bins, 0, 255)
+    assert left.size == 300 and right.size == 0
+    left, right = orc.partition_rows(bins, 0, -1)
+    assert left.size == 0 and right.size == 300
+    left, right = orc.partition_rows(bins, 2, 3, np.zeros(0, np.int32))
+    assert left.size == 0 and right.size == 0
+    with pytest.raises(ValueError):
+        orc.partition_rows(bins, 3, 1)                                  # no such feature
+    with pytest.raises(ValueError):
+        orc.partition_rows(bins, 0, 1, np.array([300], np.int32))       # no such row
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_partition_sizes_and_sums_match_the_split_record(seed):
+    """Two routes to the children: the split search derives their counts and sums from the
+    parent's histogram; the partition walks the rows.  They must describe the same children,
+    and the children's own histograms must add up to the parent's."""
+    rng = np.random.default_rng(40 + seed)
+    n, F, B = 2000, 7, 32
+    bins = rng.integers(0, B, size=(n, F), dtype=np.uint8)
+    grad = rng.normal(size=n).astype(np.float32)
+    hess = rng.uniform(0.1, 1.0, size=n).astype(np.float32)
+    rows = np.sort(rng.choice(n, size=1500, replace=False)).astype(np.int32)
+    parent = orc.hist_build(bins, B, grad, hess, rows)
+    s = orc.best_split(parent, 1.0, 1e-3)
+    assert s["feature"] >= 0
+    left, right = orc.partition_rows(bins, s["feature"], s["bin"], rows)
+    assert left.size == s["left_count"] and right.size == s["right_count"]
+    assert np.isclose(grad[left].astype(np.float64).sum(), s["left_grad"], rtol=0, atol=1e-9)
+    assert np.isclose(hess[right].astype(np.float64).sum(), s["right_hess"], rtol=0, atol=1e-9)
+    hl = orc.hist_build(bins, B, grad, hess, left)
+    hr = orc.hist_build(bins, B, grad, hess, right)
+    assert np.array_equal(hl["count"] + hr["count"], parent["count"])
+    assert np.allclose(hl["grad"] + hr["grad"], parent["grad"], rtol=0, atol=1e-9)
