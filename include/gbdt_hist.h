@@ -1,8 +1,8 @@
 /*
  * gbdt_hist.h -- C ABI of libgbdt_hist: feature-histogram construction for the
  * leaves of a histogram-based gradient-boosted decision tree, the sibling
- * histogram by subtraction, and the best-split gain scan, on one AMD gfx950
- * (MI355X) GPU.  Method: "GPU-acceleration for Large-scale Tree Boosting"
+ * histogram by subtraction, the best-split gain scan and the row partition that
+ * follows a split, on one AMD gfx950 (MI355X) GPU.  Method: "GPU-acceleration for Large-scale Tree Boosting"
  * (arXiv 1706.08359), Sec. 3.3 / Alg. 1 (what a feature histogram is), Sec. 4
  * (building many of them at once on a GPU), App. C.4 (4-bit bins).
  *
@@ -20,8 +20,9 @@
  *  - Bins are 0-based: a binned value b satisfies 0 <= b < n_bins (the paper
  *    writes 1..k).  2 <= n_bins <= 256.
  *  - The library keeps one scratch workspace per process (partial histograms,
- *    split candidates).  Calls that use it (gbdt_hist_build, gbdt_best_split)
- *    must not run concurrently on different streams.
+ *    split candidates, partition flags).  Calls that use it (gbdt_hist_build,
+ *    gbdt_best_split, gbdt_partition_rows) must not run concurrently on different
+ *    streams.
  */
 #ifndef GBDT_HIST_H_
 #define GBDT_HIST_H_
@@ -167,12 +168,43 @@ int gbdt_best_split(const gbdt_bin_t* hist, float lambda, float min_child_hess,
                     gbdt_split_t* split_out, int32_t n_features, int32_t n_bins, void* stream);
 
 /*
+ * Row partition of a leaf into its two children (the Split() step of App. C.1; it
+ * produces the per-leaf sample index list that App. A.5 has the CPU rebuild and copy
+ * to the GPU after every split -- here the list never leaves the device).
+ * A leaf row with row id d goes left when bin(d, split->feature) <= split->bin, right
+ * otherwise -- the convention of gbdt_split_t.  children_out receives the left rows,
+ * then the right rows, each side in the order the parent listed them (ascending lists
+ * stay ascending), so the children are children_out[0 .. n_left) and
+ * children_out[n_left .. n_leaf_rows) and both can be passed to gbdt_hist_build as
+ * leaf_row_idx.  n_left equals split->left_count when the record came from the leaf's own
+ * histogram.
+ *   bin_matrix     DEVICE, layout written by gbdt_bins_pack with the same n_rows,
+ *                  n_features, n_bins
+ *   leaf_row_idx   DEVICE int32 [n_leaf_rows] or NULL (rows 0..n_leaf_rows-1), as in
+ *                  gbdt_hist_build
+ *   split          DEVICE, one gbdt_split_t (e.g. as written by gbdt_best_split); only
+ *                  feature and bin are read, on the device.  A feature outside
+ *                  [0, n_features) -- such as the -1 of "no admissible split" -- sends
+ *                  every row left.
+ *   children_out   DEVICE int32 [n_leaf_rows], fully overwritten; must not overlap
+ *                  leaf_row_idx
+ *   n_left_out     DEVICE int64 [1], receives the number of left rows; may be NULL
+ * Uses the scratch workspace (n_leaf_rows / 8 bytes of flags plus a few KiB).  Exact
+ * integer work: the result is unique and reproducible.
+ */
+int gbdt_partition_rows(const void* bin_matrix, int64_t n_rows, int32_t n_features,
+                        int32_t n_bins, const int32_t* leaf_row_idx, int64_t n_leaf_rows,
+                        const gbdt_split_t* split, int32_t* children_out, int64_t* n_left_out,
+                        void* stream);
+
+/*
  * Scratch workspace.  By default the library allocates device scratch itself
  * on first use and grows it when a larger problem arrives (hipMalloc inside
- * gbdt_hist_build / gbdt_best_split).  A caller that wants no allocation in
+ * gbdt_hist_build / gbdt_best_split / gbdt_partition_rows).  A caller that wants no allocation in
  * those calls registers its own buffer:
- *   gbdt_workspace_bytes  upper bound on scratch needed by gbdt_hist_build and
- *                         gbdt_best_split for this problem shape on the
+ *   gbdt_workspace_bytes  upper bound on scratch needed by gbdt_hist_build,
+ *                         gbdt_best_split and gbdt_partition_rows (leaves of at
+ *                         most n_rows entries) for this problem shape on the
  *                         current device (0 on invalid arguments)
  *   gbdt_set_workspace    DEVICE buffer, 256-byte aligned, kept until replaced;
  *                         (NULL, 0) returns to library-owned scratch.  With a

@@ -21,7 +21,7 @@ EXPORTS = [
     "gbdt_best_split", "gbdt_workspace_bytes", "gbdt_set_workspace", "gbdt_strerror",
     "gbdt_last_hip_error", "gbdt_debug_geometry", "gbdt_debug_locate",
     "gbdt_profile_enable", "gbdt_profile_collect", "gbdt_debug_occupancy",
-    "gbdt_calibration_copy", "gbdt_set_deterministic",
+    "gbdt_calibration_copy", "gbdt_set_deterministic", "gbdt_partition_rows",
 ]
 
 # numpy views of the two C structs
@@ -60,6 +60,9 @@ def load():
     lib.gbdt_best_split.restype = c.c_int
     lib.gbdt_best_split.argtypes = [c.c_void_p, c.c_float, c.c_float, c.c_void_p, c.c_int32,
                                     c.c_int32, c.c_void_p]
+    lib.gbdt_partition_rows.restype = c.c_int
+    lib.gbdt_partition_rows.argtypes = [c.c_void_p, c.c_int64, c.c_int32, c.c_int32, c.c_void_p,
+                                        c.c_int64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p]
     lib.gbdt_workspace_bytes.restype = c.c_size_t
     lib.gbdt_workspace_bytes.argtypes = [c.c_int64, c.c_int32, c.c_int32]
     lib.gbdt_set_workspace.restype = c.c_int
@@ -191,6 +194,39 @@ def gbdt_best_split(hist, lam, min_child_hess, split_out=None, stream=None):
                                   float(min_child_hess), _dev(split_out, torch.int32, "split_out"),
                                   n_features, n_bins, _stream(stream)), "gbdt_best_split")
     return split_out
+
+
+def gbdt_partition_rows(bin_matrix, n_rows, n_features, n_bins, leaf_row_idx, n_leaf_rows, split,
+                        children_out=None, n_left_out=None, stream=None):
+    """split: int32 CUDA tensor [9] holding one gbdt_split_t (as gbdt_best_split returns it).
+    Returns (children_out int32 [n_leaf_rows]: left rows then right rows, n_left_out int64 [1])."""
+    idx_p = None if leaf_row_idx is None else _dev(leaf_row_idx, torch.int32, "leaf_row_idx")
+    if leaf_row_idx is not None and leaf_row_idx.numel() < n_leaf_rows:
+        raise GbdtError("leaf_row_idx shorter than n_leaf_rows")
+    if bin_matrix.numel() < gbdt_bins_packed_bytes(n_rows, n_features, n_bins):
+        raise GbdtError("bin_matrix smaller than the packed layout of this shape")
+    if split.numel() < 9:
+        raise GbdtError("split: expected one gbdt_split_t (9 words)")
+    if children_out is None:
+        children_out = torch.empty(max(n_leaf_rows, 1), dtype=torch.int32, device=bin_matrix.device)
+    elif children_out.numel() < n_leaf_rows:
+        raise GbdtError("children_out too small")
+    if n_left_out is None:
+        n_left_out = torch.empty(1, dtype=torch.int64, device=bin_matrix.device)
+    _check(load().gbdt_partition_rows(_dev(bin_matrix, torch.uint8, "bin_matrix"), n_rows,
+                                      n_features, n_bins, idx_p, n_leaf_rows,
+                                      _dev(split, torch.int32, "split"),
+                                      _dev(children_out, torch.int32, "children_out"),
+                                      _dev(n_left_out, torch.int64, "n_left_out"),
+                                      _stream(stream)), "gbdt_partition_rows")
+    return children_out, n_left_out
+
+
+def split_record(feature: int, bin_: int, device) -> torch.Tensor:
+    """A gbdt_split_t on the device that carries only a (feature, threshold bin) pair."""
+    a = np.zeros(1, dtype=SPLIT_DTYPE)
+    a["feature"], a["bin"] = feature, bin_
+    return torch.from_numpy(a.view(np.int32).copy()).to(device)
 
 
 GEOMETRY_FIELDS = ["cap", "nib", "wm", "n_main", "wr", "row_bytes", "feat_bytes", "threads",

@@ -902,6 +902,159 @@ split_argmax_kernel(const SplitCand* __restrict__ cand, int32_t n_cand,
   }
 }
 
+// ------------------------------------------------------------- partition kernels
+
+// Split() of App. C.1 on the device: the rows of a leaf are handed to its two children
+// by the bin of one feature, left rows (bin <= threshold) first, each side in the
+// parent's order.  The paper leaves this step on the CPU and copies the new index list to
+// the GPU after every split (App. A.5); with the list kept in HBM nothing is copied.
+//
+// Two passes over chunks of kPartThreads * rows_per_thread consecutive leaf positions,
+// one workgroup per chunk, no waiting between workgroups:
+//   1. flag pass: fetch each row's bin, ballot "goes left" into one 64-bit word per
+//      (wavefront, step) and count the chunk's left rows;
+//   2. scatter pass: every workgroup sums the chunk counts before its own (at most
+//      kPartMaxChunks of them) to find where its rows start on either side, then ranks
+//      its rows inside the chunk from the flag words and writes the row ids.
+// The flag words save the second pass the scattered read of the bin matrix, which is
+// by far the larger part of the traffic (one 32- or 64-byte tile row per leaf row).
+constexpr int kPartThreads = 256;
+constexpr int kPartWaves = kPartThreads / 64;
+constexpr int kPartMaxChunks = 8192;
+
+struct PartGeom {
+  int32_t rows_per_thread;  // steps of kPartThreads rows a workgroup takes
+  int32_t n_chunks;
+  size_t flag_words;        // 64-bit words
+  size_t bytes;             // flags, then one 32-bit count per chunk
+};
+
+PartGeom make_part_geom(int64_t n_leaf) {
+  PartGeom g;
+  g.rows_per_thread = 8;
+  while ((n_leaf + (int64_t)kPartThreads * g.rows_per_thread - 1) /
+             ((int64_t)kPartThreads * g.rows_per_thread) > kPartMaxChunks)
+    g.rows_per_thread *= 2;
+  const int64_t chunk_rows = (int64_t)kPartThreads * g.rows_per_thread;
+  g.n_chunks = (int32_t)((n_leaf + chunk_rows - 1) / chunk_rows);
+  g.flag_words = (size_t)g.n_chunks * g.rows_per_thread * kPartWaves;
+  g.bytes = g.flag_words * 8 + (size_t)g.n_chunks * 4;
+  return g;
+}
+
+__global__ void __launch_bounds__(kPartThreads)
+partition_flag_kernel(const uint8_t* __restrict__ packed, int64_t n_rows, int32_t n_features,
+                      TilePlan plan, const int32_t* __restrict__ idx, int64_t n_leaf,
+                      const gbdt_split_t* __restrict__ split, int32_t rows_per_thread,
+                      uint64_t* __restrict__ flags, uint32_t* __restrict__ chunk_left) {
+  __shared__ uint32_t s_left[kPartWaves];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int32_t f = split->feature;
+  const int32_t thr = split->bin;
+  const bool has_split = f >= 0 && f < n_features;
+  // byte of the tile row that holds feature f, and the bits of it that are f's bin
+  int64_t tile_off = 0;
+  int32_t w = plan.wm, col = 0, shift = 0;
+  uint32_t mask = 0xffu;
+  if (has_split) {
+    const int32_t fb = plan.nib ? (f >> 1) : f;
+    int32_t t = fb / plan.wm;
+    if (t > plan.n_main) t = plan.n_main;
+    w = plan_tile_width(plan, t);
+    col = fb - t * plan.wm;
+    tile_off = n_rows * ((int64_t)t * plan.wm);
+    if (plan.nib) {
+      shift = (f & 1) ? 4 : 0;
+      mask = 15u;
+    }
+  }
+  const int64_t chunk_base = (int64_t)blockIdx.x * kPartThreads * rows_per_thread;
+  uint64_t* my_flags = flags + (size_t)blockIdx.x * rows_per_thread * kPartWaves;
+  uint32_t wave_left = 0;
+  for (int32_t k = 0; k < rows_per_thread; ++k) {
+    const int64_t e = chunk_base + (int64_t)k * kPartThreads + tid;
+    bool left = false;
+    if (e < n_leaf) {
+      left = true;
+      if (has_split) {
+        int64_t r = idx ? (int64_t)idx[e] : e;
+        r = r < 0 ? 0 : (r >= n_rows ? n_rows - 1 : r);  // a bad row id must not fault
+        const uint32_t b = ((uint32_t)packed[tile_off + r * w + col] >> shift) & mask;
+        left = (int32_t)b <= thr;
+      }
+    }
+    const uint64_t m = __ballot(left);
+    if (lane == 0) my_flags[k * kPartWaves + wave] = m;
+    wave_left += (uint32_t)__popcll(m);
+  }
+  if (lane == 0) s_left[wave] = wave_left;
+  __syncthreads();
+  if (tid == 0) {
+    uint32_t c = 0;
+#pragma unroll
+    for (int i = 0; i < kPartWaves; ++i) c += s_left[i];
+    chunk_left[blockIdx.x] = c;
+  }
+}
+
+__global__ void __launch_bounds__(kPartThreads)
+partition_scatter_kernel(const int32_t* __restrict__ idx, int64_t n_leaf, int32_t rows_per_thread,
+                         const uint64_t* __restrict__ flags, const uint32_t* __restrict__ chunk_left,
+                         int32_t n_chunks, int32_t* __restrict__ out, int64_t* __restrict__ n_left_out) {
+  __shared__ int64_t s_before[kPartWaves], s_total[kPartWaves];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int32_t chunk = blockIdx.x;
+  // left rows in the chunks before this one, and in the whole leaf
+  int64_t before = 0, total = 0;
+  for (int32_t c = tid; c < n_chunks; c += kPartThreads) {
+    const int64_t v = chunk_left[c];
+    total += v;
+    if (c < chunk) before += v;
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    before += __shfl_xor(before, o);
+    total += __shfl_xor(total, o);
+  }
+  if (lane == 0) {
+    s_before[wave] = before;
+    s_total[wave] = total;
+  }
+  __syncthreads();
+  before = 0;
+  total = 0;
+#pragma unroll
+  for (int i = 0; i < kPartWaves; ++i) {
+    before += s_before[i];
+    total += s_total[i];
+  }
+  if (chunk == 0 && tid == 0 && n_left_out) *n_left_out = total;
+
+  const int64_t chunk_base = (int64_t)chunk * kPartThreads * rows_per_thread;
+  const uint64_t* my_flags = flags + (size_t)chunk * rows_per_thread * kPartWaves;
+  const uint64_t below = lane == 0 ? 0ull : (~0ull >> (64 - lane));
+  int64_t left_pos = before;  // left rows before the current step
+  for (int32_t k = 0; k < rows_per_thread; ++k) {
+    uint64_t m = 0;
+    int64_t wave_base = left_pos;
+#pragma unroll
+    for (int i = 0; i < kPartWaves; ++i) {
+      const uint64_t mi = my_flags[k * kPartWaves + i];
+      const int64_t ci = __popcll(mi);
+      if (i < wave) wave_base += ci;
+      if (i == wave) m = mi;
+      left_pos += ci;
+    }
+    const int64_t e = chunk_base + (int64_t)k * kPartThreads + tid;
+    if (e < n_leaf) {
+      const int32_t r = idx ? idx[e] : (int32_t)e;
+      const int64_t lefts_before_e = wave_base + __popcll(m & below);
+      const bool left = (m >> lane) & 1ull;
+      out[left ? lefts_before_e : total + (e - lefts_before_e)] = r;
+    }
+  }
+}
+
 // ------------------------------------------------------- calibration copy kernel
 
 // Plain copy of n 16-byte words: a kernel of known HBM traffic (n * 16 bytes read, n *
@@ -1179,6 +1332,8 @@ size_t gbdt_workspace_bytes(int64_t n_rows, int32_t n_features, int32_t n_bins) 
   split_grouping(n_features, n_bins, &sg, &sn);
   const size_t cand = (size_t)sn * sizeof(SplitCand);
   if (cand > b) b = cand;
+  const size_t part = make_part_geom(n_rows > 0 ? n_rows : 1).bytes;
+  if (part > b) b = part;
   return (b + 255) / 256 * 256;
 }
 
@@ -1294,6 +1449,36 @@ int gbdt_best_split(const gbdt_bin_t* hist, float lambda, float min_child_hess,
   HIP_TRY(hipGetLastError());
   hipLaunchKernelGGL(split_argmax_kernel, dim3(1), dim3(256), 0, s, (const SplitCand*)ws,
                      n_groups, split_out);
+  HIP_TRY(hipGetLastError());
+  return GBDT_OK;
+}
+
+int gbdt_partition_rows(const void* bin_matrix, int64_t n_rows, int32_t n_features,
+                        int32_t n_bins, const int32_t* leaf_row_idx, int64_t n_leaf_rows,
+                        const gbdt_split_t* split, int32_t* children_out, int64_t* n_left_out,
+                        void* stream) {
+  if (!valid_shape(n_rows, n_features, n_bins)) return GBDT_EINVAL;
+  if (!bin_matrix || !split || !children_out) return GBDT_EINVAL;
+  if (n_leaf_rows < 0) return GBDT_EINVAL;
+  if (!leaf_row_idx && n_leaf_rows > n_rows) return GBDT_EINVAL;
+  if (n_rows == 0 && n_leaf_rows > 0) return GBDT_EINVAL;
+  if (n_rows >= ((int64_t)1 << 30) || n_leaf_rows >= ((int64_t)1 << 31)) return GBDT_EUNSUPPORTED;
+  hipStream_t s = (hipStream_t)stream;
+  const PartGeom g = make_part_geom(n_leaf_rows > 0 ? n_leaf_rows : 1);
+  void* ws = nullptr;
+  int rc = get_workspace(g.bytes, &ws);
+  if (rc != GBDT_OK) return rc;
+  uint64_t* flags = (uint64_t*)ws;
+  uint32_t* chunk_left = (uint32_t*)(flags + g.flag_words);
+  const TilePlan p = make_tile_plan(n_features, n_bins);
+  // an empty leaf still runs one workgroup, which writes n_left_out = 0
+  hipLaunchKernelGGL(partition_flag_kernel, dim3(g.n_chunks), dim3(kPartThreads), 0, s,
+                     (const uint8_t*)bin_matrix, n_rows, n_features, p, leaf_row_idx, n_leaf_rows,
+                     split, g.rows_per_thread, flags, chunk_left);
+  HIP_TRY(hipGetLastError());
+  hipLaunchKernelGGL(partition_scatter_kernel, dim3(g.n_chunks), dim3(kPartThreads), 0, s,
+                     leaf_row_idx, n_leaf_rows, g.rows_per_thread, (const uint64_t*)flags,
+                     (const uint32_t*)chunk_left, g.n_chunks, children_out, n_left_out);
   HIP_TRY(hipGetLastError());
   return GBDT_OK;
 }
