@@ -9,6 +9,8 @@ CPU oracle is timed beside it on a bounded sample of the same leaf.
     python -m paper_1706_08359_amd.measure_all                # the five workloads
     python -m paper_1706_08359_amd.measure_all --depth-sweep  # App. C.2: 8,000,000 x 500, leaf = N / 2^D
     python -m paper_1706_08359_amd.measure_all --skew         # App. A.3: constant-bin features
+    python -m paper_1706_08359_amd.measure_all --partition    # row partition after a split (App. C.1)
+    python -m paper_1706_08359_amd.measure_all --tree         # 255-leaf trees grown with library calls only
 """
 from __future__ import annotations
 
@@ -175,10 +177,141 @@ def skew(args, torch, B, synth, dev):
             torch.cuda.empty_cache()
 
 
+WORKLOADS = {
+    "tiny_dense": lambda synth, dev: synth.config1_tiny_dense(device=dev),
+    "dense_wide": lambda synth, dev: synth.config2_dense_wide(device=dev, with_leaves=False),
+    "dense_tall": lambda synth, dev: synth.config3_dense_tall(device=dev),
+    "ranking_sparse": lambda synth, dev: synth.config4_ranking_sparse(device=dev, fractions=(1.0,)),
+    "categorical": lambda synth, dev: synth.config5_categorical(device=dev),
+}
+
+
+def _events(torch):
+    return torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+
+def partition(args, torch, B, synth, dev):
+    """gbdt_partition_rows (flag pass + scatter pass) on the root and on an index-list leaf of
+    every workload, split on a middle feature at the middle bin.  Bytes: what the step must
+    move (row id in if listed, one bin value, row id out) and what a row-major tile layout
+    makes it fetch (the whole tile row that holds the bin value)."""
+    print("| workload | leaf | leaf rows | call ms (median) | call ms (min) | G rows/s | "
+          "algorithmic MB | tile-row MB fetched | tile-row GB/s |")
+    print("|" + "---|" * 9, flush=True)
+    for name, make in WORKLOADS.items():
+        if args.only and name not in args.only:
+            continue
+        w = make(synth, dev)
+        n, F, nb = w.n_rows, w.n_features, w.n_bins
+        packed = B.gbdt_bins_pack(w.bins, nb)
+        geo = B.gbdt_debug_geometry(F, nb, n)
+        f = F // 2
+        rec = B.split_record(f, nb // 2 - 1, dev)
+        tile, _ = B.gbdt_debug_locate(F, nb, f)
+        width = geo["wm"] if tile < geo["n_main"] else geo["wr"]
+        half = torch.nonzero(w.bins[:, 0] <= (nb - 1) // 2).flatten().to(torch.int32)
+        out = torch.empty(n, dtype=torch.int32, device=dev)
+        n_left = torch.empty(1, dtype=torch.int64, device=dev)
+        for leaf_name, leaf in (("root", None), (f"{100.0 * half.numel() / n:.1f} % (index list)", half)):
+            n_leaf = n if leaf is None else leaf.numel()
+            times = []
+            for rep in range(23):
+                e0, e1 = _events(torch)
+                e0.record()
+                B.gbdt_partition_rows(packed, n, F, nb, leaf, n_leaf, rec, out, n_left)
+                e1.record()
+                torch.cuda.synchronize()
+                if rep >= 3:
+                    times.append(e0.elapsed_time(e1))
+            med, mn = statistics.median(times), min(times)
+            alg = n_leaf * ((4 if leaf is not None else 0) + (0.5 if nb <= 16 else 1.0) + 4)
+            tile_bytes = n_leaf * (width + 4 + (8 if leaf is not None else 4))
+            print(f"| {name} | {leaf_name} | {n_leaf:,} | {med:.4f} | {mn:.4f} | {n_leaf / (med * 1e-3) / 1e9:.1f} | "
+                  f"{alg / 1e6:.1f} | {tile_bytes / 1e6:.1f} | {tile_bytes / (med * 1e-3) / 1e9:,.0f} |", flush=True)
+        del w, packed, half, out
+        torch.cuda.empty_cache()
+
+
+def grow_tree(B, torch, packed, w, n_leaves, timers=None):
+    """Leaf-wise growth (Sec. 5: 255 leaves) from library calls alone: root build, then per split
+    partition the best open leaf, build its smaller child, subtract for the sibling, search both.
+    Row lists and histograms never leave the device; the host reads the two new split records per
+    split (it needs them to pick the next leaf).  Returns the number of leaves reached."""
+    n, F, nb = w.n_rows, w.n_features, w.n_bins
+
+    def timed(key, fn):
+        if timers is None:
+            return fn()
+        e0, e1 = _events(torch)
+        e0.record()
+        r = fn()
+        e1.record()
+        timers.setdefault(key, []).append((e0, e1))
+        return r
+
+    hist = timed("build", lambda: B.gbdt_hist_build(packed, n, F, nb, None, n, w.grad, w.hess))
+    rec = timed("split", lambda: B.gbdt_best_split(hist, w.lam, w.min_child_hess))
+    leaves = [dict(rows=None, n=n, hist=hist, rec=rec, s=B.split_to_dict(rec))]
+    while len(leaves) < n_leaves:
+        best = None
+        for l in leaves:
+            if l["s"]["feature"] >= 0 and (best is None or l["s"]["gain"] > best["s"]["gain"]):
+                best = l
+        if best is None:
+            break
+        leaves = [l for l in leaves if l is not best]
+        kids, _ = timed("partition", lambda: B.gbdt_partition_rows(packed, n, F, nb, best["rows"], best["n"], best["rec"]))
+        nl, nr = best["s"]["left_count"], best["s"]["right_count"]
+        rows_l, rows_r = kids[:nl], kids[nl:nl + nr]
+        small = rows_l if nl <= nr else rows_r
+        h_small = timed("build", lambda: B.gbdt_hist_build(packed, n, F, nb, small, small.numel(), w.grad, w.hess))
+        h_large = timed("subtract", lambda: B.gbdt_hist_subtract(best["hist"], h_small))
+        h_l, h_r = (h_small, h_large) if nl <= nr else (h_large, h_small)
+        rec_l = timed("split", lambda: B.gbdt_best_split(h_l, w.lam, w.min_child_hess))
+        rec_r = timed("split", lambda: B.gbdt_best_split(h_r, w.lam, w.min_child_hess))
+        leaves.append(dict(rows=rows_l, n=nl, hist=h_l, rec=rec_l, s=B.split_to_dict(rec_l)))
+        leaves.append(dict(rows=rows_r, n=nr, hist=h_r, rec=rec_r, s=B.split_to_dict(rec_r)))
+    return len(leaves)
+
+
+def tree(args, torch, B, synth, dev):
+    """Whole 255-leaf trees (the tree size of Sec. 5) on every workload: wall time per tree and
+    the GPU time of each kind of call inside it."""
+    print("| workload | leaves | wall ms / tree | build ms (calls) | partition ms (calls) | subtract ms | "
+          "split search ms | GPU busy % of wall |")
+    print("|" + "---|" * 8, flush=True)
+    for name, make in WORKLOADS.items():
+        if args.only and name not in args.only:
+            continue
+        w = make(synth, dev)
+        packed = B.gbdt_bins_pack(w.bins, w.n_bins)
+        grow_tree(B, torch, packed, w, 255)                     # warm-up (scratch allocation)
+        torch.cuda.synchronize()
+        walls = []
+        for _ in range(3):
+            t0 = time.perf_counter()
+            reached = grow_tree(B, torch, packed, w, 255)
+            torch.cuda.synchronize()
+            walls.append((time.perf_counter() - t0) * 1e3)
+        timers = {}
+        grow_tree(B, torch, packed, w, 255, timers)
+        torch.cuda.synchronize()
+        ms = {k: sum(a.elapsed_time(b) for a, b in v) for k, v in timers.items()}
+        busy = sum(ms.values())
+        wall = statistics.median(walls)
+        print(f"| {name} | {reached} | {wall:.1f} | {ms.get('build', 0):.2f} ({len(timers.get('build', []))}) | "
+              f"{ms.get('partition', 0):.2f} ({len(timers.get('partition', []))}) | {ms.get('subtract', 0):.2f} | "
+              f"{ms.get('split', 0):.2f} | {100 * busy / wall:.0f} |", flush=True)
+        del w, packed
+        torch.cuda.empty_cache()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--depth-sweep", action="store_true")
     ap.add_argument("--skew", action="store_true")
+    ap.add_argument("--partition", action="store_true")
+    ap.add_argument("--tree", action="store_true")
     ap.add_argument("--oracle", action="store_true", help="time the CPU oracle on the root leaves")
     ap.add_argument("--only", nargs="*", default=None)
     args = ap.parse_args()
@@ -195,6 +328,10 @@ def main():
         depth_sweep(args, torch, B, synth, dev)
     elif args.skew:
         skew(args, torch, B, synth, dev)
+    elif args.partition:
+        partition(args, torch, B, synth, dev)
+    elif args.tree:
+        tree(args, torch, B, synth, dev)
     else:
         five_workloads(args, torch, B, synth, dev)
 

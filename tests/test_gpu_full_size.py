@@ -6,7 +6,9 @@ SAMPLED outputs one by one -- the complete histograms of a handful of features o
 whole leaf -- and the rest is covered by properties that hold at any size: every
 feature's counts sum to the leaf size exactly, its gradient / hessian sums reproduce the
 leaf totals, the sibling is the exact element-wise difference, and the split chosen by
-the GPU scan equals the oracle's scan of the same fp32 histogram.
+the GPU scan equals the oracle's scan of the same fp32 histogram.  The row partition that
+follows the split is integer work on one column, which the oracle redoes in full: every
+row id of both children is compared.
 """
 import numpy as np
 import pytest
@@ -71,11 +73,33 @@ def _check_leaf(w, packed, leaf, cols, what):
     assert dg <= REL_TOL * abs_g and dh <= REL_TOL * abs_h
 
     # the GPU scan of this fp32 histogram picks what the oracle scan of the same numbers picks
-    s_gpu = B.split_to_dict(B.gbdt_best_split(hist, w.lam, w.min_child_hess))
+    rec = B.gbdt_best_split(hist, w.lam, w.min_child_hess)
+    s_gpu = B.split_to_dict(rec)
     s_ref = orc.best_split(orc.from_f32_hist(got["grad"], got["hess"], got["count"]), w.lam, w.min_child_hess)
     assert (s_gpu["feature"], s_gpu["bin"]) == (s_ref["feature"], s_ref["bin"]), (what, s_gpu, s_ref)
     assert s_gpu["left_count"] == s_ref["left_count"] and s_gpu["right_count"] == s_ref["right_count"]
+    _check_partition(w, packed, leaf, rec, s_gpu, what)
     return hist, got
+
+
+def _check_partition(w, packed, leaf, rec, s_gpu, what):
+    """Partition the leaf by the split record the GPU just wrote; every row id of both children
+    against the oracle, which gets the one column it needs (and nothing from the GPU path)."""
+    n, F, nb = w.n_rows, w.n_features, w.n_bins
+    n_leaf = n if leaf is None else leaf.numel()
+    kids, n_left = B.gbdt_partition_rows(packed, n, F, nb, leaf, n_leaf, rec)
+    torch.cuda.synchronize()
+    f = s_gpu["feature"]
+    if f < 0:
+        assert int(n_left.item()) == n_leaf
+        return
+    col = w.bins[:, f].contiguous().cpu().numpy().reshape(-1, 1)
+    ref_l, ref_r = orc.partition_rows(col, 0, s_gpu["bin"], None if leaf is None else leaf.cpu().numpy())
+    got = kids.cpu().numpy()
+    nl = int(n_left.item())
+    assert nl == ref_l.size == s_gpu["left_count"], (what, nl, ref_l.size, s_gpu)
+    assert np.array_equal(got[:nl], ref_l) and np.array_equal(got[nl:n_leaf], ref_r), f"{what}: partition"
+    _say(f"{what}: partition on feature {f} bin {s_gpu['bin']}: {nl} left, {n_leaf - nl} right, identical")
 
 
 def _subset_leaf(n_rows, fraction, seed):
