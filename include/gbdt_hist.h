@@ -20,9 +20,9 @@
  *  - Bins are 0-based: a binned value b satisfies 0 <= b < n_bins (the paper
  *    writes 1..k).  2 <= n_bins <= 256.
  *  - The library keeps one scratch workspace per process (partial histograms,
- *    split candidates, partition flags).  Calls that use it (gbdt_hist_build,
- *    gbdt_best_split, gbdt_partition_rows) must not run concurrently on different
- *    streams.
+ *    split candidates, partition flags).  Calls that use it (gbdt_hist_build[_batch],
+ *    gbdt_best_split[_batch], gbdt_partition_rows) must not run concurrently on
+ *    different streams.
  */
 #ifndef GBDT_HIST_H_
 #define GBDT_HIST_H_
@@ -130,6 +130,36 @@ int gbdt_hist_build(const void* bin_matrix, int64_t n_rows, int32_t n_features, 
                     const float* hess, gbdt_bin_t* hist_out, void* stream);
 
 /*
+ * Feature histograms of several leaves in one call: hist_out[l] is what gbdt_hist_build
+ * writes for the leaf whose row list is row_idx[leaf_offsets[l] .. leaf_offsets[l + 1]).
+ * The paper builds one leaf at a time, and its kernel benchmark (App. C.2) shows the
+ * rate falling as leaves get small, because a small leaf cannot fill the GPU; a level of
+ * a depth-wise tree, or the small children of several splits, can when they share a
+ * launch.  Up to 128 leaves go into one kernel launch (plus one reduction launch);
+ * longer batches are cut into such launches.
+ *   row_idx        DEVICE int32: the leaves' row lists back to back (e.g. the
+ *                  children_out segments gbdt_partition_rows wrote), row ids in
+ *                  [0, n_rows); may be NULL when every leaf is empty
+ *   leaf_offsets   HOST int64 [n_leaves + 1], non-decreasing, leaf_offsets[0] >= 0;
+ *                  read before the call returns.  Leaves may be empty; each holds fewer
+ *                  than 2^31 rows and each launch of 128 leaves fewer than 2^32.
+ *   grad, hess     DEVICE float [n_rows], indexed by row id
+ *   hist_out       DEVICE gbdt_bin_t [n_leaves][n_features][n_bins], fully overwritten
+ * Arithmetic and error bound per leaf as for gbdt_hist_build; the split of a leaf's rows
+ * among workgroups is fixed by the batch's shape and the device, so the same call gives
+ * the same bits every time.  Scratch: see gbdt_hist_build_batch_workspace_bytes.
+ */
+int gbdt_hist_build_batch(const void* bin_matrix, int64_t n_rows, int32_t n_features,
+                          int32_t n_bins, const int32_t* row_idx, const int64_t* leaf_offsets,
+                          int32_t n_leaves, const float* grad, const float* hess,
+                          gbdt_bin_t* hist_out, void* stream);
+
+/* Upper bound on the scratch gbdt_hist_build_batch needs for batches of at most n_leaves
+ * leaves of this shape on the current device (0 on invalid arguments); to be covered by
+ * the buffer given to gbdt_set_workspace when the caller owns the scratch. */
+size_t gbdt_hist_build_batch_workspace_bytes(int32_t n_features, int32_t n_bins, int32_t n_leaves);
+
+/*
  * Bit-reproducible histograms (App. A.6 weighs precision against speed; this switch
  * weighs run-to-run reproducibility against speed).  By default the workgroups of
  * gbdt_hist_build share out a leaf's rows at run time, which balances them best but
@@ -166,6 +196,18 @@ int gbdt_hist_subtract(const gbdt_bin_t* parent, const gbdt_bin_t* child, gbdt_b
  */
 int gbdt_best_split(const gbdt_bin_t* hist, float lambda, float min_child_hess,
                     gbdt_split_t* split_out, int32_t n_features, int32_t n_bins, void* stream);
+
+/*
+ * gbdt_best_split for n_hists histograms at once: splits_out[i] is the best split of
+ * hists[i] (e.g. the two children of a split, or a level of a tree), same rule, same
+ * arithmetic, two kernel launches for the whole batch.
+ *   hists       DEVICE gbdt_bin_t [n_hists][n_features][n_bins]
+ *   splits_out  DEVICE gbdt_split_t [n_hists], overwritten
+ * n_hists == 0 is a no-op.
+ */
+int gbdt_best_split_batch(const gbdt_bin_t* hists, int32_t n_hists, float lambda,
+                          float min_child_hess, gbdt_split_t* splits_out, int32_t n_features,
+                          int32_t n_bins, void* stream);
 
 /*
  * Row partition of a leaf into its two children (the Split() step of App. C.1; it
@@ -249,6 +291,14 @@ int gbdt_calibration_copy(const void* src, void* dst, size_t bytes, void* stream
  */
 int gbdt_debug_geometry(int32_t n_features, int32_t n_bins, int64_t n_leaf_rows, int32_t n_cus,
                         int64_t* out, int32_t n_out);
+/* Launch plan of the first (at most 128-leaf) launch of gbdt_hist_build_batch on a device
+ * with n_cus compute units holding wg_per_cu workgroups each: per leaf the workgroups per
+ * tile and the epochs per unit; for block i < max_blocks of the grid, block_out[3 i ..
+ * 3 i + 2] = (leaf, tile, workgroup of that leaf and tile), computed by the function the
+ * kernel uses.  Returns the number of blocks, or a negative gbdt_status. */
+int gbdt_debug_batch_plan(int32_t n_features, int32_t n_bins, const int64_t* leaf_offsets,
+                          int32_t n_leaves, int32_t n_cus, int32_t wg_per_cu, int32_t* leaf_wgs_out,
+                          int32_t* leaf_unit_epochs_out, int32_t* block_out, int32_t max_blocks);
 /* Resident workgroups per compute unit of the build kernel variant that serves
  * n_bins (indexed != 0: the variant that gathers through leaf_row_idx), as the HIP
  * runtime reports it on the current device; 0 if the query is not possible. */

@@ -22,6 +22,8 @@ EXPORTS = [
     "gbdt_last_hip_error", "gbdt_debug_geometry", "gbdt_debug_locate",
     "gbdt_profile_enable", "gbdt_profile_collect", "gbdt_debug_occupancy",
     "gbdt_calibration_copy", "gbdt_set_deterministic", "gbdt_partition_rows",
+    "gbdt_hist_build_batch", "gbdt_hist_build_batch_workspace_bytes", "gbdt_best_split_batch",
+    "gbdt_debug_batch_plan",
 ]
 
 # numpy views of the two C structs
@@ -60,6 +62,15 @@ def load():
     lib.gbdt_best_split.restype = c.c_int
     lib.gbdt_best_split.argtypes = [c.c_void_p, c.c_float, c.c_float, c.c_void_p, c.c_int32,
                                     c.c_int32, c.c_void_p]
+    lib.gbdt_hist_build_batch.restype = c.c_int
+    lib.gbdt_hist_build_batch.argtypes = [c.c_void_p, c.c_int64, c.c_int32, c.c_int32, c.c_void_p,
+                                          c.POINTER(c.c_int64), c.c_int32, c.c_void_p, c.c_void_p,
+                                          c.c_void_p, c.c_void_p]
+    lib.gbdt_hist_build_batch_workspace_bytes.restype = c.c_size_t
+    lib.gbdt_hist_build_batch_workspace_bytes.argtypes = [c.c_int32, c.c_int32, c.c_int32]
+    lib.gbdt_best_split_batch.restype = c.c_int
+    lib.gbdt_best_split_batch.argtypes = [c.c_void_p, c.c_int32, c.c_float, c.c_float, c.c_void_p,
+                                          c.c_int32, c.c_int32, c.c_void_p]
     lib.gbdt_partition_rows.restype = c.c_int
     lib.gbdt_partition_rows.argtypes = [c.c_void_p, c.c_int64, c.c_int32, c.c_int32, c.c_void_p,
                                         c.c_int64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p]
@@ -172,6 +183,52 @@ def gbdt_hist_build(bin_matrix, n_rows, n_features, n_bins, leaf_row_idx, n_leaf
     return hist_out
 
 
+def gbdt_hist_build_batch(bin_matrix, n_rows, n_features, n_bins, row_idx, leaf_offsets, grad, hess,
+                          hist_out=None, stream=None):
+    """leaf_offsets: host sequence of n_leaves + 1 ints into row_idx (int32 CUDA tensor).
+    Returns hist_out: float32 CUDA tensor [n_leaves, n_features, n_bins, 3]."""
+    offs = [int(o) for o in leaf_offsets]
+    n_leaves = len(offs) - 1
+    if n_leaves < 0:
+        raise GbdtError("leaf_offsets: need n_leaves + 1 entries")
+    if hist_out is None:
+        hist_out = torch.empty((n_leaves, n_features, n_bins, 3), dtype=torch.float32, device=grad.device)
+    elif hist_out.numel() < n_leaves * n_features * n_bins * 3:
+        raise GbdtError("hist_out too small")
+    idx_p = None if row_idx is None else _dev(row_idx, torch.int32, "row_idx")
+    if row_idx is not None and offs and row_idx.numel() < offs[-1]:
+        raise GbdtError("row_idx shorter than leaf_offsets[-1]")
+    if grad.numel() < n_rows or hess.numel() < n_rows:
+        raise GbdtError("grad/hess shorter than n_rows")
+    if bin_matrix.numel() < gbdt_bins_packed_bytes(n_rows, n_features, n_bins):
+        raise GbdtError("bin_matrix smaller than the packed layout of this shape")
+    arr = (ctypes.c_int64 * (n_leaves + 1))(*offs)
+    _check(load().gbdt_hist_build_batch(_dev(bin_matrix, torch.uint8, "bin_matrix"), n_rows, n_features,
+                                        n_bins, idx_p, arr, n_leaves, _dev(grad, torch.float32, "grad"),
+                                        _dev(hess, torch.float32, "hess"),
+                                        _dev(hist_out, torch.float32, "hist_out"), _stream(stream)),
+           "gbdt_hist_build_batch")
+    return hist_out
+
+
+def gbdt_hist_build_batch_workspace_bytes(n_features: int, n_bins: int, n_leaves: int) -> int:
+    return int(load().gbdt_hist_build_batch_workspace_bytes(n_features, n_bins, n_leaves))
+
+
+def gbdt_best_split_batch(hists, lam, min_child_hess, splits_out=None, stream=None):
+    """hists: float32 CUDA tensor [n_hists, n_features, n_bins, 3].  Returns splits_out: int32
+    CUDA tensor [n_hists, 9], one gbdt_split_t per histogram."""
+    n_hists, n_features, n_bins = hists.shape[0], hists.shape[1], hists.shape[2]
+    if splits_out is None:
+        splits_out = torch.empty((n_hists, 9), dtype=torch.int32, device=hists.device)
+    elif splits_out.numel() < n_hists * 9:
+        raise GbdtError("splits_out too small")
+    _check(load().gbdt_best_split_batch(_dev(hists, torch.float32, "hists"), n_hists, float(lam),
+                                        float(min_child_hess), _dev(splits_out, torch.int32, "splits_out"),
+                                        n_features, n_bins, _stream(stream)), "gbdt_best_split_batch")
+    return splits_out
+
+
 def gbdt_hist_subtract(parent, child, sibling_out=None, stream=None):
     n_features, n_bins = parent.shape[0], parent.shape[1]
     if child.shape != parent.shape:
@@ -240,6 +297,28 @@ def gbdt_debug_geometry(n_features: int, n_bins: int, n_leaf_rows: int, n_cus: i
     return {k: int(out[i]) for i, k in enumerate(GEOMETRY_FIELDS)}
 
 
+def gbdt_debug_batch_plan(n_features, n_bins, leaf_offsets, n_cus=256, wg_per_cu=3):
+    """(leaf_wgs, leaf_unit_epochs, blocks [n_blocks, 3] = leaf, tile, workgroup) of the launch."""
+    offs = [int(o) for o in leaf_offsets]
+    n_leaves = len(offs) - 1
+    lib = load()
+    lib.gbdt_debug_batch_plan.restype = ctypes.c_int
+    lib.gbdt_debug_batch_plan.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.POINTER(ctypes.c_int64),
+                                          ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p,
+                                          ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32]
+    arr = (ctypes.c_int64 * (n_leaves + 1))(*offs)
+    wgs = np.zeros(max(n_leaves, 1), np.int32)
+    ue = np.zeros(max(n_leaves, 1), np.int32)
+    n = lib.gbdt_debug_batch_plan(n_features, n_bins, arr, n_leaves, n_cus, wg_per_cu, wgs.ctypes.data,
+                                  ue.ctypes.data, None, 0)
+    _check(min(n, 0), "gbdt_debug_batch_plan")
+    blocks = np.zeros((max(n, 1), 3), np.int32)
+    n2 = lib.gbdt_debug_batch_plan(n_features, n_bins, arr, n_leaves, n_cus, wg_per_cu, wgs.ctypes.data,
+                                   ue.ctypes.data, blocks.ctypes.data, n)
+    _check(min(n2, 0), "gbdt_debug_batch_plan")
+    return wgs[:n_leaves], ue[:n_leaves], blocks[:n]
+
+
 def gbdt_debug_occupancy(n_bins: int, indexed: bool) -> int:
     lib = load()
     lib.gbdt_debug_occupancy.restype = ctypes.c_int
@@ -281,11 +360,17 @@ def gbdt_profile_collect():
 
 
 def hist_to_numpy(hist: torch.Tensor) -> np.ndarray:
-    """[n_features, n_bins] structured array (grad f4, hess f4, count u4)."""
+    """[..., n_features, n_bins] structured array (grad f4, hess f4, count u4)."""
     a = hist.detach().cpu().contiguous().numpy()
-    return a.view(BIN_DTYPE).reshape(a.shape[0], a.shape[1])
+    return a.view(BIN_DTYPE).reshape(a.shape[:-1])
 
 
 def split_to_dict(split: torch.Tensor) -> dict:
     a = split.detach().cpu().contiguous().numpy().view(SPLIT_DTYPE)[0]
     return {k: a[k].item() for k in SPLIT_DTYPE.names}
+
+
+def splits_to_dicts(splits: torch.Tensor) -> list:
+    """One dict per gbdt_split_t of a [n, 9] int32 tensor (one device-to-host copy)."""
+    a = splits.detach().cpu().contiguous().numpy().reshape(-1, 9).view(SPLIT_DTYPE).reshape(-1)
+    return [{k: r[k].item() for k in SPLIT_DTYPE.names} for r in a]

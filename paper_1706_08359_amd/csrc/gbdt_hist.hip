@@ -27,6 +27,7 @@
 
 #include "../../include/gbdt_hist.h"
 #include "tile_plan.h"
+#include "batch_plan.h"
 
 namespace {
 
@@ -604,6 +605,69 @@ counters_init_kernel(uint32_t* counters, int32_t wgs, int32_t n_counters) {
   if (i < n_counters) counters[i] = (uint32_t)wgs;
 }
 
+// Several leaves in one launch.  Small leaves cannot fill the machine on their own (the
+// synthetic benchmark of App. C.2 shows the rate falling with the leaf size); a level of
+// a tree, or both children of a split, can.  The launch carries a table of up to
+// kBatchLeaves leaves as kernel arguments -- nothing is staged through memory.  Leaf l
+// (batch_plan.h) owns the row list idx[row_off .. row_off + n) and wgs workgroups per tile, which take
+// its units of unit_epochs epochs in a fixed stride (no counters): a workgroup of leaf l
+// runs build_tile exactly as a single-leaf launch in its fixed-split mode would, and the
+// leaves' partial blocks lie back to back, each leaf's in the single-leaf order.
+struct BatchArgs {
+  const uint8_t* packed;
+  const int32_t* idx;
+  const float* grad;
+  const float* hess;
+  uint32_t* partials;
+  int64_t n_rows;
+  int32_t n_main;
+  int32_t wr;
+  int32_t n_leaves;
+  BatchLeaf leaf[kBatchLeaves];
+};
+
+// Words of the partial blocks one workgroup column (one workgroup of every tile) writes.
+template <int CAP, int WM, bool NIB, int NT>
+__device__ __host__ inline size_t column_words(int32_t n_main, int32_t wr) {
+  size_t w = (size_t)n_main * block_words<CAP, WM, NIB, NT>();
+  if (wr == 16) w += block_words<CAP, 16, NIB, NT>();
+  if (wr == 32) w += block_words<CAP, 32, NIB, NT>();
+  return w;
+}
+
+template <int CAP, int WM, bool NIB, int NT, int WPE, typename ACC>
+__global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(WPE, WPE)))
+hist_build_batch_kernel(BatchArgs a) {
+  constexpr int kCells = TileShape<CAP, WM, NIB, NT>::CELLS;
+  __shared__ __align__(16) unsigned long long lds[kCells + (4 * (NT / 64) * 4 + 7) / 8 + 1];
+  const BatchBlock blk = batch_block(a.leaf, a.n_leaves, a.n_main, a.wr, blockIdx.x);
+  const BatchLeaf lf = a.leaf[blk.leaf];
+  const int32_t wgs = (int32_t)(lf.wgs_unit & 0xffffu);
+  const uint32_t unit_epochs = lf.wgs_unit >> 16;
+  const int32_t main_blocks = a.n_main * wgs;
+  const int32_t t = blk.tile, c = blk.wg;
+  const bool is_main = t < a.n_main;
+  const uint8_t* tile = a.packed + a.n_rows * ((int64_t)t * WM);
+  const int32_t* idx = a.idx + lf.row_off;
+  uint32_t* leaf_out = a.partials + (size_t)lf.first_wg * column_words<CAP, WM, NIB, NT>(a.n_main, a.wr);
+  if (is_main) {
+    build_tile<CAP, WM, NIB, NT, ACC, true>(
+        tile, idx, a.grad, a.hess, lf.n, (uint32_t)c, unit_epochs, (uint32_t)wgs, nullptr, lds,
+        leaf_out + ((size_t)t * wgs + c) * (size_t)block_words<CAP, WM, NIB, NT>());
+  } else {
+    uint32_t* rem_base = leaf_out + (size_t)main_blocks * (size_t)block_words<CAP, WM, NIB, NT>();
+    if (a.wr == 16) {
+      build_tile<CAP, 16, NIB, NT, ACC, true>(tile, idx, a.grad, a.hess, lf.n, (uint32_t)c, unit_epochs,
+                                              (uint32_t)wgs, nullptr, lds,
+                                              rem_base + (size_t)c * (size_t)block_words<CAP, 16, NIB, NT>());
+    } else if constexpr (WM > 32) {
+      build_tile<CAP, 32, NIB, NT, ACC, true>(tile, idx, a.grad, a.hess, lf.n, (uint32_t)c, unit_epochs,
+                                              (uint32_t)wgs, nullptr, lds,
+                                              rem_base + (size_t)c * (size_t)block_words<CAP, 32, NIB, NT>());
+    }
+  }
+}
+
 // ------------------------------------------------------------------ merge kernel
 
 struct MergeArgs {
@@ -625,7 +689,7 @@ constexpr int kMergeLanes = 4;    // threads that share the chunks of one cell
 // in runs of 32); 4 threads per pair each sum every 4th chunk in fp64, in chunk
 // order, and the 4 sub-sums are added in a fixed order: the result does not depend
 // on scheduling.  Counts are summed as integers.  grid.y = tile.
-__global__ void __launch_bounds__(kMergeCells * kMergeLanes) hist_merge_kernel(MergeArgs a) {
+__device__ __forceinline__ void merge_cells(const MergeArgs& a) {
   __shared__ double s_g[kMergeLanes][kMergeCells];
   __shared__ double s_h[kMergeLanes][kMergeCells];
   __shared__ uint32_t s_n[kMergeLanes][kMergeCells];
@@ -680,6 +744,30 @@ __global__ void __launch_bounds__(kMergeCells * kMergeLanes) hist_merge_kernel(M
       a.out[(size_t)f * a.n_bins + bin] = r;
     }
   }
+}
+
+__global__ void __launch_bounds__(kMergeCells * kMergeLanes) hist_merge_kernel(MergeArgs a) {
+  merge_cells(a);
+}
+
+// The same reduction for a batched launch: grid.z = leaf of the launch; its partial
+// blocks start first_wg workgroup columns into the buffer, its histogram is the leaf's
+// [n_features][n_bins] slice of the output.  A leaf without rows has no partial blocks
+// and gets zeros.
+struct BatchMergeArgs {
+  MergeArgs m;            // partials / out of leaf 0 of the launch; chunk counts unused
+  uint64_t column_words;  // words of one workgroup column
+  BatchLeaf leaf[kBatchLeaves];
+};
+
+__global__ void __launch_bounds__(kMergeCells * kMergeLanes) hist_merge_batch_kernel(BatchMergeArgs a) {
+  const BatchLeaf lf = a.leaf[blockIdx.z];
+  MergeArgs m = a.m;
+  m.partials += (size_t)lf.first_wg * a.column_words;
+  m.out += (size_t)blockIdx.z * m.n_features * m.n_bins;
+  m.chunks_main = (int32_t)(lf.wgs_unit & 0xffffu);
+  m.chunks_rem = m.plan.wr ? m.chunks_main : 0;
+  merge_cells(m);
 }
 
 // --------------------------------------------------------------- subtract kernel
@@ -745,6 +833,9 @@ split_gain_kernel(const gbdt_bin_t* __restrict__ hist, int32_t n_features, int32
   __shared__ double s_gain[kSplitThreads];
   __shared__ int32_t s_pair[kSplitThreads];
   const int tid = threadIdx.x;
+  // grid.y = histogram of a batched call
+  hist += (size_t)blockIdx.y * n_features * n_bins;
+  cand += (size_t)blockIdx.y * gridDim.x;
   const int32_t f0 = blockIdx.x * group;
   const int32_t nf = (n_features - f0 < group) ? (n_features - f0) : group;
   const int B = n_bins;
@@ -842,13 +933,16 @@ split_gain_kernel(const gbdt_bin_t* __restrict__ hist, int32_t n_features, int32
 
 // Arg-max over the per-workgroup candidates (workgroups hold ascending feature
 // groups, so "smaller candidate index" is "smaller feature").  One workgroup; each
-// thread folds a strided subset in ascending order, then a tree reduction.
+// thread folds a strided subset in ascending order, then a tree reduction.  grid.x =
+// histogram of a batched call.
 __global__ void __launch_bounds__(256)
 split_argmax_kernel(const SplitCand* __restrict__ cand, int32_t n_cand,
                     gbdt_split_t* __restrict__ out) {
   __shared__ double s_gain[256];
   __shared__ int32_t s_idx[256];
   const int tid = threadIdx.x;
+  cand += (size_t)blockIdx.x * n_cand;
+  out += blockIdx.x;
   double bg = 0.0;
   int32_t bi = -1;
   for (int32_t i = tid; i < n_cand; i += 256) {
@@ -1262,31 +1356,110 @@ bool valid_shape(int64_t n_rows, int32_t n_features, int32_t n_bins) {
   return n_rows >= 0 && n_features > 0 && n_bins >= 2 && n_bins <= 256;
 }
 
+// Brackets the build kernel with events while profiling is enabled.
+struct BuildTimer {
+  hipEvent_t ev0 = nullptr, ev1 = nullptr;
+  bool on = false;
+  int begin(hipStream_t s) {
+    {
+      std::lock_guard<std::mutex> lk(g_prof.mu);
+      on = g_prof.on;
+    }
+    if (on) {
+      HIP_TRY(hipEventCreate(&ev0));
+      HIP_TRY(hipEventCreate(&ev1));
+      HIP_TRY(hipEventRecord(ev0, s));
+    }
+    return GBDT_OK;
+  }
+  int end(hipStream_t s) {
+    if (on) {
+      HIP_TRY(hipEventRecord(ev1, s));
+      std::lock_guard<std::mutex> lk(g_prof.mu);
+      g_prof.pairs.emplace_back(ev0, ev1);
+    }
+    return GBDT_OK;
+  }
+};
+
 template <int CAP, int WM, bool NIB, int NT, int WPE, typename ACC>
 int launch_build(const BuildArgs& a, int blocks, hipStream_t s) {
-  hipEvent_t ev0 = nullptr, ev1 = nullptr;
-  bool prof = false;
-  {
-    std::lock_guard<std::mutex> lk(g_prof.mu);
-    prof = g_prof.on;
-  }
-  if (prof) {
-    HIP_TRY(hipEventCreate(&ev0));
-    HIP_TRY(hipEventCreate(&ev1));
-    HIP_TRY(hipEventRecord(ev0, s));
-  }
+  BuildTimer timer;
+  int rc = timer.begin(s);
+  if (rc != GBDT_OK) return rc;
   if (a.idx) {
     hipLaunchKernelGGL((hist_build_kernel<CAP, WM, NIB, NT, WPE, ACC, true>), dim3(blocks), dim3(NT), 0, s, a);
   } else {
     hipLaunchKernelGGL((hist_build_kernel<CAP, WM, NIB, NT, WPE, ACC, false>), dim3(blocks), dim3(NT), 0, s, a);
   }
   HIP_TRY(hipGetLastError());
-  if (prof) {
-    HIP_TRY(hipEventRecord(ev1, s));
-    std::lock_guard<std::mutex> lk(g_prof.mu);
-    g_prof.pairs.emplace_back(ev0, ev1);
+  return timer.end(s);
+}
+
+template <int CAP, int WM, bool NIB, int NT, int WPE, typename ACC>
+int launch_build_batch(const BatchArgs& a, int blocks, hipStream_t s) {
+  BuildTimer timer;
+  int rc = timer.begin(s);
+  if (rc != GBDT_OK) return rc;
+  hipLaunchKernelGGL((hist_build_batch_kernel<CAP, WM, NIB, NT, WPE, ACC>), dim3(blocks), dim3(NT), 0, s, a);
+  HIP_TRY(hipGetLastError());
+  return timer.end(s);
+}
+
+template <int CAP, int WM, bool NIB, int NT, int WPE, typename ACC>
+size_t variant_column_words(const TilePlan& p) {
+  return column_words<CAP, WM, NIB, NT>(p.n_main, p.wr);
+}
+
+// Workgroups per tile and epochs per unit for a leaf of n_epochs epochs that may use
+// `budget` workgroups per tile: units of kUnitEpochs when every workgroup gets at least
+// one of them; otherwise (short leaf) one shorter unit per workgroup.
+void plan_leaf_units(int64_t n_epochs, int64_t budget, int* wgs_out, int* unit_epochs_out) {
+  int64_t wgs = budget;
+  if (wgs > n_epochs) wgs = n_epochs;
+  if (wgs < 1) wgs = 1;
+  int unit_epochs = kUnitEpochs;
+  if (wgs * kUnitEpochs > n_epochs) {
+    unit_epochs = (int)((n_epochs + wgs - 1) / wgs);
+    if (unit_epochs < 1) unit_epochs = 1;
+    const int64_t n_units = (n_epochs + unit_epochs - 1) / unit_epochs;
+    if (n_units >= 1 && wgs > n_units) wgs = n_units;  // no workgroup without a unit
   }
-  return GBDT_OK;
+  *wgs_out = (int)wgs;
+  *unit_epochs_out = unit_epochs;
+}
+
+// Plan of one batched launch: leaves [l0, l0 + n) of the call share the machine in
+// proportion to their epochs, at least one workgroup per tile each.
+struct BatchPlan {
+  BatchLeaf leaf[kBatchLeaves];
+  int n = 0;
+  uint32_t total_wgs = 0;  // workgroups per tile over all leaves
+};
+
+BatchPlan plan_batch(const int64_t* leaf_offsets, int32_t l0, int32_t n, int64_t resident,
+                     int n_tiles) {
+  BatchPlan b;
+  b.n = n;
+  int64_t total_epochs = 0;
+  for (int i = 0; i < n; ++i)
+    total_epochs += (leaf_offsets[l0 + i + 1] - leaf_offsets[l0 + i] + kEpochRows - 1) / kEpochRows;
+  int64_t budget = resident / n_tiles;
+  if (budget < 1) budget = 1;
+  uint32_t first = 0;
+  for (int i = 0; i < n; ++i) {
+    const int64_t rows = leaf_offsets[l0 + i + 1] - leaf_offsets[l0 + i];
+    const int64_t n_epochs = (rows + kEpochRows - 1) / kEpochRows;
+    int wgs = 0, unit_epochs = 1;
+    if (n_epochs > 0) plan_leaf_units(n_epochs, budget * n_epochs / total_epochs, &wgs, &unit_epochs);
+    b.leaf[i].row_off = (uint32_t)(leaf_offsets[l0 + i] - leaf_offsets[l0]);
+    b.leaf[i].n = (uint32_t)rows;
+    b.leaf[i].first_wg = first;
+    b.leaf[i].wgs_unit = (uint32_t)wgs | ((uint32_t)unit_epochs << 16);
+    first += (uint32_t)wgs;
+  }
+  b.total_wgs = first;
+  return b;
 }
 
 }  // namespace
@@ -1420,6 +1593,106 @@ int gbdt_hist_build(const void* bin_matrix, int64_t n_rows, int32_t n_features, 
   return GBDT_OK;
 }
 
+int gbdt_hist_build_batch(const void* bin_matrix, int64_t n_rows, int32_t n_features,
+                          int32_t n_bins, const int32_t* row_idx, const int64_t* leaf_offsets,
+                          int32_t n_leaves, const float* grad, const float* hess,
+                          gbdt_bin_t* hist_out, void* stream) {
+  if (!valid_shape(n_rows, n_features, n_bins)) return GBDT_EINVAL;
+  if (n_leaves < 0) return GBDT_EINVAL;
+  if (n_leaves == 0) return GBDT_OK;
+  if (!leaf_offsets || !hist_out) return GBDT_EINVAL;
+  if (leaf_offsets[0] < 0) return GBDT_EINVAL;
+  for (int32_t l = 0; l < n_leaves; ++l)
+    if (leaf_offsets[l + 1] < leaf_offsets[l]) return GBDT_EINVAL;
+  const int64_t total_rows = leaf_offsets[n_leaves] - leaf_offsets[0];
+  if (total_rows > 0 && (!bin_matrix || !row_idx || !grad || !hess)) return GBDT_EINVAL;
+  if (total_rows > 0 && n_rows == 0) return GBDT_EINVAL;
+  if (n_rows >= ((int64_t)1 << 30)) return GBDT_EUNSUPPORTED;
+  const TilePlan p = make_tile_plan(n_features, n_bins);
+  const int n_tiles = plan_n_tiles(p);
+  if (n_tiles > 65535) return GBDT_EUNSUPPORTED;
+  if ((n_rows + kEpochRows) * (int64_t)p.wm >= ((int64_t)1 << 32)) return GBDT_EUNSUPPORTED;
+  const int64_t resident = (int64_t)device_cu_count() * build_wg_per_cu(p.cap, true);
+  const size_t col = p.cap == 16 ? variant_column_words<GBDT_VARIANT_16>(p)
+                                 : (p.cap == 64 ? variant_column_words<GBDT_VARIANT_64>(p)
+                                                : variant_column_words<GBDT_VARIANT_256>(p));
+  // one scratch buffer serves the launches one after the other: size it for the largest
+  size_t need_words = 0;
+  for (int32_t l0 = 0; l0 < n_leaves; l0 += kBatchLeaves) {
+    const int32_t n = n_leaves - l0 < kBatchLeaves ? n_leaves - l0 : kBatchLeaves;
+    for (int32_t i = 0; i < n; ++i)
+      if (leaf_offsets[l0 + i + 1] - leaf_offsets[l0 + i] >= ((int64_t)1 << 31)) return GBDT_EUNSUPPORTED;
+    if (leaf_offsets[l0 + n] - leaf_offsets[l0] >= ((int64_t)1 << 32)) return GBDT_EUNSUPPORTED;
+    const BatchPlan b = plan_batch(leaf_offsets, l0, n, resident, n_tiles);
+    if ((int64_t)b.total_wgs * n_tiles >= ((int64_t)1 << 31)) return GBDT_EUNSUPPORTED;
+    const size_t w = (size_t)b.total_wgs * col;
+    if (w > need_words) need_words = w;
+  }
+  void* ws = nullptr;
+  int rc = get_workspace(need_words * 4 + 256, &ws);
+  if (rc != GBDT_OK) return rc;
+  hipStream_t s = (hipStream_t)stream;
+  for (int32_t l0 = 0; l0 < n_leaves; l0 += kBatchLeaves) {
+    const int32_t n = n_leaves - l0 < kBatchLeaves ? n_leaves - l0 : kBatchLeaves;
+    const BatchPlan b = plan_batch(leaf_offsets, l0, n, resident, n_tiles);
+    BatchMergeArgs m;
+    m.m.partials = (const uint32_t*)ws;
+    m.m.out = hist_out + (size_t)l0 * n_features * n_bins;
+    m.m.plan = p;
+    m.m.n_features = n_features;
+    m.m.n_bins = n_bins;
+    m.m.chunks_main = 0;
+    m.m.chunks_rem = 0;
+    m.column_words = col;
+    memcpy(m.leaf, b.leaf, sizeof m.leaf);
+    if (b.total_wgs > 0) {
+      BatchArgs a;
+      a.packed = (const uint8_t*)bin_matrix;
+      a.idx = row_idx + leaf_offsets[l0];
+      a.grad = grad;
+      a.hess = hess;
+      a.partials = (uint32_t*)ws;
+      a.n_rows = n_rows;
+      a.n_main = p.n_main;
+      a.wr = p.wr;
+      a.n_leaves = n;
+      memcpy(a.leaf, b.leaf, sizeof a.leaf);
+      const int blocks = (int)b.total_wgs * n_tiles;
+      if (p.cap == 16) {
+        rc = launch_build_batch<GBDT_VARIANT_16>(a, blocks, s);
+      } else if (p.cap == 64) {
+        rc = launch_build_batch<GBDT_VARIANT_64>(a, blocks, s);
+      } else {
+        rc = launch_build_batch<GBDT_VARIANT_256>(a, blocks, s);
+      }
+      if (rc != GBDT_OK) return rc;
+    }
+    const int max_slots = plan_slots(p, p.wm);
+    const int mx = (n_bins * max_slots + kMergeCells - 1) / kMergeCells;
+    hipLaunchKernelGGL(hist_merge_batch_kernel, dim3(mx, n_tiles, n), dim3(kMergeCells * kMergeLanes), 0,
+                       s, m);
+    HIP_TRY(hipGetLastError());
+  }
+  return GBDT_OK;
+}
+
+size_t gbdt_hist_build_batch_workspace_bytes(int32_t n_features, int32_t n_bins, int32_t n_leaves) {
+  if (n_features <= 0 || n_bins < 2 || n_bins > 256 || n_leaves < 0) return 0;
+  const TilePlan p = make_tile_plan(n_features, n_bins);
+  const int n_tiles = plan_n_tiles(p);
+  const int64_t resident = (int64_t)device_cu_count() * build_wg_per_cu(p.cap, true);
+  const size_t col = p.cap == 16 ? variant_column_words<GBDT_VARIANT_16>(p)
+                                 : (p.cap == 64 ? variant_column_words<GBDT_VARIANT_64>(p)
+                                                : variant_column_words<GBDT_VARIANT_256>(p));
+  // every leaf of a launch gets its share of the resident workgroups, rounded down, but
+  // at least one workgroup per tile
+  int64_t budget = resident / n_tiles;
+  if (budget < 1) budget = 1;
+  const int64_t per_launch = n_leaves < kBatchLeaves ? n_leaves : kBatchLeaves;
+  const size_t b = (size_t)(budget + per_launch) * col * 4 + 256;
+  return (b + 255) / 256 * 256;
+}
+
 int gbdt_hist_subtract(const gbdt_bin_t* parent, const gbdt_bin_t* child, gbdt_bin_t* sibling_out,
                        int32_t n_features, int32_t n_bins, void* stream) {
   if (!parent || !child || !sibling_out) return GBDT_EINVAL;
@@ -1431,26 +1704,41 @@ int gbdt_hist_subtract(const gbdt_bin_t* parent, const gbdt_bin_t* child, gbdt_b
   return GBDT_OK;
 }
 
-int gbdt_best_split(const gbdt_bin_t* hist, float lambda, float min_child_hess,
-                    gbdt_split_t* split_out, int32_t n_features, int32_t n_bins, void* stream) {
-  if (!hist || !split_out) return GBDT_EINVAL;
+int gbdt_best_split_batch(const gbdt_bin_t* hists, int32_t n_hists, float lambda,
+                          float min_child_hess, gbdt_split_t* splits_out, int32_t n_features,
+                          int32_t n_bins, void* stream) {
+  if (n_hists < 0) return GBDT_EINVAL;
   if (n_features <= 0 || n_bins < 2 || n_bins > 256) return GBDT_EINVAL;
   if (!(lambda >= 0.0f)) return GBDT_EINVAL;
+  if (n_hists == 0) return GBDT_OK;
+  if (!hists || !splits_out) return GBDT_EINVAL;
   int group = 0, n_groups = 0;
   split_grouping(n_features, n_bins, &group, &n_groups);
+  constexpr int32_t kMaxPerLaunch = 32768;  // grid.y limit is 65535
+  const int32_t per_launch = n_hists < kMaxPerLaunch ? n_hists : kMaxPerLaunch;
   void* ws = nullptr;
-  int rc = get_workspace((size_t)n_groups * sizeof(SplitCand), &ws);
+  int rc = get_workspace((size_t)per_launch * n_groups * sizeof(SplitCand), &ws);
   if (rc != GBDT_OK) return rc;
   hipStream_t s = (hipStream_t)stream;
   const size_t lds = (size_t)group * split_feature_bytes(n_bins);
-  hipLaunchKernelGGL(split_gain_kernel, dim3(n_groups), dim3(kSplitThreads), lds, s, hist,
-                     n_features, n_bins, group, (double)lambda, (double)min_child_hess,
-                     (SplitCand*)ws);
-  HIP_TRY(hipGetLastError());
-  hipLaunchKernelGGL(split_argmax_kernel, dim3(1), dim3(256), 0, s, (const SplitCand*)ws,
-                     n_groups, split_out);
-  HIP_TRY(hipGetLastError());
+  for (int32_t h0 = 0; h0 < n_hists; h0 += per_launch) {
+    const int32_t nh = n_hists - h0 < per_launch ? n_hists - h0 : per_launch;
+    hipLaunchKernelGGL(split_gain_kernel, dim3(n_groups, nh), dim3(kSplitThreads), lds, s,
+                       hists + (size_t)h0 * n_features * n_bins, n_features, n_bins, group,
+                       (double)lambda, (double)min_child_hess, (SplitCand*)ws);
+    HIP_TRY(hipGetLastError());
+    hipLaunchKernelGGL(split_argmax_kernel, dim3(nh), dim3(256), 0, s, (const SplitCand*)ws,
+                       n_groups, splits_out + h0);
+    HIP_TRY(hipGetLastError());
+  }
   return GBDT_OK;
+}
+
+int gbdt_best_split(const gbdt_bin_t* hist, float lambda, float min_child_hess,
+                    gbdt_split_t* split_out, int32_t n_features, int32_t n_bins, void* stream) {
+  if (!hist || !split_out) return GBDT_EINVAL;
+  return gbdt_best_split_batch(hist, 1, lambda, min_child_hess, split_out, n_features, n_bins,
+                               stream);
 }
 
 int gbdt_partition_rows(const void* bin_matrix, int64_t n_rows, int32_t n_features,
@@ -1495,6 +1783,32 @@ int gbdt_debug_geometry(int32_t n_features, int32_t n_bins, int64_t n_leaf_rows,
                          0,             0, 0, 0};
   for (int i = 0; i < 16; ++i) out[i] = v[i];
   return GBDT_OK;
+}
+
+int gbdt_debug_batch_plan(int32_t n_features, int32_t n_bins, const int64_t* leaf_offsets,
+                          int32_t n_leaves, int32_t n_cus, int32_t wg_per_cu, int32_t* leaf_wgs_out,
+                          int32_t* leaf_unit_epochs_out, int32_t* block_out, int32_t max_blocks) {
+  if (n_features <= 0 || n_bins < 2 || n_bins > 256 || !leaf_offsets || n_leaves < 1 ||
+      n_leaves > kBatchLeaves || n_cus <= 0 || wg_per_cu <= 0 || !leaf_wgs_out ||
+      !leaf_unit_epochs_out || (!block_out && max_blocks > 0))
+    return GBDT_EINVAL;
+  for (int32_t l = 0; l < n_leaves; ++l)
+    if (leaf_offsets[l + 1] < leaf_offsets[l]) return GBDT_EINVAL;
+  const TilePlan p = make_tile_plan(n_features, n_bins);
+  const int n_tiles = plan_n_tiles(p);
+  const BatchPlan b = plan_batch(leaf_offsets, 0, n_leaves, (int64_t)n_cus * wg_per_cu, n_tiles);
+  for (int32_t l = 0; l < n_leaves; ++l) {
+    leaf_wgs_out[l] = (int32_t)(b.leaf[l].wgs_unit & 0xffffu);
+    leaf_unit_epochs_out[l] = (int32_t)(b.leaf[l].wgs_unit >> 16);
+  }
+  const int64_t blocks = (int64_t)b.total_wgs * n_tiles;
+  for (int64_t i = 0; i < blocks && i < max_blocks; ++i) {
+    const BatchBlock k = batch_block(b.leaf, n_leaves, p.n_main, p.wr, (uint32_t)i);
+    block_out[3 * i] = k.leaf;
+    block_out[3 * i + 1] = k.tile;
+    block_out[3 * i + 2] = k.wg;
+  }
+  return (int)blocks;
 }
 
 int gbdt_debug_occupancy(int32_t n_bins, int32_t indexed) {

@@ -1,0 +1,235 @@
+"""GPU parity of the batched calls (through the C ABI): gbdt_hist_build_batch against the
+oracle's Alg. 1 leaf by leaf (counts bit-exact, sums within 1e-5 * sum|g| of that leaf) and
+gbdt_best_split_batch against the oracle scan of the same fp32 histograms; a depth-wise tree
+grown level by level with the batched calls is replayed node by node with the oracle."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import gbdt_oracle as orc
+from paper_1706_08359_amd import binding as B
+from paper_1706_08359_amd import synth
+
+from gpu_util import GpuProblem, assert_hist_close
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def _problem(n_rows, n_features, n_bins, seed):
+    rng = np.random.default_rng(seed)
+    bins = rng.integers(0, n_bins, size=(n_rows, n_features), dtype=np.uint8)
+    bins[:, 0] = n_bins - 1
+    grad = rng.normal(size=n_rows).astype(np.float32)
+    hess = rng.uniform(0.01, 1.0, size=n_rows).astype(np.float32)
+    return GpuProblem(bins, n_bins, grad, hess), rng
+
+
+def _check_batch(p, lists, what, pad_front=0):
+    """lists: one int32 numpy row list per leaf (may be empty)."""
+    cat = np.concatenate([np.zeros(pad_front, np.int32)] + [np.asarray(l, np.int32) for l in lists])
+    offs = np.concatenate([[pad_front], pad_front + np.cumsum([len(l) for l in lists])]).astype(np.int64)
+    idx_d = torch.from_numpy(cat).to(p.dev) if cat.size else None
+    hists = B.gbdt_hist_build_batch(p.packed, p.n_rows, p.n_features, p.n_bins, idx_d, offs, p.grad, p.hess)
+    torch.cuda.synchronize()
+    got = B.hist_to_numpy(hists)
+    assert got.shape == (len(lists), p.n_features, p.n_bins)
+    for l, rows in enumerate(lists):
+        rows = np.asarray(rows, np.int32)
+        ref = p.oracle(rows)
+        sg, sh = p.leaf_abs_sums(rows) if rows.size else (0.0, 0.0)
+        assert_hist_close(got[l], ref, sg, sh, f"{what} leaf {l} ({rows.size} rows)")
+    return hists, got
+
+
+SHAPES = [(5003, 65, 65), (3001, 100, 256), (7001, 137, 255), (2500, 129, 16), (2500, 257, 15),
+          (20011, 150, 32), (4099, 33, 63), (9001, 28, 255)]
+
+
+@pytest.mark.parametrize("n_rows,n_features,n_bins", SHAPES)
+def test_batch_small_shapes(n_rows, n_features, n_bins):
+    _say(f"batch small {n_rows}x{n_features} bins={n_bins}")
+    p, rng = _problem(n_rows, n_features, n_bins, 7 * n_rows + n_features)
+    perm = rng.permutation(n_rows).astype(np.int32)
+    # a level of a tree: disjoint sorted lists of very different sizes, one of them empty
+    cuts = np.sort(rng.choice(n_rows, size=6, replace=False))
+    level = [np.sort(part) for part in np.split(perm, cuts)]
+    level.insert(3, np.zeros(0, np.int32))
+    _check_batch(p, level, "level", pad_front=3)
+    # lists need not be disjoint, sorted or repeat-free
+    any_lists = [rng.integers(0, n_rows, size=int(s)).astype(np.int32) for s in (1, 513, 700, 2048, 5)]
+    _check_batch(p, any_lists, "any order")
+    _check_batch(p, [np.arange(n_rows, dtype=np.int32)], "one leaf = root")
+    _check_batch(p, [np.zeros(0, np.int32), np.zeros(0, np.int32)], "only empty leaves")
+
+
+def test_batch_more_leaves_than_one_launch_and_reproducible():
+    n_rows, n_features, n_bins = 60_000, 70, 64
+    _say(f"batch 300 leaves {n_rows}x{n_features} bins={n_bins}")
+    p, rng = _problem(n_rows, n_features, n_bins, 99)
+    perm = rng.permutation(n_rows).astype(np.int32)
+    cuts = np.sort(rng.choice(n_rows, size=299, replace=False))
+    lists = [np.sort(part) for part in np.split(perm, cuts)]
+    h1, got1 = _check_batch(p, lists, "300 leaves")
+    h2, got2 = _check_batch(p, lists, "300 leaves again")
+    assert torch.equal(h1, h2)                       # fixed split of the rows: same bits every time
+
+
+def test_batch_equals_single_leaf_calls_on_large_mixed_leaves():
+    """A few large leaves (many workgroups each, several units per workgroup) next to tiny ones."""
+    n_rows, n_features, n_bins = 700_000, 100, 200
+    _say(f"batch mixed {n_rows}x{n_features} bins={n_bins}")
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(5)
+    dev = torch.device("cuda:0")
+    bins = synth.uniform_bins(n_rows, n_features, n_bins, gen, dev)
+    grad, hess = synth.logistic_grad_hess(n_rows, gen, dev)
+    p = GpuProblem(bins, n_bins, grad, hess)
+    rng = np.random.default_rng(6)
+    perm = rng.permutation(n_rows).astype(np.int32)
+    sizes = [400_000, 3, 250_000, 0, 40_000, 600, 9_397]
+    lists, at = [], 0
+    for s in sizes:
+        lists.append(np.sort(perm[at:at + s]))
+        at += s
+    cols = np.array([0, 31, 32, 63, 64, 99])         # features of every tile, sampled for the oracle
+    cat = np.concatenate(lists)
+    offs = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    hists = B.gbdt_hist_build_batch(p.packed, n_rows, n_features, n_bins, torch.from_numpy(cat).to(dev), offs,
+                                    p.grad, p.hess)
+    got = B.hist_to_numpy(hists)
+    sub = np.ascontiguousarray(p.bins_cpu.numpy()[:, cols])
+    g_np, h_np = p.grad_cpu.numpy(), p.hess_cpu.numpy()
+    for l, rows in enumerate(lists):
+        assert (got[l]["count"].sum(axis=1, dtype=np.uint64) == rows.size).all()
+        ref = orc.hist_build(sub, n_bins, g_np, h_np, rows)
+        sg, sh = p.leaf_abs_sums(rows) if rows.size else (0.0, 0.0)
+        assert_hist_close(got[l][cols], ref, sg, sh, f"mixed leaf {l}")
+        # and the single-leaf call agrees on the counts everywhere
+        one = B.hist_to_numpy(p.build(rows)) if rows.size else None
+        if one is not None:
+            assert (one["count"] == got[l]["count"]).all()
+
+
+def test_best_split_batch_equals_single_calls_and_oracle():
+    n_rows, n_features, n_bins = 8000, 45, 64
+    _say("best_split_batch")
+    p, rng = _problem(n_rows, n_features, n_bins, 3)
+    perm = rng.permutation(n_rows).astype(np.int32)
+    lists = [np.sort(x) for x in np.split(perm, [10, 11, 3000, 3000, 7000])]   # 10, 1, 2989, 0, 4000, 1000 rows
+    hists, got = _check_batch(p, lists, "for split")
+    recs = B.gbdt_best_split_batch(hists, 1.0, 1e-3)
+    dicts = B.splits_to_dicts(recs)
+    assert len(dicts) == len(lists)
+    for l in range(len(lists)):
+        single = B.gbdt_best_split(hists[l], 1.0, 1e-3)
+        assert torch.equal(single, recs[l]), l                     # same kernel, same bits
+        lifted = orc.from_f32_hist(got[l]["grad"], got[l]["hess"], got[l]["count"])
+        s_ref = orc.best_split(lifted, 1.0, 1e-3)
+        assert (dicts[l]["feature"], dicts[l]["bin"]) == (s_ref["feature"], s_ref["bin"]), (l, dicts[l], s_ref)
+        if s_ref["feature"] >= 0:
+            assert dicts[l]["left_count"] == s_ref["left_count"]
+    assert dicts[1]["feature"] == -1 and dicts[3]["feature"] == -1   # one row / no rows: nothing to split
+
+
+# ------------------------------------------------------------------ a depth-wise tree, level by level
+
+def _grow_depthwise(p, depth, lam, mch):
+    """Level-wise growth with the batched calls: per level one batched split search over all
+    nodes, one partition per node that splits (into the level's shared row buffer, so the
+    children's lists lie back to back), ONE batched build of every smaller child, one
+    subtraction for all siblings, and the host reads the level's split records once."""
+    dev = p.dev
+    n, F, nb = p.n_rows, p.n_features, p.n_bins
+    rows = torch.arange(n, dtype=torch.int32, device=dev)
+    offs = [0, n]                                                   # node k of the level = rows[offs[k]:offs[k+1]]
+    hists = B.gbdt_hist_build_batch(p.packed, n, F, nb, rows, offs, p.grad, p.hess)
+    levels = []
+    for d in range(depth):
+        recs = B.gbdt_best_split_batch(hists, lam, mch)
+        dicts = B.splits_to_dicts(recs)
+        n_nodes = len(offs) - 1
+        new_rows = torch.empty_like(rows)
+        new_offs = [0]
+        small_offs, small_is_left, parents = [0], [], []
+        small_rows = torch.empty_like(rows)
+        for k in range(n_nodes):
+            lo, hi = offs[k], offs[k + 1]
+            s = dicts[k]
+            if s["feature"] < 0:                                    # stays a leaf: carried along unsplit
+                new_rows[lo:hi] = rows[lo:hi]
+                new_offs.append(hi)
+                continue
+            B.gbdt_partition_rows(p.packed, n, F, nb, rows[lo:hi], hi - lo, recs[k], new_rows[lo:hi])
+            nl = s["left_count"]
+            new_offs += [lo + nl, hi]
+            left_small = nl <= hi - lo - nl
+            a, b = (lo, lo + nl) if left_small else (lo + nl, hi)
+            small_rows[small_offs[-1]:small_offs[-1] + (b - a)] = new_rows[a:b]
+            small_offs.append(small_offs[-1] + (b - a))
+            small_is_left.append(left_small)
+            parents.append(k)
+        levels.append(dict(rows=rows, offs=offs, dicts=dicts, hists=hists))
+        if not parents:
+            break
+        h_small = B.gbdt_hist_build_batch(p.packed, n, F, nb, small_rows, small_offs, p.grad, p.hess)
+        par = hists[torch.tensor(parents, device=dev)]
+        h_large = B.gbdt_hist_subtract(par.reshape(-1, nb, 3), h_small.reshape(-1, nb, 3)).reshape(h_small.shape)
+        # children in node order; unsplit nodes keep their histogram
+        next_h, j = [], 0
+        for k in range(n_nodes):
+            if dicts[k]["feature"] < 0:
+                next_h.append(hists[k])
+                continue
+            l_h, r_h = (h_small[j], h_large[j]) if small_is_left[j] else (h_large[j], h_small[j])
+            next_h += [l_h, r_h]
+            j += 1
+        hists = torch.stack(next_h).contiguous()
+        rows, offs = new_rows, new_offs
+    levels.append(dict(rows=rows, offs=offs, dicts=None, hists=hists))
+    return levels
+
+
+@pytest.mark.parametrize("shape", [(50_000, 28, 255, 5), (40_000, 90, 16, 4), (30_000, 100, 64, 5)])
+def test_depthwise_tree_with_batched_calls_matches_oracle(shape):
+    n, F, nb, depth = shape
+    _say(f"depth-wise tree {n}x{F} bins={nb} depth={depth}")
+    rng = np.random.default_rng(n + F + 1)
+    bins = rng.integers(0, nb, size=(n, F), dtype=np.uint8)
+    y = (bins[:, 2] > nb // 2) ^ (bins[:, F // 2] > nb // 4) ^ (rng.random(n) < 0.25)
+    prob = 1.0 / (1.0 + np.exp(-rng.normal(0, 0.3, size=n)))
+    grad = (prob - y).astype(np.float32)
+    hess = (prob * (1 - prob)).astype(np.float32)
+    p = GpuProblem(bins, nb, grad, hess)
+    lam, mch = 1.0, 1e-3
+    levels = _grow_depthwise(p, depth, lam, mch)
+    assert len(levels) == depth + 1 and len(levels[-1]["offs"]) - 1 > 2 ** (depth - 1)
+    g64, h64 = np.abs(grad.astype(np.float64)), np.abs(hess.astype(np.float64))
+    root_budget = (g64.sum(), h64.sum())
+    for d, lv in enumerate(levels):
+        rows = lv["rows"].cpu().numpy()
+        got = B.hist_to_numpy(lv["hists"])
+        offs = lv["offs"]
+        # the level's nodes partition the rows, each list ascending
+        assert np.array_equal(np.sort(rows), np.arange(n))
+        for k in range(len(offs) - 1):
+            node = rows[offs[k]:offs[k + 1]]
+            assert np.all(np.diff(node) > 0)
+            # histogram of the node: built or subtracted along a chain of at most d builds, each
+            # within 1e-5 of its own leaf's sums, which the root's sums bound
+            ref = orc.hist_build(bins, nb, grad, hess, node)
+            assert_hist_close(got[k], ref, (d + 1) * root_budget[0], (d + 1) * root_budget[1], f"level {d} node {k}")
+            if lv["dicts"] is None:
+                continue
+            s = lv["dicts"][k]
+            lifted = orc.from_f32_hist(got[k]["grad"], got[k]["hess"], got[k]["count"])
+            s_same = orc.best_split(lifted, lam, mch)
+            assert (s["feature"], s["bin"]) == (s_same["feature"], s_same["bin"]), (d, k)
+            if s["feature"] >= 0:                                   # children = the oracle's partition
+                nxt = levels[d + 1]
+                ref_l, ref_r = orc.partition_rows(bins, s["feature"], s["bin"], node)
+                kids = nxt["rows"].cpu().numpy()[offs[k]:offs[k + 1]]
+                assert np.array_equal(kids[:ref_l.size], ref_l) and np.array_equal(kids[ref_l.size:], ref_r)

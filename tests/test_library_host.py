@@ -5,6 +5,7 @@ import ctypes
 import os
 import re
 
+import numpy as np
 import pytest
 
 from paper_1706_08359_amd import binding as B
@@ -62,6 +63,34 @@ def test_argument_errors_are_rejected_before_any_gpu_work():
     assert lib.gbdt_best_split(one, -1.0, 0.0, one, 5, 64, None) == EINVAL
     assert lib.gbdt_best_split(one, float("nan"), 0.0, one, 5, 64, None) == EINVAL
     assert lib.gbdt_best_split(one, 1.0, 0.0, one, 0, 64, None) == EINVAL
+    # batched build: the offsets are a HOST array, validated before anything else happens
+    offs = lambda *v: (ctypes.c_int64 * len(v))(*v)
+    B.load()
+    assert lib.gbdt_hist_build_batch(one, 10, 5, 64, one, offs(0, 3, 7), -1, one, one, one, None) == EINVAL
+    assert lib.gbdt_hist_build_batch(one, 10, 5, 64, one, offs(0, 3, 7), 0, one, one, one, None) == 0
+    assert lib.gbdt_hist_build_batch(one, 10, 5, 64, one, None, 2, one, one, one, None) == EINVAL
+    assert lib.gbdt_hist_build_batch(one, 10, 5, 64, one, offs(0, 3, 7), 2, one, one, None, None) == EINVAL
+    assert lib.gbdt_hist_build_batch(one, 10, 5, 64, one, offs(0, 7, 3), 2, one, one, one, None) == EINVAL
+    assert lib.gbdt_hist_build_batch(one, 10, 5, 64, one, offs(-1, 3, 7), 2, one, one, one, None) == EINVAL
+    assert lib.gbdt_hist_build_batch(one, 10, 5, 64, None, offs(0, 3, 7), 2, one, one, one, None) == EINVAL
+    assert lib.gbdt_hist_build_batch(None, 10, 5, 64, one, offs(0, 3, 7), 2, one, one, one, None) == EINVAL
+    assert lib.gbdt_hist_build_batch(one, 10, 5, 64, one, offs(0, 3, 7), 2, None, one, one, None) == EINVAL
+    assert lib.gbdt_hist_build_batch(one, 10, 5, 1, one, offs(0, 3, 7), 2, one, one, one, None) == EINVAL
+    assert lib.gbdt_hist_build_batch(one, 0, 5, 64, one, offs(0, 3, 7), 2, one, one, one, None) == EINVAL
+    assert lib.gbdt_hist_build_batch(one, 1 << 31, 5, 64, one, offs(0, 3, 7), 2, one, one, one, None) == EUNSUP
+    assert lib.gbdt_hist_build_batch_workspace_bytes(5, 1, 4) == 0
+    assert lib.gbdt_hist_build_batch_workspace_bytes(5, 64, -1) == 0
+    assert lib.gbdt_best_split_batch(one, -1, 1.0, 0.0, one, 5, 64, None) == EINVAL
+    assert lib.gbdt_best_split_batch(one, 0, 1.0, 0.0, one, 5, 64, None) == 0
+    assert lib.gbdt_best_split_batch(None, 2, 1.0, 0.0, one, 5, 64, None) == EINVAL
+    assert lib.gbdt_best_split_batch(one, 2, 1.0, 0.0, None, 5, 64, None) == EINVAL
+    assert lib.gbdt_best_split_batch(one, 2, -1.0, 0.0, one, 5, 64, None) == EINVAL
+    assert lib.gbdt_partition_rows(None, 10, 5, 64, None, 5, one, one, one, None) == EINVAL
+    assert lib.gbdt_partition_rows(one, 10, 5, 64, None, 5, None, one, one, None) == EINVAL
+    assert lib.gbdt_partition_rows(one, 10, 5, 64, None, 5, one, None, one, None) == EINVAL
+    assert lib.gbdt_partition_rows(one, 10, 5, 64, None, 11, one, one, one, None) == EINVAL
+    assert lib.gbdt_partition_rows(one, 10, 5, 64, None, -1, one, one, one, None) == EINVAL
+    assert lib.gbdt_partition_rows(one, 1 << 31, 5, 64, None, 5, one, one, one, None) == EUNSUP
     assert lib.gbdt_set_workspace(one, 0) == EINVAL
     assert lib.gbdt_set_workspace(None, 16) == EINVAL
     assert lib.gbdt_set_workspace(ctypes.c_void_p(100), 1024) == EINVAL               # misaligned
@@ -120,3 +149,47 @@ def test_workgroups_per_tile(n_features, n_bins, n_leaf):
     assert words == g["partial_words"]
     assert B.gbdt_workspace_bytes(n_leaf, n_features, n_bins) >= 4 * (g["partial_words"] + n_tiles)
     assert n_tiles * wgs < 2 ** 31
+
+
+@pytest.mark.parametrize("n_features,n_bins,wg_per_cu", [(28, 255, 2), (2000, 63, 3), (700, 16, 4), (137, 255, 2), (40, 64, 3)])
+def test_batched_launch_plan_covers_every_leaf_exactly(n_features, n_bins, wg_per_cu):
+    """Host planning of gbdt_hist_build_batch and the block -> (leaf, tile, workgroup) mapping
+    the kernel uses: every (leaf, tile, workgroup) is hit by exactly one block, empty leaves get
+    none, and a leaf's workgroups (unit c, c + wgs, ...) cover each of its epochs exactly once."""
+    rng = np.random.default_rng(n_features + n_bins)
+    geo = B.gbdt_debug_geometry(n_features, n_bins, 1)
+    n_tiles = geo["n_main"] + (1 if geo["wr"] else 0)
+    for trial in range(12):
+        n_leaves = int(rng.integers(1, 129))
+        kind = trial % 4
+        if kind == 0:
+            sizes = rng.integers(0, 3000, size=n_leaves)
+        elif kind == 1:
+            sizes = rng.integers(0, 2, size=n_leaves) * rng.integers(1, 200_000, size=n_leaves)
+        elif kind == 2:
+            sizes = np.full(n_leaves, 1)
+            sizes[0] = 3_000_000
+        else:
+            sizes = (2_000_000 * rng.dirichlet(np.ones(n_leaves))).astype(np.int64)
+        offs = np.concatenate([[5], 5 + np.cumsum(sizes)])
+        wgs, ue, blocks = B.gbdt_debug_batch_plan(n_features, n_bins, offs, 256, wg_per_cu)
+        assert blocks.shape[0] == int(wgs.sum()) * n_tiles
+        seen = set()
+        for leaf, tile, wg in blocks.tolist():
+            assert 0 <= leaf < n_leaves and 0 <= tile < n_tiles and 0 <= wg < wgs[leaf], (leaf, tile, wg)
+            seen.add((leaf, tile, wg))
+        assert len(seen) == blocks.shape[0]                      # no (leaf, tile, wg) twice
+        for l in range(n_leaves):
+            n_epochs = -(-int(sizes[l]) // 512)
+            if n_epochs == 0:
+                assert wgs[l] == 0
+                continue
+            assert 1 <= wgs[l] <= n_epochs and 1 <= ue[l] <= 4
+            n_units = -(-n_epochs // int(ue[l]))
+            assert wgs[l] <= n_units                             # no workgroup without a unit
+            # workgroup c takes units c, c + wgs, ...: together all units, each once
+            taken = sorted(u for c in range(wgs[l]) for u in range(c, n_units, int(wgs[l])))
+            assert taken == list(range(n_units))
+        # the leaves share the machine: about one machine-full of workgroup columns, plus the
+        # at-least-one of every leaf
+        assert int(wgs.sum()) <= 256 * wg_per_cu // n_tiles + n_leaves
