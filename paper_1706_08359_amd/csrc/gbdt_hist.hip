@@ -81,6 +81,9 @@ struct BuildArgs {
   int32_t wgs;          // workgroups per tile
   int32_t unit_epochs;  // consecutive epochs a workgroup takes at a time
   int32_t fixed_stride; // 0: units from the tile's counter; else unit u is followed by u + this
+  gbdt_bin_t* direct_out;  // wgs == 1 only: the histogram itself, written by the build kernel
+  int32_t n_features;
+  int32_t n_bins;
 };
 
 // A histogram cell is ONE 64-bit integer that carries, from the low bits up, the
@@ -134,6 +137,15 @@ __device__ __forceinline__ float wave_sum_to_lane63(float v) {
   v = dpp_add<0x143, 0xc>(v);  // row_bcast31: rows 2 and 3 add lane 31 (rows 0 + 1)
   return v;
 }
+
+// Where a workgroup that is the only one of its (leaf, tile) writes the finished
+// histogram itself instead of a partial block for the reduction pass (hist == NULL:
+// partial block).
+struct DirectOut {
+  gbdt_bin_t* hist;  // [n_features][n_bins] of the leaf
+  int32_t tile, wm, n_main, wr;
+  int32_t n_features, n_bins;
+};
 
 // Compile-time shape of the work of one wavefront on a tile of width W.
 template <int CAP, int W, bool NIB, int NT>
@@ -207,7 +219,7 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
                                            uint32_t first_unit, uint32_t unit_epochs,
                                            uint32_t fixed_stride, uint32_t* counter,
                                            unsigned long long* lds,
-                                           uint32_t* __restrict__ out) {
+                                           uint32_t* __restrict__ out, const DirectOut& direct) {
   using S = TileShape<CAP, W, NIB, NT>;
   constexpr int VEC = S::VEC, NWORD = S::NWORD, LPR = S::LPR, RPW = S::RPW, NBW = S::NBW;
   constexpr int CELLS = S::CELLS, PP = S::PP, NW = S::NW;
@@ -541,6 +553,32 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
     __syncthreads();  // cells are clear, `red` and the unit box are read, before reuse
   }
 
+  if (direct.hist) {
+    // The tile's only workgroup: its sums are the histogram.  Cell -> (bin, slot) ->
+    // feature, as the reduction pass would do it.
+    TilePlan plan;
+    plan.cap = CAP;
+    plan.nib = NIB ? 1 : 0;
+    plan.wm = direct.wm;
+    plan.n_main = direct.n_main;
+    plan.wr = direct.wr;
+    plan.row_bytes = plan.feat_bytes = 0;  // not used by the slot -> feature map
+#pragma unroll
+    for (int m = 0; m < PP; ++m) {
+      const int cell = tid + m * NT;
+      const int bin = (cell >> 5) % CAP;
+      const int slot = (cell / (CAP * 32)) * 32 + (cell & 31);
+      const int32_t f = plan_feature_of(plan, direct.tile, slot);
+      if (slot < S::SLOTS && bin < direct.n_bins && f < direct.n_features) {
+        gbdt_bin_t r;
+        r.grad = (float)acc_g[m];
+        r.hess = (float)acc_h[m];
+        r.count = acc_c[m];
+        direct.hist[(size_t)f * direct.n_bins + bin] = r;
+      }
+    }
+    return;
+  }
   // partial block layout: [stat][cell] words
 #pragma unroll
   for (int m = 0; m < PP; ++m) {
@@ -575,23 +613,24 @@ hist_build_kernel(BuildArgs a) {
   const int32_t c = b < main_blocks ? b / a.n_main : b - main_blocks;  // workgroup of the tile
   uint32_t* counter = a.counters + t;
   const uint8_t* tile = a.packed + a.n_rows * ((int64_t)t * WM);
+  const DirectOut direct = {a.direct_out, t, WM, a.n_main, a.wr, a.n_features, a.n_bins};
   if (b < main_blocks) {
     uint32_t* out = a.partials + ((size_t)t * a.wgs + c) * (size_t)block_words<CAP, WM, NIB, NT>();
     build_tile<CAP, WM, NIB, NT, ACC, INDEXED>(tile, a.idx, a.grad, a.hess, n_leaf, (uint32_t)c,
                                                (uint32_t)a.unit_epochs, (uint32_t)a.fixed_stride, counter,
-                                               lds, out);
+                                               lds, out, direct);
   } else {
     uint32_t* rem_base = a.partials + (size_t)main_blocks * (size_t)block_words<CAP, WM, NIB, NT>();
     if (a.wr == 16) {
       build_tile<CAP, 16, NIB, NT, ACC, INDEXED>(
           tile, a.idx, a.grad, a.hess, n_leaf, (uint32_t)c, (uint32_t)a.unit_epochs,
           (uint32_t)a.fixed_stride, counter, lds,
-          rem_base + (size_t)c * (size_t)block_words<CAP, 16, NIB, NT>());
+          rem_base + (size_t)c * (size_t)block_words<CAP, 16, NIB, NT>(), direct);
     } else if constexpr (WM > 32) {
       build_tile<CAP, 32, NIB, NT, ACC, INDEXED>(
           tile, a.idx, a.grad, a.hess, n_leaf, (uint32_t)c, (uint32_t)a.unit_epochs,
           (uint32_t)a.fixed_stride, counter, lds,
-          rem_base + (size_t)c * (size_t)block_words<CAP, 32, NIB, NT>());
+          rem_base + (size_t)c * (size_t)block_words<CAP, 32, NIB, NT>(), direct);
     }
   }
 }
@@ -612,7 +651,8 @@ counters_init_kernel(uint32_t* counters, int32_t wgs, int32_t n_counters) {
 // (batch_plan.h) owns the row list idx[row_off .. row_off + n) and wgs workgroups per tile, which take
 // its units of unit_epochs epochs in a fixed stride (no counters): a workgroup of leaf l
 // runs build_tile exactly as a single-leaf launch in its fixed-split mode would, and the
-// leaves' partial blocks lie back to back, each leaf's in the single-leaf order.
+// leaves' partial blocks lie back to back, each leaf's in the single-leaf order.  A leaf
+// with one workgroup per tile writes its histogram itself and skips the reduction pass.
 struct BatchArgs {
   const uint8_t* packed;
   const int32_t* idx;
@@ -623,6 +663,9 @@ struct BatchArgs {
   int32_t n_main;
   int32_t wr;
   int32_t n_leaves;
+  gbdt_bin_t* hist_out;  // [n_leaves][n_features][n_bins]: written directly by leaves of one workgroup per tile
+  int32_t n_features;
+  int32_t n_bins;
   BatchLeaf leaf[kBatchLeaves];
 };
 
@@ -650,20 +693,25 @@ hist_build_batch_kernel(BatchArgs a) {
   const uint8_t* tile = a.packed + a.n_rows * ((int64_t)t * WM);
   const int32_t* idx = a.idx + lf.row_off;
   uint32_t* leaf_out = a.partials + (size_t)lf.first_wg * column_words<CAP, WM, NIB, NT>(a.n_main, a.wr);
+  const DirectOut direct = {
+      wgs == 1 ? a.hist_out + (size_t)blk.leaf * a.n_features * a.n_bins : nullptr,
+      t, WM, a.n_main, a.wr, a.n_features, a.n_bins};
   if (is_main) {
     build_tile<CAP, WM, NIB, NT, ACC, true>(
         tile, idx, a.grad, a.hess, lf.n, (uint32_t)c, unit_epochs, (uint32_t)wgs, nullptr, lds,
-        leaf_out + ((size_t)t * wgs + c) * (size_t)block_words<CAP, WM, NIB, NT>());
+        leaf_out + ((size_t)t * wgs + c) * (size_t)block_words<CAP, WM, NIB, NT>(), direct);
   } else {
     uint32_t* rem_base = leaf_out + (size_t)main_blocks * (size_t)block_words<CAP, WM, NIB, NT>();
     if (a.wr == 16) {
       build_tile<CAP, 16, NIB, NT, ACC, true>(tile, idx, a.grad, a.hess, lf.n, (uint32_t)c, unit_epochs,
                                               (uint32_t)wgs, nullptr, lds,
-                                              rem_base + (size_t)c * (size_t)block_words<CAP, 16, NIB, NT>());
+                                              rem_base + (size_t)c * (size_t)block_words<CAP, 16, NIB, NT>(),
+                                              direct);
     } else if constexpr (WM > 32) {
       build_tile<CAP, 32, NIB, NT, ACC, true>(tile, idx, a.grad, a.hess, lf.n, (uint32_t)c, unit_epochs,
                                               (uint32_t)wgs, nullptr, lds,
-                                              rem_base + (size_t)c * (size_t)block_words<CAP, 32, NIB, NT>());
+                                              rem_base + (size_t)c * (size_t)block_words<CAP, 32, NIB, NT>(),
+                                              direct);
     }
   }
 }
@@ -753,7 +801,7 @@ __global__ void __launch_bounds__(kMergeCells * kMergeLanes) hist_merge_kernel(M
 // The same reduction for a batched launch: grid.z = leaf of the launch; its partial
 // blocks start first_wg workgroup columns into the buffer, its histogram is the leaf's
 // [n_features][n_bins] slice of the output.  A leaf without rows has no partial blocks
-// and gets zeros.
+// and gets zeros; a leaf with a single workgroup per tile is skipped.
 struct BatchMergeArgs {
   MergeArgs m;            // partials / out of leaf 0 of the launch; chunk counts unused
   uint64_t column_words;  // words of one workgroup column
@@ -762,6 +810,7 @@ struct BatchMergeArgs {
 
 __global__ void __launch_bounds__(kMergeCells * kMergeLanes) hist_merge_batch_kernel(BatchMergeArgs a) {
   const BatchLeaf lf = a.leaf[blockIdx.z];
+  if ((lf.wgs_unit & 0xffffu) == 1u) return;  // written by the build kernel itself
   MergeArgs m = a.m;
   m.partials += (size_t)lf.first_wg * a.column_words;
   m.out += (size_t)blockIdx.z * m.n_features * m.n_bins;
@@ -1256,9 +1305,39 @@ struct BuildGeom {
   size_t lds_bytes;     // LDS per workgroup
   int wgs;              // workgroups per tile
   int unit_epochs;      // epochs per unit
+  bool one_unit_each;   // short leaf: every workgroup has exactly one unit, no counter
   size_t partial_words;  // total words of all partial blocks
   size_t counter_words;  // one unit counter per tile
 };
+
+// Leaves of at most this many epochs get ONE workgroup per tile, which writes the
+// finished histogram itself: a second launch (the reduction pass) would cost more than
+// the few epochs a second workgroup could take over.
+constexpr int kDirectEpochs = 4;
+
+// Workgroups per tile and epochs per unit for a leaf of n_epochs epochs that may use
+// `budget` workgroups per tile: units of kUnitEpochs when every workgroup gets at least
+// one of them; otherwise (short leaf) one shorter unit per workgroup, and the unit
+// counter is not needed (*one_unit_each_out).
+void plan_leaf_units(int64_t n_epochs, int64_t budget, int* wgs_out, int* unit_epochs_out,
+                     bool* one_unit_each_out) {
+  int64_t wgs = budget;
+  if (wgs > n_epochs) wgs = n_epochs;
+  if (n_epochs <= kDirectEpochs) wgs = 1;
+  if (wgs < 1) wgs = 1;
+  int unit_epochs = kUnitEpochs;
+  bool one_each = false;
+  if (wgs * kUnitEpochs >= n_epochs) {
+    unit_epochs = (int)((n_epochs + wgs - 1) / wgs);
+    if (unit_epochs < 1) unit_epochs = 1;
+    const int64_t n_units = (n_epochs + unit_epochs - 1) / unit_epochs;
+    if (n_units >= 1 && wgs > n_units) wgs = n_units;  // no workgroup without a unit
+    one_each = true;
+  }
+  *wgs_out = (int)wgs;
+  *unit_epochs_out = unit_epochs;
+  *one_unit_each_out = one_each;
+}
 
 // Chooses the grid: as many workgroups per tile as fit the machine at once (they stay
 // until their tile's units are used up), and the unit size.  wg_per_cu: resident
@@ -1284,19 +1363,7 @@ BuildGeom make_geom(int32_t n_features, int32_t n_bins, int64_t n_leaf, int cus,
   const int64_t n_epochs = (n_leaf + kEpochRows - 1) / kEpochRows;
   // (A narrow tile's epochs are cheaper, but not by much: the per-epoch overhead does
   // not shrink with the tile.  It gets as many workgroups as a main tile.)
-  int64_t wgs = resident / n_tiles;  // per tile
-  if (wgs > n_epochs) wgs = n_epochs;
-  if (wgs < 1) wgs = 1;
-  // Units: kUnitEpochs when every workgroup gets at least one of them; otherwise (short
-  // leaf) one shorter unit per workgroup, none from the counter.
-  g.unit_epochs = kUnitEpochs;
-  if (wgs * kUnitEpochs > n_epochs) {
-    g.unit_epochs = (int)((n_epochs + wgs - 1) / wgs);
-    if (g.unit_epochs < 1) g.unit_epochs = 1;
-    const int64_t n_units = (n_epochs + g.unit_epochs - 1) / g.unit_epochs;
-    if (n_units >= 1 && wgs > n_units) wgs = n_units;  // no workgroup without a unit
-  }
-  g.wgs = (int)wgs;
+  plan_leaf_units(n_epochs, resident / n_tiles, &g.wgs, &g.unit_epochs, &g.one_unit_each);
   g.partial_words = (size_t)p.n_main * g.wgs * main_block +
                     (size_t)(p.wr ? g.wgs : 0) * 3 * (p.wr ? plan_cells(p, p.wr) : 0);
   g.counter_words = (size_t)n_tiles;
@@ -1411,24 +1478,6 @@ size_t variant_column_words(const TilePlan& p) {
   return column_words<CAP, WM, NIB, NT>(p.n_main, p.wr);
 }
 
-// Workgroups per tile and epochs per unit for a leaf of n_epochs epochs that may use
-// `budget` workgroups per tile: units of kUnitEpochs when every workgroup gets at least
-// one of them; otherwise (short leaf) one shorter unit per workgroup.
-void plan_leaf_units(int64_t n_epochs, int64_t budget, int* wgs_out, int* unit_epochs_out) {
-  int64_t wgs = budget;
-  if (wgs > n_epochs) wgs = n_epochs;
-  if (wgs < 1) wgs = 1;
-  int unit_epochs = kUnitEpochs;
-  if (wgs * kUnitEpochs > n_epochs) {
-    unit_epochs = (int)((n_epochs + wgs - 1) / wgs);
-    if (unit_epochs < 1) unit_epochs = 1;
-    const int64_t n_units = (n_epochs + unit_epochs - 1) / unit_epochs;
-    if (n_units >= 1 && wgs > n_units) wgs = n_units;  // no workgroup without a unit
-  }
-  *wgs_out = (int)wgs;
-  *unit_epochs_out = unit_epochs;
-}
-
 // Plan of one batched launch: leaves [l0, l0 + n) of the call share the machine in
 // proportion to their epochs, at least one workgroup per tile each.
 struct BatchPlan {
@@ -1451,7 +1500,8 @@ BatchPlan plan_batch(const int64_t* leaf_offsets, int32_t l0, int32_t n, int64_t
     const int64_t rows = leaf_offsets[l0 + i + 1] - leaf_offsets[l0 + i];
     const int64_t n_epochs = (rows + kEpochRows - 1) / kEpochRows;
     int wgs = 0, unit_epochs = 1;
-    if (n_epochs > 0) plan_leaf_units(n_epochs, budget * n_epochs / total_epochs, &wgs, &unit_epochs);
+    bool one_each = false;
+    if (n_epochs > 0) plan_leaf_units(n_epochs, budget * n_epochs / total_epochs, &wgs, &unit_epochs, &one_each);
     b.leaf[i].row_off = (uint32_t)(leaf_offsets[l0 + i] - leaf_offsets[l0]);
     b.leaf[i].n = (uint32_t)rows;
     b.leaf[i].first_wg = first;
@@ -1560,13 +1610,19 @@ int gbdt_hist_build(const void* bin_matrix, int64_t n_rows, int32_t n_features, 
   a.wr = p.wr;
   a.wgs = g.wgs;
   a.unit_epochs = g.unit_epochs;
-  a.fixed_stride = g_deterministic.load() ? g.wgs : 0;
+  // no counter when every workgroup has one unit anyway, or when the split must be fixed
+  a.fixed_stride = (g.one_unit_each || g_deterministic.load()) ? g.wgs : 0;
+  a.direct_out = g.wgs == 1 ? hist_out : nullptr;
+  a.n_features = n_features;
+  a.n_bins = n_bins;
   const int n_tiles = plan_n_tiles(p);
   const int blocks = n_tiles * g.wgs;
-  const int n_counters = (int)g.counter_words;
-  hipLaunchKernelGGL(counters_init_kernel, dim3((n_counters + 255) / 256), dim3(256), 0, s,
-                     a.counters, g.wgs, n_counters);
-  HIP_TRY(hipGetLastError());
+  if (a.fixed_stride == 0) {
+    const int n_counters = (int)g.counter_words;
+    hipLaunchKernelGGL(counters_init_kernel, dim3((n_counters + 255) / 256), dim3(256), 0, s,
+                       a.counters, g.wgs, n_counters);
+    HIP_TRY(hipGetLastError());
+  }
 
   if (p.cap == 16) {
     rc = launch_build<GBDT_VARIANT_16>(a, blocks, s);
@@ -1576,6 +1632,7 @@ int gbdt_hist_build(const void* bin_matrix, int64_t n_rows, int32_t n_features, 
     rc = launch_build<GBDT_VARIANT_256>(a, blocks, s);
   }
   if (rc != GBDT_OK) return rc;
+  if (a.direct_out) return GBDT_OK;  // one workgroup per tile: the histogram is written
 
   MergeArgs m;
   m.partials = (const uint32_t*)ws;
@@ -1656,6 +1713,9 @@ int gbdt_hist_build_batch(const void* bin_matrix, int64_t n_rows, int32_t n_feat
       a.n_main = p.n_main;
       a.wr = p.wr;
       a.n_leaves = n;
+      a.hist_out = hist_out + (size_t)l0 * n_features * n_bins;
+      a.n_features = n_features;
+      a.n_bins = n_bins;
       memcpy(a.leaf, b.leaf, sizeof a.leaf);
       const int blocks = (int)b.total_wgs * n_tiles;
       if (p.cap == 16) {
@@ -1667,6 +1727,9 @@ int gbdt_hist_build_batch(const void* bin_matrix, int64_t n_rows, int32_t n_feat
       }
       if (rc != GBDT_OK) return rc;
     }
+    bool any_to_merge = false;  // empty leaves (zeros) or leaves of several workgroups per tile
+    for (int32_t i = 0; i < n; ++i) any_to_merge |= (b.leaf[i].wgs_unit & 0xffffu) != 1u;
+    if (!any_to_merge) continue;
     const int max_slots = plan_slots(p, p.wm);
     const int mx = (n_bins * max_slots + kMergeCells - 1) / kMergeCells;
     hipLaunchKernelGGL(hist_merge_batch_kernel, dim3(mx, n_tiles, n), dim3(kMergeCells * kMergeLanes), 0,

@@ -11,6 +11,7 @@ CPU oracle is timed beside it on a bounded sample of the same leaf.
     python -m paper_1706_08359_amd.measure_all --skew         # App. A.3: constant-bin features
     python -m paper_1706_08359_amd.measure_all --partition    # row partition after a split (App. C.1)
     python -m paper_1706_08359_amd.measure_all --tree         # 255-leaf trees grown with library calls only
+    python -m paper_1706_08359_amd.measure_all --batch-sweep  # a whole tree level per launch vs. leaf by leaf
 """
 from __future__ import annotations
 
@@ -306,12 +307,71 @@ def tree(args, torch, B, synth, dev):
         torch.cuda.empty_cache()
 
 
+def batch_sweep(args, torch, B, synth, dev):
+    """The depth benchmark of App. C.2 (8,000,000 x 500, leaves of N / 2^D rows), taken over a
+    whole tree level: the 2^D leaves of depth D (a random partition of the rows into equal
+    sorted lists) built one call per leaf, and all of them in one gbdt_hist_build_batch call."""
+    print("| bins | D | leaves | rows per leaf | leaf by leaf: ms per level (calls) | batched: ms per level | "
+          "batched build kernels ms | speed-up | batched G feature-values/s | batched algorithmic GB/s | % of 8 TB/s |")
+    print("|" + "---|" * 11, flush=True)
+    n, F = 8_000_000, 500
+    for nb in (64, 256):
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(100 + nb)
+        bins = synth.uniform_bins(n, F, nb, gen, dev)
+        grad, hess = synth.logistic_grad_hess(n, gen, dev)
+        packed = B.gbdt_bins_pack(bins, nb)
+        del bins
+        perm = torch.randperm(n, generator=gen, device=dev).to(torch.int32)
+        for depth in range(1, 11):
+            n_leaves = 2 ** depth
+            per = n // n_leaves
+            offs = [i * per for i in range(n_leaves)] + [n]
+            rows = torch.cat([torch.sort(perm[offs[i]:offs[i + 1]]).values for i in range(n_leaves)]).contiguous()
+            hist = torch.empty((n_leaves, F, nb, 3), dtype=torch.float32, device=dev)
+
+            def one_by_one():
+                for i in range(n_leaves):
+                    B.gbdt_hist_build(packed, n, F, nb, rows[offs[i]:offs[i + 1]], offs[i + 1] - offs[i],
+                                      grad, hess, hist_out=hist[i])
+
+            def batched():
+                B.gbdt_hist_build_batch(packed, n, F, nb, rows, offs, grad, hess, hist_out=hist)
+
+            res = {}
+            for name, fn, reps in (("single", one_by_one, 3 if depth >= 7 else 5), ("batch", batched, 10)):
+                fn()
+                torch.cuda.synchronize()
+                ts, ks = [], []
+                for _ in range(reps):
+                    B.gbdt_profile_enable(True)
+                    e0, e1 = _events(torch)
+                    e0.record()
+                    fn()
+                    e1.record()
+                    torch.cuda.synchronize()
+                    B.gbdt_profile_enable(False)
+                    ms, _k = B.gbdt_profile_collect()
+                    ts.append(e0.elapsed_time(e1))
+                    ks.append(ms)
+                res[name] = (statistics.median(ts), statistics.median(ks))
+            t_single, t_batch, k_batch = res["single"][0], res["batch"][0], res["batch"][1]
+            alg = algorithmic_bytes(n, F, nb, True) + (n_leaves - 1) * F * nb * 12
+            print(f"| {nb} | {depth} | {n_leaves} | {per:,} | {t_single:.3f} ({n_leaves}) | {t_batch:.3f} | {k_batch:.3f} | "
+                  f"{t_single / t_batch:.2f}x | {n * F / (t_batch * 1e-3) / 1e9:,.0f} | {alg / (t_batch * 1e-3) / 1e9:,.0f} | "
+                  f"{100 * alg / (t_batch * 1e-3) / 1e9 / HBM_PEAK_GBS:.1f} |", flush=True)
+            del rows, hist
+        del packed, perm
+        torch.cuda.empty_cache()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--depth-sweep", action="store_true")
     ap.add_argument("--skew", action="store_true")
     ap.add_argument("--partition", action="store_true")
     ap.add_argument("--tree", action="store_true")
+    ap.add_argument("--batch-sweep", action="store_true")
     ap.add_argument("--oracle", action="store_true", help="time the CPU oracle on the root leaves")
     ap.add_argument("--only", nargs="*", default=None)
     args = ap.parse_args()
@@ -332,6 +392,8 @@ def main():
         partition(args, torch, B, synth, dev)
     elif args.tree:
         tree(args, torch, B, synth, dev)
+    elif args.batch_sweep:
+        batch_sweep(args, torch, B, synth, dev)
     else:
         five_workloads(args, torch, B, synth, dev)
 

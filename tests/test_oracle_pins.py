@@ -352,3 +352,99 @@ def test_partition_sizes_and_sums_match_the_split_record(seed):
     hr = orc.hist_build(bins, B, grad, hess, right)
     assert np.array_equal(hl["count"] + hr["count"], parent["count"])
     assert np.allclose(hl["grad"] + hr["grad"], parent["grad"], rtol=0, atol=1e-9)
+
+
+# ------------------------------------------------------------ leaf-wise tree growth (Sec. 3.1, Sec. 5)
+
+from oracle import tree_oracle  # noqa: E402
+
+
+def _tree_problem(seed, n=400, F=4, B=8):
+    rng = np.random.default_rng(seed)
+    bins = rng.integers(0, B, size=(n, F), dtype=np.uint8)
+    grad = rng.normal(size=n).astype(np.float32)
+    hess = rng.uniform(0.2, 1.0, size=n).astype(np.float32)
+    return bins, grad, hess, B
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_tree_every_step_is_the_greedy_choice_by_brute_force(seed):
+    """Replays the growth: at every step the node that was split must be the open leaf whose
+    best split -- found by exhaustive search over raw rows, no histogram -- has the largest
+    gain, and its (feature, bin) must be that exhaustive search's answer."""
+    bins, grad, hess, B = _tree_problem(seed)
+    lam, mch = 0.5, 1e-3
+    nodes = tree_oracle.grow_tree(bins, B, grad, hess, 9, lam, mch)
+    assert sum(1 for nd in nodes if nd["left"] < 0) == 9 and len(nodes) == 17
+    bf = {}
+
+    def brute(k):
+        if k not in bf:
+            bf[k] = brute_force_best_split(bins, B, grad, hess, nodes[k]["rows"], lam, mch)
+        return bf[k]
+
+    open_leaves = [0]
+    # splits were made in the creation order of their children
+    order = sorted((nd["left"], k) for k, nd in enumerate(nodes) if nd["left"] >= 0)
+    for _, k in order:
+        gains = {j: brute(j)[2] for j in open_leaves if brute(j)[0] >= 0}
+        assert k in gains
+        assert gains[k] >= max(gains.values()) - 1e-9 * max(1.0, abs(gains[k]))
+        f, t, _ = brute(k)
+        assert (nodes[k]["split"]["feature"], nodes[k]["split"]["bin"]) == (f, t)
+        open_leaves.remove(k)
+        open_leaves += [nodes[k]["left"], nodes[k]["right"]]
+
+
+def test_tree_rows_are_where_the_splits_route_them():
+    bins, grad, hess, B = _tree_problem(7, n=3000, F=6, B=16)
+    nodes = tree_oracle.grow_tree(bins, B, grad, hess, 31, 1.0, 1e-3)
+    at = tree_oracle.route_rows(bins, nodes)
+    leaves = [k for k, nd in enumerate(nodes) if nd["left"] < 0]
+    assert len(leaves) == 31
+    total = 0
+    for k in leaves:
+        assert np.array_equal(np.nonzero(at == k)[0], nodes[k]["rows"])      # ascending, complete
+        total += nodes[k]["count"]
+    assert total == 3000
+    for nd in nodes:
+        if nd["left"] >= 0:
+            l, r = nodes[nd["left"]], nodes[nd["right"]]
+            assert l["parent"] == r["parent"] == nodes.index(nd)
+            assert l["count"] == nd["split"]["left_count"] and r["count"] == nd["split"]["right_count"]
+            assert np.isclose(l["sum_grad"], nd["split"]["left_grad"], rtol=0, atol=1e-9)
+            assert np.isclose(r["sum_hess"], nd["split"]["right_hess"], rtol=0, atol=1e-9)
+            assert np.isclose(l["sum_grad"] + r["sum_grad"], nd["sum_grad"], rtol=0, atol=1e-9)
+
+
+def test_tree_recovers_a_planted_two_level_structure():
+    """Labels are a function of (feature 1 > 3) and then, on each side, of a different feature:
+    the first three splits must be exactly those."""
+    rng = np.random.default_rng(11)
+    n, F, B = 4000, 5, 8
+    bins = rng.integers(0, B, size=(n, F), dtype=np.uint8)
+    a = bins[:, 1] > 3
+    y = np.where(a, np.where(bins[:, 3] > 5, 4.0, 1.0), np.where(bins[:, 0] > 1, -1.0, -4.0))
+    grad = (-y).astype(np.float32)                    # square loss at prediction 0: g = -y, h = 1
+    hess = np.ones(n, np.float32)
+    nodes = tree_oracle.grow_tree(bins, B, grad, hess, 4, 0.0, 0.0)
+    assert (nodes[0]["split"]["feature"], nodes[0]["split"]["bin"]) == (1, 3)
+    kids = {(nodes[k]["split"]["feature"], nodes[k]["split"]["bin"]) for k in (1, 2)}
+    assert kids == {(0, 1), (3, 5)}
+    # with 4 leaves every leaf is pure: its value -G/H is the planted label
+    for nd in nodes:
+        if nd["left"] < 0:
+            val = -nd["sum_grad"] / nd["sum_hess"]
+            assert min(abs(val - v) for v in (4.0, 1.0, -1.0, -4.0)) < 1e-9
+
+
+def test_tree_stops_when_nothing_can_be_split():
+    bins = np.zeros((50, 3), np.uint8)               # every feature constant: no admissible threshold
+    grad = np.linspace(-1, 1, 50).astype(np.float32)
+    hess = np.ones(50, np.float32)
+    nodes = tree_oracle.grow_tree(bins, 4, grad, hess, 8, 1.0, 0.0)
+    assert len(nodes) == 1 and nodes[0]["split"]["feature"] == -1 and nodes[0]["count"] == 50
+    # a gain threshold no split reaches stops growth the same way
+    bins, grad, hess, B = _tree_problem(3)
+    nodes = tree_oracle.grow_tree(bins, B, grad, hess, 8, 1.0, 1e-3, min_split_gain=1e9)
+    assert len(nodes) == 1
