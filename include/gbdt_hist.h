@@ -12,7 +12,8 @@
  *    `stream` has finished.  No call takes a host data pointer.
  *  - `stream` is a hipStream_t passed as void*; NULL is the default stream.
  *    Calls enqueue kernels and return; they do not synchronise and never read
- *    device data on the host.
+ *    device data on the host (gbdt_grow_tree, which drives the others, is the one
+ *    exception and says so).
  *  - Return value: GBDT_OK (0) or a negative gbdt_status code.  Argument
  *    errors are detected before anything is enqueued.  Contents of device
  *    buffers (bin values < n_bins, row ids < n_rows) are NOT checked;
@@ -238,6 +239,55 @@ int gbdt_partition_rows(const void* bin_matrix, int64_t n_rows, int32_t n_featur
                         int32_t n_bins, const int32_t* leaf_row_idx, int64_t n_leaf_rows,
                         const gbdt_split_t* split, int32_t* children_out, int64_t* n_left_out,
                         void* stream);
+
+/*
+ * One node of a tree grown by gbdt_grow_tree (a HOST struct).  Node 0 is the root; the two
+ * children of a split get the next two ids, left first, so parents precede children.
+ */
+typedef struct {
+  int32_t parent;  /* -1 for the root */
+  int32_t left;    /* children; -1 for a leaf */
+  int32_t right;
+  int32_t feature; /* the node's best split as gbdt_best_split found it (applied when left >= 0); */
+  int32_t bin;     /* feature = bin = -1 when no threshold is admissible */
+  float gain;
+  float sum_grad;  /* sums over the node's rows (for a leaf value such as -G / (H + lambda)) */
+  float sum_hess;
+  uint32_t count;
+  int32_t reserved;
+  int64_t row_begin; /* the node's rows are row_order_out[row_begin .. row_begin + count) */
+} gbdt_tree_node_t;
+
+/*
+ * Grows one regression tree leaf-wise, entirely from the calls above, with row lists and
+ * histograms resident on the device (Sec. 3.1: start from the root and keep splitting
+ * leaves; Sec. 5: stop at a fixed number of leaves, 255 in the experiments, at least one
+ * sample per leaf; App. A.5 / App. C.1: what the CPU does around the histogram kernel --
+ * rebuild and copy the index list after each split -- is done here by
+ * gbdt_partition_rows, so nothing but two 36-byte split records per split crosses the
+ * bus).  The paper does not say which leaf is split next; this takes the open leaf whose
+ * best split has the largest gain (it must exceed min_split_gain), the older leaf on
+ * equal gains.  Per split: partition the leaf's rows, build the histogram of the smaller
+ * child, subtract it from the parent's for the sibling, search both for their best split.
+ *   grad, hess       DEVICE float [n_rows]
+ *   max_leaves       >= 1; growth also stops when no open leaf has an admissible split
+ *   scratch          DEVICE, 256-byte aligned, gbdt_grow_tree_scratch_bytes(...) bytes
+ *                    (two row lists, max_leaves histograms, the split records); the
+ *                    calls inside also use the library's scratch workspace
+ *   nodes_out        HOST gbdt_tree_node_t [2 * max_leaves - 1]
+ *   n_nodes_out      HOST, receives the number of nodes written (always odd)
+ *   row_order_out    DEVICE int32 [n_rows] or NULL: all row ids, grouped by leaf, ascending
+ *                    inside each node's segment (see row_begin)
+ * Unlike the other calls this one WAITS for `stream` (once per split, to read the two
+ * new split records) and allocates a few bytes of page-locked host memory on first use.
+ */
+int gbdt_grow_tree(const void* bin_matrix, int64_t n_rows, int32_t n_features, int32_t n_bins,
+                   const float* grad, const float* hess, int32_t max_leaves, float lambda,
+                   float min_child_hess, float min_split_gain, void* scratch, size_t scratch_bytes,
+                   gbdt_tree_node_t* nodes_out, int32_t* n_nodes_out, int32_t* row_order_out,
+                   void* stream);
+size_t gbdt_grow_tree_scratch_bytes(int64_t n_rows, int32_t n_features, int32_t n_bins,
+                                    int32_t max_leaves);
 
 /*
  * Scratch workspace.  By default the library allocates device scratch itself

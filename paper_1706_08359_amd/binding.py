@@ -23,7 +23,7 @@ EXPORTS = [
     "gbdt_profile_enable", "gbdt_profile_collect", "gbdt_debug_occupancy",
     "gbdt_calibration_copy", "gbdt_set_deterministic", "gbdt_partition_rows",
     "gbdt_hist_build_batch", "gbdt_hist_build_batch_workspace_bytes", "gbdt_best_split_batch",
-    "gbdt_debug_batch_plan",
+    "gbdt_debug_batch_plan", "gbdt_grow_tree", "gbdt_grow_tree_scratch_bytes",
 ]
 
 # numpy views of the two C structs
@@ -31,6 +31,10 @@ BIN_DTYPE = np.dtype([("grad", "<f4"), ("hess", "<f4"), ("count", "<u4")])
 SPLIT_DTYPE = np.dtype([("feature", "<i4"), ("bin", "<i4"), ("gain", "<f4"),
                         ("left_grad", "<f4"), ("left_hess", "<f4"), ("left_count", "<u4"),
                         ("right_grad", "<f4"), ("right_hess", "<f4"), ("right_count", "<u4")])
+
+NODE_DTYPE = np.dtype([("parent", "<i4"), ("left", "<i4"), ("right", "<i4"), ("feature", "<i4"),
+                       ("bin", "<i4"), ("gain", "<f4"), ("sum_grad", "<f4"), ("sum_hess", "<f4"),
+                       ("count", "<u4"), ("reserved", "<i4"), ("row_begin", "<i8")])
 
 _lib = None
 
@@ -71,6 +75,12 @@ def load():
     lib.gbdt_best_split_batch.restype = c.c_int
     lib.gbdt_best_split_batch.argtypes = [c.c_void_p, c.c_int32, c.c_float, c.c_float, c.c_void_p,
                                           c.c_int32, c.c_int32, c.c_void_p]
+    lib.gbdt_grow_tree.restype = c.c_int
+    lib.gbdt_grow_tree.argtypes = [c.c_void_p, c.c_int64, c.c_int32, c.c_int32, c.c_void_p, c.c_void_p,
+                                   c.c_int32, c.c_float, c.c_float, c.c_float, c.c_void_p, c.c_size_t,
+                                   c.c_void_p, c.POINTER(c.c_int32), c.c_void_p, c.c_void_p]
+    lib.gbdt_grow_tree_scratch_bytes.restype = c.c_size_t
+    lib.gbdt_grow_tree_scratch_bytes.argtypes = [c.c_int64, c.c_int32, c.c_int32, c.c_int32]
     lib.gbdt_partition_rows.restype = c.c_int
     lib.gbdt_partition_rows.argtypes = [c.c_void_p, c.c_int64, c.c_int32, c.c_int32, c.c_void_p,
                                         c.c_int64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p]
@@ -277,6 +287,38 @@ def gbdt_partition_rows(bin_matrix, n_rows, n_features, n_bins, leaf_row_idx, n_
                                       _dev(n_left_out, torch.int64, "n_left_out"),
                                       _stream(stream)), "gbdt_partition_rows")
     return children_out, n_left_out
+
+
+def gbdt_grow_tree_scratch_bytes(n_rows: int, n_features: int, n_bins: int, max_leaves: int) -> int:
+    return int(load().gbdt_grow_tree_scratch_bytes(n_rows, n_features, n_bins, max_leaves))
+
+
+def gbdt_grow_tree(bin_matrix, n_rows, n_features, n_bins, grad, hess, max_leaves, lam, min_child_hess,
+                   min_split_gain=0.0, scratch=None, row_order_out=None, want_rows=True, stream=None):
+    """Returns (nodes, row_order_out, scratch): nodes is a numpy structured array (NODE_DTYPE) of
+    the nodes written; row_order_out an int32 CUDA tensor [n_rows] (None with want_rows=False);
+    scratch the uint8 CUDA tensor used (pass it back in to avoid reallocating).  Waits for the stream."""
+    need = gbdt_grow_tree_scratch_bytes(n_rows, n_features, n_bins, max_leaves)
+    if need == 0:
+        raise GbdtError("gbdt_grow_tree_scratch_bytes: invalid argument")
+    if scratch is None or scratch.numel() < need:
+        scratch = torch.empty(need, dtype=torch.uint8, device=grad.device)
+    if grad.numel() < n_rows or hess.numel() < n_rows:
+        raise GbdtError("grad/hess shorter than n_rows")
+    if bin_matrix.numel() < gbdt_bins_packed_bytes(n_rows, n_features, n_bins):
+        raise GbdtError("bin_matrix smaller than the packed layout of this shape")
+    if want_rows and row_order_out is None:
+        row_order_out = torch.empty(max(n_rows, 1), dtype=torch.int32, device=grad.device)
+    nodes = np.zeros(2 * max_leaves - 1, dtype=NODE_DTYPE)
+    n_nodes = ctypes.c_int32(0)
+    _check(load().gbdt_grow_tree(_dev(bin_matrix, torch.uint8, "bin_matrix"), n_rows, n_features, n_bins,
+                                 _dev(grad, torch.float32, "grad"), _dev(hess, torch.float32, "hess"),
+                                 max_leaves, float(lam), float(min_child_hess), float(min_split_gain),
+                                 _dev(scratch, torch.uint8, "scratch"), scratch.numel(),
+                                 nodes.ctypes.data, ctypes.byref(n_nodes),
+                                 None if row_order_out is None else _dev(row_order_out, torch.int32, "row_order_out"),
+                                 _stream(stream)), "gbdt_grow_tree")
+    return nodes[:n_nodes.value], row_order_out, scratch
 
 
 def split_record(feature: int, bin_: int, device) -> torch.Tensor:

@@ -1198,6 +1198,12 @@ partition_scatter_kernel(const int32_t* __restrict__ idx, int64_t n_leaf, int32_
   }
 }
 
+// out[i] = i: the row list of the root, for a tree that never splits.
+__global__ void __launch_bounds__(256) row_iota_kernel(int32_t* __restrict__ out, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) out[i] = (int32_t)i;
+}
+
 // ------------------------------------------------------- calibration copy kernel
 
 // Plain copy of n 16-byte words: a kernel of known HBM traffic (n * 16 bytes read, n *
@@ -1511,6 +1517,42 @@ BatchPlan plan_batch(const int64_t* leaf_offsets, int32_t l0, int32_t n, int64_t
   b.total_wgs = first;
   return b;
 }
+
+// Scratch of gbdt_grow_tree.
+size_t align256(size_t b) { return (b + 255) / 256 * 256; }
+
+struct TreeScratch {
+  size_t rows_a, rows_b, hists, recs, total;  // byte offsets
+};
+
+TreeScratch tree_scratch_layout(int64_t n_rows, int32_t n_features, int32_t n_bins, int32_t max_leaves) {
+  TreeScratch t;
+  const size_t rows = align256((size_t)(n_rows > 0 ? n_rows : 1) * sizeof(int32_t));
+  t.rows_a = 0;
+  t.rows_b = rows;
+  t.hists = 2 * rows;
+  t.recs = t.hists + align256((size_t)max_leaves * n_features * n_bins * sizeof(gbdt_bin_t));
+  t.total = t.recs + align256((size_t)2 * max_leaves * sizeof(gbdt_split_t));
+  return t;
+}
+
+// Two split records in page-locked host memory, the landing place of the per-split
+// device-to-host copy (one per process, never freed).
+gbdt_split_t* pinned_records() {
+  static gbdt_split_t* p = nullptr;
+  static std::mutex mu;
+  std::lock_guard<std::mutex> lk(mu);
+  if (!p) {
+    void* q = nullptr;
+    if (hipHostMalloc(&q, 2 * sizeof(gbdt_split_t), hipHostMallocDefault) != hipSuccess) {
+      (void)hipGetLastError();
+      return nullptr;
+    }
+    p = (gbdt_split_t*)q;
+  }
+  return p;
+}
+
 
 }  // namespace
 
@@ -1831,6 +1873,153 @@ int gbdt_partition_rows(const void* bin_matrix, int64_t n_rows, int32_t n_featur
                      leaf_row_idx, n_leaf_rows, g.rows_per_thread, (const uint64_t*)flags,
                      (const uint32_t*)chunk_left, g.n_chunks, children_out, n_left_out);
   HIP_TRY(hipGetLastError());
+  return GBDT_OK;
+}
+
+// --- leaf-wise tree growth -------------------------------------------------------------
+
+size_t gbdt_grow_tree_scratch_bytes(int64_t n_rows, int32_t n_features, int32_t n_bins,
+                                    int32_t max_leaves) {
+  if (!valid_shape(n_rows, n_features, n_bins) || max_leaves < 1) return 0;
+  return tree_scratch_layout(n_rows, n_features, n_bins, max_leaves).total;
+}
+
+int gbdt_grow_tree(const void* bin_matrix, int64_t n_rows, int32_t n_features, int32_t n_bins,
+                   const float* grad, const float* hess, int32_t max_leaves, float lambda,
+                   float min_child_hess, float min_split_gain, void* scratch, size_t scratch_bytes,
+                   gbdt_tree_node_t* nodes_out, int32_t* n_nodes_out, int32_t* row_order_out,
+                   void* stream) {
+  if (!valid_shape(n_rows, n_features, n_bins)) return GBDT_EINVAL;
+  if (max_leaves < 1 || !nodes_out || !n_nodes_out || !scratch) return GBDT_EINVAL;
+  if (!(lambda >= 0.0f) || min_split_gain != min_split_gain) return GBDT_EINVAL;
+  if (n_rows > 0 && (!bin_matrix || !grad || !hess)) return GBDT_EINVAL;
+  if (((uintptr_t)scratch & 255u) != 0) return GBDT_EINVAL;
+  if (n_rows >= ((int64_t)1 << 30)) return GBDT_EUNSUPPORTED;
+  const TreeScratch lay = tree_scratch_layout(n_rows, n_features, n_bins, max_leaves);
+  if (scratch_bytes < lay.total) return GBDT_ENOMEM;
+  gbdt_split_t* pinned = pinned_records();
+  if (!pinned) return GBDT_ENOMEM;
+  hipStream_t s = (hipStream_t)stream;
+  char* base = (char*)scratch;
+  int32_t* rows_buf[2] = {(int32_t*)(base + lay.rows_a), (int32_t*)(base + lay.rows_b)};
+  gbdt_bin_t* pool = (gbdt_bin_t*)(base + lay.hists);
+  gbdt_split_t* recs = (gbdt_split_t*)(base + lay.recs);
+  const size_t hist_elems = (size_t)n_features * n_bins;
+
+  struct Leaf {
+    int slot;  // histogram slot in the pool
+    int buf;   // row buffer that holds the node's rows; -1: rows 0..n-1, nowhere stored
+  };
+  std::vector<Leaf> state(2 * (size_t)max_leaves);
+  std::vector<gbdt_split_t> host_recs(2 * (size_t)max_leaves);  // every node's record, as read back
+  auto fill_node = [&](int k, int parent, const gbdt_split_t& r, float sg, float sh, uint32_t cnt,
+                       int64_t begin) {
+    gbdt_tree_node_t& nd = nodes_out[k];
+    nd.parent = parent;
+    nd.left = nd.right = -1;
+    nd.feature = r.feature;
+    nd.bin = r.bin;
+    nd.gain = r.gain;
+    nd.sum_grad = sg;
+    nd.sum_hess = sh;
+    nd.count = cnt;
+    nd.reserved = 0;
+    nd.row_begin = begin;
+  };
+
+  // root
+  int rc = gbdt_hist_build(bin_matrix, n_rows, n_features, n_bins, nullptr, n_rows, grad, hess, pool, s);
+  if (rc != GBDT_OK) return rc;
+  rc = gbdt_best_split(pool, lambda, min_child_hess, recs, n_features, n_bins, s);
+  if (rc != GBDT_OK) return rc;
+  HIP_TRY(hipMemcpyAsync(pinned, recs, sizeof(gbdt_split_t), hipMemcpyDeviceToHost, s));
+  HIP_TRY(hipStreamSynchronize(s));
+  {
+    const gbdt_split_t r = pinned[0];
+    float sg = r.left_grad + r.right_grad, sh = r.left_hess + r.right_hess;
+    if (r.feature < 0 && n_rows > 0) {
+      // no split record carries the totals: sum feature 0's bins on the host
+      std::vector<gbdt_bin_t> row((size_t)n_bins);
+      HIP_TRY(hipMemcpyAsync(row.data(), pool, (size_t)n_bins * sizeof(gbdt_bin_t), hipMemcpyDeviceToHost, s));
+      HIP_TRY(hipStreamSynchronize(s));
+      double g = 0.0, h = 0.0;
+      for (const gbdt_bin_t& b : row) {
+        g += b.grad;
+        h += b.hess;
+      }
+      sg = (float)g;
+      sh = (float)h;
+    }
+    fill_node(0, -1, r, sg, sh, (uint32_t)n_rows, 0);
+    state[0] = {0, -1};
+    host_recs[0] = r;
+  }
+  int n_nodes = 1, n_leaves = 1, next_slot = 1;
+  while (n_leaves < max_leaves) {
+    int k = -1;
+    for (int i = 0; i < n_nodes; ++i) {  // ascending id: equal gains go to the older leaf
+      const gbdt_tree_node_t& nd = nodes_out[i];
+      if (nd.left >= 0 || nd.feature < 0 || !(nd.gain > min_split_gain)) continue;
+      if (k < 0 || nd.gain > nodes_out[k].gain) k = i;
+    }
+    if (k < 0) break;
+    gbdt_tree_node_t& par = nodes_out[k];
+    const int64_t begin = par.row_begin;
+    const int src_buf = state[k].buf;
+    const int dst_buf = src_buf == 0 ? 1 : 0;
+    const int32_t* src = src_buf < 0 ? nullptr : rows_buf[src_buf] + begin;
+    int32_t* dst = rows_buf[dst_buf] + begin;
+    rc = gbdt_partition_rows(bin_matrix, n_rows, n_features, n_bins, src, par.count, recs + k, dst,
+                             nullptr, s);
+    if (rc != GBDT_OK) return rc;
+    const gbdt_split_t prec = host_recs[k];  // the same record the device partitions by
+    const uint32_t nl = prec.left_count, nr = prec.right_count;
+    const int left = n_nodes, right = n_nodes + 1;
+    const bool left_small = nl <= nr;
+    const int small = left_small ? left : right, large = left_small ? right : left;
+    const int64_t small_begin = left_small ? begin : begin + nl;
+    const uint32_t small_n = left_small ? nl : nr;
+    state[small] = {next_slot++, dst_buf};
+    state[large] = {state[k].slot, dst_buf};  // the sibling takes over the parent's histogram slot
+    gbdt_bin_t* h_small = pool + (size_t)state[small].slot * hist_elems;
+    gbdt_bin_t* h_large = pool + (size_t)state[large].slot * hist_elems;
+    rc = gbdt_hist_build(bin_matrix, n_rows, n_features, n_bins, rows_buf[dst_buf] + small_begin, small_n,
+                         grad, hess, h_small, s);
+    if (rc != GBDT_OK) return rc;
+    rc = gbdt_hist_subtract(h_large, h_small, h_large, n_features, n_bins, s);
+    if (rc != GBDT_OK) return rc;
+    rc = gbdt_best_split(pool + (size_t)state[left].slot * hist_elems, lambda, min_child_hess, recs + left,
+                         n_features, n_bins, s);
+    if (rc != GBDT_OK) return rc;
+    rc = gbdt_best_split(pool + (size_t)state[right].slot * hist_elems, lambda, min_child_hess, recs + right,
+                         n_features, n_bins, s);
+    if (rc != GBDT_OK) return rc;
+    HIP_TRY(hipMemcpyAsync(pinned, recs + left, 2 * sizeof(gbdt_split_t), hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    par.left = left;
+    par.right = right;
+    host_recs[left] = pinned[0];
+    host_recs[right] = pinned[1];
+    fill_node(left, k, pinned[0], prec.left_grad, prec.left_hess, nl, begin);
+    fill_node(right, k, pinned[1], prec.right_grad, prec.right_hess, nr, begin + nl);
+    n_nodes += 2;
+    n_leaves += 1;
+  }
+  *n_nodes_out = n_nodes;
+  if (row_order_out && n_rows > 0) {
+    for (int i = 0; i < n_nodes; ++i) {
+      const gbdt_tree_node_t& nd = nodes_out[i];
+      if (nd.left >= 0 || nd.count == 0) continue;
+      if (state[i].buf < 0) {
+        hipLaunchKernelGGL(row_iota_kernel, dim3((unsigned)((n_rows + 255) / 256)), dim3(256), 0, s,
+                           row_order_out, n_rows);
+        HIP_TRY(hipGetLastError());
+      } else {
+        HIP_TRY(hipMemcpyAsync(row_order_out + nd.row_begin, rows_buf[state[i].buf] + nd.row_begin,
+                               (size_t)nd.count * sizeof(int32_t), hipMemcpyDeviceToDevice, s));
+      }
+    }
+  }
   return GBDT_OK;
 }
 
