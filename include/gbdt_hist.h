@@ -201,10 +201,11 @@ int gbdt_best_split(const gbdt_bin_t* hist, float lambda, float min_child_hess,
 /*
  * gbdt_best_split for n_hists histograms at once: splits_out[i] is the best split of
  * hists[i] (e.g. the two children of a split, or a level of a tree), same rule, same
- * arithmetic, two kernel launches for the whole batch.
+ * arithmetic, one kernel launch for up to 32768 histograms.
  *   hists       DEVICE gbdt_bin_t [n_hists][n_features][n_bins]
  *   splits_out  DEVICE gbdt_split_t [n_hists], overwritten
- * n_hists == 0 is a no-op.
+ * n_hists == 0 is a no-op.  Scratch: 56 bytes per histogram and group of up to 32
+ * features (a caller-owned workspace sized by gbdt_workspace_bytes covers two histograms).
  */
 int gbdt_best_split_batch(const gbdt_bin_t* hists, int32_t n_hists, float lambda,
                           float min_child_hess, gbdt_split_t* splits_out, int32_t n_features,

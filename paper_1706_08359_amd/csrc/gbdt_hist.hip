@@ -858,8 +858,53 @@ struct SplitCand {
   int32_t bin;
 };
 
+static_assert(sizeof(SplitCand) == 7 * 8, "a candidate is moved as 7 64-bit words");
+
 constexpr int kSplitThreads = 256;
 constexpr int kSplitLdsBudget = 48 * 1024;
+constexpr int kSplitMaxHists = 32768;  // histograms per launch (grid.y)
+
+// One ticket counter per histogram of a launch: the workgroups of a histogram count
+// themselves off, and the last of them sets the counter back to zero, so the counters
+// need no resetting between launches (zero when the module is loaded).
+__device__ unsigned int g_split_ticket[kSplitMaxHists];
+
+// Candidates cross from the workgroups that write them to the one that reduces them,
+// possibly on another XCD with its own L2: they are moved with device-scope atomic
+// accesses (which bypass the caches that are not coherent across XCDs), inside the
+// release / acquire fences around the ticket.
+__device__ __forceinline__ void store_cand(SplitCand* dst, const SplitCand& c) {
+  unsigned long long w[7];
+  memcpy(w, &c, sizeof c);
+  unsigned long long* d = reinterpret_cast<unsigned long long*>(dst);
+#pragma unroll
+  for (int i = 0; i < 7; ++i) __hip_atomic_store(d + i, w[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ SplitCand load_cand(const SplitCand* src) {
+  unsigned long long w[7];
+  const unsigned long long* p = reinterpret_cast<const unsigned long long*>(src);
+#pragma unroll
+  for (int i = 0; i < 7; ++i)
+    w[i] = __hip_atomic_load(const_cast<unsigned long long*>(p) + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  SplitCand c;
+  memcpy(&c, w, sizeof c);
+  return c;
+}
+__device__ __forceinline__ double load_cand_gain(const SplitCand* src) {
+  const unsigned long long w = __hip_atomic_load(
+      const_cast<unsigned long long*>(reinterpret_cast<const unsigned long long*>(src)), __ATOMIC_RELAXED,
+      __HIP_MEMORY_SCOPE_AGENT);
+  double g;
+  memcpy(&g, &w, sizeof g);
+  return g;
+}
+__device__ __forceinline__ int32_t load_cand_feature(const SplitCand* src) {
+  // word 6 = (feature, bin)
+  const unsigned long long w = __hip_atomic_load(
+      const_cast<unsigned long long*>(reinterpret_cast<const unsigned long long*>(src)) + 6, __ATOMIC_RELAXED,
+      __HIP_MEMORY_SCOPE_AGENT);
+  return (int32_t)(uint32_t)(w & 0xffffffffull);
+}
 
 // LDS bytes one feature needs in split_gain_kernel: raw bins (12 B) + fp64 prefix of
 // grad and hess (16 B) + prefix of count (4 B) per bin, + the feature's parent term.
@@ -874,17 +919,25 @@ __host__ __device__ inline int split_feature_bytes(int n_bins) { return 32 * n_b
 //     the order "larger gain, then smaller feature, then smaller bin".
 // Feature totals are the prefix at the last bin, right = total - left, a threshold is
 // admissible when both sides hold >= 1 sample and >= min_child_hess of hessian.
+//  4. The workgroup that finishes last for its histogram (a ticket taken after its own
+//     candidate is written and fenced; nobody waits) reduces the candidates of all
+//     workgroups to the histogram's split record: workgroups hold ascending feature
+//     groups, so "smaller candidate index" is "smaller feature".
+// grid.y = histogram of the call; histogram y starts hist_stride bins after histogram
+// y - 1 (the stride may be negative: any two histograms of a pool can be searched in
+// one launch).
 __global__ void __launch_bounds__(kSplitThreads)
-split_gain_kernel(const gbdt_bin_t* __restrict__ hist, int32_t n_features, int32_t n_bins,
-                  int32_t group, double lambda, double min_child_hess,
-                  SplitCand* __restrict__ cand) {
+split_gain_kernel(const gbdt_bin_t* __restrict__ hist, int64_t hist_stride, int32_t n_features,
+                  int32_t n_bins, int32_t group, double lambda, double min_child_hess,
+                  SplitCand* __restrict__ cand, gbdt_split_t* __restrict__ out) {
   extern __shared__ __align__(16) unsigned char smem[];
   __shared__ double s_gain[kSplitThreads];
   __shared__ int32_t s_pair[kSplitThreads];
+  __shared__ int s_last;
   const int tid = threadIdx.x;
-  // grid.y = histogram of a batched call
-  hist += (size_t)blockIdx.y * n_features * n_bins;
+  hist += (int64_t)blockIdx.y * hist_stride;
   cand += (size_t)blockIdx.y * gridDim.x;
+  out += blockIdx.y;
   const int32_t f0 = blockIdx.x * group;
   const int32_t nf = (n_features - f0 < group) ? (n_features - f0) : group;
   const int B = n_bins;
@@ -904,7 +957,24 @@ split_gain_kernel(const gbdt_bin_t* __restrict__ hist, int32_t n_features, int32
     const uint32_t* r = raw + (size_t)tid * B * 3;
     double G = 0.0, H = 0.0;
     uint32_t N = 0;
-    for (int b = 0; b < B; ++b) {
+    // The sums run strictly left to right; only the reads of the next 8 bins are issued
+    // together, ahead of the adds that need them (the loop is bound by LDS latency).
+    int b0 = 0;
+    for (; b0 + 8 <= B; b0 += 8) {
+      uint32_t w[24];
+#pragma unroll
+      for (int i = 0; i < 24; ++i) w[i] = r[3 * b0 + i];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        G = G + (double)__uint_as_float(w[3 * i]);
+        H = H + (double)__uint_as_float(w[3 * i + 1]);
+        N = N + w[3 * i + 2];
+        pg[tid * B + b0 + i] = G;
+        ph[tid * B + b0 + i] = H;
+        pn[tid * B + b0 + i] = N;
+      }
+    }
+    for (int b = b0; b < B; ++b) {
       G = G + (double)__uint_as_float(r[3 * b]);
       H = H + (double)__uint_as_float(r[3 * b + 1]);
       N = N + r[3 * b + 2];
@@ -976,27 +1046,32 @@ split_gain_kernel(const gbdt_bin_t* __restrict__ hist, int32_t n_features, int32
       c.feature = f0 + fl;
       c.bin = t;
     }
-    cand[blockIdx.x] = c;
+    store_cand(cand + blockIdx.x, c);
+    // The candidate's stores are device-scope atomics (written through, not left dirty in
+    // this XCD's L2): once they are acknowledged they are visible device-wide, so waiting
+    // for them (vmcnt(0)) is all the release the ticket needs -- a full fence would also
+    // write back every dirty line of the L2, which costs tens of microseconds here.
+    __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0); expcnt, lgkmcnt untouched
+    const unsigned int old = __hip_atomic_fetch_add(&g_split_ticket[blockIdx.y], 1u, __ATOMIC_RELAXED,
+                                                    __HIP_MEMORY_SCOPE_AGENT);
+    const bool last = old == gridDim.x - 1;
+    if (last)  // back to zero for the next launch
+      __hip_atomic_store(&g_split_ticket[blockIdx.y], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    s_last = last;
   }
-}
+  __syncthreads();
+  if (!s_last) return;
+  // The ticket's value has arrived, so every other workgroup's candidate was acknowledged
+  // before its ticket; the loads below are device-scope atomics and bypass stale caches.
 
-// Arg-max over the per-workgroup candidates (workgroups hold ascending feature
-// groups, so "smaller candidate index" is "smaller feature").  One workgroup; each
-// thread folds a strided subset in ascending order, then a tree reduction.  grid.x =
-// histogram of a batched call.
-__global__ void __launch_bounds__(256)
-split_argmax_kernel(const SplitCand* __restrict__ cand, int32_t n_cand,
-                    gbdt_split_t* __restrict__ out) {
-  __shared__ double s_gain[256];
-  __shared__ int32_t s_idx[256];
-  const int tid = threadIdx.x;
-  cand += (size_t)blockIdx.x * n_cand;
-  out += blockIdx.x;
+  // ---- the histogram's last workgroup: arg-max over all candidates.  Each thread folds
+  // a strided subset in ascending order, then a tree reduction.
+  const int32_t n_cand = (int32_t)gridDim.x;
   double bg = 0.0;
   int32_t bi = -1;
-  for (int32_t i = tid; i < n_cand; i += 256) {
-    if (cand[i].feature >= 0) {
-      const double g = cand[i].gain;
+  for (int32_t i = tid; i < n_cand; i += kSplitThreads) {
+    if (load_cand_feature(cand + i) >= 0) {
+      const double g = load_cand_gain(cand + i);
       if (bi < 0 || g > bg) {  // i ascends, so ties keep the smaller feature
         bg = g;
         bi = i;
@@ -1004,25 +1079,25 @@ split_argmax_kernel(const SplitCand* __restrict__ cand, int32_t n_cand,
     }
   }
   s_gain[tid] = bg;
-  s_idx[tid] = bi;
+  s_pair[tid] = bi;
   __syncthreads();
-  for (int s = 128; s > 0; s >>= 1) {
+  for (int s = kSplitThreads / 2; s > 0; s >>= 1) {
     if (tid < s) {
       const double g2 = s_gain[tid + s];
-      const int32_t i2 = s_idx[tid + s];
+      const int32_t i2 = s_pair[tid + s];
       const double g1 = s_gain[tid];
-      const int32_t i1 = s_idx[tid];
+      const int32_t i1 = s_pair[tid];
       const bool take = i2 >= 0 && (i1 < 0 || g2 > g1 || (g2 == g1 && i2 < i1));
       if (take) {
         s_gain[tid] = g2;
-        s_idx[tid] = i2;
+        s_pair[tid] = i2;
       }
     }
     __syncthreads();
   }
   if (tid == 0) {
     gbdt_split_t r;
-    const int32_t i = s_idx[0];
+    const int32_t i = s_pair[0];
     if (i < 0) {
       r.feature = -1;
       r.bin = -1;
@@ -1030,7 +1105,7 @@ split_argmax_kernel(const SplitCand* __restrict__ cand, int32_t n_cand,
       r.left_grad = r.left_hess = r.right_grad = r.right_hess = 0.0f;
       r.left_count = r.right_count = 0;
     } else {
-      const SplitCand c = cand[i];
+      const SplitCand c = load_cand(cand + i);
       r.feature = c.feature;
       r.bin = c.bin;
       r.gain = (float)c.gain;
@@ -1518,6 +1593,24 @@ BatchPlan plan_batch(const int64_t* leaf_offsets, int32_t l0, int32_t n, int64_t
   return b;
 }
 
+// Split search of n_hists (<= kSplitMaxHists) histograms, hist_stride bins apart, in one
+// launch; splits_out[i] receives the record of histogram i.
+int launch_split(const gbdt_bin_t* hists, int64_t hist_stride, int32_t n_hists, float lambda,
+                 float min_child_hess, gbdt_split_t* splits_out, int32_t n_features, int32_t n_bins,
+                 hipStream_t s) {
+  int group = 0, n_groups = 0;
+  split_grouping(n_features, n_bins, &group, &n_groups);
+  void* ws = nullptr;
+  int rc = get_workspace((size_t)n_hists * n_groups * sizeof(SplitCand), &ws);
+  if (rc != GBDT_OK) return rc;
+  const size_t lds = (size_t)group * split_feature_bytes(n_bins);
+  hipLaunchKernelGGL(split_gain_kernel, dim3(n_groups, n_hists), dim3(kSplitThreads), lds, s, hists,
+                     hist_stride, n_features, n_bins, group, (double)lambda, (double)min_child_hess,
+                     (SplitCand*)ws, splits_out);
+  HIP_TRY(hipGetLastError());
+  return GBDT_OK;
+}
+
 // Scratch of gbdt_grow_tree.
 size_t align256(size_t b) { return (b + 255) / 256 * 256; }
 
@@ -1595,7 +1688,7 @@ size_t gbdt_workspace_bytes(int64_t n_rows, int32_t n_features, int32_t n_bins) 
              g0.counter_words * 4;
   int sg = 0, sn = 0;
   split_grouping(n_features, n_bins, &sg, &sn);
-  const size_t cand = (size_t)sn * sizeof(SplitCand);
+  const size_t cand = (size_t)2 * sn * sizeof(SplitCand);  // gbdt_grow_tree searches two histograms at once
   if (cand > b) b = cand;
   const size_t part = make_part_geom(n_rows > 0 ? n_rows : 1).bytes;
   if (part > b) b = part;
@@ -1817,24 +1910,12 @@ int gbdt_best_split_batch(const gbdt_bin_t* hists, int32_t n_hists, float lambda
   if (!(lambda >= 0.0f)) return GBDT_EINVAL;
   if (n_hists == 0) return GBDT_OK;
   if (!hists || !splits_out) return GBDT_EINVAL;
-  int group = 0, n_groups = 0;
-  split_grouping(n_features, n_bins, &group, &n_groups);
-  constexpr int32_t kMaxPerLaunch = 32768;  // grid.y limit is 65535
-  const int32_t per_launch = n_hists < kMaxPerLaunch ? n_hists : kMaxPerLaunch;
-  void* ws = nullptr;
-  int rc = get_workspace((size_t)per_launch * n_groups * sizeof(SplitCand), &ws);
-  if (rc != GBDT_OK) return rc;
-  hipStream_t s = (hipStream_t)stream;
-  const size_t lds = (size_t)group * split_feature_bytes(n_bins);
-  for (int32_t h0 = 0; h0 < n_hists; h0 += per_launch) {
-    const int32_t nh = n_hists - h0 < per_launch ? n_hists - h0 : per_launch;
-    hipLaunchKernelGGL(split_gain_kernel, dim3(n_groups, nh), dim3(kSplitThreads), lds, s,
-                       hists + (size_t)h0 * n_features * n_bins, n_features, n_bins, group,
-                       (double)lambda, (double)min_child_hess, (SplitCand*)ws);
-    HIP_TRY(hipGetLastError());
-    hipLaunchKernelGGL(split_argmax_kernel, dim3(nh), dim3(256), 0, s, (const SplitCand*)ws,
-                       n_groups, splits_out + h0);
-    HIP_TRY(hipGetLastError());
+  const int64_t stride = (int64_t)n_features * n_bins;
+  for (int32_t h0 = 0; h0 < n_hists; h0 += kSplitMaxHists) {
+    const int32_t nh = n_hists - h0 < kSplitMaxHists ? n_hists - h0 : kSplitMaxHists;
+    const int rc = launch_split(hists + (size_t)h0 * stride, stride, nh, lambda, min_child_hess,
+                                splits_out + h0, n_features, n_bins, (hipStream_t)stream);
+    if (rc != GBDT_OK) return rc;
   }
   return GBDT_OK;
 }
@@ -1988,11 +2069,10 @@ int gbdt_grow_tree(const void* bin_matrix, int64_t n_rows, int32_t n_features, i
     if (rc != GBDT_OK) return rc;
     rc = gbdt_hist_subtract(h_large, h_small, h_large, n_features, n_bins, s);
     if (rc != GBDT_OK) return rc;
-    rc = gbdt_best_split(pool + (size_t)state[left].slot * hist_elems, lambda, min_child_hess, recs + left,
-                         n_features, n_bins, s);
-    if (rc != GBDT_OK) return rc;
-    rc = gbdt_best_split(pool + (size_t)state[right].slot * hist_elems, lambda, min_child_hess, recs + right,
-                         n_features, n_bins, s);
+    // both children in one launch: their histograms sit in two slots of the pool
+    rc = launch_split(pool + (size_t)state[left].slot * hist_elems,
+                      ((int64_t)state[right].slot - state[left].slot) * (int64_t)hist_elems, 2, lambda,
+                      min_child_hess, recs + left, n_features, n_bins, s);
     if (rc != GBDT_OK) return rc;
     HIP_TRY(hipMemcpyAsync(pinned, recs + left, 2 * sizeof(gbdt_split_t), hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));

@@ -10,7 +10,7 @@ CPU oracle is timed beside it on a bounded sample of the same leaf.
     python -m paper_1706_08359_amd.measure_all --depth-sweep  # App. C.2: 8,000,000 x 500, leaf = N / 2^D
     python -m paper_1706_08359_amd.measure_all --skew         # App. A.3: constant-bin features
     python -m paper_1706_08359_amd.measure_all --partition    # row partition after a split (App. C.1)
-    python -m paper_1706_08359_amd.measure_all --tree         # 255-leaf trees grown with library calls only
+    python -m paper_1706_08359_amd.measure_all --tree         # 255-leaf trees grown by gbdt_grow_tree
     python -m paper_1706_08359_amd.measure_all --batch-sweep  # a whole tree level per launch vs. leaf by leaf
 """
 from __future__ import annotations
@@ -233,77 +233,37 @@ def partition(args, torch, B, synth, dev):
         torch.cuda.empty_cache()
 
 
-def grow_tree(B, torch, packed, w, n_leaves, timers=None):
-    """Leaf-wise growth (Sec. 5: 255 leaves) from library calls alone: root build, then per split
-    partition the best open leaf, build its smaller child, subtract for the sibling, search both.
-    Row lists and histograms never leave the device; the host reads the two new split records per
-    split (it needs them to pick the next leaf).  Returns the number of leaves reached."""
-    n, F, nb = w.n_rows, w.n_features, w.n_bins
-
-    def timed(key, fn):
-        if timers is None:
-            return fn()
-        e0, e1 = _events(torch)
-        e0.record()
-        r = fn()
-        e1.record()
-        timers.setdefault(key, []).append((e0, e1))
-        return r
-
-    hist = timed("build", lambda: B.gbdt_hist_build(packed, n, F, nb, None, n, w.grad, w.hess))
-    rec = timed("split", lambda: B.gbdt_best_split(hist, w.lam, w.min_child_hess))
-    leaves = [dict(rows=None, n=n, hist=hist, rec=rec, s=B.split_to_dict(rec))]
-    while len(leaves) < n_leaves:
-        best = None
-        for l in leaves:
-            if l["s"]["feature"] >= 0 and (best is None or l["s"]["gain"] > best["s"]["gain"]):
-                best = l
-        if best is None:
-            break
-        leaves = [l for l in leaves if l is not best]
-        kids, _ = timed("partition", lambda: B.gbdt_partition_rows(packed, n, F, nb, best["rows"], best["n"], best["rec"]))
-        nl, nr = best["s"]["left_count"], best["s"]["right_count"]
-        rows_l, rows_r = kids[:nl], kids[nl:nl + nr]
-        small = rows_l if nl <= nr else rows_r
-        h_small = timed("build", lambda: B.gbdt_hist_build(packed, n, F, nb, small, small.numel(), w.grad, w.hess))
-        h_large = timed("subtract", lambda: B.gbdt_hist_subtract(best["hist"], h_small))
-        h_l, h_r = (h_small, h_large) if nl <= nr else (h_large, h_small)
-        rec_l = timed("split", lambda: B.gbdt_best_split(h_l, w.lam, w.min_child_hess))
-        rec_r = timed("split", lambda: B.gbdt_best_split(h_r, w.lam, w.min_child_hess))
-        leaves.append(dict(rows=rows_l, n=nl, hist=h_l, rec=rec_l, s=B.split_to_dict(rec_l)))
-        leaves.append(dict(rows=rows_r, n=nr, hist=h_r, rec=rec_r, s=B.split_to_dict(rec_r)))
-    return len(leaves)
-
-
 def tree(args, torch, B, synth, dev):
-    """Whole 255-leaf trees (the tree size of Sec. 5) on every workload: wall time per tree and
-    the GPU time of each kind of call inside it."""
-    print("| workload | leaves | wall ms / tree | build ms (calls) | partition ms (calls) | subtract ms | "
-          "split search ms | GPU busy % of wall |")
-    print("|" + "---|" * 8, flush=True)
+    """Whole 255-leaf trees (the tree size of Sec. 5) grown by gbdt_grow_tree on every workload:
+    host wall time per tree, stream synchronised at both ends (median of 5 after a warm-up)."""
+    print("| workload | rows x features, bins | leaves reached | deepest leaf | wall ms / tree (median) | wall ms / tree (min) | "
+          "splits / s |")
+    print("|" + "---|" * 7, flush=True)
     for name, make in WORKLOADS.items():
         if args.only and name not in args.only:
             continue
         w = make(synth, dev)
-        packed = B.gbdt_bins_pack(w.bins, w.n_bins)
-        grow_tree(B, torch, packed, w, 255)                     # warm-up (scratch allocation)
-        torch.cuda.synchronize()
+        n, F, nb = w.n_rows, w.n_features, w.n_bins
+        packed = B.gbdt_bins_pack(w.bins, nb)
+        del w.bins
+        scratch, order = None, torch.empty(n, dtype=torch.int32, device=dev)
         walls = []
-        for _ in range(3):
-            t0 = time.perf_counter()
-            reached = grow_tree(B, torch, packed, w, 255)
+        for rep in range(6):
             torch.cuda.synchronize()
-            walls.append((time.perf_counter() - t0) * 1e3)
-        timers = {}
-        grow_tree(B, torch, packed, w, 255, timers)
-        torch.cuda.synchronize()
-        ms = {k: sum(a.elapsed_time(b) for a, b in v) for k, v in timers.items()}
-        busy = sum(ms.values())
-        wall = statistics.median(walls)
-        print(f"| {name} | {reached} | {wall:.1f} | {ms.get('build', 0):.2f} ({len(timers.get('build', []))}) | "
-              f"{ms.get('partition', 0):.2f} ({len(timers.get('partition', []))}) | {ms.get('subtract', 0):.2f} | "
-              f"{ms.get('split', 0):.2f} | {100 * busy / wall:.0f} |", flush=True)
-        del w, packed
+            t0 = time.perf_counter()
+            nodes, _, scratch = B.gbdt_grow_tree(packed, n, F, nb, w.grad, w.hess, 255, w.lam, w.min_child_hess,
+                                                 scratch=scratch, row_order_out=order)
+            torch.cuda.synchronize()
+            if rep:
+                walls.append((time.perf_counter() - t0) * 1e3)
+        leaves = int((nodes["left"] < 0).sum())
+        depth = [0] * len(nodes)
+        for k in range(1, len(nodes)):
+            depth[k] = depth[int(nodes[k]["parent"])] + 1
+        med = statistics.median(walls)
+        print(f"| {name} | {n:,} x {F}, {nb} | {leaves} | {max(depth)} | {med:.2f} | {min(walls):.2f} | "
+              f"{(leaves - 1) / (med * 1e-3):,.0f} |", flush=True)
+        del w, packed, scratch, order
         torch.cuda.empty_cache()
 
 
