@@ -14,7 +14,8 @@ import numpy as np
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libgbdt_hist.so")
+# GBDT_HIST_LIB: path of another build of the library (tuning experiments); default in-tree
+LIB_PATH = os.environ.get("GBDT_HIST_LIB") or os.path.join(_HERE, "libgbdt_hist.so")
 
 EXPORTS = [
     "gbdt_bins_packed_bytes", "gbdt_bins_pack", "gbdt_hist_build", "gbdt_hist_subtract",
