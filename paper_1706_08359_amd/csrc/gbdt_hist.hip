@@ -19,6 +19,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <algorithm>
 #include <atomic>
 #include <mutex>
 #include <type_traits>
@@ -906,14 +907,15 @@ __device__ __forceinline__ int32_t load_cand_feature(const SplitCand* src) {
   return (int32_t)(uint32_t)(w & 0xffffffffull);
 }
 
-// LDS bytes one feature needs in split_gain_kernel: raw bins (12 B) + fp64 prefix of
-// grad and hess (16 B) + prefix of count (4 B) per bin, + the feature's parent term.
-__host__ __device__ inline int split_feature_bytes(int n_bins) { return 32 * n_bins + 8; }
+// LDS bytes one feature needs in split_gain_kernel: fp64 running sums of gradient,
+// hessian and count per bin (bins padded to a multiple of 8), + the feature's parent term.
+__host__ __device__ inline int split_padded_bins(int n_bins) { return (n_bins + 7) & ~7; }
+__host__ __device__ inline int split_feature_bytes(int n_bins) { return 24 * split_padded_bins(n_bins) + 8; }
 
 // Gain scan of Sec. 3.3.  A workgroup takes a group of consecutive features.
-//  1. Their histogram rows are copied into local memory with coalesced reads.
-//  2. One lane per feature runs the left-to-right prefix sums of grad, hess and count
-//     in fp64, bins ascending (this fixes the rounding order; it is the cheap part).
+//  1. Their histogram rows are copied into local memory as doubles.
+//  2. One lane per (feature, statistic) runs the left-to-right prefix sum of grad, hess
+//     or count in fp64, bins ascending (this fixes the rounding order).
 //  3. All lanes then evaluate the gain of every (feature, threshold) pair from those
 //     prefixes -- the divisions, the expensive part -- and keep the best pair under
 //     the order "larger gain, then smaller feature, then smaller bin".
@@ -941,47 +943,53 @@ split_gain_kernel(const gbdt_bin_t* __restrict__ hist, int64_t hist_stride, int3
   const int32_t f0 = blockIdx.x * group;
   const int32_t nf = (n_features - f0 < group) ? (n_features - f0) : group;
   const int B = n_bins;
-  // layout: pg[group][B] | ph[group][B] | parent[group] (doubles) | pn[group][B] | raw[group][3B] (words)
+  const int Bp = split_padded_bins(B);
+  // layout (doubles): pg[group][Bp] | ph[group][Bp] | pn[group][Bp] | parent[group]
   double* pg = reinterpret_cast<double*>(smem);
-  double* ph = pg + (size_t)group * B;
-  double* parent = ph + (size_t)group * B;
-  uint32_t* pn = reinterpret_cast<uint32_t*>(parent + group);
-  uint32_t* raw = pn + (size_t)group * B;
+  double* ph = pg + (size_t)group * Bp;
+  double* pn = ph + (size_t)group * Bp;
+  double* parent = pn + (size_t)group * Bp;
 
-  const uint32_t* src = reinterpret_cast<const uint32_t*>(hist + (size_t)f0 * B);
-  const int n_words = nf * B * 3;
-  for (int e = tid; e < n_words; e += kSplitThreads) raw[e] = src[e];
+  // 1. every bin's (gradient, hessian, count) as doubles (all exact), zeros in the padding
+  for (int e = tid; e < nf * Bp; e += kSplitThreads) {
+    const int fl = e / Bp;
+    const int b = e - fl * Bp;
+    gbdt_bin_t v = {0.0f, 0.0f, 0u};
+    if (b < B) v = hist[(size_t)(f0 + fl) * B + b];
+    pg[e] = (double)v.grad;
+    ph[e] = (double)v.hess;
+    pn[e] = (double)v.count;
+  }
   __syncthreads();
 
-  if (tid < nf) {
-    const uint32_t* r = raw + (size_t)tid * B * 3;
-    double G = 0.0, H = 0.0;
-    uint32_t N = 0;
-    // The sums run strictly left to right; only the reads of the next 8 bins are issued
-    // together, ahead of the adds that need them (the loop is bound by LDS latency).
-    int b0 = 0;
-    for (; b0 + 8 <= B; b0 += 8) {
-      uint32_t w[24];
+  // 2. running sums in place, strictly left to right, one lane per (statistic, feature).
+  // The loop is bound by LDS latency: the next 8 values are requested before the current
+  // 8 are added and written back.
+  if (tid < 3 * nf) {
+    const int st = tid / nf;
+    const int fl = tid - st * nf;
+    double* p = pg + ((size_t)st * group + fl) * Bp;
+    double cur[8], nxt[8];
 #pragma unroll
-      for (int i = 0; i < 24; ++i) w[i] = r[3 * b0 + i];
+    for (int i = 0; i < 8; ++i) cur[i] = p[i];
+    double acc = 0.0;
+    for (int b0 = 0; b0 < Bp; b0 += 8) {
+      if (b0 + 8 < Bp) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) nxt[i] = p[b0 + 8 + i];
+      }
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
-        G = G + (double)__uint_as_float(w[3 * i]);
-        H = H + (double)__uint_as_float(w[3 * i + 1]);
-        N = N + w[3 * i + 2];
-        pg[tid * B + b0 + i] = G;
-        ph[tid * B + b0 + i] = H;
-        pn[tid * B + b0 + i] = N;
+        acc = acc + cur[i];
+        p[b0 + i] = acc;
       }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) cur[i] = nxt[i];
     }
-    for (int b = b0; b < B; ++b) {
-      G = G + (double)__uint_as_float(r[3 * b]);
-      H = H + (double)__uint_as_float(r[3 * b + 1]);
-      N = N + r[3 * b + 2];
-      pg[tid * B + b] = G;
-      ph[tid * B + b] = H;
-      pn[tid * B + b] = N;
-    }
+  }
+  __syncthreads();
+  if (tid < nf) {
+    const double G = pg[tid * Bp + B - 1], H = ph[tid * Bp + B - 1];
     parent[tid] = __ddiv_rn(__dmul_rn(G, G), H + lambda);
   }
   __syncthreads();
@@ -992,11 +1000,10 @@ split_gain_kernel(const gbdt_bin_t* __restrict__ hist, int64_t hist_stride, int3
   for (int e = tid; e < n_pairs; e += kSplitThreads) {
     const int fl = e / (B - 1);
     const int t = e - fl * (B - 1);
-    const double GL = pg[fl * B + t], HL = ph[fl * B + t];
-    const uint32_t NL = pn[fl * B + t];
-    const double GR = pg[fl * B + B - 1] - GL, HR = ph[fl * B + B - 1] - HL;
-    const uint32_t NR = pn[fl * B + B - 1] - NL;
-    const bool ok = NL >= 1u && NR >= 1u && HL >= min_child_hess && HR >= min_child_hess;
+    const double GL = pg[fl * Bp + t], HL = ph[fl * Bp + t], NL = pn[fl * Bp + t];
+    const double GR = pg[fl * Bp + B - 1] - GL, HR = ph[fl * Bp + B - 1] - HL;
+    const double NR = pn[fl * Bp + B - 1] - NL;  // counts are exact in fp64
+    const bool ok = NL >= 1.0 && NR >= 1.0 && HL >= min_child_hess && HR >= min_child_hess;
     if (ok) {
       const double lt = __ddiv_rn(__dmul_rn(GL, GL), HL + lambda);
       const double rt = __ddiv_rn(__dmul_rn(GR, GR), HR + lambda);
@@ -1037,12 +1044,12 @@ split_gain_kernel(const gbdt_bin_t* __restrict__ hist, int64_t hist_stride, int3
       const int fl = e / (B - 1);
       const int t = e - fl * (B - 1);
       c.gain = s_gain[0];
-      c.gl = pg[fl * B + t];
-      c.hl = ph[fl * B + t];
-      c.nl = pn[fl * B + t];
-      c.gr = pg[fl * B + B - 1] - c.gl;
-      c.hr = ph[fl * B + B - 1] - c.hl;
-      c.nr = pn[fl * B + B - 1] - c.nl;
+      c.gl = pg[fl * Bp + t];
+      c.hl = ph[fl * Bp + t];
+      c.nl = (uint32_t)pn[fl * Bp + t];
+      c.gr = pg[fl * Bp + B - 1] - c.gl;
+      c.hr = ph[fl * Bp + B - 1] - c.hl;
+      c.nr = (uint32_t)(pn[fl * Bp + B - 1] - pn[fl * Bp + t]);
       c.feature = f0 + fl;
       c.bin = t;
     }
@@ -1160,6 +1167,55 @@ PartGeom make_part_geom(int64_t n_leaf) {
   return g;
 }
 
+// Where the bin of the split feature sits in a row of the packed matrix, and the test
+// "this leaf position goes left".
+struct SplitColumn {
+  bool has_split;    // false: the record holds no split, every row goes left
+  int64_t tile_off;  // byte offset of the feature's tile
+  int32_t w, col;    // tile width; byte of the tile row
+  int32_t shift;     // 4-bit bins: the nibble
+  uint32_t mask;
+  int32_t thr;
+};
+
+__device__ __forceinline__ SplitColumn split_column(const gbdt_split_t* __restrict__ split,
+                                                    const TilePlan& plan, int64_t n_rows,
+                                                    int32_t n_features) {
+  SplitColumn c;
+  const int32_t f = split->feature;
+  c.thr = split->bin;
+  c.has_split = f >= 0 && f < n_features;
+  c.tile_off = 0;
+  c.w = plan.wm;
+  c.col = 0;
+  c.shift = 0;
+  c.mask = 0xffu;
+  if (c.has_split) {
+    const int32_t fb = plan.nib ? (f >> 1) : f;
+    int32_t t = fb / plan.wm;
+    if (t > plan.n_main) t = plan.n_main;
+    c.w = plan_tile_width(plan, t);
+    c.col = fb - t * plan.wm;
+    c.tile_off = n_rows * ((int64_t)t * plan.wm);
+    if (plan.nib) {
+      c.shift = (f & 1) ? 4 : 0;
+      c.mask = 15u;
+    }
+  }
+  return c;
+}
+
+__device__ __forceinline__ bool goes_left(const SplitColumn& c, const uint8_t* __restrict__ packed,
+                                          int64_t n_rows, const int32_t* __restrict__ idx, int64_t e,
+                                          int64_t n_leaf) {
+  if (e >= n_leaf) return false;
+  if (!c.has_split) return true;
+  int64_t r = idx ? (int64_t)idx[e] : e;
+  r = r < 0 ? 0 : (r >= n_rows ? n_rows - 1 : r);  // a bad row id must not fault
+  const uint32_t b = ((uint32_t)packed[c.tile_off + r * c.w + c.col] >> c.shift) & c.mask;
+  return (int32_t)b <= c.thr;
+}
+
 __global__ void __launch_bounds__(kPartThreads)
 partition_flag_kernel(const uint8_t* __restrict__ packed, int64_t n_rows, int32_t n_features,
                       TilePlan plan, const int32_t* __restrict__ idx, int64_t n_leaf,
@@ -1167,41 +1223,13 @@ partition_flag_kernel(const uint8_t* __restrict__ packed, int64_t n_rows, int32_
                       uint64_t* __restrict__ flags, uint32_t* __restrict__ chunk_left) {
   __shared__ uint32_t s_left[kPartWaves];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int32_t f = split->feature;
-  const int32_t thr = split->bin;
-  const bool has_split = f >= 0 && f < n_features;
-  // byte of the tile row that holds feature f, and the bits of it that are f's bin
-  int64_t tile_off = 0;
-  int32_t w = plan.wm, col = 0, shift = 0;
-  uint32_t mask = 0xffu;
-  if (has_split) {
-    const int32_t fb = plan.nib ? (f >> 1) : f;
-    int32_t t = fb / plan.wm;
-    if (t > plan.n_main) t = plan.n_main;
-    w = plan_tile_width(plan, t);
-    col = fb - t * plan.wm;
-    tile_off = n_rows * ((int64_t)t * plan.wm);
-    if (plan.nib) {
-      shift = (f & 1) ? 4 : 0;
-      mask = 15u;
-    }
-  }
+  const SplitColumn sc = split_column(split, plan, n_rows, n_features);
   const int64_t chunk_base = (int64_t)blockIdx.x * kPartThreads * rows_per_thread;
   uint64_t* my_flags = flags + (size_t)blockIdx.x * rows_per_thread * kPartWaves;
   uint32_t wave_left = 0;
   for (int32_t k = 0; k < rows_per_thread; ++k) {
     const int64_t e = chunk_base + (int64_t)k * kPartThreads + tid;
-    bool left = false;
-    if (e < n_leaf) {
-      left = true;
-      if (has_split) {
-        int64_t r = idx ? (int64_t)idx[e] : e;
-        r = r < 0 ? 0 : (r >= n_rows ? n_rows - 1 : r);  // a bad row id must not fault
-        const uint32_t b = ((uint32_t)packed[tile_off + r * w + col] >> shift) & mask;
-        left = (int32_t)b <= thr;
-      }
-    }
-    const uint64_t m = __ballot(left);
+    const uint64_t m = __ballot(goes_left(sc, packed, n_rows, idx, e, n_leaf));
     if (lane == 0) my_flags[k * kPartWaves + wave] = m;
     wave_left += (uint32_t)__popcll(m);
   }
@@ -1273,10 +1301,83 @@ partition_scatter_kernel(const int32_t* __restrict__ idx, int64_t n_leaf, int32_
   }
 }
 
+// A leaf of at most kPartThreads * kPartOneSteps rows: both passes in one workgroup, the
+// flag words in local memory, one launch.
+constexpr int kPartOneSteps = 32;
+
+__global__ void __launch_bounds__(kPartThreads)
+partition_one_kernel(const uint8_t* __restrict__ packed, int64_t n_rows, int32_t n_features,
+                     TilePlan plan, const int32_t* __restrict__ idx, int32_t n_leaf,
+                     const gbdt_split_t* __restrict__ split, int32_t* __restrict__ out,
+                     int64_t* __restrict__ n_left_out) {
+  __shared__ uint64_t s_flags[kPartOneSteps * kPartWaves];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const SplitColumn sc = split_column(split, plan, n_rows, n_features);
+  const int32_t steps = (n_leaf + kPartThreads - 1) / kPartThreads;
+  for (int32_t k = 0; k < steps; ++k) {
+    const uint64_t m = __ballot(goes_left(sc, packed, n_rows, idx, (int64_t)k * kPartThreads + tid, n_leaf));
+    if (lane == 0) s_flags[k * kPartWaves + wave] = m;
+  }
+  __syncthreads();
+  int32_t total = 0;
+  for (int32_t i = 0; i < steps * kPartWaves; ++i) total += __popcll(s_flags[i]);
+  if (tid == 0 && n_left_out) *n_left_out = total;
+  const uint64_t below = lane == 0 ? 0ull : (~0ull >> (64 - lane));
+  int32_t left_pos = 0;  // left rows before the current step
+  for (int32_t k = 0; k < steps; ++k) {
+    uint64_t m = 0;
+    int32_t wave_base = left_pos;
+#pragma unroll
+    for (int i = 0; i < kPartWaves; ++i) {
+      const uint64_t mi = s_flags[k * kPartWaves + i];
+      const int32_t ci = __popcll(mi);
+      if (i < wave) wave_base += ci;
+      if (i == wave) m = mi;
+      left_pos += ci;
+    }
+    const int32_t e = k * kPartThreads + tid;
+    if (e < n_leaf) {
+      const int32_t r = idx ? idx[e] : e;
+      const int32_t lefts_before_e = wave_base + __popcll(m & below);
+      const bool left = (m >> lane) & 1ull;
+      out[left ? lefts_before_e : total + (e - lefts_before_e)] = r;
+    }
+  }
+}
+
 // out[i] = i: the row list of the root, for a tree that never splits.
 __global__ void __launch_bounds__(256) row_iota_kernel(int32_t* __restrict__ out, int64_t n) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) out[i] = (int32_t)i;
+}
+
+// The leaves of a grown tree tile the positions 0..n-1 with segments, each held by one of
+// two row buffers.  out[i] = (buffer of i's segment)[i] for the positions of up to
+// kSegTable consecutive segments, whose starts (ascending; bit 31 = buffer) travel as
+// kernel arguments.
+constexpr int kSegTable = 960;
+struct SegTable {
+  uint32_t start[kSegTable];
+  uint32_t end;     // one past the last position of the last segment
+  int32_t n_seg;
+};
+
+__global__ void __launch_bounds__(256)
+leaf_rows_gather_kernel(const int32_t* __restrict__ buf0, const int32_t* __restrict__ buf1, SegTable t,
+                        int32_t* __restrict__ out) {
+  const uint32_t first = t.start[0] & 0x7fffffffu;
+  const uint32_t i = first + blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= t.end) return;
+  int32_t lo = 0, hi = t.n_seg - 1;  // last segment that starts at or before i
+  while (lo < hi) {
+    const int32_t mid = (lo + hi + 1) >> 1;
+    if ((t.start[mid] & 0x7fffffffu) <= i) {
+      lo = mid;
+    } else {
+      hi = mid - 1;
+    }
+  }
+  out[i] = (t.start[lo] >> 31) ? buf1[i] : buf0[i];
 }
 
 // ------------------------------------------------------- calibration copy kernel
@@ -1938,14 +2039,20 @@ int gbdt_partition_rows(const void* bin_matrix, int64_t n_rows, int32_t n_featur
   if (n_rows == 0 && n_leaf_rows > 0) return GBDT_EINVAL;
   if (n_rows >= ((int64_t)1 << 30) || n_leaf_rows >= ((int64_t)1 << 31)) return GBDT_EUNSUPPORTED;
   hipStream_t s = (hipStream_t)stream;
+  const TilePlan p = make_tile_plan(n_features, n_bins);
+  if (n_leaf_rows <= (int64_t)kPartThreads * kPartOneSteps) {  // small leaf: one workgroup, one launch
+    hipLaunchKernelGGL(partition_one_kernel, dim3(1), dim3(kPartThreads), 0, s, (const uint8_t*)bin_matrix,
+                       n_rows, n_features, p, leaf_row_idx, (int32_t)n_leaf_rows, split, children_out,
+                       n_left_out);
+    HIP_TRY(hipGetLastError());
+    return GBDT_OK;
+  }
   const PartGeom g = make_part_geom(n_leaf_rows > 0 ? n_leaf_rows : 1);
   void* ws = nullptr;
   int rc = get_workspace(g.bytes, &ws);
   if (rc != GBDT_OK) return rc;
   uint64_t* flags = (uint64_t*)ws;
   uint32_t* chunk_left = (uint32_t*)(flags + g.flag_words);
-  const TilePlan p = make_tile_plan(n_features, n_bins);
-  // an empty leaf still runs one workgroup, which writes n_left_out = 0
   hipLaunchKernelGGL(partition_flag_kernel, dim3(g.n_chunks), dim3(kPartThreads), 0, s,
                      (const uint8_t*)bin_matrix, n_rows, n_features, p, leaf_row_idx, n_leaf_rows,
                      split, g.rows_per_thread, flags, chunk_left);
@@ -2087,16 +2194,27 @@ int gbdt_grow_tree(const void* bin_matrix, int64_t n_rows, int32_t n_features, i
   }
   *n_nodes_out = n_nodes;
   if (row_order_out && n_rows > 0) {
-    for (int i = 0; i < n_nodes; ++i) {
-      const gbdt_tree_node_t& nd = nodes_out[i];
-      if (nd.left >= 0 || nd.count == 0) continue;
-      if (state[i].buf < 0) {
-        hipLaunchKernelGGL(row_iota_kernel, dim3((unsigned)((n_rows + 255) / 256)), dim3(256), 0, s,
-                           row_order_out, n_rows);
+    if (n_nodes == 1) {  // never split: the rows in their own order
+      hipLaunchKernelGGL(row_iota_kernel, dim3((unsigned)((n_rows + 255) / 256)), dim3(256), 0, s,
+                         row_order_out, n_rows);
+      HIP_TRY(hipGetLastError());
+    } else {
+      // the leaves' segments in position order, a table-full per launch
+      std::vector<std::pair<uint32_t, int>> segs;  // (begin, buffer)
+      for (int i = 0; i < n_nodes; ++i)
+        if (nodes_out[i].left < 0) segs.emplace_back((uint32_t)nodes_out[i].row_begin, state[i].buf);
+      std::sort(segs.begin(), segs.end());
+      for (size_t s0 = 0; s0 < segs.size(); s0 += kSegTable) {
+        SegTable t;
+        const size_t ns = segs.size() - s0 < (size_t)kSegTable ? segs.size() - s0 : (size_t)kSegTable;
+        for (size_t j = 0; j < ns; ++j)
+          t.start[j] = segs[s0 + j].first | ((uint32_t)segs[s0 + j].second << 31);
+        t.n_seg = (int32_t)ns;
+        t.end = s0 + ns < segs.size() ? segs[s0 + ns].first : (uint32_t)n_rows;
+        const uint32_t span = t.end - segs[s0].first;
+        hipLaunchKernelGGL(leaf_rows_gather_kernel, dim3((span + 255) / 256), dim3(256), 0, s,
+                           (const int32_t*)rows_buf[0], (const int32_t*)rows_buf[1], t, row_order_out);
         HIP_TRY(hipGetLastError());
-      } else {
-        HIP_TRY(hipMemcpyAsync(row_order_out + nd.row_begin, rows_buf[state[i].buf] + nd.row_begin,
-                               (size_t)nd.count * sizeof(int32_t), hipMemcpyDeviceToDevice, s));
       }
     }
   }
