@@ -1,0 +1,152 @@
+// The reduction pass over the workgroups' partial histograms (Sec. 4, "final reduction
+// program") and the sibling histogram by subtraction.  Included by gbdt_hist.hip only, after
+// hist_build_kernels.h.
+#ifndef GBDT_HIST_REDUCE_KERNELS_H_
+#define GBDT_HIST_REDUCE_KERNELS_H_
+
+#include <hip/hip_runtime.h>
+
+#include <stdint.h>
+#include <string.h>
+
+#include "../../include/gbdt_hist.h"
+#include "tile_plan.h"
+#include "batch_plan.h"
+
+namespace {
+
+// ------------------------------------------------------------------ merge kernel
+
+struct MergeArgs {
+  const uint32_t* partials;
+  gbdt_bin_t* out;
+  TilePlan plan;
+  int32_t n_features;
+  int32_t n_bins;
+  int32_t chunks_main;
+  int32_t chunks_rem;
+};
+
+constexpr int kMergeCells = 64;   // histogram cells per workgroup
+constexpr int kMergeLanes = 4;    // threads that share the chunks of one cell
+
+// The "final reduction program" of Sec. 4: sums the partial histograms of the
+// workgroups that shared a feature tile.  A workgroup takes 64 consecutive (bin,
+// slot) pairs of one tile (slot fastest, so reads of a partial block are coalesced
+// in runs of 32); 4 threads per pair each sum every 4th chunk in fp64, in chunk
+// order, and the 4 sub-sums are added in a fixed order: the result does not depend
+// on scheduling.  Counts are summed as integers.  grid.y = tile.
+__device__ __forceinline__ void merge_cells(const MergeArgs& a) {
+  __shared__ double s_g[kMergeLanes][kMergeCells];
+  __shared__ double s_h[kMergeLanes][kMergeCells];
+  __shared__ uint32_t s_n[kMergeLanes][kMergeCells];
+  const int32_t t = blockIdx.y;
+  const int32_t w = plan_tile_width(a.plan, t);
+  const int32_t slots = plan_slots(a.plan, w);
+  const int cell = threadIdx.x % kMergeCells;
+  const int part = threadIdx.x / kMergeCells;
+  const int32_t e = blockIdx.x * kMergeCells + cell;
+  const bool live = e < a.n_bins * slots;
+  const int32_t bin = live ? e / slots : 0;
+  const int32_t slot = live ? e - bin * slots : 0;
+  const size_t hw = (size_t)plan_cells(a.plan, w);
+  const size_t main_block = (size_t)3 * plan_cells(a.plan, a.plan.wm);
+  const uint32_t* p;
+  int32_t chunks;
+  if (t < a.plan.n_main) {
+    p = a.partials + (size_t)t * a.chunks_main * main_block;
+    chunks = a.chunks_main;
+  } else {
+    p = a.partials + (size_t)a.plan.n_main * a.chunks_main * main_block;
+    chunks = a.chunks_rem;
+  }
+  p += (size_t)plan_cell(a.plan, bin, slot) + (size_t)part * 3 * hw;
+  double g = 0.0, h = 0.0;
+  uint32_t n = 0;
+  if (live) {
+    for (int32_t c = part; c < chunks; c += kMergeLanes) {
+      g += (double)__uint_as_float(p[0]);
+      h += (double)__uint_as_float(p[hw]);
+      n += p[2 * hw];
+      p += (size_t)kMergeLanes * 3 * hw;
+    }
+  }
+  s_g[part][cell] = g;
+  s_h[part][cell] = h;
+  s_n[part][cell] = n;
+  __syncthreads();
+  if (part == 0 && live) {
+    const int32_t f = plan_feature_of(a.plan, t, slot);
+    if (f < a.n_features) {  // else: padding slot
+#pragma unroll
+      for (int q = 1; q < kMergeLanes; ++q) {
+        g += s_g[q][cell];
+        h += s_h[q][cell];
+        n += s_n[q][cell];
+      }
+      gbdt_bin_t r;
+      r.grad = (float)g;
+      r.hess = (float)h;
+      r.count = n;
+      a.out[(size_t)f * a.n_bins + bin] = r;
+    }
+  }
+}
+
+__global__ void __launch_bounds__(kMergeCells * kMergeLanes) hist_merge_kernel(MergeArgs a) {
+  merge_cells(a);
+}
+
+// The same reduction for a batched launch: grid.z = leaf of the launch; its partial
+// blocks start first_wg workgroup columns into the buffer, its histogram is the leaf's
+// [n_features][n_bins] slice of the output.  A leaf without rows has no partial blocks
+// and gets zeros; a leaf with a single workgroup per tile is skipped.
+struct BatchMergeArgs {
+  MergeArgs m;            // partials / out of leaf 0 of the launch; chunk counts unused
+  uint64_t column_words;  // words of one workgroup column
+  BatchLeaf leaf[kBatchLeaves];
+};
+
+__global__ void __launch_bounds__(kMergeCells * kMergeLanes) hist_merge_batch_kernel(BatchMergeArgs a) {
+  const BatchLeaf lf = a.leaf[blockIdx.z];
+  if ((lf.wgs_unit & 0xffffu) == 1u) return;  // written by the build kernel itself
+  MergeArgs m = a.m;
+  m.partials += (size_t)lf.first_wg * a.column_words;
+  m.out += (size_t)blockIdx.z * m.n_features * m.n_bins;
+  m.chunks_main = (int32_t)(lf.wgs_unit & 0xffffu);
+  m.chunks_rem = m.plan.wr ? m.chunks_main : 0;
+  merge_cells(m);
+}
+
+// --------------------------------------------------------------- subtract kernel
+
+// sibling = parent - child, element by element over [n_features][n_bins].
+__global__ void __launch_bounds__(256)
+hist_subtract_kernel(const gbdt_bin_t* parent, const gbdt_bin_t* child, gbdt_bin_t* sibling,
+                     int32_t n) {
+  const int32_t e = blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= n) return;
+  const gbdt_bin_t p = parent[e];
+  const gbdt_bin_t c = child[e];
+  gbdt_bin_t s;
+  s.grad = p.grad - c.grad;
+  s.hess = p.hess - c.hess;
+  s.count = p.count - c.count;
+  sibling[e] = s;
+}
+
+// Histogram of an empty leaf: all zero.  (A fill kernel, not a memset node, so the
+// call can be captured into a graph.)
+__global__ void __launch_bounds__(256) hist_zero_kernel(gbdt_bin_t* hist, int32_t n) {
+  const int32_t e = blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= n) return;
+  gbdt_bin_t z;
+  z.grad = 0.0f;
+  z.hess = 0.0f;
+  z.count = 0;
+  hist[e] = z;
+}
+
+}  // namespace
+
+#endif  // GBDT_HIST_REDUCE_KERNELS_H_

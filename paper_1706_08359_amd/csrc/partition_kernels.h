@@ -1,0 +1,271 @@
+// Row partition of a leaf after a split (App. C.1, Split()) and the row-list helpers of
+// tree growth.  Included by gbdt_hist.hip only.
+#ifndef GBDT_PARTITION_KERNELS_H_
+#define GBDT_PARTITION_KERNELS_H_
+
+#include <hip/hip_runtime.h>
+
+#include <stdint.h>
+#include <string.h>
+
+#include "../../include/gbdt_hist.h"
+#include "tile_plan.h"
+
+namespace {
+
+// ------------------------------------------------------------- partition kernels
+
+// Split() of App. C.1 on the device: the rows of a leaf are handed to its two children
+// by the bin of one feature, left rows (bin <= threshold) first, each side in the
+// parent's order.  The paper leaves this step on the CPU and copies the new index list to
+// the GPU after every split (App. A.5); with the list kept in HBM nothing is copied.
+//
+// Two passes over chunks of kPartThreads * rows_per_thread consecutive leaf positions,
+// one workgroup per chunk, no waiting between workgroups:
+//   1. flag pass: fetch each row's bin, ballot "goes left" into one 64-bit word per
+//      (wavefront, step) and count the chunk's left rows;
+//   2. scatter pass: every workgroup sums the chunk counts before its own (at most
+//      kPartMaxChunks of them) to find where its rows start on either side, then ranks
+//      its rows inside the chunk from the flag words and writes the row ids.
+// The flag words save the second pass the scattered read of the bin matrix, which is
+// by far the larger part of the traffic (one 32- or 64-byte tile row per leaf row).
+constexpr int kPartThreads = 256;
+constexpr int kPartWaves = kPartThreads / 64;
+constexpr int kPartMaxChunks = 8192;
+
+struct PartGeom {
+  int32_t rows_per_thread;  // steps of kPartThreads rows a workgroup takes
+  int32_t n_chunks;
+  size_t flag_words;        // 64-bit words
+  size_t bytes;             // flags, then one 32-bit count per chunk
+};
+
+PartGeom make_part_geom(int64_t n_leaf) {
+  PartGeom g;
+  g.rows_per_thread = 8;
+  while ((n_leaf + (int64_t)kPartThreads * g.rows_per_thread - 1) /
+             ((int64_t)kPartThreads * g.rows_per_thread) > kPartMaxChunks)
+    g.rows_per_thread *= 2;
+  const int64_t chunk_rows = (int64_t)kPartThreads * g.rows_per_thread;
+  g.n_chunks = (int32_t)((n_leaf + chunk_rows - 1) / chunk_rows);
+  g.flag_words = (size_t)g.n_chunks * g.rows_per_thread * kPartWaves;
+  g.bytes = g.flag_words * 8 + (size_t)g.n_chunks * 4;
+  return g;
+}
+
+// Where the bin of the split feature sits in a row of the packed matrix, and the test
+// "this leaf position goes left".
+struct SplitColumn {
+  bool has_split;    // false: the record holds no split, every row goes left
+  int64_t tile_off;  // byte offset of the feature's tile
+  int32_t w, col;    // tile width; byte of the tile row
+  int32_t shift;     // 4-bit bins: the nibble
+  uint32_t mask;
+  int32_t thr;
+};
+
+__device__ __forceinline__ SplitColumn split_column(const gbdt_split_t* __restrict__ split,
+                                                    const TilePlan& plan, int64_t n_rows,
+                                                    int32_t n_features) {
+  SplitColumn c;
+  const int32_t f = split->feature;
+  c.thr = split->bin;
+  c.has_split = f >= 0 && f < n_features;
+  c.tile_off = 0;
+  c.w = plan.wm;
+  c.col = 0;
+  c.shift = 0;
+  c.mask = 0xffu;
+  if (c.has_split) {
+    const int32_t fb = plan.nib ? (f >> 1) : f;
+    int32_t t = fb / plan.wm;
+    if (t > plan.n_main) t = plan.n_main;
+    c.w = plan_tile_width(plan, t);
+    c.col = fb - t * plan.wm;
+    c.tile_off = n_rows * ((int64_t)t * plan.wm);
+    if (plan.nib) {
+      c.shift = (f & 1) ? 4 : 0;
+      c.mask = 15u;
+    }
+  }
+  return c;
+}
+
+__device__ __forceinline__ bool goes_left(const SplitColumn& c, const uint8_t* __restrict__ packed,
+                                          int64_t n_rows, const int32_t* __restrict__ idx, int64_t e,
+                                          int64_t n_leaf) {
+  if (e >= n_leaf) return false;
+  if (!c.has_split) return true;
+  int64_t r = idx ? (int64_t)idx[e] : e;
+  r = r < 0 ? 0 : (r >= n_rows ? n_rows - 1 : r);  // a bad row id must not fault
+  const uint32_t b = ((uint32_t)packed[c.tile_off + r * c.w + c.col] >> c.shift) & c.mask;
+  return (int32_t)b <= c.thr;
+}
+
+__global__ void __launch_bounds__(kPartThreads)
+partition_flag_kernel(const uint8_t* __restrict__ packed, int64_t n_rows, int32_t n_features,
+                      TilePlan plan, const int32_t* __restrict__ idx, int64_t n_leaf,
+                      const gbdt_split_t* __restrict__ split, int32_t rows_per_thread,
+                      uint64_t* __restrict__ flags, uint32_t* __restrict__ chunk_left) {
+  __shared__ uint32_t s_left[kPartWaves];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const SplitColumn sc = split_column(split, plan, n_rows, n_features);
+  const int64_t chunk_base = (int64_t)blockIdx.x * kPartThreads * rows_per_thread;
+  uint64_t* my_flags = flags + (size_t)blockIdx.x * rows_per_thread * kPartWaves;
+  uint32_t wave_left = 0;
+  for (int32_t k = 0; k < rows_per_thread; ++k) {
+    const int64_t e = chunk_base + (int64_t)k * kPartThreads + tid;
+    const uint64_t m = __ballot(goes_left(sc, packed, n_rows, idx, e, n_leaf));
+    if (lane == 0) my_flags[k * kPartWaves + wave] = m;
+    wave_left += (uint32_t)__popcll(m);
+  }
+  if (lane == 0) s_left[wave] = wave_left;
+  __syncthreads();
+  if (tid == 0) {
+    uint32_t c = 0;
+#pragma unroll
+    for (int i = 0; i < kPartWaves; ++i) c += s_left[i];
+    chunk_left[blockIdx.x] = c;
+  }
+}
+
+__global__ void __launch_bounds__(kPartThreads)
+partition_scatter_kernel(const int32_t* __restrict__ idx, int64_t n_leaf, int32_t rows_per_thread,
+                         const uint64_t* __restrict__ flags, const uint32_t* __restrict__ chunk_left,
+                         int32_t n_chunks, int32_t* __restrict__ out, int64_t* __restrict__ n_left_out) {
+  __shared__ int64_t s_before[kPartWaves], s_total[kPartWaves];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int32_t chunk = blockIdx.x;
+  // left rows in the chunks before this one, and in the whole leaf
+  int64_t before = 0, total = 0;
+  for (int32_t c = tid; c < n_chunks; c += kPartThreads) {
+    const int64_t v = chunk_left[c];
+    total += v;
+    if (c < chunk) before += v;
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    before += __shfl_xor(before, o);
+    total += __shfl_xor(total, o);
+  }
+  if (lane == 0) {
+    s_before[wave] = before;
+    s_total[wave] = total;
+  }
+  __syncthreads();
+  before = 0;
+  total = 0;
+#pragma unroll
+  for (int i = 0; i < kPartWaves; ++i) {
+    before += s_before[i];
+    total += s_total[i];
+  }
+  if (chunk == 0 && tid == 0 && n_left_out) *n_left_out = total;
+
+  const int64_t chunk_base = (int64_t)chunk * kPartThreads * rows_per_thread;
+  const uint64_t* my_flags = flags + (size_t)chunk * rows_per_thread * kPartWaves;
+  const uint64_t below = lane == 0 ? 0ull : (~0ull >> (64 - lane));
+  int64_t left_pos = before;  // left rows before the current step
+  for (int32_t k = 0; k < rows_per_thread; ++k) {
+    uint64_t m = 0;
+    int64_t wave_base = left_pos;
+#pragma unroll
+    for (int i = 0; i < kPartWaves; ++i) {
+      const uint64_t mi = my_flags[k * kPartWaves + i];
+      const int64_t ci = __popcll(mi);
+      if (i < wave) wave_base += ci;
+      if (i == wave) m = mi;
+      left_pos += ci;
+    }
+    const int64_t e = chunk_base + (int64_t)k * kPartThreads + tid;
+    if (e < n_leaf) {
+      const int32_t r = idx ? idx[e] : (int32_t)e;
+      const int64_t lefts_before_e = wave_base + __popcll(m & below);
+      const bool left = (m >> lane) & 1ull;
+      out[left ? lefts_before_e : total + (e - lefts_before_e)] = r;
+    }
+  }
+}
+
+// A leaf of at most kPartThreads * kPartOneSteps rows: both passes in one workgroup, the
+// flag words in local memory, one launch.
+constexpr int kPartOneSteps = 32;
+
+__global__ void __launch_bounds__(kPartThreads)
+partition_one_kernel(const uint8_t* __restrict__ packed, int64_t n_rows, int32_t n_features,
+                     TilePlan plan, const int32_t* __restrict__ idx, int32_t n_leaf,
+                     const gbdt_split_t* __restrict__ split, int32_t* __restrict__ out,
+                     int64_t* __restrict__ n_left_out) {
+  __shared__ uint64_t s_flags[kPartOneSteps * kPartWaves];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const SplitColumn sc = split_column(split, plan, n_rows, n_features);
+  const int32_t steps = (n_leaf + kPartThreads - 1) / kPartThreads;
+  for (int32_t k = 0; k < steps; ++k) {
+    const uint64_t m = __ballot(goes_left(sc, packed, n_rows, idx, (int64_t)k * kPartThreads + tid, n_leaf));
+    if (lane == 0) s_flags[k * kPartWaves + wave] = m;
+  }
+  __syncthreads();
+  int32_t total = 0;
+  for (int32_t i = 0; i < steps * kPartWaves; ++i) total += __popcll(s_flags[i]);
+  if (tid == 0 && n_left_out) *n_left_out = total;
+  const uint64_t below = lane == 0 ? 0ull : (~0ull >> (64 - lane));
+  int32_t left_pos = 0;  // left rows before the current step
+  for (int32_t k = 0; k < steps; ++k) {
+    uint64_t m = 0;
+    int32_t wave_base = left_pos;
+#pragma unroll
+    for (int i = 0; i < kPartWaves; ++i) {
+      const uint64_t mi = s_flags[k * kPartWaves + i];
+      const int32_t ci = __popcll(mi);
+      if (i < wave) wave_base += ci;
+      if (i == wave) m = mi;
+      left_pos += ci;
+    }
+    const int32_t e = k * kPartThreads + tid;
+    if (e < n_leaf) {
+      const int32_t r = idx ? idx[e] : e;
+      const int32_t lefts_before_e = wave_base + __popcll(m & below);
+      const bool left = (m >> lane) & 1ull;
+      out[left ? lefts_before_e : total + (e - lefts_before_e)] = r;
+    }
+  }
+}
+
+// out[i] = i: the row list of the root, for a tree that never splits.
+__global__ void __launch_bounds__(256) row_iota_kernel(int32_t* __restrict__ out, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) out[i] = (int32_t)i;
+}
+
+// The leaves of a grown tree tile the positions 0..n-1 with segments, each held by one of
+// two row buffers.  out[i] = (buffer of i's segment)[i] for the positions of up to
+// kSegTable consecutive segments, whose starts (ascending; bit 31 = buffer) travel as
+// kernel arguments.
+constexpr int kSegTable = 960;
+struct SegTable {
+  uint32_t start[kSegTable];
+  uint32_t end;     // one past the last position of the last segment
+  int32_t n_seg;
+};
+
+__global__ void __launch_bounds__(256)
+leaf_rows_gather_kernel(const int32_t* __restrict__ buf0, const int32_t* __restrict__ buf1, SegTable t,
+                        int32_t* __restrict__ out) {
+  const uint32_t first = t.start[0] & 0x7fffffffu;
+  const uint32_t i = first + blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= t.end) return;
+  int32_t lo = 0, hi = t.n_seg - 1;  // last segment that starts at or before i
+  while (lo < hi) {
+    const int32_t mid = (lo + hi + 1) >> 1;
+    if ((t.start[mid] & 0x7fffffffu) <= i) {
+      lo = mid;
+    } else {
+      hi = mid - 1;
+    }
+  }
+  out[i] = (t.start[lo] >> 31) ? buf1[i] : buf0[i];
+}
+
+}  // namespace
+
+#endif  // GBDT_PARTITION_KERNELS_H_

@@ -1,0 +1,294 @@
+// Best-split search over bin boundaries (Sec. 3.3).  Included by gbdt_hist.hip only.
+#ifndef GBDT_SPLIT_KERNELS_H_
+#define GBDT_SPLIT_KERNELS_H_
+
+#include <hip/hip_runtime.h>
+
+#include <stdint.h>
+#include <string.h>
+
+#include "../../include/gbdt_hist.h"
+
+namespace {
+
+// ------------------------------------------------------------------ split kernels
+
+struct SplitCand {
+  double gain;
+  double gl, hl, gr, hr;
+  uint32_t nl, nr;
+  int32_t feature;  // -1: no admissible threshold among this workgroup's features
+  int32_t bin;
+};
+
+static_assert(sizeof(SplitCand) == 7 * 8, "a candidate is moved as 7 64-bit words");
+
+constexpr int kSplitThreads = 256;
+constexpr int kSplitLdsBudget = 48 * 1024;
+constexpr int kSplitMaxHists = 32768;  // histograms per launch (grid.y)
+
+// One ticket counter per histogram of a launch: the workgroups of a histogram count
+// themselves off, and the last of them sets the counter back to zero, so the counters
+// need no resetting between launches (zero when the module is loaded).
+__device__ unsigned int g_split_ticket[kSplitMaxHists];
+
+// Candidates cross from the workgroups that write them to the one that reduces them,
+// possibly on another XCD with its own L2: they are moved with device-scope atomic
+// accesses (which bypass the caches that are not coherent across XCDs), inside the
+// release / acquire fences around the ticket.
+__device__ __forceinline__ void store_cand(SplitCand* dst, const SplitCand& c) {
+  unsigned long long w[7];
+  memcpy(w, &c, sizeof c);
+  unsigned long long* d = reinterpret_cast<unsigned long long*>(dst);
+#pragma unroll
+  for (int i = 0; i < 7; ++i) __hip_atomic_store(d + i, w[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ SplitCand load_cand(const SplitCand* src) {
+  unsigned long long w[7];
+  const unsigned long long* p = reinterpret_cast<const unsigned long long*>(src);
+#pragma unroll
+  for (int i = 0; i < 7; ++i)
+    w[i] = __hip_atomic_load(const_cast<unsigned long long*>(p) + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  SplitCand c;
+  memcpy(&c, w, sizeof c);
+  return c;
+}
+__device__ __forceinline__ double load_cand_gain(const SplitCand* src) {
+  const unsigned long long w = __hip_atomic_load(
+      const_cast<unsigned long long*>(reinterpret_cast<const unsigned long long*>(src)), __ATOMIC_RELAXED,
+      __HIP_MEMORY_SCOPE_AGENT);
+  double g;
+  memcpy(&g, &w, sizeof g);
+  return g;
+}
+__device__ __forceinline__ int32_t load_cand_feature(const SplitCand* src) {
+  // word 6 = (feature, bin)
+  const unsigned long long w = __hip_atomic_load(
+      const_cast<unsigned long long*>(reinterpret_cast<const unsigned long long*>(src)) + 6, __ATOMIC_RELAXED,
+      __HIP_MEMORY_SCOPE_AGENT);
+  return (int32_t)(uint32_t)(w & 0xffffffffull);
+}
+
+// LDS bytes one feature needs in split_gain_kernel: fp64 running sums of gradient,
+// hessian and count per bin (bins padded to a multiple of 8), + the feature's parent term.
+__host__ __device__ inline int split_padded_bins(int n_bins) { return (n_bins + 7) & ~7; }
+__host__ __device__ inline int split_feature_bytes(int n_bins) { return 24 * split_padded_bins(n_bins) + 8; }
+
+// Gain scan of Sec. 3.3.  A workgroup takes a group of consecutive features.
+//  1. Their histogram rows are copied into local memory as doubles.
+//  2. One lane per (feature, statistic) runs the left-to-right prefix sum of grad, hess
+//     or count in fp64, bins ascending (this fixes the rounding order).
+//  3. All lanes then evaluate the gain of every (feature, threshold) pair from those
+//     prefixes -- the divisions, the expensive part -- and keep the best pair under
+//     the order "larger gain, then smaller feature, then smaller bin".
+// Feature totals are the prefix at the last bin, right = total - left, a threshold is
+// admissible when both sides hold >= 1 sample and >= min_child_hess of hessian.
+//  4. The workgroup that finishes last for its histogram (a ticket taken after its own
+//     candidate is written and fenced; nobody waits) reduces the candidates of all
+//     workgroups to the histogram's split record: workgroups hold ascending feature
+//     groups, so "smaller candidate index" is "smaller feature".
+// grid.y = histogram of the call; histogram y starts hist_stride bins after histogram
+// y - 1 (the stride may be negative: any two histograms of a pool can be searched in
+// one launch).
+__global__ void __launch_bounds__(kSplitThreads)
+split_gain_kernel(const gbdt_bin_t* __restrict__ hist, int64_t hist_stride, int32_t n_features,
+                  int32_t n_bins, int32_t group, double lambda, double min_child_hess,
+                  SplitCand* __restrict__ cand, gbdt_split_t* __restrict__ out) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  __shared__ double s_gain[kSplitThreads];
+  __shared__ int32_t s_pair[kSplitThreads];
+  __shared__ int s_last;
+  const int tid = threadIdx.x;
+  hist += (int64_t)blockIdx.y * hist_stride;
+  cand += (size_t)blockIdx.y * gridDim.x;
+  out += blockIdx.y;
+  const int32_t f0 = blockIdx.x * group;
+  const int32_t nf = (n_features - f0 < group) ? (n_features - f0) : group;
+  const int B = n_bins;
+  const int Bp = split_padded_bins(B);
+  // layout (doubles): pg[group][Bp] | ph[group][Bp] | pn[group][Bp] | parent[group]
+  double* pg = reinterpret_cast<double*>(smem);
+  double* ph = pg + (size_t)group * Bp;
+  double* pn = ph + (size_t)group * Bp;
+  double* parent = pn + (size_t)group * Bp;
+
+  // 1. every bin's (gradient, hessian, count) as doubles (all exact), zeros in the padding
+  for (int e = tid; e < nf * Bp; e += kSplitThreads) {
+    const int fl = e / Bp;
+    const int b = e - fl * Bp;
+    gbdt_bin_t v = {0.0f, 0.0f, 0u};
+    if (b < B) v = hist[(size_t)(f0 + fl) * B + b];
+    pg[e] = (double)v.grad;
+    ph[e] = (double)v.hess;
+    pn[e] = (double)v.count;
+  }
+  __syncthreads();
+
+  // 2. running sums in place, strictly left to right, one lane per (statistic, feature).
+  // The loop is bound by LDS latency: the next 8 values are requested before the current
+  // 8 are added and written back.
+  if (tid < 3 * nf) {
+    const int st = tid / nf;
+    const int fl = tid - st * nf;
+    double* p = pg + ((size_t)st * group + fl) * Bp;
+    double cur[8], nxt[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) cur[i] = p[i];
+    double acc = 0.0;
+    for (int b0 = 0; b0 < Bp; b0 += 8) {
+      if (b0 + 8 < Bp) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) nxt[i] = p[b0 + 8 + i];
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        acc = acc + cur[i];
+        p[b0 + i] = acc;
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) cur[i] = nxt[i];
+    }
+  }
+  __syncthreads();
+  if (tid < nf) {
+    const double G = pg[tid * Bp + B - 1], H = ph[tid * Bp + B - 1];
+    parent[tid] = __ddiv_rn(__dmul_rn(G, G), H + lambda);
+  }
+  __syncthreads();
+
+  double best_gain = 0.0;
+  int32_t best_pair = -1;  // fl * (B - 1) + t, ascending in (feature, bin)
+  const int n_pairs = nf * (B - 1);
+  for (int e = tid; e < n_pairs; e += kSplitThreads) {
+    const int fl = e / (B - 1);
+    const int t = e - fl * (B - 1);
+    const double GL = pg[fl * Bp + t], HL = ph[fl * Bp + t], NL = pn[fl * Bp + t];
+    const double GR = pg[fl * Bp + B - 1] - GL, HR = ph[fl * Bp + B - 1] - HL;
+    const double NR = pn[fl * Bp + B - 1] - NL;  // counts are exact in fp64
+    const bool ok = NL >= 1.0 && NR >= 1.0 && HL >= min_child_hess && HR >= min_child_hess;
+    if (ok) {
+      const double lt = __ddiv_rn(__dmul_rn(GL, GL), HL + lambda);
+      const double rt = __ddiv_rn(__dmul_rn(GR, GR), HR + lambda);
+      const double gain = __dsub_rn(__dadd_rn(lt, rt), parent[fl]);
+      if (best_pair < 0 || gain > best_gain) {  // e ascends: ties keep the earlier pair
+        best_gain = gain;
+        best_pair = e;
+      }
+    }
+  }
+  s_gain[tid] = best_gain;
+  s_pair[tid] = best_pair;
+  __syncthreads();
+  for (int s = kSplitThreads / 2; s > 0; s >>= 1) {
+    if (tid < s) {
+      const double g2 = s_gain[tid + s];
+      const int32_t p2 = s_pair[tid + s];
+      const double g1 = s_gain[tid];
+      const int32_t p1 = s_pair[tid];
+      const bool take = p2 >= 0 && (p1 < 0 || g2 > g1 || (g2 == g1 && p2 < p1));
+      if (take) {
+        s_gain[tid] = g2;
+        s_pair[tid] = p2;
+      }
+    }
+    __syncthreads();
+  }
+  if (tid == 0) {
+    SplitCand c;
+    const int32_t e = s_pair[0];
+    if (e < 0) {
+      c.gain = 0.0;
+      c.gl = c.hl = c.gr = c.hr = 0.0;
+      c.nl = c.nr = 0;
+      c.feature = -1;
+      c.bin = -1;
+    } else {
+      const int fl = e / (B - 1);
+      const int t = e - fl * (B - 1);
+      c.gain = s_gain[0];
+      c.gl = pg[fl * Bp + t];
+      c.hl = ph[fl * Bp + t];
+      c.nl = (uint32_t)pn[fl * Bp + t];
+      c.gr = pg[fl * Bp + B - 1] - c.gl;
+      c.hr = ph[fl * Bp + B - 1] - c.hl;
+      c.nr = (uint32_t)(pn[fl * Bp + B - 1] - pn[fl * Bp + t]);
+      c.feature = f0 + fl;
+      c.bin = t;
+    }
+    store_cand(cand + blockIdx.x, c);
+    // The candidate's stores are device-scope atomics (written through, not left dirty in
+    // this XCD's L2): once they are acknowledged they are visible device-wide, so waiting
+    // for them (vmcnt(0)) is all the release the ticket needs -- a full fence would also
+    // write back every dirty line of the L2, which costs tens of microseconds here.
+    __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0); expcnt, lgkmcnt untouched
+    const unsigned int old = __hip_atomic_fetch_add(&g_split_ticket[blockIdx.y], 1u, __ATOMIC_RELAXED,
+                                                    __HIP_MEMORY_SCOPE_AGENT);
+    const bool last = old == gridDim.x - 1;
+    if (last)  // back to zero for the next launch
+      __hip_atomic_store(&g_split_ticket[blockIdx.y], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    s_last = last;
+  }
+  __syncthreads();
+  if (!s_last) return;
+  // The ticket's value has arrived, so every other workgroup's candidate was acknowledged
+  // before its ticket; the loads below are device-scope atomics and bypass stale caches.
+
+  // ---- the histogram's last workgroup: arg-max over all candidates.  Each thread folds
+  // a strided subset in ascending order, then a tree reduction.
+  const int32_t n_cand = (int32_t)gridDim.x;
+  double bg = 0.0;
+  int32_t bi = -1;
+  for (int32_t i = tid; i < n_cand; i += kSplitThreads) {
+    if (load_cand_feature(cand + i) >= 0) {
+      const double g = load_cand_gain(cand + i);
+      if (bi < 0 || g > bg) {  // i ascends, so ties keep the smaller feature
+        bg = g;
+        bi = i;
+      }
+    }
+  }
+  s_gain[tid] = bg;
+  s_pair[tid] = bi;
+  __syncthreads();
+  for (int s = kSplitThreads / 2; s > 0; s >>= 1) {
+    if (tid < s) {
+      const double g2 = s_gain[tid + s];
+      const int32_t i2 = s_pair[tid + s];
+      const double g1 = s_gain[tid];
+      const int32_t i1 = s_pair[tid];
+      const bool take = i2 >= 0 && (i1 < 0 || g2 > g1 || (g2 == g1 && i2 < i1));
+      if (take) {
+        s_gain[tid] = g2;
+        s_pair[tid] = i2;
+      }
+    }
+    __syncthreads();
+  }
+  if (tid == 0) {
+    gbdt_split_t r;
+    const int32_t i = s_pair[0];
+    if (i < 0) {
+      r.feature = -1;
+      r.bin = -1;
+      r.gain = 0.0f;
+      r.left_grad = r.left_hess = r.right_grad = r.right_hess = 0.0f;
+      r.left_count = r.right_count = 0;
+    } else {
+      const SplitCand c = load_cand(cand + i);
+      r.feature = c.feature;
+      r.bin = c.bin;
+      r.gain = (float)c.gain;
+      r.left_grad = (float)c.gl;
+      r.left_hess = (float)c.hl;
+      r.left_count = c.nl;
+      r.right_grad = (float)c.gr;
+      r.right_hess = (float)c.hr;
+      r.right_count = c.nr;
+    }
+    *out = r;
+  }
+}
+
+}  // namespace
+
+#endif  // GBDT_SPLIT_KERNELS_H_
