@@ -513,7 +513,12 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
       lo = ok ? lo : 0u;
       hi = ok ? hi : 0u;
     }
+    // The atomics are what the kernel is bound by; the drain of a co-resident workgroup is
+    // mostly VALU work.  Raised priority lets the waves that feed the LDS pipe issue first,
+    // and the other workgroup's drain fills the gaps (8-12 % on the 256-bin variants).
+    __builtin_amdgcn_s_setprio(1);
     add_and_reload(w, lo, hi, row_nxt, p1.row);
+    __builtin_amdgcn_s_setprio(0);
 
     parity ^= 1u;
     {
