@@ -71,39 +71,64 @@ struct Workspace {
   int own_device = -1;
   void* user = nullptr;  // caller-registered scratch
   size_t user_bytes = 0;
+  void* zeroed = nullptr;  // the buffer whose counter head is known to be all zero
 };
 Workspace g_ws;
 
+// The head of every scratch buffer holds the build kernels' unit counters (one per
+// feature tile, at most 65535 tiles); the scratch handed to a call starts behind it.
+constexpr int kCounterSlots = 65536;
+constexpr size_t kWsHeadBytes = (size_t)kCounterSlots * sizeof(uint32_t);
+
 // Returns a scratch pointer of at least `bytes`, growing the library-owned buffer
-// when no caller buffer is registered.
-int get_workspace(size_t bytes, void** out) {
+// when no caller buffer is registered.  counters_out: the counter head of the same
+// buffer; *counters_zero_out: whether it is known to be all zero.
+int get_workspace(size_t bytes, void** out, uint32_t** counters_out = nullptr,
+                  bool* counters_zero_out = nullptr) {
   std::lock_guard<std::mutex> lk(g_ws.mu);
+  bytes += kWsHeadBytes;
+  void* base = nullptr;
   if (g_ws.user) {
     if (bytes > g_ws.user_bytes) return GBDT_ENOMEM;
-    *out = g_ws.user;
-    return GBDT_OK;
-  }
-  int dev = 0;
-  HIP_TRY(hipGetDevice(&dev));
-  if (g_ws.own && (g_ws.own_device != dev || g_ws.own_bytes < bytes)) {
-    HIP_TRY(hipDeviceSynchronize());  // earlier work may still use the old buffer
-    HIP_TRY(hipFree(g_ws.own));
-    g_ws.own = nullptr;
-    g_ws.own_bytes = 0;
-  }
-  if (!g_ws.own) {
-    size_t want = bytes < (size_t)(1 << 20) ? (size_t)(1 << 20) : bytes;
-    hipError_t e = hipMalloc(&g_ws.own, want);
-    if (e != hipSuccess) {
+    base = g_ws.user;
+  } else {
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    if (g_ws.own && (g_ws.own_device != dev || g_ws.own_bytes < bytes)) {
+      HIP_TRY(hipDeviceSynchronize());  // earlier work may still use the old buffer
+      HIP_TRY(hipFree(g_ws.own));
+      if (g_ws.zeroed == g_ws.own) g_ws.zeroed = nullptr;
       g_ws.own = nullptr;
-      hip_fail(e, "hipMalloc(workspace)");
-      return GBDT_ENOMEM;
+      g_ws.own_bytes = 0;
     }
-    g_ws.own_bytes = want;
-    g_ws.own_device = dev;
+    if (!g_ws.own) {
+      size_t want = bytes < (size_t)(1 << 20) ? (size_t)(1 << 20) : bytes;
+      hipError_t e = hipMalloc(&g_ws.own, want);
+      if (e != hipSuccess) {
+        g_ws.own = nullptr;
+        hip_fail(e, "hipMalloc(workspace)");
+        return GBDT_ENOMEM;
+      }
+      g_ws.own_bytes = want;
+      g_ws.own_device = dev;
+      g_ws.zeroed = nullptr;
+    }
+    base = g_ws.own;
   }
-  *out = g_ws.own;
+  *out = (char*)base + kWsHeadBytes;
+  if (counters_out) *counters_out = (uint32_t*)base;
+  if (counters_zero_out) *counters_zero_out = g_ws.zeroed == base;
   return GBDT_OK;
+}
+
+// Records whether the counter head of the buffer `counters` heads is all zero.
+void set_counters_zero(uint32_t* counters, bool zero) {
+  std::lock_guard<std::mutex> lk(g_ws.mu);
+  if (zero) {
+    g_ws.zeroed = counters;
+  } else if (g_ws.zeroed == counters) {
+    g_ws.zeroed = nullptr;
+  }
 }
 
 // Optional timing of the build kernel alone (it shares its C-ABI call with the merge
@@ -146,7 +171,6 @@ struct BuildGeom {
   int unit_epochs;      // epochs per unit
   bool one_unit_each;   // short leaf: every workgroup has exactly one unit, no counter
   size_t partial_words;  // total words of all partial blocks
-  size_t counter_words;  // one unit counter per tile
 };
 
 // Leaves of at most this many epochs get ONE workgroup per tile, which writes the
@@ -205,7 +229,6 @@ BuildGeom make_geom(int32_t n_features, int32_t n_bins, int64_t n_leaf, int cus,
   plan_leaf_units(n_epochs, resident / n_tiles, &g.wgs, &g.unit_epochs, &g.one_unit_each);
   g.partial_words = (size_t)p.n_main * g.wgs * main_block +
                     (size_t)(p.wr ? g.wgs : 0) * 3 * (p.wr ? plan_cells(p, p.wr) : 0);
-  g.counter_words = (size_t)n_tiles;
   return g;
 }
 
@@ -442,15 +465,14 @@ size_t gbdt_workspace_bytes(int64_t n_rows, int32_t n_features, int32_t n_bins) 
   const int cap = make_tile_plan(n_features, n_bins).cap;
   const BuildGeom g0 = make_geom(n_features, n_bins, n_rows, device_cu_count(), build_wg_per_cu(cap, false));
   const BuildGeom g1 = make_geom(n_features, n_bins, n_rows, device_cu_count(), build_wg_per_cu(cap, true));
-  size_t b = (g0.partial_words > g1.partial_words ? g0.partial_words : g1.partial_words) * 4 +
-             g0.counter_words * 4;
+  size_t b = (g0.partial_words > g1.partial_words ? g0.partial_words : g1.partial_words) * 4;
   int sg = 0, sn = 0;
   split_grouping(n_features, n_bins, &sg, &sn);
   const size_t cand = (size_t)2 * sn * sizeof(SplitCand);  // gbdt_grow_tree searches two histograms at once
   if (cand > b) b = cand;
   const size_t part = make_part_geom(n_rows > 0 ? n_rows : 1).bytes;
   if (part > b) b = part;
-  return (b + 255) / 256 * 256;
+  return (b + 255) / 256 * 256 + kWsHeadBytes;
 }
 
 int gbdt_set_workspace(void* dev_ptr, size_t bytes) {
@@ -459,6 +481,7 @@ int gbdt_set_workspace(void* dev_ptr, size_t bytes) {
   std::lock_guard<std::mutex> lk(g_ws.mu);
   g_ws.user = dev_ptr;
   g_ws.user_bytes = bytes;
+  g_ws.zeroed = g_ws.zeroed == dev_ptr ? nullptr : g_ws.zeroed;  // a caller buffer starts with unknown contents
   return GBDT_OK;
 }
 
@@ -487,7 +510,9 @@ int gbdt_hist_build(const void* bin_matrix, int64_t n_rows, int32_t n_features, 
   // byte offsets inside a tile (slack included) are formed in 32 bits
   if ((n_rows + kEpochRows) * (int64_t)p.wm >= ((int64_t)1 << 32)) return GBDT_EUNSUPPORTED;
   void* ws = nullptr;
-  int rc = get_workspace((g.partial_words + g.counter_words) * 4, &ws);
+  uint32_t* counters = nullptr;
+  bool counters_zero = false;
+  int rc = get_workspace(g.partial_words * 4, &ws, &counters, &counters_zero);
   if (rc != GBDT_OK) return rc;
 
   BuildArgs a;
@@ -496,7 +521,7 @@ int gbdt_hist_build(const void* bin_matrix, int64_t n_rows, int32_t n_features, 
   a.grad = grad;
   a.hess = hess;
   a.partials = (uint32_t*)ws;
-  a.counters = (uint32_t*)ws + g.partial_words;
+  a.counters = counters;
   a.n_rows = n_rows;
   a.n_leaf = n_leaf_rows;
   a.n_main = p.n_main;
@@ -510,12 +535,31 @@ int gbdt_hist_build(const void* bin_matrix, int64_t n_rows, int32_t n_features, 
   a.n_bins = n_bins;
   const int n_tiles = plan_n_tiles(p);
   const int blocks = n_tiles * g.wgs;
-  if (a.fixed_stride == 0) {
-    const int n_counters = (int)g.counter_words;
-    hipLaunchKernelGGL(counters_init_kernel, dim3((n_counters + 255) / 256), dim3(256), 0, s,
-                       a.counters, g.wgs, n_counters);
-    HIP_TRY(hipGetLastError());
+  const bool uses_counters = a.fixed_stride == 0;
+  // While the stream is being captured nothing runs now, so what is known about the
+  // counters must not change: the captured sequence zeroes them itself, before and (if
+  // no reduction pass follows) after the build, and leaves them zero on every replay.
+  bool capturing = false;
+  {
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(s, &cs) == hipSuccess) {
+      capturing = cs == hipStreamCaptureStatusActive;
+    } else {
+      (void)hipGetLastError();
+    }
   }
+  auto zero_counters = [&]() -> int {
+    hipLaunchKernelGGL(counters_zero_kernel, dim3(kCounterSlots / 256), dim3(256), 0, s, counters,
+                       kCounterSlots);
+    HIP_TRY(hipGetLastError());
+    return GBDT_OK;
+  };
+  if (uses_counters && (capturing || !counters_zero)) {  // e.g. a new scratch buffer
+    rc = zero_counters();
+    if (rc != GBDT_OK) return rc;
+  }
+  // From here until the reduction pass has been enqueued the counters are in use.
+  if (uses_counters && !capturing) set_counters_zero(counters, false);
 
   if (p.cap == 16) {
     rc = launch_build<GBDT_VARIANT_16>(a, blocks, s);
@@ -525,7 +569,10 @@ int gbdt_hist_build(const void* bin_matrix, int64_t n_rows, int32_t n_features, 
     rc = launch_build<GBDT_VARIANT_256>(a, blocks, s);
   }
   if (rc != GBDT_OK) return rc;
-  if (a.direct_out) return GBDT_OK;  // one workgroup per tile: the histogram is written
+  if (a.direct_out) {  // one workgroup per tile: the histogram is written
+    if (uses_counters && capturing) return zero_counters();
+    return GBDT_OK;
+  }
 
   MergeArgs m;
   m.partials = (const uint32_t*)ws;
@@ -535,11 +582,13 @@ int gbdt_hist_build(const void* bin_matrix, int64_t n_rows, int32_t n_features, 
   m.n_bins = n_bins;
   m.chunks_main = g.wgs;
   m.chunks_rem = p.wr ? g.wgs : 0;
+  m.counters = uses_counters ? counters : nullptr;
   const int max_slots = plan_slots(p, p.wm);
   const int mx = (n_bins * max_slots + kMergeCells - 1) / kMergeCells;
   hipLaunchKernelGGL(hist_merge_kernel, dim3(mx, plan_n_tiles(p)), dim3(kMergeCells * kMergeLanes),
                      0, s, m);
   HIP_TRY(hipGetLastError());
+  if (uses_counters && !capturing) set_counters_zero(counters, true);  // the reduction pass leaves them zero
   return GBDT_OK;
 }
 
@@ -593,6 +642,7 @@ int gbdt_hist_build_batch(const void* bin_matrix, int64_t n_rows, int32_t n_feat
     m.m.n_bins = n_bins;
     m.m.chunks_main = 0;
     m.m.chunks_rem = 0;
+    m.m.counters = nullptr;
     m.column_words = col;
     memcpy(m.leaf, b.leaf, sizeof m.leaf);
     if (b.total_wgs > 0) {
@@ -646,7 +696,7 @@ size_t gbdt_hist_build_batch_workspace_bytes(int32_t n_features, int32_t n_bins,
   if (budget < 1) budget = 1;
   const int64_t per_launch = n_leaves < kBatchLeaves ? n_leaves : kBatchLeaves;
   const size_t b = (size_t)(budget + per_launch) * col * 4 + 256;
-  return (b + 255) / 256 * 256;
+  return (b + 255) / 256 * 256 + kWsHeadBytes;
 }
 
 int gbdt_hist_subtract(const gbdt_bin_t* parent, const gbdt_bin_t* child, gbdt_bin_t* sibling_out,

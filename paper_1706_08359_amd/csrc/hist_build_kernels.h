@@ -204,7 +204,7 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
                                            const float* __restrict__ hess, uint32_t end,
                                            uint32_t first_unit, uint32_t unit_epochs,
                                            uint32_t fixed_stride, uint32_t* counter,
-                                           unsigned long long* lds,
+                                           uint32_t counter_base, unsigned long long* lds,
                                            uint32_t* __restrict__ out, const DirectOut& direct) {
   using S = TileShape<CAP, W, NIB, NT>;
   constexpr int VEC = S::VEC, NWORD = S::NWORD, LPR = S::LPR, RPW = S::RPW, NBW = S::NBW;
@@ -432,7 +432,8 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
   // Work distribution.  The workgroups of a tile share out the n_epochs epochs of the
   // leaf in units of unit_epochs consecutive epochs.  Workgroup c of the tile starts
   // with unit c; when it enters a unit, one lane takes the next one from the tile's
-  // counter (a global atomic), and the pipeline of
+  // counter (a global atomic that starts at zero: the take is counter_base + its old
+  // value, counter_base = the units the workgroups started with), and the pipeline of
   // requests (row ids two epochs ahead, gradients / hessians and bins one epoch ahead)
   // runs on from the last epoch of a unit into the first epoch of the next.  Fast and
   // slow workgroups (the CU issues the instructions of its oldest workgroup first) so
@@ -495,7 +496,7 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
       if (fixed_stride) {
         taken = p0.row / (unit_epochs * (uint32_t)kEpochRows) + fixed_stride;
       } else if (tid == 0) {
-        taken = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        taken = counter_base + __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
     }
     // ---- requests for later epochs
@@ -609,30 +610,31 @@ hist_build_kernel(BuildArgs a) {
     uint32_t* out = a.partials + ((size_t)t * a.wgs + c) * (size_t)block_words<CAP, WM, NIB, NT>();
     build_tile<CAP, WM, NIB, NT, ACC, INDEXED>(tile, a.idx, a.grad, a.hess, n_leaf, (uint32_t)c,
                                                (uint32_t)a.unit_epochs, (uint32_t)a.fixed_stride, counter,
-                                               lds, out, direct);
+                                               (uint32_t)a.wgs, lds, out, direct);
   } else {
     uint32_t* rem_base = a.partials + (size_t)main_blocks * (size_t)block_words<CAP, WM, NIB, NT>();
     if (a.wr == 16) {
       build_tile<CAP, 16, NIB, NT, ACC, INDEXED>(
           tile, a.idx, a.grad, a.hess, n_leaf, (uint32_t)c, (uint32_t)a.unit_epochs,
-          (uint32_t)a.fixed_stride, counter, lds,
+          (uint32_t)a.fixed_stride, counter, (uint32_t)a.wgs, lds,
           rem_base + (size_t)c * (size_t)block_words<CAP, 16, NIB, NT>(), direct);
     } else if constexpr (WM > 32) {
       build_tile<CAP, 32, NIB, NT, ACC, INDEXED>(
           tile, a.idx, a.grad, a.hess, n_leaf, (uint32_t)c, (uint32_t)a.unit_epochs,
-          (uint32_t)a.fixed_stride, counter, lds,
+          (uint32_t)a.fixed_stride, counter, (uint32_t)a.wgs, lds,
           rem_base + (size_t)c * (size_t)block_words<CAP, 32, NIB, NT>(), direct);
     }
   }
 }
 
-// Sets every tile's unit counter to the number of units its workgroups start with
-// (one each).  (A fill kernel, not a memset node, so the call can be captured into a
-// graph.)
-__global__ void __launch_bounds__(256)
-counters_init_kernel(uint32_t* counters, int32_t wgs, int32_t n_counters) {
+// The unit counters of all tiles live at the head of the scratch workspace and are zero
+// between calls: a workgroup's take is (workgroups per tile) + (old counter value), and
+// the reduction pass, which follows every build that used them, sets them back to zero.
+// This kernel zeroes them when a workspace is new.  (A fill kernel, not a memset node, so
+// the call can be captured into a graph.)
+__global__ void __launch_bounds__(256) counters_zero_kernel(uint32_t* counters, int32_t n_counters) {
   const int32_t i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n_counters) counters[i] = (uint32_t)wgs;
+  if (i < n_counters) counters[i] = 0u;
 }
 
 // Several leaves in one launch.  Small leaves cannot fill the machine on their own (the
@@ -689,18 +691,18 @@ hist_build_batch_kernel(BatchArgs a) {
       t, WM, a.n_main, a.wr, a.n_features, a.n_bins};
   if (is_main) {
     build_tile<CAP, WM, NIB, NT, ACC, true>(
-        tile, idx, a.grad, a.hess, lf.n, (uint32_t)c, unit_epochs, (uint32_t)wgs, nullptr, lds,
+        tile, idx, a.grad, a.hess, lf.n, (uint32_t)c, unit_epochs, (uint32_t)wgs, nullptr, 0u, lds,
         leaf_out + ((size_t)t * wgs + c) * (size_t)block_words<CAP, WM, NIB, NT>(), direct);
   } else {
     uint32_t* rem_base = leaf_out + (size_t)main_blocks * (size_t)block_words<CAP, WM, NIB, NT>();
     if (a.wr == 16) {
       build_tile<CAP, 16, NIB, NT, ACC, true>(tile, idx, a.grad, a.hess, lf.n, (uint32_t)c, unit_epochs,
-                                              (uint32_t)wgs, nullptr, lds,
+                                              (uint32_t)wgs, nullptr, 0u, lds,
                                               rem_base + (size_t)c * (size_t)block_words<CAP, 16, NIB, NT>(),
                                               direct);
     } else if constexpr (WM > 32) {
       build_tile<CAP, 32, NIB, NT, ACC, true>(tile, idx, a.grad, a.hess, lf.n, (uint32_t)c, unit_epochs,
-                                              (uint32_t)wgs, nullptr, lds,
+                                              (uint32_t)wgs, nullptr, 0u, lds,
                                               rem_base + (size_t)c * (size_t)block_words<CAP, 32, NIB, NT>(),
                                               direct);
     }

@@ -25,6 +25,7 @@ struct MergeArgs {
   int32_t n_bins;
   int32_t chunks_main;
   int32_t chunks_rem;
+  uint32_t* counters;  // the tiles' unit counters, set back to zero here; NULL: not used by the build
 };
 
 constexpr int kMergeCells = 64;   // histogram cells per workgroup
@@ -37,6 +38,7 @@ constexpr int kMergeLanes = 4;    // threads that share the chunks of one cell
 // order, and the 4 sub-sums are added in a fixed order: the result does not depend
 // on scheduling.  Counts are summed as integers.  grid.y = tile.
 __device__ __forceinline__ void merge_cells(const MergeArgs& a) {
+  if (a.counters && blockIdx.x == 0 && threadIdx.x == 0) a.counters[blockIdx.y] = 0u;
   __shared__ double s_g[kMergeLanes][kMergeCells];
   __shared__ double s_h[kMergeLanes][kMergeCells];
   __shared__ uint32_t s_n[kMergeLanes][kMergeCells];

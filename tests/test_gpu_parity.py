@@ -239,6 +239,58 @@ def test_graph_capture_replays_match_eager():
         B.gbdt_set_deterministic(False)
 
 
+def test_unit_counters_stay_consistent_across_scratch_buffers_and_graphs():
+    """The run-time hand-out of work keeps its counters at the head of the scratch buffer and
+    expects them zero between calls.  Buffers that arrive full of garbage, switching between
+    caller and library scratch, and a captured graph replayed between eager calls must all
+    leave every histogram right (a wrong counter would skip or repeat units: counts off)."""
+    n, F, nb = 300_000, 40, 64
+    rng = np.random.default_rng(77)
+    bins = rng.integers(0, nb, size=(n, F), dtype=np.uint8)
+    grad = rng.normal(size=n).astype(np.float32)
+    hess = rng.uniform(0.1, 1.0, size=n).astype(np.float32)
+    p = GpuProblem(bins, nb, grad, hess)
+    idx = torch.arange(0, n, 2, dtype=torch.int32, device="cuda:0")
+    ref_root, ref_leaf = p.oracle(), p.oracle(idx)
+    sg, sh = p.leaf_abs_sums()
+    lg, lh = p.leaf_abs_sums(idx)
+
+    def check(tag):
+        assert_hist_close(B.hist_to_numpy(p.build()), ref_root, sg, sh, tag + " root")
+        assert_hist_close(B.hist_to_numpy(p.build(idx)), ref_leaf, lg, lh, tag + " leaf")
+
+    need = B.gbdt_workspace_bytes(n, F, nb)
+    ws_a = torch.full((need,), 0xAB, dtype=torch.uint8, device="cuda:0")
+    ws_b = torch.full((need,), 0xFF, dtype=torch.uint8, device="cuda:0")
+    try:
+        check("library scratch")
+        B.gbdt_set_workspace(ws_a)
+        check("caller scratch A (garbage)")
+        check("caller scratch A again")
+        B.gbdt_set_workspace(None)
+        check("library scratch again")
+        B.gbdt_set_workspace(ws_b)
+        check("caller scratch B (garbage)")
+        ws_b.fill_(0x5C)                      # the caller overwrote its buffer and registers it anew
+        B.gbdt_set_workspace(ws_b)
+        check("caller scratch B refilled")
+        # a graph captured on this buffer, replayed between eager calls
+        hist = torch.empty((F, nb, 3), dtype=torch.float32, device="cuda:0")
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            B.gbdt_hist_build(p.packed, n, F, nb, idx, idx.numel(), p.grad, p.hess, hist_out=hist)
+        for trial in range(3):
+            hist.zero_()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert_hist_close(B.hist_to_numpy(hist), ref_leaf, lg, lh, f"replay {trial}")
+            check(f"eager after replay {trial}")
+    finally:
+        B.gbdt_set_workspace(None)
+    check("library scratch at the end")
+
+
 def test_runs_on_a_side_stream():
     w = synth.config1_tiny_dense()
     p = GpuProblem(w.bins, w.n_bins, w.grad, w.hess)
