@@ -17,7 +17,10 @@
  *  - Return value: GBDT_OK (0) or a negative gbdt_status code.  Argument
  *    errors are detected before anything is enqueued.  Contents of device
  *    buffers (bin values < n_bins, row ids < n_rows) are NOT checked;
- *    violating them is undefined behaviour.
+ *    violating them is undefined behaviour.  Debugging aid: with the environment
+ *    variable GBDT_HIST_CHECK_INPUTS=1 every call that takes a row list first counts
+ *    its out-of-range entries on the device, waits for the stream, and returns
+ *    GBDT_EINVAL if there are any.
  *  - Bins are 0-based: a binned value b satisfies 0 <= b < n_bins (the paper
  *    writes 1..k).  2 <= n_bins <= 256.
  *  - The library keeps one scratch workspace per process (partial histograms,

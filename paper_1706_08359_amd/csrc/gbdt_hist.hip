@@ -281,6 +281,39 @@ void split_grouping(int32_t n_features, int32_t n_bins, int* group_out, int* n_g
   *n_groups_out = (n_features + group - 1) / group;
 }
 
+// GBDT_HIST_CHECK_INPUTS=1 (debugging): every call that takes a row list first counts its
+// out-of-range entries on the device, WAITS for the stream and fails with GBDT_EINVAL if
+// there are any, instead of the undefined behaviour of the unchecked path.
+bool check_inputs_enabled() {
+  static const bool on = [] {
+    const char* e = getenv("GBDT_HIST_CHECK_INPUTS");
+    return e && atoi(e) > 0;
+  }();
+  return on;
+}
+
+int check_row_ids(const int32_t* idx, int64_t n, int64_t n_rows, hipStream_t s) {
+  if (!check_inputs_enabled() || !idx || n <= 0) return GBDT_OK;
+  void* ws = nullptr;
+  int rc = get_workspace(256, &ws);
+  if (rc != GBDT_OK) return rc;
+  unsigned long long* n_bad = (unsigned long long*)ws;
+  hipLaunchKernelGGL(counters_zero_kernel, dim3(1), dim3(256), 0, s, (uint32_t*)ws, 2);
+  HIP_TRY(hipGetLastError());
+  const int64_t blocks = (n + 255) / 256;
+  hipLaunchKernelGGL(row_ids_check_kernel, dim3((unsigned)(blocks < 4096 ? blocks : 4096)), dim3(256), 0, s, idx,
+                     n, n_rows, n_bad);
+  HIP_TRY(hipGetLastError());
+  unsigned long long bad = 0;
+  HIP_TRY(hipMemcpyAsync(&bad, n_bad, sizeof bad, hipMemcpyDeviceToHost, s));
+  HIP_TRY(hipStreamSynchronize(s));
+  if (bad) {
+    snprintf(g_hip_err, sizeof g_hip_err, "%llu row ids outside [0, n_rows)", bad);
+    return GBDT_EINVAL;
+  }
+  return GBDT_OK;
+}
+
 bool valid_shape(int64_t n_rows, int32_t n_features, int32_t n_bins) {
   return n_rows >= 0 && n_features > 0 && n_bins >= 2 && n_bins <= 256;
 }
@@ -501,6 +534,10 @@ int gbdt_hist_build(const void* bin_matrix, int64_t n_rows, int32_t n_features, 
     return GBDT_OK;
   }
   if (!bin_matrix || !grad || !hess) return GBDT_EINVAL;
+  {
+    const int rc_ids = check_row_ids(leaf_row_idx, n_leaf_rows, n_rows, s);
+    if (rc_ids != GBDT_OK) return rc_ids;
+  }
 
   const BuildGeom g =
       make_geom(n_features, n_bins, n_leaf_rows, device_cu_count(),
@@ -627,10 +664,14 @@ int gbdt_hist_build_batch(const void* bin_matrix, int64_t n_rows, int32_t n_feat
     const size_t w = (size_t)b.total_wgs * col;
     if (w > need_words) need_words = w;
   }
+  hipStream_t s = (hipStream_t)stream;
+  if (total_rows > 0) {
+    const int rc_ids = check_row_ids(row_idx + leaf_offsets[0], total_rows, n_rows, s);
+    if (rc_ids != GBDT_OK) return rc_ids;
+  }
   void* ws = nullptr;
   int rc = get_workspace(need_words * 4 + 256, &ws);
   if (rc != GBDT_OK) return rc;
-  hipStream_t s = (hipStream_t)stream;
   for (int32_t l0 = 0; l0 < n_leaves; l0 += kBatchLeaves) {
     const int32_t n = n_leaves - l0 < kBatchLeaves ? n_leaves - l0 : kBatchLeaves;
     const BatchPlan b = plan_batch(leaf_offsets, l0, n, resident, n_tiles);
@@ -746,6 +787,10 @@ int gbdt_partition_rows(const void* bin_matrix, int64_t n_rows, int32_t n_featur
   if (n_rows == 0 && n_leaf_rows > 0) return GBDT_EINVAL;
   if (n_rows >= ((int64_t)1 << 30) || n_leaf_rows >= ((int64_t)1 << 31)) return GBDT_EUNSUPPORTED;
   hipStream_t s = (hipStream_t)stream;
+  {
+    const int rc_ids = check_row_ids(leaf_row_idx, n_leaf_rows, n_rows, s);
+    if (rc_ids != GBDT_OK) return rc_ids;
+  }
   const TilePlan p = make_tile_plan(n_features, n_bins);
   if (n_leaf_rows <= (int64_t)kPartThreads * kPartOneSteps) {  // small leaf: one workgroup, one launch
     hipLaunchKernelGGL(partition_one_kernel, dim3(1), dim3(kPartThreads), 0, s, (const uint8_t*)bin_matrix,

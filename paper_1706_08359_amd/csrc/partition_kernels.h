@@ -231,6 +231,19 @@ partition_one_kernel(const uint8_t* __restrict__ packed, int64_t n_rows, int32_t
   }
 }
 
+// Debug aid: counts the entries of a row list that are not row ids of the matrix.
+__global__ void __launch_bounds__(256)
+row_ids_check_kernel(const int32_t* __restrict__ idx, int64_t n, int64_t n_rows,
+                     unsigned long long* __restrict__ n_bad) {
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  unsigned long long bad = 0;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+    const int64_t r = idx[i];
+    bad += (r < 0 || r >= n_rows) ? 1ull : 0ull;
+  }
+  if (bad) atomicAdd(n_bad, bad);
+}
+
 // out[i] = i: the row list of the root, for a tree that never splits.
 __global__ void __launch_bounds__(256) row_iota_kernel(int32_t* __restrict__ out, int64_t n) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;

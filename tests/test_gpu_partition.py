@@ -219,3 +219,42 @@ def test_tree_grown_on_device_matches_oracle_node_by_node(shape):
     # the first split is found identically by both sides end to end
     ref_root = orc.best_split(orc.hist_build(bins, nb, grad, hess), lam, mch)
     assert (made[0]["s"]["feature"], made[0]["s"]["bin"]) == (ref_root["feature"], ref_root["bin"])
+
+
+def test_check_inputs_env_turns_a_bad_row_id_into_an_error():
+    """GBDT_HIST_CHECK_INPUTS=1 is read when the library is first used, so this runs in a child
+    process: a row list with an id past the matrix must come back as GBDT_EINVAL from the build,
+    the batched build and the partition, and a clean list must still work."""
+    import os
+    import subprocess
+    import sys
+    code = r'''
+import numpy as np, torch
+from paper_1706_08359_amd import binding as B
+dev = torch.device("cuda:0")
+bins = torch.randint(0, 32, (5000, 20), dtype=torch.uint8, device=dev)
+packed = B.gbdt_bins_pack(bins, 32)
+g = torch.randn(5000, device=dev); h = torch.rand(5000, device=dev)
+good = torch.arange(0, 5000, 2, dtype=torch.int32, device=dev)
+bad = good.clone(); bad[100] = 5000      # one past the last row: inside every buffer's slack, so harmless even unchecked
+rec = B.split_record(3, 10, dev)
+B.gbdt_hist_build(packed, 5000, 20, 32, good, good.numel(), g, h)
+B.gbdt_hist_build_batch(packed, 5000, 20, 32, good, [0, 1000, 2500], g, h)
+B.gbdt_partition_rows(packed, 5000, 20, 32, good, good.numel(), rec)
+n_err = 0
+for call in (lambda: B.gbdt_hist_build(packed, 5000, 20, 32, bad, bad.numel(), g, h),
+             lambda: B.gbdt_hist_build_batch(packed, 5000, 20, 32, bad, [0, 1000, 2500], g, h),
+             lambda: B.gbdt_partition_rows(packed, 5000, 20, 32, bad, bad.numel(), rec)):
+    try:
+        call()
+    except B.GbdtError as e:
+        assert "(-1)" in str(e), e
+        n_err += 1
+torch.cuda.synchronize()
+assert n_err == 3, n_err
+print("checked ok")
+'''
+    env = dict(os.environ, GBDT_HIST_CHECK_INPUTS="1")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    res = subprocess.run([sys.executable, "-c", code], cwd=root, env=env, capture_output=True, text=True, timeout=180)
+    assert res.returncode == 0 and "checked ok" in res.stdout, res.stdout + res.stderr
