@@ -1,5 +1,8 @@
-// libgbdt_hist: feature-histogram construction, sibling subtraction and best-split
-// scan for histogram-based GBDT training on AMD gfx950 (MI355X).
+// libgbdt_hist: feature-histogram construction, sibling subtraction, best-split scan,
+// row partition and leaf-wise tree growth for histogram-based GBDT training on AMD
+// gfx950 (MI355X).  This file holds the host side (launch planning, scratch, the C ABI);
+// the kernels are in hist_build_kernels.h, hist_reduce_kernels.h, split_kernels.h and
+// partition_kernels.h, the layouts in tile_plan.h and batch_plan.h.
 // Method: arXiv 1706.08359 -- Alg. 1 (Sec. 3.3) defines the histogram, Sec. 4 /
 // Alg. 2 / App. A.1 describe a GPU organisation for older hardware.  What is
 // kept from that design: one lane handles a bundle of adjacent features of one
