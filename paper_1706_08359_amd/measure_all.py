@@ -239,11 +239,19 @@ def tree(args, torch, B, synth, dev):
     print("| workload | rows x features, bins | leaves reached | deepest leaf | wall ms / tree (median) | wall ms / tree (min) | "
           "splits / s |")
     print("|" + "---|" * 7, flush=True)
-    for name, make in WORKLOADS.items():
+    runs = [(name, make, False) for name, make in WORKLOADS.items()]
+    # the three large shapes once more with labels that depend on the features (balanced trees)
+    runs += [(name, WORKLOADS[name], True) for name in ("dense_wide", "dense_tall", "categorical")]
+    for name, make, signal in runs:
         if args.only and name not in args.only:
             continue
         w = make(synth, dev)
         n, F, nb = w.n_rows, w.n_features, w.n_bins
+        if signal:
+            gen = torch.Generator(device=dev)
+            gen.manual_seed(31)
+            w.grad, w.hess = synth.labels_with_signal(w.bins, nb, gen)
+            name = name + " + signal"
         packed = B.gbdt_bins_pack(w.bins, nb)
         del w.bins
         scratch, order = None, torch.empty(n, dtype=torch.int32, device=dev)

@@ -90,6 +90,20 @@ def logistic_grad_hess(n_rows, gen, device, score_std=0.1):
     return (p - y).to(torch.float32), (p * (1.0 - p)).to(torch.float32)
 
 
+def labels_with_signal(bins, n_bins, gen):
+    """Binary labels that depend on the features (a smooth term, two steps and an interaction on
+    five columns, through a logistic link), for measurements on whole trees: with labels drawn
+    independently of the features every split is chosen among noise and trees degenerate into
+    long chains of tiny leaves.  Returns (grad, hess) of the logistic loss at score 0."""
+    n, F = bins.shape
+    col = lambda j: bins[:, j % F].to(torch.float32) / float(n_bins - 1)
+    z = (2.0 * (col(0) - 0.5) + 1.2 * (col(3) > 0.6).float() - 0.9 * (col(7) < 0.25).float()
+         + 1.5 * (col(11) - 0.5) * (col(2) - 0.5) + 0.8 * torch.sin(6.0 * col(5)))
+    y = (torch.rand(n, generator=gen, device=bins.device) < torch.sigmoid(z)).to(torch.float32)
+    p = torch.full((n,), 0.5, device=bins.device)
+    return (p - y).to(torch.float32), (p * (1.0 - p)).to(torch.float32)
+
+
 def leaf_by_truncated_permutation(n_rows, fraction, gen, device) -> torch.Tensor:
     """App. C.2 recipe: random permutation, truncate to fraction*n_rows, sort."""
     k = max(1, int(round(fraction * n_rows)))
