@@ -241,7 +241,7 @@ def tree(args, torch, B, synth, dev):
     print("|" + "---|" * 7, flush=True)
     runs = [(name, make, False) for name, make in WORKLOADS.items()]
     # the three large shapes once more with labels that depend on the features (balanced trees)
-    runs += [(name, WORKLOADS[name], True) for name in ("dense_wide", "dense_tall", "categorical")]
+    runs += [(name + "+signal", WORKLOADS[name], True) for name in ("dense_wide", "dense_tall", "categorical")]
     for name, make, signal in runs:
         if args.only and name not in args.only:
             continue
@@ -251,7 +251,6 @@ def tree(args, torch, B, synth, dev):
             gen = torch.Generator(device=dev)
             gen.manual_seed(31)
             w.grad, w.hess = synth.labels_with_signal(w.bins, nb, gen)
-            name = name + " + signal"
         packed = B.gbdt_bins_pack(w.bins, nb)
         del w.bins
         scratch, order = None, torch.empty(n, dtype=torch.int32, device=dev)
