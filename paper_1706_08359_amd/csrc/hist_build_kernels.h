@@ -58,6 +58,7 @@ struct BuildArgs {
   const int32_t* idx;  // NULL: rows 0..n_leaf-1
   const float* grad;
   const float* hess;
+  int32_t stats_by_pos;  // grad / hess are indexed by leaf position (gathered beforehand), not by row id
   uint32_t* partials;  // one [3][cells] block of words per workgroup
   uint32_t* counters;  // per tile: the next unit of work to hand out
   int64_t n_rows;
@@ -201,7 +202,8 @@ template <int CAP, int W, bool NIB, int NT, typename ACC, bool INDEXED>
 __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
                                            const int32_t* __restrict__ idx,
                                            const float* __restrict__ grad,
-                                           const float* __restrict__ hess, uint32_t end,
+                                           const float* __restrict__ hess, bool stats_by_pos,
+                                           uint32_t end,
                                            uint32_t first_unit, uint32_t unit_epochs,
                                            uint32_t fixed_stride, uint32_t* counter,
                                            uint32_t counter_base, unsigned long long* lds,
@@ -477,8 +479,10 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
   // rows the lane owns in the current epoch and the next one; the current row's stats
   uint32_t row_cur = load_row_id(p0.row);
   uint32_t row_nxt = load_row_id(p1.row);
-  float g_cur = load_stat(grad, row_cur);
-  float h_cur = load_stat(hess, row_cur);
+  // gradients / hessians are indexed by row id, or (stats_by_pos) by leaf position when the
+  // call has gathered them into leaf order beforehand
+  float g_cur = load_stat(grad, stats_by_pos ? own_pos(p0.row) : row_cur);
+  float h_cur = load_stat(hess, stats_by_pos ? own_pos(p0.row) : row_cur);
   uint4 w[GPE];
   load_epoch(w, row_cur, p0.row);
   {
@@ -501,8 +505,9 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
     }
     // ---- requests for later epochs
     const uint32_t row_nn = load_row_id(p2.row);
-    const float g_nxt = load_stat(grad, row_nxt);
-    const float h_nxt = load_stat(hess, row_nxt);
+    const uint32_t stat_nxt = stats_by_pos ? own_pos(p1.row) : row_nxt;
+    const float g_nxt = load_stat(grad, stat_nxt);
+    const float h_nxt = load_stat(hess, stat_nxt);
     // ---- this lane's row -> 64-bit addend 1 + gq * 2^10 + hq * 2^37 (two's complement)
     uint32_t lo, hi;
     {
@@ -608,23 +613,37 @@ hist_build_kernel(BuildArgs a) {
   const DirectOut direct = {a.direct_out, t, WM, a.n_main, a.wr, a.n_features, a.n_bins};
   if (b < main_blocks) {
     uint32_t* out = a.partials + ((size_t)t * a.wgs + c) * (size_t)block_words<CAP, WM, NIB, NT>();
-    build_tile<CAP, WM, NIB, NT, ACC, INDEXED>(tile, a.idx, a.grad, a.hess, n_leaf, (uint32_t)c,
+    build_tile<CAP, WM, NIB, NT, ACC, INDEXED>(tile, a.idx, a.grad, a.hess, a.stats_by_pos != 0, n_leaf, (uint32_t)c,
                                                (uint32_t)a.unit_epochs, (uint32_t)a.fixed_stride, counter,
                                                (uint32_t)a.wgs, lds, out, direct);
   } else {
     uint32_t* rem_base = a.partials + (size_t)main_blocks * (size_t)block_words<CAP, WM, NIB, NT>();
     if (a.wr == 16) {
       build_tile<CAP, 16, NIB, NT, ACC, INDEXED>(
-          tile, a.idx, a.grad, a.hess, n_leaf, (uint32_t)c, (uint32_t)a.unit_epochs,
+          tile, a.idx, a.grad, a.hess, a.stats_by_pos != 0, n_leaf, (uint32_t)c, (uint32_t)a.unit_epochs,
           (uint32_t)a.fixed_stride, counter, (uint32_t)a.wgs, lds,
           rem_base + (size_t)c * (size_t)block_words<CAP, 16, NIB, NT>(), direct);
     } else if constexpr (WM > 32) {
       build_tile<CAP, 32, NIB, NT, ACC, INDEXED>(
-          tile, a.idx, a.grad, a.hess, n_leaf, (uint32_t)c, (uint32_t)a.unit_epochs,
+          tile, a.idx, a.grad, a.hess, a.stats_by_pos != 0, n_leaf, (uint32_t)c, (uint32_t)a.unit_epochs,
           (uint32_t)a.fixed_stride, counter, (uint32_t)a.wgs, lds,
           rem_base + (size_t)c * (size_t)block_words<CAP, 32, NIB, NT>(), direct);
     }
   }
+}
+
+// Gradients and hessians of a row list, in list order: g_out[i] = grad[idx[i]].  The paper
+// has the CPU prepare these "ordered" arrays for every leaf (App. A.5, App. C.1); here they pay
+// when many feature tiles would each gather the same scattered 4-byte values again.
+__global__ void __launch_bounds__(256)
+stats_gather_kernel(const int32_t* __restrict__ idx, const float* __restrict__ grad,
+                    const float* __restrict__ hess, int64_t n, float* __restrict__ g_out,
+                    float* __restrict__ h_out) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  const uint32_t r = (uint32_t)idx[i];
+  g_out[i] = grad[r];
+  h_out[i] = hess[r];
 }
 
 // The unit counters of all tiles live at the head of the scratch workspace and are zero
@@ -651,6 +670,7 @@ struct BatchArgs {
   const int32_t* idx;
   const float* grad;
   const float* hess;
+  int32_t stats_by_pos;
   uint32_t* partials;
   int64_t n_rows;
   int32_t n_main;
@@ -685,23 +705,26 @@ hist_build_batch_kernel(BatchArgs a) {
   const bool is_main = t < a.n_main;
   const uint8_t* tile = a.packed + a.n_rows * ((int64_t)t * WM);
   const int32_t* idx = a.idx + lf.row_off;
+  const bool by_pos = a.stats_by_pos != 0;  // then grad / hess follow the concatenated row lists
+  const float* grad = by_pos ? a.grad + lf.row_off : a.grad;
+  const float* hess = by_pos ? a.hess + lf.row_off : a.hess;
   uint32_t* leaf_out = a.partials + (size_t)lf.first_wg * column_words<CAP, WM, NIB, NT>(a.n_main, a.wr);
   const DirectOut direct = {
       wgs == 1 ? a.hist_out + (size_t)blk.leaf * a.n_features * a.n_bins : nullptr,
       t, WM, a.n_main, a.wr, a.n_features, a.n_bins};
   if (is_main) {
     build_tile<CAP, WM, NIB, NT, ACC, true>(
-        tile, idx, a.grad, a.hess, lf.n, (uint32_t)c, unit_epochs, (uint32_t)wgs, nullptr, 0u, lds,
+        tile, idx, grad, hess, by_pos, lf.n, (uint32_t)c, unit_epochs, (uint32_t)wgs, nullptr, 0u, lds,
         leaf_out + ((size_t)t * wgs + c) * (size_t)block_words<CAP, WM, NIB, NT>(), direct);
   } else {
     uint32_t* rem_base = leaf_out + (size_t)main_blocks * (size_t)block_words<CAP, WM, NIB, NT>();
     if (a.wr == 16) {
-      build_tile<CAP, 16, NIB, NT, ACC, true>(tile, idx, a.grad, a.hess, lf.n, (uint32_t)c, unit_epochs,
+      build_tile<CAP, 16, NIB, NT, ACC, true>(tile, idx, grad, hess, by_pos, lf.n, (uint32_t)c, unit_epochs,
                                               (uint32_t)wgs, nullptr, 0u, lds,
                                               rem_base + (size_t)c * (size_t)block_words<CAP, 16, NIB, NT>(),
                                               direct);
     } else if constexpr (WM > 32) {
-      build_tile<CAP, 32, NIB, NT, ACC, true>(tile, idx, a.grad, a.hess, lf.n, (uint32_t)c, unit_epochs,
+      build_tile<CAP, 32, NIB, NT, ACC, true>(tile, idx, grad, hess, by_pos, lf.n, (uint32_t)c, unit_epochs,
                                               (uint32_t)wgs, nullptr, 0u, lds,
                                               rem_base + (size_t)c * (size_t)block_words<CAP, 32, NIB, NT>(),
                                               direct);

@@ -233,3 +233,43 @@ def test_depthwise_tree_with_batched_calls_matches_oracle(shape):
                 ref_l, ref_r = orc.partition_rows(bins, s["feature"], s["bin"], node)
                 kids = nxt["rows"].cpu().numpy()[offs[k]:offs[k + 1]]
                 assert np.array_equal(kids[:ref_l.size], ref_l) and np.array_equal(kids[ref_l.size:], ref_r)
+
+
+def test_sparse_leaves_with_stats_gathered_into_list_order():
+    """Leaves that are sparse in a many-tile matrix take the path that first gathers grad / hess
+    into list order (single-leaf and batched call): same histograms, same tolerance."""
+    n_rows, n_features, n_bins = 400_000, 300, 64
+    _say(f"sparse leaves {n_rows}x{n_features} bins={n_bins}")
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(15)
+    bins = synth.uniform_bins(n_rows, n_features, n_bins, gen, dev)
+    grad, hess = synth.logistic_grad_hess(n_rows, gen, dev)
+    p = GpuProblem(bins, n_bins, grad, hess)
+    rng = np.random.default_rng(16)
+    perm = rng.permutation(n_rows).astype(np.int32)
+    sizes = [40_000, 35_001, 50_000, 0, 33_333, 45_000]
+    lists, at = [], 0
+    for s in sizes:
+        lists.append(np.sort(perm[at:at + s]))
+        at += s
+    cols = np.array([0, 63, 64, 150, 255, 256, 299])
+    sub = np.ascontiguousarray(p.bins_cpu.numpy()[:, cols])
+    g_np, h_np = p.grad_cpu.numpy(), p.hess_cpu.numpy()
+    cat = torch.from_numpy(np.concatenate(lists)).to(dev)
+    offs = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    batched = B.hist_to_numpy(B.gbdt_hist_build_batch(p.packed, n_rows, n_features, n_bins, cat, offs, p.grad, p.hess))
+    for l, rows in enumerate(lists):
+        ref = orc.hist_build(sub, n_bins, g_np, h_np, rows)
+        sg, sh = p.leaf_abs_sums(rows) if rows.size else (0.0, 0.0)
+        assert (batched[l]["count"].sum(axis=1, dtype=np.uint64) == rows.size).all()
+        assert_hist_close(batched[l][cols], ref, sg, sh, f"batched sparse leaf {l}")
+        if rows.size:
+            single = B.hist_to_numpy(p.build(rows))
+            assert (single["count"] == batched[l]["count"]).all()
+            assert_hist_close(single[cols], ref, sg, sh, f"single sparse leaf {l}")
+    # an unsorted list with repeats goes the same way
+    rep = rng.integers(0, n_rows, size=60_000).astype(np.int32)
+    ref = orc.hist_build(sub, n_bins, g_np, h_np, rep)
+    sg, sh = p.leaf_abs_sums(rep)
+    assert_hist_close(B.hist_to_numpy(p.build(rep))[cols], ref, sg, sh, "unsorted sparse leaf")
