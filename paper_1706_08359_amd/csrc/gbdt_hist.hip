@@ -184,12 +184,16 @@ constexpr int kDirectEpochs = 4;
 // When an index-list build gathers grad / hess into leaf order first: with several feature
 // tiles (each would gather the same scattered values again), a leaf that is sparse in the
 // matrix (scattered 4-byte reads cost a memory sector each) and big enough for the saving
-// to exceed one more small launch.  Measured: 10-35 % off the build kernel of such leaves
-// on the 700-feature and 137-feature workloads, nothing to gain above a fifth of the rows.
+// to exceed one more small launch.  While the two arrays fit an XCD's L2 (4 MB) the tiles'
+// gathers mostly hit there and only leaves below a fifth of the rows gain; beyond that,
+// leaves up to half of the rows do.  Measured: 10-45 % off the build kernel of such leaves
+// on the 137-, 500- and 700-feature matrices.
 constexpr int kStatsGatherMinTiles = 4;
-constexpr int64_t kStatsGatherMinRows = 32768;
+constexpr int64_t kStatsGatherMinRows = 8192;
 bool stats_gather_pays(int n_tiles, int64_t list_rows, int64_t rows_per_leaf, int64_t n_rows) {
-  return n_tiles >= kStatsGatherMinTiles && list_rows >= kStatsGatherMinRows && rows_per_leaf * 5 <= n_rows;
+  const int64_t dense_limit = n_rows >= (1 << 20) ? 2 : 5;  // leaf holds at most 1/2 or 1/5 of the rows
+  return n_tiles >= kStatsGatherMinTiles && list_rows >= kStatsGatherMinRows &&
+         rows_per_leaf * dense_limit <= n_rows;
 }
 
 // Workgroups per tile and epochs per unit for a leaf of n_epochs epochs that may use
