@@ -41,6 +41,15 @@ def make_workload(name: str, device):
         return synth.config4_ranking_sparse(device=device, fractions=(1.0,))
     if name == "categorical":
         return synth.config5_categorical(device=device)
+    if name in ("paper_synthetic_k64", "paper_synthetic_k256"):
+        # the matrix of the paper's kernel benchmark (App. C.2): 8,000,000 x 500 uniform random bins
+        import torch
+        nb = 64 if name.endswith("k64") else 256
+        gen = torch.Generator(device=device)
+        gen.manual_seed(100 + nb)
+        bins = synth.uniform_bins(8_000_000, 500, nb, gen, device)
+        grad, hess = synth.logistic_grad_hess(8_000_000, gen, device)
+        return synth.Workload(name, bins, nb, grad, hess)
     raise SystemExit(f"unknown workload {name}")
 
 
