@@ -9,7 +9,10 @@
  * Conventions shared by every call
  *  - Pointers marked DEVICE are device (HBM) addresses owned by the caller;
  *    the library neither frees nor keeps them after the call's work on
- *    `stream` has finished.  No call takes a host data pointer.
+ *    `stream` has finished.  All data is passed by device pointer; the only
+ *    HOST pointers are small descriptors marked as such (the leaf offsets of
+ *    gbdt_hist_build_batch, the node array gbdt_grow_tree returns), which are
+ *    read or written before the call returns.
  *  - `stream` is a hipStream_t passed as void*; NULL is the default stream.
  *    Calls enqueue kernels and return; they do not synchronise and never read
  *    device data on the host (gbdt_grow_tree, which drives the others, is the one
