@@ -273,3 +273,30 @@ def test_sparse_leaves_with_stats_gathered_into_list_order():
     ref = orc.hist_build(sub, n_bins, g_np, h_np, rep)
     sg, sh = p.leaf_abs_sums(rep)
     assert_hist_close(B.hist_to_numpy(p.build(rep))[cols], ref, sg, sh, "unsorted sparse leaf")
+
+
+def test_batched_calls_with_caller_scratch():
+    """gbdt_hist_build_batch and gbdt_best_split_batch with a caller-owned scratch buffer: sized by
+    the two query functions they work; one that is too small is refused with GBDT_ENOMEM before
+    anything runs."""
+    n_rows, n_features, n_bins = 30_000, 90, 64
+    p, rng = _problem(n_rows, n_features, n_bins, 41)
+    perm = rng.permutation(n_rows).astype(np.int32)
+    lists = [np.sort(x) for x in np.split(perm, [9000, 9100, 20000])]
+    need = max(B.gbdt_hist_build_batch_workspace_bytes(n_features, n_bins, len(lists)) + 8 * n_rows + 512,
+               B.gbdt_workspace_bytes(n_rows, n_features, n_bins))
+    ws = torch.full((need,), 0x77, dtype=torch.uint8, device="cuda:0")
+    B.gbdt_set_workspace(ws)
+    try:
+        hists, got = _check_batch(p, lists, "caller scratch")
+        recs = B.splits_to_dicts(B.gbdt_best_split_batch(hists[:2], 1.0, 1e-3))
+        for l in range(2):
+            lifted = orc.from_f32_hist(got[l]["grad"], got[l]["hess"], got[l]["count"])
+            s_ref = orc.best_split(lifted, 1.0, 1e-3)
+            assert (recs[l]["feature"], recs[l]["bin"]) == (s_ref["feature"], s_ref["bin"])
+        small = torch.empty(256 * 1024 + 4096, dtype=torch.uint8, device="cuda:0")   # the counter head and little more
+        B.gbdt_set_workspace(small)
+        with pytest.raises(B.GbdtError, match=r"\(-4\)"):
+            _check_batch(p, lists, "too small")
+    finally:
+        B.gbdt_set_workspace(None)
