@@ -61,6 +61,43 @@ def grow_tree(bins, n_bins, grad, hess, max_leaves, lam, min_child_hess, min_spl
     return nodes
 
 
+def grow_tree_depthwise(bins, n_bins, grad, hess, max_depth, lam, min_child_hess, min_split_gain=0.0):
+    """Level-wise growth (the other common stopping rule: Sec. 5 runs the comparison trainers
+    with a maximum tree depth of 8): every node of the current level whose best split is
+    admissible and gains more than min_split_gain is split, level after level, until max_depth.
+    Nodes are numbered level by level, the children of a level in the order of their parents,
+    left first.  Same node dicts as grow_tree, plus "depth"."""
+    bins = np.ascontiguousarray(bins, dtype=np.uint8)
+    grad = np.ascontiguousarray(grad, dtype=np.float32)
+    hess = np.ascontiguousarray(hess, dtype=np.float32)
+
+    def make_node(parent, rows, depth):
+        hist = orc.hist_build(bins, n_bins, grad, hess, rows)
+        return dict(parent=parent, left=-1, right=-1, rows=rows, depth=depth,
+                    split=orc.best_split(hist, lam, min_child_hess),
+                    count=int(rows.size),
+                    sum_grad=float(grad[rows].astype(np.float64).sum()),
+                    sum_hess=float(hess[rows].astype(np.float64).sum()))
+
+    nodes = [make_node(-1, np.arange(bins.shape[0], dtype=np.int32), 0)]
+    level = [0]
+    for depth in range(max_depth):
+        nxt = []
+        for k in level:
+            nd = nodes[k]
+            if nd["split"]["feature"] < 0 or not nd["split"]["gain"] > min_split_gain:
+                continue
+            left, right = orc.partition_rows(bins, nd["split"]["feature"], nd["split"]["bin"], nd["rows"])
+            nd["left"], nd["right"] = len(nodes), len(nodes) + 1
+            nodes.append(make_node(k, left, depth + 1))
+            nodes.append(make_node(k, right, depth + 1))
+            nxt += [nd["left"], nd["right"]]
+        if not nxt:
+            break
+        level = nxt
+    return nodes
+
+
 def route_rows(bins, nodes):
     """Leaf reached by every row when it is sent down the tree by the stored splits alone
     (left when bin <= threshold).  Independent of the row lists kept while growing."""

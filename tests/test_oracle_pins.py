@@ -448,3 +448,47 @@ def test_tree_stops_when_nothing_can_be_split():
     bins, grad, hess, B = _tree_problem(3)
     nodes = tree_oracle.grow_tree(bins, B, grad, hess, 8, 1.0, 1e-3, min_split_gain=1e9)
     assert len(nodes) == 1
+
+
+def test_depthwise_tree_splits_every_splittable_node_level_by_level():
+    bins, grad, hess, B = _tree_problem(5, n=1500, F=5, B=12)
+    lam, mch = 0.5, 1e-3
+    nodes = tree_oracle.grow_tree_depthwise(bins, B, grad, hess, 4, lam, mch)
+    assert nodes[0]["depth"] == 0 and max(nd["depth"] for nd in nodes) <= 4
+    # numbering: level by level, children in the order of their parents, left first
+    depths = [nd["depth"] for nd in nodes]
+    assert depths == sorted(depths)
+    for k, nd in enumerate(nodes):
+        f, t, gain = brute_force_best_split(bins, B, grad, hess, nd["rows"], lam, mch)
+        if nd["left"] >= 0:
+            assert nd["right"] == nd["left"] + 1 and nodes[nd["left"]]["depth"] == nd["depth"] + 1
+            assert (nd["split"]["feature"], nd["split"]["bin"]) == (f, t)       # exhaustive search agrees
+        else:
+            # a leaf is either at the depth limit or cannot be split at all
+            assert nd["depth"] == 4 or f < 0 or not gain > 0.0
+    parents = [k for k, nd in enumerate(nodes) if nd["left"] >= 0]
+    assert [nodes[k]["left"] for k in parents] == sorted(nodes[k]["left"] for k in parents)
+    # rows are where the splits route them
+    at = tree_oracle.route_rows(bins, nodes)
+    for k, nd in enumerate(nodes):
+        if nd["left"] < 0:
+            assert np.array_equal(np.nonzero(at == k)[0], nd["rows"])
+    # depth 0 is the root alone; a gain threshold nothing reaches stops at the root too
+    assert len(tree_oracle.grow_tree_depthwise(bins, B, grad, hess, 0, lam, mch)) == 1
+    assert len(tree_oracle.grow_tree_depthwise(bins, B, grad, hess, 4, lam, mch, min_split_gain=1e9)) == 1
+
+
+def test_depthwise_tree_recovers_the_planted_two_level_structure():
+    rng = np.random.default_rng(12)
+    n, F, B = 4000, 5, 8
+    bins = rng.integers(0, B, size=(n, F), dtype=np.uint8)
+    a = bins[:, 1] > 3
+    y = np.where(a, np.where(bins[:, 3] > 5, 4.0, 1.0), np.where(bins[:, 0] > 1, -1.0, -4.0))
+    grad, hess = (-y).astype(np.float32), np.ones(n, np.float32)
+    nodes = tree_oracle.grow_tree_depthwise(bins, B, grad, hess, 2, 0.0, 0.0)
+    assert len(nodes) == 7
+    assert (nodes[0]["split"]["feature"], nodes[0]["split"]["bin"]) == (1, 3)
+    assert (nodes[1]["split"]["feature"], nodes[1]["split"]["bin"]) == (0, 1)      # left child: bins[:,1] <= 3
+    assert (nodes[2]["split"]["feature"], nodes[2]["split"]["bin"]) == (3, 5)
+    for nd in nodes[3:]:
+        assert min(abs(-nd["sum_grad"] / nd["sum_hess"] - v) for v in (4.0, 1.0, -1.0, -4.0)) < 1e-9
