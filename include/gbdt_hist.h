@@ -248,6 +248,23 @@ int gbdt_partition_rows(const void* bin_matrix, int64_t n_rows, int32_t n_featur
                         void* stream);
 
 /*
+ * gbdt_partition_rows for several leaves at once (a level of a tree): leaf l has the row list
+ * row_idx[leaf_offsets[l] .. leaf_offsets[l + 1]) and the split record splits[l]; its children
+ * are written to the same positions of children_out (left rows, then right rows, order
+ * kept), so the children of a whole level again lie back to back and can go straight into
+ * gbdt_hist_build_batch.  Two kernel launches per 256 leaves.
+ *   row_idx        DEVICE int32, row ids in [0, n_rows)
+ *   leaf_offsets   HOST int64 [n_leaves + 1], non-decreasing, read before the call returns
+ *   splits         DEVICE gbdt_split_t [n_leaves]; a record without a split keeps all rows left
+ *   children_out   DEVICE int32, as long as row_idx; must not overlap it
+ *   n_left_out     DEVICE int64 [n_leaves] or NULL
+ */
+int gbdt_partition_rows_batch(const void* bin_matrix, int64_t n_rows, int32_t n_features,
+                              int32_t n_bins, const int32_t* row_idx, const int64_t* leaf_offsets,
+                              int32_t n_leaves, const gbdt_split_t* splits, int32_t* children_out,
+                              int64_t* n_left_out, void* stream);
+
+/*
  * One node of a tree grown by gbdt_grow_tree (a HOST struct).  Node 0 is the root; the two
  * children of a split get the next two ids, left first, so parents precede children.
  */

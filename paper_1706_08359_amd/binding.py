@@ -25,6 +25,7 @@ EXPORTS = [
     "gbdt_calibration_copy", "gbdt_set_deterministic", "gbdt_partition_rows",
     "gbdt_hist_build_batch", "gbdt_hist_build_batch_workspace_bytes", "gbdt_best_split_batch",
     "gbdt_debug_batch_plan", "gbdt_grow_tree", "gbdt_grow_tree_scratch_bytes",
+    "gbdt_partition_rows_batch",
 ]
 
 # numpy views of the two C structs
@@ -76,6 +77,10 @@ def load():
     lib.gbdt_best_split_batch.restype = c.c_int
     lib.gbdt_best_split_batch.argtypes = [c.c_void_p, c.c_int32, c.c_float, c.c_float, c.c_void_p,
                                           c.c_int32, c.c_int32, c.c_void_p]
+    lib.gbdt_partition_rows_batch.restype = c.c_int
+    lib.gbdt_partition_rows_batch.argtypes = [c.c_void_p, c.c_int64, c.c_int32, c.c_int32, c.c_void_p,
+                                              c.POINTER(c.c_int64), c.c_int32, c.c_void_p, c.c_void_p,
+                                              c.c_void_p, c.c_void_p]
     lib.gbdt_grow_tree.restype = c.c_int
     lib.gbdt_grow_tree.argtypes = [c.c_void_p, c.c_int64, c.c_int32, c.c_int32, c.c_void_p, c.c_void_p,
                                    c.c_int32, c.c_float, c.c_float, c.c_float, c.c_void_p, c.c_size_t,
@@ -287,6 +292,34 @@ def gbdt_partition_rows(bin_matrix, n_rows, n_features, n_bins, leaf_row_idx, n_
                                       _dev(children_out, torch.int32, "children_out"),
                                       _dev(n_left_out, torch.int64, "n_left_out"),
                                       _stream(stream)), "gbdt_partition_rows")
+    return children_out, n_left_out
+
+
+def gbdt_partition_rows_batch(bin_matrix, n_rows, n_features, n_bins, row_idx, leaf_offsets, splits,
+                              children_out=None, n_left_out=None, stream=None):
+    """splits: int32 CUDA tensor [n_leaves, 9].  Returns (children_out int32 like row_idx,
+    n_left_out int64 [n_leaves])."""
+    offs = [int(o) for o in leaf_offsets]
+    n_leaves = len(offs) - 1
+    if splits.numel() < 9 * n_leaves:
+        raise GbdtError("splits: expected one gbdt_split_t per leaf")
+    if row_idx.numel() < offs[-1]:
+        raise GbdtError("row_idx shorter than leaf_offsets[-1]")
+    if bin_matrix.numel() < gbdt_bins_packed_bytes(n_rows, n_features, n_bins):
+        raise GbdtError("bin_matrix smaller than the packed layout of this shape")
+    if children_out is None:
+        children_out = torch.empty_like(row_idx)
+    elif children_out.numel() < offs[-1]:
+        raise GbdtError("children_out too small")
+    if n_left_out is None:
+        n_left_out = torch.empty(max(n_leaves, 1), dtype=torch.int64, device=row_idx.device)
+    arr = (ctypes.c_int64 * (n_leaves + 1))(*offs)
+    _check(load().gbdt_partition_rows_batch(_dev(bin_matrix, torch.uint8, "bin_matrix"), n_rows, n_features,
+                                            n_bins, _dev(row_idx, torch.int32, "row_idx"), arr, n_leaves,
+                                            _dev(splits, torch.int32, "splits"),
+                                            _dev(children_out, torch.int32, "children_out"),
+                                            _dev(n_left_out, torch.int64, "n_left_out"), _stream(stream)),
+           "gbdt_partition_rows_batch")
     return children_out, n_left_out
 
 

@@ -863,6 +863,92 @@ int gbdt_partition_rows(const void* bin_matrix, int64_t n_rows, int32_t n_featur
   return GBDT_OK;
 }
 
+int gbdt_partition_rows_batch(const void* bin_matrix, int64_t n_rows, int32_t n_features,
+                              int32_t n_bins, const int32_t* row_idx, const int64_t* leaf_offsets,
+                              int32_t n_leaves, const gbdt_split_t* splits, int32_t* children_out,
+                              int64_t* n_left_out, void* stream) {
+  if (!valid_shape(n_rows, n_features, n_bins)) return GBDT_EINVAL;
+  if (n_leaves < 0) return GBDT_EINVAL;
+  if (n_leaves == 0) return GBDT_OK;
+  if (!leaf_offsets || !splits) return GBDT_EINVAL;
+  if (leaf_offsets[0] < 0) return GBDT_EINVAL;
+  int64_t longest = 0;
+  for (int32_t l = 0; l < n_leaves; ++l) {
+    const int64_t n = leaf_offsets[l + 1] - leaf_offsets[l];
+    if (n < 0) return GBDT_EINVAL;
+    if (n >= ((int64_t)1 << 31)) return GBDT_EUNSUPPORTED;
+    if (n > longest) longest = n;
+  }
+  const int64_t total_rows = leaf_offsets[n_leaves] - leaf_offsets[0];
+  if (total_rows > 0 && (!bin_matrix || !row_idx || !children_out)) return GBDT_EINVAL;
+  if (total_rows > 0 && n_rows == 0) return GBDT_EINVAL;
+  if (n_rows >= ((int64_t)1 << 30)) return GBDT_EUNSUPPORTED;
+  hipStream_t s = (hipStream_t)stream;
+  if (total_rows > 0) {
+    const int rc_ids = check_row_ids(row_idx + leaf_offsets[0], total_rows, n_rows, s);
+    if (rc_ids != GBDT_OK) return rc_ids;
+  }
+  // chunks of 256 * rows_per_thread positions, at most kPartMaxChunks per leaf
+  const int32_t rpt = make_part_geom(longest > 0 ? longest : 1).rows_per_thread;
+  const int64_t chunk_rows = (int64_t)kPartThreads * rpt;
+  // scratch for the launch with the most chunks
+  int64_t max_chunks = 0;
+  for (int32_t l0 = 0; l0 < n_leaves; l0 += kPartBatchLeaves) {
+    const int32_t n = n_leaves - l0 < kPartBatchLeaves ? n_leaves - l0 : kPartBatchLeaves;
+    if (leaf_offsets[l0 + n] - leaf_offsets[l0] >= ((int64_t)1 << 32)) return GBDT_EUNSUPPORTED;
+    int64_t chunks = 0;
+    for (int32_t i = 0; i < n; ++i)
+      chunks += (leaf_offsets[l0 + i + 1] - leaf_offsets[l0 + i] + chunk_rows - 1) / chunk_rows;
+    if (chunks > max_chunks) max_chunks = chunks;
+  }
+  if (max_chunks >= ((int64_t)1 << 31)) return GBDT_EUNSUPPORTED;
+  const size_t flag_words = (size_t)max_chunks * rpt * kPartWaves;
+  void* ws = nullptr;
+  int rc = get_workspace(flag_words * 8 + (size_t)max_chunks * 4 + 256, &ws);
+  if (rc != GBDT_OK) return rc;
+  const TilePlan p = make_tile_plan(n_features, n_bins);
+  for (int32_t l0 = 0; l0 < n_leaves; l0 += kPartBatchLeaves) {
+    const int32_t n = n_leaves - l0 < kPartBatchLeaves ? n_leaves - l0 : kPartBatchLeaves;
+    PartBatchArgs a;
+    a.packed = (const uint8_t*)bin_matrix;
+    a.idx = row_idx + leaf_offsets[l0];
+    a.split = splits + l0;
+    a.out = children_out + leaf_offsets[l0];
+    a.n_left_out = n_left_out ? n_left_out + l0 : nullptr;
+    a.flags = (uint64_t*)ws;
+    a.chunk_left = (uint32_t*)(a.flags + flag_words);
+    a.n_rows = n_rows;
+    a.plan = p;
+    a.n_features = n_features;
+    a.rows_per_thread = rpt;
+    a.n_leaves = n;
+    uint32_t chunks = 0;
+    for (int32_t i = 0; i < kPartBatchLeaves; ++i) {
+      PartLeaf& lf = a.leaf[i];
+      if (i < n) {
+        lf.row_off = (uint32_t)(leaf_offsets[l0 + i] - leaf_offsets[l0]);
+        lf.n = (uint32_t)(leaf_offsets[l0 + i + 1] - leaf_offsets[l0 + i]);
+        lf.first_chunk = chunks;
+        chunks += (uint32_t)(((int64_t)lf.n + chunk_rows - 1) / chunk_rows);
+      } else {
+        lf.row_off = lf.n = 0;
+        lf.first_chunk = chunks;
+      }
+    }
+    a.n_chunks = chunks;
+    if (n_left_out) {
+      hipLaunchKernelGGL(partition_empty_counts_kernel, dim3((n + 255) / 256), dim3(256), 0, s, a);
+      HIP_TRY(hipGetLastError());
+    }
+    if (chunks == 0) continue;
+    hipLaunchKernelGGL(partition_flag_batch_kernel, dim3(chunks), dim3(kPartThreads), 0, s, a);
+    HIP_TRY(hipGetLastError());
+    hipLaunchKernelGGL(partition_scatter_batch_kernel, dim3(chunks), dim3(kPartThreads), 0, s, a);
+    HIP_TRY(hipGetLastError());
+  }
+  return GBDT_OK;
+}
+
 // --- leaf-wise tree growth -------------------------------------------------------------
 
 size_t gbdt_grow_tree_scratch_bytes(int64_t n_rows, int32_t n_features, int32_t n_bins,

@@ -102,16 +102,15 @@ __device__ __forceinline__ bool goes_left(const SplitColumn& c, const uint8_t* _
   return (int32_t)b <= c.thr;
 }
 
-__global__ void __launch_bounds__(kPartThreads)
-partition_flag_kernel(const uint8_t* __restrict__ packed, int64_t n_rows, int32_t n_features,
-                      TilePlan plan, const int32_t* __restrict__ idx, int64_t n_leaf,
-                      const gbdt_split_t* __restrict__ split, int32_t rows_per_thread,
-                      uint64_t* __restrict__ flags, uint32_t* __restrict__ chunk_left) {
+// Flag pass of one chunk: positions [chunk * 256 * rows_per_thread, ...) of the list idx[0..n_leaf).
+__device__ __forceinline__ void partition_flag_chunk(const SplitColumn& sc, const uint8_t* __restrict__ packed,
+                                                     int64_t n_rows, const int32_t* __restrict__ idx,
+                                                     int64_t n_leaf, int32_t chunk, int32_t rows_per_thread,
+                                                     uint64_t* __restrict__ my_flags,
+                                                     uint32_t* __restrict__ my_chunk_left) {
   __shared__ uint32_t s_left[kPartWaves];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const SplitColumn sc = split_column(split, plan, n_rows, n_features);
-  const int64_t chunk_base = (int64_t)blockIdx.x * kPartThreads * rows_per_thread;
-  uint64_t* my_flags = flags + (size_t)blockIdx.x * rows_per_thread * kPartWaves;
+  const int64_t chunk_base = (int64_t)chunk * kPartThreads * rows_per_thread;
   uint32_t wave_left = 0;
   for (int32_t k = 0; k < rows_per_thread; ++k) {
     const int64_t e = chunk_base + (int64_t)k * kPartThreads + tid;
@@ -125,18 +124,22 @@ partition_flag_kernel(const uint8_t* __restrict__ packed, int64_t n_rows, int32_
     uint32_t c = 0;
 #pragma unroll
     for (int i = 0; i < kPartWaves; ++i) c += s_left[i];
-    chunk_left[blockIdx.x] = c;
+    *my_chunk_left = c;
   }
 }
 
-__global__ void __launch_bounds__(kPartThreads)
-partition_scatter_kernel(const int32_t* __restrict__ idx, int64_t n_leaf, int32_t rows_per_thread,
-                         const uint64_t* __restrict__ flags, const uint32_t* __restrict__ chunk_left,
-                         int32_t n_chunks, int32_t* __restrict__ out, int64_t* __restrict__ n_left_out) {
+// Scatter pass of one chunk of a list with n_chunks chunks whose left counts are
+// chunk_left[0..n_chunks) and whose flag words start at `flags`.
+__device__ __forceinline__ void partition_scatter_chunk(const int32_t* __restrict__ idx, int64_t n_leaf,
+                                                        int32_t chunk, int32_t n_chunks,
+                                                        int32_t rows_per_thread,
+                                                        const uint64_t* __restrict__ flags,
+                                                        const uint32_t* __restrict__ chunk_left,
+                                                        int32_t* __restrict__ out,
+                                                        int64_t* __restrict__ n_left_out) {
   __shared__ int64_t s_before[kPartWaves], s_total[kPartWaves];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int32_t chunk = blockIdx.x;
-  // left rows in the chunks before this one, and in the whole leaf
+  // left rows in the chunks before this one, and in the whole list
   int64_t before = 0, total = 0;
   for (int32_t c = tid; c < n_chunks; c += kPartThreads) {
     const int64_t v = chunk_left[c];
@@ -185,6 +188,92 @@ partition_scatter_kernel(const int32_t* __restrict__ idx, int64_t n_leaf, int32_
       out[left ? lefts_before_e : total + (e - lefts_before_e)] = r;
     }
   }
+}
+
+__global__ void __launch_bounds__(kPartThreads)
+partition_flag_kernel(const uint8_t* __restrict__ packed, int64_t n_rows, int32_t n_features,
+                      TilePlan plan, const int32_t* __restrict__ idx, int64_t n_leaf,
+                      const gbdt_split_t* __restrict__ split, int32_t rows_per_thread,
+                      uint64_t* __restrict__ flags, uint32_t* __restrict__ chunk_left) {
+  const SplitColumn sc = split_column(split, plan, n_rows, n_features);
+  partition_flag_chunk(sc, packed, n_rows, idx, n_leaf, (int32_t)blockIdx.x, rows_per_thread,
+                       flags + (size_t)blockIdx.x * rows_per_thread * kPartWaves, chunk_left + blockIdx.x);
+}
+
+__global__ void __launch_bounds__(kPartThreads)
+partition_scatter_kernel(const int32_t* __restrict__ idx, int64_t n_leaf, int32_t rows_per_thread,
+                         const uint64_t* __restrict__ flags, const uint32_t* __restrict__ chunk_left,
+                         int32_t n_chunks, int32_t* __restrict__ out, int64_t* __restrict__ n_left_out) {
+  partition_scatter_chunk(idx, n_leaf, (int32_t)blockIdx.x, n_chunks, rows_per_thread, flags, chunk_left, out,
+                          n_left_out);
+}
+
+// Several leaves per launch (a level of a tree): leaf l of the launch owns the row list
+// idx[row_off .. row_off + n), the split record split[l], chunks first_chunk .. of the
+// launch's flag / count arrays, and writes its children to out[row_off .. row_off + n).
+// The table travels as kernel arguments.
+constexpr int kPartBatchLeaves = 256;
+struct PartLeaf {
+  uint32_t row_off, n, first_chunk;
+};
+struct PartBatchArgs {
+  const uint8_t* packed;
+  const int32_t* idx;
+  const gbdt_split_t* split;
+  int32_t* out;
+  int64_t* n_left_out;  // [n_leaves] or NULL
+  uint64_t* flags;
+  uint32_t* chunk_left;
+  int64_t n_rows;
+  TilePlan plan;
+  int32_t n_features;
+  int32_t rows_per_thread;
+  int32_t n_leaves;
+  uint32_t n_chunks;  // of the whole launch
+  PartLeaf leaf[kPartBatchLeaves];
+};
+
+// the leaf that owns chunk `b` of the launch (leaves without rows own no chunk)
+__device__ __forceinline__ int32_t part_leaf_of(const PartLeaf* leaf, int32_t n_leaves, uint32_t b) {
+  int32_t lo = 0, hi = n_leaves - 1;
+  while (lo < hi) {
+    const int32_t mid = (lo + hi + 1) >> 1;
+    if (leaf[mid].first_chunk <= b) {
+      lo = mid;
+    } else {
+      hi = mid - 1;
+    }
+  }
+  return lo;
+}
+
+__global__ void __launch_bounds__(kPartThreads) partition_flag_batch_kernel(PartBatchArgs a) {
+  const int32_t l = part_leaf_of(a.leaf, a.n_leaves, blockIdx.x);
+  const PartLeaf lf = a.leaf[l];
+  const SplitColumn sc = split_column(a.split + l, a.plan, a.n_rows, a.n_features);
+  partition_flag_chunk(sc, a.packed, a.n_rows, a.idx + lf.row_off, lf.n, (int32_t)(blockIdx.x - lf.first_chunk),
+                       a.rows_per_thread, a.flags + (size_t)blockIdx.x * a.rows_per_thread * kPartWaves,
+                       a.chunk_left + blockIdx.x);
+}
+
+__global__ void __launch_bounds__(kPartThreads) partition_scatter_batch_kernel(PartBatchArgs a) {
+  const int32_t l = part_leaf_of(a.leaf, a.n_leaves, blockIdx.x);
+  const PartLeaf lf = a.leaf[l];
+  const uint32_t next_first = l + 1 < a.n_leaves ? a.leaf[l + 1].first_chunk : a.n_chunks;
+  // (a later leaf without rows shares its first chunk with the next one: this leaf's
+  // chunks end where the next leaf WITH rows begins, which is what first_chunk gives)
+  partition_scatter_chunk(a.idx + lf.row_off, lf.n, (int32_t)(blockIdx.x - lf.first_chunk),
+                          (int32_t)(next_first - lf.first_chunk), a.rows_per_thread,
+                          a.flags + (size_t)lf.first_chunk * a.rows_per_thread * kPartWaves,
+                          a.chunk_left + lf.first_chunk, a.out + lf.row_off,
+                          a.n_left_out ? a.n_left_out + l : nullptr);
+}
+
+// n_left_out[l] = 0 for the leaves of a batched partition that have no rows (they own no
+// chunk, so no workgroup of the scatter pass writes their count).
+__global__ void __launch_bounds__(256) partition_empty_counts_kernel(PartBatchArgs a) {
+  const int32_t l = blockIdx.x * blockDim.x + threadIdx.x;
+  if (l < a.n_leaves && a.leaf[l].n == 0 && a.n_left_out) a.n_left_out[l] = 0;
 }
 
 // A leaf of at most kPartThreads * kPartOneSteps rows: both passes in one workgroup, the

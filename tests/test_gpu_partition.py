@@ -258,3 +258,44 @@ print("checked ok")
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     res = subprocess.run([sys.executable, "-c", code], cwd=root, env=env, capture_output=True, text=True, timeout=180)
     assert res.returncode == 0 and "checked ok" in res.stdout, res.stdout + res.stderr
+
+
+@pytest.mark.parametrize("shape", [(20_011, 150, 32, 7), (9_001, 28, 255, 300), (2_500, 129, 16, 40),
+                                   (400_000, 70, 64, 5)])
+def test_partition_batch_equals_oracle_leaf_by_leaf(shape):
+    """A level of a tree in one call: every leaf's segment of children_out must be the oracle's
+    partition of that leaf by that leaf's own split record (empty leaves, records without a
+    split, tiny and multi-chunk leaves, more leaves than one launch holds)."""
+    n_rows, n_features, n_bins, n_leaves = shape
+    _say(f"partition batch {n_rows}x{n_features} bins={n_bins} leaves={n_leaves}")
+    rng = np.random.default_rng(n_rows + n_leaves)
+    bins = rng.integers(0, n_bins, size=(n_rows, n_features), dtype=np.uint8)
+    zeros = np.zeros(n_rows, np.float32)
+    p = GpuProblem(bins, n_bins, zeros, zeros)
+    perm = rng.permutation(n_rows).astype(np.int32)
+    cuts = np.sort(rng.choice(n_rows, size=n_leaves - 1, replace=False))
+    lists = [np.sort(x) for x in np.split(perm, cuts)]
+    lists[1] = np.zeros(0, np.int32) if n_leaves > 2 else lists[1]          # an empty leaf
+    offs = np.concatenate([[3], 3 + np.cumsum([len(l) for l in lists])]).astype(np.int64)
+    cat = np.concatenate([np.full(3, -1, np.int32)] + lists + [np.full(5, -1, np.int32)])
+    feats = rng.integers(0, n_features, size=n_leaves)
+    thrs = rng.integers(0, n_bins - 1, size=n_leaves)
+    feats[0] = -1                                                            # "no split": all rows stay left
+    recs = np.zeros(n_leaves, dtype=B.SPLIT_DTYPE)
+    recs["feature"], recs["bin"] = feats, thrs
+    recs_d = torch.from_numpy(recs.view(np.int32).reshape(n_leaves, 9).copy()).to(p.dev)
+    out = torch.full((cat.size,), -7, dtype=torch.int32, device=p.dev)
+    n_left = torch.full((n_leaves,), -1, dtype=torch.int64, device=p.dev)
+    B.gbdt_partition_rows_batch(p.packed, n_rows, n_features, n_bins, torch.from_numpy(cat).to(p.dev), offs,
+                                recs_d, out, n_left)
+    torch.cuda.synchronize()
+    o, nl = out.cpu().numpy(), n_left.cpu().numpy()
+    assert (o[:3] == -7).all() and (o[offs[-1]:] == -7).all()              # nothing outside the lists
+    for l, rows in enumerate(lists):
+        seg = o[offs[l]:offs[l + 1]]
+        if feats[l] < 0:
+            assert nl[l] == rows.size and np.array_equal(seg, rows), l
+            continue
+        ref_l, ref_r = orc.partition_rows(bins, int(feats[l]), int(thrs[l]), rows)
+        assert nl[l] == ref_l.size, (l, nl[l], ref_l.size)
+        assert np.array_equal(seg[:ref_l.size], ref_l) and np.array_equal(seg[ref_l.size:], ref_r), l
