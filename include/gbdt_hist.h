@@ -314,6 +314,28 @@ size_t gbdt_grow_tree_scratch_bytes(int64_t n_rows, int32_t n_features, int32_t 
                                     int32_t max_leaves);
 
 /*
+ * The same tree, grown level by level to a maximum depth instead of leaf by leaf to a
+ * number of leaves (Sec. 5 runs its comparison trainers with a maximum depth of 8): every
+ * node of the current level whose best split is admissible and gains more than
+ * min_split_gain is split.  A whole level costs a handful of launches whatever its width:
+ * one batched split search and one read-back of the level's records, one batched
+ * partition, one batched histogram build of all the smaller children, one subtraction
+ * kernel for their siblings.  Nodes are numbered level by level, the children of a level
+ * in the order of their parents, left first (parents precede children).
+ *   max_depth        0 .. 16; at most 2^max_depth leaves
+ *   scratch          DEVICE, 256-byte aligned, gbdt_grow_tree_depthwise_scratch_bytes(...)
+ *   nodes_out        HOST gbdt_tree_node_t [2^(max_depth + 1) - 1]
+ *   other arguments, waiting and allocation as for gbdt_grow_tree (one wait per level).
+ */
+int gbdt_grow_tree_depthwise(const void* bin_matrix, int64_t n_rows, int32_t n_features,
+                             int32_t n_bins, const float* grad, const float* hess, int32_t max_depth,
+                             float lambda, float min_child_hess, float min_split_gain, void* scratch,
+                             size_t scratch_bytes, gbdt_tree_node_t* nodes_out, int32_t* n_nodes_out,
+                             int32_t* row_order_out, void* stream);
+size_t gbdt_grow_tree_depthwise_scratch_bytes(int64_t n_rows, int32_t n_features, int32_t n_bins,
+                                              int32_t max_depth);
+
+/*
  * Scratch workspace.  By default the library allocates device scratch itself
  * on first use and grows it when a larger problem arrives (hipMalloc inside
  * gbdt_hist_build / gbdt_best_split / gbdt_partition_rows).  A caller that wants no allocation in

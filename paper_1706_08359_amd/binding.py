@@ -25,7 +25,7 @@ EXPORTS = [
     "gbdt_calibration_copy", "gbdt_set_deterministic", "gbdt_partition_rows",
     "gbdt_hist_build_batch", "gbdt_hist_build_batch_workspace_bytes", "gbdt_best_split_batch",
     "gbdt_debug_batch_plan", "gbdt_grow_tree", "gbdt_grow_tree_scratch_bytes",
-    "gbdt_partition_rows_batch",
+    "gbdt_partition_rows_batch", "gbdt_grow_tree_depthwise", "gbdt_grow_tree_depthwise_scratch_bytes",
 ]
 
 # numpy views of the two C structs
@@ -85,6 +85,10 @@ def load():
     lib.gbdt_grow_tree.argtypes = [c.c_void_p, c.c_int64, c.c_int32, c.c_int32, c.c_void_p, c.c_void_p,
                                    c.c_int32, c.c_float, c.c_float, c.c_float, c.c_void_p, c.c_size_t,
                                    c.c_void_p, c.POINTER(c.c_int32), c.c_void_p, c.c_void_p]
+    lib.gbdt_grow_tree_depthwise.restype = c.c_int
+    lib.gbdt_grow_tree_depthwise.argtypes = lib.gbdt_grow_tree.argtypes
+    lib.gbdt_grow_tree_depthwise_scratch_bytes.restype = c.c_size_t
+    lib.gbdt_grow_tree_depthwise_scratch_bytes.argtypes = [c.c_int64, c.c_int32, c.c_int32, c.c_int32]
     lib.gbdt_grow_tree_scratch_bytes.restype = c.c_size_t
     lib.gbdt_grow_tree_scratch_bytes.argtypes = [c.c_int64, c.c_int32, c.c_int32, c.c_int32]
     lib.gbdt_partition_rows.restype = c.c_int
@@ -352,6 +356,34 @@ def gbdt_grow_tree(bin_matrix, n_rows, n_features, n_bins, grad, hess, max_leave
                                  nodes.ctypes.data, ctypes.byref(n_nodes),
                                  None if row_order_out is None else _dev(row_order_out, torch.int32, "row_order_out"),
                                  _stream(stream)), "gbdt_grow_tree")
+    return nodes[:n_nodes.value], row_order_out, scratch
+
+
+def gbdt_grow_tree_depthwise(bin_matrix, n_rows, n_features, n_bins, grad, hess, max_depth, lam,
+                             min_child_hess, min_split_gain=0.0, scratch=None, row_order_out=None,
+                             want_rows=True, stream=None):
+    """Level-wise growth to max_depth.  Returns (nodes, row_order_out, scratch) as gbdt_grow_tree."""
+    lib = load()
+    need = int(lib.gbdt_grow_tree_depthwise_scratch_bytes(n_rows, n_features, n_bins, max_depth))
+    if need == 0:
+        raise GbdtError("gbdt_grow_tree_depthwise_scratch_bytes: invalid argument")
+    if scratch is None or scratch.numel() < need:
+        scratch = torch.empty(need, dtype=torch.uint8, device=grad.device)
+    if grad.numel() < n_rows or hess.numel() < n_rows:
+        raise GbdtError("grad/hess shorter than n_rows")
+    if bin_matrix.numel() < gbdt_bins_packed_bytes(n_rows, n_features, n_bins):
+        raise GbdtError("bin_matrix smaller than the packed layout of this shape")
+    if want_rows and row_order_out is None:
+        row_order_out = torch.empty(max(n_rows, 1), dtype=torch.int32, device=grad.device)
+    nodes = np.zeros(2 ** (max_depth + 1) - 1, dtype=NODE_DTYPE)
+    n_nodes = ctypes.c_int32(0)
+    _check(lib.gbdt_grow_tree_depthwise(_dev(bin_matrix, torch.uint8, "bin_matrix"), n_rows, n_features, n_bins,
+                                        _dev(grad, torch.float32, "grad"), _dev(hess, torch.float32, "hess"),
+                                        max_depth, float(lam), float(min_child_hess), float(min_split_gain),
+                                        _dev(scratch, torch.uint8, "scratch"), scratch.numel(),
+                                        nodes.ctypes.data, ctypes.byref(n_nodes),
+                                        None if row_order_out is None else _dev(row_order_out, torch.int32, "row_order_out"),
+                                        _stream(stream)), "gbdt_grow_tree_depthwise")
     return nodes[:n_nodes.value], row_order_out, scratch
 
 

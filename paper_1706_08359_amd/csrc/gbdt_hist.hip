@@ -479,6 +479,51 @@ gbdt_split_t* pinned_records() {
 }
 
 
+// Scratch of gbdt_grow_tree_depthwise: two row buffers, the smaller children's rows, two
+// levels of histograms, the split records of a level and the records its partition uses.
+constexpr int kMaxTreeDepth = 16;
+struct LevelScratch {
+  size_t rows_a, rows_b, rows_small, hists_a, hists_b, recs, part_recs, total;
+};
+
+LevelScratch level_scratch_layout(int64_t n_rows, int32_t n_features, int32_t n_bins, int32_t max_depth) {
+  LevelScratch t;
+  const size_t rows = align256((size_t)(n_rows > 0 ? n_rows : 1) * sizeof(int32_t));
+  const size_t width = (size_t)1 << max_depth;
+  const size_t hists = align256(width * n_features * n_bins * sizeof(gbdt_bin_t));
+  const size_t recs = align256(width * sizeof(gbdt_split_t));
+  t.rows_a = 0;
+  t.rows_b = rows;
+  t.rows_small = 2 * rows;
+  t.hists_a = 3 * rows;
+  t.hists_b = t.hists_a + hists;
+  t.recs = t.hists_b + hists;
+  t.part_recs = t.recs + recs;
+  t.total = t.part_recs + recs;
+  return t;
+}
+
+// Page-locked host memory for the split records of a level (grows, never freed).
+gbdt_split_t* pinned_level_records(size_t n) {
+  static gbdt_split_t* p = nullptr;
+  static size_t cap = 0;
+  static std::mutex mu;
+  std::lock_guard<std::mutex> lk(mu);
+  if (cap < n) {
+    if (p) (void)hipHostFree(p);
+    p = nullptr;
+    cap = 0;
+    void* q = nullptr;
+    if (hipHostMalloc(&q, n * sizeof(gbdt_split_t), hipHostMallocDefault) != hipSuccess) {
+      (void)hipGetLastError();
+      return nullptr;
+    }
+    p = (gbdt_split_t*)q;
+    cap = n;
+  }
+  return p;
+}
+
 }  // namespace
 
 // ----------------------------------------------------------------------- C ABI
@@ -1103,6 +1148,216 @@ int gbdt_grow_tree(const void* bin_matrix, int64_t n_rows, int32_t n_features, i
       }
     }
   }
+  return GBDT_OK;
+}
+
+// --- level-wise tree growth ------------------------------------------------------------
+
+size_t gbdt_grow_tree_depthwise_scratch_bytes(int64_t n_rows, int32_t n_features, int32_t n_bins,
+                                              int32_t max_depth) {
+  if (!valid_shape(n_rows, n_features, n_bins) || max_depth < 0 || max_depth > kMaxTreeDepth) return 0;
+  return level_scratch_layout(n_rows, n_features, n_bins, max_depth).total;
+}
+
+int gbdt_grow_tree_depthwise(const void* bin_matrix, int64_t n_rows, int32_t n_features,
+                             int32_t n_bins, const float* grad, const float* hess, int32_t max_depth,
+                             float lambda, float min_child_hess, float min_split_gain, void* scratch,
+                             size_t scratch_bytes, gbdt_tree_node_t* nodes_out, int32_t* n_nodes_out,
+                             int32_t* row_order_out, void* stream) {
+  if (!valid_shape(n_rows, n_features, n_bins)) return GBDT_EINVAL;
+  if (max_depth < 0 || max_depth > kMaxTreeDepth || !nodes_out || !n_nodes_out || !scratch) return GBDT_EINVAL;
+  if (!(lambda >= 0.0f) || min_split_gain != min_split_gain) return GBDT_EINVAL;
+  if (n_rows > 0 && (!bin_matrix || !grad || !hess)) return GBDT_EINVAL;
+  if (((uintptr_t)scratch & 255u) != 0) return GBDT_EINVAL;
+  if (n_rows >= ((int64_t)1 << 30)) return GBDT_EUNSUPPORTED;
+  const LevelScratch lay = level_scratch_layout(n_rows, n_features, n_bins, max_depth);
+  if (scratch_bytes < lay.total) return GBDT_ENOMEM;
+  const size_t width = (size_t)1 << max_depth;  // most nodes a level can hold
+  gbdt_split_t* pinned = pinned_level_records(2 * width);
+  if (!pinned) return GBDT_ENOMEM;
+  gbdt_split_t* pinned_part = pinned + width;  // records the partition of a level is driven by
+  hipStream_t s = (hipStream_t)stream;
+  char* base = (char*)scratch;
+  int32_t* rows_buf[2] = {(int32_t*)(base + lay.rows_a), (int32_t*)(base + lay.rows_b)};
+  int32_t* small_rows = (int32_t*)(base + lay.rows_small);
+  gbdt_bin_t* hist_buf[2] = {(gbdt_bin_t*)(base + lay.hists_a), (gbdt_bin_t*)(base + lay.hists_b)};
+  gbdt_split_t* recs = (gbdt_split_t*)(base + lay.recs);
+  gbdt_split_t* part_recs = (gbdt_split_t*)(base + lay.part_recs);
+  const size_t hist_elems = (size_t)n_features * n_bins;
+
+  auto fill_node = [&](int k, int parent, const gbdt_split_t& r, float sg, float sh, uint32_t cnt,
+                       int64_t begin) {
+    gbdt_tree_node_t& nd = nodes_out[k];
+    nd.parent = parent;
+    nd.left = nd.right = -1;
+    nd.feature = r.feature;
+    nd.bin = r.bin;
+    nd.gain = r.gain;
+    nd.sum_grad = sg;
+    nd.sum_hess = sh;
+    nd.count = cnt;
+    nd.reserved = 0;
+    nd.row_begin = begin;
+  };
+
+  // root: its histogram without an index list; the row list 0..n-1 for the first partition
+  int cur = 0;  // row buffer and histogram buffer of the current level
+  int rc = gbdt_hist_build(bin_matrix, n_rows, n_features, n_bins, nullptr, n_rows, grad, hess, hist_buf[cur], s);
+  if (rc != GBDT_OK) return rc;
+  if (n_rows > 0) {
+    hipLaunchKernelGGL(row_iota_kernel, dim3((unsigned)((n_rows + 255) / 256)), dim3(256), 0, s, rows_buf[cur],
+                       n_rows);
+    HIP_TRY(hipGetLastError());
+  }
+  // the level: its nodes in position order with their histogram slots; `frontier` also holds
+  // the finished leaves, whose rows every later partition copies through unchanged
+  struct Entry {
+    int node;   // node id
+    int slot;   // histogram slot in hist_buf[cur]; -1: a finished leaf
+  };
+  std::vector<Entry> frontier = {{0, 0}};
+  int n_nodes = 1;
+  bool root_done = false;
+  for (int depth = 0;; ++depth) {
+    // ---- best split of every open node of the level, one launch, one read-back
+    std::vector<int> open;  // indices into frontier, in histogram slot order
+    for (size_t i = 0; i < frontier.size(); ++i)
+      if (frontier[i].slot >= 0) open.push_back((int)i);
+    std::sort(open.begin(), open.end(), [&](int a, int b) { return frontier[a].slot < frontier[b].slot; });
+    const int n_open = (int)open.size();
+    if (n_open == 0) break;
+    rc = gbdt_best_split_batch(hist_buf[cur], n_open, lambda, min_child_hess, recs, n_features, n_bins, s);
+    if (rc != GBDT_OK) return rc;
+    HIP_TRY(hipMemcpyAsync(pinned, recs, (size_t)n_open * sizeof(gbdt_split_t), hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    if (!root_done) {
+      const gbdt_split_t r = pinned[0];
+      float sg = r.left_grad + r.right_grad, sh = r.left_hess + r.right_hess;
+      if (r.feature < 0 && n_rows > 0) {  // no record carries the totals: sum feature 0's bins here
+        std::vector<gbdt_bin_t> row((size_t)n_bins);
+        HIP_TRY(hipMemcpyAsync(row.data(), hist_buf[cur], (size_t)n_bins * sizeof(gbdt_bin_t),
+                               hipMemcpyDeviceToHost, s));
+        HIP_TRY(hipStreamSynchronize(s));
+        double g = 0.0, h = 0.0;
+        for (const gbdt_bin_t& b : row) {
+          g += b.grad;
+          h += b.hess;
+        }
+        sg = (float)g;
+        sh = (float)h;
+      }
+      fill_node(0, -1, r, sg, sh, (uint32_t)n_rows, 0);
+      root_done = true;
+    }
+    // the records of the level's nodes (slot order = order of `open`)
+    std::vector<gbdt_split_t> rec_of(frontier.size());
+    for (int j = 0; j < n_open; ++j) {
+      const gbdt_split_t& r = pinned[frontier[open[j]].slot];
+      rec_of[open[j]] = r;
+      gbdt_tree_node_t& nd = nodes_out[frontier[open[j]].node];
+      nd.feature = r.feature;
+      nd.bin = r.bin;
+      nd.gain = r.gain;
+    }
+    if (depth == max_depth) break;
+    // ---- which nodes split; the partition records of ALL entries (others: no split)
+    std::vector<Entry> next;
+    std::vector<int64_t> offs;          // positions of the entries of this level
+    std::vector<int> splitting;         // indices into frontier
+    for (size_t i = 0; i < frontier.size(); ++i) {
+      const gbdt_tree_node_t& nd = nodes_out[frontier[i].node];
+      offs.push_back(nd.row_begin);
+      gbdt_split_t pr;
+      memset(&pr, 0, sizeof pr);
+      pr.feature = pr.bin = -1;
+      if (frontier[i].slot >= 0 && rec_of[i].feature >= 0 && rec_of[i].gain > min_split_gain) {
+        pr = rec_of[i];
+        splitting.push_back((int)i);
+      }
+      pinned_part[i] = pr;
+    }
+    offs.push_back(n_rows);
+    if (splitting.empty()) break;
+    HIP_TRY(hipMemcpyAsync(part_recs, pinned_part, frontier.size() * sizeof(gbdt_split_t),
+                           hipMemcpyHostToDevice, s));
+    const int nxt = cur ^ 1;
+    rc = gbdt_partition_rows_batch(bin_matrix, n_rows, n_features, n_bins, rows_buf[cur], offs.data(),
+                                   (int32_t)frontier.size(), part_recs, rows_buf[nxt], nullptr, s);
+    if (rc != GBDT_OK) return rc;
+    // ---- children: node ids in the order of their parents' ids (the level's numbering),
+    // histogram slots: the smaller children first (built), then the larger (by subtraction)
+    std::vector<int> by_node = splitting;
+    std::sort(by_node.begin(), by_node.end(), [&](int a, int b) { return frontier[a].node < frontier[b].node; });
+    const int k = (int)by_node.size();
+    std::vector<int64_t> small_offs = {0};
+    std::vector<int> parent_slot((size_t)k);
+    std::vector<std::pair<uint32_t, uint32_t>> small_seg((size_t)k);  // (begin in the row buffer, length)
+    std::vector<std::pair<Entry, Entry>> kids(frontier.size());
+    for (int j = 0; j < k; ++j) {
+      const int i = by_node[j];
+      const int parent = frontier[i].node;
+      const gbdt_split_t& r = rec_of[i];
+      const int64_t begin = nodes_out[parent].row_begin;
+      const int left = n_nodes, right = n_nodes + 1;
+      n_nodes += 2;
+      nodes_out[parent].left = left;
+      nodes_out[parent].right = right;
+      gbdt_split_t none;
+      memset(&none, 0, sizeof none);
+      none.feature = none.bin = -1;
+      fill_node(left, parent, none, r.left_grad, r.left_hess, r.left_count, begin);
+      fill_node(right, parent, none, r.right_grad, r.right_hess, r.right_count, begin + r.left_count);
+      const bool left_small = r.left_count <= r.right_count;
+      small_seg[j] = left_small ? std::make_pair((uint32_t)begin, r.left_count)
+                                : std::make_pair((uint32_t)(begin + r.left_count), r.right_count);
+      small_offs.push_back(small_offs.back() + small_seg[j].second);
+      parent_slot[j] = frontier[i].slot;
+      kids[i] = left_small ? std::make_pair(Entry{left, j}, Entry{right, k + j})
+                           : std::make_pair(Entry{left, k + j}, Entry{right, j});
+    }
+    for (size_t i = 0; i < frontier.size(); ++i) {
+      if (nodes_out[frontier[i].node].left >= 0) {
+        next.push_back(kids[i].first);
+        next.push_back(kids[i].second);
+      } else {
+        next.push_back(Entry{frontier[i].node, -1});  // a leaf from now on
+      }
+    }
+    // ---- the smaller children's rows back to back, their histograms in one batched build
+    for (int j0 = 0; j0 < k; j0 += kCompactSegs) {
+      CompactTable t;
+      const int ns = k - j0 < kCompactSegs ? k - j0 : kCompactSegs;
+      for (int j = 0; j < ns; ++j) {
+        t.src_begin[j] = small_seg[j0 + j].first;
+        t.dst_begin[j] = (uint32_t)small_offs[j0 + j];
+      }
+      t.dst_begin[ns] = (uint32_t)small_offs[j0 + ns];
+      t.n_seg = ns;
+      const uint32_t span = t.dst_begin[ns] - t.dst_begin[0];
+      if (span == 0) continue;
+      hipLaunchKernelGGL(segments_compact_kernel, dim3((span + 255) / 256), dim3(256), 0, s,
+                         (const int32_t*)rows_buf[nxt], t, small_rows);
+      HIP_TRY(hipGetLastError());
+    }
+    rc = gbdt_hist_build_batch(bin_matrix, n_rows, n_features, n_bins, small_rows, small_offs.data(), k, grad,
+                               hess, hist_buf[nxt], s);
+    if (rc != GBDT_OK) return rc;
+    for (int j0 = 0; j0 < k; j0 += kSiblingTable) {
+      SiblingTable t;
+      const int ns = k - j0 < kSiblingTable ? k - j0 : kSiblingTable;
+      for (int j = 0; j < ns; ++j) t.parent_slot[j] = parent_slot[j0 + j];
+      hipLaunchKernelGGL(hist_siblings_kernel, dim3((unsigned)((hist_elems + 255) / 256), ns), dim3(256), 0, s,
+                         (const gbdt_bin_t*)hist_buf[cur], (const gbdt_bin_t*)(hist_buf[nxt] + (size_t)j0 * hist_elems),
+                         hist_buf[nxt] + (size_t)(k + j0) * hist_elems, (int32_t)hist_elems, t);
+      HIP_TRY(hipGetLastError());
+    }
+    frontier.swap(next);
+    cur = nxt;
+  }
+  *n_nodes_out = n_nodes;
+  if (row_order_out && n_rows > 0)
+    HIP_TRY(hipMemcpyAsync(row_order_out, rows_buf[cur], (size_t)n_rows * sizeof(int32_t),
+                           hipMemcpyDeviceToDevice, s));
   return GBDT_OK;
 }
 

@@ -157,6 +157,28 @@ hist_subtract_kernel(const gbdt_bin_t* parent, const gbdt_bin_t* child, gbdt_bin
   sibling[e] = s;
 }
 
+// Siblings of a tree level: large[j] = parent[parent_slot[j]] - small[j], histograms of n
+// (bin, feature) elements; grid.y = j.  The slots travel as kernel arguments.
+constexpr int kSiblingTable = 960;
+struct SiblingTable {
+  int32_t parent_slot[kSiblingTable];
+};
+
+__global__ void __launch_bounds__(256)
+hist_siblings_kernel(const gbdt_bin_t* __restrict__ parents, const gbdt_bin_t* __restrict__ small,
+                     gbdt_bin_t* __restrict__ large, int32_t n, SiblingTable t) {
+  const int32_t e = blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= n) return;
+  const size_t j = blockIdx.y;
+  const gbdt_bin_t p = parents[(size_t)t.parent_slot[j] * n + e];
+  const gbdt_bin_t c = small[j * n + e];
+  gbdt_bin_t s;
+  s.grad = p.grad - c.grad;
+  s.hess = p.hess - c.hess;
+  s.count = p.count - c.count;
+  large[j * n + e] = s;
+}
+
 // Histogram of an empty leaf: all zero.  (A fill kernel, not a memset node, so the
 // call can be captured into a graph.)
 __global__ void __launch_bounds__(256) hist_zero_kernel(gbdt_bin_t* hist, int32_t n) {

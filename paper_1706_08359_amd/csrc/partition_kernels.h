@@ -320,6 +320,33 @@ partition_one_kernel(const uint8_t* __restrict__ packed, int64_t n_rows, int32_t
   }
 }
 
+// Copies up to kCompactSegs segments of a row buffer back to back into another list:
+// segment j = src[src_begin[j] .. src_begin[j] + len_j) goes to dst[dst_begin[j] ..), the
+// dst_begin ascending with dst_begin[n_seg] = total.  (The smaller children of a tree
+// level, gathered for one batched histogram build.)
+constexpr int kCompactSegs = 448;
+struct CompactTable {
+  uint32_t src_begin[kCompactSegs];
+  uint32_t dst_begin[kCompactSegs + 1];
+  int32_t n_seg;
+};
+
+__global__ void __launch_bounds__(256)
+segments_compact_kernel(const int32_t* __restrict__ src, CompactTable t, int32_t* __restrict__ dst) {
+  const uint32_t i = t.dst_begin[0] + blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= t.dst_begin[t.n_seg]) return;
+  int32_t lo = 0, hi = t.n_seg - 1;  // last segment that starts at or before i
+  while (lo < hi) {
+    const int32_t mid = (lo + hi + 1) >> 1;
+    if (t.dst_begin[mid] <= i) {
+      lo = mid;
+    } else {
+      hi = mid - 1;
+    }
+  }
+  dst[i] = src[t.src_begin[lo] + (i - t.dst_begin[lo])];
+}
+
 // Debug aid: counts the entries of a row list that are not row ids of the matrix.
 __global__ void __launch_bounds__(256)
 row_ids_check_kernel(const int32_t* __restrict__ idx, int64_t n, int64_t n_rows,

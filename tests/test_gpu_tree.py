@@ -224,3 +224,130 @@ def test_grow_tree_255_leaves_on_two_million_rows():
     _check_structure(nodes, order, bins)
     _, _, near = _replay(nodes, bins, nb, grad, hess, 1.0, 1e-3)
     _say(f"  255 leaves, {near} near-tie decisions")
+
+
+# ------------------------------------------------------------------ level-wise growth
+
+def _replay_depthwise(nodes, bins, n_bins, grad, hess, lam, mch, max_depth, min_gain=0.0):
+    """Every node of the device tree against the oracle on the node's own rows: the split chosen
+    (or a near-tie), the rule "every splittable node above max_depth is split", the children's
+    rows, counts and sums.  Returns the number of near-tie decisions."""
+    g64, h64 = grad.astype(np.float64), hess.astype(np.float64)
+    rows = {0: np.arange(bins.shape[0], dtype=np.int32)}
+    budget = {0: (np.abs(g64).sum(), np.abs(h64).sum())}
+    depth = {0: 0}
+    near = 0
+    for k, nd in enumerate(nodes):                      # parents precede children
+        s_ref, gains = orc.best_split(orc.hist_build(bins, n_bins, grad, hess, rows[k]), lam, mch, return_gains=True)
+        scale = max(1.0, abs(s_ref["gain"]))
+        if nd["left"] < 0:
+            # a leaf: at the depth limit, or nothing (worth) splitting
+            assert depth[k] == max_depth or s_ref["feature"] < 0 or s_ref["gain"] <= min_gain + BAND * scale, k
+            if s_ref["feature"] < 0:
+                assert nd["feature"] == -1
+            continue
+        assert depth[k] < max_depth
+        assert s_ref["feature"] >= 0, k
+        g_at = gains[nd["feature"], nd["bin"]]
+        assert np.isfinite(g_at), k
+        if (nd["feature"], nd["bin"]) != (s_ref["feature"], s_ref["bin"]):
+            assert s_ref["gain"] - g_at <= BAND * scale, (k, nd, s_ref)
+            near += 1
+        assert abs(nd["gain"] - g_at) <= BAND * scale
+        left, right = orc.partition_rows(bins, nd["feature"], nd["bin"], rows[k])
+        small_is_left = left.size <= right.size
+        small = left if small_is_left else right
+        b_small = (np.abs(g64[small]).sum(), np.abs(h64[small]).sum())
+        b_large = (budget[k][0] + b_small[0], budget[k][1] + b_small[1])
+        for side, kid, r in (("left", int(nd["left"]), left), ("right", int(nd["right"]), right)):
+            c = nodes[kid]
+            assert c["count"] == r.size and c["parent"] == k
+            assert abs(c["sum_grad"] - g64[r].sum()) <= REL_TOL * budget[k][0] + 1e-6 * abs(g64[r].sum())
+            assert abs(c["sum_hess"] - h64[r].sum()) <= REL_TOL * budget[k][1] + 1e-6 * abs(h64[r].sum())
+            rows[kid], depth[kid] = r, depth[k] + 1
+            budget[kid] = b_small if (side == "left") == small_is_left else b_large
+    return near
+
+
+@pytest.mark.parametrize("shape", [(60_000, 28, 255, 6), (40_000, 70, 16, 5), (30_000, 100, 64, 5),
+                                   (3_000, 9, 33, 9)])
+def test_depthwise_tree_replayed_with_the_oracle(shape):
+    n, F, nb, max_depth = shape
+    _say(f"grow_tree_depthwise {n}x{F} bins={nb} depth={max_depth}")
+    bins, grad, hess = _planted(n, F, nb, n + F + 3)
+    p = GpuProblem(bins, nb, grad, hess)
+    lam, mch = 1.0, 1e-3
+    nodes, order, _ = B.gbdt_grow_tree_depthwise(p.packed, n, F, nb, p.grad, p.hess, max_depth, lam, mch)
+    torch.cuda.synchronize()
+    _check_structure(nodes, order.cpu().numpy()[:n], bins)
+    # numbered level by level, children of a level in the order of their parents
+    parents = [k for k in range(len(nodes)) if nodes[k]["left"] >= 0]
+    assert [int(nodes[k]["left"]) for k in parents] == sorted(int(nodes[k]["left"]) for k in parents)
+    near = _replay_depthwise(nodes, bins, nb, grad, hess, lam, mch, max_depth)
+    _say(f"  {len(nodes)} nodes, {near} near-tie decisions")
+
+
+def test_depthwise_tree_equals_the_oracles_tree_on_separated_gains():
+    rng = np.random.default_rng(6)
+    n, F, nb = 20_000, 12, 32
+    bins = rng.integers(0, nb, size=(n, F), dtype=np.uint8)
+    y = (np.where(bins[:, 3] > 15, 8.0, -8.0) + np.where(bins[:, 7] > 9, 3.0, -3.0)
+         + np.where(bins[:, 0] > 20, 1.0, -1.0))
+    grad, hess = (-y).astype(np.float32), np.ones(n, np.float32)
+    p = GpuProblem(bins, nb, grad, hess)
+    nodes, order, _ = B.gbdt_grow_tree_depthwise(p.packed, n, F, nb, p.grad, p.hess, 3, 0.0, 1.0)
+    ref = tree_oracle.grow_tree_depthwise(bins, nb, grad, hess, 3, 0.0, 1.0)
+    assert len(nodes) == len(ref) == 15
+    order = order.cpu().numpy()
+    for k, (a, b) in enumerate(zip(nodes, ref)):
+        assert (a["left"], a["right"], a["parent"], a["count"]) == (b["left"], b["right"], b["parent"], b["count"]), k
+        assert (a["feature"], a["bin"]) == (b["split"]["feature"], b["split"]["bin"]), k
+        if b["left"] < 0:
+            assert np.array_equal(order[a["row_begin"]:a["row_begin"] + a["count"]], b["rows"])
+
+
+def test_depthwise_tree_edge_cases():
+    _say("grow_tree_depthwise edge cases")
+    rng = np.random.default_rng(9)
+    n, F, nb = 3000, 5, 16
+    bins = rng.integers(0, nb, size=(n, F), dtype=np.uint8)
+    grad = rng.normal(size=n).astype(np.float32)
+    hess = rng.uniform(0.1, 1, size=n).astype(np.float32)
+    p = GpuProblem(bins, nb, grad, hess)
+    nodes, order, scratch = B.gbdt_grow_tree_depthwise(p.packed, n, F, nb, p.grad, p.hess, 0, 1.0, 1e-3)
+    assert len(nodes) == 1 and nodes[0]["count"] == n and nodes[0]["feature"] >= 0      # depth 0: the root, with its split
+    assert np.array_equal(order.cpu().numpy(), np.arange(n))
+    nodes, order, _ = B.gbdt_grow_tree_depthwise(p.packed, n, F, nb, p.grad, p.hess, 4, 1.0, 1e-3, min_split_gain=1e12)
+    assert len(nodes) == 1
+    pz = GpuProblem(np.zeros((n, F), np.uint8), nb, grad, hess)
+    nodes, order, _ = B.gbdt_grow_tree_depthwise(pz.packed, n, F, nb, pz.grad, pz.hess, 4, 1.0, 1e-3)
+    assert len(nodes) == 1 and nodes[0]["feature"] == -1
+    assert abs(nodes[0]["sum_hess"] - hess.astype(np.float64).sum()) <= REL_TOL * np.abs(hess).sum()
+    tiny = GpuProblem(bins[:6], nb, grad[:6], hess[:6])
+    nodes, order, _ = B.gbdt_grow_tree_depthwise(tiny.packed, 6, F, nb, tiny.grad, tiny.hess, 8, 0.0, 0.0)
+    _check_structure(nodes, order.cpu().numpy()[:6], bins[:6])
+    assert int((nodes["left"] < 0).sum()) <= 6
+    with pytest.raises(B.GbdtError):
+        B.gbdt_grow_tree_depthwise(p.packed, n, F, nb, p.grad, p.hess, 17, 1.0, 1e-3)
+
+
+def test_depthwise_tree_depth_8_on_two_million_rows():
+    n, F, nb = 2_000_000, 28, 255
+    _say(f"grow_tree_depthwise {n}x{F} bins={nb} depth=8")
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(23)
+    bins_d = synth.uniform_bins(n, F, nb, gen, dev)
+    bins = bins_d.cpu().numpy()
+    rng = np.random.default_rng(24)
+    score = (bins[:, 2].astype(np.float32) / nb - 0.5) * 2 + (bins[:, 11] > 100) * 1.0 - (bins[:, 20] < 40) * 0.7
+    y = rng.random(n) < 1.0 / (1.0 + np.exp(-score))
+    prob = np.full(n, 0.5, np.float32)
+    grad, hess = (prob - y).astype(np.float32), (prob * (1 - prob)).astype(np.float32)
+    p = GpuProblem(bins_d, nb, grad, hess)
+    nodes, order, _ = B.gbdt_grow_tree_depthwise(p.packed, n, F, nb, p.grad, p.hess, 8, 1.0, 1e-3)
+    torch.cuda.synchronize()
+    assert len(nodes) == 511
+    _check_structure(nodes, order.cpu().numpy(), bins)
+    near = _replay_depthwise(nodes, bins, nb, grad, hess, 1.0, 1e-3, 8)
+    _say(f"  511 nodes, {near} near-tie decisions")
