@@ -234,11 +234,13 @@ def partition(args, torch, B, synth, dev):
 
 
 def tree(args, torch, B, synth, dev):
-    """Whole 255-leaf trees (the tree size of Sec. 5) grown by gbdt_grow_tree on every workload:
-    host wall time per tree, stream synchronised at both ends (median of 5 after a warm-up)."""
-    print("| workload | rows x features, bins | leaves reached | deepest leaf | wall ms / tree (median) | wall ms / tree (min) | "
-          "splits / s |")
-    print("|" + "---|" * 7, flush=True)
+    """Whole trees on every workload: 255 leaves grown leaf-wise by gbdt_grow_tree (the tree size of
+    Sec. 5) and depth 8 grown level-wise by gbdt_grow_tree_depthwise (the depth Sec. 5 gives the
+    comparison trainers).  Host wall time per tree, stream synchronised at both ends (median of 5
+    after a warm-up)."""
+    print("| workload | rows x features, bins | growth | leaves reached | deepest leaf | wall ms / tree (median) | "
+          "wall ms / tree (min) | splits / s |")
+    print("|" + "---|" * 8, flush=True)
     runs = [(name, make, False) for name, make in WORKLOADS.items()]
     # the three large shapes once more with labels that depend on the features (balanced trees)
     runs += [(name + "+signal", WORKLOADS[name], True) for name in ("dense_wide", "dense_tall", "categorical")]
@@ -253,24 +255,31 @@ def tree(args, torch, B, synth, dev):
             w.grad, w.hess = synth.labels_with_signal(w.bins, nb, gen)
         packed = B.gbdt_bins_pack(w.bins, nb)
         del w.bins
-        scratch, order = None, torch.empty(n, dtype=torch.int32, device=dev)
-        walls = []
-        for rep in range(6):
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            nodes, _, scratch = B.gbdt_grow_tree(packed, n, F, nb, w.grad, w.hess, 255, w.lam, w.min_child_hess,
-                                                 scratch=scratch, row_order_out=order)
-            torch.cuda.synchronize()
-            if rep:
-                walls.append((time.perf_counter() - t0) * 1e3)
-        leaves = int((nodes["left"] < 0).sum())
-        depth = [0] * len(nodes)
-        for k in range(1, len(nodes)):
-            depth[k] = depth[int(nodes[k]["parent"])] + 1
-        med = statistics.median(walls)
-        print(f"| {name} | {n:,} x {F}, {nb} | {leaves} | {max(depth)} | {med:.2f} | {min(walls):.2f} | "
-              f"{(leaves - 1) / (med * 1e-3):,.0f} |", flush=True)
-        del w, packed, scratch, order
+        order = torch.empty(n, dtype=torch.int32, device=dev)
+        for growth in ("leaf-wise, 255 leaves", "level-wise, depth 8"):
+            scratch, walls = None, []
+            for rep in range(6):
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                if growth.startswith("leaf"):
+                    nodes, _, scratch = B.gbdt_grow_tree(packed, n, F, nb, w.grad, w.hess, 255, w.lam,
+                                                         w.min_child_hess, scratch=scratch, row_order_out=order)
+                else:
+                    nodes, _, scratch = B.gbdt_grow_tree_depthwise(packed, n, F, nb, w.grad, w.hess, 8, w.lam,
+                                                                   w.min_child_hess, scratch=scratch,
+                                                                   row_order_out=order)
+                torch.cuda.synchronize()
+                if rep:
+                    walls.append((time.perf_counter() - t0) * 1e3)
+            leaves = int((nodes["left"] < 0).sum())
+            depth = [0] * len(nodes)
+            for k in range(1, len(nodes)):
+                depth[k] = depth[int(nodes[k]["parent"])] + 1
+            med = statistics.median(walls)
+            print(f"| {name} | {n:,} x {F}, {nb} | {growth} | {leaves} | {max(depth)} | {med:.2f} | {min(walls):.2f} | "
+                  f"{(leaves - 1) / (med * 1e-3):,.0f} |", flush=True)
+            del scratch
+        del w, packed, order
         torch.cuda.empty_cache()
 
 
