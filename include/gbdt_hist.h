@@ -142,14 +142,14 @@ int gbdt_hist_build(const void* bin_matrix, int64_t n_rows, int32_t n_features, 
  * The paper builds one leaf at a time, and its kernel benchmark (App. C.2) shows the
  * rate falling as leaves get small, because a small leaf cannot fill the GPU; a level of
  * a depth-wise tree, or the small children of several splits, can when they share a
- * launch.  Up to 128 leaves go into one kernel launch (plus one reduction launch);
+ * launch.  Up to 224 leaves go into one kernel launch (plus one reduction launch);
  * longer batches are cut into such launches.
  *   row_idx        DEVICE int32: the leaves' row lists back to back (e.g. the
  *                  children_out segments gbdt_partition_rows wrote), row ids in
  *                  [0, n_rows); may be NULL when every leaf is empty
  *   leaf_offsets   HOST int64 [n_leaves + 1], non-decreasing, leaf_offsets[0] >= 0;
  *                  read before the call returns.  Leaves may be empty; each holds fewer
- *                  than 2^31 rows and each launch of 128 leaves fewer than 2^32.
+ *                  than 2^31 rows and each launch of 224 leaves fewer than 2^32.
  *   grad, hess     DEVICE float [n_rows], indexed by row id
  *   hist_out       DEVICE gbdt_bin_t [n_leaves][n_features][n_bins], fully overwritten
  * Arithmetic and error bound per leaf as for gbdt_hist_build; the split of a leaf's rows

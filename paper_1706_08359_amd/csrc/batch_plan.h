@@ -7,7 +7,7 @@
 
 #include "tile_plan.h"
 
-constexpr int kBatchLeaves = 128;  // leaves per launch: the table travels as kernel arguments
+constexpr int kBatchLeaves = 224;  // leaves per launch: the table travels as kernel arguments (4 KB at most)
 
 struct BatchLeaf {
   uint32_t row_off;   // first entry of the leaf's row list
