@@ -26,6 +26,7 @@ EXPORTS = [
     "gbdt_hist_build_batch", "gbdt_hist_build_batch_workspace_bytes", "gbdt_best_split_batch",
     "gbdt_debug_batch_plan", "gbdt_grow_tree", "gbdt_grow_tree_scratch_bytes",
     "gbdt_partition_rows_batch", "gbdt_grow_tree_depthwise", "gbdt_grow_tree_depthwise_scratch_bytes",
+    "gbdt_set_wide_accumulation",
 ]
 
 # numpy views of the two C structs
@@ -114,6 +115,8 @@ def load():
     lib.gbdt_profile_collect.argtypes = [c.POINTER(c.c_double), c.POINTER(c.c_int64)]
     lib.gbdt_set_deterministic.restype = c.c_int
     lib.gbdt_set_deterministic.argtypes = [c.c_int]
+    lib.gbdt_set_wide_accumulation.restype = c.c_int
+    lib.gbdt_set_wide_accumulation.argtypes = [c.c_int]
     lib.gbdt_calibration_copy.restype = c.c_int
     lib.gbdt_calibration_copy.argtypes = [c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p]
     _lib = lib
@@ -443,6 +446,10 @@ def gbdt_debug_locate(n_features: int, n_bins: int, feature: int):
 
 def gbdt_set_deterministic(enable: bool) -> None:
     _check(load().gbdt_set_deterministic(1 if enable else 0), "gbdt_set_deterministic")
+
+
+def gbdt_set_wide_accumulation(enable: bool) -> None:
+    _check(load().gbdt_set_wide_accumulation(1 if enable else 0), "gbdt_set_wide_accumulation")
 
 
 def gbdt_calibration_copy(src: torch.Tensor, dst: torch.Tensor, stream=None) -> None:

@@ -66,6 +66,7 @@ int hip_fail(hipError_t e, const char* what) {
   } while (0)
 
 std::atomic<int> g_deterministic{0};
+std::atomic<int> g_wide{0};  // wide (fp64-grade) accumulation, see gbdt_set_wide_accumulation
 
 struct Workspace {
   std::mutex mu;
@@ -173,6 +174,7 @@ struct BuildGeom {
   int wgs;              // workgroups per tile
   int unit_epochs;      // epochs per unit
   bool one_unit_each;   // short leaf: every workgroup has exactly one unit, no counter
+  int blocks_per_wg;    // partial blocks a workgroup writes: 1, or 2 with wide accumulation
   size_t partial_words;  // total words of all partial blocks
 };
 
@@ -225,13 +227,14 @@ void plan_leaf_units(int64_t n_epochs, int64_t budget, int* wgs_out, int* unit_e
 // workgroups per CU of the kernel variant as reported by the runtime (<= 0: estimate
 // from the LDS footprint alone).
 BuildGeom make_geom(int32_t n_features, int32_t n_bins, int64_t n_leaf, int cus,
-                    int wg_per_cu_hint) {
+                    int wg_per_cu_hint, bool wide = false) {
   BuildGeom g;
   g.plan = make_tile_plan(n_features, n_bins);
   const TilePlan& p = g.plan;
   g.nt = kBuildThreads;
+  g.blocks_per_wg = wide ? 2 : 1;
   const size_t main_block = (size_t)3 * plan_cells(p, p.wm);
-  g.lds_bytes = (size_t)plan_cells(p, p.wm) * 8 + 4 * (g.nt / 64) * sizeof(float) + 8;
+  g.lds_bytes = (size_t)plan_cells(p, p.wm) * 8 * g.blocks_per_wg + 4 * (g.nt / 64) * sizeof(float) + 8;
   int wg_per_cu = wg_per_cu_hint;
   if (wg_per_cu <= 0) {
     wg_per_cu = (int)(kLdsPerCu / g.lds_bytes);
@@ -245,8 +248,9 @@ BuildGeom make_geom(int32_t n_features, int32_t n_bins, int64_t n_leaf, int cus,
   // (A narrow tile's epochs are cheaper, but not by much: the per-epoch overhead does
   // not shrink with the tile.  It gets as many workgroups as a main tile.)
   plan_leaf_units(n_epochs, resident / n_tiles, &g.wgs, &g.unit_epochs, &g.one_unit_each);
-  g.partial_words = (size_t)p.n_main * g.wgs * main_block +
-                    (size_t)(p.wr ? g.wgs : 0) * 3 * (p.wr ? plan_cells(p, p.wr) : 0);
+  g.partial_words = ((size_t)p.n_main * g.wgs * main_block +
+                     (size_t)(p.wr ? g.wgs : 0) * 3 * (p.wr ? plan_cells(p, p.wr) : 0)) *
+                    g.blocks_per_wg;
   return g;
 }
 
@@ -255,12 +259,16 @@ BuildGeom make_geom(int32_t n_features, int32_t n_bins, int64_t n_leaf, int cus,
 #define GBDT_VARIANT_16 16, 64, true, kBuildThreads, 8, double
 #define GBDT_VARIANT_64 64, 64, false, kBuildThreads, 6, float
 #define GBDT_VARIANT_256 256, 32, false, kBuildThreads, 4, float
+// The same with wide accumulation: twice the LDS, fp64 accumulators.
+#define GBDT_VARIANT_16W 16, 64, true, kBuildThreads, 6, double
+#define GBDT_VARIANT_64W 64, 64, false, kBuildThreads, 4, double
+#define GBDT_VARIANT_256W 256, 32, false, kBuildThreads, 2, double
 
-template <int CAP, int WM, bool NIB, int NT, int WPE, typename ACC, bool INDEXED>
+template <int CAP, int WM, bool NIB, int NT, int WPE, typename ACC, bool INDEXED, bool WIDE = false>
 int query_occupancy() {
   int n = 0;
   hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(
-      &n, reinterpret_cast<const void*>(hist_build_kernel<CAP, WM, NIB, NT, WPE, ACC, INDEXED>), NT, 0);
+      &n, reinterpret_cast<const void*>(hist_build_kernel<CAP, WM, NIB, NT, WPE, ACC, INDEXED, WIDE>), NT, 0);
   if (e != hipSuccess) {
     (void)hipGetLastError();
     return 0;
@@ -270,15 +278,20 @@ int query_occupancy() {
 
 // Resident workgroups per CU of the build kernel variant for this bin capacity
 // (registers, LDS and wave slots taken into account by the runtime); cached.
-int build_wg_per_cu(int cap, bool indexed) {
+int build_wg_per_cu(int cap, bool indexed, bool wide = false) {
   // GBDT_HIST_WG_PER_CU overrides the runtime's answer (tuning experiments only)
   if (const char* e = getenv("GBDT_HIST_WG_PER_CU")) {
     const int v = atoi(e);
     if (v > 0) return v;
   }
-  static int cache[3][2] = {{-1, -1}, {-1, -1}, {-1, -1}};
+  static int cache[6][2] = {{-1, -1}, {-1, -1}, {-1, -1}, {-1, -1}, {-1, -1}, {-1, -1}};
   const int ci = cap == 16 ? 0 : (cap == 64 ? 1 : 2);
-  int& c = cache[ci][indexed ? 1 : 0];
+  int& c = cache[ci + (wide ? 3 : 0)][indexed ? 1 : 0];
+  if (c < 0 && wide) {
+    if (cap == 16) c = indexed ? query_occupancy<GBDT_VARIANT_16W, true, true>() : query_occupancy<GBDT_VARIANT_16W, false, true>();
+    else if (cap == 64) c = indexed ? query_occupancy<GBDT_VARIANT_64W, true, true>() : query_occupancy<GBDT_VARIANT_64W, false, true>();
+    else c = indexed ? query_occupancy<GBDT_VARIANT_256W, true, true>() : query_occupancy<GBDT_VARIANT_256W, false, true>();
+  }
   if (c < 0) {
     if (cap == 16) c = indexed ? query_occupancy<GBDT_VARIANT_16, true>() : query_occupancy<GBDT_VARIANT_16, false>();
     else if (cap == 64) c = indexed ? query_occupancy<GBDT_VARIANT_64, true>() : query_occupancy<GBDT_VARIANT_64, false>();
@@ -362,26 +375,28 @@ struct BuildTimer {
   }
 };
 
-template <int CAP, int WM, bool NIB, int NT, int WPE, typename ACC>
+template <int CAP, int WM, bool NIB, int NT, int WPE, typename ACC, bool WIDE = false>
 int launch_build(const BuildArgs& a, int blocks, hipStream_t s) {
   BuildTimer timer;
   int rc = timer.begin(s);
   if (rc != GBDT_OK) return rc;
   if (a.idx) {
-    hipLaunchKernelGGL((hist_build_kernel<CAP, WM, NIB, NT, WPE, ACC, true>), dim3(blocks), dim3(NT), 0, s, a);
+    hipLaunchKernelGGL((hist_build_kernel<CAP, WM, NIB, NT, WPE, ACC, true, WIDE>), dim3(blocks), dim3(NT), 0, s,
+                       a);
   } else {
-    hipLaunchKernelGGL((hist_build_kernel<CAP, WM, NIB, NT, WPE, ACC, false>), dim3(blocks), dim3(NT), 0, s, a);
+    hipLaunchKernelGGL((hist_build_kernel<CAP, WM, NIB, NT, WPE, ACC, false, WIDE>), dim3(blocks), dim3(NT), 0, s,
+                       a);
   }
   HIP_TRY(hipGetLastError());
   return timer.end(s);
 }
 
-template <int CAP, int WM, bool NIB, int NT, int WPE, typename ACC>
+template <int CAP, int WM, bool NIB, int NT, int WPE, typename ACC, bool WIDE = false>
 int launch_build_batch(const BatchArgs& a, int blocks, hipStream_t s) {
   BuildTimer timer;
   int rc = timer.begin(s);
   if (rc != GBDT_OK) return rc;
-  hipLaunchKernelGGL((hist_build_batch_kernel<CAP, WM, NIB, NT, WPE, ACC>), dim3(blocks), dim3(NT), 0, s, a);
+  hipLaunchKernelGGL((hist_build_batch_kernel<CAP, WM, NIB, NT, WPE, ACC, WIDE>), dim3(blocks), dim3(NT), 0, s, a);
   HIP_TRY(hipGetLastError());
   return timer.end(s);
 }
@@ -559,8 +574,11 @@ int gbdt_bins_pack(const uint8_t* bins_rowmajor, int64_t n_rows, int32_t n_featu
 size_t gbdt_workspace_bytes(int64_t n_rows, int32_t n_features, int32_t n_bins) {
   if (!valid_shape(n_rows, n_features, n_bins)) return 0;
   const int cap = make_tile_plan(n_features, n_bins).cap;
-  const BuildGeom g0 = make_geom(n_features, n_bins, n_rows, device_cu_count(), build_wg_per_cu(cap, false));
-  const BuildGeom g1 = make_geom(n_features, n_bins, n_rows, device_cu_count(), build_wg_per_cu(cap, true));
+  const bool wide = g_wide.load() != 0;
+  const BuildGeom g0 =
+      make_geom(n_features, n_bins, n_rows, device_cu_count(), build_wg_per_cu(cap, false, wide), wide);
+  const BuildGeom g1 =
+      make_geom(n_features, n_bins, n_rows, device_cu_count(), build_wg_per_cu(cap, true, wide), wide);
   size_t b = (g0.partial_words > g1.partial_words ? g0.partial_words : g1.partial_words) * 4 +
              2 * (((size_t)n_rows + 63) / 64 * 64) * 4;  // + grad / hess of a leaf in leaf order
   int sg = 0, sn = 0;
@@ -603,9 +621,10 @@ int gbdt_hist_build(const void* bin_matrix, int64_t n_rows, int32_t n_features, 
     if (rc_ids != GBDT_OK) return rc_ids;
   }
 
+  const bool wide = g_wide.load() != 0;
   const BuildGeom g =
       make_geom(n_features, n_bins, n_leaf_rows, device_cu_count(),
-                build_wg_per_cu(make_tile_plan(n_features, n_bins).cap, leaf_row_idx != nullptr));
+                build_wg_per_cu(make_tile_plan(n_features, n_bins).cap, leaf_row_idx != nullptr, wide), wide);
   const TilePlan& p = g.plan;
   if (plan_n_tiles(p) > 65535) return GBDT_EUNSUPPORTED;
   // byte offsets inside a tile (slack included) are formed in 32 bits
@@ -643,6 +662,7 @@ int gbdt_hist_build(const void* bin_matrix, int64_t n_rows, int32_t n_features, 
   a.n_main = p.n_main;
   a.wr = p.wr;
   a.wgs = g.wgs;
+  a.chunks = g.wgs * g.blocks_per_wg;
   a.unit_epochs = g.unit_epochs;
   // no counter when every workgroup has one unit anyway, or when the split must be fixed
   a.fixed_stride = (g.one_unit_each || g_deterministic.load()) ? g.wgs : 0;
@@ -677,7 +697,15 @@ int gbdt_hist_build(const void* bin_matrix, int64_t n_rows, int32_t n_features, 
   // From here until the reduction pass has been enqueued the counters are in use.
   if (uses_counters && !capturing) set_counters_zero(counters, false);
 
-  if (p.cap == 16) {
+  if (wide) {
+    if (p.cap == 16) {
+      rc = launch_build<GBDT_VARIANT_16W, true>(a, blocks, s);
+    } else if (p.cap == 64) {
+      rc = launch_build<GBDT_VARIANT_64W, true>(a, blocks, s);
+    } else {
+      rc = launch_build<GBDT_VARIANT_256W, true>(a, blocks, s);
+    }
+  } else if (p.cap == 16) {
     rc = launch_build<GBDT_VARIANT_16>(a, blocks, s);
   } else if (p.cap == 64) {
     rc = launch_build<GBDT_VARIANT_64>(a, blocks, s);
@@ -696,8 +724,8 @@ int gbdt_hist_build(const void* bin_matrix, int64_t n_rows, int32_t n_features, 
   m.plan = p;
   m.n_features = n_features;
   m.n_bins = n_bins;
-  m.chunks_main = g.wgs;
-  m.chunks_rem = p.wr ? g.wgs : 0;
+  m.chunks_main = a.chunks;
+  m.chunks_rem = p.wr ? a.chunks : 0;
   m.counters = uses_counters ? counters : nullptr;
   const int max_slots = plan_slots(p, p.wm);
   const int mx = (n_bins * max_slots + kMergeCells - 1) / kMergeCells;
@@ -727,10 +755,13 @@ int gbdt_hist_build_batch(const void* bin_matrix, int64_t n_rows, int32_t n_feat
   const int n_tiles = plan_n_tiles(p);
   if (n_tiles > 65535) return GBDT_EUNSUPPORTED;
   if ((n_rows + kEpochRows) * (int64_t)p.wm >= ((int64_t)1 << 32)) return GBDT_EUNSUPPORTED;
-  const int64_t resident = (int64_t)device_cu_count() * build_wg_per_cu(p.cap, true);
-  const size_t col = p.cap == 16 ? variant_column_words<GBDT_VARIANT_16>(p)
-                                 : (p.cap == 64 ? variant_column_words<GBDT_VARIANT_64>(p)
-                                                : variant_column_words<GBDT_VARIANT_256>(p));
+  const bool wide = g_wide.load() != 0;
+  const int64_t resident = (int64_t)device_cu_count() * build_wg_per_cu(p.cap, true, wide);
+  // words of the partial blocks of one workgroup column (two blocks each with wide accumulation)
+  const size_t col = (p.cap == 16 ? variant_column_words<GBDT_VARIANT_16>(p)
+                                  : (p.cap == 64 ? variant_column_words<GBDT_VARIANT_64>(p)
+                                                 : variant_column_words<GBDT_VARIANT_256>(p))) *
+                     (wide ? 2 : 1);
   // one scratch buffer serves the launches one after the other: size it for the largest
   size_t need_words = 0;
   for (int32_t l0 = 0; l0 < n_leaves; l0 += kBatchLeaves) {
@@ -774,6 +805,7 @@ int gbdt_hist_build_batch(const void* bin_matrix, int64_t n_rows, int32_t n_feat
     m.m.chunks_rem = 0;
     m.m.counters = nullptr;
     m.column_words = col;
+    m.blocks_per_wg = wide ? 2 : 1;
     memcpy(m.leaf, b.leaf, sizeof m.leaf);
     if (b.total_wgs > 0) {
       BatchArgs a;
@@ -792,7 +824,15 @@ int gbdt_hist_build_batch(const void* bin_matrix, int64_t n_rows, int32_t n_feat
       a.n_bins = n_bins;
       memcpy(a.leaf, b.leaf, sizeof a.leaf);
       const int blocks = (int)b.total_wgs * n_tiles;
-      if (p.cap == 16) {
+      if (wide) {
+        if (p.cap == 16) {
+          rc = launch_build_batch<GBDT_VARIANT_16W, true>(a, blocks, s);
+        } else if (p.cap == 64) {
+          rc = launch_build_batch<GBDT_VARIANT_64W, true>(a, blocks, s);
+        } else {
+          rc = launch_build_batch<GBDT_VARIANT_256W, true>(a, blocks, s);
+        }
+      } else if (p.cap == 16) {
         rc = launch_build_batch<GBDT_VARIANT_16>(a, blocks, s);
       } else if (p.cap == 64) {
         rc = launch_build_batch<GBDT_VARIANT_64>(a, blocks, s);
@@ -817,10 +857,12 @@ size_t gbdt_hist_build_batch_workspace_bytes(int32_t n_features, int32_t n_bins,
   if (n_features <= 0 || n_bins < 2 || n_bins > 256 || n_leaves < 0) return 0;
   const TilePlan p = make_tile_plan(n_features, n_bins);
   const int n_tiles = plan_n_tiles(p);
-  const int64_t resident = (int64_t)device_cu_count() * build_wg_per_cu(p.cap, true);
-  const size_t col = p.cap == 16 ? variant_column_words<GBDT_VARIANT_16>(p)
-                                 : (p.cap == 64 ? variant_column_words<GBDT_VARIANT_64>(p)
-                                                : variant_column_words<GBDT_VARIANT_256>(p));
+  const bool wide = g_wide.load() != 0;
+  const int64_t resident = (int64_t)device_cu_count() * build_wg_per_cu(p.cap, true, wide);
+  const size_t col = (p.cap == 16 ? variant_column_words<GBDT_VARIANT_16>(p)
+                                  : (p.cap == 64 ? variant_column_words<GBDT_VARIANT_64>(p)
+                                                 : variant_column_words<GBDT_VARIANT_256>(p))) *
+                     (wide ? 2 : 1);
   // every leaf of a launch gets its share of the resident workgroups, rounded down, but
   // at least one workgroup per tile
   int64_t budget = resident / n_tiles;
@@ -1420,6 +1462,11 @@ int gbdt_debug_locate(int32_t n_features, int32_t n_bins, int32_t feature, int32
 
 int gbdt_set_deterministic(int enable) {
   g_deterministic.store(enable != 0);
+  return GBDT_OK;
+}
+
+int gbdt_set_wide_accumulation(int enable) {
+  g_wide.store(enable != 0);
   return GBDT_OK;
 }
 

@@ -66,6 +66,7 @@ struct BuildArgs {
   int32_t n_main;       // main tiles
   int32_t wr;           // remainder tile width, 0 if none
   int32_t wgs;          // workgroups per tile
+  int32_t chunks;       // partial blocks per tile: wgs, or 2 * wgs with wide accumulation
   int32_t unit_epochs;  // consecutive epochs a workgroup takes at a time
   int32_t fixed_stride; // 0: units from the tile's counter; else unit u is followed by u + this
   gbdt_bin_t* direct_out;  // wgs == 1 only: the histogram itself, written by the build kernel
@@ -103,6 +104,22 @@ __device__ __forceinline__ int epoch_scale_exp(uint32_t m_bits) {
   return k;
 }
 __device__ __forceinline__ float pow2f(int k) { return __uint_as_float((uint32_t)(k + 127) << 23); }
+
+// Wide accumulation (the double precision switch of App. A.6): a (bin, feature) pair owns TWO
+// 64-bit cells, gradient and hessian, each a signed 54-bit sum above the 10-bit count field (the
+// count is kept in the gradient cell).  Values are scaled by 2^(k + kWideShift), k the exponent
+// of the narrow format, so an epoch's sum of magnitudes stays below 2^50 and a value is rounded
+// at 2^-50 of it at worst -- a fp32 value that is not 2^26 times smaller than the epoch's sum is
+// taken exactly.  Cells are drained into fp64 accumulators.  Twice the LDS atomics and twice the
+// LDS space of the default format.
+constexpr int kWideShift = 24;
+__device__ __forceinline__ double pow2d(int k) {
+  return __longlong_as_double((long long)(k + 1023) << 52);
+}
+// round-to-nearest-even of |v| < 2^51 to a 64-bit integer (the sum's low mantissa bits)
+__device__ __forceinline__ long long rint_to_i64(double v) {
+  return __double_as_longlong(v + 6755399441055744.0) - 0x4338000000000000LL;
+}
 
 // Sum over the lanes of a wavefront with DPP moves (no LDS traffic); the total
 // arrives in lane 63.
@@ -198,7 +215,7 @@ struct TileShape {
 // epoch barriers and across the hand-out of work.
 //
 // All wavefronts of a workgroup share ONE histogram; no replica has to be reduced.
-template <int CAP, int W, bool NIB, int NT, typename ACC, bool INDEXED>
+template <int CAP, int W, bool NIB, int NT, typename ACC, bool INDEXED, bool WIDE = false>
 __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
                                            const int32_t* __restrict__ idx,
                                            const float* __restrict__ grad,
@@ -207,14 +224,17 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
                                            uint32_t first_unit, uint32_t unit_epochs,
                                            uint32_t fixed_stride, uint32_t* counter,
                                            uint32_t counter_base, unsigned long long* lds,
-                                           uint32_t* __restrict__ out, const DirectOut& direct) {
+                                           uint32_t* __restrict__ out, const DirectOut& direct,
+                                           uint32_t* __restrict__ out_lo = nullptr) {
+  static_assert(!WIDE || sizeof(ACC) == 8, "wide cells are drained into fp64 accumulators");
   using S = TileShape<CAP, W, NIB, NT>;
   constexpr int VEC = S::VEC, NWORD = S::NWORD, LPR = S::LPR, RPW = S::RPW, NBW = S::NBW;
   constexpr int CELLS = S::CELLS, PP = S::PP, NW = S::NW;
   constexpr int NTBL = LPR == 8 ? 1 : 2;  // LPR 4: two byte-words share a page of 32 slots
 
   char* cells = reinterpret_cast<char*>(lds);
-  float* red = reinterpret_cast<float*>(lds + CELLS);  // [2 parities][2 stats][NW]
+  constexpr int NCELLARR = WIDE ? 2 : 1;  // wide: gradient cells, then hessian cells
+  float* red = reinterpret_cast<float*>(lds + NCELLARR * CELLS);  // [2 parities][2 stats][NW]
   uint32_t* unit_box = reinterpret_cast<uint32_t*>(red + 4 * NW);  // the unit just taken from the counter
 
   const int tid = threadIdx.x;
@@ -240,7 +260,7 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
   }
 
 #pragma unroll
-  for (int m = 0; m < PP; ++m) lds[tid + m * NT] = 0ull;
+  for (int m = 0; m < PP * NCELLARR; ++m) lds[tid + m * NT] = 0ull;
   ACC acc_g[PP], acc_h[PP];
   uint32_t acc_c[PP];
 #pragma unroll
@@ -327,10 +347,13 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
       w.x = *reinterpret_cast<const uint32_t*>(tile + off);
     }
   };
-  // lo, hi: the addend of the row this lane owns (zero for a row past the chunk end)
-  auto add_group = [&](const uint4& w, uint32_t lo, uint32_t hi, auto gi_tag) {
+  // lo, hi: the addend of the row this lane owns (zero for a row past the chunk end); wide:
+  // the gradient cell's addend, and lo2, hi2 the hessian cell's
+  auto add_group = [&](const uint4& w, uint32_t lo, uint32_t hi, uint32_t lo2, uint32_t hi2, auto gi_tag) {
     const unsigned long long add =
         ((unsigned long long)from_owner(hi, gi_tag) << 32) | from_owner(lo, gi_tag);
+    unsigned long long add2 = 0ull;
+    if (WIDE) add2 = ((unsigned long long)from_owner(hi2, gi_tag) << 32) | from_owner(lo2, gi_tag);
     uint32_t bword[NBW];
 #pragma unroll
     for (int x = 0; x < NWORD; ++x) {
@@ -352,6 +375,11 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
         __hip_atomic_fetch_add(
             reinterpret_cast<unsigned long long*>(cells + a + page * (CAP * 256)), add,
             __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        if (WIDE) {
+          __hip_atomic_fetch_add(
+              reinterpret_cast<unsigned long long*>(cells + a + page * (CAP * 256) + CELLS * 8), add2,
+              __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        }
       }
     }
   };
@@ -386,7 +414,18 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
     }
   };
   // Moves the sums of cell m into this thread's accumulators and clears it.
-  auto drain_cell = [&](int m, float inv_g, float inv_h) {
+  auto drain_cell = [&](int m, float inv_g, float inv_h, double inv_gw, double inv_hw) {
+    if constexpr (WIDE) {
+      const unsigned long long tg = __hip_atomic_exchange(&lds[tid + m * NT], 0ull, __ATOMIC_RELAXED,
+                                                          __HIP_MEMORY_SCOPE_WORKGROUP);
+      const unsigned long long th = __hip_atomic_exchange(&lds[CELLS + tid + m * NT], 0ull, __ATOMIC_RELAXED,
+                                                          __HIP_MEMORY_SCOPE_WORKGROUP);
+      // the count sits below the gradient sum; an arithmetic shift drops it whatever the sign
+      acc_c[m] += (uint32_t)tg & ((1u << kCountBits) - 1u);
+      acc_g[m] = (ACC)fma((double)((long long)tg >> kCountBits), inv_gw, (double)acc_g[m]);
+      acc_h[m] = (ACC)fma((double)((long long)th >> kCountBits), inv_hw, (double)acc_h[m]);
+      return;
+    }
     // read and clear in one LDS operation
     const unsigned long long t = __hip_atomic_exchange(&lds[tid + m * NT], 0ull, __ATOMIC_RELAXED,
                                                        __HIP_MEMORY_SCOPE_WORKGROUP);
@@ -411,12 +450,12 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
   // requests the same group of the next epoch into them: every request has a whole
   // epoch to complete, requests are spread evenly over the epoch, and one register set
   // serves both epochs.
-  auto add_and_reload = [&](uint4 (&w)[GPE], uint32_t lo, uint32_t hi, uint32_t rows_nxt,
-                            uint32_t e0_nxt) {
+  auto add_and_reload = [&](uint4 (&w)[GPE], uint32_t lo, uint32_t hi, uint32_t lo2, uint32_t hi2,
+                            uint32_t rows_nxt, uint32_t e0_nxt) {
     const uint32_t off0 = group_offset0(e0_nxt);
     auto step = [&](auto gi_tag) {
       constexpr int gi = decltype(gi_tag)::value;
-      add_group(w[gi], lo, hi, gi_tag);
+      add_group(w[gi], lo, hi, lo2, hi2, gi_tag);
       load_group(w[gi], rows_nxt, off0, gi_tag);
     };
     step(std::integral_constant<int, 0>{});
@@ -509,8 +548,19 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
     const float g_nxt = load_stat(grad, stat_nxt);
     const float h_nxt = load_stat(hess, stat_nxt);
     // ---- this lane's row -> 64-bit addend 1 + gq * 2^10 + hq * 2^37 (two's complement)
-    uint32_t lo, hi;
-    {
+    //      (wide: 1 + gq * 2^10 into the gradient cell, hq * 2^10 into the hessian cell)
+    uint32_t lo, hi, lo2 = 0u, hi2 = 0u;
+    if constexpr (WIDE) {
+      const long long gq = rint_to_i64((double)g_cur * pow2d(kg + kWideShift));
+      const long long hq = rint_to_i64((double)h_cur * pow2d(kh + kWideShift));
+      const unsigned long long ag = ((unsigned long long)gq << kCountBits) + 1ull;
+      const unsigned long long ah = (unsigned long long)hq << kCountBits;
+      const bool ok = own_valid(p0.row);
+      lo = ok ? (uint32_t)ag : 0u;
+      hi = ok ? (uint32_t)(ag >> 32) : 0u;
+      lo2 = ok ? (uint32_t)ah : 0u;
+      hi2 = ok ? (uint32_t)(ah >> 32) : 0u;
+    } else {
       const int32_t gq = __float2int_rn(g_cur * pow2f(kg));
       const int32_t hq = __float2int_rn(h_cur * pow2f(kh));
       lo = ((uint32_t)gq << kCountBits) + 1u;
@@ -523,7 +573,7 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
     // mostly VALU work.  Raised priority lets the waves that feed the LDS pipe issue first,
     // and the other workgroup's drain fills the gaps (8-12 % on the 256-bin variants).
     __builtin_amdgcn_s_setprio(1);
-    add_and_reload(w, lo, hi, row_nxt, p1.row);
+    add_and_reload(w, lo, hi, lo2, hi2, row_nxt, p1.row);
     __builtin_amdgcn_s_setprio(0);
 
     parity ^= 1u;
@@ -536,8 +586,9 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
 
     // ---- drain: integer sums -> registers, clear the cells for the next epoch
     const float inv_g = pow2f(-kg), inv_h = pow2f(-kh);
+    const double inv_gw = pow2d(-kg - kWideShift), inv_hw = pow2d(-kh - kWideShift);
 #pragma unroll
-    for (int m = 0; m < PP; ++m) drain_cell(m, inv_g, inv_h);
+    for (int m = 0; m < PP; ++m) drain_cell(m, inv_g, inv_h, inv_gw, inv_hw);
     read_scales((int)parity, kg, kh);
     if (enters_unit) next_unit = __builtin_amdgcn_readfirstlane(fixed_stride ? taken : unit_box[0]);
     p0 = p1;
@@ -583,6 +634,17 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
     out[CELLS + tid + m * NT] = __float_as_uint((float)acc_h[m]);
     out[2 * CELLS + tid + m * NT] = acc_c[m];
   }
+  if constexpr (WIDE) {
+    // what fp32 cannot hold of the fp64 sums goes into a second block of the same layout (count
+    // 0), which the reduction pass adds like any other workgroup's
+#pragma unroll
+    for (int m = 0; m < PP; ++m) {
+      const double g = (double)acc_g[m], h = (double)acc_h[m];
+      out_lo[tid + m * NT] = __float_as_uint((float)(g - (double)(float)g));
+      out_lo[CELLS + tid + m * NT] = __float_as_uint((float)(h - (double)(float)h));
+      out_lo[2 * CELLS + tid + m * NT] = 0u;
+    }
+  }
 }
 
 // Words of one partial block of a tile of width W.
@@ -596,12 +658,12 @@ __device__ __host__ constexpr int block_words() {
 // -> (tile, workgroup of the tile); consecutive blocks take different tiles, so the
 // row ids / gradients / hessians of an epoch are fetched from HBM once and served to
 // the other tiles from cache.
-template <int CAP, int WM, bool NIB, int NT, int WPE, typename ACC, bool INDEXED>
+template <int CAP, int WM, bool NIB, int NT, int WPE, typename ACC, bool INDEXED, bool WIDE = false>
 __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(WPE, WPE)))
 hist_build_kernel(BuildArgs a) {
-  // one histogram of the main tile width (8 bytes per cell), the reduction scratch and
-  // the unit box
-  constexpr int kCells = TileShape<CAP, WM, NIB, NT>::CELLS;
+  // one histogram of the main tile width (8 bytes per cell; two with wide accumulation), the
+  // reduction scratch and the unit box
+  constexpr int kCells = (WIDE ? 2 : 1) * TileShape<CAP, WM, NIB, NT>::CELLS;
   __shared__ __align__(16) unsigned long long lds[kCells + (4 * (NT / 64) * 4 + 7) / 8 + 1];
   const int32_t main_blocks = a.n_main * a.wgs;
   const int32_t b = blockIdx.x;
@@ -611,23 +673,29 @@ hist_build_kernel(BuildArgs a) {
   uint32_t* counter = a.counters + t;
   const uint8_t* tile = a.packed + a.n_rows * ((int64_t)t * WM);
   const DirectOut direct = {a.direct_out, t, WM, a.n_main, a.wr, a.n_features, a.n_bins};
+  // wide accumulation: the workgroup's second block lies a.wgs blocks behind its first
   if (b < main_blocks) {
-    uint32_t* out = a.partials + ((size_t)t * a.wgs + c) * (size_t)block_words<CAP, WM, NIB, NT>();
-    build_tile<CAP, WM, NIB, NT, ACC, INDEXED>(tile, a.idx, a.grad, a.hess, a.stats_by_pos != 0, n_leaf, (uint32_t)c,
-                                               (uint32_t)a.unit_epochs, (uint32_t)a.fixed_stride, counter,
-                                               (uint32_t)a.wgs, lds, out, direct);
+    constexpr size_t kBlock = (size_t)block_words<CAP, WM, NIB, NT>();
+    uint32_t* out = a.partials + ((size_t)t * a.chunks + c) * kBlock;
+    build_tile<CAP, WM, NIB, NT, ACC, INDEXED, WIDE>(tile, a.idx, a.grad, a.hess, a.stats_by_pos != 0, n_leaf,
+                                                     (uint32_t)c, (uint32_t)a.unit_epochs,
+                                                     (uint32_t)a.fixed_stride, counter, (uint32_t)a.wgs, lds,
+                                                     out, direct, out + (size_t)a.wgs * kBlock);
   } else {
-    uint32_t* rem_base = a.partials + (size_t)main_blocks * (size_t)block_words<CAP, WM, NIB, NT>();
+    uint32_t* rem_base =
+        a.partials + (size_t)a.n_main * a.chunks * (size_t)block_words<CAP, WM, NIB, NT>();
     if (a.wr == 16) {
-      build_tile<CAP, 16, NIB, NT, ACC, INDEXED>(
+      constexpr size_t kBlock = (size_t)block_words<CAP, 16, NIB, NT>();
+      build_tile<CAP, 16, NIB, NT, ACC, INDEXED, WIDE>(
           tile, a.idx, a.grad, a.hess, a.stats_by_pos != 0, n_leaf, (uint32_t)c, (uint32_t)a.unit_epochs,
-          (uint32_t)a.fixed_stride, counter, (uint32_t)a.wgs, lds,
-          rem_base + (size_t)c * (size_t)block_words<CAP, 16, NIB, NT>(), direct);
+          (uint32_t)a.fixed_stride, counter, (uint32_t)a.wgs, lds, rem_base + (size_t)c * kBlock, direct,
+          rem_base + (size_t)(a.wgs + c) * kBlock);
     } else if constexpr (WM > 32) {
-      build_tile<CAP, 32, NIB, NT, ACC, INDEXED>(
+      constexpr size_t kBlock = (size_t)block_words<CAP, 32, NIB, NT>();
+      build_tile<CAP, 32, NIB, NT, ACC, INDEXED, WIDE>(
           tile, a.idx, a.grad, a.hess, a.stats_by_pos != 0, n_leaf, (uint32_t)c, (uint32_t)a.unit_epochs,
-          (uint32_t)a.fixed_stride, counter, (uint32_t)a.wgs, lds,
-          rem_base + (size_t)c * (size_t)block_words<CAP, 32, NIB, NT>(), direct);
+          (uint32_t)a.fixed_stride, counter, (uint32_t)a.wgs, lds, rem_base + (size_t)c * kBlock, direct,
+          rem_base + (size_t)(a.wgs + c) * kBlock);
     }
   }
 }
@@ -691,16 +759,17 @@ __device__ __host__ inline size_t column_words(int32_t n_main, int32_t wr) {
   return w;
 }
 
-template <int CAP, int WM, bool NIB, int NT, int WPE, typename ACC>
+template <int CAP, int WM, bool NIB, int NT, int WPE, typename ACC, bool WIDE = false>
 __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(WPE, WPE)))
 hist_build_batch_kernel(BatchArgs a) {
-  constexpr int kCells = TileShape<CAP, WM, NIB, NT>::CELLS;
+  constexpr int kCells = (WIDE ? 2 : 1) * TileShape<CAP, WM, NIB, NT>::CELLS;
   __shared__ __align__(16) unsigned long long lds[kCells + (4 * (NT / 64) * 4 + 7) / 8 + 1];
   const BatchBlock blk = batch_block(a.leaf, a.n_leaves, a.n_main, a.wr, blockIdx.x);
   const BatchLeaf lf = a.leaf[blk.leaf];
   const int32_t wgs = (int32_t)(lf.wgs_unit & 0xffffu);
   const uint32_t unit_epochs = lf.wgs_unit >> 16;
-  const int32_t main_blocks = a.n_main * wgs;
+  constexpr int kPerWg = WIDE ? 2 : 1;  // partial blocks per workgroup
+  const int32_t chunks = kPerWg * wgs;
   const int32_t t = blk.tile, c = blk.wg;
   const bool is_main = t < a.n_main;
   const uint8_t* tile = a.packed + a.n_rows * ((int64_t)t * WM);
@@ -708,26 +777,29 @@ hist_build_batch_kernel(BatchArgs a) {
   const bool by_pos = a.stats_by_pos != 0;  // then grad / hess follow the concatenated row lists
   const float* grad = by_pos ? a.grad + lf.row_off : a.grad;
   const float* hess = by_pos ? a.hess + lf.row_off : a.hess;
-  uint32_t* leaf_out = a.partials + (size_t)lf.first_wg * column_words<CAP, WM, NIB, NT>(a.n_main, a.wr);
+  uint32_t* leaf_out =
+      a.partials + (size_t)lf.first_wg * kPerWg * column_words<CAP, WM, NIB, NT>(a.n_main, a.wr);
   const DirectOut direct = {
       wgs == 1 ? a.hist_out + (size_t)blk.leaf * a.n_features * a.n_bins : nullptr,
       t, WM, a.n_main, a.wr, a.n_features, a.n_bins};
   if (is_main) {
-    build_tile<CAP, WM, NIB, NT, ACC, true>(
-        tile, idx, grad, hess, by_pos, lf.n, (uint32_t)c, unit_epochs, (uint32_t)wgs, nullptr, 0u, lds,
-        leaf_out + ((size_t)t * wgs + c) * (size_t)block_words<CAP, WM, NIB, NT>(), direct);
+    constexpr size_t kBlock = (size_t)block_words<CAP, WM, NIB, NT>();
+    uint32_t* out = leaf_out + ((size_t)t * chunks + c) * kBlock;
+    build_tile<CAP, WM, NIB, NT, ACC, true, WIDE>(tile, idx, grad, hess, by_pos, lf.n, (uint32_t)c, unit_epochs,
+                                                  (uint32_t)wgs, nullptr, 0u, lds, out, direct,
+                                                  out + (size_t)wgs * kBlock);
   } else {
-    uint32_t* rem_base = leaf_out + (size_t)main_blocks * (size_t)block_words<CAP, WM, NIB, NT>();
+    uint32_t* rem_base = leaf_out + (size_t)a.n_main * chunks * (size_t)block_words<CAP, WM, NIB, NT>();
     if (a.wr == 16) {
-      build_tile<CAP, 16, NIB, NT, ACC, true>(tile, idx, grad, hess, by_pos, lf.n, (uint32_t)c, unit_epochs,
-                                              (uint32_t)wgs, nullptr, 0u, lds,
-                                              rem_base + (size_t)c * (size_t)block_words<CAP, 16, NIB, NT>(),
-                                              direct);
+      constexpr size_t kBlock = (size_t)block_words<CAP, 16, NIB, NT>();
+      build_tile<CAP, 16, NIB, NT, ACC, true, WIDE>(tile, idx, grad, hess, by_pos, lf.n, (uint32_t)c, unit_epochs,
+                                                    (uint32_t)wgs, nullptr, 0u, lds, rem_base + (size_t)c * kBlock,
+                                                    direct, rem_base + (size_t)(wgs + c) * kBlock);
     } else if constexpr (WM > 32) {
-      build_tile<CAP, 32, NIB, NT, ACC, true>(tile, idx, grad, hess, by_pos, lf.n, (uint32_t)c, unit_epochs,
-                                              (uint32_t)wgs, nullptr, 0u, lds,
-                                              rem_base + (size_t)c * (size_t)block_words<CAP, 32, NIB, NT>(),
-                                              direct);
+      constexpr size_t kBlock = (size_t)block_words<CAP, 32, NIB, NT>();
+      build_tile<CAP, 32, NIB, NT, ACC, true, WIDE>(tile, idx, grad, hess, by_pos, lf.n, (uint32_t)c, unit_epochs,
+                                                    (uint32_t)wgs, nullptr, 0u, lds, rem_base + (size_t)c * kBlock,
+                                                    direct, rem_base + (size_t)(wgs + c) * kBlock);
     }
   }
 }

@@ -126,6 +126,7 @@ __global__ void __launch_bounds__(kMergeCells * kMergeLanes) hist_merge_kernel(M
 struct BatchMergeArgs {
   MergeArgs m;            // partials / out of leaf 0 of the launch; chunk counts unused
   uint64_t column_words;  // words of one workgroup column
+  int32_t blocks_per_wg;  // partial blocks a workgroup wrote: 1, or 2 with wide accumulation
   BatchLeaf leaf[kBatchLeaves];
 };
 
@@ -135,7 +136,7 @@ __global__ void __launch_bounds__(kMergeCells * kMergeLanes) hist_merge_batch_ke
   MergeArgs m = a.m;
   m.partials += (size_t)lf.first_wg * a.column_words;
   m.out += (size_t)blockIdx.z * m.n_features * m.n_bins;
-  m.chunks_main = (int32_t)(lf.wgs_unit & 0xffffu);
+  m.chunks_main = (int32_t)(lf.wgs_unit & 0xffffu) * a.blocks_per_wg;
   m.chunks_rem = m.plan.wr ? m.chunks_main : 0;
   merge_cells(m);
 }

@@ -350,6 +350,8 @@ def main():
     ap.add_argument("--batch-sweep", action="store_true")
     ap.add_argument("--oracle", action="store_true", help="time the CPU oracle on the root leaves")
     ap.add_argument("--only", nargs="*", default=None)
+    ap.add_argument("--wide", action="store_true", help="measure in the wide-accumulation mode")
+    ap.add_argument("--deterministic", action="store_true", help="measure with the fixed split of units")
     args = ap.parse_args()
 
     import torch
@@ -359,6 +361,8 @@ def main():
     if not torch.cuda.is_available():
         raise SystemExit("measure_all needs a GPU")
     B.load()
+    B.gbdt_set_wide_accumulation(args.wide)
+    B.gbdt_set_deterministic(args.deterministic)
     dev = torch.device("cuda:0")
     if args.depth_sweep:
         depth_sweep(args, torch, B, synth, dev)
