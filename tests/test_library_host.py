@@ -193,3 +193,21 @@ def test_batched_launch_plan_covers_every_leaf_exactly(n_features, n_bins, wg_pe
         # the leaves share the machine: about one machine-full of workgroup columns, plus the
         # at-least-one of every leaf
         assert int(wgs.sum()) <= 256 * wg_per_cu // n_tiles + n_leaves
+
+
+@pytest.mark.parametrize("n_features,n_bins", [(28, 64), (2000, 63), (137, 255), (700, 16)])
+def test_wide_accumulation_doubles_the_partial_blocks(n_features, n_bins):
+    """The wide mode writes two partial blocks per workgroup; the sizes the library reports for
+    caller-owned scratch follow the switch (and go back with it)."""
+    n_leaf = 266_000
+    narrow = B.gbdt_workspace_bytes(n_leaf, n_features, n_bins)
+    narrow_batch = B.gbdt_hist_build_batch_workspace_bytes(n_features, n_bins, 64)
+    B.gbdt_set_wide_accumulation(True)
+    try:
+        wide = B.gbdt_workspace_bytes(n_leaf, n_features, n_bins)
+        wide_batch = B.gbdt_hist_build_batch_workspace_bytes(n_features, n_bins, 64)
+    finally:
+        B.gbdt_set_wide_accumulation(False)
+    assert wide >= narrow and wide_batch > narrow_batch
+    assert wide_batch <= 2 * narrow_batch
+    assert B.gbdt_workspace_bytes(n_leaf, n_features, n_bins) == narrow
