@@ -444,16 +444,18 @@ BatchPlan plan_batch(const int64_t* leaf_offsets, int32_t l0, int32_t n, int64_t
 // launch; splits_out[i] receives the record of histogram i.
 int launch_split(const gbdt_bin_t* hists, int64_t hist_stride, int32_t n_hists, float lambda,
                  float min_child_hess, gbdt_split_t* splits_out, int32_t n_features, int32_t n_bins,
-                 hipStream_t s) {
+                 hipStream_t s, gbdt_split_t* host_mirror = nullptr, const gbdt_bin_t* minus = nullptr,
+                 int32_t minus_y = -1) {
   int group = 0, n_groups = 0;
   split_grouping(n_features, n_bins, &group, &n_groups);
   void* ws = nullptr;
   int rc = get_workspace((size_t)n_hists * n_groups * sizeof(SplitCand), &ws);
   if (rc != GBDT_OK) return rc;
   const size_t lds = (size_t)group * split_feature_bytes(n_bins);
-  hipLaunchKernelGGL(split_gain_kernel, dim3(n_groups, n_hists), dim3(kSplitThreads), lds, s, hists,
-                     hist_stride, n_features, n_bins, group, (double)lambda, (double)min_child_hess,
-                     (SplitCand*)ws, splits_out);
+  // (only with `minus` does the kernel write to the histograms)
+  hipLaunchKernelGGL(split_gain_kernel, dim3(n_groups, n_hists), dim3(kSplitThreads), lds, s,
+                     const_cast<gbdt_bin_t*>(hists), hist_stride, n_features, n_bins, group, (double)lambda,
+                     (double)min_child_hess, (SplitCand*)ws, splits_out, host_mirror, minus, minus_y);
   HIP_TRY(hipGetLastError());
   return GBDT_OK;
 }
@@ -476,20 +478,31 @@ TreeScratch tree_scratch_layout(int64_t n_rows, int32_t n_features, int32_t n_bi
   return t;
 }
 
-// Two split records in page-locked host memory, the landing place of the per-split
-// device-to-host copy (one per process, never freed).
-gbdt_split_t* pinned_records() {
+// Two split records in page-locked host memory that the device can write: the split search
+// of gbdt_grow_tree stores its two records there as well, and the host reads them after
+// waiting for the stream, without a copy (one per process, never freed).  *dev_out: the
+// address the device uses for it.
+gbdt_split_t* pinned_records(gbdt_split_t** dev_out) {
   static gbdt_split_t* p = nullptr;
+  static gbdt_split_t* d = nullptr;
   static std::mutex mu;
   std::lock_guard<std::mutex> lk(mu);
   if (!p) {
     void* q = nullptr;
-    if (hipHostMalloc(&q, 2 * sizeof(gbdt_split_t), hipHostMallocDefault) != hipSuccess) {
+    if (hipHostMalloc(&q, 2 * sizeof(gbdt_split_t), hipHostMallocMapped) != hipSuccess) {
       (void)hipGetLastError();
       return nullptr;
     }
+    void* dq = nullptr;
+    if (hipHostGetDevicePointer(&dq, q, 0) != hipSuccess) {
+      (void)hipGetLastError();
+      (void)hipHostFree(q);
+      return nullptr;
+    }
     p = (gbdt_split_t*)q;
+    d = (gbdt_split_t*)dq;
   }
+  *dev_out = d;
   return p;
 }
 
@@ -1057,7 +1070,8 @@ int gbdt_grow_tree(const void* bin_matrix, int64_t n_rows, int32_t n_features, i
   if (n_rows >= ((int64_t)1 << 30)) return GBDT_EUNSUPPORTED;
   const TreeScratch lay = tree_scratch_layout(n_rows, n_features, n_bins, max_leaves);
   if (scratch_bytes < lay.total) return GBDT_ENOMEM;
-  gbdt_split_t* pinned = pinned_records();
+  gbdt_split_t* pinned_dev = nullptr;
+  gbdt_split_t* pinned = pinned_records(&pinned_dev);
   if (!pinned) return GBDT_ENOMEM;
   hipStream_t s = (hipStream_t)stream;
   char* base = (char*)scratch;
@@ -1090,9 +1104,8 @@ int gbdt_grow_tree(const void* bin_matrix, int64_t n_rows, int32_t n_features, i
   // root
   int rc = gbdt_hist_build(bin_matrix, n_rows, n_features, n_bins, nullptr, n_rows, grad, hess, pool, s);
   if (rc != GBDT_OK) return rc;
-  rc = gbdt_best_split(pool, lambda, min_child_hess, recs, n_features, n_bins, s);
+  rc = launch_split(pool, 0, 1, lambda, min_child_hess, recs, n_features, n_bins, s, pinned_dev);
   if (rc != GBDT_OK) return rc;
-  HIP_TRY(hipMemcpyAsync(pinned, recs, sizeof(gbdt_split_t), hipMemcpyDeviceToHost, s));
   HIP_TRY(hipStreamSynchronize(s));
   {
     const gbdt_split_t r = pinned[0];
@@ -1146,15 +1159,15 @@ int gbdt_grow_tree(const void* bin_matrix, int64_t n_rows, int32_t n_features, i
     rc = gbdt_hist_build(bin_matrix, n_rows, n_features, n_bins, rows_buf[dst_buf] + small_begin, small_n,
                          grad, hess, h_small, s);
     if (rc != GBDT_OK) return rc;
-    rc = gbdt_hist_subtract(h_large, h_small, h_large, n_features, n_bins, s);
-    if (rc != GBDT_OK) return rc;
-    // both children in one launch: their histograms sit in two slots of the pool
+    // both children in one launch: their histograms sit in two slots of the pool; the larger
+    // child's is still its parent's and becomes parent - smaller child in the same launch
+    (void)h_large;
     rc = launch_split(pool + (size_t)state[left].slot * hist_elems,
                       ((int64_t)state[right].slot - state[left].slot) * (int64_t)hist_elems, 2, lambda,
-                      min_child_hess, recs + left, n_features, n_bins, s);
+                      min_child_hess, recs + left, n_features, n_bins, s, pinned_dev, h_small,
+                      large == left ? 0 : 1);
     if (rc != GBDT_OK) return rc;
-    HIP_TRY(hipMemcpyAsync(pinned, recs + left, 2 * sizeof(gbdt_split_t), hipMemcpyDeviceToHost, s));
-    HIP_TRY(hipStreamSynchronize(s));
+    HIP_TRY(hipStreamSynchronize(s));  // the two records are in `pinned` as well
     par.left = left;
     par.right = right;
     host_recs[left] = pinned[0];

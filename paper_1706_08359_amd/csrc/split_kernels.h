@@ -89,11 +89,18 @@ __host__ __device__ inline int split_feature_bytes(int n_bins) { return 24 * spl
 //     groups, so "smaller candidate index" is "smaller feature".
 // grid.y = histogram of the call; histogram y starts hist_stride bins after histogram
 // y - 1 (the stride may be negative: any two histograms of a pool can be searched in
-// one launch).
+// one launch).  mirror (may be NULL): a second place for the records, page-locked host
+// memory that the device can write, so that a caller who must look at them on the host
+// needs no copy after the kernel, only to wait for it.
+// minus (may be NULL): histogram minus_y of the call is first replaced, in place, by itself
+// minus this one (the sibling by subtraction, element by element as hist_subtract_kernel does
+// it), and the result is searched: every (feature, bin) is read by exactly one workgroup, which
+// also writes the difference back.
 __global__ void __launch_bounds__(kSplitThreads)
-split_gain_kernel(const gbdt_bin_t* __restrict__ hist, int64_t hist_stride, int32_t n_features,
+split_gain_kernel(gbdt_bin_t* hist, int64_t hist_stride, int32_t n_features,
                   int32_t n_bins, int32_t group, double lambda, double min_child_hess,
-                  SplitCand* __restrict__ cand, gbdt_split_t* __restrict__ out) {
+                  SplitCand* __restrict__ cand, gbdt_split_t* __restrict__ out,
+                  gbdt_split_t* __restrict__ mirror, const gbdt_bin_t* minus, int32_t minus_y) {
   extern __shared__ __align__(16) unsigned char smem[];
   __shared__ double s_gain[kSplitThreads];
   __shared__ int32_t s_pair[kSplitThreads];
@@ -117,7 +124,17 @@ split_gain_kernel(const gbdt_bin_t* __restrict__ hist, int64_t hist_stride, int3
     const int fl = e / Bp;
     const int b = e - fl * Bp;
     gbdt_bin_t v = {0.0f, 0.0f, 0u};
-    if (b < B) v = hist[(size_t)(f0 + fl) * B + b];
+    if (b < B) {
+      const size_t at = (size_t)(f0 + fl) * B + b;
+      v = hist[at];
+      if (minus && (int32_t)blockIdx.y == minus_y) {
+        const gbdt_bin_t c = minus[at];
+        v.grad = v.grad - c.grad;
+        v.hess = v.hess - c.hess;
+        v.count = v.count - c.count;
+        hist[at] = v;
+      }
+    }
     pg[e] = (double)v.grad;
     ph[e] = (double)v.hess;
     pn[e] = (double)v.count;
@@ -286,6 +303,7 @@ split_gain_kernel(const gbdt_bin_t* __restrict__ hist, int64_t hist_stride, int3
       r.right_count = c.nr;
     }
     *out = r;
+    if (mirror) mirror[blockIdx.y] = r;
   }
 }
 
