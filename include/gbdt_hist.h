@@ -78,8 +78,12 @@ typedef struct {
  * per value; Sec. 4 "Data Structure": features are bundled so that one thread
  * loads a 4-byte group of one sample).  Rows are kept contiguous inside
  * feature tiles of 16, 32 or 64 bytes; 32 KiB of slack follow the last tile (the
- * build kernel may read, and ignore, whole row groups past the last row).
- * Returns 0 on invalid arguments.
+ * build kernel may read, and ignore, whole row groups past the last row).  Behind
+ * them the matrix is stored once more column by column, one byte per value
+ * (columns padded to a multiple of 256 rows): the row partition after a split reads
+ * one feature of every leaf row from there, a byte instead of a tile row.  The layout
+ * therefore takes about twice the bytes of the row-major matrix (three times with
+ * 4-bit bins).  Returns 0 on invalid arguments.
  */
 size_t gbdt_bins_packed_bytes(int64_t n_rows, int32_t n_features, int32_t n_bins);
 
@@ -89,9 +93,9 @@ size_t gbdt_bins_packed_bytes(int64_t n_rows, int32_t n_features, int32_t n_bins
  * unchanged).
  *   bins_rowmajor  DEVICE, uint8 [n_rows][n_features], every value < n_bins
  *   packed_out     DEVICE, gbdt_bins_packed_bytes(...) bytes, 16-byte aligned;
- *                  the tiles are fully overwritten (padding bytes are written as 0,
- *                  bin values are reduced modulo the kernel's bin capacity 16 / 64 /
- *                  256), the slack is left as it is
+ *                  the tiles and columns are fully overwritten (padding is written
+ *                  as 0, bin values are reduced modulo the kernel's bin capacity
+ *                  16 / 64 / 256), the slack is left as it is
  */
 int gbdt_bins_pack(const uint8_t* bins_rowmajor, int64_t n_rows, int32_t n_features,
                    int32_t n_bins, void* packed_out, void* stream);

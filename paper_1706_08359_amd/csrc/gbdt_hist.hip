@@ -161,10 +161,7 @@ int device_cu_count() {
 
 constexpr size_t kLdsPerCu = 160 * 1024;
 constexpr int kMinRowsPerChunk = kEpochRows;
-// Bytes behind the last tile that the build kernel may read (and ignore): its last
-// epoch of a root leaf fetches whole row groups, up to one epoch of rows of the widest
-// tile past the end.
-constexpr size_t kPackSlackBytes = (size_t)kEpochRows * 64;
+static_assert(kPlanSlackBytes == (int64_t)kEpochRows * 64, "slack behind the tiles: one epoch of the widest tile");
 constexpr int kBuildThreads = 512;  // threads per workgroup of every build kernel variant
 
 struct BuildGeom {
@@ -561,7 +558,7 @@ extern "C" {
 size_t gbdt_bins_packed_bytes(int64_t n_rows, int32_t n_features, int32_t n_bins) {
   if (!valid_shape(n_rows, n_features, n_bins)) return 0;
   const TilePlan p = make_tile_plan(n_features, n_bins);
-  return (size_t)n_rows * (size_t)p.row_bytes + kPackSlackBytes;
+  return (size_t)plan_packed_bytes(p, n_rows, n_features);
 }
 
 int gbdt_bins_pack(const uint8_t* bins_rowmajor, int64_t n_rows, int32_t n_features,
@@ -580,6 +577,14 @@ int gbdt_bins_pack(const uint8_t* bins_rowmajor, int64_t n_rows, int32_t n_featu
   hipLaunchKernelGGL(pack_kernel, dim3((unsigned)bx, (unsigned)tiles), dim3(256), 0,
                      (hipStream_t)stream, bins_rowmajor, n_rows, n_features, p,
                      (uint8_t*)packed_out);
+  HIP_TRY(hipGetLastError());
+  // the column-major copy behind the tiles
+  const int64_t rb = (n_rows + 63) / 64;
+  const int32_t fb = (n_features + 63) / 64;
+  if (fb > 65535) return GBDT_EUNSUPPORTED;
+  hipLaunchKernelGGL(pack_columns_kernel, dim3((unsigned)rb, (unsigned)fb), dim3(256), 0, (hipStream_t)stream,
+                     bins_rowmajor, n_rows, n_features, p.nib ? 15u : (uint32_t)(p.cap - 1),
+                     (uint8_t*)packed_out + plan_columns_base(p, n_rows), plan_column_stride(n_rows));
   HIP_TRY(hipGetLastError());
   return GBDT_OK;
 }

@@ -51,6 +51,38 @@ pack_kernel(const uint8_t* __restrict__ src, int64_t n_rows, int32_t n_features,
   *reinterpret_cast<uint32_t*>(dst + tile_off + r * w + 4 * j) = word;
 }
 
+// The column-major copy behind the tiles: a 64 x 64 block of the row-major matrix is read a
+// row at a time (a wavefront = 64 consecutive features of one row), turned in local memory,
+// and written a column at a time, four rows per thread.  grid = (row blocks, feature blocks).
+__global__ void __launch_bounds__(256)
+pack_columns_kernel(const uint8_t* __restrict__ src, int64_t n_rows, int32_t n_features, uint32_t mask,
+                    uint8_t* __restrict__ cols, int64_t stride) {
+  __shared__ uint8_t t[64][64 + 4];  // [feature][row]
+  const int tid = threadIdx.x;
+  const int64_t r0 = (int64_t)blockIdx.x * 64;
+  const int32_t f0 = (int32_t)blockIdx.y * 64;
+#pragma unroll 4
+  for (int i = 0; i < 16; ++i) {
+    const int rl = (tid >> 6) + 4 * i, fl = tid & 63;
+    const int64_t r = r0 + rl;
+    const int32_t f = f0 + fl;
+    uint32_t v = 0;
+    if (r < n_rows && f < n_features) v = src[r * n_features + f] & mask;
+    t[fl][rl] = (uint8_t)v;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int fl = (tid >> 4) + 16 * i, rq = (tid & 15) * 4;
+    const int32_t f = f0 + fl;
+    if (f < n_features) {  // rows past n_rows fall into the column's padding (stride >= r0 + 64)
+      const uint32_t w = (uint32_t)t[fl][rq] | ((uint32_t)t[fl][rq + 1] << 8) |
+                         ((uint32_t)t[fl][rq + 2] << 16) | ((uint32_t)t[fl][rq + 3] << 24);
+      *reinterpret_cast<uint32_t*>(cols + (int64_t)f * stride + r0 + rq) = w;
+    }
+  }
+}
+
 // ----------------------------------------------------------- histogram build kernel
 
 struct BuildArgs {

@@ -27,8 +27,11 @@ namespace {
 //   2. scatter pass: every workgroup sums the chunk counts before its own (at most
 //      kPartMaxChunks of them) to find where its rows start on either side, then ranks
 //      its rows inside the chunk from the flag words and writes the row ids.
-// The flag words save the second pass the scattered read of the bin matrix, which is
-// by far the larger part of the traffic (one 32- or 64-byte tile row per leaf row).
+// The split feature's bins come from the column-major copy of the matrix (tile_plan.h): one
+// byte per leaf row instead of a 32- or 64-byte tile row.  The flag words save the second
+// pass even that read.  (Leaves small enough for partition_one_kernel read the tiles instead:
+// their tile rows were fetched a moment ago, by the histogram build of the same leaf, and
+// are still in cache, while the column bytes would come from HBM.)
 constexpr int kPartThreads = 256;
 constexpr int kPartWaves = kPartThreads / 64;
 constexpr int kPartMaxChunks = 8192;
@@ -53,10 +56,12 @@ PartGeom make_part_geom(int64_t n_leaf) {
   return g;
 }
 
-// Where the bin of the split feature sits in a row of the packed matrix, and the test
-// "this leaf position goes left".
+// Where the bins of the split feature sit in the packed matrix -- in the column-major copy,
+// or in the feature's tile -- and the test "this leaf position goes left".
 struct SplitColumn {
   bool has_split;    // false: the record holds no split, every row goes left
+  bool from_tiles;
+  int64_t col_off;   // byte offset of the feature's column
   int64_t tile_off;  // byte offset of the feature's tile
   int32_t w, col;    // tile width; byte of the tile row
   int32_t shift;     // 4-bit bins: the nibble
@@ -66,17 +71,20 @@ struct SplitColumn {
 
 __device__ __forceinline__ SplitColumn split_column(const gbdt_split_t* __restrict__ split,
                                                     const TilePlan& plan, int64_t n_rows,
-                                                    int32_t n_features) {
+                                                    int32_t n_features, bool from_tiles = false) {
   SplitColumn c;
   const int32_t f = split->feature;
   c.thr = split->bin;
   c.has_split = f >= 0 && f < n_features;
+  c.from_tiles = from_tiles;
+  c.col_off = 0;
   c.tile_off = 0;
   c.w = plan.wm;
   c.col = 0;
   c.shift = 0;
   c.mask = 0xffu;
   if (c.has_split) {
+    c.col_off = plan_columns_base(plan, n_rows) + (int64_t)f * plan_column_stride(n_rows);
     const int32_t fb = plan.nib ? (f >> 1) : f;
     int32_t t = fb / plan.wm;
     if (t > plan.n_main) t = plan.n_main;
@@ -98,6 +106,7 @@ __device__ __forceinline__ bool goes_left(const SplitColumn& c, const uint8_t* _
   if (!c.has_split) return true;
   int64_t r = idx ? (int64_t)idx[e] : e;
   r = r < 0 ? 0 : (r >= n_rows ? n_rows - 1 : r);  // a bad row id must not fault
+  if (!c.from_tiles) return (int32_t)packed[c.col_off + r] <= c.thr;
   const uint32_t b = ((uint32_t)packed[c.tile_off + r * c.w + c.col] >> c.shift) & c.mask;
   return (int32_t)b <= c.thr;
 }
@@ -287,7 +296,7 @@ partition_one_kernel(const uint8_t* __restrict__ packed, int64_t n_rows, int32_t
                      int64_t* __restrict__ n_left_out) {
   __shared__ uint64_t s_flags[kPartOneSteps * kPartWaves];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const SplitColumn sc = split_column(split, plan, n_rows, n_features);
+  const SplitColumn sc = split_column(split, plan, n_rows, n_features, /*from_tiles=*/true);
   const int32_t steps = (n_leaf + kPartThreads - 1) / kPartThreads;
   for (int32_t k = 0; k < steps; ++k) {
     const uint64_t m = __ballot(goes_left(sc, packed, n_rows, idx, (int64_t)k * kPartThreads + tid, n_leaf));

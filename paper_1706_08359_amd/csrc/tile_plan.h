@@ -13,6 +13,15 @@
 // All tiles have the "main" width WM except possibly the last one, which is 16
 // or 32 bytes wide when few feature bytes remain (so that padding stays small).
 //
+// Behind the tiles, and a slack the build kernels may read (and ignore) past the last
+// tile, the matrix is stored ONCE MORE, column by column, one byte per value:
+//
+//   packed = [tiles][slack][column 0: stride bytes][column 1] ...     stride = n_rows rounded up to 256
+//
+// The row partition after a split looks at ONE feature of every row of a leaf; from the
+// tiles that costs a whole 32- or 64-byte tile row per row, from a column one byte.  The
+// copy doubles the resident matrix (triples it with 4-bit bins) -- memory this part has.
+//
 // Inside a tile, a lane loads VEC consecutive bytes of a row (W / 4 with 8-bit bins;
 // 4 or 8 with 4-bit bins), so a row is LPR = W / VEC = 4 or 8 lane-chunks.  Byte i of the tile row
 // is byte bl = i % VEC of lane-chunk j = i / VEC.  The lane splits its bytes
@@ -64,6 +73,18 @@ GBDT_HD TilePlan make_tile_plan(int32_t n_features, int32_t n_bins) {
   }
   p.row_bytes = p.n_main * p.wm + p.wr;
   return p;
+}
+
+// Bytes behind the last tile that the build kernel may read (and ignore): its last epoch
+// of a root leaf fetches whole row groups, up to one epoch (512 rows) of the widest tile
+// past the end.
+constexpr int64_t kPlanSlackBytes = 512 * 64;
+GBDT_HD int64_t plan_column_stride(int64_t n_rows) { return (n_rows + 255) / 256 * 256; }
+GBDT_HD int64_t plan_columns_base(const TilePlan& p, int64_t n_rows) {
+  return (n_rows * (int64_t)p.row_bytes + kPlanSlackBytes + 255) / 256 * 256;
+}
+GBDT_HD int64_t plan_packed_bytes(const TilePlan& p, int64_t n_rows, int32_t n_features) {
+  return plan_columns_base(p, n_rows) + (int64_t)n_features * plan_column_stride(n_rows);
 }
 
 GBDT_HD int32_t plan_n_tiles(const TilePlan& p) { return p.n_main + (p.wr ? 1 : 0); }

@@ -194,22 +194,18 @@ def _events(torch):
 def partition(args, torch, B, synth, dev):
     """gbdt_partition_rows (flag pass + scatter pass) on the root and on an index-list leaf of
     every workload, split on a middle feature at the middle bin.  Bytes: what the step must
-    move (row id in if listed, one bin value, row id out) and what a row-major tile layout
-    makes it fetch (the whole tile row that holds the bin value)."""
+    move -- row id in (if listed), one bin value from the column-major copy, row id out."""
     print("| workload | leaf | leaf rows | call ms (median) | call ms (min) | G rows/s | "
-          "algorithmic MB | tile-row MB fetched | tile-row GB/s |")
-    print("|" + "---|" * 9, flush=True)
+          "algorithmic MB | algorithmic GB/s |")
+    print("|" + "---|" * 8, flush=True)
     for name, make in WORKLOADS.items():
         if args.only and name not in args.only:
             continue
         w = make(synth, dev)
         n, F, nb = w.n_rows, w.n_features, w.n_bins
         packed = B.gbdt_bins_pack(w.bins, nb)
-        geo = B.gbdt_debug_geometry(F, nb, n)
         f = F // 2
         rec = B.split_record(f, nb // 2 - 1, dev)
-        tile, _ = B.gbdt_debug_locate(F, nb, f)
-        width = geo["wm"] if tile < geo["n_main"] else geo["wr"]
         half = torch.nonzero(w.bins[:, 0] <= (nb - 1) // 2).flatten().to(torch.int32)
         out = torch.empty(n, dtype=torch.int32, device=dev)
         n_left = torch.empty(1, dtype=torch.int64, device=dev)
@@ -225,10 +221,9 @@ def partition(args, torch, B, synth, dev):
                 if rep >= 3:
                     times.append(e0.elapsed_time(e1))
             med, mn = statistics.median(times), min(times)
-            alg = n_leaf * ((4 if leaf is not None else 0) + (0.5 if nb <= 16 else 1.0) + 4)
-            tile_bytes = n_leaf * (width + 4 + (8 if leaf is not None else 4))
+            alg = n_leaf * ((4 if leaf is not None else 0) + 1 + 4)
             print(f"| {name} | {leaf_name} | {n_leaf:,} | {med:.4f} | {mn:.4f} | {n_leaf / (med * 1e-3) / 1e9:.1f} | "
-                  f"{alg / 1e6:.1f} | {tile_bytes / 1e6:.1f} | {tile_bytes / (med * 1e-3) / 1e9:,.0f} |", flush=True)
+                  f"{alg / 1e6:.1f} | {alg / (med * 1e-3) / 1e9:,.0f} |", flush=True)
         del w, packed, half, out
         torch.cuda.empty_cache()
 
