@@ -186,8 +186,11 @@ def test_batched_launch_plan_covers_every_leaf_exactly(n_features, n_bins, wg_pe
             if n_epochs == 0:
                 assert wgs[l] == 0
                 continue
-            assert 1 <= wgs[l] <= n_epochs and 1 <= ue[l] <= 4
+            # units of 4 epochs, or an even split with one longer unit per workgroup (at most 3 x 4)
+            assert 1 <= wgs[l] <= n_epochs and 1 <= ue[l] <= 12
             n_units = -(-n_epochs // int(ue[l]))
+            if ue[l] > 4:
+                assert n_units == wgs[l]
             assert wgs[l] <= n_units                             # no workgroup without a unit
             # workgroup c takes units c, c + wgs, ...: together all units, each once
             taken = sorted(u for c in range(wgs[l]) for u in range(c, n_units, int(wgs[l])))
