@@ -299,3 +299,21 @@ def test_partition_batch_equals_oracle_leaf_by_leaf(shape):
         ref_l, ref_r = orc.partition_rows(bins, int(feats[l]), int(thrs[l]), rows)
         assert nl[l] == ref_l.size, (l, nl[l], ref_l.size)
         assert np.array_equal(seg[:ref_l.size], ref_l) and np.array_equal(seg[ref_l.size:], ref_r), l
+
+
+@pytest.mark.parametrize("n_rows,n_features,n_bins", [(1, 1, 2), (63, 5, 16), (1000, 28, 64), (4099, 137, 255),
+                                                      (2500, 257, 15), (70_001, 65, 63)])
+def test_packed_layout_holds_a_column_major_copy(n_rows, n_features, n_bins):
+    """Behind the tiles and their slack gbdt_bins_pack stores every feature once more as a column
+    of bytes (padded to a multiple of 256 rows): the bytes there are the matrix, transposed."""
+    rng = np.random.default_rng(n_rows + n_features)
+    bins = rng.integers(0, n_bins, size=(n_rows, n_features), dtype=np.uint8)
+    packed = B.gbdt_bins_pack(torch.from_numpy(bins).to("cuda:0"), n_bins)
+    torch.cuda.synchronize()
+    g = B.gbdt_debug_geometry(n_features, n_bins, n_rows)
+    base = (n_rows * g["row_bytes"] + 512 * 64 + 255) // 256 * 256
+    stride = (n_rows + 255) // 256 * 256
+    assert packed.numel() == B.gbdt_bins_packed_bytes(n_rows, n_features, n_bins) == base + n_features * stride
+    cols = packed.cpu().numpy()[base:base + n_features * stride].reshape(n_features, stride)
+    assert np.array_equal(cols[:, :n_rows], bins.T)
+    assert not cols[:, n_rows:(n_rows + 63) // 64 * 64].any()      # the written part of the padding is zero
