@@ -194,7 +194,8 @@ __device__ __forceinline__ void partition_scatter_chunk(const int32_t* __restric
       const int32_t r = idx ? idx[e] : (int32_t)e;
       const int64_t lefts_before_e = wave_base + __popcll(m & below);
       const bool left = (m >> lane) & 1ull;
-      out[left ? lefts_before_e : total + (e - lefts_before_e)] = r;
+      // (streaming store: the list is written once, front to back on either side)
+      __builtin_nontemporal_store(r, &out[left ? lefts_before_e : total + (e - lefts_before_e)]);
     }
   }
 }
