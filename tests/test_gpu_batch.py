@@ -300,3 +300,68 @@ def test_batched_calls_with_caller_scratch():
             _check_batch(p, lists, "too small")
     finally:
         B.gbdt_set_workspace(None)
+
+
+def test_graph_capture_of_a_level_step_replays_like_eager():
+    """One step of level-wise growth with fixed leaf sizes -- batched build of four leaves, one
+    split search over their histograms, the root's split and the partition of the rows by it --
+    captured into a graph and replayed with changing gradients; every replay is compared with
+    the same calls made eagerly (all of them enqueue only: no memset nodes, no waits)."""
+    rng = np.random.default_rng(3)
+    n, F, nb = 120_000, 137, 255
+    bins = rng.integers(0, nb, size=(n, F), dtype=np.uint8)
+    grad = rng.normal(size=n).astype(np.float32)
+    hess = rng.uniform(0.01, 1.0, size=n).astype(np.float32)
+    p = GpuProblem(bins, nb, grad, hess)
+    perm = rng.permutation(n).astype(np.int32)
+    sizes = [50_000, 1_500, 0, 30_000]
+    offs = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    rows = torch.from_numpy(np.concatenate([np.sort(perm[offs[i]:offs[i + 1]]) for i in range(4)])).to(p.dev)
+
+    def make_out():
+        return (torch.empty((4, F, nb, 3), dtype=torch.float32, device=p.dev),
+                torch.empty((4, 9), dtype=torch.int32, device=p.dev),
+                torch.empty((F, nb, 3), dtype=torch.float32, device=p.dev),
+                torch.empty(9, dtype=torch.int32, device=p.dev),
+                torch.empty(n, dtype=torch.int32, device=p.dev),
+                torch.empty(1, dtype=torch.int64, device=p.dev))
+
+    def step(hists, splits, root, root_split, kids, n_left):
+        B.gbdt_hist_build_batch(p.packed, n, F, nb, rows, offs, p.grad, p.hess, hist_out=hists)
+        B.gbdt_best_split_batch(hists, 1.0, 1e-3, splits_out=splits)
+        B.gbdt_hist_build(p.packed, n, F, nb, None, n, p.grad, p.hess, hist_out=root)
+        B.gbdt_best_split(root, 1.0, 1e-3, split_out=root_split)
+        B.gbdt_partition_rows(p.packed, n, F, nb, None, n, root_split, children_out=kids, n_left_out=n_left)
+
+    B.gbdt_set_deterministic(True)            # replays are compared bit for bit
+    try:
+        g_out, e_out = make_out(), make_out()
+        step(*g_out)                          # warm-up: scratch and occupancy queries outside the capture
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step(*g_out)
+        for trial in range(3):
+            p.grad.mul_(-1.1).add_(0.02 * trial)
+            p.hess.mul_(0.95).add_(0.03)
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            step(*e_out)
+            torch.cuda.synchronize()
+            for a, b in zip(g_out, e_out):
+                assert torch.equal(a.view(torch.int32) if a.dtype == torch.float32 else a,
+                                   b.view(torch.int32) if b.dtype == torch.float32 else b), trial
+        # the last replay against the oracle: one leaf's histogram and the root's children
+        idx = rows[:sizes[0]].cpu().numpy()
+        ref = orc.hist_build(bins, nb, p.grad.cpu().numpy(), p.hess.cpu().numpy(), idx)
+        g64 = p.grad[torch.from_numpy(idx).long().to(p.dev)].double()
+        h64 = p.hess[torch.from_numpy(idx).long().to(p.dev)].double()
+        assert_hist_close(B.hist_to_numpy(g_out[0][0]), ref, g64.abs().sum().item(), h64.abs().sum().item(), "graph")
+        s = B.split_to_dict(g_out[3])
+        ref_l, ref_r = orc.partition_rows(bins, s["feature"], s["bin"])
+        kids = g_out[4].cpu().numpy()
+        assert int(g_out[5].item()) == ref_l.size
+        assert np.array_equal(kids[:ref_l.size], ref_l) and np.array_equal(kids[ref_l.size:], ref_r)
+    finally:
+        B.gbdt_set_deterministic(False)
