@@ -70,9 +70,47 @@ __device__ __forceinline__ int32_t load_cand_feature(const SplitCand* src) {
 }
 
 // LDS bytes one feature needs in split_gain_kernel: fp64 running sums of gradient,
-// hessian and count per bin (bins padded to a multiple of 8), + the feature's parent term.
-__host__ __device__ inline int split_padded_bins(int n_bins) { return (n_bins + 7) & ~7; }
+// hessian and count per bin (bins padded to a multiple of kSplitBlock), + the feature's parent term.
+constexpr int kSplitBlock = 16;  // bins the prefix loop adds per register block
+__host__ __device__ inline int split_padded_bins(int n_bins) { return (n_bins + kSplitBlock - 1) & ~(kSplitBlock - 1); }
 __host__ __device__ inline int split_feature_bytes(int n_bins) { return 24 * split_padded_bins(n_bins) + 8; }
+
+// Arg-max over the threads of a workgroup under the order "larger gain, then smaller index"
+// (index < 0: no candidate): exchanges inside each wavefront, then the four wavefront
+// results through local memory.  The order is total, so the result does not depend on how
+// the comparisons are arranged.  Every thread returns with the winner in (gain, idx).
+__device__ __forceinline__ void block_argmax(double& gain, int32_t& idx, double* s_gain, int32_t* s_idx) {
+  auto better = [](double g2, int32_t i2, double g1, int32_t i1) {
+    return i2 >= 0 && (i1 < 0 || g2 > g1 || (g2 == g1 && i2 < i1));
+  };
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const double g2 = __shfl_xor(gain, o);
+    const int32_t i2 = __shfl_xor(idx, o);
+    if (better(g2, i2, gain, idx)) {
+      gain = g2;
+      idx = i2;
+    }
+  }
+  const int wave = threadIdx.x >> 6;
+  if ((threadIdx.x & 63) == 0) {
+    s_gain[wave] = gain;
+    s_idx[wave] = idx;
+  }
+  __syncthreads();
+  gain = s_gain[0];
+  idx = s_idx[0];
+#pragma unroll
+  for (int w = 1; w < kSplitThreads / 64; ++w) {
+    const double g2 = s_gain[w];
+    const int32_t i2 = s_idx[w];
+    if (better(g2, i2, gain, idx)) {
+      gain = g2;
+      idx = i2;
+    }
+  }
+  __syncthreads();  // the scratch may be reused
+}
 
 // Gain scan of Sec. 3.3.  A workgroup takes a group of consecutive features.
 //  1. Their histogram rows are copied into local memory as doubles.
@@ -102,8 +140,8 @@ split_gain_kernel(gbdt_bin_t* hist, int64_t hist_stride, int32_t n_features,
                   SplitCand* __restrict__ cand, gbdt_split_t* __restrict__ out,
                   gbdt_split_t* __restrict__ mirror, const gbdt_bin_t* minus, int32_t minus_y) {
   extern __shared__ __align__(16) unsigned char smem[];
-  __shared__ double s_gain[kSplitThreads];
-  __shared__ int32_t s_pair[kSplitThreads];
+  __shared__ double s_gain[kSplitThreads / 64];
+  __shared__ int32_t s_pair[kSplitThreads / 64];
   __shared__ int s_last;
   const int tid = threadIdx.x;
   hist += (int64_t)blockIdx.y * hist_stride;
@@ -142,28 +180,43 @@ split_gain_kernel(gbdt_bin_t* hist, int64_t hist_stride, int32_t n_features,
   __syncthreads();
 
   // 2. running sums in place, strictly left to right, one lane per (statistic, feature).
-  // The loop is bound by LDS latency: the next 8 values are requested before the current
-  // 8 are added and written back.
+  // The chain of dependent fp64 adds is the critical path (about 30 cycles a link).  Two
+  // register blocks of kSplitBlock bins are used in turn, without copies: while one is added
+  // and written back, the other one's values are on their way from local memory.
   if (tid < 3 * nf) {
     const int st = tid / nf;
     const int fl = tid - st * nf;
     double* p = pg + ((size_t)st * group + fl) * Bp;
-    double cur[8], nxt[8];
+    double va[kSplitBlock], vb[kSplitBlock];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) cur[i] = p[i];
+    for (int i = 0; i < kSplitBlock; ++i) va[i] = p[i];
     double acc = 0.0;
-    for (int b0 = 0; b0 < Bp; b0 += 8) {
-      if (b0 + 8 < Bp) {
+    for (int b0 = 0; b0 < Bp; b0 += 2 * kSplitBlock) {
+      const bool has_b = b0 + kSplitBlock < Bp;
+      if (has_b) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) nxt[i] = p[b0 + 8 + i];
+        for (int i = 0; i < kSplitBlock; ++i) vb[i] = p[b0 + kSplitBlock + i];
       }
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        acc = acc + cur[i];
-        p[b0 + i] = acc;
+      for (int i = 0; i < kSplitBlock; ++i) {
+        acc = acc + va[i];
+        va[i] = acc;
       }
 #pragma unroll
-      for (int i = 0; i < 8; ++i) cur[i] = nxt[i];
+      for (int i = 0; i < kSplitBlock; ++i) p[b0 + i] = va[i];
+      if (b0 + 2 * kSplitBlock < Bp) {
+#pragma unroll
+        for (int i = 0; i < kSplitBlock; ++i) va[i] = p[b0 + 2 * kSplitBlock + i];
+      }
+      if (has_b) {
+#pragma unroll
+        for (int i = 0; i < kSplitBlock; ++i) {
+          acc = acc + vb[i];
+          vb[i] = acc;
+        }
+#pragma unroll
+        for (int i = 0; i < kSplitBlock; ++i) p[b0 + kSplitBlock + i] = vb[i];
+      }
     }
   }
   __syncthreads();
@@ -193,26 +246,10 @@ split_gain_kernel(gbdt_bin_t* hist, int64_t hist_stride, int32_t n_features,
       }
     }
   }
-  s_gain[tid] = best_gain;
-  s_pair[tid] = best_pair;
-  __syncthreads();
-  for (int s = kSplitThreads / 2; s > 0; s >>= 1) {
-    if (tid < s) {
-      const double g2 = s_gain[tid + s];
-      const int32_t p2 = s_pair[tid + s];
-      const double g1 = s_gain[tid];
-      const int32_t p1 = s_pair[tid];
-      const bool take = p2 >= 0 && (p1 < 0 || g2 > g1 || (g2 == g1 && p2 < p1));
-      if (take) {
-        s_gain[tid] = g2;
-        s_pair[tid] = p2;
-      }
-    }
-    __syncthreads();
-  }
+  block_argmax(best_gain, best_pair, s_gain, s_pair);
   if (tid == 0) {
     SplitCand c;
-    const int32_t e = s_pair[0];
+    const int32_t e = best_pair;
     if (e < 0) {
       c.gain = 0.0;
       c.gl = c.hl = c.gr = c.hr = 0.0;
@@ -222,7 +259,7 @@ split_gain_kernel(gbdt_bin_t* hist, int64_t hist_stride, int32_t n_features,
     } else {
       const int fl = e / (B - 1);
       const int t = e - fl * (B - 1);
-      c.gain = s_gain[0];
+      c.gain = best_gain;
       c.gl = pg[fl * Bp + t];
       c.hl = ph[fl * Bp + t];
       c.nl = (uint32_t)pn[fl * Bp + t];
@@ -264,26 +301,10 @@ split_gain_kernel(gbdt_bin_t* hist, int64_t hist_stride, int32_t n_features,
       }
     }
   }
-  s_gain[tid] = bg;
-  s_pair[tid] = bi;
-  __syncthreads();
-  for (int s = kSplitThreads / 2; s > 0; s >>= 1) {
-    if (tid < s) {
-      const double g2 = s_gain[tid + s];
-      const int32_t i2 = s_pair[tid + s];
-      const double g1 = s_gain[tid];
-      const int32_t i1 = s_pair[tid];
-      const bool take = i2 >= 0 && (i1 < 0 || g2 > g1 || (g2 == g1 && i2 < i1));
-      if (take) {
-        s_gain[tid] = g2;
-        s_pair[tid] = i2;
-      }
-    }
-    __syncthreads();
-  }
+  block_argmax(bg, bi, s_gain, s_pair);
   if (tid == 0) {
     gbdt_split_t r;
-    const int32_t i = s_pair[0];
+    const int32_t i = bi;
     if (i < 0) {
       r.feature = -1;
       r.bin = -1;
