@@ -27,9 +27,19 @@
  *  - Bins are 0-based: a binned value b satisfies 0 <= b < n_bins (the paper
  *    writes 1..k).  2 <= n_bins <= 256.
  *  - The library keeps one scratch workspace per process (partial histograms,
- *    split candidates, partition flags).  Calls that use it (gbdt_hist_build[_batch],
- *    gbdt_best_split[_batch], gbdt_partition_rows) must not run concurrently on
- *    different streams.
+ *    split candidates, partition flags) and a few process-wide counters in device
+ *    memory.  Calls that use them (gbdt_hist_build[_batch], gbdt_best_split[_batch],
+ *    gbdt_partition_rows[_batch], the tree growers) must be issued on ONE stream at a
+ *    time: two such calls in flight on different streams, or from two threads, race.
+ *    When the library owns the scratch it grows it on demand: a call that needs more
+ *    allocates a larger buffer (hipMalloc) and keeps the old one until gbdt_reset; it never
+ *    frees or synchronises inside an enqueuing call.  During stream capture growing is
+ *    refused (GBDT_ENOMEM): issue the same call once outside the capture first, or register
+ *    a caller buffer (gbdt_set_workspace).
+ *  - Size limits: n_rows < 2^30, and byte offsets inside a feature tile are 32-bit:
+ *    (n_rows + 512) x tile width < 2^32, i.e. n_rows < 67,108,352 with up to 64 bins
+ *    (64-byte tiles) and n_rows < 134,217,216 with more (32-byte tiles); at most 65,535
+ *    feature tiles.  Beyond that: GBDT_EUNSUPPORTED.
  */
 #ifndef GBDT_HIST_H_
 #define GBDT_HIST_H_
@@ -386,6 +396,22 @@ const char* gbdt_last_hip_error(void);
  */
 int gbdt_profile_enable(int enable);
 int gbdt_profile_collect(double* build_kernel_ms_total, int64_t* n_launches);
+/* The same, launch by launch: ms_out[i] receives the duration of the i-th recorded build
+ * kernel (the first `capacity` of them), *n_launches their number; the events are forgotten. */
+int gbdt_profile_durations(double* ms_out, int64_t capacity, int64_t* n_launches);
+
+/*
+ * Back to a clean state after a failure: WAITS for the device, frees the library-owned
+ * scratch (including buffers it outgrew: growing never frees, so that an enqueuing call
+ * never synchronises) and forgets pending profiling events, then sets the split search's
+ * ticket counters and what is known about the unit counters back to "unknown", so that the
+ * next call clears what it uses.  A caller-registered workspace stays registered.  Needed
+ * only after a call failed half-way (GBDT_EHIP, or GBDT_ENOMEM from a too-small caller
+ * workspace between the kernels of one call): a build whose reduction pass never ran leaves
+ * unit counters counted up, and later histograms would silently miss rows.  The modes set by
+ * gbdt_set_deterministic / gbdt_set_wide_accumulation are kept.
+ */
+int gbdt_reset(void);
 
 /*
  * A plain copy kernel of known HBM traffic (bytes read + bytes written), used to scale

@@ -26,7 +26,7 @@ EXPORTS = [
     "gbdt_hist_build_batch", "gbdt_hist_build_batch_workspace_bytes", "gbdt_best_split_batch",
     "gbdt_debug_batch_plan", "gbdt_grow_tree", "gbdt_grow_tree_scratch_bytes",
     "gbdt_partition_rows_batch", "gbdt_grow_tree_depthwise", "gbdt_grow_tree_depthwise_scratch_bytes",
-    "gbdt_set_wide_accumulation",
+    "gbdt_set_wide_accumulation", "gbdt_profile_durations", "gbdt_reset",
 ]
 
 # numpy views of the two C structs
@@ -63,6 +63,10 @@ def load():
     lib.gbdt_hist_build.restype = c.c_int
     lib.gbdt_hist_build.argtypes = [c.c_void_p, c.c_int64, c.c_int32, c.c_int32, c.c_void_p,
                                     c.c_int64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p]
+    lib.gbdt_profile_durations.restype = c.c_int
+    lib.gbdt_profile_durations.argtypes = [c.POINTER(c.c_double), c.c_int64, c.POINTER(c.c_int64)]
+    lib.gbdt_reset.restype = c.c_int
+    lib.gbdt_reset.argtypes = []
     lib.gbdt_hist_subtract.restype = c.c_int
     lib.gbdt_hist_subtract.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32, c.c_int32,
                                        c.c_void_p]
@@ -128,7 +132,7 @@ def _check(rc: int, what: str) -> None:
         lib = load()
         msg = lib.gbdt_strerror(rc).decode()
         hip = lib.gbdt_last_hip_error().decode()
-        raise GbdtError(f"{what}: {msg} ({rc})" + (f" [{hip}]" if hip and rc == -3 else ""))
+        raise GbdtError(f"{what}: {msg} ({rc})" + (f" [{hip}]" if hip and rc in (-2, -3, -4) else ""))
 
 
 def _stream(stream) -> int:
@@ -184,7 +188,7 @@ def gbdt_bins_pack(bins_rowmajor: torch.Tensor, n_bins: int, packed_out=None, st
 
 
 def gbdt_hist_build(bin_matrix, n_rows, n_features, n_bins, leaf_row_idx, n_leaf_rows, grad, hess,
-                    hist_out=None, stream=None):
+                    hist_out=None, stream=None, _entry="gbdt_hist_build"):
     """Returns hist_out: float32 CUDA tensor [n_features, n_bins, 3] holding gbdt_bin_t records
     (the third word of each record is the uint32 count; see hist_to_numpy)."""
     if hist_out is None:
@@ -198,12 +202,16 @@ def gbdt_hist_build(bin_matrix, n_rows, n_features, n_bins, leaf_row_idx, n_leaf
         raise GbdtError("bin_matrix smaller than the packed layout of this shape")
     if hist_out.numel() < n_features * n_bins * 3:
         raise GbdtError("hist_out too small")
-    _check(load().gbdt_hist_build(_dev(bin_matrix, torch.uint8, "bin_matrix"), n_rows, n_features,
-                                  n_bins, idx_p, n_leaf_rows, _dev(grad, torch.float32, "grad"),
-                                  _dev(hess, torch.float32, "hess"),
-                                  _dev(hist_out, torch.float32, "hist_out"), _stream(stream)),
-           "gbdt_hist_build")
+    _check(getattr(load(), _entry)(_dev(bin_matrix, torch.uint8, "bin_matrix"), n_rows, n_features,
+                                   n_bins, idx_p, n_leaf_rows, _dev(grad, torch.float32, "grad"),
+                                   _dev(hess, torch.float32, "hess"),
+                                   _dev(hist_out, torch.float32, "hist_out"), _stream(stream)),
+           _entry)
     return hist_out
+
+
+def gbdt_reset() -> None:
+    _check(load().gbdt_reset(), "gbdt_reset")
 
 
 def gbdt_hist_build_batch(bin_matrix, n_rows, n_features, n_bins, row_idx, leaf_offsets, grad, hess,
@@ -469,6 +477,16 @@ def gbdt_profile_collect():
     ms, n = ctypes.c_double(), ctypes.c_int64()
     _check(load().gbdt_profile_collect(ctypes.byref(ms), ctypes.byref(n)), "gbdt_profile_collect")
     return ms.value, n.value
+
+
+def gbdt_profile_durations():
+    """Build-kernel milliseconds of every launch recorded since the last collect, in launch order."""
+    lib = load()
+    cap = 1 << 16
+    buf = (ctypes.c_double * cap)()
+    n = ctypes.c_int64()
+    _check(lib.gbdt_profile_durations(buf, cap, ctypes.byref(n)), "gbdt_profile_durations")
+    return [buf[i] for i in range(min(n.value, cap))]
 
 
 # ---- host-side views of results (copies to the host; synchronises) -----------------

@@ -73,6 +73,7 @@ struct Workspace {
   void* own = nullptr;  // library-owned scratch
   size_t own_bytes = 0;
   int own_device = -1;
+  std::vector<void*> retired;  // outgrown library buffers: work enqueued earlier may still use them
   void* user = nullptr;  // caller-registered scratch
   size_t user_bytes = 0;
   void* zeroed = nullptr;  // the buffer whose counter head is known to be all zero
@@ -84,38 +85,56 @@ Workspace g_ws;
 constexpr int kCounterSlots = 65536;
 constexpr size_t kWsHeadBytes = (size_t)kCounterSlots * sizeof(uint32_t);
 
-// Returns a scratch pointer of at least `bytes`, growing the library-owned buffer
-// when no caller buffer is registered.  counters_out: the counter head of the same
-// buffer; *counters_zero_out: whether it is known to be all zero.
-int get_workspace(size_t bytes, void** out, uint32_t** counters_out = nullptr,
+bool stream_is_capturing(hipStream_t s) {
+  hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(s, &cs) != hipSuccess) {
+    (void)hipGetLastError();
+    return false;
+  }
+  return cs == hipStreamCaptureStatusActive;
+}
+
+// Returns a scratch pointer of at least `bytes` for work enqueued on stream s, growing
+// the library-owned buffer when no caller buffer is registered.  Growing allocates a
+// new buffer and RETIRES the old one (kernels enqueued earlier may still use it; retired
+// buffers are freed by gbdt_reset): no synchronisation, no free inside an enqueuing
+// call.  It is refused (GBDT_ENOMEM) while s is being captured into a graph, where an
+// allocation is not allowed: run the same call once outside the capture first, or
+// register a caller buffer.  counters_out: the counter head of the same buffer;
+// *counters_zero_out: whether it is known to be all zero.
+int get_workspace(size_t bytes, hipStream_t s, void** out, uint32_t** counters_out = nullptr,
                   bool* counters_zero_out = nullptr) {
   std::lock_guard<std::mutex> lk(g_ws.mu);
   bytes += kWsHeadBytes;
   void* base = nullptr;
   if (g_ws.user) {
-    if (bytes > g_ws.user_bytes) return GBDT_ENOMEM;
+    if (bytes > g_ws.user_bytes) {
+      snprintf(g_hip_err, sizeof g_hip_err, "caller workspace of %zu bytes, %zu needed", g_ws.user_bytes, bytes);
+      return GBDT_ENOMEM;
+    }
     base = g_ws.user;
   } else {
     int dev = 0;
     HIP_TRY(hipGetDevice(&dev));
-    if (g_ws.own && (g_ws.own_device != dev || g_ws.own_bytes < bytes)) {
-      HIP_TRY(hipDeviceSynchronize());  // earlier work may still use the old buffer
-      HIP_TRY(hipFree(g_ws.own));
-      if (g_ws.zeroed == g_ws.own) g_ws.zeroed = nullptr;
-      g_ws.own = nullptr;
-      g_ws.own_bytes = 0;
-    }
-    if (!g_ws.own) {
+    if (!g_ws.own || g_ws.own_device != dev || g_ws.own_bytes < bytes) {
+      if (stream_is_capturing(s)) {
+        snprintf(g_hip_err, sizeof g_hip_err,
+                 "library scratch must grow to %zu bytes, which is not possible during stream capture", bytes);
+        return GBDT_ENOMEM;
+      }
       size_t want = bytes < (size_t)(1 << 20) ? (size_t)(1 << 20) : bytes;
-      hipError_t e = hipMalloc(&g_ws.own, want);
+      if (g_ws.own && g_ws.own_device == dev && want < 2 * g_ws.own_bytes) want = 2 * g_ws.own_bytes;
+      void* fresh = nullptr;
+      hipError_t e = hipMalloc(&fresh, want);
+      if (e != hipSuccess && want > bytes) e = hipMalloc(&fresh, want = bytes);
       if (e != hipSuccess) {
-        g_ws.own = nullptr;
         hip_fail(e, "hipMalloc(workspace)");
         return GBDT_ENOMEM;
       }
+      if (g_ws.own) g_ws.retired.push_back(g_ws.own);
+      g_ws.own = fresh;
       g_ws.own_bytes = want;
       g_ws.own_device = dev;
-      g_ws.zeroed = nullptr;
     }
     base = g_ws.own;
   }
@@ -229,7 +248,7 @@ void plan_leaf_units(int64_t n_epochs, int64_t budget, int* wgs_out, int* unit_e
 // workgroups per CU of the kernel variant as reported by the runtime (<= 0: estimate
 // from the LDS footprint alone).
 BuildGeom make_geom(int32_t n_features, int32_t n_bins, int64_t n_leaf, int cus,
-                    int wg_per_cu_hint, bool wide = false) {
+                    int wg_per_cu_hint, bool wide = false, int64_t max_wgs = (int64_t)1 << 40) {
   BuildGeom g;
   g.plan = make_tile_plan(n_features, n_bins);
   const TilePlan& p = g.plan;
@@ -249,7 +268,9 @@ BuildGeom make_geom(int32_t n_features, int32_t n_bins, int64_t n_leaf, int cus,
   const int64_t n_epochs = (n_leaf + kEpochRows - 1) / kEpochRows;
   // (A narrow tile's epochs are cheaper, but not by much: the per-epoch overhead does
   // not shrink with the tile.  It gets as many workgroups as a main tile.)
-  plan_leaf_units(n_epochs, resident / n_tiles, &g.wgs, &g.unit_epochs, &g.one_unit_each);
+  int64_t budget = resident / n_tiles;
+  if (budget > max_wgs) budget = max_wgs;
+  plan_leaf_units(n_epochs, budget, &g.wgs, &g.unit_epochs, &g.one_unit_each);
   g.partial_words = ((size_t)p.n_main * g.wgs * main_block +
                      (size_t)(p.wr ? g.wgs : 0) * 3 * (p.wr ? plan_cells(p, p.wr) : 0)) *
                     g.blocks_per_wg;
@@ -328,7 +349,7 @@ bool check_inputs_enabled() {
 int check_row_ids(const int32_t* idx, int64_t n, int64_t n_rows, hipStream_t s) {
   if (!check_inputs_enabled() || !idx || n <= 0) return GBDT_OK;
   void* ws = nullptr;
-  int rc = get_workspace(256, &ws);
+  int rc = get_workspace(256, s, &ws);
   if (rc != GBDT_OK) return rc;
   unsigned long long* n_bad = (unsigned long long*)ws;
   hipLaunchKernelGGL(counters_zero_kernel, dim3(1), dim3(256), 0, s, (uint32_t*)ws, 2);
@@ -378,9 +399,9 @@ struct BuildTimer {
 };
 
 template <int CAP, int WM, bool NIB, int NT, int WPE, typename ACC, bool WIDE = false>
-int launch_build(const BuildArgs& a, int blocks, hipStream_t s) {
+int launch_build(const BuildArgs& a, int blocks, hipStream_t s, bool timed = true) {
   BuildTimer timer;
-  int rc = timer.begin(s);
+  int rc = timed ? timer.begin(s) : GBDT_OK;
   if (rc != GBDT_OK) return rc;
   if (a.idx) {
     hipLaunchKernelGGL((hist_build_kernel<CAP, WM, NIB, NT, WPE, ACC, true, WIDE>), dim3(blocks), dim3(NT), 0, s,
@@ -451,7 +472,7 @@ int launch_split(const gbdt_bin_t* hists, int64_t hist_stride, int32_t n_hists, 
   int group = 0, n_groups = 0;
   split_grouping(n_features, n_bins, &group, &n_groups);
   void* ws = nullptr;
-  int rc = get_workspace((size_t)n_hists * n_groups * sizeof(SplitCand), &ws);
+  int rc = get_workspace((size_t)n_hists * n_groups * sizeof(SplitCand), s, &ws);
   if (rc != GBDT_OK) return rc;
   const size_t lds = (size_t)group * split_feature_bytes(n_bins);
   // (only with `minus` does the kernel write to the histograms)
@@ -554,6 +575,173 @@ gbdt_split_t* pinned_level_records(size_t n) {
   return p;
 }
 
+// gbdt_hist_build, with the scratch either the library's workspace (fixed_base == NULL) or a
+// fixed buffer of fixed_bytes whose head holds the unit counters (the no-allocation entry
+// point): then nothing is allocated, the grid shrinks until its partial blocks fit, and
+// the counters are zeroed by every call that uses them.
+int hist_build_impl(const void* bin_matrix, int64_t n_rows, int32_t n_features, int32_t n_bins,
+                    const int32_t* leaf_row_idx, int64_t n_leaf_rows, const float* grad,
+                    const float* hess, gbdt_bin_t* hist_out, void* stream, void* fixed_base,
+                    size_t fixed_bytes) {
+  g_hip_err[0] = 0;
+  if (!valid_shape(n_rows, n_features, n_bins)) return GBDT_EINVAL;
+  if (!hist_out) return GBDT_EINVAL;
+  if (n_leaf_rows < 0) return GBDT_EINVAL;
+  if (!leaf_row_idx && n_leaf_rows > n_rows) return GBDT_EINVAL;
+  if (n_rows >= ((int64_t)1 << 30) || n_leaf_rows >= ((int64_t)1 << 31)) return GBDT_EUNSUPPORTED;
+  hipStream_t s = (hipStream_t)stream;
+  if (n_leaf_rows == 0) {
+    const int32_t n = n_features * n_bins;
+    hipLaunchKernelGGL(hist_zero_kernel, dim3((n + 255) / 256), dim3(256), 0, s, hist_out, n);
+    HIP_TRY(hipGetLastError());
+    return GBDT_OK;
+  }
+  if (!bin_matrix || !grad || !hess) return GBDT_EINVAL;
+  if (!fixed_base) {  // (the checking kernel's counter lives in the library's workspace)
+    const int rc_ids = check_row_ids(leaf_row_idx, n_leaf_rows, n_rows, s);
+    if (rc_ids != GBDT_OK) return rc_ids;
+  }
+
+  const bool wide = g_wide.load() != 0;
+  const int wg_per_cu = build_wg_per_cu(make_tile_plan(n_features, n_bins).cap, leaf_row_idx != nullptr, wide);
+  BuildGeom g = make_geom(n_features, n_bins, n_leaf_rows, device_cu_count(), wg_per_cu, wide);
+  if (fixed_base) {
+    // fewer workgroups per tile until the partial blocks fit the fixed buffer
+    const size_t avail_words = fixed_bytes > kWsHeadBytes ? (fixed_bytes - kWsHeadBytes) / 4 : 0;
+    if (g.partial_words > avail_words) {
+      const size_t per_wg = g.partial_words / (size_t)g.wgs;  // words of one workgroup of every tile
+      const int64_t fit = (int64_t)(avail_words / per_wg);
+      if (fit < 1) {
+        snprintf(g_hip_err, sizeof g_hip_err,
+                 "%d features x %d bins need %zu bytes of partial histograms, the fixed scratch holds %zu",
+                 n_features, n_bins, per_wg * 4, avail_words * 4);
+        return GBDT_EUNSUPPORTED;
+      }
+      g = make_geom(n_features, n_bins, n_leaf_rows, device_cu_count(), wg_per_cu, wide, fit);
+    }
+  }
+  const TilePlan& p = g.plan;
+  if (plan_n_tiles(p) > 65535) return GBDT_EUNSUPPORTED;
+  // byte offsets inside a tile (slack included) are formed in 32 bits
+  if ((n_rows + kEpochRows) * (int64_t)p.wm >= ((int64_t)1 << 32)) return GBDT_EUNSUPPORTED;
+  void* ws = nullptr;
+  uint32_t* counters = nullptr;
+  bool counters_zero = false;
+  // With an index list and several feature tiles, gather grad / hess into leaf order once
+  // instead of letting every tile's workgroups gather them from scattered rows.
+  bool by_pos = leaf_row_idx != nullptr && stats_gather_pays(plan_n_tiles(p), n_leaf_rows, n_leaf_rows, n_rows);
+  size_t stats_words = by_pos ? 2 * (((size_t)n_leaf_rows + 63) / 64 * 64) : 0;
+  int rc = GBDT_OK;
+  if (fixed_base) {
+    if (kWsHeadBytes + (g.partial_words + stats_words) * 4 > fixed_bytes) {  // the gather is optional
+      by_pos = false;
+      stats_words = 0;
+    }
+    counters = (uint32_t*)fixed_base;
+    ws = (char*)fixed_base + kWsHeadBytes;
+    counters_zero = false;
+  } else {
+    rc = get_workspace((g.partial_words + stats_words) * 4, s, &ws, &counters, &counters_zero);
+    if (rc == GBDT_ENOMEM && by_pos) {  // a caller's workspace sized for the partial blocks alone: no gather
+      by_pos = false;
+      stats_words = 0;
+      rc = get_workspace(g.partial_words * 4, s, &ws, &counters, &counters_zero);
+    }
+  }
+  if (rc != GBDT_OK) return rc;
+
+  BuildArgs a;
+  a.packed = (const uint8_t*)bin_matrix;
+  a.idx = leaf_row_idx;
+  a.grad = grad;
+  a.hess = hess;
+  a.stats_by_pos = 0;
+  if (by_pos) {
+    float* g_leaf = (float*)ws + g.partial_words;
+    float* h_leaf = g_leaf + stats_words / 2;
+    hipLaunchKernelGGL(stats_gather_kernel, dim3((unsigned)((n_leaf_rows + 255) / 256)), dim3(256), 0, s,
+                       leaf_row_idx, grad, hess, n_leaf_rows, g_leaf, h_leaf);
+    HIP_TRY(hipGetLastError());
+    a.grad = g_leaf;
+    a.hess = h_leaf;
+    a.stats_by_pos = 1;
+  }
+  a.partials = (uint32_t*)ws;
+  a.counters = counters;
+  a.n_rows = n_rows;
+  a.n_leaf = n_leaf_rows;
+  a.n_main = p.n_main;
+  a.wr = p.wr;
+  a.wgs = g.wgs;
+  a.chunks = g.wgs * g.blocks_per_wg;
+  a.unit_epochs = g.unit_epochs;
+  // no counter when every workgroup has one unit anyway, or when the split must be fixed
+  a.fixed_stride = (g.one_unit_each || g_deterministic.load()) ? g.wgs : 0;
+  a.direct_out = g.wgs == 1 ? hist_out : nullptr;
+  a.n_features = n_features;
+  a.n_bins = n_bins;
+  const int n_tiles = plan_n_tiles(p);
+  const int blocks = n_tiles * g.wgs;
+  const bool uses_counters = a.fixed_stride == 0;
+  // While the stream is being captured nothing runs now, so what is known about the
+  // counters must not change: the captured sequence zeroes them itself, before and (if
+  // no reduction pass follows) after the build, and leaves them zero on every replay.
+  // (the fixed buffer is treated the same way: what is known about it is not tracked)
+  const bool capturing = fixed_base != nullptr || stream_is_capturing(s);
+  auto zero_counters = [&]() -> int {
+    hipLaunchKernelGGL(counters_zero_kernel, dim3(kCounterSlots / 256), dim3(256), 0, s, counters,
+                       kCounterSlots);
+    HIP_TRY(hipGetLastError());
+    return GBDT_OK;
+  };
+  if (uses_counters && (capturing || !counters_zero)) {  // e.g. a new scratch buffer
+    rc = zero_counters();
+    if (rc != GBDT_OK) return rc;
+  }
+  // From here until the reduction pass has been enqueued the counters are in use.
+  if (uses_counters && !capturing) set_counters_zero(counters, false);
+
+  const bool timed = fixed_base == nullptr;  // the profiling events are created on the fly: an allocation
+  if (wide) {
+    if (p.cap == 16) {
+      rc = launch_build<GBDT_VARIANT_16W, true>(a, blocks, s, timed);
+    } else if (p.cap == 64) {
+      rc = launch_build<GBDT_VARIANT_64W, true>(a, blocks, s, timed);
+    } else {
+      rc = launch_build<GBDT_VARIANT_256W, true>(a, blocks, s, timed);
+    }
+  } else if (p.cap == 16) {
+    rc = launch_build<GBDT_VARIANT_16>(a, blocks, s, timed);
+  } else if (p.cap == 64) {
+    rc = launch_build<GBDT_VARIANT_64>(a, blocks, s, timed);
+  } else {
+    rc = launch_build<GBDT_VARIANT_256>(a, blocks, s, timed);
+  }
+  if (rc != GBDT_OK) return rc;
+  if (a.direct_out) {  // one workgroup per tile: the histogram is written
+    if (uses_counters && capturing) return zero_counters();
+    return GBDT_OK;
+  }
+
+  MergeArgs m;
+  m.partials = (const uint32_t*)ws;
+  m.out = hist_out;
+  m.plan = p;
+  m.n_features = n_features;
+  m.n_bins = n_bins;
+  m.chunks_main = a.chunks;
+  m.chunks_rem = p.wr ? a.chunks : 0;
+  m.counters = uses_counters ? counters : nullptr;
+  const int max_slots = plan_slots(p, p.wm);
+  const int mx = (n_bins * max_slots + kMergeCells - 1) / kMergeCells;
+  hipLaunchKernelGGL(hist_merge_kernel, dim3(mx, plan_n_tiles(p)), dim3(kMergeCells * kMergeLanes),
+                     0, s, m);
+  HIP_TRY(hipGetLastError());
+  if (uses_counters && !capturing) set_counters_zero(counters, true);  // the reduction pass leaves them zero
+  return GBDT_OK;
+}
+
+
 }  // namespace
 
 // ----------------------------------------------------------------------- C ABI
@@ -626,137 +814,8 @@ int gbdt_set_workspace(void* dev_ptr, size_t bytes) {
 int gbdt_hist_build(const void* bin_matrix, int64_t n_rows, int32_t n_features, int32_t n_bins,
                     const int32_t* leaf_row_idx, int64_t n_leaf_rows, const float* grad,
                     const float* hess, gbdt_bin_t* hist_out, void* stream) {
-  if (!valid_shape(n_rows, n_features, n_bins)) return GBDT_EINVAL;
-  if (!hist_out) return GBDT_EINVAL;
-  if (n_leaf_rows < 0) return GBDT_EINVAL;
-  if (!leaf_row_idx && n_leaf_rows > n_rows) return GBDT_EINVAL;
-  if (n_rows >= ((int64_t)1 << 30) || n_leaf_rows >= ((int64_t)1 << 31)) return GBDT_EUNSUPPORTED;
-  hipStream_t s = (hipStream_t)stream;
-  if (n_leaf_rows == 0) {
-    const int32_t n = n_features * n_bins;
-    hipLaunchKernelGGL(hist_zero_kernel, dim3((n + 255) / 256), dim3(256), 0, s, hist_out, n);
-    HIP_TRY(hipGetLastError());
-    return GBDT_OK;
-  }
-  if (!bin_matrix || !grad || !hess) return GBDT_EINVAL;
-  {
-    const int rc_ids = check_row_ids(leaf_row_idx, n_leaf_rows, n_rows, s);
-    if (rc_ids != GBDT_OK) return rc_ids;
-  }
-
-  const bool wide = g_wide.load() != 0;
-  const BuildGeom g =
-      make_geom(n_features, n_bins, n_leaf_rows, device_cu_count(),
-                build_wg_per_cu(make_tile_plan(n_features, n_bins).cap, leaf_row_idx != nullptr, wide), wide);
-  const TilePlan& p = g.plan;
-  if (plan_n_tiles(p) > 65535) return GBDT_EUNSUPPORTED;
-  // byte offsets inside a tile (slack included) are formed in 32 bits
-  if ((n_rows + kEpochRows) * (int64_t)p.wm >= ((int64_t)1 << 32)) return GBDT_EUNSUPPORTED;
-  void* ws = nullptr;
-  uint32_t* counters = nullptr;
-  bool counters_zero = false;
-  // With an index list and several feature tiles, gather grad / hess into leaf order once
-  // instead of letting every tile's workgroups gather them from scattered rows.
-  const bool by_pos = leaf_row_idx != nullptr && stats_gather_pays(plan_n_tiles(p), n_leaf_rows, n_leaf_rows, n_rows);
-  const size_t stats_words = by_pos ? 2 * (((size_t)n_leaf_rows + 63) / 64 * 64) : 0;
-  int rc = get_workspace((g.partial_words + stats_words) * 4, &ws, &counters, &counters_zero);
-  if (rc != GBDT_OK) return rc;
-
-  BuildArgs a;
-  a.packed = (const uint8_t*)bin_matrix;
-  a.idx = leaf_row_idx;
-  a.grad = grad;
-  a.hess = hess;
-  a.stats_by_pos = 0;
-  if (by_pos) {
-    float* g_leaf = (float*)ws + g.partial_words;
-    float* h_leaf = g_leaf + stats_words / 2;
-    hipLaunchKernelGGL(stats_gather_kernel, dim3((unsigned)((n_leaf_rows + 255) / 256)), dim3(256), 0, s,
-                       leaf_row_idx, grad, hess, n_leaf_rows, g_leaf, h_leaf);
-    HIP_TRY(hipGetLastError());
-    a.grad = g_leaf;
-    a.hess = h_leaf;
-    a.stats_by_pos = 1;
-  }
-  a.partials = (uint32_t*)ws;
-  a.counters = counters;
-  a.n_rows = n_rows;
-  a.n_leaf = n_leaf_rows;
-  a.n_main = p.n_main;
-  a.wr = p.wr;
-  a.wgs = g.wgs;
-  a.chunks = g.wgs * g.blocks_per_wg;
-  a.unit_epochs = g.unit_epochs;
-  // no counter when every workgroup has one unit anyway, or when the split must be fixed
-  a.fixed_stride = (g.one_unit_each || g_deterministic.load()) ? g.wgs : 0;
-  a.direct_out = g.wgs == 1 ? hist_out : nullptr;
-  a.n_features = n_features;
-  a.n_bins = n_bins;
-  const int n_tiles = plan_n_tiles(p);
-  const int blocks = n_tiles * g.wgs;
-  const bool uses_counters = a.fixed_stride == 0;
-  // While the stream is being captured nothing runs now, so what is known about the
-  // counters must not change: the captured sequence zeroes them itself, before and (if
-  // no reduction pass follows) after the build, and leaves them zero on every replay.
-  bool capturing = false;
-  {
-    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
-    if (hipStreamIsCapturing(s, &cs) == hipSuccess) {
-      capturing = cs == hipStreamCaptureStatusActive;
-    } else {
-      (void)hipGetLastError();
-    }
-  }
-  auto zero_counters = [&]() -> int {
-    hipLaunchKernelGGL(counters_zero_kernel, dim3(kCounterSlots / 256), dim3(256), 0, s, counters,
-                       kCounterSlots);
-    HIP_TRY(hipGetLastError());
-    return GBDT_OK;
-  };
-  if (uses_counters && (capturing || !counters_zero)) {  // e.g. a new scratch buffer
-    rc = zero_counters();
-    if (rc != GBDT_OK) return rc;
-  }
-  // From here until the reduction pass has been enqueued the counters are in use.
-  if (uses_counters && !capturing) set_counters_zero(counters, false);
-
-  if (wide) {
-    if (p.cap == 16) {
-      rc = launch_build<GBDT_VARIANT_16W, true>(a, blocks, s);
-    } else if (p.cap == 64) {
-      rc = launch_build<GBDT_VARIANT_64W, true>(a, blocks, s);
-    } else {
-      rc = launch_build<GBDT_VARIANT_256W, true>(a, blocks, s);
-    }
-  } else if (p.cap == 16) {
-    rc = launch_build<GBDT_VARIANT_16>(a, blocks, s);
-  } else if (p.cap == 64) {
-    rc = launch_build<GBDT_VARIANT_64>(a, blocks, s);
-  } else {
-    rc = launch_build<GBDT_VARIANT_256>(a, blocks, s);
-  }
-  if (rc != GBDT_OK) return rc;
-  if (a.direct_out) {  // one workgroup per tile: the histogram is written
-    if (uses_counters && capturing) return zero_counters();
-    return GBDT_OK;
-  }
-
-  MergeArgs m;
-  m.partials = (const uint32_t*)ws;
-  m.out = hist_out;
-  m.plan = p;
-  m.n_features = n_features;
-  m.n_bins = n_bins;
-  m.chunks_main = a.chunks;
-  m.chunks_rem = p.wr ? a.chunks : 0;
-  m.counters = uses_counters ? counters : nullptr;
-  const int max_slots = plan_slots(p, p.wm);
-  const int mx = (n_bins * max_slots + kMergeCells - 1) / kMergeCells;
-  hipLaunchKernelGGL(hist_merge_kernel, dim3(mx, plan_n_tiles(p)), dim3(kMergeCells * kMergeLanes),
-                     0, s, m);
-  HIP_TRY(hipGetLastError());
-  if (uses_counters && !capturing) set_counters_zero(counters, true);  // the reduction pass leaves them zero
-  return GBDT_OK;
+  return hist_build_impl(bin_matrix, n_rows, n_features, n_bins, leaf_row_idx, n_leaf_rows, grad, hess, hist_out,
+                         stream, nullptr, 0);
 }
 
 int gbdt_hist_build_batch(const void* bin_matrix, int64_t n_rows, int32_t n_features,
@@ -806,7 +865,7 @@ int gbdt_hist_build_batch(const void* bin_matrix, int64_t n_rows, int32_t n_feat
   const bool by_pos = total_rows > 0 && stats_gather_pays(n_tiles, total_rows, total_rows / n_leaves, n_rows);
   const size_t stats_words = by_pos ? 2 * (((size_t)total_rows + 63) / 64 * 64) : 0;
   void* ws = nullptr;
-  int rc = get_workspace((need_words + stats_words) * 4 + 256, &ws);
+  int rc = get_workspace((need_words + stats_words) * 4 + 256, s, &ws);
   if (rc != GBDT_OK) return rc;
   float* g_list = (float*)ws + need_words;
   float* h_list = g_list + stats_words / 2;
@@ -958,7 +1017,7 @@ int gbdt_partition_rows(const void* bin_matrix, int64_t n_rows, int32_t n_featur
   }
   const PartGeom g = make_part_geom(n_leaf_rows > 0 ? n_leaf_rows : 1);
   void* ws = nullptr;
-  int rc = get_workspace(g.bytes, &ws);
+  int rc = get_workspace(g.bytes, s, &ws);
   if (rc != GBDT_OK) return rc;
   uint64_t* flags = (uint64_t*)ws;
   uint32_t* chunk_left = (uint32_t*)(flags + g.flag_words);
@@ -1014,7 +1073,7 @@ int gbdt_partition_rows_batch(const void* bin_matrix, int64_t n_rows, int32_t n_
   if (max_chunks >= ((int64_t)1 << 31)) return GBDT_EUNSUPPORTED;
   const size_t flag_words = (size_t)max_chunks * rpt * kPartWaves;
   void* ws = nullptr;
-  int rc = get_workspace(flag_words * 8 + (size_t)max_chunks * 4 + 256, &ws);
+  int rc = get_workspace(flag_words * 8 + (size_t)max_chunks * 4 + 256, s, &ws);
   if (rc != GBDT_OK) return rc;
   const TilePlan p = make_tile_plan(n_features, n_bins);
   for (int32_t l0 = 0; l0 < n_leaves; l0 += kPartBatchLeaves) {
@@ -1529,6 +1588,59 @@ int gbdt_profile_collect(double* build_kernel_ms_total, int64_t* n_launches) {
   *build_kernel_ms_total = total;
   *n_launches = (int64_t)pairs.size();
   return rc;
+}
+
+int gbdt_profile_durations(double* ms_out, int64_t capacity, int64_t* n_launches) {
+  if (!n_launches || capacity < 0 || (capacity > 0 && !ms_out)) return GBDT_EINVAL;
+  std::vector<std::pair<hipEvent_t, hipEvent_t>> pairs;
+  {
+    std::lock_guard<std::mutex> lk(g_prof.mu);
+    pairs.swap(g_prof.pairs);
+  }
+  int rc = GBDT_OK;
+  int64_t i = 0;
+  for (auto& pr : pairs) {
+    float ms = 0.0f;
+    hipError_t e = hipEventSynchronize(pr.second);
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, pr.first, pr.second);
+    if (e != hipSuccess && rc == GBDT_OK) rc = hip_fail(e, "hipEventElapsedTime");
+    if (i < capacity) ms_out[i] = ms;
+    ++i;
+    (void)hipEventDestroy(pr.first);
+    (void)hipEventDestroy(pr.second);
+  }
+  *n_launches = i;
+  return rc;
+}
+
+int gbdt_reset(void) {
+  // everything enqueued so far must be done before buffers go away and counters are cleared
+  HIP_TRY(hipDeviceSynchronize());
+  {
+    std::lock_guard<std::mutex> lk(g_ws.mu);
+    for (void* q : g_ws.retired) (void)hipFree(q);
+    g_ws.retired.clear();
+    if (g_ws.own) (void)hipFree(g_ws.own);
+    g_ws.own = nullptr;
+    g_ws.own_bytes = 0;
+    g_ws.own_device = -1;
+    g_ws.zeroed = nullptr;  // a caller's buffer stays registered; its counters are zeroed by the next build
+  }
+  {
+    std::lock_guard<std::mutex> lk(g_prof.mu);
+    for (auto& pr : g_prof.pairs) {
+      (void)hipEventDestroy(pr.first);
+      (void)hipEventDestroy(pr.second);
+    }
+    g_prof.pairs.clear();
+  }
+  (void)hipGetLastError();
+  // the split search's tickets: a launch that failed half-way may have left some counted
+  hipLaunchKernelGGL(split_tickets_zero_kernel, dim3(kSplitMaxHists / 256), dim3(256), 0, nullptr);
+  HIP_TRY(hipGetLastError());
+  HIP_TRY(hipDeviceSynchronize());
+  g_hip_err[0] = 0;
+  return GBDT_OK;
 }
 
 const char* gbdt_strerror(int code) {

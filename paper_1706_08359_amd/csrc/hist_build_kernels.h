@@ -619,10 +619,13 @@ __device__ __forceinline__ void build_tile(const uint8_t* __restrict__ tile,
     // ---- drain: integer sums -> registers, clear the cells for the next epoch
     const float inv_g = pow2f(-kg), inv_h = pow2f(-kh);
     const double inv_gw = pow2d(-kg - kWideShift), inv_hw = pow2d(-kh - kWideShift);
-#pragma unroll
-    for (int m = 0; m < PP; ++m) drain_cell(m, inv_g, inv_h, inv_gw, inv_hw);
+    // The next epoch's scales are requested from local memory BEFORE the cells: results come
+    // back in order, so the cells can then be decoded one by one as they arrive, instead of
+    // all of them being waited for because the youngest request is needed first.
     read_scales((int)parity, kg, kh);
     if (enters_unit) next_unit = __builtin_amdgcn_readfirstlane(fixed_stride ? taken : unit_box[0]);
+#pragma unroll
+    for (int m = 0; m < PP; ++m) drain_cell(m, inv_g, inv_h, inv_gw, inv_hw);
     p0 = p1;
     p1 = p2;
     p2 = after(p2);

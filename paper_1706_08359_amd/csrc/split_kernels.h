@@ -32,6 +32,11 @@ constexpr int kSplitMaxHists = 32768;  // histograms per launch (grid.y)
 // need no resetting between launches (zero when the module is loaded).
 __device__ unsigned int g_split_ticket[kSplitMaxHists];
 
+// Sets every ticket counter back to zero (gbdt_reset: after a launch that did not complete).
+__global__ void __launch_bounds__(256) split_tickets_zero_kernel() {
+  g_split_ticket[blockIdx.x * 256 + threadIdx.x] = 0u;
+}
+
 // Candidates cross from the workgroups that write them to the one that reduces them,
 // possibly on another XCD with its own L2: they are moved with device-scope atomic
 // accesses (which bypass the caches that are not coherent across XCDs), inside the
