@@ -9,10 +9,17 @@ root leaf (all rows), logistic grad/hess -- the configuration the headline metri
 is quoted on.  Inputs are synthetic, seeded, generated on the GPU and resident in
 HBM (packed once, outside the timed region) before timing starts.
 
+Protocol: untimed steps for --prewarm-s seconds of wall time (the clocks the GPU
+settles at under this load), --warmup untimed steps, then exactly --steps steps between
+two synchronisations (`ms_per_step`, `value`); then the same number of steps with the
+library's HIP events around every build kernel (recorded on the call's stream), and once
+more with events around the whole gbdt_hist_build call.
+
 Prints ONE JSON line.  `value` is feature values processed per second by whole
-steps; `roofline` prices the dominant kernel (the histogram build kernel, timed
-with HIP events on its own stream inside the library) against HBM peak using
-ALGORITHMIC bytes; `cpu_baseline` times the CPU oracle on the same workload.
+steps; `roofline` prices the dominant kernel (the histogram build kernel) against HBM
+peak using ALGORITHMIC bytes and the MEAN of the per-launch durations (median and minimum
+beside it; `build_plus_merge` prices the whole call the same way); `cpu_baseline` times
+the CPU oracle on the same workload.
 """
 from __future__ import annotations
 
@@ -104,12 +111,55 @@ def cpu_baseline(w, budget_values=1.2e9):
     }
 
 
+def cpu_baseline_build_rate(w, leaf, budget_values=6e8):
+    """G feature values / s of the CPU oracle on a bounded sample of the leaf: median of 3 passes
+    with all host threads, then of 3 passes with one thread on a tenth of the sample."""
+    import statistics
+    from oracle import gbdt_oracle as orc
+    n_leaf = w.n_rows if leaf is None else leaf.numel()
+
+    def timed(rows):
+        if leaf is None:
+            bins = w.bins[:rows].cpu().numpy()
+            grad, hess, idx = w.grad[:rows].cpu().numpy(), w.hess[:rows].cpu().numpy(), None
+        else:
+            idx = leaf[:rows].cpu().numpy()
+            hi = int(idx.max()) + 1
+            bins = w.bins[:hi].cpu().numpy()
+            grad, hess = w.grad[:hi].cpu().numpy(), w.hess[:hi].cpu().numpy()
+        dts = []
+        for _ in range(3):
+            t0 = time.perf_counter()
+            orc.hist_build(bins, w.n_bins, grad, hess, idx)
+            dts.append(time.perf_counter() - t0)
+        return rows * w.n_features / statistics.median(dts) / 1e9
+
+    rows = int(min(n_leaf, max(1, budget_values // w.n_features)))
+    threads = orc.num_threads()
+    rate = timed(rows)
+    rows1 = max(1, rows // 10)
+    orc.set_num_threads(1)
+    try:
+        rate1 = timed(rows1)
+    finally:
+        orc.set_num_threads(threads)
+    return rate, rows, threads, rate1, rows1
+
+
+def _stats(ms):
+    import statistics
+    return {"mean": sum(ms) / len(ms), "median": statistics.median(ms), "min": min(ms), "n": len(ms)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="dense_wide")
+    ap.add_argument("--prewarm-s", type=float, default=1.0,
+                    help="seconds of untimed steps before the --warmup steps (clocks ramp up under load; "
+                         "a handful of warm-up launches is a millisecond of GPU work)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -133,28 +183,61 @@ def main():
     sib = torch.empty_like(parent)
     split = torch.empty(9, dtype=torch.int32, device=dev)
 
-    def step():
+    def build():
         B.gbdt_hist_build(packed, n, F, nb, leaf, n_leaf, w.grad, w.hess, hist_out=hist)
+
+    def step():
+        build()
         B.gbdt_hist_subtract(parent, hist, sibling_out=sib)
         B.gbdt_best_split(hist, w.lam, w.min_child_hess, split_out=split)
 
+    # untimed: the same steps for a fixed wall time, so that the timed region sees the clocks the
+    # GPU settles at under this load, whatever --warmup says
+    t_pre = time.perf_counter()
+    while time.perf_counter() - t_pre < args.prewarm_s:
+        for _ in range(20):
+            step()
+        torch.cuda.synchronize()
+    prewarm_s = time.perf_counter() - t_pre
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    B.gbdt_profile_enable(True)
+
+    # ---- timed region: K whole steps, nothing else on the stream
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    B.gbdt_profile_enable(False)
-    k_ms, k_n = B.gbdt_profile_collect()
     ms_per_step = dt * 1e3 / args.steps
     values = float(n_leaf) * F
 
-    kernel_ms = k_ms / max(1, k_n)
+    # ---- the same K steps again with the library's events around every build kernel
+    # (hipEventRecord on the call's stream right before and after the kernel): per-launch durations
+    B.gbdt_profile_enable(True)
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    B.gbdt_profile_enable(False)
+    k = _stats(B.gbdt_profile_durations())
+
+    # ---- and the whole gbdt_hist_build call (build kernel + reduction pass), events on the same stream
+    call_ms = []
+    for _ in range(args.steps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        build()
+        e1.record()
+        B.gbdt_hist_subtract(parent, hist, sibling_out=sib)
+        B.gbdt_best_split(hist, w.lam, w.min_child_hess, split_out=split)
+        call_ms.append((e0, e1))
+    torch.cuda.synchronize()
+    c = _stats([a.elapsed_time(b) for a, b in call_ms])
+
     alg = algorithmic_bytes(n_leaf, F, nb, leaf is not None)
-    achieved = alg / (kernel_ms * 1e-3) / 1e9
+    gbs = lambda ms: alg / (ms * 1e-3) / 1e9
+    achieved = gbs(k["mean"])
+    traffic = measured_traffic(w.name)
     out = {
         "metric": "histogram build G feature-values/s (whole step: build + subtract + best split)",
         "value": values / (ms_per_step * 1e-3) / 1e9,
@@ -162,11 +245,13 @@ def main():
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
+        "prewarm_s": round(prewarm_s, 3),
         "ms_per_step": ms_per_step,
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f32",
+        "dtype": "f32 in/out; 27-bit fixed-point accumulation in 64-bit LDS cells per 512-row epoch, "
+                 "fp32 per-workgroup sums, fp64 merge",
         "data": "synthetic",
         "config": {"workload": f"{w.name}: {n} rows x {F} features, {nb} bins, "
                                f"leaf of {n_leaf} rows ({'root' if leaf is None else 'indexed'})"},
@@ -177,9 +262,21 @@ def main():
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
-            "traffic": measured_traffic(w.name),
-            "kernel_ms": kernel_ms,
+            "traffic": traffic,
+            "traffic_source": None if traffic is None else
+                f"profiles/hist_build_{w.name}_hbm_traffic.md (committed rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE "
+                "measurement, not re-measured by this run)",
+            "kernel_ms": k["mean"],
+            "kernel_ms_median": k["median"],
+            "kernel_ms_min": k["min"],
+            "kernel_launches": k["n"],
+            "frac_at_median": gbs(k["median"]) / HBM_PEAK_GBS,
             "algorithmic_bytes": alg,
+            "build_plus_merge": {
+                "what": "whole gbdt_hist_build call: build kernel + reduction pass, same algorithmic bytes",
+                "call_ms": c["mean"], "call_ms_median": c["median"], "call_ms_min": c["min"],
+                "achieved": gbs(c["mean"]), "frac": gbs(c["mean"]) / HBM_PEAK_GBS,
+            },
         },
     }
     if not args.no_cpu_baseline:

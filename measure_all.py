@@ -6,12 +6,12 @@ fill + build + merge, torch events) -- and prints a markdown table with feature 
 per second, algorithmic GB/s and the fraction of the 8 TB/s HBM peak.  With --oracle the
 CPU oracle is timed beside it on a bounded sample of the same leaf.
 
-    python -m paper_1706_08359_amd.measure_all                # the five workloads
-    python -m paper_1706_08359_amd.measure_all --depth-sweep  # App. C.2: 8,000,000 x 500, leaf = N / 2^D
-    python -m paper_1706_08359_amd.measure_all --skew         # App. A.3: constant-bin features
-    python -m paper_1706_08359_amd.measure_all --partition    # row partition after a split (App. C.1)
-    python -m paper_1706_08359_amd.measure_all --tree         # 255-leaf trees grown by gbdt_grow_tree
-    python -m paper_1706_08359_amd.measure_all --batch-sweep  # a whole tree level per launch vs. leaf by leaf
+    python measure_all.py                # the five workloads
+    python measure_all.py --depth-sweep  # App. C.2: 8,000,000 x 500, leaf = N / 2^D
+    python measure_all.py --skew         # App. A.3: constant-bin features
+    python measure_all.py --partition    # row partition after a split (App. C.1)
+    python measure_all.py --tree         # 255-leaf trees grown by gbdt_grow_tree
+    python measure_all.py --batch-sweep  # a whole tree level per launch vs. leaf by leaf
 """
 from __future__ import annotations
 
@@ -21,7 +21,7 @@ import statistics
 import sys
 import time
 
-ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
@@ -57,37 +57,9 @@ def time_leaf(B, torch, packed, w, leaf, reps=20, warmup=3):
 
 
 def oracle_rate(w, leaf, budget_values=6e8):
-    """G feature values / s of the CPU oracle on a bounded sample of the leaf: median of 3 passes
-    with all host threads, then of 3 passes with one thread on a tenth of the sample."""
-    from oracle import gbdt_oracle as orc
-    n_leaf = w.n_rows if leaf is None else leaf.numel()
-
-    def timed(rows):
-        if leaf is None:
-            bins = w.bins[:rows].cpu().numpy()
-            grad, hess, idx = w.grad[:rows].cpu().numpy(), w.hess[:rows].cpu().numpy(), None
-        else:
-            idx = leaf[:rows].cpu().numpy()
-            hi = int(idx.max()) + 1
-            bins = w.bins[:hi].cpu().numpy()
-            grad, hess = w.grad[:hi].cpu().numpy(), w.hess[:hi].cpu().numpy()
-        dts = []
-        for _ in range(3):
-            t0 = time.perf_counter()
-            orc.hist_build(bins, w.n_bins, grad, hess, idx)
-            dts.append(time.perf_counter() - t0)
-        return rows * w.n_features / statistics.median(dts) / 1e9
-
-    rows = int(min(n_leaf, max(1, budget_values // w.n_features)))
-    threads = orc.num_threads()
-    rate = timed(rows)
-    rows1 = max(1, rows // 10)
-    orc.set_num_threads(1)
-    try:
-        rate1 = timed(rows1)
-    finally:
-        orc.set_num_threads(threads)
-    return rate, rows, threads, rate1, rows1
+    """The CPU oracle's build rate on a bounded sample of the leaf (bench.py's cpu_baseline leg)."""
+    import bench
+    return bench.cpu_baseline_build_rate(w, leaf, budget_values)
 
 
 def row(name, leaf_name, w, leaf, k_med, k_min, call_med, oracle=None):

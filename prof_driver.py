@@ -3,7 +3,7 @@ benchmark workloads, launches its root-leaf histogram build (or, with --leaf-fra
 build of an index-list leaf) a few times through the C ABI and, with --copy-bytes, one plain copy kernel of that many bytes whose memory
 counters calibrate the build kernel's.
 
-    python -m paper_1706_08359_amd.prof_driver dense_wide --launches 3 --copy-bytes 800000000
+    python prof_driver.py dense_wide --launches 3 --copy-bytes 800000000
 """
 from __future__ import annotations
 
@@ -11,7 +11,7 @@ import argparse
 import os
 import sys
 
-ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
