@@ -1,15 +1,18 @@
 """GPU parity at the FULL sizes of the five workloads, in the launch configuration the
 benchmark times (root leaf of the whole matrix, plus index-list leaves).
 
-The oracle cannot rebuild a 400,000 x 2,000 histogram in seconds, so here it computes
-SAMPLED outputs one by one -- the complete histograms of a handful of features over the
-whole leaf -- and the rest is covered by properties that hold at any size: every
-feature's counts sum to the leaf size exactly, its gradient / hessian sums reproduce the
-leaf totals, the sibling is the exact element-wise difference, and the split chosen by
-the GPU scan equals the oracle's scan of the same fp32 histogram.  The row partition that
-follows the split is integer work on one column, which the oracle redoes in full: every
-row id of both children is compared.
+Every feature of every leaf built here is compared with the CPU oracle element by element:
+counts bit-exact, gradient / hessian sums within 1e-5 of the leaf's sum of |grad| (|hess|).
+(The oracle rebuilds the 400,000 x 2,000 histogram in about 0.4 s on the box's 16 host
+threads and the 11,000,000 x 700 one in a few seconds; its wall time is printed.)  On top:
+the sibling is the exact element-wise difference, the split chosen by the GPU scan equals
+the oracle's scan of the same fp32 histogram AND the oracle's scan of its own fp64
+histogram (or lies inside the stated near-tie band, which is then reported), and the row
+partition that follows the split -- integer work on one column, which the oracle redoes in
+full -- is compared row id by row id.
 """
+import time
+
 import numpy as np
 import pytest
 import torch
@@ -23,23 +26,30 @@ from gpu_util import REL_TOL
 pytestmark = pytest.mark.gpu
 
 DEV = "cuda:0"
+NEAR_TIE_BAND = 1e-4   # relative gain band inside which fp32 histogram sums may reorder two candidates
+near_ties = []         # (what, gap) of every decision that needed the band
 
 
 def _say(msg):
     print(msg, flush=True)
 
 
-def _sample_features(n_features, k, seed):
-    rng = np.random.default_rng(seed)
-    cols = {0, n_features - 1, n_features // 2}           # first, last (remainder tile), middle
-    while len(cols) < min(k, n_features):
-        cols.add(int(rng.integers(0, n_features)))
-    return np.array(sorted(cols), dtype=np.int64)
+class Host:
+    """Host copies of a workload's arrays for the oracle (made once per test)."""
+
+    def __init__(self, w):
+        t0 = time.perf_counter()
+        self.bins = w.bins.cpu().numpy()
+        self.grad = w.grad.cpu().numpy()
+        self.hess = w.hess.cpu().numpy()
+        self.g64 = self.grad.astype(np.float64)
+        self.h64 = self.hess.astype(np.float64)
+        _say(f"  host copy of {self.bins.shape[0]} x {self.bins.shape[1]} bins: {time.perf_counter() - t0:.1f} s")
 
 
-def _check_leaf(w, packed, leaf, cols, what):
-    """Builds one leaf on the GPU and checks it against sampled oracle histograms and the
-    size-independent properties.  leaf: None (root) or an int32 CUDA tensor of row ids."""
+def _check_leaf(w, host, packed, leaf, what):
+    """Builds one leaf on the GPU and compares EVERY bin of EVERY feature with the oracle; then
+    the split search and the row partition.  leaf: None (root) or an int32 CUDA tensor of row ids."""
     n, F, nb = w.n_rows, w.n_features, w.n_bins
     n_leaf = n if leaf is None else leaf.numel()
     _say(f"{what}: build {n_leaf} leaf rows x {F} features, {nb} bins")
@@ -47,42 +57,46 @@ def _check_leaf(w, packed, leaf, cols, what):
     torch.cuda.synchronize()
     got = B.hist_to_numpy(hist)
 
-    g = w.grad if leaf is None else w.grad[leaf.long()]
-    h = w.hess if leaf is None else w.hess[leaf.long()]
-    g64, h64 = g.double(), h.double()
-    sum_g, sum_h = g64.sum().item(), h64.sum().item()
-    abs_g, abs_h = g64.abs().sum().item(), h64.abs().sum().item()
-
-    # properties that hold at any size
-    assert (got["count"].sum(axis=1, dtype=np.uint64) == n_leaf).all(), f"{what}: counts do not sum to the leaf"
-    fg = got["grad"].astype(np.float64).sum(axis=1)
-    fh = got["hess"].astype(np.float64).sum(axis=1)
-    assert np.abs(fg - sum_g).max() <= nb * REL_TOL * abs_g, f"{what}: per-feature gradient totals"
-    assert np.abs(fh - sum_h).max() <= nb * REL_TOL * abs_h, f"{what}: per-feature hessian totals"
-
-    # sampled features, element by element against the oracle
-    cols_t = torch.from_numpy(cols).to(w.bins.device)
-    sub = w.bins[:, cols_t].contiguous().cpu().numpy()
     idx_np = None if leaf is None else leaf.cpu().numpy()
-    ref = orc.hist_build(sub, nb, w.grad.cpu().numpy(), w.hess.cpu().numpy(), idx_np)
-    sel = got[cols]
-    assert (sel["count"].astype(np.uint64) == ref["count"]).all(), f"{what}: sampled counts"
-    dg = np.abs(sel["grad"].astype(np.float64) - ref["grad"]).max()
-    dh = np.abs(sel["hess"].astype(np.float64) - ref["hess"]).max()
-    _say(f"{what}: max |err| grad {dg:.3e} (allowed {REL_TOL * abs_g:.3e}), hess {dh:.3e} (allowed {REL_TOL * abs_h:.3e})")
+    t0 = time.perf_counter()
+    ref = orc.hist_build(host.bins, nb, host.grad, host.hess, idx_np)
+    t_orc = time.perf_counter() - t0
+    abs_g = np.abs(host.g64 if idx_np is None else host.g64[idx_np]).sum()
+    abs_h = np.abs(host.h64 if idx_np is None else host.h64[idx_np]).sum()
+
+    bad = np.argwhere(got["count"].astype(np.uint64) != ref["count"])
+    assert bad.size == 0, f"{what}: {len(bad)} count mismatches, first at {bad[:3].tolist()}"
+    dg = np.abs(got["grad"].astype(np.float64) - ref["grad"]).max()
+    dh = np.abs(got["hess"].astype(np.float64) - ref["hess"]).max()
+    _say(f"{what}: all {F} x {nb} bins: max |err| grad {dg:.3e} = {dg / abs_g:.2e} of sum|g| "
+         f"(allowed {REL_TOL:.0e}), hess {dh:.3e} = {dh / abs_h:.2e} of sum|h|; oracle {t_orc:.2f} s "
+         f"on {orc.num_threads()} threads")
     assert dg <= REL_TOL * abs_g and dh <= REL_TOL * abs_h
 
-    # the GPU scan of this fp32 histogram picks what the oracle scan of the same numbers picks
+    # the GPU scan of this fp32 histogram picks what the oracle scan of the same numbers picks ...
     rec = B.gbdt_best_split(hist, w.lam, w.min_child_hess)
     s_gpu = B.split_to_dict(rec)
-    s_ref = orc.best_split(orc.from_f32_hist(got["grad"], got["hess"], got["count"]), w.lam, w.min_child_hess)
-    assert (s_gpu["feature"], s_gpu["bin"]) == (s_ref["feature"], s_ref["bin"]), (what, s_gpu, s_ref)
-    assert s_gpu["left_count"] == s_ref["left_count"] and s_gpu["right_count"] == s_ref["right_count"]
-    _check_partition(w, packed, leaf, rec, s_gpu, what)
-    return hist, got
+    s_same = orc.best_split(orc.from_f32_hist(got["grad"], got["hess"], got["count"]), w.lam, w.min_child_hess)
+    assert (s_gpu["feature"], s_gpu["bin"]) == (s_same["feature"], s_same["bin"]), (what, s_gpu, s_same)
+    assert s_gpu["left_count"] == s_same["left_count"] and s_gpu["right_count"] == s_same["right_count"]
+    # ... and what the oracle picks from its own fp64 histogram, unless the two best candidates are
+    # closer than fp32 sums can tell apart (then the choice must lie inside the band, and is reported)
+    s_ref, gains = orc.best_split(ref, w.lam, w.min_child_hess, return_gains=True)
+    if (s_gpu["feature"], s_gpu["bin"]) != (s_ref["feature"], s_ref["bin"]):
+        assert s_ref["feature"] >= 0 and s_gpu["feature"] >= 0, (what, s_gpu, s_ref)
+        g_at = gains[s_gpu["feature"], s_gpu["bin"]]
+        gap = s_ref["gain"] - g_at
+        assert np.isfinite(g_at) and gap <= NEAR_TIE_BAND * max(1.0, abs(s_ref["gain"])), (what, s_gpu, s_ref, g_at)
+        near_ties.append((what, gap))
+        _say(f"{what}: [near-tie] gpu {s_gpu['feature'], s_gpu['bin']} vs oracle "
+             f"{s_ref['feature'], s_ref['bin']}, gain gap {gap:.3e} of {s_ref['gain']:.3e}")
+    else:
+        _say(f"{what}: split (feature {s_gpu['feature']}, bin {s_gpu['bin']}) identical to the oracle's")
+    _check_partition(w, host, packed, leaf, rec, s_gpu, what)
+    return hist, got, ref
 
 
-def _check_partition(w, packed, leaf, rec, s_gpu, what):
+def _check_partition(w, host, packed, leaf, rec, s_gpu, what):
     """Partition the leaf by the split record the GPU just wrote; every row id of both children
     against the oracle, which gets the one column it needs (and nothing from the GPU path)."""
     n, F, nb = w.n_rows, w.n_features, w.n_bins
@@ -93,13 +107,30 @@ def _check_partition(w, packed, leaf, rec, s_gpu, what):
     if f < 0:
         assert int(n_left.item()) == n_leaf
         return
-    col = w.bins[:, f].contiguous().cpu().numpy().reshape(-1, 1)
+    col = np.ascontiguousarray(host.bins[:, f]).reshape(-1, 1)
     ref_l, ref_r = orc.partition_rows(col, 0, s_gpu["bin"], None if leaf is None else leaf.cpu().numpy())
     got = kids.cpu().numpy()
     nl = int(n_left.item())
     assert nl == ref_l.size == s_gpu["left_count"], (what, nl, ref_l.size, s_gpu)
     assert np.array_equal(got[:nl], ref_l) and np.array_equal(got[nl:n_leaf], ref_r), f"{what}: partition"
     _say(f"{what}: partition on feature {f} bin {s_gpu['bin']}: {nl} left, {n_leaf - nl} right, identical")
+
+
+def _check_sibling(parent, got_p, ref_p, child, got_c, ref_c, abs_g_parent, abs_h_parent, what):
+    """sibling = parent - child on the GPU: the exact element-wise difference of the two fp32
+    histograms, and within the parent's tolerance of the oracle's own subtraction."""
+    sib = B.hist_to_numpy(B.gbdt_hist_subtract(parent, child))
+    assert (sib["count"] == got_p["count"] - got_c["count"]).all()
+    assert (sib["grad"] == got_p["grad"] - got_c["grad"]).all()
+    assert (sib["hess"] == got_p["hess"] - got_c["hess"]).all()
+    ref_s = orc.hist_subtract(ref_p, ref_c)
+    assert (sib["count"].astype(np.uint64) == ref_s["count"]).all()
+    dg = np.abs(sib["grad"].astype(np.float64) - ref_s["grad"]).max()
+    dh = np.abs(sib["hess"].astype(np.float64) - ref_s["hess"]).max()
+    _say(f"{what}: sibling by subtraction: max |err| grad {dg / abs_g_parent:.2e} of the parent's sum|g|, "
+         f"hess {dh / abs_h_parent:.2e}")
+    assert dg <= REL_TOL * abs_g_parent and dh <= REL_TOL * abs_h_parent
+    return sib
 
 
 def _subset_leaf(n_rows, fraction, seed):
@@ -110,47 +141,51 @@ def _subset_leaf(n_rows, fraction, seed):
 
 def test_config2_dense_wide_full_size():
     w = synth.config2_dense_wide(device=DEV, with_leaves=False)
+    host = Host(w)
     packed = B.gbdt_bins_pack(w.bins, w.n_bins)
-    cols = _sample_features(w.n_features, 8, 2)
-    parent, got_p = _check_leaf(w, packed, None, cols, "config2 root")
+    parent, got_p, ref_p = _check_leaf(w, host, packed, None, "config2 root")
+    ag, ah = np.abs(host.g64).sum(), np.abs(host.h64).sum()
     for frac in (0.5, 0.013):
         leaf = _subset_leaf(w.n_rows, frac, int(frac * 1000))
-        child, got_c = _check_leaf(w, packed, leaf, cols, f"config2 leaf {frac}")
-        sib = B.hist_to_numpy(B.gbdt_hist_subtract(parent, child))
-        assert (sib["count"] == got_p["count"] - got_c["count"]).all()
-        assert (sib["grad"] == got_p["grad"] - got_c["grad"]).all()
-        assert (sib["hess"] == got_p["hess"] - got_c["hess"]).all()
+        child, got_c, ref_c = _check_leaf(w, host, packed, leaf, f"config2 leaf {frac}")
+        _check_sibling(parent, got_p, ref_p, child, got_c, ref_c, ag, ah, f"config2 leaf {frac}")
 
 
 def test_config3_dense_tall_full_size():
     w = synth.config3_dense_tall(device=DEV)
+    host = Host(w)
     packed = B.gbdt_bins_pack(w.bins, w.n_bins)
-    cols = _sample_features(w.n_features, 5, 3)
-    parent, got_p = _check_leaf(w, packed, None, cols, "config3 root")
-    # the smaller child of a split of the root on feature 3 at its median bin, then the sibling
+    parent, got_p, ref_p = _check_leaf(w, host, packed, None, "config3 root")
+    # the smaller child of a split of the root on feature 3 at bin 100, then the sibling
     leaf = torch.nonzero(w.bins[:, 3] <= 100).flatten().to(torch.int32)
-    child, got_c = _check_leaf(w, packed, leaf, cols, "config3 child")
-    sib = B.hist_to_numpy(B.gbdt_hist_subtract(parent, child))
-    assert (sib["count"] == got_p["count"] - got_c["count"]).all()
+    child, got_c, ref_c = _check_leaf(w, host, packed, leaf, "config3 child")
+    sib = _check_sibling(parent, got_p, ref_p, child, got_c, ref_c, np.abs(host.g64).sum(), np.abs(host.h64).sum(),
+                         "config3 child")
     assert (sib["count"].sum(axis=1, dtype=np.uint64) == w.n_rows - leaf.numel()).all()
     assert (sib["count"][3, :101] == 0).all()          # nothing of the right child is left of the threshold
 
 
 def test_config4_ranking_sparse_full_size():
     w = synth.config4_ranking_sparse(device=DEV, fractions=(1.0, 0.25, 0.05))
+    host = Host(w)
     packed = B.gbdt_bins_pack(w.bins, w.n_bins)
-    cols = _sample_features(w.n_features, 6, 4)
     for k, leaf in enumerate(w.leaves):
-        _check_leaf(w, packed, leaf, cols, f"config4 leaf{k}")
+        _check_leaf(w, host, packed, leaf, f"config4 leaf{k}")
 
 
 def test_config5_categorical_full_size():
     w = synth.config5_categorical(device=DEV)
+    host = Host(w)
     packed = B.gbdt_bins_pack(w.bins, w.n_bins)
-    cols = _sample_features(w.n_features, 6, 5)
-    parent, got_p = _check_leaf(w, packed, None, cols, "config5 root")
+    parent, got_p, ref_p = _check_leaf(w, host, packed, None, "config5 root")
     leaf = torch.nonzero(w.bins[:, 10] == 0).flatten().to(torch.int32)
-    child, got_c = _check_leaf(w, packed, leaf, cols, "config5 child")
-    sib = B.hist_to_numpy(B.gbdt_hist_subtract(parent, child))
-    assert (sib["count"] == got_p["count"] - got_c["count"]).all()
+    child, got_c, ref_c = _check_leaf(w, host, packed, leaf, "config5 child")
+    sib = _check_sibling(parent, got_p, ref_p, child, got_c, ref_c, np.abs(host.g64).sum(), np.abs(host.h64).sum(),
+                         "config5 child")
     assert (sib["count"][10, 0] == 0)
+
+
+def test_near_tie_band_usage_is_reported():
+    """Runs last in this file: how often the near-tie band was needed above."""
+    _say(f"near-tie decisions in the full-size checks: {len(near_ties)} {near_ties}")
+    assert all(gap >= 0 for _, gap in near_ties)
