@@ -35,7 +35,7 @@
  *    allocates a larger buffer (hipMalloc) and keeps the old one until gbdt_reset; it never
  *    frees or synchronises inside an enqueuing call.  During stream capture growing is
  *    refused (GBDT_ENOMEM): issue the same call once outside the capture first, or register
- *    a caller buffer (gbdt_set_workspace).
+ *    a caller buffer (gbdt_set_workspace), or use gbdt_hist_build_noalloc.
  *  - Size limits: n_rows < 2^30, and byte offsets inside a feature tile are 32-bit:
  *    (n_rows + 512) x tile width < 2^32, i.e. n_rows < 67,108,352 with up to 64 bins
  *    (64-byte tiles) and n_rows < 134,217,216 with more (32-byte tiles); at most 65,535
@@ -149,6 +149,28 @@ int gbdt_bins_pack(const uint8_t* bins_rowmajor, int64_t n_rows, int32_t n_featu
 int gbdt_hist_build(const void* bin_matrix, int64_t n_rows, int32_t n_features, int32_t n_bins,
                     const int32_t* leaf_row_idx, int64_t n_leaf_rows, const float* grad,
                     const float* hess, gbdt_bin_t* hist_out, void* stream);
+
+/*
+ * gbdt_hist_build for callers that cannot allocate: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, same results and error
+ * bound as gbdt_hist_build, but the scratch (unit counters and the workgroups' partial
+ * histograms) is a fixed array inside the library's device code -- 64 MiB of partial
+ * histograms plus a 256 KiB head, one copy per GPU the library runs on, held until the
+ * process ends -- and the call neither allocates, frees nor synchronises (no hipMalloc /
+ * hipFree, no profiling events, no row-id checking pass; it ignores gbdt_set_workspace and
+ * gbdt_profile_enable).  A leaf whose usual grid would write more partial histograms than
+ * the array holds is built with fewer workgroups per feature tile (slower, same result up
+ * to the summation order); if even one workgroup per tile does not fit (roughly n_features
+ * x bin capacity x 12 bytes > 64 MiB, e.g. more than 21,800 features at 256 bins) the call
+ * returns GBDT_EUNSUPPORTED and gbdt_last_hip_error() says so.  The array keeps the last
+ * call's contents; every call clears the counters it uses itself.  All calls on one GPU
+ * share the array: calls that overlap on one GPU (two streams, two threads) race.
+ * gbdt_hist_build_noalloc_max_partial_bytes: the capacity for partial histograms.
+ */
+int gbdt_hist_build_noalloc(const void* bin_matrix, int64_t n_rows, int32_t n_features,
+                            int32_t n_bins, const int32_t* leaf_row_idx, int64_t n_leaf_rows,
+                            const float* grad, const float* hess, gbdt_bin_t* hist_out, void* stream);
+size_t gbdt_hist_build_noalloc_max_partial_bytes(void);
 
 /*
  * Feature histograms of several leaves in one call: hist_out[l] is what gbdt_hist_build

@@ -27,6 +27,7 @@ EXPORTS = [
     "gbdt_debug_batch_plan", "gbdt_grow_tree", "gbdt_grow_tree_scratch_bytes",
     "gbdt_partition_rows_batch", "gbdt_grow_tree_depthwise", "gbdt_grow_tree_depthwise_scratch_bytes",
     "gbdt_set_wide_accumulation", "gbdt_profile_durations", "gbdt_reset",
+    "gbdt_hist_build_noalloc", "gbdt_hist_build_noalloc_max_partial_bytes",
 ]
 
 # numpy views of the two C structs
@@ -63,6 +64,10 @@ def load():
     lib.gbdt_hist_build.restype = c.c_int
     lib.gbdt_hist_build.argtypes = [c.c_void_p, c.c_int64, c.c_int32, c.c_int32, c.c_void_p,
                                     c.c_int64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p]
+    lib.gbdt_hist_build_noalloc.restype = c.c_int
+    lib.gbdt_hist_build_noalloc.argtypes = lib.gbdt_hist_build.argtypes
+    lib.gbdt_hist_build_noalloc_max_partial_bytes.restype = c.c_size_t
+    lib.gbdt_hist_build_noalloc_max_partial_bytes.argtypes = []
     lib.gbdt_profile_durations.restype = c.c_int
     lib.gbdt_profile_durations.argtypes = [c.POINTER(c.c_double), c.c_int64, c.POINTER(c.c_int64)]
     lib.gbdt_reset.restype = c.c_int
@@ -208,6 +213,17 @@ def gbdt_hist_build(bin_matrix, n_rows, n_features, n_bins, leaf_row_idx, n_leaf
                                    _dev(hist_out, torch.float32, "hist_out"), _stream(stream)),
            _entry)
     return hist_out
+
+
+def gbdt_hist_build_noalloc(bin_matrix, n_rows, n_features, n_bins, leaf_row_idx, n_leaf_rows, grad, hess,
+                            hist_out, stream=None):
+    """gbdt_hist_build through the entry point that allocates nothing; hist_out is required."""
+    return gbdt_hist_build(bin_matrix, n_rows, n_features, n_bins, leaf_row_idx, n_leaf_rows, grad, hess,
+                           hist_out=hist_out, stream=stream, _entry="gbdt_hist_build_noalloc")
+
+
+def gbdt_hist_build_noalloc_max_partial_bytes() -> int:
+    return int(load().gbdt_hist_build_noalloc_max_partial_bytes())
 
 
 def gbdt_reset() -> None:

@@ -38,6 +38,15 @@
 #include "split_kernels.h"
 #include "partition_kernels.h"
 
+// Scratch of the no-allocation entry point (gbdt_hist_build_noalloc): the unit counters
+// (256 KiB head, as in every scratch buffer of this library) and up to 64 MiB of partial
+// histograms.  One copy per GPU the library runs on, held until the process ends.  In host
+// code this name is only a stand-in for the symbol: the device address is looked up once
+// per device (noalloc_scratch_ptr) and that pointer is what kernels and fills receive.
+constexpr size_t kNoAllocPartialBytes = (size_t)64 << 20;
+constexpr size_t kNoAllocScratchBytes = (size_t)65536 * sizeof(uint32_t) + kNoAllocPartialBytes;
+static __device__ __align__(256) unsigned char scratch[kNoAllocScratchBytes];
+
 namespace {
 
 // ------------------------------------------------------- calibration copy kernel
@@ -84,6 +93,7 @@ Workspace g_ws;
 // feature tile, at most 65535 tiles); the scratch handed to a call starts behind it.
 constexpr int kCounterSlots = 65536;
 constexpr size_t kWsHeadBytes = (size_t)kCounterSlots * sizeof(uint32_t);
+static_assert(kNoAllocScratchBytes == kWsHeadBytes + kNoAllocPartialBytes, "head of the fixed scratch");
 
 bool stream_is_capturing(hipStream_t s) {
   hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
@@ -152,6 +162,26 @@ void set_counters_zero(uint32_t* counters, bool zero) {
   } else if (g_ws.zeroed == counters) {
     g_ws.zeroed = nullptr;
   }
+}
+
+// Device address of `scratch` on the current device, looked up on the first call there
+// (every GPU holds its own copy of the array at its own address).
+constexpr int kMaxDevices = 64;
+int noalloc_scratch_ptr(void** out) {
+  static std::mutex mu;
+  static void* ptr[kMaxDevices] = {};
+  int dev = 0;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return GBDT_EUNSUPPORTED;
+  std::lock_guard<std::mutex> lk(mu);
+  if (!ptr[dev]) {
+    void* q = nullptr;
+    HIP_TRY(hipGetSymbolAddress(&q, HIP_SYMBOL(scratch)));
+    if (!q) return GBDT_EHIP;
+    ptr[dev] = q;
+  }
+  *out = ptr[dev];
+  return GBDT_OK;
 }
 
 // Optional timing of the build kernel alone (it shares its C-ABI call with the merge
@@ -817,6 +847,18 @@ int gbdt_hist_build(const void* bin_matrix, int64_t n_rows, int32_t n_features, 
   return hist_build_impl(bin_matrix, n_rows, n_features, n_bins, leaf_row_idx, n_leaf_rows, grad, hess, hist_out,
                          stream, nullptr, 0);
 }
+
+int gbdt_hist_build_noalloc(const void* bin_matrix, int64_t n_rows, int32_t n_features, int32_t n_bins,
+                            const int32_t* leaf_row_idx, int64_t n_leaf_rows, const float* grad,
+                            const float* hess, gbdt_bin_t* hist_out, void* stream) {
+  void* base = nullptr;
+  const int rc = noalloc_scratch_ptr(&base);
+  if (rc != GBDT_OK) return rc;
+  return hist_build_impl(bin_matrix, n_rows, n_features, n_bins, leaf_row_idx, n_leaf_rows, grad, hess, hist_out,
+                         stream, base, kNoAllocScratchBytes);
+}
+
+size_t gbdt_hist_build_noalloc_max_partial_bytes(void) { return kNoAllocPartialBytes; }
 
 int gbdt_hist_build_batch(const void* bin_matrix, int64_t n_rows, int32_t n_features,
                           int32_t n_bins, const int32_t* row_idx, const int64_t* leaf_offsets,
