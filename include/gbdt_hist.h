@@ -111,6 +111,39 @@ int gbdt_bins_pack(const uint8_t* bins_rowmajor, int64_t n_rows, int32_t n_featu
                    int32_t n_bins, void* packed_out, void* stream);
 
 /*
+ * Fused columns for features with few distinct bins (optional, n_bins <= 64 only).  The paper
+ * stores features of at most 16 bins in 4 bits (App. C.4) and spreads a feature that uses few
+ * of its bins over MORE counters to cut atomic conflicts (Alg. 3, App. A.3).  On this part
+ * conflicts cost nothing and the number of local-memory atomic instructions bounds the build,
+ * so features with few levels are merged into FEWER counters: features whose level counts
+ * multiply to at most 64 share one byte per row (a mixed-radix number of their bins), the
+ * build accumulates that column's joint histogram with ONE atomic per row, and every
+ * feature's histogram is a marginal of it (exact for counts; one more fp64 sum of at most 64
+ * fp32 terms for gradients and hessians).  Constant features ride along for free.
+ * gbdt_bins_fuse finds each feature's largest bin value on the device, plans the columns on
+ * the host and, if at most 85 % as many columns as features result, writes the fused copy
+ * into fused_out and remembers it for `packed`: later gbdt_hist_build /
+ * gbdt_hist_build_noalloc calls with that bin_matrix address and shape build leaves of at
+ * least 8192 rows from the fused copy (not with wide accumulation, whose stored sums are
+ * exact sums rounded once).  Results and error bound are those of the plain path.  Unlike the
+ * other calls it WAITS for the stream (it reads the maxima on the host).
+ *   bins_rowmajor   DEVICE, the matrix gbdt_bins_pack packed
+ *   packed          DEVICE address gbdt_bins_pack wrote to (used as a key only; a buffer
+ *                   copied elsewhere is simply built from its plain tiles)
+ *   fused_out       DEVICE, 256-byte aligned, fused_bytes >= gbdt_bins_fused_bytes(...) (0:
+ *                   this shape is never fused); owned by the caller, to be kept as long as
+ *                   `packed` is used or until gbdt_bins_unfuse(packed) / a new gbdt_bins_pack
+ *                   to that address
+ *   n_columns_out   HOST: the number of fused columns, 0 when fusing does not pay (nothing
+ *                   is remembered then and fused_out may be freed)
+ */
+size_t gbdt_bins_fused_bytes(int64_t n_rows, int32_t n_features, int32_t n_bins);
+int gbdt_bins_fuse(const uint8_t* bins_rowmajor, int64_t n_rows, int32_t n_features, int32_t n_bins,
+                   const void* packed, void* fused_out, size_t fused_bytes, int32_t* n_columns_out,
+                   void* stream);
+int gbdt_bins_unfuse(const void* packed);
+
+/*
  * Feature histograms of one leaf (Alg. 1 for every feature; Sec. 4 and
  * App. A.1 for the GPU organisation: work split by features and by samples,
  * per-workgroup histograms in local memory, a final reduction pass).
@@ -303,7 +336,7 @@ int gbdt_partition_rows(const void* bin_matrix, int64_t n_rows, int32_t n_featur
  * row_idx[leaf_offsets[l] .. leaf_offsets[l + 1]) and the split record splits[l]; its children
  * are written to the same positions of children_out (left rows, then right rows, order
  * kept), so the children of a whole level again lie back to back and can go straight into
- * gbdt_hist_build_batch.  Two kernel launches per 256 leaves.
+ * gbdt_hist_build_batch.  Two kernel launches per 224 leaves.
  *   row_idx        DEVICE int32, row ids in [0, n_rows)
  *   leaf_offsets   HOST int64 [n_leaves + 1], non-decreasing, read before the call returns
  *   splits         DEVICE gbdt_split_t [n_leaves]; a record without a split keeps all rows left
@@ -338,23 +371,30 @@ typedef struct {
  * histograms resident on the device (Sec. 3.1: start from the root and keep splitting
  * leaves; Sec. 5: stop at a fixed number of leaves, 255 in the experiments, at least one
  * sample per leaf; App. A.5 / App. C.1: what the CPU does around the histogram kernel --
- * rebuild and copy the index list after each split -- is done here by
- * gbdt_partition_rows, so nothing but two 36-byte split records per split crosses the
- * bus).  The paper does not say which leaf is split next; this takes the open leaf whose
- * best split has the largest gain (it must exceed min_split_gain), the older leaf on
- * equal gains.  Per split: partition the leaf's rows, build the histogram of the smaller
- * child, subtract it from the parent's for the sibling, search both for their best split.
+ * rebuild and copy the index list after each split -- is done here on the device, so
+ * nothing but 36-byte split records crosses the bus).  The paper does not say which leaf is
+ * split next; this takes the open leaf whose best split has the largest gain (it must exceed
+ * min_split_gain), the older leaf on equal gains.  Per split: partition the leaf's rows,
+ * build the histogram of the smaller child, subtract it from the parent's for the sibling,
+ * search both for their best split.  That rule is sequential; to wait for the device once
+ * per ROUND rather than once per split, a round does this work for up to 32 open leaves at
+ * once (batched calls), and the host then applies the rule to what it knows, stopping at the
+ * first leaf whose children it has not seen.  The tree is exactly the sequential rule's; work
+ * on a leaf the rule never reaches before max_leaves is used up is dropped.
  *   grad, hess       DEVICE float [n_rows]
  *   max_leaves       >= 1; growth also stops when no open leaf has an admissible split
  *   scratch          DEVICE, 256-byte aligned, gbdt_grow_tree_scratch_bytes(...) bytes
- *                    (two row lists, max_leaves histograms, the split records); the
- *                    calls inside also use the library's scratch workspace
+ *                    (two row lists, half a row list for the smaller children of a round,
+ *                    about 3 x max_leaves histograms, the split records); the calls inside
+ *                    also use the library's scratch workspace
  *   nodes_out        HOST gbdt_tree_node_t [2 * max_leaves - 1]
  *   n_nodes_out      HOST, receives the number of nodes written (always odd)
  *   row_order_out    DEVICE int32 [n_rows] or NULL: all row ids, grouped by leaf, ascending
  *                    inside each node's segment (see row_begin)
- * Unlike the other calls this one WAITS for `stream` (once per split, to read the two
- * new split records) and allocates a few bytes of page-locked host memory on first use.
+ * Unlike the other calls this one WAITS for `stream` (once per round, to read the new split
+ * records) and allocates a few KB of page-locked host memory on first use.  The histograms
+ * of a round are built by gbdt_hist_build_batch, whose split of rows among workgroups is
+ * fixed: the same call gives the same tree, bit for bit, every time.
  */
 int gbdt_grow_tree(const void* bin_matrix, int64_t n_rows, int32_t n_features, int32_t n_bins,
                    const float* grad, const float* hess, int32_t max_leaves, float lambda,
@@ -462,6 +502,11 @@ int gbdt_debug_geometry(int32_t n_features, int32_t n_bins, int64_t n_leaf_rows,
 int gbdt_debug_batch_plan(int32_t n_features, int32_t n_bins, const int64_t* leaf_offsets,
                           int32_t n_leaves, int32_t n_cus, int32_t wg_per_cu, int32_t* leaf_wgs_out,
                           int32_t* leaf_unit_epochs_out, int32_t* block_out, int32_t max_blocks);
+/* The column plan gbdt_bins_fuse makes for features with the given numbers of levels (1..64
+ * each): col_out[f] / stride_out[f] = the column of feature f and the weight of its bin in the
+ * column's joint value; *n_cols_out the number of columns.  Host only. */
+int gbdt_debug_fusion_plan(const uint32_t* levels, int32_t n_features, int32_t* col_out, int32_t* stride_out,
+                           int32_t* n_cols_out);
 /* Resident workgroups per compute unit of the build kernel variant that serves
  * n_bins (indexed != 0: the variant that gathers through leaf_row_idx), as the HIP
  * runtime reports it on the current device; 0 if the query is not possible. */

@@ -28,6 +28,7 @@ EXPORTS = [
     "gbdt_partition_rows_batch", "gbdt_grow_tree_depthwise", "gbdt_grow_tree_depthwise_scratch_bytes",
     "gbdt_set_wide_accumulation", "gbdt_profile_durations", "gbdt_reset",
     "gbdt_hist_build_noalloc", "gbdt_hist_build_noalloc_max_partial_bytes",
+    "gbdt_bins_fused_bytes", "gbdt_bins_fuse", "gbdt_bins_unfuse", "gbdt_debug_fusion_plan",
 ]
 
 # numpy views of the two C structs
@@ -61,6 +62,13 @@ def load():
     lib.gbdt_bins_packed_bytes.argtypes = [c.c_int64, c.c_int32, c.c_int32]
     lib.gbdt_bins_pack.restype = c.c_int
     lib.gbdt_bins_pack.argtypes = [c.c_void_p, c.c_int64, c.c_int32, c.c_int32, c.c_void_p, c.c_void_p]
+    lib.gbdt_bins_fused_bytes.restype = c.c_size_t
+    lib.gbdt_bins_fused_bytes.argtypes = [c.c_int64, c.c_int32, c.c_int32]
+    lib.gbdt_bins_fuse.restype = c.c_int
+    lib.gbdt_bins_fuse.argtypes = [c.c_void_p, c.c_int64, c.c_int32, c.c_int32, c.c_void_p, c.c_void_p,
+                                   c.c_size_t, c.POINTER(c.c_int32), c.c_void_p]
+    lib.gbdt_bins_unfuse.restype = c.c_int
+    lib.gbdt_bins_unfuse.argtypes = [c.c_void_p]
     lib.gbdt_hist_build.restype = c.c_int
     lib.gbdt_hist_build.argtypes = [c.c_void_p, c.c_int64, c.c_int32, c.c_int32, c.c_void_p,
                                     c.c_int64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p]
@@ -175,8 +183,44 @@ def gbdt_set_workspace(buf) -> None:
                "gbdt_set_workspace")
 
 
-def gbdt_bins_pack(bins_rowmajor: torch.Tensor, n_bins: int, packed_out=None, stream=None):
-    """bins_rowmajor: uint8 [n_rows, n_features] on the GPU.  Returns the packed uint8 buffer."""
+FUSE_MIN_ROWS = 8192   # gbdt_bins_pack tries gbdt_bins_fuse from this many rows on (fuse=None)
+
+
+def gbdt_bins_fused_bytes(n_rows: int, n_features: int, n_bins: int) -> int:
+    return int(load().gbdt_bins_fused_bytes(n_rows, n_features, n_bins))
+
+
+def gbdt_bins_fuse(bins_rowmajor: torch.Tensor, n_bins: int, packed: torch.Tensor, stream=None):
+    """Makes the fused copy of few-level features for `packed` when it pays.  Returns (n_columns,
+    fused tensor or None); the tensor is also attached to `packed` (attribute `gbdt_fused`) so
+    that it lives as long as the packed buffer does."""
+    lib = load()
+    n_rows, n_features = bins_rowmajor.shape
+    nbytes = int(lib.gbdt_bins_fused_bytes(n_rows, n_features, n_bins))
+    packed.gbdt_fused = None
+    if nbytes == 0:
+        _check(lib.gbdt_bins_unfuse(_dev(packed, torch.uint8, "packed")), "gbdt_bins_unfuse")
+        return 0, None
+    fused = torch.empty(nbytes, dtype=torch.uint8, device=bins_rowmajor.device)
+    n_cols = ctypes.c_int32(0)
+    _check(lib.gbdt_bins_fuse(_dev(bins_rowmajor, torch.uint8, "bins_rowmajor"), n_rows, n_features, n_bins,
+                              _dev(packed, torch.uint8, "packed"), _dev(fused, torch.uint8, "fused"), nbytes,
+                              ctypes.byref(n_cols), _stream(stream)), "gbdt_bins_fuse")
+    if n_cols.value == 0:
+        return 0, None
+    packed.gbdt_fused = fused
+    return n_cols.value, fused
+
+
+def gbdt_bins_unfuse(packed: torch.Tensor) -> None:
+    _check(load().gbdt_bins_unfuse(_dev(packed, torch.uint8, "packed")), "gbdt_bins_unfuse")
+    packed.gbdt_fused = None
+
+
+def gbdt_bins_pack(bins_rowmajor: torch.Tensor, n_bins: int, packed_out=None, stream=None, fuse=None):
+    """bins_rowmajor: uint8 [n_rows, n_features] on the GPU.  Returns the packed uint8 buffer.
+    fuse: True / False: also call gbdt_bins_fuse (which waits for the stream) or not; None: from
+    FUSE_MIN_ROWS rows on."""
     src = _dev(bins_rowmajor, torch.uint8, "bins_rowmajor")
     n_rows, n_features = bins_rowmajor.shape
     nbytes = gbdt_bins_packed_bytes(n_rows, n_features, n_bins)
@@ -189,6 +233,10 @@ def gbdt_bins_pack(bins_rowmajor: torch.Tensor, n_bins: int, packed_out=None, st
     _check(load().gbdt_bins_pack(src, n_rows, n_features, n_bins,
                                  _dev(packed_out, torch.uint8, "packed_out"), _stream(stream)),
            "gbdt_bins_pack")
+    if fuse is None:
+        fuse = n_rows >= FUSE_MIN_ROWS
+    if fuse and n_rows > 0:
+        gbdt_bins_fuse(bins_rowmajor, n_bins, packed_out, stream=stream)
     return packed_out
 
 
@@ -452,6 +500,21 @@ def gbdt_debug_batch_plan(n_features, n_bins, leaf_offsets, n_cus=256, wg_per_cu
                                    ue.ctypes.data, blocks.ctypes.data, n)
     _check(min(n2, 0), "gbdt_debug_batch_plan")
     return wgs[:n_leaves], ue[:n_leaves], blocks[:n]
+
+
+def gbdt_debug_fusion_plan(levels):
+    """(column of every feature, weight of its bin in the column's joint value, number of columns)."""
+    lib = load()
+    lv = np.ascontiguousarray(levels, dtype=np.uint32)
+    F = lv.shape[0]
+    col, stride = np.zeros(F, np.int32), np.zeros(F, np.int32)
+    n = ctypes.c_int32(0)
+    lib.gbdt_debug_fusion_plan.restype = ctypes.c_int
+    lib.gbdt_debug_fusion_plan.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p,
+                                           ctypes.POINTER(ctypes.c_int32)]
+    _check(lib.gbdt_debug_fusion_plan(lv.ctypes.data, F, col.ctypes.data, stride.ctypes.data, ctypes.byref(n)),
+           "gbdt_debug_fusion_plan")
+    return col, stride, n.value
 
 
 def gbdt_debug_occupancy(n_bins: int, indexed: bool) -> int:

@@ -26,6 +26,7 @@
 #include <atomic>
 #include <mutex>
 #include <type_traits>
+#include <unordered_map>
 #include <utility>
 #include <vector>
 
@@ -182,6 +183,99 @@ int noalloc_scratch_ptr(void** out) {
   }
   *out = ptr[dev];
   return GBDT_OK;
+}
+
+// ---- fused columns (see FusedCol in hist_build_kernels.h): which packed matrices have a fused
+// copy, keyed by the address gbdt_bins_pack wrote them to
+struct FusedEntry {
+  const uint8_t* tiles = nullptr;     // the fused copy's feature tiles
+  const FusedFeat* feats = nullptr;   // [n_features] on the device, inside the fused copy
+  int64_t n_rows = 0;
+  int32_t n_features = 0, n_bins = 0, n_cols = 0;
+};
+std::mutex g_fused_mu;
+std::unordered_map<const void*, FusedEntry> g_fused;
+
+bool fused_lookup(const void* packed, int64_t n_rows, int32_t n_features, int32_t n_bins, FusedEntry* out) {
+  static const bool off = [] {
+    const char* e = getenv("GBDT_HIST_NO_FUSE");  // tuning experiments: always build from the plain tiles
+    return e && atoi(e) > 0;
+  }();
+  if (off) return false;
+  std::lock_guard<std::mutex> lk(g_fused_mu);
+  auto it = g_fused.find(packed);
+  if (it == g_fused.end()) return false;
+  const FusedEntry& e = it->second;
+  if (e.n_rows != n_rows || e.n_features != n_features || e.n_bins != n_bins) return false;
+  *out = e;
+  return true;
+}
+
+// Leaves below this many rows are built from the plain tiles: the extra launch that takes the
+// marginals costs more than the atomics the fused columns save.
+constexpr int64_t kFusedMinLeafRows = 8192;
+// A fused copy is made when it has at most this fraction of the features as columns.
+constexpr double kFusedMaxColumnRatio = 0.85;
+
+// Packs features into columns of at most kFusedCap joint levels: features in descending order
+// of their level counts, each into the fullest column that still takes it (best fit).
+void plan_fusion(const std::vector<uint32_t>& levels, std::vector<FusedCol>* cols, std::vector<FusedFeat>* feats) {
+  const int32_t F = (int32_t)levels.size();
+  std::vector<int32_t> order(F);
+  for (int32_t f = 0; f < F; ++f) order[f] = f;
+  std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return levels[a] > levels[b]; });
+  std::vector<uint32_t> prod;                          // joint levels of every column so far
+  std::vector<std::vector<int32_t>> open(kFusedCap + 1);  // columns by joint levels, with room for another part
+  cols->clear();
+  feats->assign(F, FusedFeat{});
+  for (int32_t f : order) {
+    const uint32_t L = levels[f] < 1 ? 1 : levels[f];
+    int32_t c = -1;
+    for (uint32_t pr = kFusedCap / L; pr >= 1 && c < 0; --pr) {
+      if (!open[pr].empty()) {
+        c = open[pr].back();
+        open[pr].pop_back();
+      }
+    }
+    if (c < 0) {
+      c = (int32_t)cols->size();
+      FusedCol col;
+      for (int k = 0; k < kFusedMaxParts; ++k) {
+        col.feature[k] = -1;
+        col.stride[k] = 0;
+      }
+      col.n_parts = 0;
+      col.pad = 0;
+      cols->push_back(col);
+      prod.push_back(1);
+    }
+    FusedCol& col = (*cols)[c];
+    col.feature[col.n_parts] = f;
+    col.stride[col.n_parts] = (uint8_t)prod[c];
+    FusedFeat& ff = (*feats)[f];
+    ff.col = c;
+    ff.stride = (uint8_t)prod[c];
+    ff.levels = (uint8_t)L;
+    ff.pad[0] = ff.pad[1] = 0;
+    col.n_parts += 1;
+    prod[c] *= L;
+    if (col.n_parts < kFusedMaxParts && prod[c] <= kFusedCap) open[prod[c]].push_back(c);
+  }
+}
+
+// Byte layout of a fused copy with n_cols columns: [feature tiles][slack][FusedFeat x n_features][FusedCol x n_cols]
+struct FusedLayout {
+  TilePlan plan;
+  size_t feats_off, cols_off, total;
+};
+FusedLayout fused_layout(int64_t n_rows, int32_t n_features, int32_t n_cols) {
+  FusedLayout l;
+  l.plan = make_tile_plan(n_cols, kFusedCap);
+  const size_t tiles = (size_t)n_rows * l.plan.row_bytes + (size_t)kPlanSlackBytes;
+  l.feats_off = (tiles + 255) / 256 * 256;
+  l.cols_off = (l.feats_off + (size_t)n_features * sizeof(FusedFeat) + 255) / 256 * 256;
+  l.total = (l.cols_off + (size_t)n_cols * sizeof(FusedCol) + 255) / 256 * 256;
+  return l;
 }
 
 // Optional timing of the build kernel alone (it shares its C-ABI call with the merge
@@ -516,25 +610,41 @@ int launch_split(const gbdt_bin_t* hists, int64_t hist_stride, int32_t n_hists, 
 // Scratch of gbdt_grow_tree.
 size_t align256(size_t b) { return (b + 255) / 256 * 256; }
 
+// gbdt_grow_tree expands up to kGrowRound open leaves per round (one wait for the stream per
+// round instead of one per split) and may expand leaves that best-first growth never gets to
+// before the leaf budget is used up; the histogram pool is sized for the splits of the tree plus
+// that many speculative ones.
+constexpr int kGrowRound = 32;
+int32_t grow_speculative_budget(int32_t max_leaves) { return (max_leaves - 1) / 2 + 16; }
+int32_t grow_max_expansions(int32_t max_leaves) { return (max_leaves - 1) + grow_speculative_budget(max_leaves); }
+
 struct TreeScratch {
-  size_t rows_a, rows_b, hists, recs, total;  // byte offsets
+  size_t rows_a, rows_b, rows_small, hists, recs, part_recs, total;  // byte offsets
+  size_t row_elems;   // int32 entries between the two row buffers
+  int32_t n_slots;    // histograms in the pool
 };
 
 TreeScratch tree_scratch_layout(int64_t n_rows, int32_t n_features, int32_t n_bins, int32_t max_leaves) {
   TreeScratch t;
   const size_t rows = align256((size_t)(n_rows > 0 ? n_rows : 1) * sizeof(int32_t));
+  t.row_elems = rows / sizeof(int32_t);
+  t.n_slots = 1 + 2 * grow_max_expansions(max_leaves);
   t.rows_a = 0;
   t.rows_b = rows;
-  t.hists = 2 * rows;
-  t.recs = t.hists + align256((size_t)max_leaves * n_features * n_bins * sizeof(gbdt_bin_t));
-  t.total = t.recs + align256((size_t)2 * max_leaves * sizeof(gbdt_split_t));
+  t.rows_small = 2 * rows;  // the smaller children of a round: at most half of the rows
+  t.hists = t.rows_small + align256(((size_t)(n_rows > 0 ? n_rows : 1) / 2 + 1) * sizeof(int32_t));
+  t.recs = t.hists + align256((size_t)t.n_slots * n_features * n_bins * sizeof(gbdt_bin_t));
+  t.part_recs = t.recs + align256((size_t)t.n_slots * sizeof(gbdt_split_t));
+  t.total = t.part_recs + align256((size_t)kGrowRound * sizeof(gbdt_split_t));
   return t;
 }
 
-// Two split records in page-locked host memory that the device can write: the split search
-// of gbdt_grow_tree stores its two records there as well, and the host reads them after
-// waiting for the stream, without a copy (one per process, never freed).  *dev_out: the
-// address the device uses for it.
+// Page-locked host memory of gbdt_grow_tree (one block per process, never freed): the split
+// records of a round, which the split search writes there as well as to device memory (the
+// host reads them after waiting for the stream, without a copy), and the records a round's
+// partition is driven by, staged for their copy to the device.  *dev_out: the address the
+// device uses for the first part.
+constexpr int kGrowPinnedRecs = 3 * kGrowRound;
 gbdt_split_t* pinned_records(gbdt_split_t** dev_out) {
   static gbdt_split_t* p = nullptr;
   static gbdt_split_t* d = nullptr;
@@ -542,7 +652,7 @@ gbdt_split_t* pinned_records(gbdt_split_t** dev_out) {
   std::lock_guard<std::mutex> lk(mu);
   if (!p) {
     void* q = nullptr;
-    if (hipHostMalloc(&q, 2 * sizeof(gbdt_split_t), hipHostMallocMapped) != hipSuccess) {
+    if (hipHostMalloc(&q, kGrowPinnedRecs * sizeof(gbdt_split_t), hipHostMallocMapped) != hipSuccess) {
       (void)hipGetLastError();
       return nullptr;
     }
@@ -633,11 +743,25 @@ int hist_build_impl(const void* bin_matrix, int64_t n_rows, int32_t n_features, 
   }
 
   const bool wide = g_wide.load() != 0;
+  // A fused copy of the matrix (few-level features sharing columns): the build kernel then sees
+  // build_f one-byte columns of kFusedCap joint bins, and the marginals are taken at the end.
+  FusedEntry fe;
+  // (not with wide accumulation: the joint histograms are rounded to fp32 before the marginals are
+  // taken, which would break that mode's promise of the exact sum rounded once)
+  const bool fused =
+      !wide && n_leaf_rows >= kFusedMinLeafRows && fused_lookup(bin_matrix, n_rows, n_features, n_bins, &fe);
+  const int32_t real_features = n_features, real_bins = n_bins;
+  if (fused) {
+    n_features = fe.n_cols;
+    n_bins = kFusedCap;
+  }
+  const size_t joint_words = fused ? (size_t)n_features * n_bins * 3 : 0;
   const int wg_per_cu = build_wg_per_cu(make_tile_plan(n_features, n_bins).cap, leaf_row_idx != nullptr, wide);
   BuildGeom g = make_geom(n_features, n_bins, n_leaf_rows, device_cu_count(), wg_per_cu, wide);
   if (fixed_base) {
     // fewer workgroups per tile until the partial blocks fit the fixed buffer
-    const size_t avail_words = fixed_bytes > kWsHeadBytes ? (fixed_bytes - kWsHeadBytes) / 4 : 0;
+    size_t avail_words = fixed_bytes > kWsHeadBytes ? (fixed_bytes - kWsHeadBytes) / 4 : 0;
+    avail_words = avail_words > joint_words ? avail_words - joint_words : 0;
     if (g.partial_words > avail_words) {
       const size_t per_wg = g.partial_words / (size_t)g.wgs;  // words of one workgroup of every tile
       const int64_t fit = (int64_t)(avail_words / per_wg);
@@ -663,7 +787,7 @@ int hist_build_impl(const void* bin_matrix, int64_t n_rows, int32_t n_features, 
   size_t stats_words = by_pos ? 2 * (((size_t)n_leaf_rows + 63) / 64 * 64) : 0;
   int rc = GBDT_OK;
   if (fixed_base) {
-    if (kWsHeadBytes + (g.partial_words + stats_words) * 4 > fixed_bytes) {  // the gather is optional
+    if (kWsHeadBytes + (g.partial_words + joint_words + stats_words) * 4 > fixed_bytes) {  // the gather is optional
       by_pos = false;
       stats_words = 0;
     }
@@ -671,23 +795,25 @@ int hist_build_impl(const void* bin_matrix, int64_t n_rows, int32_t n_features, 
     ws = (char*)fixed_base + kWsHeadBytes;
     counters_zero = false;
   } else {
-    rc = get_workspace((g.partial_words + stats_words) * 4, s, &ws, &counters, &counters_zero);
+    rc = get_workspace((g.partial_words + joint_words + stats_words) * 4, s, &ws, &counters, &counters_zero);
     if (rc == GBDT_ENOMEM && by_pos) {  // a caller's workspace sized for the partial blocks alone: no gather
       by_pos = false;
       stats_words = 0;
-      rc = get_workspace(g.partial_words * 4, s, &ws, &counters, &counters_zero);
+      rc = get_workspace((g.partial_words + joint_words) * 4, s, &ws, &counters, &counters_zero);
     }
   }
   if (rc != GBDT_OK) return rc;
 
+  // scratch: [partial blocks][joint histograms of the fused columns][grad / hess in leaf order]
+  gbdt_bin_t* joint = (gbdt_bin_t*)((uint32_t*)ws + g.partial_words);
   BuildArgs a;
-  a.packed = (const uint8_t*)bin_matrix;
+  a.packed = fused ? fe.tiles : (const uint8_t*)bin_matrix;
   a.idx = leaf_row_idx;
   a.grad = grad;
   a.hess = hess;
   a.stats_by_pos = 0;
   if (by_pos) {
-    float* g_leaf = (float*)ws + g.partial_words;
+    float* g_leaf = (float*)ws + g.partial_words + joint_words;
     float* h_leaf = g_leaf + stats_words / 2;
     hipLaunchKernelGGL(stats_gather_kernel, dim3((unsigned)((n_leaf_rows + 255) / 256)), dim3(256), 0, s,
                        leaf_row_idx, grad, hess, n_leaf_rows, g_leaf, h_leaf);
@@ -707,7 +833,7 @@ int hist_build_impl(const void* bin_matrix, int64_t n_rows, int32_t n_features, 
   a.unit_epochs = g.unit_epochs;
   // no counter when every workgroup has one unit anyway, or when the split must be fixed
   a.fixed_stride = (g.one_unit_each || g_deterministic.load()) ? g.wgs : 0;
-  a.direct_out = g.wgs == 1 ? hist_out : nullptr;
+  a.direct_out = (g.wgs == 1 && !fused) ? hist_out : nullptr;  // (joint histograms always take the reduction pass)
   a.n_features = n_features;
   a.n_bins = n_bins;
   const int n_tiles = plan_n_tiles(p);
@@ -755,7 +881,7 @@ int hist_build_impl(const void* bin_matrix, int64_t n_rows, int32_t n_features, 
 
   MergeArgs m;
   m.partials = (const uint32_t*)ws;
-  m.out = hist_out;
+  m.out = fused ? joint : hist_out;
   m.plan = p;
   m.n_features = n_features;
   m.n_bins = n_bins;
@@ -768,6 +894,12 @@ int hist_build_impl(const void* bin_matrix, int64_t n_rows, int32_t n_features, 
                      0, s, m);
   HIP_TRY(hipGetLastError());
   if (uses_counters && !capturing) set_counters_zero(counters, true);  // the reduction pass leaves them zero
+  if (fused) {
+    const int32_t n = real_features * real_bins;
+    hipLaunchKernelGGL(hist_unfuse_kernel, dim3((n + 255) / 256), dim3(256), 0, s, (const gbdt_bin_t*)joint, fe.feats,
+                       real_features, real_bins, hist_out);
+    HIP_TRY(hipGetLastError());
+  }
   return GBDT_OK;
 }
 
@@ -787,6 +919,7 @@ size_t gbdt_bins_packed_bytes(int64_t n_rows, int32_t n_features, int32_t n_bins
 int gbdt_bins_pack(const uint8_t* bins_rowmajor, int64_t n_rows, int32_t n_features,
                    int32_t n_bins, void* packed_out, void* stream) {
   if (!valid_shape(n_rows, n_features, n_bins)) return GBDT_EINVAL;
+  if (packed_out) (void)gbdt_bins_unfuse(packed_out);  // a fused copy registered for this address is stale now
   if (n_rows == 0) return GBDT_OK;
   if (!bins_rowmajor || !packed_out) return GBDT_EINVAL;
   if (((uintptr_t)packed_out & 15u) != 0) return GBDT_EINVAL;
@@ -809,6 +942,88 @@ int gbdt_bins_pack(const uint8_t* bins_rowmajor, int64_t n_rows, int32_t n_featu
                      bins_rowmajor, n_rows, n_features, p.nib ? 15u : (uint32_t)(p.cap - 1),
                      (uint8_t*)packed_out + plan_columns_base(p, n_rows), plan_column_stride(n_rows));
   HIP_TRY(hipGetLastError());
+  return GBDT_OK;
+}
+
+size_t gbdt_bins_fused_bytes(int64_t n_rows, int32_t n_features, int32_t n_bins) {
+  if (!valid_shape(n_rows, n_features, n_bins) || n_bins > kFusedCap || n_rows == 0) return 0;
+  const int32_t max_cols = (int32_t)(kFusedMaxColumnRatio * n_features);
+  if (max_cols < 1) return 0;
+  return fused_layout(n_rows, n_features, max_cols).total;
+}
+
+int gbdt_bins_unfuse(const void* packed) {
+  std::lock_guard<std::mutex> lk(g_fused_mu);
+  g_fused.erase(packed);
+  return GBDT_OK;
+}
+
+int gbdt_bins_fuse(const uint8_t* bins_rowmajor, int64_t n_rows, int32_t n_features, int32_t n_bins,
+                   const void* packed, void* fused_out, size_t fused_bytes, int32_t* n_columns_out,
+                   void* stream) {
+  g_hip_err[0] = 0;
+  if (!valid_shape(n_rows, n_features, n_bins) || !n_columns_out || !packed) return GBDT_EINVAL;
+  *n_columns_out = 0;
+  (void)gbdt_bins_unfuse(packed);
+  if (n_bins > kFusedCap || n_rows == 0) return GBDT_OK;  // never fused
+  if (!bins_rowmajor || !fused_out) return GBDT_EINVAL;
+  if (((uintptr_t)fused_out & 255u) != 0) return GBDT_EINVAL;
+  if (fused_bytes < (size_t)n_features * sizeof(uint32_t)) return GBDT_ENOMEM;
+  if (n_rows >= ((int64_t)1 << 30)) return GBDT_EUNSUPPORTED;
+  hipStream_t s = (hipStream_t)stream;
+  if (stream_is_capturing(s)) return GBDT_EUNSUPPORTED;  // this call reads results on the host
+  // 1. the largest bin value of every feature (the head of fused_out serves as scratch)
+  uint32_t* max_dev = (uint32_t*)fused_out;
+  hipLaunchKernelGGL(counters_zero_kernel, dim3((n_features + 255) / 256), dim3(256), 0, s, max_dev, n_features);
+  HIP_TRY(hipGetLastError());
+  const int64_t row_blocks = (n_rows + 255) / 256;
+  if (row_blocks >= ((int64_t)1 << 31)) return GBDT_EUNSUPPORTED;
+  hipLaunchKernelGGL(feature_max_kernel, dim3((unsigned)row_blocks), dim3(256), 0, s, bins_rowmajor, n_rows,
+                     n_features, max_dev);
+  HIP_TRY(hipGetLastError());
+  std::vector<uint32_t> levels((size_t)n_features);
+  HIP_TRY(hipMemcpyAsync(levels.data(), max_dev, levels.size() * sizeof(uint32_t), hipMemcpyDeviceToHost, s));
+  HIP_TRY(hipStreamSynchronize(s));
+  for (uint32_t& l : levels) {
+    l = l + 1;                       // bins 0 .. max occur (at most)
+    if (l > (uint32_t)n_bins) l = (uint32_t)n_bins;  // the build masks stray values to the capacity anyway
+  }
+  // 2. the plan; does it pay?
+  std::vector<FusedCol> cols;
+  std::vector<FusedFeat> feats;
+  plan_fusion(levels, &cols, &feats);
+  const int32_t n_cols = (int32_t)cols.size();
+  if ((double)n_cols > kFusedMaxColumnRatio * n_features) return GBDT_OK;
+  const FusedLayout lay = fused_layout(n_rows, n_features, n_cols);
+  if (lay.total > fused_bytes) {
+    snprintf(g_hip_err, sizeof g_hip_err, "fused copy needs %zu bytes, %zu given", lay.total, fused_bytes);
+    return GBDT_ENOMEM;
+  }
+  if (plan_n_tiles(lay.plan) > 65535) return GBDT_OK;
+  // 3. tables, then the tiles
+  char* base = (char*)fused_out;
+  HIP_TRY(hipMemcpyAsync(base + lay.feats_off, feats.data(), feats.size() * sizeof(FusedFeat), hipMemcpyHostToDevice, s));
+  HIP_TRY(hipMemcpyAsync(base + lay.cols_off, cols.data(), cols.size() * sizeof(FusedCol), hipMemcpyHostToDevice, s));
+  const int tiles = plan_n_tiles(lay.plan);
+  const int64_t max_words = n_rows * (lay.plan.wm / 4);
+  const int64_t bx = (max_words + 255) / 256;
+  if (bx >= ((int64_t)1 << 31)) return GBDT_EUNSUPPORTED;
+  hipLaunchKernelGGL(pack_fused_kernel, dim3((unsigned)bx, (unsigned)tiles), dim3(256), 0, s, bins_rowmajor, n_rows,
+                     n_features, lay.plan, (const FusedCol*)(base + lay.cols_off), n_cols, (uint8_t*)base);
+  HIP_TRY(hipGetLastError());
+  HIP_TRY(hipStreamSynchronize(s));  // the host tables must outlive their copies
+  FusedEntry e;
+  e.tiles = (const uint8_t*)base;
+  e.feats = (const FusedFeat*)(base + lay.feats_off);
+  e.n_rows = n_rows;
+  e.n_features = n_features;
+  e.n_bins = n_bins;
+  e.n_cols = n_cols;
+  {
+    std::lock_guard<std::mutex> lk(g_fused_mu);
+    g_fused[packed] = e;
+  }
+  *n_columns_out = n_cols;
   return GBDT_OK;
 }
 
@@ -1137,12 +1352,12 @@ int gbdt_partition_rows_batch(const void* bin_matrix, int64_t n_rows, int32_t n_
     for (int32_t i = 0; i < kPartBatchLeaves; ++i) {
       PartLeaf& lf = a.leaf[i];
       if (i < n) {
-        lf.row_off = (uint32_t)(leaf_offsets[l0 + i] - leaf_offsets[l0]);
+        lf.row_off = lf.out_off = (uint32_t)(leaf_offsets[l0 + i] - leaf_offsets[l0]);
         lf.n = (uint32_t)(leaf_offsets[l0 + i + 1] - leaf_offsets[l0 + i]);
         lf.first_chunk = chunks;
         chunks += (uint32_t)(((int64_t)lf.n + chunk_rows - 1) / chunk_rows);
       } else {
-        lf.row_off = lf.n = 0;
+        lf.row_off = lf.out_off = lf.n = 0;
         lf.first_chunk = chunks;
       }
     }
@@ -1184,44 +1399,73 @@ int gbdt_grow_tree(const void* bin_matrix, int64_t n_rows, int32_t n_features, i
   gbdt_split_t* pinned_dev = nullptr;
   gbdt_split_t* pinned = pinned_records(&pinned_dev);
   if (!pinned) return GBDT_ENOMEM;
+  gbdt_split_t* pinned_part = pinned + 2 * kGrowRound;  // staging of a round's partition records
   hipStream_t s = (hipStream_t)stream;
   char* base = (char*)scratch;
-  int32_t* rows_buf[2] = {(int32_t*)(base + lay.rows_a), (int32_t*)(base + lay.rows_b)};
+  int32_t* rows_base = (int32_t*)(base + lay.rows_a);   // row buffer b starts b * row_elems entries in
+  int32_t* small_rows = (int32_t*)(base + lay.rows_small);
   gbdt_bin_t* pool = (gbdt_bin_t*)(base + lay.hists);
-  gbdt_split_t* recs = (gbdt_split_t*)(base + lay.recs);
+  gbdt_split_t* recs = (gbdt_split_t*)(base + lay.recs);            // record of the histogram in slot i
+  gbdt_split_t* part_recs = (gbdt_split_t*)(base + lay.part_recs);
   const size_t hist_elems = (size_t)n_features * n_bins;
+  const TilePlan plan = make_tile_plan(n_features, n_bins);
 
-  struct Leaf {
-    int slot;  // histogram slot in the pool
-    int buf;   // row buffer that holds the node's rows; -1: rows 0..n-1, nowhere stored
+  // Best-first growth is sequential by definition: the open leaf with the largest gain is split,
+  // its children join the open leaves, and so on (the older leaf on equal gains).  To wait for
+  // the device once per ROUND instead of once per split, a round expands (partitions, builds,
+  // searches) the best few open leaves at once; the host then replays the sequential rule on
+  // what it knows and stops at the first leaf whose children it has not seen yet.  Every node
+  // the replay splits is one the sequential rule splits, in the same order, so the tree is the
+  // sequential one; an expansion the replay never reaches before the leaf budget is used up is
+  // dropped (its leaf keeps its rows: children are written to the other row buffer).
+  struct Cand {            // a node whose histogram exists on the device
+    int64_t begin;         // its rows: positions [begin, begin + count) of row buffer `buf`
+    uint32_t count;
+    int buf;
+    int slot;              // histogram slot in the pool
+    gbdt_split_t rec;      // its best split
+    float sum_grad, sum_hess;
+    int kid[2];            // children once expanded (-1: not yet)
+    int id;                // node id once it belongs to the tree
   };
-  std::vector<Leaf> state(2 * (size_t)max_leaves);
-  std::vector<gbdt_split_t> host_recs(2 * (size_t)max_leaves);  // every node's record, as read back
-  auto fill_node = [&](int k, int parent, const gbdt_split_t& r, float sg, float sh, uint32_t cnt,
-                       int64_t begin) {
+  std::vector<Cand> cands;
+  cands.reserve(1 + 2 * (size_t)grow_max_expansions(max_leaves));
+  auto fill_node = [&](int k, int parent, const Cand& c) {
     gbdt_tree_node_t& nd = nodes_out[k];
     nd.parent = parent;
     nd.left = nd.right = -1;
-    nd.feature = r.feature;
-    nd.bin = r.bin;
-    nd.gain = r.gain;
-    nd.sum_grad = sg;
-    nd.sum_hess = sh;
-    nd.count = cnt;
+    nd.feature = c.rec.feature;
+    nd.bin = c.rec.bin;
+    nd.gain = c.rec.gain;
+    nd.sum_grad = c.sum_grad;
+    nd.sum_hess = c.sum_hess;
+    nd.count = c.count;
     nd.reserved = 0;
-    nd.row_begin = begin;
+    nd.row_begin = c.begin;
   };
 
-  // root
+  // root: histogram without an index list, its row list 0..n-1 for the first partition
   int rc = gbdt_hist_build(bin_matrix, n_rows, n_features, n_bins, nullptr, n_rows, grad, hess, pool, s);
   if (rc != GBDT_OK) return rc;
   rc = launch_split(pool, 0, 1, lambda, min_child_hess, recs, n_features, n_bins, s, pinned_dev);
   if (rc != GBDT_OK) return rc;
+  if (n_rows > 0 && max_leaves > 1) {
+    hipLaunchKernelGGL(row_iota_kernel, dim3((unsigned)((n_rows + 255) / 256)), dim3(256), 0, s, rows_base, n_rows);
+    HIP_TRY(hipGetLastError());
+  }
   HIP_TRY(hipStreamSynchronize(s));
   {
-    const gbdt_split_t r = pinned[0];
-    float sg = r.left_grad + r.right_grad, sh = r.left_hess + r.right_hess;
-    if (r.feature < 0 && n_rows > 0) {
+    Cand root;
+    root.begin = 0;
+    root.count = (uint32_t)n_rows;
+    root.buf = 0;
+    root.slot = 0;
+    root.rec = pinned[0];
+    root.kid[0] = root.kid[1] = -1;
+    root.id = 0;
+    root.sum_grad = root.rec.left_grad + root.rec.right_grad;
+    root.sum_hess = root.rec.left_hess + root.rec.right_hess;
+    if (root.rec.feature < 0 && n_rows > 0) {
       // no split record carries the totals: sum feature 0's bins on the host
       std::vector<gbdt_bin_t> row((size_t)n_bins);
       HIP_TRY(hipMemcpyAsync(row.data(), pool, (size_t)n_bins * sizeof(gbdt_bin_t), hipMemcpyDeviceToHost, s));
@@ -1231,64 +1475,188 @@ int gbdt_grow_tree(const void* bin_matrix, int64_t n_rows, int32_t n_features, i
         g += b.grad;
         h += b.hess;
       }
-      sg = (float)g;
-      sh = (float)h;
+      root.sum_grad = (float)g;
+      root.sum_hess = (float)h;
     }
-    fill_node(0, -1, r, sg, sh, (uint32_t)n_rows, 0);
-    state[0] = {0, -1};
-    host_recs[0] = r;
+    cands.push_back(root);
+    fill_node(0, -1, root);
   }
+  auto eligible = [&](const Cand& c) { return c.rec.feature >= 0 && c.rec.gain > min_split_gain; };
+  std::vector<int> open = {0};  // candidates that are leaves of the tree so far
   int n_nodes = 1, n_leaves = 1, next_slot = 1;
-  while (n_leaves < max_leaves) {
-    int k = -1;
-    for (int i = 0; i < n_nodes; ++i) {  // ascending id: equal gains go to the older leaf
-      const gbdt_tree_node_t& nd = nodes_out[i];
-      if (nd.left >= 0 || nd.feature < 0 || !(nd.gain > min_split_gain)) continue;
-      if (k < 0 || nd.gain > nodes_out[k].gain) k = i;
+  int expansions = 0, splits = 0, rounds = 0;
+  const int spec_budget = grow_speculative_budget(max_leaves);
+  for (;;) {
+    // ---- replay the sequential rule as far as the expansions seen so far carry it
+    int blocked = -1;
+    while (n_leaves < max_leaves) {
+      int m = -1;
+      for (int h : open) {  // larger gain, then smaller node id
+        const Cand& c = cands[h];
+        if (!eligible(c)) continue;
+        if (m < 0 || c.rec.gain > cands[m].rec.gain || (c.rec.gain == cands[m].rec.gain && c.id < cands[m].id)) m = h;
+      }
+      if (m < 0) break;
+      if (cands[m].kid[0] < 0) {
+        blocked = m;
+        break;
+      }
+      const int left = n_nodes, right = n_nodes + 1;
+      nodes_out[cands[m].id].left = left;
+      nodes_out[cands[m].id].right = right;
+      for (int side = 0; side < 2; ++side) {
+        Cand& k = cands[cands[m].kid[side]];
+        k.id = side == 0 ? left : right;
+        fill_node(k.id, cands[m].id, k);
+        open.push_back(cands[m].kid[side]);
+      }
+      open.erase(std::find(open.begin(), open.end(), m));
+      n_nodes += 2;
+      n_leaves += 1;
+      splits += 1;
     }
-    if (k < 0) break;
-    gbdt_tree_node_t& par = nodes_out[k];
-    const int64_t begin = par.row_begin;
-    const int src_buf = state[k].buf;
-    const int dst_buf = src_buf == 0 ? 1 : 0;
-    const int32_t* src = src_buf < 0 ? nullptr : rows_buf[src_buf] + begin;
-    int32_t* dst = rows_buf[dst_buf] + begin;
-    rc = gbdt_partition_rows(bin_matrix, n_rows, n_features, n_bins, src, par.count, recs + k, dst,
-                             nullptr, s);
+    if (blocked < 0) break;  // leaf budget used up, or nothing left to split
+    // ---- this round: the blocking leaf and the next best open leaves without children
+    // (A width that follows the number of splits the last round made possible was tried: fewer
+    // leaves expanded in vain on deep, chain-like trees, but more rounds, and rounds cost more.)
+    int extra = kGrowRound - 1;
+    if (extra > max_leaves - n_leaves - 1) extra = max_leaves - n_leaves - 1;
+    if (extra > spec_budget - (expansions - splits)) extra = spec_budget - (expansions - splits);
+    if (extra < 0) extra = 0;
+    std::vector<int> batch = {blocked};
+    if (extra > 0) {
+      std::vector<int> more;
+      for (int h : open)
+        if (h != blocked && cands[h].kid[0] < 0 && eligible(cands[h])) more.push_back(h);
+      std::sort(more.begin(), more.end(), [&](int x, int y) {
+        return cands[x].rec.gain > cands[y].rec.gain || (cands[x].rec.gain == cands[y].rec.gain && cands[x].id < cands[y].id);
+      });
+      if ((int)more.size() > extra) more.resize(extra);
+      batch.insert(batch.end(), more.begin(), more.end());
+    }
+    const int k = (int)batch.size();
+    if (next_slot + 2 * k > lay.n_slots) return GBDT_ENOMEM;  // (cannot happen: the budget above bounds it)
+
+    // ---- partition the k leaves: children into the other row buffer, same positions
+    for (int j = 0; j < k; ++j) pinned_part[j] = cands[batch[j]].rec;
+    HIP_TRY(hipMemcpyAsync(part_recs, pinned_part, (size_t)k * sizeof(gbdt_split_t), hipMemcpyHostToDevice, s));
+    {
+      uint32_t longest = 1;
+      for (int j = 0; j < k; ++j) longest = cands[batch[j]].count > longest ? cands[batch[j]].count : longest;
+      const int32_t rpt = make_part_geom(longest).rows_per_thread;
+      const int64_t chunk_rows = (int64_t)kPartThreads * rpt;
+      PartBatchArgs a;
+      a.packed = (const uint8_t*)bin_matrix;
+      a.idx = rows_base;
+      a.split = part_recs;
+      a.out = rows_base;
+      a.n_left_out = nullptr;
+      a.n_rows = n_rows;
+      a.plan = plan;
+      a.n_features = n_features;
+      a.rows_per_thread = rpt;
+      a.n_leaves = k;
+      uint32_t chunks = 0;
+      for (int j = 0; j < kPartBatchLeaves; ++j) {
+        PartLeaf& lf = a.leaf[j];
+        lf.row_off = lf.out_off = lf.n = 0;
+        lf.first_chunk = chunks;
+        if (j < k) {
+          const Cand& c = cands[batch[j]];
+          lf.row_off = (uint32_t)(c.begin + (int64_t)c.buf * (int64_t)lay.row_elems);
+          lf.out_off = (uint32_t)(c.begin + (int64_t)(1 - c.buf) * (int64_t)lay.row_elems);
+          lf.n = c.count;
+          chunks += (uint32_t)(((int64_t)lf.n + chunk_rows - 1) / chunk_rows);
+        }
+      }
+      a.n_chunks = chunks;
+      const size_t flag_words = (size_t)chunks * rpt * kPartWaves;
+      void* ws = nullptr;
+      rc = get_workspace(flag_words * 8 + (size_t)chunks * 4 + 256, s, &ws);
+      if (rc != GBDT_OK) return rc;
+      a.flags = (uint64_t*)ws;
+      a.chunk_left = (uint32_t*)(a.flags + flag_words);
+      if (chunks > 0) {
+        hipLaunchKernelGGL(partition_flag_batch_kernel, dim3(chunks), dim3(kPartThreads), 0, s, a);
+        HIP_TRY(hipGetLastError());
+        hipLaunchKernelGGL(partition_scatter_batch_kernel, dim3(chunks), dim3(kPartThreads), 0, s, a);
+        HIP_TRY(hipGetLastError());
+      }
+    }
+    // ---- the smaller children's rows back to back, their histograms in one batched build
+    std::vector<int64_t> small_offs = {0};
+    std::vector<int> left_small((size_t)k);
+    {
+      CompactTable t;
+      for (int j = 0; j < k; ++j) {
+        const Cand& c = cands[batch[j]];
+        const uint32_t nl = c.rec.left_count, nr = c.rec.right_count;
+        left_small[j] = nl <= nr;
+        const int64_t kid_base = c.begin + (int64_t)(1 - c.buf) * (int64_t)lay.row_elems;
+        t.src_begin[j] = (uint32_t)(left_small[j] ? kid_base : kid_base + nl);
+        t.dst_begin[j] = (uint32_t)small_offs.back();
+        small_offs.push_back(small_offs.back() + (left_small[j] ? nl : nr));
+      }
+      t.dst_begin[k] = (uint32_t)small_offs.back();
+      t.n_seg = k;
+      const uint32_t span = t.dst_begin[k];
+      if (span > 0) {
+        hipLaunchKernelGGL(segments_compact_kernel, dim3((span + 255) / 256), dim3(256), 0, s,
+                           (const int32_t*)rows_base, t, small_rows);
+        HIP_TRY(hipGetLastError());
+      }
+    }
+    gbdt_bin_t* h_small = pool + (size_t)next_slot * hist_elems;        // k slots: the built children
+    gbdt_bin_t* h_large = pool + (size_t)(next_slot + k) * hist_elems;  // k slots: their siblings
+    rc = gbdt_hist_build_batch(bin_matrix, n_rows, n_features, n_bins, small_rows, small_offs.data(), k, grad, hess,
+                               h_small, s);
     if (rc != GBDT_OK) return rc;
-    const gbdt_split_t prec = host_recs[k];  // the same record the device partitions by
-    const uint32_t nl = prec.left_count, nr = prec.right_count;
-    const int left = n_nodes, right = n_nodes + 1;
-    const bool left_small = nl <= nr;
-    const int small = left_small ? left : right, large = left_small ? right : left;
-    const int64_t small_begin = left_small ? begin : begin + nl;
-    const uint32_t small_n = left_small ? nl : nr;
-    state[small] = {next_slot++, dst_buf};
-    state[large] = {state[k].slot, dst_buf};  // the sibling takes over the parent's histogram slot
-    gbdt_bin_t* h_small = pool + (size_t)state[small].slot * hist_elems;
-    gbdt_bin_t* h_large = pool + (size_t)state[large].slot * hist_elems;
-    rc = gbdt_hist_build(bin_matrix, n_rows, n_features, n_bins, rows_buf[dst_buf] + small_begin, small_n,
-                         grad, hess, h_small, s);
+    {
+      SiblingTable t;
+      for (int j = 0; j < k; ++j) t.parent_slot[j] = cands[batch[j]].slot;
+      hipLaunchKernelGGL(hist_siblings_kernel, dim3((unsigned)((hist_elems + 255) / 256), k), dim3(256), 0, s,
+                         (const gbdt_bin_t*)pool, (const gbdt_bin_t*)h_small, h_large, (int32_t)hist_elems, t);
+      HIP_TRY(hipGetLastError());
+    }
+    // ---- best splits of the 2k children, one launch; the records also land in `pinned`
+    rc = launch_split(h_small, (int64_t)hist_elems, 2 * k, lambda, min_child_hess, recs + next_slot, n_features,
+                      n_bins, s, pinned_dev);
     if (rc != GBDT_OK) return rc;
-    // both children in one launch: their histograms sit in two slots of the pool; the larger
-    // child's is still its parent's and becomes parent - smaller child in the same launch
-    (void)h_large;
-    rc = launch_split(pool + (size_t)state[left].slot * hist_elems,
-                      ((int64_t)state[right].slot - state[left].slot) * (int64_t)hist_elems, 2, lambda,
-                      min_child_hess, recs + left, n_features, n_bins, s, pinned_dev, h_small,
-                      large == left ? 0 : 1);
-    if (rc != GBDT_OK) return rc;
-    HIP_TRY(hipStreamSynchronize(s));  // the two records are in `pinned` as well
-    par.left = left;
-    par.right = right;
-    host_recs[left] = pinned[0];
-    host_recs[right] = pinned[1];
-    fill_node(left, k, pinned[0], prec.left_grad, prec.left_hess, nl, begin);
-    fill_node(right, k, pinned[1], prec.right_grad, prec.right_hess, nr, begin + nl);
-    n_nodes += 2;
-    n_leaves += 1;
+    HIP_TRY(hipStreamSynchronize(s));
+    for (int j = 0; j < k; ++j) {
+      const int par = batch[j];
+      const Cand pc = cands[par];
+      const uint32_t nl = pc.rec.left_count, nr = pc.rec.right_count;
+      for (int side = 0; side < 2; ++side) {
+        const bool is_small = (side == 0) == (left_small[j] != 0);
+        Cand c;
+        c.begin = side == 0 ? pc.begin : pc.begin + nl;
+        c.count = side == 0 ? nl : nr;
+        c.buf = 1 - pc.buf;
+        c.slot = is_small ? next_slot + j : next_slot + k + j;
+        c.rec = pinned[is_small ? j : k + j];
+        c.sum_grad = side == 0 ? pc.rec.left_grad : pc.rec.right_grad;
+        c.sum_hess = side == 0 ? pc.rec.left_hess : pc.rec.right_hess;
+        c.kid[0] = c.kid[1] = -1;
+        c.id = -1;
+        cands[par].kid[side] = (int)cands.size();
+        cands.push_back(c);
+      }
+    }
+    next_slot += 2 * k;
+    expansions += k;
+    rounds += 1;
   }
   *n_nodes_out = n_nodes;
+  {
+    static const bool trace = [] {
+      const char* e = getenv("GBDT_HIST_TRACE_TREE");  // tuning aid: one line per tree on stderr
+      return e && atoi(e) > 0;
+    }();
+    if (trace)
+      fprintf(stderr, "gbdt_grow_tree: %d leaves, %d rounds, %d leaves expanded, %d of them never split\n", n_leaves,
+              rounds, expansions, expansions - splits);
+  }
   if (row_order_out && n_rows > 0) {
     if (n_nodes == 1) {  // never split: the rows in their own order
       hipLaunchKernelGGL(row_iota_kernel, dim3((unsigned)((n_rows + 255) / 256)), dim3(256), 0, s,
@@ -1297,8 +1665,7 @@ int gbdt_grow_tree(const void* bin_matrix, int64_t n_rows, int32_t n_features, i
     } else {
       // the leaves' segments in position order, a table-full per launch
       std::vector<std::pair<uint32_t, int>> segs;  // (begin, buffer)
-      for (int i = 0; i < n_nodes; ++i)
-        if (nodes_out[i].left < 0) segs.emplace_back((uint32_t)nodes_out[i].row_begin, state[i].buf);
+      for (int h : open) segs.emplace_back((uint32_t)cands[h].begin, cands[h].buf);
       std::sort(segs.begin(), segs.end());
       for (size_t s0 = 0; s0 < segs.size(); s0 += kSegTable) {
         SegTable t;
@@ -1309,7 +1676,7 @@ int gbdt_grow_tree(const void* bin_matrix, int64_t n_rows, int32_t n_features, i
         t.end = s0 + ns < segs.size() ? segs[s0 + ns].first : (uint32_t)n_rows;
         const uint32_t span = t.end - segs[s0].first;
         hipLaunchKernelGGL(leaf_rows_gather_kernel, dim3((span + 255) / 256), dim3(256), 0, s,
-                           (const int32_t*)rows_buf[0], (const int32_t*)rows_buf[1], t, row_order_out);
+                           (const int32_t*)rows_base, (const int32_t*)(rows_base + lay.row_elems), t, row_order_out);
         HIP_TRY(hipGetLastError());
       }
     }
@@ -1565,6 +1932,23 @@ int gbdt_debug_batch_plan(int32_t n_features, int32_t n_bins, const int64_t* lea
     block_out[3 * i + 2] = k.wg;
   }
   return (int)blocks;
+}
+
+int gbdt_debug_fusion_plan(const uint32_t* levels, int32_t n_features, int32_t* col_out, int32_t* stride_out,
+                           int32_t* n_cols_out) {
+  if (!levels || n_features <= 0 || !col_out || !stride_out || !n_cols_out) return GBDT_EINVAL;
+  std::vector<uint32_t> lv(levels, levels + n_features);
+  for (uint32_t l : lv)
+    if (l < 1 || l > (uint32_t)kFusedCap) return GBDT_EINVAL;
+  std::vector<FusedCol> cols;
+  std::vector<FusedFeat> feats;
+  plan_fusion(lv, &cols, &feats);
+  for (int32_t f = 0; f < n_features; ++f) {
+    col_out[f] = feats[f].col;
+    stride_out[f] = feats[f].stride;
+  }
+  *n_cols_out = (int32_t)cols.size();
+  return GBDT_OK;
 }
 
 int gbdt_debug_occupancy(int32_t n_bins, int32_t indexed) {

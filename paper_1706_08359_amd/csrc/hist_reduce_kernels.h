@@ -141,6 +141,44 @@ __global__ void __launch_bounds__(kMergeCells * kMergeLanes) hist_merge_batch_ke
   merge_cells(m);
 }
 
+// ----------------------------------------------------------------- unfuse kernel
+
+// Marginals of the fused columns' joint histograms (see FusedCol): bin b of feature f is the sum
+// of the joint bins v of its column with (v / stride) mod levels == b, v ascending, in fp64;
+// bins that do not occur are zero.  One thread per (feature, bin).
+__global__ void __launch_bounds__(256)
+hist_unfuse_kernel(const gbdt_bin_t* __restrict__ joint, const FusedFeat* __restrict__ feats,
+                   int32_t n_features, int32_t n_bins, gbdt_bin_t* __restrict__ out) {
+  const int32_t e = blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= n_features * n_bins) return;
+  const int32_t f = e / n_bins;
+  const int32_t b = e - f * n_bins;
+  const FusedFeat ff = feats[f];
+  gbdt_bin_t r;
+  r.grad = 0.0f;
+  r.hess = 0.0f;
+  r.count = 0u;
+  if (b < (int32_t)ff.levels) {
+    const gbdt_bin_t* col = joint + (size_t)ff.col * kFusedCap;
+    const int32_t stride = ff.stride, period = stride * (int32_t)ff.levels;
+    double g = 0.0, h = 0.0;
+    uint32_t n = 0;
+    // v = hi * period + b * stride + lo, lo < stride
+    for (int32_t base = b * stride; base < kFusedCap; base += period) {
+      for (int32_t lo = 0; lo < stride && base + lo < kFusedCap; ++lo) {
+        const gbdt_bin_t c = col[base + lo];
+        g += (double)c.grad;
+        h += (double)c.hess;
+        n += c.count;
+      }
+    }
+    r.grad = (float)g;
+    r.hess = (float)h;
+    r.count = n;
+  }
+  out[e] = r;
+}
+
 // --------------------------------------------------------------- subtract kernel
 
 // sibling = parent - child, element by element over [n_features][n_bins].

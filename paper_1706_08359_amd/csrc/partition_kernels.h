@@ -220,11 +220,11 @@ partition_scatter_kernel(const int32_t* __restrict__ idx, int64_t n_leaf, int32_
 
 // Several leaves per launch (a level of a tree): leaf l of the launch owns the row list
 // idx[row_off .. row_off + n), the split record split[l], chunks first_chunk .. of the
-// launch's flag / count arrays, and writes its children to out[row_off .. row_off + n).
+// launch's flag / count arrays, and writes its children to out[out_off .. out_off + n).
 // The table travels as kernel arguments.
-constexpr int kPartBatchLeaves = 256;
+constexpr int kPartBatchLeaves = 224;
 struct PartLeaf {
-  uint32_t row_off, n, first_chunk;
+  uint32_t row_off, out_off, n, first_chunk;
 };
 struct PartBatchArgs {
   const uint8_t* packed;
@@ -275,7 +275,7 @@ __global__ void __launch_bounds__(kPartThreads) partition_scatter_batch_kernel(P
   partition_scatter_chunk(a.idx + lf.row_off, lf.n, (int32_t)(blockIdx.x - lf.first_chunk),
                           (int32_t)(next_first - lf.first_chunk), a.rows_per_thread,
                           a.flags + (size_t)lf.first_chunk * a.rows_per_thread * kPartWaves,
-                          a.chunk_left + lf.first_chunk, a.out + lf.row_off,
+                          a.chunk_left + lf.first_chunk, a.out + lf.out_off,
                           a.n_left_out ? a.n_left_out + l : nullptr);
 }
 

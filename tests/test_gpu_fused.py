@@ -1,0 +1,171 @@
+"""Fused columns (gbdt_bins_fuse): features with few levels share one histogram column and
+their histograms are marginals of the column's joint histogram.  Through the C ABI, against
+the CPU oracle (which knows nothing of the fusion: it reads the row-major matrix) and against
+the plain path on the same matrix -- counts bit-exact, sums within 1e-5 of the leaf's sum of
+magnitudes, the chosen split and a grown tree identical.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import gbdt_oracle as orc
+from oracle import tree_oracle
+from paper_1706_08359_amd import binding as B
+from paper_1706_08359_amd import synth
+
+from gpu_util import REL_TOL, assert_hist_close
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def _mixed_matrix(n, levels, seed):
+    """Feature f takes bins 0 .. levels[f] - 1, skewed towards the low ones."""
+    rng = np.random.default_rng(seed)
+    cols = []
+    for L in levels:
+        p = (np.arange(L) + 1.0) ** -0.8
+        cols.append(rng.choice(L, size=n, p=p / p.sum()).astype(np.uint8))
+    return np.stack(cols, axis=1)
+
+
+def _stats(n, seed):
+    rng = np.random.default_rng(seed)
+    return rng.normal(size=n).astype(np.float32), rng.uniform(0.01, 1.0, size=n).astype(np.float32)
+
+
+def _build(packed, n, F, nb, idx, grad_d, hess_d, entry=B.gbdt_hist_build, **kw):
+    n_leaf = n if idx is None else idx.numel()
+    return entry(packed, n, F, nb, idx, n_leaf, grad_d, hess_d, **kw)
+
+
+@pytest.mark.parametrize("nb", [64, 16, 33])
+def test_fused_build_equals_the_oracle_and_the_plain_path(nb):
+    n = 60_000
+    rng = np.random.default_rng(nb)
+    levels = [1, 1, 2, 2, 2, 3, 3, 4, 5, 7, 8, 8, 9, 11, 16] + [int(x) for x in rng.integers(1, min(nb, 20) + 1, size=150)]
+    levels += [nb, nb, min(nb, 33), 2, 1]
+    levels = [min(L, nb) for L in levels]
+    bins = _mixed_matrix(n, levels, 7 + nb)
+    F = bins.shape[1]
+    grad, hess = _stats(n, 8 + nb)
+    bins_d = torch.from_numpy(bins).to(DEV)
+    grad_d, hess_d = torch.from_numpy(grad).to(DEV), torch.from_numpy(hess).to(DEV)
+    plain = B.gbdt_bins_pack(bins_d, nb, fuse=False)
+    packed = B.gbdt_bins_pack(bins_d, nb, fuse=False)
+    n_cols, fused = B.gbdt_bins_fuse(bins_d, nb, packed)
+    _say(f"bins {nb}: {F} features in {n_cols} fused columns")
+    assert 0 < n_cols <= 0.85 * F and fused is not None
+    leaves = [("root", None),
+              ("index list", torch.from_numpy(np.sort(rng.choice(n, size=n // 3, replace=False)).astype(np.int32)).to(DEV)),
+              ("list with repeats", torch.from_numpy(rng.integers(0, n, size=20_000).astype(np.int32)).to(DEV)),
+              ("short leaf (plain tiles)", torch.arange(0, 5000, dtype=torch.int32, device=DEV))]
+    for what, idx in leaves:
+        idx_np = None if idx is None else idx.cpu().numpy()
+        ref = orc.hist_build(bins, nb, grad, hess, idx_np)
+        sel = slice(None) if idx_np is None else idx_np
+        sg, sh = np.abs(grad[sel].astype(np.float64)).sum(), np.abs(hess[sel].astype(np.float64)).sum()
+        for mode in ("default", "deterministic", "wide"):
+            B.gbdt_set_deterministic(mode == "deterministic")
+            B.gbdt_set_wide_accumulation(mode == "wide")
+            try:
+                h_fused = _build(packed, n, F, nb, idx, grad_d, hess_d)
+                h_plain = _build(plain, n, F, nb, idx, grad_d, hess_d)
+                out = torch.full_like(h_fused, float("nan"))
+                _build(packed, n, F, nb, idx, grad_d, hess_d, entry=B.gbdt_hist_build_noalloc, hist_out=out)
+                torch.cuda.synchronize()
+            finally:
+                B.gbdt_set_deterministic(False)
+                B.gbdt_set_wide_accumulation(False)
+            a, b, c = B.hist_to_numpy(h_fused), B.hist_to_numpy(h_plain), B.hist_to_numpy(out)
+            assert_hist_close(a, ref, sg, sh, f"fused {what} {mode}")
+            assert_hist_close(c, ref, sg, sh, f"fused noalloc {what} {mode}")
+            assert (a["count"] == b["count"]).all() and (a["count"] == c["count"]).all()
+            assert np.abs(a["grad"].astype(np.float64) - b["grad"]).max() <= REL_TOL * sg
+            # bins that never occur are exactly zero
+            for f, L in enumerate(levels):
+                assert (a["count"][f, L:] == 0).all() and (a["grad"][f, L:] == 0).all()
+        # the split search sees the same histogram either way
+        s_f = B.split_to_dict(B.gbdt_best_split(h_fused, 1.0, 1e-3))
+        s_o = orc.best_split(ref, 1.0, 1e-3)
+        assert (s_f["feature"], s_f["bin"]) == (s_o["feature"], s_o["bin"]), (what, s_f, s_o)
+    # forgetting the fused copy: back to the plain tiles, same histogram
+    B.gbdt_bins_unfuse(packed)
+    h2 = _build(packed, n, F, nb, None, grad_d, hess_d)
+    assert (B.hist_to_numpy(h2)["count"] == B.hist_to_numpy(_build(plain, n, F, nb, None, grad_d, hess_d))["count"]).all()
+
+
+def test_fused_exact_sums_stay_exact():
+    """hess = 0.25 and grad = +-0.5: every partial sum is exact in fp32, so the fused path must
+    equal the oracle bit for bit, marginals included."""
+    n = 40_000
+    levels = [2, 3, 4, 5, 6, 2, 2, 2, 2, 2, 2, 8, 8, 1, 16, 4, 4, 4]
+    bins = _mixed_matrix(n, levels, 31)
+    rng = np.random.default_rng(32)
+    grad = np.where(rng.random(n) < 0.5, 0.5, -0.5).astype(np.float32)
+    hess = np.full(n, 0.25, np.float32)
+    bins_d = torch.from_numpy(bins).to(DEV)
+    packed = B.gbdt_bins_pack(bins_d, 16, fuse=False)
+    n_cols, _ = B.gbdt_bins_fuse(bins_d, 16, packed)
+    assert n_cols > 0
+    h = B.hist_to_numpy(_build(packed, n, len(levels), 16, None, torch.from_numpy(grad).to(DEV),
+                               torch.from_numpy(hess).to(DEV)))
+    ref = orc.hist_build(bins, 16, grad, hess)
+    assert (h["count"] == ref["count"]).all()
+    assert (h["grad"].astype(np.float64) == ref["grad"]).all() and (h["hess"].astype(np.float64) == ref["hess"]).all()
+
+
+def test_fusing_is_declined_when_it_does_not_pay_and_for_wide_bins():
+    n = 20_000
+    rng = np.random.default_rng(41)
+    bins = rng.integers(0, 63, size=(n, 50), dtype=np.uint8)           # 63 levels each: nothing shares a column
+    bins_d = torch.from_numpy(bins).to(DEV)
+    packed = B.gbdt_bins_pack(bins_d, 63, fuse=False)
+    assert B.gbdt_bins_fuse(bins_d, 63, packed) == (0, None)
+    bins255 = rng.integers(0, 3, size=(n, 50), dtype=np.uint8)         # few levels, but a 255-bin matrix
+    packed255 = B.gbdt_bins_pack(torch.from_numpy(bins255).to(DEV), 255, fuse=False)
+    assert B.gbdt_bins_fused_bytes(n, 50, 255) == 0
+    assert B.gbdt_bins_fuse(torch.from_numpy(bins255).to(DEV), 255, packed255) == (0, None)
+
+
+def test_tree_on_a_fused_matrix_equals_the_oracles_tree():
+    """Square loss on a noiseless piecewise-constant target over few-level features: every gain is far
+    from the next, so the device tree (built through the fused copy at the top, the plain tiles
+    further down) must equal the oracle's node for node."""
+    n = 120_000
+    levels = [4, 3, 2, 5, 2, 8, 6, 2, 3, 4, 7, 2]
+    bins = _mixed_matrix(n, levels, 51)
+    y = (np.where(bins[:, 3] > 1, 8.0, -8.0) + np.where(bins[:, 5] > 3, 3.0, -3.0) + np.where(bins[:, 0] > 0, 1.0, -1.0))
+    grad, hess = (-y).astype(np.float32), np.ones(n, np.float32)
+    bins_d = torch.from_numpy(bins).to(DEV)
+    packed = B.gbdt_bins_pack(bins_d, 16)                              # fuses by itself from 8192 rows on
+    assert getattr(packed, "gbdt_fused", None) is not None
+    grad_d, hess_d = torch.from_numpy(grad).to(DEV), torch.from_numpy(hess).to(DEV)
+    nodes, order, _ = B.gbdt_grow_tree(packed, n, len(levels), 16, grad_d, hess_d, 8, 0.0, 1.0)
+    ref = tree_oracle.grow_tree(bins, 16, grad, hess, 8, 0.0, 1.0)
+    assert len(nodes) == len(ref) == 15
+    order = order.cpu().numpy()
+    for k, (a, b) in enumerate(zip(nodes, ref)):
+        assert (a["left"], a["right"], a["parent"], a["count"]) == (b["left"], b["right"], b["parent"], b["count"]), k
+        if b["left"] >= 0:
+            assert (a["feature"], a["bin"]) == (b["split"]["feature"], b["split"]["bin"]), k
+        else:
+            assert np.array_equal(order[a["row_begin"]:a["row_begin"] + a["count"]], b["rows"])
+
+
+def test_categorical_workload_is_fused_and_matches_the_oracle_on_a_slice():
+    """The categorical workload's recipe (2..16 levels per feature, Zipf frequencies) at 300,000 rows:
+    about 0.57 columns per feature."""
+    w = synth.config5_categorical(device=DEV, n_rows=300_000)
+    packed = B.gbdt_bins_pack(w.bins, w.n_bins, fuse=False)
+    n_cols, _ = B.gbdt_bins_fuse(w.bins, w.n_bins, packed)
+    _say(f"categorical recipe: {w.n_features} features in {n_cols} fused columns")
+    assert 0 < n_cols < 0.65 * w.n_features
+    h = B.hist_to_numpy(_build(packed, w.n_rows, w.n_features, w.n_bins, None, w.grad, w.hess))
+    ref = orc.hist_build(w.bins.cpu().numpy(), w.n_bins, w.grad.cpu().numpy(), w.hess.cpu().numpy())
+    assert_hist_close(h, ref, w.grad.double().abs().sum().item(), w.hess.double().abs().sum().item(), "categorical")

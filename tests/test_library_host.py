@@ -216,3 +216,36 @@ def test_wide_accumulation_doubles_the_partial_blocks(n_features, n_bins):
     assert wide >= narrow and wide_batch > narrow_batch
     assert wide_batch <= 2 * narrow_batch
     assert B.gbdt_workspace_bytes(n_leaf, n_features, n_bins) == narrow
+
+
+def test_fusion_plan_is_a_valid_mixed_radix_packing():
+    """Host planner of gbdt_bins_fuse: every feature sits in exactly one column, the levels of a
+    column multiply to at most 64, at most 6 features share a column, the weights are the running
+    products of the levels in some order of the column's features -- so that a joint value
+    decodes back to every feature's bin -- and few-level features really share columns."""
+    rng = np.random.default_rng(3)
+    for levels in (rng.integers(2, 17, size=700), rng.integers(1, 65, size=333), np.full(40, 2), np.full(9, 64),
+                   np.array([1, 1, 1, 64, 33, 2]), rng.integers(1, 5, size=1000)):
+        levels = levels.astype(np.uint32)
+        col, stride, n_cols = B.gbdt_debug_fusion_plan(levels)
+        assert col.min() == 0 and col.max() == n_cols - 1 and len(np.unique(col)) == n_cols
+        for c in range(n_cols):
+            fs = np.nonzero(col == c)[0]
+            assert 1 <= len(fs) <= 6
+            assert int(np.prod(levels[fs].astype(np.int64))) <= 64
+            order = fs[np.argsort(stride[fs], kind="stable")]
+            run = 1
+            for f in order:                       # weights: 1, L_a, L_a L_b, ...
+                assert stride[f] == run, (c, fs, stride[fs], levels[fs])
+                run *= int(levels[f])
+            # decode a random joint value
+            b = [int(rng.integers(0, levels[f])) for f in fs]
+            v = sum(bi * int(stride[f]) for bi, f in zip(b, fs))
+            assert v < 64
+            assert [(v // int(stride[f])) % int(levels[f]) for f in fs] == b
+        # lower bound on columns: the sum of log2(levels) in units of 6 bits
+        assert n_cols >= int(np.ceil(np.log2(levels.astype(np.float64)).sum() / 6.0 - 1e-9))
+    col, stride, n_cols = B.gbdt_debug_fusion_plan(np.full(40, 2, np.uint32))
+    assert n_cols == 7                            # six binary features per column
+    col, stride, n_cols = B.gbdt_debug_fusion_plan(np.full(9, 64, np.uint32))
+    assert n_cols == 9
