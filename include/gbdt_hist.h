@@ -232,7 +232,10 @@ int gbdt_hist_build_batch(const void* bin_matrix, int64_t n_rows, int32_t n_feat
 
 /* Upper bound on the scratch gbdt_hist_build_batch needs for batches of at most n_leaves
  * leaves of this shape on the current device (0 on invalid arguments); to be covered by
- * the buffer given to gbdt_set_workspace when the caller owns the scratch. */
+ * the buffer given to gbdt_set_workspace when the caller owns the scratch.  (With 8 more
+ * bytes per listed row to spare the call first gathers grad / hess of sparse leaves into list
+ * order, which is faster on matrices of many feature tiles; a buffer of exactly this size
+ * makes it read them by row id instead.) */
 size_t gbdt_hist_build_batch_workspace_bytes(int32_t n_features, int32_t n_bins, int32_t n_leaves);
 
 /*
@@ -336,7 +339,7 @@ int gbdt_partition_rows(const void* bin_matrix, int64_t n_rows, int32_t n_featur
  * row_idx[leaf_offsets[l] .. leaf_offsets[l + 1]) and the split record splits[l]; its children
  * are written to the same positions of children_out (left rows, then right rows, order
  * kept), so the children of a whole level again lie back to back and can go straight into
- * gbdt_hist_build_batch.  Two kernel launches per 224 leaves.
+ * gbdt_hist_build_batch.  Two kernel launches per 192 leaves.
  *   row_idx        DEVICE int32, row ids in [0, n_rows)
  *   leaf_offsets   HOST int64 [n_leaves + 1], non-decreasing, read before the call returns
  *   splits         DEVICE gbdt_split_t [n_leaves]; a record without a split keeps all rows left

@@ -591,18 +591,23 @@ BatchPlan plan_batch(const int64_t* leaf_offsets, int32_t l0, int32_t n, int64_t
 // launch; splits_out[i] receives the record of histogram i.
 int launch_split(const gbdt_bin_t* hists, int64_t hist_stride, int32_t n_hists, float lambda,
                  float min_child_hess, gbdt_split_t* splits_out, int32_t n_features, int32_t n_bins,
-                 hipStream_t s, gbdt_split_t* host_mirror = nullptr, const gbdt_bin_t* minus = nullptr,
-                 int32_t minus_y = -1) {
+                 hipStream_t s, gbdt_split_t* host_mirror = nullptr, const SplitSiblings* siblings = nullptr) {
   int group = 0, n_groups = 0;
   split_grouping(n_features, n_bins, &group, &n_groups);
   void* ws = nullptr;
   int rc = get_workspace((size_t)n_hists * n_groups * sizeof(SplitCand), s, &ws);
   if (rc != GBDT_OK) return rc;
   const size_t lds = (size_t)group * split_feature_bytes(n_bins);
-  // (only with `minus` does the kernel write to the histograms)
+  SplitSiblings sib;
+  if (siblings) {
+    sib = *siblings;
+  } else {
+    memset(&sib, 0, sizeof sib);
+  }
+  // (only with siblings does the kernel write to the histograms)
   hipLaunchKernelGGL(split_gain_kernel, dim3(n_groups, n_hists), dim3(kSplitThreads), lds, s,
                      const_cast<gbdt_bin_t*>(hists), hist_stride, n_features, n_bins, group, (double)lambda,
-                     (double)min_child_hess, (SplitCand*)ws, splits_out, host_mirror, minus, minus_y);
+                     (double)min_child_hess, (SplitCand*)ws, splits_out, host_mirror, sib);
   HIP_TRY(hipGetLastError());
   return GBDT_OK;
 }
@@ -615,11 +620,12 @@ size_t align256(size_t b) { return (b + 255) / 256 * 256; }
 // before the leaf budget is used up; the histogram pool is sized for the splits of the tree plus
 // that many speculative ones.
 constexpr int kGrowRound = 32;
+static_assert(kGrowRound <= kSplitSiblings, "a round's siblings travel as one kernel argument");
 int32_t grow_speculative_budget(int32_t max_leaves) { return (max_leaves - 1) / 2 + 16; }
 int32_t grow_max_expansions(int32_t max_leaves) { return (max_leaves - 1) + grow_speculative_budget(max_leaves); }
 
 struct TreeScratch {
-  size_t rows_a, rows_b, rows_small, hists, recs, part_recs, total;  // byte offsets
+  size_t rows_a, rows_b, rows_small, hists, recs, total;  // byte offsets
   size_t row_elems;   // int32 entries between the two row buffers
   int32_t n_slots;    // histograms in the pool
 };
@@ -634,17 +640,15 @@ TreeScratch tree_scratch_layout(int64_t n_rows, int32_t n_features, int32_t n_bi
   t.rows_small = 2 * rows;  // the smaller children of a round: at most half of the rows
   t.hists = t.rows_small + align256(((size_t)(n_rows > 0 ? n_rows : 1) / 2 + 1) * sizeof(int32_t));
   t.recs = t.hists + align256((size_t)t.n_slots * n_features * n_bins * sizeof(gbdt_bin_t));
-  t.part_recs = t.recs + align256((size_t)t.n_slots * sizeof(gbdt_split_t));
-  t.total = t.part_recs + align256((size_t)kGrowRound * sizeof(gbdt_split_t));
+  t.total = t.recs + align256((size_t)t.n_slots * sizeof(gbdt_split_t));
   return t;
 }
 
 // Page-locked host memory of gbdt_grow_tree (one block per process, never freed): the split
 // records of a round, which the split search writes there as well as to device memory (the
-// host reads them after waiting for the stream, without a copy), and the records a round's
-// partition is driven by, staged for their copy to the device.  *dev_out: the address the
-// device uses for the first part.
-constexpr int kGrowPinnedRecs = 3 * kGrowRound;
+// host reads them after waiting for the stream, without a copy).  *dev_out: the address the
+// device uses for it.
+constexpr int kGrowPinnedRecs = 2 * kGrowRound;
 gbdt_split_t* pinned_records(gbdt_split_t** dev_out) {
   static gbdt_split_t* p = nullptr;
   static gbdt_split_t* d = nullptr;
@@ -1075,10 +1079,13 @@ int gbdt_hist_build_noalloc(const void* bin_matrix, int64_t n_rows, int32_t n_fe
 
 size_t gbdt_hist_build_noalloc_max_partial_bytes(void) { return kNoAllocPartialBytes; }
 
-int gbdt_hist_build_batch(const void* bin_matrix, int64_t n_rows, int32_t n_features,
+// gbdt_hist_build_batch; with seg_off (gbdt_grow_tree: the leaves of a round are segments of its
+// row buffers, not one list back to back) leaf l's rows are row_idx[seg_off[l] .. seg_off[l] + its
+// length by leaf_offsets), and grad / hess are always read by row id.
+static int hist_build_batch_impl(const void* bin_matrix, int64_t n_rows, int32_t n_features,
                           int32_t n_bins, const int32_t* row_idx, const int64_t* leaf_offsets,
                           int32_t n_leaves, const float* grad, const float* hess,
-                          gbdt_bin_t* hist_out, void* stream) {
+                          gbdt_bin_t* hist_out, void* stream, const uint32_t* seg_off) {
   if (!valid_shape(n_rows, n_features, n_bins)) return GBDT_EINVAL;
   if (n_leaves < 0) return GBDT_EINVAL;
   if (n_leaves == 0) return GBDT_OK;
@@ -1114,15 +1121,20 @@ int gbdt_hist_build_batch(const void* bin_matrix, int64_t n_rows, int32_t n_feat
     if (w > need_words) need_words = w;
   }
   hipStream_t s = (hipStream_t)stream;
-  if (total_rows > 0) {
+  if (total_rows > 0 && !seg_off) {
     const int rc_ids = check_row_ids(row_idx + leaf_offsets[0], total_rows, n_rows, s);
     if (rc_ids != GBDT_OK) return rc_ids;
   }
   // grad / hess of the whole concatenated list in list order, gathered once (see stats_gather_pays)
-  const bool by_pos = total_rows > 0 && stats_gather_pays(n_tiles, total_rows, total_rows / n_leaves, n_rows);
-  const size_t stats_words = by_pos ? 2 * (((size_t)total_rows + 63) / 64 * 64) : 0;
+  bool by_pos = !seg_off && total_rows > 0 && stats_gather_pays(n_tiles, total_rows, total_rows / n_leaves, n_rows);
+  size_t stats_words = by_pos ? 2 * (((size_t)total_rows + 63) / 64 * 64) : 0;
   void* ws = nullptr;
   int rc = get_workspace((need_words + stats_words) * 4 + 256, s, &ws);
+  if (rc == GBDT_ENOMEM && by_pos) {  // a caller's workspace sized for the partial blocks alone: no gather
+    by_pos = false;
+    stats_words = 0;
+    rc = get_workspace(need_words * 4 + 256, s, &ws);
+  }
   if (rc != GBDT_OK) return rc;
   float* g_list = (float*)ws + need_words;
   float* h_list = g_list + stats_words / 2;
@@ -1133,7 +1145,9 @@ int gbdt_hist_build_batch(const void* bin_matrix, int64_t n_rows, int32_t n_feat
   }
   for (int32_t l0 = 0; l0 < n_leaves; l0 += kBatchLeaves) {
     const int32_t n = n_leaves - l0 < kBatchLeaves ? n_leaves - l0 : kBatchLeaves;
-    const BatchPlan b = plan_batch(leaf_offsets, l0, n, resident, n_tiles);
+    BatchPlan b = plan_batch(leaf_offsets, l0, n, resident, n_tiles);
+    if (seg_off)
+      for (int32_t i = 0; i < n; ++i) b.leaf[i].row_off = seg_off[l0 + i];
     BatchMergeArgs m;
     m.m.partials = (const uint32_t*)ws;
     m.m.out = hist_out + (size_t)l0 * n_features * n_bins;
@@ -1149,7 +1163,7 @@ int gbdt_hist_build_batch(const void* bin_matrix, int64_t n_rows, int32_t n_feat
     if (b.total_wgs > 0) {
       BatchArgs a;
       a.packed = (const uint8_t*)bin_matrix;
-      a.idx = row_idx + leaf_offsets[l0];
+      a.idx = seg_off ? row_idx : row_idx + leaf_offsets[l0];
       a.grad = by_pos ? g_list + (leaf_offsets[l0] - leaf_offsets[0]) : grad;
       a.hess = by_pos ? h_list + (leaf_offsets[l0] - leaf_offsets[0]) : hess;
       a.stats_by_pos = by_pos ? 1 : 0;
@@ -1192,6 +1206,14 @@ int gbdt_hist_build_batch(const void* bin_matrix, int64_t n_rows, int32_t n_feat
   return GBDT_OK;
 }
 
+int gbdt_hist_build_batch(const void* bin_matrix, int64_t n_rows, int32_t n_features,
+                          int32_t n_bins, const int32_t* row_idx, const int64_t* leaf_offsets,
+                          int32_t n_leaves, const float* grad, const float* hess,
+                          gbdt_bin_t* hist_out, void* stream) {
+  return hist_build_batch_impl(bin_matrix, n_rows, n_features, n_bins, row_idx, leaf_offsets, n_leaves, grad, hess,
+                               hist_out, stream, nullptr);
+}
+
 size_t gbdt_hist_build_batch_workspace_bytes(int32_t n_features, int32_t n_bins, int32_t n_leaves) {
   if (n_features <= 0 || n_bins < 2 || n_bins > 256 || n_leaves < 0) return 0;
   const TilePlan p = make_tile_plan(n_features, n_bins);
@@ -1207,8 +1229,8 @@ size_t gbdt_hist_build_batch_workspace_bytes(int32_t n_features, int32_t n_bins,
   int64_t budget = resident / n_tiles;
   if (budget < 1) budget = 1;
   const int64_t per_launch = n_leaves < kBatchLeaves ? n_leaves : kBatchLeaves;
-  // (+ 8 bytes per listed row when the call gathers grad / hess into list order: callers that
-  // own the scratch add that for their longest list)
+  // (the call gathers grad / hess into list order only when the scratch has 8 more bytes per listed
+  // row to spare; with a caller buffer of exactly this size it reads them by row id)
   const size_t b = (size_t)(budget + per_launch) * col * 4 + 256;
   return (b + 255) / 256 * 256 + kWsHeadBytes;
 }
@@ -1354,10 +1376,11 @@ int gbdt_partition_rows_batch(const void* bin_matrix, int64_t n_rows, int32_t n_
       if (i < n) {
         lf.row_off = lf.out_off = (uint32_t)(leaf_offsets[l0 + i] - leaf_offsets[l0]);
         lf.n = (uint32_t)(leaf_offsets[l0 + i + 1] - leaf_offsets[l0 + i]);
+        lf.split_idx = (uint32_t)i;
         lf.first_chunk = chunks;
         chunks += (uint32_t)(((int64_t)lf.n + chunk_rows - 1) / chunk_rows);
       } else {
-        lf.row_off = lf.out_off = lf.n = 0;
+        lf.row_off = lf.out_off = lf.n = lf.split_idx = 0;
         lf.first_chunk = chunks;
       }
     }
@@ -1399,14 +1422,12 @@ int gbdt_grow_tree(const void* bin_matrix, int64_t n_rows, int32_t n_features, i
   gbdt_split_t* pinned_dev = nullptr;
   gbdt_split_t* pinned = pinned_records(&pinned_dev);
   if (!pinned) return GBDT_ENOMEM;
-  gbdt_split_t* pinned_part = pinned + 2 * kGrowRound;  // staging of a round's partition records
   hipStream_t s = (hipStream_t)stream;
   char* base = (char*)scratch;
   int32_t* rows_base = (int32_t*)(base + lay.rows_a);   // row buffer b starts b * row_elems entries in
   int32_t* small_rows = (int32_t*)(base + lay.rows_small);
   gbdt_bin_t* pool = (gbdt_bin_t*)(base + lay.hists);
   gbdt_split_t* recs = (gbdt_split_t*)(base + lay.recs);            // record of the histogram in slot i
-  gbdt_split_t* part_recs = (gbdt_split_t*)(base + lay.part_recs);
   const size_t hist_elems = (size_t)n_features * n_bins;
   const TilePlan plan = make_tile_plan(n_features, n_bins);
 
@@ -1537,9 +1558,8 @@ int gbdt_grow_tree(const void* bin_matrix, int64_t n_rows, int32_t n_features, i
     const int k = (int)batch.size();
     if (next_slot + 2 * k > lay.n_slots) return GBDT_ENOMEM;  // (cannot happen: the budget above bounds it)
 
-    // ---- partition the k leaves: children into the other row buffer, same positions
-    for (int j = 0; j < k; ++j) pinned_part[j] = cands[batch[j]].rec;
-    HIP_TRY(hipMemcpyAsync(part_recs, pinned_part, (size_t)k * sizeof(gbdt_split_t), hipMemcpyHostToDevice, s));
+    // ---- partition the k leaves: children into the other row buffer, same positions; every leaf's
+    // split record is read on the device, from the records by histogram slot
     {
       uint32_t longest = 1;
       for (int j = 0; j < k; ++j) longest = cands[batch[j]].count > longest ? cands[batch[j]].count : longest;
@@ -1548,7 +1568,7 @@ int gbdt_grow_tree(const void* bin_matrix, int64_t n_rows, int32_t n_features, i
       PartBatchArgs a;
       a.packed = (const uint8_t*)bin_matrix;
       a.idx = rows_base;
-      a.split = part_recs;
+      a.split = recs;
       a.out = rows_base;
       a.n_left_out = nullptr;
       a.n_rows = n_rows;
@@ -1559,13 +1579,14 @@ int gbdt_grow_tree(const void* bin_matrix, int64_t n_rows, int32_t n_features, i
       uint32_t chunks = 0;
       for (int j = 0; j < kPartBatchLeaves; ++j) {
         PartLeaf& lf = a.leaf[j];
-        lf.row_off = lf.out_off = lf.n = 0;
+        lf.row_off = lf.out_off = lf.n = lf.split_idx = 0;
         lf.first_chunk = chunks;
         if (j < k) {
           const Cand& c = cands[batch[j]];
           lf.row_off = (uint32_t)(c.begin + (int64_t)c.buf * (int64_t)lay.row_elems);
           lf.out_off = (uint32_t)(c.begin + (int64_t)(1 - c.buf) * (int64_t)lay.row_elems);
           lf.n = c.count;
+          lf.split_idx = (uint32_t)c.slot;
           chunks += (uint32_t)(((int64_t)lf.n + chunk_rows - 1) / chunk_rows);
         }
       }
@@ -1583,45 +1604,52 @@ int gbdt_grow_tree(const void* bin_matrix, int64_t n_rows, int32_t n_features, i
         HIP_TRY(hipGetLastError());
       }
     }
-    // ---- the smaller children's rows back to back, their histograms in one batched build
+    // ---- the smaller children's histograms in one batched build, straight from their segments of
+    // the row buffers -- or, where gathering grad / hess into list order pays (sparse leaves of a
+    // matrix of many tiles), from a copy of their rows back to back
     std::vector<int64_t> small_offs = {0};
+    std::vector<uint32_t> small_seg((size_t)k);
     std::vector<int> left_small((size_t)k);
-    {
+    for (int j = 0; j < k; ++j) {
+      const Cand& c = cands[batch[j]];
+      const uint32_t nl = c.rec.left_count, nr = c.rec.right_count;
+      left_small[j] = nl <= nr;
+      const int64_t kid_base = c.begin + (int64_t)(1 - c.buf) * (int64_t)lay.row_elems;
+      small_seg[j] = (uint32_t)(left_small[j] ? kid_base : kid_base + nl);
+      small_offs.push_back(small_offs.back() + (left_small[j] ? nl : nr));
+    }
+    gbdt_bin_t* h_small = pool + (size_t)next_slot * hist_elems;  // k slots: the built children; then k: their siblings
+    const int64_t small_total = small_offs.back();
+    if (small_total > 0 && stats_gather_pays(plan_n_tiles(plan), small_total, small_total / k, n_rows)) {
       CompactTable t;
       for (int j = 0; j < k; ++j) {
-        const Cand& c = cands[batch[j]];
-        const uint32_t nl = c.rec.left_count, nr = c.rec.right_count;
-        left_small[j] = nl <= nr;
-        const int64_t kid_base = c.begin + (int64_t)(1 - c.buf) * (int64_t)lay.row_elems;
-        t.src_begin[j] = (uint32_t)(left_small[j] ? kid_base : kid_base + nl);
-        t.dst_begin[j] = (uint32_t)small_offs.back();
-        small_offs.push_back(small_offs.back() + (left_small[j] ? nl : nr));
+        t.src_begin[j] = small_seg[j];
+        t.dst_begin[j] = (uint32_t)small_offs[j];
       }
-      t.dst_begin[k] = (uint32_t)small_offs.back();
+      t.dst_begin[k] = (uint32_t)small_total;
       t.n_seg = k;
-      const uint32_t span = t.dst_begin[k];
-      if (span > 0) {
-        hipLaunchKernelGGL(segments_compact_kernel, dim3((span + 255) / 256), dim3(256), 0, s,
-                           (const int32_t*)rows_base, t, small_rows);
-        HIP_TRY(hipGetLastError());
-      }
-    }
-    gbdt_bin_t* h_small = pool + (size_t)next_slot * hist_elems;        // k slots: the built children
-    gbdt_bin_t* h_large = pool + (size_t)(next_slot + k) * hist_elems;  // k slots: their siblings
-    rc = gbdt_hist_build_batch(bin_matrix, n_rows, n_features, n_bins, small_rows, small_offs.data(), k, grad, hess,
-                               h_small, s);
-    if (rc != GBDT_OK) return rc;
-    {
-      SiblingTable t;
-      for (int j = 0; j < k; ++j) t.parent_slot[j] = cands[batch[j]].slot;
-      hipLaunchKernelGGL(hist_siblings_kernel, dim3((unsigned)((hist_elems + 255) / 256), k), dim3(256), 0, s,
-                         (const gbdt_bin_t*)pool, (const gbdt_bin_t*)h_small, h_large, (int32_t)hist_elems, t);
+      hipLaunchKernelGGL(segments_compact_kernel, dim3((unsigned)((small_total + 255) / 256)), dim3(256), 0, s,
+                         (const int32_t*)rows_base, t, small_rows);
       HIP_TRY(hipGetLastError());
+      rc = hist_build_batch_impl(bin_matrix, n_rows, n_features, n_bins, small_rows, small_offs.data(), k, grad,
+                                 hess, h_small, s, nullptr);
+    } else {
+      rc = hist_build_batch_impl(bin_matrix, n_rows, n_features, n_bins, rows_base, small_offs.data(), k, grad,
+                                 hess, h_small, s, small_seg.data());
     }
-    // ---- best splits of the 2k children, one launch; the records also land in `pinned`
-    rc = launch_split(h_small, (int64_t)hist_elems, 2 * k, lambda, min_child_hess, recs + next_slot, n_features,
-                      n_bins, s, pinned_dev);
     if (rc != GBDT_OK) return rc;
+    // ---- best splits of the 2k children, one launch, which first forms the k siblings as parent -
+    // built child; the records also land in `pinned`
+    {
+      SplitSiblings sib;
+      sib.pool = pool;
+      sib.first = k;
+      sib.n = k;
+      for (int j = 0; j < kSplitSiblings; ++j) sib.parent_slot[j] = j < k ? cands[batch[j]].slot : 0;
+      rc = launch_split(h_small, (int64_t)hist_elems, 2 * k, lambda, min_child_hess, recs + next_slot, n_features,
+                        n_bins, s, pinned_dev, &sib);
+      if (rc != GBDT_OK) return rc;
+    }
     HIP_TRY(hipStreamSynchronize(s));
     for (int j = 0; j < k; ++j) {
       const int par = batch[j];

@@ -219,12 +219,12 @@ partition_scatter_kernel(const int32_t* __restrict__ idx, int64_t n_leaf, int32_
 }
 
 // Several leaves per launch (a level of a tree): leaf l of the launch owns the row list
-// idx[row_off .. row_off + n), the split record split[l], chunks first_chunk .. of the
-// launch's flag / count arrays, and writes its children to out[out_off .. out_off + n).
-// The table travels as kernel arguments.
-constexpr int kPartBatchLeaves = 224;
+// idx[row_off .. row_off + n), chunks first_chunk .. of the
+// launch's flag / count arrays, the split record split[split_idx], and writes its children to
+// out[out_off .. out_off + n).  The table travels as kernel arguments.
+constexpr int kPartBatchLeaves = 192;
 struct PartLeaf {
-  uint32_t row_off, out_off, n, first_chunk;
+  uint32_t row_off, out_off, n, first_chunk, split_idx;
 };
 struct PartBatchArgs {
   const uint8_t* packed;
@@ -260,7 +260,7 @@ __device__ __forceinline__ int32_t part_leaf_of(const PartLeaf* leaf, int32_t n_
 __global__ void __launch_bounds__(kPartThreads) partition_flag_batch_kernel(PartBatchArgs a) {
   const int32_t l = part_leaf_of(a.leaf, a.n_leaves, blockIdx.x);
   const PartLeaf lf = a.leaf[l];
-  const SplitColumn sc = split_column(a.split + l, a.plan, a.n_rows, a.n_features);
+  const SplitColumn sc = split_column(a.split + lf.split_idx, a.plan, a.n_rows, a.n_features);
   partition_flag_chunk(sc, a.packed, a.n_rows, a.idx + lf.row_off, lf.n, (int32_t)(blockIdx.x - lf.first_chunk),
                        a.rows_per_thread, a.flags + (size_t)blockIdx.x * a.rows_per_thread * kPartWaves,
                        a.chunk_left + blockIdx.x);

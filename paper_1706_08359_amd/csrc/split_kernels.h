@@ -135,20 +135,32 @@ __device__ __forceinline__ void block_argmax(double& gain, int32_t& idx, double*
 // one launch).  mirror (may be NULL): a second place for the records, page-locked host
 // memory that the device can write, so that a caller who must look at them on the host
 // needs no copy after the kernel, only to wait for it.
-// minus (may be NULL): histogram minus_y of the call is first replaced, in place, by itself
-// minus this one (the sibling by subtraction, element by element as hist_subtract_kernel does
-// it), and the result is searched: every (feature, bin) is read by exactly one workgroup, which
-// also writes the difference back.
+// sib (sib.n may be 0): histograms sib.first .. sib.first + sib.n - 1 of the call are siblings
+// by subtraction that do not exist yet: histogram sib.first + j is first formed, element by
+// element as hist_subtract_kernel does it, as (pool histogram parent_slot[j]) - (histogram j of
+// the call, the built child), written to its place and searched in the same pass: every
+// (feature, bin) is read by exactly one workgroup, which also writes the difference.
+constexpr int kSplitSiblings = 32;
+struct SplitSiblings {
+  const gbdt_bin_t* pool;  // histograms of hist_elems bins each
+  int32_t first, n;
+  int32_t parent_slot[kSplitSiblings];
+};
+
 __global__ void __launch_bounds__(kSplitThreads)
 split_gain_kernel(gbdt_bin_t* hist, int64_t hist_stride, int32_t n_features,
                   int32_t n_bins, int32_t group, double lambda, double min_child_hess,
                   SplitCand* __restrict__ cand, gbdt_split_t* __restrict__ out,
-                  gbdt_split_t* __restrict__ mirror, const gbdt_bin_t* minus, int32_t minus_y) {
+                  gbdt_split_t* __restrict__ mirror, SplitSiblings sib) {
   extern __shared__ __align__(16) unsigned char smem[];
   __shared__ double s_gain[kSplitThreads / 64];
   __shared__ int32_t s_pair[kSplitThreads / 64];
   __shared__ int s_last;
   const int tid = threadIdx.x;
+  const int32_t sib_j = (int32_t)blockIdx.y - sib.first;
+  const bool is_sib = sib_j >= 0 && sib_j < sib.n;
+  const gbdt_bin_t* built = hist + (int64_t)(is_sib ? sib_j : 0) * hist_stride;  // the sibling's built twin
+  const gbdt_bin_t* sib_parent = is_sib ? sib.pool + (int64_t)sib.parent_slot[sib_j] * hist_stride : nullptr;
   hist += (int64_t)blockIdx.y * hist_stride;
   cand += (size_t)blockIdx.y * gridDim.x;
   out += blockIdx.y;
@@ -169,13 +181,15 @@ split_gain_kernel(gbdt_bin_t* hist, int64_t hist_stride, int32_t n_features,
     gbdt_bin_t v = {0.0f, 0.0f, 0u};
     if (b < B) {
       const size_t at = (size_t)(f0 + fl) * B + b;
-      v = hist[at];
-      if (minus && (int32_t)blockIdx.y == minus_y) {
-        const gbdt_bin_t c = minus[at];
-        v.grad = v.grad - c.grad;
-        v.hess = v.hess - c.hess;
-        v.count = v.count - c.count;
+      if (is_sib) {
+        const gbdt_bin_t pv = sib_parent[at];
+        const gbdt_bin_t c = built[at];
+        v.grad = pv.grad - c.grad;
+        v.hess = pv.hess - c.hess;
+        v.count = pv.count - c.count;
         hist[at] = v;
+      } else {
+        v = hist[at];
       }
     }
     pg[e] = (double)v.grad;

@@ -283,7 +283,7 @@ def test_batched_calls_with_caller_scratch():
     p, rng = _problem(n_rows, n_features, n_bins, 41)
     perm = rng.permutation(n_rows).astype(np.int32)
     lists = [np.sort(x) for x in np.split(perm, [9000, 9100, 20000])]
-    need = max(B.gbdt_hist_build_batch_workspace_bytes(n_features, n_bins, len(lists)) + 8 * n_rows + 512,
+    need = max(B.gbdt_hist_build_batch_workspace_bytes(n_features, n_bins, len(lists)),
                B.gbdt_workspace_bytes(n_rows, n_features, n_bins))
     ws = torch.full((need,), 0x77, dtype=torch.uint8, device="cuda:0")
     B.gbdt_set_workspace(ws)
