@@ -123,9 +123,10 @@ int gbdt_bins_pack(const uint8_t* bins_rowmajor, int64_t n_rows, int32_t n_featu
  * gbdt_bins_fuse finds each feature's largest bin value on the device, plans the columns on
  * the host and, if at most 85 % as many columns as features result, writes the fused copy
  * into fused_out and remembers it for `packed`: later gbdt_hist_build /
- * gbdt_hist_build_noalloc calls with that bin_matrix address and shape build leaves of at
- * least 8192 rows from the fused copy (not with wide accumulation, whose stored sums are
- * exact sums rounded once).  Results and error bound are those of the plain path.  Unlike the
+ * gbdt_hist_build_noalloc calls with that bin_matrix address and shape build leaves that hold
+ * at least 8192 rows and a third of the matrix's rows from the fused copy (sparser leaves are
+ * bound by HBM traffic, where the plain tiles' narrower rows win; also not with wide
+ * accumulation, whose stored sums are exact sums rounded once).  Results and error bound are those of the plain path.  Unlike the
  * other calls it WAITS for the stream (it reads the maxima on the host).
  *   bins_rowmajor   DEVICE, the matrix gbdt_bins_pack packed
  *   packed          DEVICE address gbdt_bins_pack wrote to (used as a key only; a buffer

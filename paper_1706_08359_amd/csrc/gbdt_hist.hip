@@ -214,6 +214,11 @@ bool fused_lookup(const void* packed, int64_t n_rows, int32_t n_features, int32_
 // Leaves below this many rows are built from the plain tiles: the extra launch that takes the
 // marginals costs more than the atomics the fused columns save.
 constexpr int64_t kFusedMinLeafRows = 8192;
+// ... and leaves that hold less than a third of the matrix's rows: a gathered row drags its whole
+// 128-byte line along, so sparse leaves are bound by HBM traffic, and a fused copy's rows are wider
+// than 4-bit rows (measured on 11 M x 700 with 2..16 levels: 0.78x the time at half of the rows and
+// more, break-even at a quarter, 1-3 % slower below).
+constexpr int64_t kFusedMinLeafFraction = 3;
 // A fused copy is made when it has at most this fraction of the features as columns.
 constexpr double kFusedMaxColumnRatio = 0.85;
 
@@ -752,8 +757,8 @@ int hist_build_impl(const void* bin_matrix, int64_t n_rows, int32_t n_features, 
   FusedEntry fe;
   // (not with wide accumulation: the joint histograms are rounded to fp32 before the marginals are
   // taken, which would break that mode's promise of the exact sum rounded once)
-  const bool fused =
-      !wide && n_leaf_rows >= kFusedMinLeafRows && fused_lookup(bin_matrix, n_rows, n_features, n_bins, &fe);
+  const bool fused = !wide && n_leaf_rows >= kFusedMinLeafRows && n_leaf_rows * kFusedMinLeafFraction >= n_rows &&
+                     fused_lookup(bin_matrix, n_rows, n_features, n_bins, &fe);
   const int32_t real_features = n_features, real_bins = n_bins;
   if (fused) {
     n_features = fe.n_cols;
@@ -894,8 +899,13 @@ int hist_build_impl(const void* bin_matrix, int64_t n_rows, int32_t n_features, 
   m.counters = uses_counters ? counters : nullptr;
   const int max_slots = plan_slots(p, p.wm);
   const int mx = (n_bins * max_slots + kMergeCells - 1) / kMergeCells;
-  hipLaunchKernelGGL(hist_merge_kernel, dim3(mx, plan_n_tiles(p)), dim3(kMergeCells * kMergeLanes),
-                     0, s, m);
+  if (merge_lanes((int64_t)mx * plan_n_tiles(p), a.chunks) == kMergeLanesWide) {
+    hipLaunchKernelGGL(hist_merge_kernel<kMergeLanesWide>, dim3(mx, plan_n_tiles(p)),
+                       dim3(kMergeCells * kMergeLanesWide), 0, s, m);
+  } else {
+    hipLaunchKernelGGL(hist_merge_kernel<kMergeLanes>, dim3(mx, plan_n_tiles(p)), dim3(kMergeCells * kMergeLanes),
+                       0, s, m);
+  }
   HIP_TRY(hipGetLastError());
   if (uses_counters && !capturing) set_counters_zero(counters, true);  // the reduction pass leaves them zero
   if (fused) {
@@ -1041,6 +1051,8 @@ size_t gbdt_workspace_bytes(int64_t n_rows, int32_t n_features, int32_t n_bins) 
       make_geom(n_features, n_bins, n_rows, device_cu_count(), build_wg_per_cu(cap, true, wide), wide);
   size_t b = (g0.partial_words > g1.partial_words ? g0.partial_words : g1.partial_words) * 4 +
              2 * (((size_t)n_rows + 63) / 64 * 64) * 4;  // + grad / hess of a leaf in leaf order
+  // + the joint histograms of a fused copy (at most one column per feature)
+  if (n_bins <= kFusedCap) b += (size_t)n_features * kFusedCap * sizeof(gbdt_bin_t);
   int sg = 0, sn = 0;
   split_grouping(n_features, n_bins, &sg, &sn);
   const size_t cand = (size_t)2 * sn * sizeof(SplitCand);  // gbdt_grow_tree searches two histograms at once
@@ -1097,6 +1109,8 @@ static int hist_build_batch_impl(const void* bin_matrix, int64_t n_rows, int32_t
   if (total_rows > 0 && (!bin_matrix || !row_idx || !grad || !hess)) return GBDT_EINVAL;
   if (total_rows > 0 && n_rows == 0) return GBDT_EINVAL;
   if (n_rows >= ((int64_t)1 << 30)) return GBDT_EUNSUPPORTED;
+  // (always from the plain tiles: the leaves of a batch are sparse in the matrix, where a fused copy's
+  // wider rows cost more HBM traffic than its fewer columns save in atomics)
   const TilePlan p = make_tile_plan(n_features, n_bins);
   const int n_tiles = plan_n_tiles(p);
   if (n_tiles > 65535) return GBDT_EUNSUPPORTED;
@@ -1199,8 +1213,18 @@ static int hist_build_batch_impl(const void* bin_matrix, int64_t n_rows, int32_t
     if (!any_to_merge) continue;
     const int max_slots = plan_slots(p, p.wm);
     const int mx = (n_bins * max_slots + kMergeCells - 1) / kMergeCells;
-    hipLaunchKernelGGL(hist_merge_batch_kernel, dim3(mx, n_tiles, n), dim3(kMergeCells * kMergeLanes), 0,
-                       s, m);
+    int32_t most_chunks = 0;
+    for (int32_t i = 0; i < n; ++i) {
+      const int32_t c = (int32_t)(b.leaf[i].wgs_unit & 0xffffu) * (wide ? 2 : 1);
+      most_chunks = c > most_chunks ? c : most_chunks;
+    }
+    if (merge_lanes((int64_t)mx * n_tiles * n, most_chunks) == kMergeLanesWide) {
+      hipLaunchKernelGGL(hist_merge_batch_kernel<kMergeLanesWide>, dim3(mx, n_tiles, n),
+                         dim3(kMergeCells * kMergeLanesWide), 0, s, m);
+    } else {
+      hipLaunchKernelGGL(hist_merge_batch_kernel<kMergeLanes>, dim3(mx, n_tiles, n),
+                         dim3(kMergeCells * kMergeLanes), 0, s, m);
+    }
     HIP_TRY(hipGetLastError());
   }
   return GBDT_OK;

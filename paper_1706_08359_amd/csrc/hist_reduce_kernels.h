@@ -29,15 +29,20 @@ struct MergeArgs {
 };
 
 constexpr int kMergeCells = 64;   // histogram cells per workgroup
-constexpr int kMergeLanes = 4;    // threads that share the chunks of one cell
+constexpr int kMergeLanes = 4;    // threads that share the chunks of one cell ...
+constexpr int kMergeLanesWide = 16;  // ... and when there are few cells and many chunks (one or two tiles built
+                                     // by hundreds of workgroups): 4 lanes would leave most of the machine idle
 
 // The "final reduction program" of Sec. 4: sums the partial histograms of the
 // workgroups that shared a feature tile.  A workgroup takes 64 consecutive (bin,
 // slot) pairs of one tile (slot fastest, so reads of a partial block are coalesced
 // in runs of 32); 4 threads per pair each sum every 4th chunk in fp64, in chunk
 // order, and the 4 sub-sums are added in a fixed order: the result does not depend
-// on scheduling.  Counts are summed as integers.  grid.y = tile.
+// on scheduling.  Counts are summed as integers.  grid.y = tile.  (LANES = 4 or 16 threads per
+// pair; which one is a function of the launch's shape only.)
+template <int LANES>
 __device__ __forceinline__ void merge_cells(const MergeArgs& a) {
+  constexpr int kMergeLanes = LANES;
   if (a.counters && blockIdx.x == 0 && threadIdx.x == 0) a.counters[blockIdx.y] = 0u;
   __shared__ double s_g[kMergeLanes][kMergeCells];
   __shared__ double s_h[kMergeLanes][kMergeCells];
@@ -115,8 +120,15 @@ __device__ __forceinline__ void merge_cells(const MergeArgs& a) {
   }
 }
 
-__global__ void __launch_bounds__(kMergeCells * kMergeLanes) hist_merge_kernel(MergeArgs a) {
-  merge_cells(a);
+template <int LANES>
+__global__ void __launch_bounds__(kMergeCells * LANES) hist_merge_kernel(MergeArgs a) {
+  merge_cells<LANES>(a);
+}
+
+// Threads per (bin, slot) pair for a reduction over `blocks` workgroups of 4-lane pairs and up to
+// `chunks` partial blocks per pair.
+inline int merge_lanes(int64_t blocks, int32_t chunks) {
+  return (blocks < 512 && chunks >= 64) ? kMergeLanesWide : kMergeLanes;
 }
 
 // The same reduction for a batched launch: grid.z = leaf of the launch; its partial
@@ -130,7 +142,8 @@ struct BatchMergeArgs {
   BatchLeaf leaf[kBatchLeaves];
 };
 
-__global__ void __launch_bounds__(kMergeCells * kMergeLanes) hist_merge_batch_kernel(BatchMergeArgs a) {
+template <int LANES>
+__global__ void __launch_bounds__(kMergeCells * LANES) hist_merge_batch_kernel(BatchMergeArgs a) {
   const BatchLeaf lf = a.leaf[blockIdx.z];
   if ((lf.wgs_unit & 0xffffu) == 1u) return;  // written by the build kernel itself
   MergeArgs m = a.m;
@@ -138,7 +151,7 @@ __global__ void __launch_bounds__(kMergeCells * kMergeLanes) hist_merge_batch_ke
   m.out += (size_t)blockIdx.z * m.n_features * m.n_bins;
   m.chunks_main = (int32_t)(lf.wgs_unit & 0xffffu) * a.blocks_per_wg;
   m.chunks_rem = m.plan.wr ? m.chunks_main : 0;
-  merge_cells(m);
+  merge_cells<LANES>(m);
 }
 
 // ----------------------------------------------------------------- unfuse kernel
@@ -163,13 +176,29 @@ hist_unfuse_kernel(const gbdt_bin_t* __restrict__ joint, const FusedFeat* __rest
     const int32_t stride = ff.stride, period = stride * (int32_t)ff.levels;
     double g = 0.0, h = 0.0;
     uint32_t n = 0;
-    // v = hi * period + b * stride + lo, lo < stride
-    for (int32_t base = b * stride; base < kFusedCap; base += period) {
-      for (int32_t lo = 0; lo < stride && base + lo < kFusedCap; ++lo) {
-        const gbdt_bin_t c = col[base + lo];
-        g += (double)c.grad;
-        h += (double)c.hess;
-        n += c.count;
+    // the joint bins v = hi * period + b * stride + lo (lo < stride) in ascending order, sixteen at a
+    // time: their loads are issued together (they do not depend on one another), then summed in order
+    int32_t base = b * stride, lo = 0;
+    while (base < kFusedCap) {
+      gbdt_bin_t c[16];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int32_t v = base + lo;
+        const bool ok = base < kFusedCap && v < kFusedCap;
+        c[i].grad = 0.0f;
+        c[i].hess = 0.0f;
+        c[i].count = 0u;
+        if (ok) c[i] = col[v];
+        if (++lo == stride) {
+          lo = 0;
+          base += period;
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        g += (double)c[i].grad;
+        h += (double)c[i].hess;
+        n += c[i].count;
       }
     }
     r.grad = (float)g;

@@ -62,8 +62,9 @@ def test_fused_build_equals_the_oracle_and_the_plain_path(nb):
     _say(f"bins {nb}: {F} features in {n_cols} fused columns")
     assert 0 < n_cols <= 0.85 * F and fused is not None
     leaves = [("root", None),
-              ("index list", torch.from_numpy(np.sort(rng.choice(n, size=n // 3, replace=False)).astype(np.int32)).to(DEV)),
-              ("list with repeats", torch.from_numpy(rng.integers(0, n, size=20_000).astype(np.int32)).to(DEV)),
+              ("index list", torch.from_numpy(np.sort(rng.choice(n, size=n // 2, replace=False)).astype(np.int32)).to(DEV)),
+              ("list with repeats", torch.from_numpy(rng.integers(0, n, size=45_000).astype(np.int32)).to(DEV)),
+              ("sparse list (plain tiles)", torch.from_numpy(np.sort(rng.choice(n, size=n // 5, replace=False)).astype(np.int32)).to(DEV)),
               ("short leaf (plain tiles)", torch.arange(0, 5000, dtype=torch.int32, device=DEV))]
     for what, idx in leaves:
         idx_np = None if idx is None else idx.cpu().numpy()
@@ -98,6 +99,34 @@ def test_fused_build_equals_the_oracle_and_the_plain_path(nb):
     B.gbdt_bins_unfuse(packed)
     h2 = _build(packed, n, F, nb, None, grad_d, hess_d)
     assert (B.hist_to_numpy(h2)["count"] == B.hist_to_numpy(_build(plain, n, F, nb, None, grad_d, hess_d))["count"]).all()
+
+
+def test_fused_batched_build_equals_the_oracle_leaf_by_leaf():
+    """gbdt_hist_build_batch on a matrix that has a fused copy (it builds from the plain tiles): big and
+    tiny leaves, an empty one, in one call."""
+    n = 90_000
+    levels = [2, 3, 4, 5, 6, 7, 8, 9, 10, 12, 16, 1, 2, 2, 2, 3, 3] * 6
+    bins = _mixed_matrix(n, levels, 61)
+    F, nb = bins.shape[1], 16
+    grad, hess = _stats(n, 62)
+    bins_d = torch.from_numpy(bins).to(DEV)
+    grad_d, hess_d = torch.from_numpy(grad).to(DEV), torch.from_numpy(hess).to(DEV)
+    packed = B.gbdt_bins_pack(bins_d, nb, fuse=True)
+    assert getattr(packed, "gbdt_fused", None) is not None
+    rng = np.random.default_rng(63)
+    perm = rng.permutation(n).astype(np.int32)
+    lists = [np.sort(x) for x in np.split(perm, [40_000, 40_000, 40_700, 71_000, 71_003])]   # one list is empty
+    offs = np.concatenate([[0], np.cumsum([len(x) for x in lists])])
+    rows_d = torch.from_numpy(np.concatenate(lists)).to(DEV)
+    hists = B.gbdt_hist_build_batch(packed, n, F, nb, rows_d, offs, grad_d, hess_d)
+    torch.cuda.synchronize()
+    got = B.hist_to_numpy(hists)
+    for l, rows in enumerate(lists):
+        ref = orc.hist_build(bins, nb, grad, hess, rows)
+        sg, sh = np.abs(grad[rows].astype(np.float64)).sum(), np.abs(hess[rows].astype(np.float64)).sum()
+        assert_hist_close(got[l], ref, sg, sh, f"fused batch leaf {l} ({len(rows)} rows)")
+        for f, L in enumerate(levels):
+            assert (got[l]["count"][f, L:] == 0).all()
 
 
 def test_fused_exact_sums_stay_exact():
