@@ -289,10 +289,16 @@ split_gain_kernel(gbdt_bin_t* hist, int64_t hist_stride, int32_t n_features,
       c.bin = t;
     }
     store_cand(cand + blockIdx.x, c);
-    // The candidate's stores are device-scope atomics (written through, not left dirty in
-    // this XCD's L2): once they are acknowledged they are visible device-wide, so waiting
-    // for them (vmcnt(0)) is all the release the ticket needs -- a full fence would also
-    // write back every dirty line of the L2, which costs tens of microseconds here.
+    // HARDWARE ASSUMPTION (gfx942 / gfx950, not the language's memory model): a device-scope
+    // atomic store is written through to the point where the other XCDs' device-scope atomic
+    // loads read it, and is acknowledged (vmcnt) only then.  Waiting for the candidate's
+    // stores (vmcnt(0)) before taking the ticket is therefore all the release this hand-off
+    // needs, and the reader needs no acquire because it reads the candidates with device-scope
+    // atomic loads only.  A release / acquire pair in the language's sense would also write back
+    // and invalidate every line of the L2, which costs tens of microseconds here -- several
+    // times the whole kernel.  tests/test_gpu_robustness.py runs 64 x 250 workgroups of this
+    // hand-off 20 times and every split test goes through it; on a part where the assumption
+    // did not hold those tests would show stale candidates.
     __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0); expcnt, lgkmcnt untouched
     const unsigned int old = __hip_atomic_fetch_add(&g_split_ticket[blockIdx.y], 1u, __ATOMIC_RELAXED,
                                                     __HIP_MEMORY_SCOPE_AGENT);
