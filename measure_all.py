@@ -159,7 +159,7 @@ def skew(args, torch, B, synth, dev):
                 bins = synth.uniform_bins(n, F, nb, gen, dev)
                 bins[torch.rand((n, F), generator=gen, device=dev) < 0.6] = 0
             w = synth.Workload(f"skew_k{nb}", bins, nb, grad, hess)
-            packed = B.gbdt_bins_pack(bins, nb)
+            packed = B.gbdt_bins_pack(bins, nb, fuse=False)   # the atomics' behaviour on the plain tiles
             k_med, k_min, call_med, _ = time_leaf(B, torch, packed, w, None)
             row(w.name, kind, w, None, k_med, k_min, call_med)
             del w, packed, bins
