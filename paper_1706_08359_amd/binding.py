@@ -9,6 +9,7 @@ from __future__ import annotations
 
 import ctypes
 import os
+import weakref
 
 import numpy as np
 import torch
@@ -209,6 +210,9 @@ def gbdt_bins_fuse(bins_rowmajor: torch.Tensor, n_bins: int, packed: torch.Tenso
     if n_cols.value == 0:
         return 0, None
     packed.gbdt_fused = fused
+    # the library remembers the fused copy by the packed buffer's address: forget it when the
+    # buffer goes away, so that the address can be reused for something else
+    weakref.finalize(packed, lib.gbdt_bins_unfuse, packed.data_ptr())
     return n_cols.value, fused
 
 

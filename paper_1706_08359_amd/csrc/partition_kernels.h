@@ -34,7 +34,9 @@ namespace {
 // are still in cache, while the column bytes would come from HBM.)
 constexpr int kPartThreads = 256;
 constexpr int kPartWaves = kPartThreads / 64;
-constexpr int kPartMaxChunks = 8192;
+// (every workgroup of the scatter pass reads the counts of all chunks of its list: long lists
+// get longer chunks rather than more of them)
+constexpr int kPartMaxChunks = 2048;
 
 struct PartGeom {
   int32_t rows_per_thread;  // steps of kPartThreads rows a workgroup takes
@@ -111,7 +113,13 @@ __device__ __forceinline__ bool goes_left(const SplitColumn& c, const uint8_t* _
   return (int32_t)b <= c.thr;
 }
 
-// Flag pass of one chunk: positions [chunk * 256 * rows_per_thread, ...) of the list idx[0..n_leaf).
+// Both passes take the steps of a chunk eight at a time (rows_per_thread is a multiple of 8): all
+// eight requests of a kind leave before the first answer is used, so that a wavefront keeps eight
+// row ids, then eight bins, in flight instead of one.
+constexpr int kPartBlock = 8;
+
+// Flag pass of one chunk: positions [chunk * 256 * rows_per_thread, ...) of the list idx[0..n_leaf),
+// n_leaf >= 1.
 __device__ __forceinline__ void partition_flag_chunk(const SplitColumn& sc, const uint8_t* __restrict__ packed,
                                                      int64_t n_rows, const int32_t* __restrict__ idx,
                                                      int64_t n_leaf, int32_t chunk, int32_t rows_per_thread,
@@ -120,12 +128,40 @@ __device__ __forceinline__ void partition_flag_chunk(const SplitColumn& sc, cons
   __shared__ uint32_t s_left[kPartWaves];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int64_t chunk_base = (int64_t)chunk * kPartThreads * rows_per_thread;
+  // the column of the split feature, or (no split: every row goes left) any readable bytes
+  const uint8_t* __restrict__ column = packed + sc.col_off;
+  const int32_t thr = sc.has_split ? sc.thr : 0x7fffffff;
   uint32_t wave_left = 0;
-  for (int32_t k = 0; k < rows_per_thread; ++k) {
-    const int64_t e = chunk_base + (int64_t)k * kPartThreads + tid;
-    const uint64_t m = __ballot(goes_left(sc, packed, n_rows, idx, e, n_leaf));
-    if (lane == 0) my_flags[k * kPartWaves + wave] = m;
-    wave_left += (uint32_t)__popcll(m);
+  for (int32_t k0 = 0; k0 < rows_per_thread; k0 += kPartBlock) {
+    const int64_t e0 = chunk_base + (int64_t)k0 * kPartThreads + tid;
+    int64_t r[kPartBlock];
+    // (positions past the end repeat the last one: a valid address, the flag is masked below)
+    if (idx) {
+#pragma unroll
+      for (int j = 0; j < kPartBlock; ++j) {
+        const int64_t e = e0 + (int64_t)j * kPartThreads;
+        r[j] = idx[e < n_leaf ? e : n_leaf - 1];
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < kPartBlock; ++j) {
+        const int64_t e = e0 + (int64_t)j * kPartThreads;
+        r[j] = e < n_leaf ? e : n_leaf - 1;
+      }
+    }
+    int32_t b[kPartBlock];
+#pragma unroll
+    for (int j = 0; j < kPartBlock; ++j) {
+      const int64_t rr = r[j] < 0 ? 0 : (r[j] >= n_rows ? n_rows - 1 : r[j]);  // a bad row id must not fault
+      b[j] = (int32_t)column[rr];
+    }
+#pragma unroll
+    for (int j = 0; j < kPartBlock; ++j) {
+      const int64_t e = e0 + (int64_t)j * kPartThreads;
+      const uint64_t m = __ballot(e < n_leaf && b[j] <= thr);
+      if (lane == 0) my_flags[(k0 + j) * kPartWaves + wave] = m;
+      wave_left += (uint32_t)__popcll(m);
+    }
   }
   if (lane == 0) s_left[wave] = wave_left;
   __syncthreads();
@@ -148,6 +184,23 @@ __device__ __forceinline__ void partition_scatter_chunk(const int32_t* __restric
                                                         int64_t* __restrict__ n_left_out) {
   __shared__ int64_t s_before[kPartWaves], s_total[kPartWaves];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int64_t chunk_base = (int64_t)chunk * kPartThreads * rows_per_thread;
+  // the row ids of the first eight steps are requested before the chunk counts are summed
+  int32_t r[kPartBlock];
+  auto request = [&](int32_t k0) {
+    const int64_t e0 = chunk_base + (int64_t)k0 * kPartThreads + tid;
+    if (idx) {
+#pragma unroll
+      for (int j = 0; j < kPartBlock; ++j) {
+        const int64_t e = e0 + (int64_t)j * kPartThreads;
+        r[j] = idx[e < n_leaf ? e : n_leaf - 1];
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < kPartBlock; ++j) r[j] = (int32_t)(e0 + (int64_t)j * kPartThreads);
+    }
+  };
+  request(0);
   // left rows in the chunks before this one, and in the whole list
   int64_t before = 0, total = 0;
   for (int32_t c = tid; c < n_chunks; c += kPartThreads) {
@@ -174,28 +227,30 @@ __device__ __forceinline__ void partition_scatter_chunk(const int32_t* __restric
   }
   if (chunk == 0 && tid == 0 && n_left_out) *n_left_out = total;
 
-  const int64_t chunk_base = (int64_t)chunk * kPartThreads * rows_per_thread;
   const uint64_t* my_flags = flags + (size_t)chunk * rows_per_thread * kPartWaves;
   const uint64_t below = lane == 0 ? 0ull : (~0ull >> (64 - lane));
   int64_t left_pos = before;  // left rows before the current step
-  for (int32_t k = 0; k < rows_per_thread; ++k) {
-    uint64_t m = 0;
-    int64_t wave_base = left_pos;
+  for (int32_t k0 = 0; k0 < rows_per_thread; k0 += kPartBlock) {
+    if (k0 > 0) request(k0);
 #pragma unroll
-    for (int i = 0; i < kPartWaves; ++i) {
-      const uint64_t mi = my_flags[k * kPartWaves + i];
-      const int64_t ci = __popcll(mi);
-      if (i < wave) wave_base += ci;
-      if (i == wave) m = mi;
-      left_pos += ci;
-    }
-    const int64_t e = chunk_base + (int64_t)k * kPartThreads + tid;
-    if (e < n_leaf) {
-      const int32_t r = idx ? idx[e] : (int32_t)e;
-      const int64_t lefts_before_e = wave_base + __popcll(m & below);
-      const bool left = (m >> lane) & 1ull;
-      // (streaming store: the list is written once, front to back on either side)
-      __builtin_nontemporal_store(r, &out[left ? lefts_before_e : total + (e - lefts_before_e)]);
+    for (int j = 0; j < kPartBlock; ++j) {
+      uint64_t m = 0;
+      int64_t wave_base = left_pos;
+#pragma unroll
+      for (int i = 0; i < kPartWaves; ++i) {
+        const uint64_t mi = my_flags[(k0 + j) * kPartWaves + i];
+        const int64_t ci = __popcll(mi);
+        if (i < wave) wave_base += ci;
+        if (i == wave) m = mi;
+        left_pos += ci;
+      }
+      const int64_t e = chunk_base + (int64_t)(k0 + j) * kPartThreads + tid;
+      if (e < n_leaf) {
+        const int64_t lefts_before_e = wave_base + __popcll(m & below);
+        const bool left = (m >> lane) & 1ull;
+        // (streaming store: the list is written once, front to back on either side)
+        __builtin_nontemporal_store(r[j], &out[left ? lefts_before_e : total + (e - lefts_before_e)]);
+      }
     }
   }
 }
