@@ -113,52 +113,81 @@ __device__ __forceinline__ bool goes_left(const SplitColumn& c, const uint8_t* _
   return (int32_t)b <= c.thr;
 }
 
-// Both passes take the steps of a chunk eight at a time (rows_per_thread is a multiple of 8): all
-// eight requests of a kind leave before the first answer is used, so that a wavefront keeps eight
-// row ids, then eight bins, in flight instead of one.
-constexpr int kPartBlock = 8;
+// Both passes are chains of dependent memory round trips (row id -> bin -> flag word; flag words
+// and row id -> store) around a little integer arithmetic per row, and that arithmetic is what
+// bounds them once enough requests are in flight (with the stores taken out, the first scatter pass
+// of a 10 M-row list ran 10 % faster, no more).  So: a thread takes S = min(rows_per_thread, 16) steps of
+// its chunk at a time, all S requests of a kind leaving before the first answer is used, and
+// everything per row is 32-bit and relative to the chunk (lists hold fewer than 2^32 positions,
+// matrices fewer than 2^30 rows).  (rows_per_thread is 8 or a multiple of 16.)
+constexpr int kPartMaxBlock = 16;
 
-// Flag pass of one chunk: positions [chunk * 256 * rows_per_thread, ...) of the list idx[0..n_leaf),
-// n_leaf >= 1.
+// What a workgroup knows about its chunk: positions [base, base + n_valid) of the list.
+struct PartChunk {
+  int64_t base;
+  uint32_t n_valid;  // >= 1
+};
+__device__ __forceinline__ PartChunk part_chunk(int64_t n_leaf, int32_t chunk, int32_t rows_per_thread) {
+  PartChunk c;
+  const uint32_t chunk_rows = (uint32_t)kPartThreads * (uint32_t)rows_per_thread;
+  c.base = (int64_t)chunk * chunk_rows;
+  const int64_t rest = n_leaf - c.base;
+  c.n_valid = rest < (int64_t)chunk_rows ? (uint32_t)rest : chunk_rows;
+  return c;
+}
+
+// Row ids of S steps of a thread, from chunk position p0 on in strides of kPartThreads.
+// Positions past the end repeat the last one: a valid address, and the callers mask them.
+template <int S>
+__device__ __forceinline__ void part_request_rows(const int32_t* __restrict__ idx, const PartChunk& c, uint32_t p0,
+                                                  int32_t (&r)[S]) {
+  const uint32_t last = c.n_valid - 1;
+  if (idx) {
+    const int32_t* __restrict__ idx_c = idx + c.base;
+#pragma unroll
+    for (int j = 0; j < S; ++j) {
+      const uint32_t p = p0 + (uint32_t)j * kPartThreads;
+      r[j] = idx_c[p < last ? p : last];
+    }
+  } else {
+    const int32_t first_row = (int32_t)c.base;  // the list is 0, 1, 2, ...: fewer than 2^30 of them
+#pragma unroll
+    for (int j = 0; j < S; ++j) {
+      const uint32_t p = p0 + (uint32_t)j * kPartThreads;
+      r[j] = first_row + (int32_t)(p < last ? p : last);
+    }
+  }
+}
+
+// Flag pass of one chunk of the list idx[0..n_leaf), n_leaf >= 1.
+template <int S>
 __device__ __forceinline__ void partition_flag_chunk(const SplitColumn& sc, const uint8_t* __restrict__ packed,
                                                      int64_t n_rows, const int32_t* __restrict__ idx,
                                                      int64_t n_leaf, int32_t chunk, int32_t rows_per_thread,
                                                      uint64_t* __restrict__ my_flags,
                                                      uint32_t* __restrict__ my_chunk_left) {
   __shared__ uint32_t s_left[kPartWaves];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int64_t chunk_base = (int64_t)chunk * kPartThreads * rows_per_thread;
+  const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const PartChunk c = part_chunk(n_leaf, chunk, rows_per_thread);
   // the column of the split feature, or (no split: every row goes left) any readable bytes
   const uint8_t* __restrict__ column = packed + sc.col_off;
   const int32_t thr = sc.has_split ? sc.thr : 0x7fffffff;
+  const int32_t last_row = (int32_t)(n_rows - 1);
   uint32_t wave_left = 0;
-  for (int32_t k0 = 0; k0 < rows_per_thread; k0 += kPartBlock) {
-    const int64_t e0 = chunk_base + (int64_t)k0 * kPartThreads + tid;
-    int64_t r[kPartBlock];
-    // (positions past the end repeat the last one: a valid address, the flag is masked below)
-    if (idx) {
+  for (int32_t k0 = 0; k0 < rows_per_thread; k0 += S) {
+    const uint32_t p0 = (uint32_t)k0 * kPartThreads + tid;
+    int32_t r[S];
+    part_request_rows<S>(idx, c, p0, r);
+    int32_t b[S];
 #pragma unroll
-      for (int j = 0; j < kPartBlock; ++j) {
-        const int64_t e = e0 + (int64_t)j * kPartThreads;
-        r[j] = idx[e < n_leaf ? e : n_leaf - 1];
-      }
-    } else {
-#pragma unroll
-      for (int j = 0; j < kPartBlock; ++j) {
-        const int64_t e = e0 + (int64_t)j * kPartThreads;
-        r[j] = e < n_leaf ? e : n_leaf - 1;
-      }
-    }
-    int32_t b[kPartBlock];
-#pragma unroll
-    for (int j = 0; j < kPartBlock; ++j) {
-      const int64_t rr = r[j] < 0 ? 0 : (r[j] >= n_rows ? n_rows - 1 : r[j]);  // a bad row id must not fault
-      b[j] = (int32_t)column[rr];
+    for (int j = 0; j < S; ++j) {
+      const int32_t rr = r[j] < 0 ? 0 : (r[j] > last_row ? last_row : r[j]);  // a bad row id must not fault
+      b[j] = (int32_t)column[(uint32_t)rr];
     }
 #pragma unroll
-    for (int j = 0; j < kPartBlock; ++j) {
-      const int64_t e = e0 + (int64_t)j * kPartThreads;
-      const uint64_t m = __ballot(e < n_leaf && b[j] <= thr);
+    for (int j = 0; j < S; ++j) {
+      const uint32_t p = p0 + (uint32_t)j * kPartThreads;
+      const uint64_t m = __ballot(p < c.n_valid && b[j] <= thr);
       if (lane == 0) my_flags[(k0 + j) * kPartWaves + wave] = m;
       wave_left += (uint32_t)__popcll(m);
     }
@@ -166,15 +195,16 @@ __device__ __forceinline__ void partition_flag_chunk(const SplitColumn& sc, cons
   if (lane == 0) s_left[wave] = wave_left;
   __syncthreads();
   if (tid == 0) {
-    uint32_t c = 0;
+    uint32_t n = 0;
 #pragma unroll
-    for (int i = 0; i < kPartWaves; ++i) c += s_left[i];
-    *my_chunk_left = c;
+    for (int i = 0; i < kPartWaves; ++i) n += s_left[i];
+    *my_chunk_left = n;
   }
 }
 
 // Scatter pass of one chunk of a list with n_chunks chunks whose left counts are
 // chunk_left[0..n_chunks) and whose flag words start at `flags`.
+template <int S>
 __device__ __forceinline__ void partition_scatter_chunk(const int32_t* __restrict__ idx, int64_t n_leaf,
                                                         int32_t chunk, int32_t n_chunks,
                                                         int32_t rows_per_thread,
@@ -182,78 +212,116 @@ __device__ __forceinline__ void partition_scatter_chunk(const int32_t* __restric
                                                         const uint32_t* __restrict__ chunk_left,
                                                         int32_t* __restrict__ out,
                                                         int64_t* __restrict__ n_left_out) {
-  __shared__ int64_t s_before[kPartWaves], s_total[kPartWaves];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int64_t chunk_base = (int64_t)chunk * kPartThreads * rows_per_thread;
-  // the row ids of the first eight steps are requested before the chunk counts are summed
-  int32_t r[kPartBlock];
-  auto request = [&](int32_t k0) {
-    const int64_t e0 = chunk_base + (int64_t)k0 * kPartThreads + tid;
-    if (idx) {
-#pragma unroll
-      for (int j = 0; j < kPartBlock; ++j) {
-        const int64_t e = e0 + (int64_t)j * kPartThreads;
-        r[j] = idx[e < n_leaf ? e : n_leaf - 1];
-      }
-    } else {
-#pragma unroll
-      for (int j = 0; j < kPartBlock; ++j) r[j] = (int32_t)(e0 + (int64_t)j * kPartThreads);
-    }
-  };
-  request(0);
-  // left rows in the chunks before this one, and in the whole list
-  int64_t before = 0, total = 0;
-  for (int32_t c = tid; c < n_chunks; c += kPartThreads) {
-    const int64_t v = chunk_left[c];
-    total += v;
-    if (c < chunk) before += v;
-  }
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    before += __shfl_xor(before, o);
-    total += __shfl_xor(total, o);
-  }
-  if (lane == 0) {
-    s_before[wave] = before;
-    s_total[wave] = total;
-  }
-  __syncthreads();
-  before = 0;
-  total = 0;
-#pragma unroll
-  for (int i = 0; i < kPartWaves; ++i) {
-    before += s_before[i];
-    total += s_total[i];
-  }
-  if (chunk == 0 && tid == 0 && n_left_out) *n_left_out = total;
-
+  static_assert(S * kPartWaves / 2 <= 64, "one wavefront fetches the flag words of S steps, two per lane");
+  __shared__ uint32_t s_before[kPartWaves], s_total[kPartWaves];
+  // per (step, wavefront) of the S steps in hand: the flag word, the left rows of these steps
+  // before it; and the left rows of all S steps
+  __shared__ uint64_t s_flag[S * kPartWaves];
+  __shared__ uint32_t s_base[S * kPartWaves];
+  __shared__ uint32_t s_steps_left;
+  const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const PartChunk c = part_chunk(n_leaf, chunk, rows_per_thread);
   const uint64_t* my_flags = flags + (size_t)chunk * rows_per_thread * kPartWaves;
-  const uint64_t below = lane == 0 ? 0ull : (~0ull >> (64 - lane));
-  int64_t left_pos = before;  // left rows before the current step
-  for (int32_t k0 = 0; k0 < rows_per_thread; k0 += kPartBlock) {
-    if (k0 > 0) request(k0);
+  const uint32_t below_lo = lane >= 32 ? ~0u : ((1u << lane) - 1u);
+  const uint32_t below_hi = lane > 32 ? ((1u << (lane - 32)) - 1u) : 0u;
+  const uint32_t own_lo = lane < 32 ? (1u << lane) : 0u, own_hi = lane >= 32 ? (1u << (lane - 32)) : 0u;
+  uint32_t before = 0, total = 0;
+  // where the chunk's left and right rows start, and its left rows before the current steps
+  int32_t* __restrict__ out_left = out;
+  int32_t* __restrict__ out_right = out;
+  uint32_t left_in_chunk = 0;
+  for (int32_t k0 = 0; k0 < rows_per_thread; k0 += S) {
+    if (k0 > 0) __syncthreads();  // everybody has read the words of the steps before
+    // requests: the row ids of S steps, ...
+    const uint32_t p0 = (uint32_t)k0 * kPartThreads + tid;
+    int32_t r[S];
+    part_request_rows<S>(idx, c, p0, r);
+    // ... their flag words (the first wavefront: two per lane, ranked with a scan over the lanes) ...
+    if (wave == 0) {
+      uint64_t m0 = 0, m1 = 0;
+      if (lane < S * kPartWaves / 2) {
+        m0 = my_flags[k0 * kPartWaves + 2 * lane];
+        m1 = my_flags[k0 * kPartWaves + 2 * lane + 1];
+      }
+      const uint32_t n0 = (uint32_t)__popcll(m0), n1 = (uint32_t)__popcll(m1);
+      uint32_t inc = n0 + n1;
 #pragma unroll
-    for (int j = 0; j < kPartBlock; ++j) {
-      uint64_t m = 0;
-      int64_t wave_base = left_pos;
+      for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t up = __shfl_up(inc, o);
+        if (lane >= (uint32_t)o) inc += up;
+      }
+      if (lane < S * kPartWaves / 2) {
+        const uint32_t ex = inc - n0 - n1;
+        s_flag[2 * lane] = m0;
+        s_flag[2 * lane + 1] = m1;
+        s_base[2 * lane] = ex;
+        s_base[2 * lane + 1] = ex + n0;
+      }
+      if (lane == 63) s_steps_left = inc;
+    }
+    if (k0 == 0) {
+      // ... and the left rows in the chunks before this one, and in the whole list
+      for (int32_t i = tid; i < n_chunks; i += kPartThreads) {
+        const uint32_t v = chunk_left[i];
+        total += v;
+        if (i < chunk) before += v;
+      }
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) {
+        before += __shfl_xor(before, o);
+        total += __shfl_xor(total, o);
+      }
+      if (lane == 0) {
+        s_before[wave] = before;
+        s_total[wave] = total;
+      }
+    }
+    __syncthreads();
+    if (k0 == 0) {
+      before = 0;
+      total = 0;
 #pragma unroll
       for (int i = 0; i < kPartWaves; ++i) {
-        const uint64_t mi = my_flags[(k0 + j) * kPartWaves + i];
-        const int64_t ci = __popcll(mi);
-        if (i < wave) wave_base += ci;
-        if (i == wave) m = mi;
-        left_pos += ci;
+        before += s_before[i];
+        total += s_total[i];
       }
-      const int64_t e = chunk_base + (int64_t)(k0 + j) * kPartThreads + tid;
-      if (e < n_leaf) {
-        const int64_t lefts_before_e = wave_base + __popcll(m & below);
-        const bool left = (m >> lane) & 1ull;
-        // (streaming store: the list is written once, front to back on either side)
-        __builtin_nontemporal_store(r[j], &out[left ? lefts_before_e : total + (e - lefts_before_e)]);
+      if (chunk == 0 && tid == 0 && n_left_out) *n_left_out = (int64_t)total;
+      out_left = out + before;
+      out_right = out + ((int64_t)total + (c.base - (int64_t)before));
+    }
+#pragma unroll
+    for (int j = 0; j < S; ++j) {
+      const uint64_t m = s_flag[j * kPartWaves + wave];
+      const uint32_t m_lo = (uint32_t)m, m_hi = (uint32_t)(m >> 32);
+      // left rows of the chunk before this position
+      const uint32_t lefts = left_in_chunk + s_base[j * kPartWaves + wave] + __popc(m_lo & below_lo) +
+                             __popc(m_hi & below_hi);
+      const uint32_t p = p0 + (uint32_t)j * kPartThreads;
+      if (p < c.n_valid) {
+        // (ordinary stores: a wavefront's ids go to two runs that end inside cache lines which the
+        // next wavefront completes; marked as streaming they took a third longer on an even split)
+        if ((m_lo & own_lo) | (m_hi & own_hi)) {
+          out_left[lefts] = r[j];
+        } else {
+          out_right[p - lefts] = r[j];
+        }
       }
     }
+    left_in_chunk += s_steps_left;
   }
 }
+
+// The two passes with the number of steps in flight chosen from rows_per_thread.
+#define GBDT_PART_DISPATCH(rows_per_thread, CALL) \
+  do {                                            \
+    if ((rows_per_thread) == 8) {                 \
+      constexpr int S = 8;                        \
+      CALL;                                       \
+    } else {                                      \
+      constexpr int S = kPartMaxBlock;            \
+      CALL;                                       \
+    }                                             \
+  } while (0)
 
 __global__ void __launch_bounds__(kPartThreads)
 partition_flag_kernel(const uint8_t* __restrict__ packed, int64_t n_rows, int32_t n_features,
@@ -261,16 +329,19 @@ partition_flag_kernel(const uint8_t* __restrict__ packed, int64_t n_rows, int32_
                       const gbdt_split_t* __restrict__ split, int32_t rows_per_thread,
                       uint64_t* __restrict__ flags, uint32_t* __restrict__ chunk_left) {
   const SplitColumn sc = split_column(split, plan, n_rows, n_features);
-  partition_flag_chunk(sc, packed, n_rows, idx, n_leaf, (int32_t)blockIdx.x, rows_per_thread,
-                       flags + (size_t)blockIdx.x * rows_per_thread * kPartWaves, chunk_left + blockIdx.x);
+  GBDT_PART_DISPATCH(rows_per_thread,
+                     partition_flag_chunk<S>(sc, packed, n_rows, idx, n_leaf, (int32_t)blockIdx.x, rows_per_thread,
+                                             flags + (size_t)blockIdx.x * rows_per_thread * kPartWaves,
+                                             chunk_left + blockIdx.x));
 }
 
 __global__ void __launch_bounds__(kPartThreads)
 partition_scatter_kernel(const int32_t* __restrict__ idx, int64_t n_leaf, int32_t rows_per_thread,
                          const uint64_t* __restrict__ flags, const uint32_t* __restrict__ chunk_left,
                          int32_t n_chunks, int32_t* __restrict__ out, int64_t* __restrict__ n_left_out) {
-  partition_scatter_chunk(idx, n_leaf, (int32_t)blockIdx.x, n_chunks, rows_per_thread, flags, chunk_left, out,
-                          n_left_out);
+  GBDT_PART_DISPATCH(rows_per_thread,
+                     partition_scatter_chunk<S>(idx, n_leaf, (int32_t)blockIdx.x, n_chunks, rows_per_thread, flags,
+                                                chunk_left, out, n_left_out));
 }
 
 // Several leaves per launch (a level of a tree): leaf l of the launch owns the row list
@@ -316,9 +387,11 @@ __global__ void __launch_bounds__(kPartThreads) partition_flag_batch_kernel(Part
   const int32_t l = part_leaf_of(a.leaf, a.n_leaves, blockIdx.x);
   const PartLeaf lf = a.leaf[l];
   const SplitColumn sc = split_column(a.split + lf.split_idx, a.plan, a.n_rows, a.n_features);
-  partition_flag_chunk(sc, a.packed, a.n_rows, a.idx + lf.row_off, lf.n, (int32_t)(blockIdx.x - lf.first_chunk),
-                       a.rows_per_thread, a.flags + (size_t)blockIdx.x * a.rows_per_thread * kPartWaves,
-                       a.chunk_left + blockIdx.x);
+  GBDT_PART_DISPATCH(a.rows_per_thread,
+                     partition_flag_chunk<S>(sc, a.packed, a.n_rows, a.idx + lf.row_off, lf.n,
+                                             (int32_t)(blockIdx.x - lf.first_chunk), a.rows_per_thread,
+                                             a.flags + (size_t)blockIdx.x * a.rows_per_thread * kPartWaves,
+                                             a.chunk_left + blockIdx.x));
 }
 
 __global__ void __launch_bounds__(kPartThreads) partition_scatter_batch_kernel(PartBatchArgs a) {
@@ -327,11 +400,12 @@ __global__ void __launch_bounds__(kPartThreads) partition_scatter_batch_kernel(P
   const uint32_t next_first = l + 1 < a.n_leaves ? a.leaf[l + 1].first_chunk : a.n_chunks;
   // (a later leaf without rows shares its first chunk with the next one: this leaf's
   // chunks end where the next leaf WITH rows begins, which is what first_chunk gives)
-  partition_scatter_chunk(a.idx + lf.row_off, lf.n, (int32_t)(blockIdx.x - lf.first_chunk),
-                          (int32_t)(next_first - lf.first_chunk), a.rows_per_thread,
-                          a.flags + (size_t)lf.first_chunk * a.rows_per_thread * kPartWaves,
-                          a.chunk_left + lf.first_chunk, a.out + lf.out_off,
-                          a.n_left_out ? a.n_left_out + l : nullptr);
+  GBDT_PART_DISPATCH(a.rows_per_thread,
+                     partition_scatter_chunk<S>(a.idx + lf.row_off, lf.n, (int32_t)(blockIdx.x - lf.first_chunk),
+                                                (int32_t)(next_first - lf.first_chunk), a.rows_per_thread,
+                                                a.flags + (size_t)lf.first_chunk * a.rows_per_thread * kPartWaves,
+                                                a.chunk_left + lf.first_chunk, a.out + lf.out_off,
+                                                a.n_left_out ? a.n_left_out + l : nullptr));
 }
 
 // n_left_out[l] = 0 for the leaves of a batched partition that have no rows (they own no
