@@ -452,16 +452,37 @@ int build_wg_per_cu(int cap, bool indexed, bool wide = false) {
   return c;
 }
 
-// Features per workgroup of split_gain_kernel: as many as fit its LDS budget, at most
-// 32, but fewer when that leaves the machine short of workgroups.
-void split_grouping(int32_t n_features, int32_t n_bins, int* group_out, int* n_groups_out) {
-  int group = kSplitLdsBudget / split_feature_bytes(n_bins);
-  if (group > 32) group = 32;
-  const int spread = (n_features + 255) / 256;  // features per group that gives ~256 groups
-  if (spread < group) group = spread;
-  if (group < 1) group = 1;
-  *group_out = group;
-  *n_groups_out = (n_features + group - 1) / group;
+// Work split of split_gain_kernel over the n_hists histograms of a launch.  group: features a
+// workgroup holds in local memory at a time; passes: groups it takes one after the other; n_wg:
+// workgroups, and candidates, per histogram.  A workgroup's time is a chain of latencies (loads,
+// the serial fp64 prefix, the candidate's hand-off) that hardly depends on the group, so a lone
+// histogram is spread over about 256 workgroups, and a launch with many histograms gets larger
+// groups (up to 16 features: more leave too few workgroups per CU to hide those latencies), then
+// up to 4 passes, aiming at 500-1000 workgroups in all.  (2,000 features x 63 bins, 64
+// histograms: 188 us with 8 features per workgroup as for a lone histogram, 85 us with 16 x 4;
+// 137 x 255, 64 histograms: 113 us with one feature per workgroup, 40 us with 7 x 2.)
+struct SplitGrouping {
+  int group, passes, n_wg;
+};
+SplitGrouping split_grouping(int32_t n_features, int32_t n_bins, int32_t n_hists) {
+  SplitGrouping g;
+  int cap = kSplitLdsBudget / split_feature_bytes(n_bins);
+  if (cap > 16) cap = 16;
+  if (cap < 1) cap = 1;
+  const int spread = (n_features + 255) / 256;  // a lone histogram: about 256 groups
+  const int64_t total = (int64_t)n_features * (n_hists > 0 ? n_hists : 1);
+  const int64_t shared = (total + 511) / 512;   // many histograms: about 512 groups in all
+  g.group = (int)(shared > spread ? shared : spread);
+  if (g.group > cap) g.group = cap;
+  if (g.group < 1) g.group = 1;
+  const int n_groups = (n_features + g.group - 1) / g.group;
+  const int64_t wgs = (int64_t)n_groups * (n_hists > 0 ? n_hists : 1);
+  g.passes = (int)((wgs + 1023) / 1024);
+  if (g.passes > 4) g.passes = 4;
+  if (g.passes > n_groups) g.passes = n_groups;
+  if (g.passes < 1) g.passes = 1;
+  g.n_wg = (n_groups + g.passes - 1) / g.passes;
+  return g;
 }
 
 // GBDT_HIST_CHECK_INPUTS=1 (debugging): every call that takes a row list first counts its
@@ -597,12 +618,11 @@ BatchPlan plan_batch(const int64_t* leaf_offsets, int32_t l0, int32_t n, int64_t
 int launch_split(const gbdt_bin_t* hists, int64_t hist_stride, int32_t n_hists, float lambda,
                  float min_child_hess, gbdt_split_t* splits_out, int32_t n_features, int32_t n_bins,
                  hipStream_t s, gbdt_split_t* host_mirror = nullptr, const SplitSiblings* siblings = nullptr) {
-  int group = 0, n_groups = 0;
-  split_grouping(n_features, n_bins, &group, &n_groups);
+  const SplitGrouping sg = split_grouping(n_features, n_bins, n_hists);
   void* ws = nullptr;
-  int rc = get_workspace((size_t)n_hists * n_groups * sizeof(SplitCand), s, &ws);
+  int rc = get_workspace((size_t)n_hists * sg.n_wg * sizeof(SplitCand), s, &ws);
   if (rc != GBDT_OK) return rc;
-  const size_t lds = (size_t)group * split_feature_bytes(n_bins);
+  const size_t lds = (size_t)sg.group * split_feature_bytes(n_bins);
   SplitSiblings sib;
   if (siblings) {
     sib = *siblings;
@@ -610,9 +630,9 @@ int launch_split(const gbdt_bin_t* hists, int64_t hist_stride, int32_t n_hists, 
     memset(&sib, 0, sizeof sib);
   }
   // (only with siblings does the kernel write to the histograms)
-  hipLaunchKernelGGL(split_gain_kernel, dim3(n_groups, n_hists), dim3(kSplitThreads), lds, s,
-                     const_cast<gbdt_bin_t*>(hists), hist_stride, n_features, n_bins, group, (double)lambda,
-                     (double)min_child_hess, (SplitCand*)ws, splits_out, host_mirror, sib);
+  hipLaunchKernelGGL(split_gain_kernel, dim3(sg.n_wg, n_hists), dim3(kSplitThreads), lds, s,
+                     const_cast<gbdt_bin_t*>(hists), hist_stride, n_features, n_bins, sg.group, sg.passes,
+                     (double)lambda, (double)min_child_hess, (SplitCand*)ws, splits_out, host_mirror, sib);
   HIP_TRY(hipGetLastError());
   return GBDT_OK;
 }
@@ -1053,9 +1073,8 @@ size_t gbdt_workspace_bytes(int64_t n_rows, int32_t n_features, int32_t n_bins) 
              2 * (((size_t)n_rows + 63) / 64 * 64) * 4;  // + grad / hess of a leaf in leaf order
   // + the joint histograms of a fused copy (at most one column per feature)
   if (n_bins <= kFusedCap) b += (size_t)n_features * kFusedCap * sizeof(gbdt_bin_t);
-  int sg = 0, sn = 0;
-  split_grouping(n_features, n_bins, &sg, &sn);
-  const size_t cand = (size_t)2 * sn * sizeof(SplitCand);  // gbdt_grow_tree searches two histograms at once
+  // gbdt_grow_tree searches the children of a round in one launch
+  const size_t cand = (size_t)2 * kGrowRound * split_grouping(n_features, n_bins, 1).n_wg * sizeof(SplitCand);
   if (cand > b) b = cand;
   const size_t part = make_part_geom(n_rows > 0 ? n_rows : 1).bytes;
   if (part > b) b = part;
