@@ -784,7 +784,7 @@ hist_build_kernel(BuildArgs a) {
   const uint32_t n_leaf = (uint32_t)a.n_leaf;
   const int32_t t = b < main_blocks ? b % a.n_main : a.n_main;         // tile
   const int32_t c = b < main_blocks ? b / a.n_main : b - main_blocks;  // workgroup of the tile
-  uint32_t* counter = a.counters + t;
+  uint32_t* counter = a.counters + plan_counter_slot(t);
   const uint8_t* tile = a.packed + a.n_rows * ((int64_t)t * WM);
   const DirectOut direct = {a.direct_out, t, WM, a.n_main, a.wr, a.n_features, a.n_bins};
   // wide accumulation: the workgroup's second block lies a.wgs blocks behind its first

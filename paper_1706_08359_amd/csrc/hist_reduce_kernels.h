@@ -43,7 +43,7 @@ constexpr int kMergeLanesWide = 16;  // ... and when there are few cells and man
 template <int LANES>
 __device__ __forceinline__ void merge_cells(const MergeArgs& a) {
   constexpr int kMergeLanes = LANES;
-  if (a.counters && blockIdx.x == 0 && threadIdx.x == 0) a.counters[blockIdx.y] = 0u;
+  if (a.counters && blockIdx.x == 0 && threadIdx.x == 0) a.counters[plan_counter_slot((int32_t)blockIdx.y)] = 0u;
   __shared__ double s_g[kMergeLanes][kMergeCells];
   __shared__ double s_h[kMergeLanes][kMergeCells];
   __shared__ uint32_t s_n[kMergeLanes][kMergeCells];

@@ -144,4 +144,9 @@ GBDT_HD int32_t plan_feature_of(const TilePlan& p, int32_t t, int32_t slot) {
   return t * p.wm + j * vec + 4 * bw + q;
 }
 
+// The unit counter of tile t in the head of a scratch buffer (65,536 words): neighbouring tiles'
+// counters lie 256 bytes apart, so that the device-scope atomics of a launch's workgroups do not
+// all queue at the memory channel of one cache line.
+GBDT_HD int32_t plan_counter_slot(int32_t t) { return (t & 1023) * 64 + (t >> 10); }
+
 #endif  // GBDT_TILE_PLAN_H_
