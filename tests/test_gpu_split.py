@@ -1,11 +1,11 @@
 """GPU parity of gbdt_best_split on hand-made histograms (through the C ABI), against the oracle's
 scan of the SAME fp32 numbers: the chosen (feature, bin) must be identical, with no tolerance.
 
-The kernel sums a feature's bins in parallel chunks when it can prove that every partial sum is
-exact in fp64 (then any order gives the same bits as the left-to-right sum that defines the
-result), and left to right otherwise.  These histograms steer rows into both paths and put
-exact ties and near-ties on the thresholds, where a prefix sum that differed in its last bit
-would change the choice."""
+The kernel sums a feature's bins strictly left to right in fp64, as the oracle does.  These
+histograms put exact ties and near-ties on the thresholds, where a prefix sum that differed in
+its last bit would change the choice, spread bin sums over 60 binary orders of magnitude, and
+fill launches with many histograms, where a workgroup takes several groups of features in turn
+and ties between them must still fall to the smaller feature."""
 import numpy as np
 import pytest
 import torch
@@ -41,7 +41,7 @@ def _check(grad, hess, count, lam=1.0, mch=1e-3, what=""):
 
 @pytest.mark.parametrize("F,nb", [(1, 2), (3, 16), (28, 64), (70, 63), (28, 255), (137, 256), (300, 17), (2000, 63)])
 def test_split_of_ordinary_histograms(F, nb):
-    """Magnitudes within a few decades: every row takes the chunked (provably exact) path."""
+    """Magnitudes within a few decades."""
     _say(f"split {F}x{nb} ordinary")
     rng = np.random.default_rng(F * 1000 + nb)
     count = rng.integers(0, 500, size=(F, nb)).astype(np.uint32)
@@ -52,8 +52,8 @@ def test_split_of_ordinary_histograms(F, nb):
 
 @pytest.mark.parametrize("F,nb", [(3, 16), (28, 64), (28, 255), (137, 256), (500, 63)])
 def test_split_of_wide_range_histograms(F, nb):
-    """Bin sums spread over 60 binary orders of magnitude: partial sums round, the rows must be
-    summed strictly left to right, and mixed with ordinary rows in the same workgroup."""
+    """Bin sums spread over 60 binary orders of magnitude: partial sums round, so the order of the
+    additions shows in the result; such rows are mixed with ordinary rows in the same workgroup."""
     _say(f"split {F}x{nb} wide range")
     rng = np.random.default_rng(F * 77 + nb)
     count = rng.integers(1, 500, size=(F, nb)).astype(np.uint32)
@@ -94,3 +94,39 @@ def test_split_denormals_zeros_and_huge_counts():
     grad[3, 6:] = np.float32(1e-30)
     grad[4] = -grad[2]
     _check(grad, hess, count, what="denormals")
+
+
+@pytest.mark.parametrize("F,nb,H", [(2000, 63, 24), (137, 255, 64), (700, 16, 40), (28, 255, 64), (45, 64, 3)])
+def test_split_batch_of_many_histograms(F, nb, H):
+    """One launch over H histograms: the work split depends on H (larger feature groups, several
+    groups per workgroup, a ragged last group), the records must not.  Every histogram against the
+    oracle; two of them are copies of one another up to a shift of the features by one group, so
+    that the same gain turns up in different workgroups and passes."""
+    _say(f"split batch {H} x {F}x{nb}")
+    rng = np.random.default_rng(F * 31 + nb * 7 + H)
+    count = rng.integers(0, 400, size=(H, F, nb)).astype(np.uint32)
+    grad = (rng.normal(size=(H, F, nb)) * np.sqrt(count + 1.0)).astype(np.float32) * (count > 0)
+    hess = (rng.uniform(0.05, 0.25, size=(H, F, nb)) * count).astype(np.float32)
+    if H >= 2 and F > 20:
+        count[1], grad[1], hess[1] = np.roll(count[0], 17, axis=0), np.roll(grad[0], 17, axis=0), np.roll(hess[0], 17, axis=0)
+    # the same feature twice, far apart: an exact tie that the smaller feature must win
+    if F > 20:
+        for h in range(2, H, 5):
+            a, b = int(rng.integers(0, F // 2)), int(rng.integers(F // 2, F))
+            grad[h, a] *= 3.0                                     # make it the likely winner
+            count[h, b], grad[h, b], hess[h, b] = count[h, a], grad[h, a], hess[h, a]
+    hist = np.zeros((H, F, nb), dtype=B.BIN_DTYPE)
+    hist["grad"], hist["hess"], hist["count"] = grad, hess, count
+    t = torch.from_numpy(hist.view(np.float32).reshape(H, F, nb, 3).copy()).to("cuda:0")
+    got = B.splits_to_dicts(B.gbdt_best_split_batch(t, 1.0, 1e-3))
+    for h in range(H):
+        ref = orc.best_split(orc.from_f32_hist(grad[h], hess[h], count[h]), 1.0, 1e-3)
+        assert (got[h]["feature"], got[h]["bin"]) == (ref["feature"], ref["bin"]), (h, got[h], ref)
+        if ref["feature"] >= 0:
+            assert got[h]["left_count"] == ref["left_count"] and got[h]["right_count"] == ref["right_count"], h
+            assert np.float32(ref["left_grad"]) == np.float32(got[h]["left_grad"]), h
+            assert np.float32(ref["right_hess"]) == np.float32(got[h]["right_hess"]), h
+    # and one histogram at a time gives the same records
+    for h in (0, H - 1):
+        one = B.split_to_dict(B.gbdt_best_split(t[h], 1.0, 1e-3))
+        assert one == got[h], h
