@@ -266,6 +266,36 @@ def tree(args, torch, B, synth, dev):
         torch.cuda.empty_cache()
 
 
+def split_sweep(args, torch, B, synth, dev):
+    """gbdt_best_split_batch over 1 .. 64 histograms in one launch, at the shapes of the five
+    workloads (random histograms: the time does not depend on the values).  A round of leaf-wise
+    growth searches up to 64 children at once, a level of level-wise growth up to 256."""
+    print("| features x bins | histograms | call ms (median) | call ms (min) | us per histogram | "
+          "histogram GB/s |")
+    print("|" + "---|" * 6, flush=True)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(7)
+    for F, nb in ((28, 64), (2000, 63), (28, 255), (137, 255), (700, 16)):
+        for nh in (1, 2, 4, 8, 16, 32, 64, 256):
+            h = torch.rand((nh, F, nb, 3), device=dev, generator=gen)
+            h.view(torch.int32)[..., 2] = torch.randint(1, 100, (nh, F, nb), device=dev, dtype=torch.int32,
+                                                        generator=gen)
+            out = torch.empty((nh, 9), dtype=torch.int32, device=dev)
+            times = []
+            for rep in range(25):
+                e0, e1 = _events(torch)
+                e0.record()
+                B.gbdt_best_split_batch(h, 1.0, 1e-3, out)
+                e1.record()
+                torch.cuda.synchronize()
+                if rep >= 5:
+                    times.append(e0.elapsed_time(e1))
+            med, mn = statistics.median(times), min(times)
+            print(f"| {F} x {nb} | {nh} | {med:.4f} | {mn:.4f} | {med * 1e3 / nh:.2f} | "
+                  f"{nh * F * nb * 12 / (med * 1e-3) / 1e9:,.0f} |", flush=True)
+            del h, out
+
+
 def batch_sweep(args, torch, B, synth, dev):
     """The depth benchmark of App. C.2 (8,000,000 x 500, leaves of N / 2^D rows), taken over a
     whole tree level: the 2^D leaves of depth D (a random partition of the rows into equal
@@ -331,6 +361,7 @@ def main():
     ap.add_argument("--partition", action="store_true")
     ap.add_argument("--tree", action="store_true")
     ap.add_argument("--batch-sweep", action="store_true")
+    ap.add_argument("--split", action="store_true", help="split search over 1 .. 256 histograms per launch")
     ap.add_argument("--oracle", action="store_true", help="time the CPU oracle on the root leaves")
     ap.add_argument("--only", nargs="*", default=None)
     ap.add_argument("--wide", action="store_true", help="measure in the wide-accumulation mode")
@@ -357,6 +388,8 @@ def main():
         tree(args, torch, B, synth, dev)
     elif args.batch_sweep:
         batch_sweep(args, torch, B, synth, dev)
+    elif args.split:
+        split_sweep(args, torch, B, synth, dev)
     else:
         five_workloads(args, torch, B, synth, dev)
 
