@@ -515,6 +515,15 @@ int gbdt_debug_fusion_plan(const uint32_t* levels, int32_t n_features, int32_t* 
  * n_bins (indexed != 0: the variant that gathers through leaf_row_idx), as the HIP
  * runtime reports it on the current device; 0 if the query is not possible. */
 int gbdt_debug_occupancy(int32_t n_bins, int32_t indexed);
+/* How gbdt_best_split_batch splits a launch over n_hists histograms of n_features x n_bins:
+ * out[0] = features a workgroup holds in local memory at a time, out[1] = such groups it takes
+ * one after the other, out[2] = workgroups (and candidates) per histogram, out[3] = bytes of
+ * local memory per workgroup.  Host only. */
+int gbdt_debug_split_plan(int32_t n_features, int32_t n_bins, int32_t n_hists, int64_t* out, int32_t n_out);
+/* How gbdt_partition_rows cuts a list of n_leaf_rows positions into chunks: out[0] = steps of
+ * 256 positions a workgroup takes (positions per chunk / 256), out[1] = chunks, out[2] = bytes of
+ * scratch (flag words and chunk counts).  Host only. */
+int gbdt_debug_partition_plan(int64_t n_leaf_rows, int64_t* out, int32_t n_out);
 int gbdt_debug_locate(int32_t n_features, int32_t n_bins, int32_t feature, int32_t* tile_out,
                       int32_t* slot_out);
 

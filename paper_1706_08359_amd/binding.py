@@ -22,7 +22,8 @@ EXPORTS = [
     "gbdt_bins_packed_bytes", "gbdt_bins_pack", "gbdt_hist_build", "gbdt_hist_subtract",
     "gbdt_best_split", "gbdt_workspace_bytes", "gbdt_set_workspace", "gbdt_strerror",
     "gbdt_last_hip_error", "gbdt_debug_geometry", "gbdt_debug_locate",
-    "gbdt_profile_enable", "gbdt_profile_collect", "gbdt_debug_occupancy",
+    "gbdt_profile_enable", "gbdt_profile_collect", "gbdt_debug_occupancy", "gbdt_debug_split_plan",
+    "gbdt_debug_partition_plan",
     "gbdt_calibration_copy", "gbdt_set_deterministic", "gbdt_partition_rows",
     "gbdt_hist_build_batch", "gbdt_hist_build_batch_workspace_bytes", "gbdt_best_split_batch",
     "gbdt_debug_batch_plan", "gbdt_grow_tree", "gbdt_grow_tree_scratch_bytes",
@@ -526,6 +527,25 @@ def gbdt_debug_occupancy(n_bins: int, indexed: bool) -> int:
     lib.gbdt_debug_occupancy.restype = ctypes.c_int
     lib.gbdt_debug_occupancy.argtypes = [ctypes.c_int32, ctypes.c_int32]
     return int(lib.gbdt_debug_occupancy(n_bins, 1 if indexed else 0))
+
+
+def gbdt_debug_split_plan(n_features: int, n_bins: int, n_hists: int) -> dict:
+    lib = load()
+    out = (ctypes.c_int64 * 4)()
+    lib.gbdt_debug_split_plan.restype = ctypes.c_int
+    lib.gbdt_debug_split_plan.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p,
+                                          ctypes.c_int32]
+    _check(lib.gbdt_debug_split_plan(n_features, n_bins, n_hists, out, 4), "gbdt_debug_split_plan")
+    return dict(zip(("group", "passes", "workgroups", "lds_bytes"), (int(v) for v in out)))
+
+
+def gbdt_debug_partition_plan(n_leaf_rows: int) -> dict:
+    lib = load()
+    out = (ctypes.c_int64 * 3)()
+    lib.gbdt_debug_partition_plan.restype = ctypes.c_int
+    lib.gbdt_debug_partition_plan.argtypes = [ctypes.c_int64, ctypes.c_void_p, ctypes.c_int32]
+    _check(lib.gbdt_debug_partition_plan(n_leaf_rows, out, 3), "gbdt_debug_partition_plan")
+    return dict(zip(("rows_per_thread", "chunks", "bytes"), (int(v) for v in out)))
 
 
 def gbdt_debug_locate(n_features: int, n_bins: int, feature: int):

@@ -2027,6 +2027,25 @@ int gbdt_debug_occupancy(int32_t n_bins, int32_t indexed) {
   return build_wg_per_cu(n_bins <= 16 ? 16 : (n_bins <= 64 ? 64 : 256), indexed != 0);
 }
 
+int gbdt_debug_split_plan(int32_t n_features, int32_t n_bins, int32_t n_hists, int64_t* out, int32_t n_out) {
+  if (!out || n_out < 4 || n_features <= 0 || n_bins < 2 || n_bins > 256 || n_hists < 1) return GBDT_EINVAL;
+  const SplitGrouping g = split_grouping(n_features, n_bins, n_hists);
+  out[0] = g.group;
+  out[1] = g.passes;
+  out[2] = g.n_wg;
+  out[3] = (int64_t)g.group * split_feature_bytes(n_bins);
+  return GBDT_OK;
+}
+
+int gbdt_debug_partition_plan(int64_t n_leaf_rows, int64_t* out, int32_t n_out) {
+  if (!out || n_out < 3 || n_leaf_rows < 1 || n_leaf_rows >= ((int64_t)1 << 32)) return GBDT_EINVAL;
+  const PartGeom g = make_part_geom(n_leaf_rows);
+  out[0] = g.rows_per_thread;
+  out[1] = g.n_chunks;
+  out[2] = (int64_t)g.bytes;
+  return GBDT_OK;
+}
+
 int gbdt_debug_locate(int32_t n_features, int32_t n_bins, int32_t feature, int32_t* tile_out,
                       int32_t* slot_out) {
   if (!tile_out || !slot_out || n_features <= 0 || n_bins < 2 || n_bins > 256 || feature < 0 ||

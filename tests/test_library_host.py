@@ -249,3 +249,39 @@ def test_fusion_plan_is_a_valid_mixed_radix_packing():
     assert n_cols == 7                            # six binary features per column
     col, stride, n_cols = B.gbdt_debug_fusion_plan(np.full(9, 64, np.uint32))
     assert n_cols == 9
+
+
+@pytest.mark.parametrize("n_bins", [2, 16, 63, 64, 100, 255, 256])
+def test_split_search_plan_covers_every_feature_within_the_lds_budget(n_bins):
+    """The work split of the split search follows the number of histograms of the launch; whatever
+    it picks, the groups of all workgroups cover the features, a group fits the kernel's local
+    memory budget, and a launch never has more candidates per histogram than a lone histogram
+    (the scratch of gbdt_workspace_bytes is sized by that)."""
+    for n_features in (1, 2, 7, 28, 137, 255, 256, 257, 700, 2000, 4000, 20000):
+        lone = B.gbdt_debug_split_plan(n_features, n_bins, 1)
+        for n_hists in (1, 2, 3, 8, 31, 64, 256, 1024, 32768):
+            p = B.gbdt_debug_split_plan(n_features, n_bins, n_hists)
+            assert p["group"] >= 1 and p["passes"] >= 1 and p["workgroups"] >= 1
+            assert p["lds_bytes"] <= 48 * 1024
+            assert p["group"] * p["passes"] * p["workgroups"] >= n_features
+            # no workgroup without a feature
+            assert p["group"] * p["passes"] * (p["workgroups"] - 1) < n_features
+            assert p["workgroups"] <= lone["workgroups"]
+            # the prefix sums run on one lane per (feature, statistic) of a 256-thread workgroup
+            assert 3 * p["group"] <= 256
+
+
+def test_partition_plan_chunks_cover_the_list():
+    """Chunks of 256 * rows_per_thread positions: 8 steps, or a multiple of 16 (the kernels take
+    8 or 16 steps at a time), at most 2048 chunks, every position in exactly one chunk."""
+    for n in (1, 255, 256, 2047, 2048, 2049, 8192, 8193, 4_194_304, 4_194_305, 10_500_000, 11_000_000,
+              67_108_864, 2**31 - 1, 2**32 - 1):
+        p = B.gbdt_debug_partition_plan(n)
+        r, c = p["rows_per_thread"], p["chunks"]
+        assert r == 8 or r % 16 == 0
+        assert r & (r - 1) == 0
+        assert 1 <= c <= 2048
+        assert (c - 1) * 256 * r < n <= c * 256 * r
+        assert p["bytes"] == c * r * 4 * 8 + c * 4
+    with pytest.raises(B.GbdtError):
+        B.gbdt_debug_partition_plan(0)
