@@ -136,6 +136,32 @@ def test_partition_many_chunks_and_caller_workspace():
         B.gbdt_set_workspace(None)
 
 
+@pytest.mark.parametrize("n", [4_194_304 + 5, 8_388_608 + 4099, 17_000_001])
+def test_partition_long_lists_take_longer_chunks(n):
+    """Lists of more than 2048 x 2048 positions are cut into chunks of 4096, 8192, ... positions,
+    which a workgroup takes 16 steps at a time: the root, a sorted list with a ragged end that
+    falls in the first steps of the last chunk, and an unsorted list with repeated rows; one
+    split that sends nearly every row left, one that splits evenly."""
+    F, nb = 2, 50
+    plan = B.gbdt_debug_partition_plan(n)
+    _say(f"partition {n}x{F} bins={nb}: {plan}")
+    assert plan["rows_per_thread"] >= 16
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(n % 1000)
+    bins = synth.uniform_bins(n, F, nb, gen, torch.device("cuda:0"))
+    zeros = torch.zeros(n, dtype=torch.float32)
+    p = GpuProblem(bins, nb, zeros, zeros)
+    _check(p, 1, 24, None, None, "root, even split")
+    _check(p, 0, 47, None, None, "root, nearly all left")
+    rng = np.random.default_rng(n % 977)
+    m = plan["rows_per_thread"] * 256 * (plan["chunks"] - 2) + 300     # ends in the first steps of a chunk
+    if B.gbdt_debug_partition_plan(m)["rows_per_thread"] >= 16:
+        sub = np.sort(rng.choice(n, size=m, replace=False)).astype(np.int32)
+        _check(p, 1, 10, sub, None, "sorted list, ragged end")
+    rep = rng.integers(0, n, size=4_194_304 + 77).astype(np.int32)      # unsorted, with repeats
+    _check(p, 0, 30, rep, None, "unsorted list with repeats")
+
+
 # ------------------------------------------------------------------ whole trees on the device
 
 def _grow_tree_on_device(p, n_leaves, lam, mch):
