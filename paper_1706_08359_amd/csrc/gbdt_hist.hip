@@ -24,6 +24,7 @@
 
 #include <algorithm>
 #include <atomic>
+#include <chrono>
 #include <mutex>
 #include <type_traits>
 #include <unordered_map>
@@ -1550,6 +1551,9 @@ int gbdt_grow_tree(const void* bin_matrix, int64_t n_rows, int32_t n_features, i
   int n_nodes = 1, n_leaves = 1, next_slot = 1;
   int expansions = 0, splits = 0, rounds = 0;
   const int spec_budget = grow_speculative_budget(max_leaves);
+  // (host clock, for the trace line: all rounds, and the part of them spent waiting for the stream)
+  double wait_us = 0, rounds_us = 0;
+  auto last_round_end = std::chrono::steady_clock::now();
   for (;;) {
     // ---- replay the sequential rule as far as the expansions seen so far carry it
     int blocked = -1;
@@ -1693,7 +1697,14 @@ int gbdt_grow_tree(const void* bin_matrix, int64_t n_rows, int32_t n_features, i
                         n_bins, s, pinned_dev, &sib);
       if (rc != GBDT_OK) return rc;
     }
-    HIP_TRY(hipStreamSynchronize(s));
+    {
+      auto t0 = std::chrono::steady_clock::now();
+      HIP_TRY(hipStreamSynchronize(s));
+      auto t1 = std::chrono::steady_clock::now();
+      wait_us += std::chrono::duration<double, std::micro>(t1 - t0).count();
+      rounds_us += std::chrono::duration<double, std::micro>(t1 - last_round_end).count();
+      last_round_end = t1;
+    }
     for (int j = 0; j < k; ++j) {
       const int par = batch[j];
       const Cand pc = cands[par];
@@ -1725,8 +1736,9 @@ int gbdt_grow_tree(const void* bin_matrix, int64_t n_rows, int32_t n_features, i
       return e && atoi(e) > 0;
     }();
     if (trace)
-      fprintf(stderr, "gbdt_grow_tree: %d leaves, %d rounds, %d leaves expanded, %d of them never split\n", n_leaves,
-              rounds, expansions, expansions - splits);
+      fprintf(stderr, "gbdt_grow_tree: %d leaves, %d rounds, %d leaves expanded, %d of them never split; rounds %.0f us, "
+              "of which %.0f us waiting for the stream\n", n_leaves,
+              rounds, expansions, expansions - splits, rounds_us, wait_us);
   }
   if (row_order_out && n_rows > 0) {
     if (n_nodes == 1) {  // never split: the rows in their own order
