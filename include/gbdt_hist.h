@@ -257,7 +257,7 @@ int gbdt_set_deterministic(int enable);
  * affects later gbdt_hist_build / gbdt_hist_build_batch calls and the tree growers,
  * which build through them) a workgroup sums gradients and hessians in 54-bit fixed
  * point and fp64 instead of 27-bit fixed point and fp32: a stored sum is the exact sum
- * rounded to fp32, up to 5e-13 of the leaf's sum of magnitudes.  1.7-2.1x the build
+ * rounded to fp32, up to 5e-13 of the leaf's sum of magnitudes.  1.6-2.0x the build
  * time; twice the LDS and twice the scratch for partial results, so query
  * gbdt_workspace_bytes / gbdt_hist_build_batch_workspace_bytes AFTER setting the mode
  * when the caller owns the scratch.  Together with gbdt_set_deterministic the sums are
@@ -498,7 +498,7 @@ int gbdt_calibration_copy(const void* src, void* dst, size_t bytes, void* stream
  */
 int gbdt_debug_geometry(int32_t n_features, int32_t n_bins, int64_t n_leaf_rows, int32_t n_cus,
                         int64_t* out, int32_t n_out);
-/* Launch plan of the first (at most 128-leaf) launch of gbdt_hist_build_batch on a device
+/* Launch plan of the first (at most 224-leaf) launch of gbdt_hist_build_batch on a device
  * with n_cus compute units holding wg_per_cu workgroups each: per leaf the workgroups per
  * tile and the epochs per unit; for block i < max_blocks of the grid, block_out[3 i ..
  * 3 i + 2] = (leaf, tile, workgroup of that leaf and tile), computed by the function the
