@@ -154,3 +154,33 @@ def test_config5_categorical_255_leaf_tree_full_size():
     _say(f"  255 leaves, deepest node at depth {_max_depth(nodes)}, {near} near-tie decisions; routing check "
          f"{t1 - t0:.1f} s, replay {time.perf_counter() - t1:.1f} s of which {t_full:.1f} s for the oracle's full "
          f"histograms of the first 31 splits")
+
+
+@pytest.mark.parametrize("name", ["dense_tall", "dense_wide"])
+def test_255_leaf_tree_on_labels_with_signal_full_size(name):
+    """The same matrices with labels that depend on the features: balanced trees, so a round of
+    the grower really splits many leaves (32 partitions, one batched build, one split search over
+    64 children per round) instead of peeling one small leaf off a chain.  Every node replayed in
+    full with the oracle."""
+    w = synth.config3_dense_tall(device=DEV) if name == "dense_tall" else \
+        synth.config2_dense_wide(device=DEV, with_leaves=False)
+    n, F, nb = w.n_rows, w.n_features, w.n_bins
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(31)
+    w.grad, w.hess = synth.labels_with_signal(w.bins, nb, gen)
+    _say(f"grow_tree {n}x{F} bins={nb} leaves=255 (full {name}, labels with signal)")
+    packed = B.gbdt_bins_pack(w.bins, nb)
+    nodes, order, _ = B.gbdt_grow_tree(packed, n, F, nb, w.grad, w.hess, 255, w.lam, w.min_child_hess)
+    torch.cuda.synchronize()
+    order = order.cpu().numpy()
+    del packed
+    bins, grad, hess = w.bins.cpu().numpy(), w.grad.cpu().numpy(), w.hess.cpu().numpy()
+    n_leaves = int((nodes["left"] < 0).sum())
+    assert n_leaves == 255 and len(nodes) == 509
+    assert _max_depth(nodes) <= 16, "labels with signal should give a balanced tree"
+    t0 = time.perf_counter()
+    _check_structure(nodes, order, bins)
+    t1 = time.perf_counter()
+    _, _, near = _replay(nodes, bins, nb, grad, hess, w.lam, w.min_child_hess)
+    _say(f"  255 leaves, deepest node at depth {_max_depth(nodes)}, {near} near-tie decisions; "
+         f"routing check {t1 - t0:.1f} s, oracle replay of all 509 nodes {time.perf_counter() - t1:.1f} s")
