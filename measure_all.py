@@ -296,6 +296,40 @@ def split_sweep(args, torch, B, synth, dev):
             del h, out
 
 
+def copy_sweep(args, torch, B, synth, dev):
+    """Plain copies and fills of the sizes the row partition moves (42 MB = the row ids of a
+    10.5 M-row list), as a yardstick for its two passes: the library's calibration copy kernel and
+    torch's copy_ / fill_, calls back to back, median of 50."""
+    print("| bytes | library copy kernel us | torch copy_ us | torch fill_ us | copy GB/s (read + write) |")
+    print("|" + "---|" * 5, flush=True)
+
+    def timed(fn, n=50):
+        for _ in range(5):
+            fn()
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(n):
+            e0, e1 = _events(torch)
+            e0.record()
+            fn()
+            e1.record()
+            torch.cuda.synchronize()
+            ts.append(e0.elapsed_time(e1) * 1e3)
+        return statistics.median(ts)
+
+    for mb in (2, 10, 42, 168, 672):
+        nbytes = mb * 1_000_000 // 16 * 16
+        src = torch.ones(nbytes, dtype=torch.uint8, device=dev)
+        dst = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+        lib_us = timed(lambda: B.gbdt_calibration_copy(src, dst))
+        t_copy = timed(lambda: dst.copy_(src))
+        t_fill = timed(lambda: dst.fill_(3))
+        best = min(lib_us, t_copy)
+        print(f"| {nbytes:,} | {lib_us:.1f} | {t_copy:.1f} | {t_fill:.1f} | {2 * nbytes / (best * 1e-6) / 1e9:,.0f} |",
+              flush=True)
+        del src, dst
+
+
 def batch_sweep(args, torch, B, synth, dev):
     """The depth benchmark of App. C.2 (8,000,000 x 500, leaves of N / 2^D rows), taken over a
     whole tree level: the 2^D leaves of depth D (a random partition of the rows into equal
@@ -362,6 +396,7 @@ def main():
     ap.add_argument("--tree", action="store_true")
     ap.add_argument("--batch-sweep", action="store_true")
     ap.add_argument("--split", action="store_true", help="split search over 1 .. 256 histograms per launch")
+    ap.add_argument("--copy", action="store_true", help="plain copies and fills, the yardstick of the row partition")
     ap.add_argument("--oracle", action="store_true", help="time the CPU oracle on the root leaves")
     ap.add_argument("--only", nargs="*", default=None)
     ap.add_argument("--wide", action="store_true", help="measure in the wide-accumulation mode")
@@ -390,6 +425,8 @@ def main():
         batch_sweep(args, torch, B, synth, dev)
     elif args.split:
         split_sweep(args, torch, B, synth, dev)
+    elif args.copy:
+        copy_sweep(args, torch, B, synth, dev)
     else:
         five_workloads(args, torch, B, synth, dev)
 
