@@ -298,8 +298,9 @@ int gbdt_best_split(const gbdt_bin_t* hist, float lambda, float min_child_hess,
  * arithmetic, one kernel launch for up to 32768 histograms.
  *   hists       DEVICE gbdt_bin_t [n_hists][n_features][n_bins]
  *   splits_out  DEVICE gbdt_split_t [n_hists], overwritten
- * n_hists == 0 is a no-op.  Scratch: 56 bytes per histogram and group of up to 32
- * features (a caller-owned workspace sized by gbdt_workspace_bytes covers two histograms).
+ * n_hists == 0 is a no-op.  Scratch: 56 bytes per histogram and workgroup of the launch (never
+ * more workgroups per histogram than a lone histogram gets, see gbdt_debug_split_plan; a
+ * caller-owned workspace sized by gbdt_workspace_bytes covers 64 histograms).
  */
 int gbdt_best_split_batch(const gbdt_bin_t* hists, int32_t n_hists, float lambda,
                           float min_child_hess, gbdt_split_t* splits_out, int32_t n_features,
