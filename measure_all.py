@@ -141,6 +141,34 @@ def depth_sweep(args, torch, B, synth, dev):
         torch.cuda.empty_cache()
 
 
+def paired_leaves(args, torch, B, synth, dev):
+    """What the 128-byte cache line costs index-list leaves: the depth benchmark's matrix (8,000,000 x
+    500, 64 bins: 64-byte tile rows, two per line), leaves of N / 2^D rows drawn as single random rows
+    (the paper's recipe), as random ALIGNED PAIRS of rows (2i, 2i + 1: every fetched line is used in
+    full) and as aligned groups of four.  Same kernel, same number of rows; build kernel time."""
+    print("| D | leaf rows | random rows: kernel ms | aligned pairs: kernel ms | speed-up | aligned fours: kernel ms | "
+          "speed-up |")
+    print("|" + "---|" * 7, flush=True)
+    n, F, nb = 8_000_000, 500, 64
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(164)
+    bins = synth.uniform_bins(n, F, nb, gen, dev)
+    grad, hess = synth.logistic_grad_hess(n, gen, dev)
+    w = synth.Workload("paper_synthetic_k64", bins, nb, grad, hess)
+    packed = B.gbdt_bins_pack(w.bins, nb)
+    for depth in range(1, 8):
+        m = n >> depth
+        single = synth.leaf_by_truncated_permutation(n, 0.5 ** depth, gen, dev)
+        base2 = torch.sort(torch.randperm(n // 2, generator=gen, device=dev)[:m // 2]).values
+        pairs = torch.stack([2 * base2, 2 * base2 + 1], 1).flatten().to(torch.int32)
+        base4 = torch.sort(torch.randperm(n // 4, generator=gen, device=dev)[:m // 4]).values
+        fours = (4 * base4[:, None] + torch.arange(4, device=dev)[None, :]).flatten().to(torch.int32)
+        a = time_leaf(B, torch, packed, w, single)[0]
+        b = time_leaf(B, torch, packed, w, pairs)[0]
+        c = time_leaf(B, torch, packed, w, fours)[0]
+        print(f"| {depth} | {single.numel():,} | {a:.4f} | {b:.4f} | {a / b:.2f}x | {c:.4f} | {a / c:.2f}x |", flush=True)
+
+
 def skew(args, torch, B, synth, dev):
     """App. A.3: every feature holds a single bin value (the paper's worst case, ~4x slower
     there) against uniform bins, same shape."""
@@ -392,6 +420,8 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--depth-sweep", action="store_true")
     ap.add_argument("--skew", action="store_true")
+    ap.add_argument("--paired-leaves", action="store_true",
+                    help="index-list leaves of single rows against leaves of aligned row pairs")
     ap.add_argument("--partition", action="store_true")
     ap.add_argument("--tree", action="store_true")
     ap.add_argument("--batch-sweep", action="store_true")
@@ -417,6 +447,8 @@ def main():
         depth_sweep(args, torch, B, synth, dev)
     elif args.skew:
         skew(args, torch, B, synth, dev)
+    elif args.paired_leaves:
+        paired_leaves(args, torch, B, synth, dev)
     elif args.partition:
         partition(args, torch, B, synth, dev)
     elif args.tree:
